@@ -1,0 +1,316 @@
+"""ctypes face of the CPU oracle (oracle/qzo_oracle.cpp) -- TEST INFRASTRUCTURE ONLY.
+
+Imported by tests/, the smoke check and the benchmark's cpu_baseline leg; never
+by the product.  It imports nothing from the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+            _build.build()
+        _lib = C.CDLL(path)
+        _lib.orc_bf16_rne.restype = C.c_float
+        _lib.orc_bf16_rne.argtypes = [C.c_float]
+        _lib.orc_sumsq_bf16.restype = C.c_double
+        _lib.orc_next_token_ce.restype = C.c_double
+        _lib.orc_forward_loss.restype = C.c_double
+        _lib.orc_spsa_d.restype = C.c_float
+        _lib.orc_spsa_d.argtypes = [C.c_float, C.c_float, C.c_float]
+        _lib.orc_clip.restype = C.c_float
+        _lib.orc_clip.argtypes = [C.c_float, C.c_float]
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+# ----------------------------------------------------------------- RNG -----
+def philox4x32_10(ctr, key):
+    ctr = np.asarray(ctr, dtype=np.uint32)
+    key = np.asarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(_p(ctr), _p(key), _p(out))
+    return out
+
+
+def normal_pairs(words):
+    w = np.ascontiguousarray(words, dtype=np.uint32)
+    out = np.zeros((w.size, 2), dtype=np.float32)
+    lib().orc_normal_pairs(_p(w), C.c_uint64(w.size), _p(out))
+    return out
+
+
+def scale_normals(seed, row0, n_rows, G, stream=0):
+    out = np.zeros((n_rows, G), dtype=np.float32)
+    lib().orc_scale_normals(C.c_uint64(seed), C.c_uint32(stream), C.c_uint32(row0),
+                            C.c_uint32(n_rows), C.c_uint32(G), _p(out))
+    return out
+
+
+def flat_normals(seed, first, n, stream=1):
+    out = np.zeros(n, dtype=np.float32)
+    lib().orc_flat_normals(C.c_uint64(seed), C.c_uint32(stream), C.c_uint64(first),
+                           C.c_uint64(n), _p(out))
+    return out
+
+
+def bf16_rne(x):
+    a = _f32(x).copy()
+    lib().orc_bf16_rne_array(_p(a), C.c_uint64(a.size))
+    return a
+
+
+# --------------------------------------------------------- quantization ----
+def rtn_quantize(w, group=128):
+    w = _f32(w)
+    N, K = w.shape
+    qp = np.zeros((N, K // 2), dtype=np.uint8)
+    s = np.zeros((N, K // group), dtype=np.float32)
+    lib().orc_rtn_quantize(_p(w), C.c_uint64(N), C.c_uint64(K), C.c_uint32(group), _p(qp), _p(s))
+    return qp, s
+
+
+def unpack_int4(qp, K):
+    qp = np.ascontiguousarray(qp, dtype=np.uint8)
+    N = qp.shape[0]
+    q = np.zeros((N, K), dtype=np.int8)
+    lib().orc_unpack_int4(_p(qp), C.c_uint64(N), C.c_uint64(K), _p(q))
+    return q
+
+
+def effective_scales(s, row_base, seed, eps_signed):
+    s = _f32(s)
+    n_rows, G = s.shape
+    out = np.zeros((n_rows, G), dtype=np.float64)
+    lib().orc_effective_scales(_p(s), C.c_uint32(n_rows), C.c_uint32(G), C.c_uint32(row_base),
+                               C.c_uint64(seed), C.c_float(eps_signed), _p(out))
+    return out
+
+
+def dequant(qp, s, seed, row_base, eps_signed, group=128, to_bf16=False):
+    qp = np.ascontiguousarray(qp, dtype=np.uint8)
+    s = _f32(s)
+    N, K = qp.shape[0], qp.shape[1] * 2
+    out = np.zeros((N, K), dtype=np.float32)
+    lib().orc_dequant(_p(qp), _p(s), C.c_uint64(N), C.c_uint64(K), C.c_uint32(group),
+                      C.c_uint64(seed), C.c_uint32(row_base), C.c_float(eps_signed),
+                      C.c_int(1 if to_bf16 else 0), _p(out))
+    return out
+
+
+def qlinear(x, qp, s_eff, group=128, bias=None):
+    x = _f64(x)
+    qp = np.ascontiguousarray(qp, dtype=np.uint8)
+    s_eff = _f64(s_eff)
+    M, K = x.shape
+    N = qp.shape[0]
+    y = np.zeros((M, N), dtype=np.float64)
+    b = _f32(bias) if bias is not None else None
+    lib().orc_qlinear(_p(x), C.c_uint64(M), C.c_uint64(K), _p(qp), _p(s_eff), C.c_uint64(N),
+                      C.c_uint32(group), _p(b) if b is not None else None, _p(y))
+    return y
+
+
+def linear(x, w, bias=None):
+    x = _f64(x)
+    w = _f32(w)
+    M, K = x.shape
+    N = w.shape[0]
+    y = np.zeros((M, N), dtype=np.float64)
+    b = _f32(bias) if bias is not None else None
+    lib().orc_linear(_p(x), C.c_uint64(M), C.c_uint64(K), _p(w), C.c_uint64(N),
+                     _p(b) if b is not None else None, _p(y))
+    return y
+
+
+def sumsq_bf16(y):
+    y = _f64(y)
+    return float(lib().orc_sumsq_bf16(_p(y), C.c_uint64(y.size)))
+
+
+# --------------------------------------------------------------- blocks ----
+def rmsnorm(x, gain, eps=1e-5):
+    x = _f64(x)
+    g = _f32(gain)
+    y = np.zeros_like(x)
+    lib().orc_rmsnorm(_p(x), C.c_uint64(x.shape[0]), C.c_uint64(x.shape[1]), _p(g),
+                      C.c_double(eps), _p(y))
+    return y
+
+
+def layernorm(x, gain, bias, eps=1e-5):
+    x = _f64(x)
+    g, b = _f32(gain), _f32(bias)
+    y = np.zeros_like(x)
+    lib().orc_layernorm(_p(x), C.c_uint64(x.shape[0]), C.c_uint64(x.shape[1]), _p(g), _p(b),
+                        C.c_double(eps), _p(y))
+    return y
+
+
+def rope(x, B, S, col0, n_heads, dh, theta=10000.0):
+    x = _f64(x).copy()
+    lib().orc_rope(_p(x), C.c_uint64(B), C.c_uint64(S), C.c_uint64(x.shape[1]), C.c_uint64(col0),
+                   C.c_uint64(n_heads), C.c_uint64(dh), C.c_double(theta))
+    return x
+
+
+def attention(qkv, B, S, n_heads, dh):
+    qkv = _f64(qkv)
+    out = np.zeros((B * S, n_heads * dh), dtype=np.float64)
+    lib().orc_attention(_p(qkv), C.c_uint64(B), C.c_uint64(S), C.c_uint64(n_heads),
+                        C.c_uint64(dh), _p(out))
+    return out
+
+
+def swiglu(gu, F):
+    gu = _f64(gu)
+    out = np.zeros((gu.shape[0], F), dtype=np.float64)
+    lib().orc_swiglu(_p(gu), C.c_uint64(gu.shape[0]), C.c_uint64(F), _p(out))
+    return out
+
+
+def next_token_ce(logits, tok):
+    logits = _f64(logits)
+    tok = np.ascontiguousarray(tok, dtype=np.int32)
+    B, S = tok.shape
+    return float(lib().orc_next_token_ce(_p(logits), _p(tok), C.c_uint64(B), C.c_uint64(S),
+                                         C.c_uint64(logits.shape[-1])))
+
+
+# ---------------------------------------------------------------- model ----
+class _Cfg(C.Structure):
+    _fields_ = [("arch", C.c_uint32), ("n_layers", C.c_uint32), ("d_model", C.c_uint32),
+                ("n_heads", C.c_uint32), ("d_ffn", C.c_uint32), ("vocab", C.c_uint32),
+                ("max_seq", C.c_uint32), ("group", C.c_uint32),
+                ("norm_eps", C.c_double), ("rope_theta", C.c_double)]
+
+
+@dataclass
+class Segment:
+    """One quantized linear's slice of the scale arena."""
+    name: str
+    offset: int      # first scale in the arena
+    rows: int        # N
+    G: int           # K / group
+    row_base: int    # model-wide index of its first output row
+
+
+@dataclass
+class Model:
+    shape: dict
+    tensors: list            # numpy arrays in forward order (fp32 bf16-valued, or uint8 packed)
+    names: list
+    scales: np.ndarray       # flat fp32 arena of bf16-valued scales
+    segments: list = field(default_factory=list)
+    group: int = 128
+
+    @property
+    def n_rows(self):
+        return sum(s.rows for s in self.segments)
+
+
+def build_model(shape: dict, table, group=128) -> Model:
+    """Quantize the 'w' entries of a (name, kind, array) table with RTN
+    (Eq. 3 with the absmax scale) and lay the scales out in arena order."""
+    tensors, names, segs, scales = [], [], [], []
+    off = 0
+    row = 0
+    for name, kind, arr in table:
+        if kind == "w":
+            qp, s = rtn_quantize(arr, group)
+            tensors.append(qp)
+            segs.append(Segment(name, off, s.shape[0], s.shape[1], row))
+            scales.append(s.reshape(-1))
+            off += s.size
+            row += s.shape[0]
+        else:
+            tensors.append(_f32(arr))
+        names.append(name)
+    return Model(shape, tensors, names, np.concatenate(scales).astype(np.float32), segs, group)
+
+
+def perturbed_scales(model: Model, seed: int, eps_signed: float, scales=None) -> np.ndarray:
+    """Delta + (sigma*eps) z over the whole arena (PERTURB_SCALES, functional form)."""
+    sc = model.scales if scales is None else scales
+    out = np.zeros(sc.size, dtype=np.float64)
+    for sg in model.segments:
+        sl = slice(sg.offset, sg.offset + sg.rows * sg.G)
+        out[sl] = effective_scales(sc[sl].reshape(sg.rows, sg.G), sg.row_base, seed,
+                                   eps_signed).reshape(-1)
+    return out
+
+
+def forward_loss(model: Model, s_eff, tok, act_bf16=True, want_hidden=False, want_logits=False):
+    sh = model.shape
+    cfg = _Cfg(0 if sh["arch"] == "llama" else 1, sh["n_layers"], sh["d_model"], sh["n_heads"],
+               sh["d_ffn"], sh["vocab"], sh["max_seq"], model.group,
+               sh.get("norm_eps", 1e-5), sh.get("rope_theta", 10000.0))
+    tok = np.ascontiguousarray(tok, dtype=np.int32)
+    B, S = tok.shape
+    s_eff = _f64(s_eff)
+    ptrs = (C.c_void_p * len(model.tensors))(*[t.ctypes.data for t in model.tensors])
+    hid = np.zeros((B * S, sh["d_model"]), dtype=np.float64) if want_hidden else None
+    lg = np.zeros((B * S, sh["vocab"]), dtype=np.float64) if want_logits else None
+    loss = lib().orc_forward_loss(C.byref(cfg), ptrs, _p(s_eff), _p(tok), C.c_uint32(B),
+                                  C.c_uint32(S), C.c_int(1 if act_bf16 else 0),
+                                  _p(hid) if hid is not None else None,
+                                  _p(lg) if lg is not None else None)
+    extra = tuple(x for x in (hid, lg) if x is not None)
+    return (float(loss),) + extra if extra else float(loss)
+
+
+def spsa_d(loss_plus, loss_minus, eps):
+    return float(lib().orc_spsa_d(loss_plus, loss_minus, eps))
+
+
+def clip(d, Cthr):
+    return float(lib().orc_clip(d, Cthr))
+
+
+def update_scales(model: Model, seed: int, eta: float, d_clipped: float, scales=None) -> np.ndarray:
+    """Returns the updated arena (Algorithm 1's update loop); input untouched."""
+    sc = (model.scales if scales is None else scales).astype(np.float32).copy()
+    for sg in model.segments:
+        view = sc[sg.offset:sg.offset + sg.rows * sg.G]
+        lib().orc_update_scales(_p(view), C.c_uint32(sg.rows), C.c_uint32(sg.G),
+                                C.c_uint32(sg.row_base), C.c_uint64(seed), C.c_float(eta),
+                                C.c_float(d_clipped))
+    return sc
+
+
+def qzo_step(model: Model, tok, seed, eps, eta, Cthr, act_bf16=True):
+    """One iteration of Algorithm 1.  Returns dict(loss_plus, loss_minus, d,
+    d_clipped, status, scales) and leaves `model` untouched.  A non-finite d
+    skips the update (status 1): the paper's clip is undefined there."""
+    lp = forward_loss(model, perturbed_scales(model, seed, +eps), tok, act_bf16)
+    lm = forward_loss(model, perturbed_scales(model, seed, -eps), tok, act_bf16)
+    d = spsa_d(np.float32(lp), np.float32(lm), np.float32(eps))
+    if not np.isfinite(d):
+        return dict(loss_plus=lp, loss_minus=lm, d=d, d_clipped=0.0, status=1,
+                    scales=model.scales.copy())
+    dc = clip(d, Cthr)
+    return dict(loss_plus=lp, loss_minus=lm, d=d, d_clipped=dc, status=0,
+                scales=update_scales(model, seed, eta, dc))

@@ -1,0 +1,359 @@
+"""Pins for the oracle's forward blocks, Q-SPSA scalar, DDC and update (CPU only)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from paper_2505_13430_amd import synth
+
+
+def _t(x):
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float64))
+
+
+# ------------------------------------------------ blocks vs library routines ----
+def test_qlinear_special_cases_and_matmul(oracle):
+    rng = np.random.default_rng(2)
+    M, N, K = 5, 7, 256
+    x = rng.standard_normal((M, K))
+    # s = 1, q in {+1,-1, 0}: Y is a signed sum of X columns
+    q = np.zeros((N, K), np.int64)
+    q[0, 3] = 1
+    q[1, 200] = -1
+    q[2, :] = 1
+    q[3, 128:] = -1
+    qp = ((q[:, 0::2] + 8) | ((q[:, 1::2] + 8) << 4)).astype(np.uint8)
+    y = oracle.qlinear(x, qp, np.ones((N, 2)))
+    assert np.allclose(y[:, 0], x[:, 3], atol=1e-13) and np.allclose(y[:, 1], -x[:, 200], atol=1e-13)
+    assert np.allclose(y[:, 2], x.sum(1), atol=1e-12) and np.allclose(y[:, 3], -x[:, 128:].sum(1), atol=1e-12)
+    assert np.abs(y[:, 4:]).max() == 0
+    # the group index is k // 128 along K of the same output row
+    se = np.arange(1, 2 * N + 1, dtype=np.float64).reshape(N, 2)
+    y = oracle.qlinear(x, qp, se)
+    assert np.allclose(y[:, 2], se[2, 0] * x[:, :128].sum(1) + se[2, 1] * x[:, 128:].sum(1))
+    # general case against a library matmul of the dequantized matrix, with bias
+    qp = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    qi = oracle.unpack_int4(qp, K).astype(np.float64)
+    se = rng.uniform(0.005, 0.02, (N, 2))
+    b = rng.standard_normal(N).astype(np.float32)
+    want = _t(x) @ _t(np.repeat(se, 128, axis=1) * qi).T + _t(b)
+    assert np.allclose(oracle.qlinear(x, qp, se, bias=b), want.numpy(), rtol=1e-12, atol=1e-12)
+    w = rng.standard_normal((N, K)).astype(np.float32)
+    assert np.allclose(oracle.linear(x, w), (_t(x) @ _t(w).T).numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_dequant_is_scale_times_integer(oracle):
+    rng = np.random.default_rng(3)
+    N, K = 9, 384
+    qp = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    s = synth.bf16_exact(rng.uniform(0.005, 0.02, (N, 3)).astype(np.float32))
+    qi = oracle.unpack_int4(qp, K).astype(np.float32)
+    # eps = 0: Eq. 4, W = Delta * wbar
+    assert np.array_equal(oracle.dequant(qp, s, seed=1, row_base=0, eps_signed=0.0),
+                          np.repeat(s, 128, axis=1) * qi)
+    # eps != 0: (Delta + eps z) * wbar with z of (row_base + n, g); antisymmetric in the sign
+    z = oracle.scale_normals(11, 40, N, 3)
+    wp = oracle.dequant(qp, s, 11, 40, +1e-3)
+    wm = oracle.dequant(qp, s, 11, 40, -1e-3)
+    want = (s.astype(np.float64) + 1e-3 * z)
+    assert np.allclose(wp, np.repeat(want, 128, axis=1) * qi, rtol=1e-6, atol=1e-9)
+    assert np.allclose((wp.astype(np.float64) + wm) / 2, np.repeat(s, 128, axis=1) * qi, rtol=1e-6, atol=1e-9)
+    se = oracle.effective_scales(s, 40, 11, 1e-3)
+    assert np.array_equal(se.astype(np.float32), (np.float32(1e-3) * z.astype(np.float64) + s).astype(np.float32))
+    wb = oracle.dequant(qp, s, 11, 40, +1e-3, to_bf16=True)
+    assert np.array_equal(wb, torch.from_numpy(wp).to(torch.bfloat16).float().numpy())
+
+
+def test_norms_against_torch(oracle):
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((6, 96)) * 3 + 0.5
+    g = rng.standard_normal(96).astype(np.float32)
+    b = rng.standard_normal(96).astype(np.float32)
+    assert np.allclose(oracle.rmsnorm(x, g, 1e-5),
+                       F.rms_norm(_t(x), (96,), _t(g), 1e-5).numpy(), rtol=1e-12)
+    assert np.allclose(oracle.layernorm(x, g, b, 1e-5),
+                       F.layer_norm(_t(x), (96,), _t(g), _t(b), 1e-5).numpy(), rtol=1e-11, atol=1e-12)
+
+
+def test_rope_properties(oracle):
+    rng = np.random.default_rng(6)
+    B, S, H, dh = 2, 9, 3, 16
+    x = rng.standard_normal((B * S, 3 * H * dh))
+    r = oracle.rope(x, B, S, col0=0, n_heads=H, dh=dh)
+    assert np.array_equal(r[:, H * dh:], x[:, H * dh:])            # only the addressed block moves
+    xr, rr = x[:, :H * dh].reshape(B, S, H, dh), r[:, :H * dh].reshape(B, S, H, dh)
+    assert np.allclose(rr[:, 0], xr[:, 0])                          # position 0 is the identity
+    # complex form: (x_i + i x_{i+dh/2}) * exp(i t theta^(-2i/dh))
+    t = np.arange(S)[None, :, None, None]
+    i = np.arange(dh // 2)[None, None, None, :]
+    rot = np.exp(1j * t * 10000.0 ** (-2.0 * i / dh))
+    zc = (xr[..., :dh // 2] + 1j * xr[..., dh // 2:]) * rot
+    assert np.allclose(rr[..., :dh // 2], zc.real) and np.allclose(rr[..., dh // 2:], zc.imag)
+    # q.k after rotation depends on the position difference only
+    q = rng.standard_normal(dh)
+    k = rng.standard_normal(dh)
+    buf = np.zeros((1 * 8, 2 * dh))
+    buf[:, :dh] = q
+    buf[:, dh:] = k
+    rq = oracle.rope(oracle.rope(buf, 1, 8, 0, 1, dh), 1, 8, dh, 1, dh)
+    dots = [rq[a, :dh] @ rq[a - 2, dh:] for a in range(2, 8)]
+    assert np.allclose(dots, dots[0])
+
+
+def test_attention_swiglu_ce_against_torch(oracle):
+    rng = np.random.default_rng(7)
+    B, S, H, dh = 2, 11, 3, 8
+    d = H * dh
+    qkv = rng.standard_normal((B * S, 3 * d))
+    q, k, v = [_t(qkv[:, j * d:(j + 1) * d]).reshape(B, S, H, dh).transpose(1, 2) for j in range(3)]
+    want = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(B * S, d)
+    assert np.allclose(oracle.attention(qkv, B, S, H, dh), want.numpy(), rtol=1e-10, atol=1e-12)
+    gu = rng.standard_normal((5, 24))
+    assert np.allclose(oracle.swiglu(gu, 12), (F.silu(_t(gu[:, :12])) * _t(gu[:, 12:])).numpy(), rtol=1e-12)
+    V = 37
+    logits = rng.standard_normal((B * S, V)) * 4
+    tok = rng.integers(0, V, (B, S)).astype(np.int32)
+    lt = _t(logits).reshape(B, S, V)[:, :-1].reshape(-1, V)
+    tgt = torch.from_numpy(tok[:, 1:].astype(np.int64)).reshape(-1)
+    assert math.isclose(oracle.next_token_ce(logits, tok), F.cross_entropy(lt, tgt).item(), rel_tol=1e-12)
+
+
+# ----------------------------------------- whole forward vs torch library ops ----
+def _torch_forward(model, s_eff, tok, oracle):
+    """The same decoder written with torch's own fp64 ops (no oracle routine)."""
+    sh = model.shape
+    d, Hh, Fd, V = sh["d_model"], sh["n_heads"], sh["d_ffn"], sh["vocab"]
+    dh = d // Hh
+    B, S = tok.shape
+    T = {n: t for n, t in zip(model.names, model.tensors)}
+    seg = {s.name: s for s in model.segments}
+
+    def W(name):
+        s = seg[name]
+        K = T[name].shape[1] * 2
+        qi = oracle.unpack_int4(T[name], K).astype(np.float64)
+        se = s_eff[s.offset:s.offset + s.rows * s.G].reshape(s.rows, s.G)
+        return _t(np.repeat(se, 128, axis=1) * qi)
+
+    tk = torch.from_numpy(tok.astype(np.int64))
+    h = _t(T["tok_emb"])[tk]                                   # [B,S,d]
+    llama = sh["arch"] == "llama"
+    if not llama:
+        h = h + _t(T["pos_emb"])[:S]
+    pos = torch.arange(S, dtype=torch.float64)
+    inv = 10000.0 ** (-torch.arange(0, dh, 2, dtype=torch.float64) / dh)
+    ang = pos[:, None] * inv[None, :]
+    cos, sin = torch.cos(ang)[None, None], torch.sin(ang)[None, None]
+
+    def rot(x):   # [B,H,S,dh]
+        a, b = x[..., :dh // 2], x[..., dh // 2:]
+        return torch.cat([a * cos - b * sin, b * cos + a * sin], -1)
+
+    for l in range(sh["n_layers"]):
+        p = f"l{l}."
+        if llama:
+            a = F.rms_norm(h, (d,), _t(T[p + "attn_norm"]), 1e-5)
+            qkv = a @ W(p + "wqkv").T
+        else:
+            a = F.layer_norm(h, (d,), _t(T[p + "ln1_g"]), _t(T[p + "ln1_b"]), 1e-5)
+            qkv = a @ W(p + "wqkv").T + _t(T[p + "bqkv"])
+        q, k, v = [x.reshape(B, S, Hh, dh).transpose(1, 2) for x in qkv.split(d, -1)]
+        if llama:
+            q, k = rot(q), rot(k)
+        o = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(B, S, d)
+        if llama:
+            h = h + o @ W(p + "wo").T
+            b = F.rms_norm(h, (d,), _t(T[p + "ffn_norm"]), 1e-5)
+            gu = b @ W(p + "wgu").T
+            h = h + (F.silu(gu[..., :Fd]) * gu[..., Fd:]) @ W(p + "wdown").T
+        else:
+            h = h + o @ W(p + "wo").T + _t(T[p + "bo"])
+            b = F.layer_norm(h, (d,), _t(T[p + "ln2_g"]), _t(T[p + "ln2_b"]), 1e-5)
+            f1 = F.relu(b @ W(p + "wfc1").T + _t(T[p + "bfc1"]))
+            h = h + f1 @ W(p + "wfc2").T + _t(T[p + "bfc2"])
+    if llama:
+        h = F.rms_norm(h, (d,), _t(T["final_norm"]), 1e-5)
+    else:
+        h = F.layer_norm(h, (d,), _t(T["lnf_g"]), _t(T["lnf_b"]), 1e-5)
+    logits = h @ _t(T["lm_head"]).T
+    return F.cross_entropy(logits[:, :-1].reshape(-1, V), tk[:, 1:].reshape(-1)).item()
+
+
+MINI = dict(n_layers=2, d_model=128, n_heads=2, d_ffn=256, vocab=96, max_seq=12, batch=2, seq=12)
+
+
+@pytest.mark.parametrize("arch", ["llama", "opt"])
+def test_forward_matches_torch_composition(oracle, arch):
+    sh = dict(MINI, arch=arch)
+    m = oracle.build_model(sh, synth.tensor_table(sh, 3))
+    tok = synth.tokens(sh, 4)
+    se = oracle.perturbed_scales(m, seed=5, eps_signed=1e-3)
+    got = oracle.forward_loss(m, se, tok, act_bf16=False)
+    assert math.isclose(got, _torch_forward(m, se, tok, oracle), rel_tol=1e-10)
+    # random init: loss is about ln V (closed form, loose)
+    assert abs(got - math.log(sh["vocab"])) < 0.2
+    # 16-bit activation rounding moves the loss only by bf16-sized amounts
+    assert abs(oracle.forward_loss(m, se, tok, act_bf16=True) - got) < 2e-2 * got
+
+
+# --------------------------------------------------------- Q-SPSA (Eq. 5) ----
+def test_spsa_scalar_is_exact_directional_derivative_on_a_quadratic(oracle):
+    # l(s) = sum_mn Y^2 with Y = X (s (.) q)^T is quadratic in s, so the central
+    # difference of Eq. 5 equals grad_s l . z up to rounding, grad in closed form.
+    rng = np.random.default_rng(8)
+    M, N, K, eps, seed = 6, 5, 256, 1e-3, 77
+    x = rng.standard_normal((M, K))
+    qp = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    s = synth.bf16_exact(rng.uniform(0.005, 0.02, (N, 2)).astype(np.float32))
+    lp = (oracle.qlinear(x, qp, oracle.effective_scales(s, 3, seed, +eps)) ** 2).sum()
+    lm = (oracle.qlinear(x, qp, oracle.effective_scales(s, 3, seed, -eps)) ** 2).sum()
+    qi = oracle.unpack_int4(qp, K).astype(np.float64)
+    y0 = x @ (np.repeat(s.astype(np.float64), 128, 1) * qi).T                # [M,N]
+    part = np.einsum("mgk,ngk->mng", x.reshape(M, 2, 128), qi.reshape(N, 2, 128))
+    grad = 2 * np.einsum("mn,mng->ng", y0, part)
+    z = oracle.scale_normals(seed, 3, N, 2).astype(np.float64)
+    eps32 = float(np.float32(eps))
+    assert math.isclose((lp - lm) / (2 * eps32), (grad * z).sum(), rel_tol=1e-5)
+
+
+def test_spsa_scalar_matches_brute_force_finite_differences(oracle):
+    # d = (l+ - l-)/(2 eps) ~ z^T grad l (Eq. 5), grad by one central difference
+    # per scale on a sub-tiny model, everything in double without A16 rounding.
+    sh = dict(arch="llama", n_layers=1, d_model=128, n_heads=2, d_ffn=128, vocab=48, max_seq=6,
+              batch=2, seq=6)
+    m = oracle.build_model(sh, synth.tensor_table(sh, 9))
+    tok = synth.tokens(sh, 10)
+    base = m.scales.astype(np.float64)
+    n = base.size
+    grad = np.zeros(n)
+    h = 1e-5
+    for i in range(n):
+        e = np.zeros(n)
+        e[i] = h
+        grad[i] = (oracle.forward_loss(m, base + e, tok, False)
+                   - oracle.forward_loss(m, base - e, tok, False)) / (2 * h)
+    z = np.concatenate([oracle.scale_normals(21, sg.row_base, sg.rows, sg.G).ravel()
+                        for sg in m.segments]).astype(np.float64)
+    eps = 1e-4
+    lp = oracle.forward_loss(m, oracle.perturbed_scales(m, 21, +eps), tok, False)
+    lm = oracle.forward_loss(m, oracle.perturbed_scales(m, 21, -eps), tok, False)
+    d = (lp - lm) / (2 * float(np.float32(eps)))
+    assert abs(grad @ z) > 1e-3
+    assert math.isclose(d, grad @ z, rel_tol=2e-3)
+
+
+def test_functional_perturbation_equals_algorithm_1_sequence(oracle):
+    # Algorithm 1 rewrites Delta three times (+eps, -2eps, +eps); on scales of
+    # unlimited precision that visits Delta+eps z, Delta-eps z and returns to Delta.
+    sh = dict(MINI, arch="llama")
+    m = oracle.build_model(sh, synth.tensor_table(sh, 3))
+    sg = m.segments[2]
+    s0 = m.scales[sg.offset:sg.offset + sg.rows * sg.G].reshape(sg.rows, sg.G)
+    eps = 1e-3
+    s = s0.astype(np.float64).copy()
+
+    def perturb(arr, e):
+        import ctypes as C
+        oracle.lib().orc_perturb_in_place(arr.ctypes.data_as(C.c_void_p), C.c_uint32(sg.rows),
+                                          C.c_uint32(sg.G), C.c_uint32(sg.row_base), C.c_uint64(31),
+                                          C.c_double(e))
+    perturb(s, eps)
+    plus = oracle.effective_scales(s0, sg.row_base, 31, np.float32(eps))
+    assert np.allclose(s, plus, rtol=1e-6, atol=1e-10)
+    perturb(s, -2 * eps)
+    minus = oracle.effective_scales(s0, sg.row_base, 31, -np.float32(eps))
+    assert np.allclose(s, minus, rtol=1e-6, atol=1e-10)
+    perturb(s, eps)
+    assert np.allclose(s, s0, rtol=0, atol=1e-15)
+    # same z in both passes: the midpoint of the two perturbed scales is Delta
+    assert np.allclose((plus + minus) / 2, s0, rtol=1e-6, atol=1e-10)
+
+
+# ------------------------------------------------- DDC (Eq. 6) and update ----
+def test_clip_is_eq6(oracle):
+    for d in (-1e9, -100.5, -100.0, -3.25, 0.0, 1e-7, 99.9, 100.0, 100.1, 1e30):
+        for Cthr in (0.0, 1.0, 100.0):
+            c = oracle.clip(d, Cthr)
+            assert abs(c) <= Cthr and float(c) ** 2 <= float(np.float32(d)) ** 2
+            if abs(d) <= Cthr:
+                assert c == np.float32(d)
+            else:
+                assert c == math.copysign(Cthr, d)
+    assert oracle.spsa_d(7.0, 6.5, 1e-3) == np.float32(0.5) / (np.float32(2) * np.float32(1e-3))
+    assert oracle.spsa_d(6.5, 7.0, 1e-3) < 0
+
+
+def test_update_rule(oracle):
+    sh = dict(MINI, arch="llama")
+    m = oracle.build_model(sh, synth.tensor_table(sh, 3))
+    s0 = m.scales
+    assert np.array_equal(oracle.update_scales(m, 5, 0.0, 50.0), s0)         # eta = 0
+    assert np.array_equal(oracle.update_scales(m, 5, 1e-5, 0.0), s0)         # C = 0 <=> d' = 0: zero-shot
+    up = oracle.update_scales(m, 5, 1e-5, 40.0)
+    z = np.concatenate([oracle.scale_normals(5, g.row_base, g.rows, g.G).ravel() for g in m.segments])
+    want = torch.from_numpy(np.maximum(s0.astype(np.float64) - 1e-5 * 40.0 * z, 0)).to(torch.bfloat16).float().numpy()
+    # the fp32 fma and the double formula round to the same bf16 except on a few near-ties
+    assert (up != want).mean() < 2e-3
+    assert np.abs(up - want).max() <= np.abs(s0).max() * 2 ** -7
+    # descent direction: s moves against sign(d' z)
+    moved = up != s0
+    assert moved.mean() > 0.5
+    assert (np.sign(up[moved] - s0[moved]) == -np.sign(z[moved])).all()
+    # non-negative clamp
+    big = oracle.update_scales(m, 5, 1.0, 100.0)
+    assert big.min() == 0.0 and (big[z > 0.01] == 0).all() and (big[z < -0.01] > 0).all()
+    # opposite sign of d' moves the other way
+    dn = oracle.update_scales(m, 5, 1e-5, -40.0)
+    assert (np.sign(dn[moved] - s0[moved]) * np.sign(up[moved] - s0[moved]) <= 0).all()
+
+
+def test_step_special_cases(oracle):
+    sh = dict(MINI, arch="llama")
+    m = oracle.build_model(sh, synth.tensor_table(sh, 3))
+    tok = synth.tokens(sh, 4)
+    r = oracle.qzo_step(m, tok, seed=1, eps=0.0, eta=1e-5, Cthr=100.0)
+    assert r["loss_plus"] == r["loss_minus"] and r["status"] == 1          # 0/0: skipped
+    assert np.array_equal(r["scales"], m.scales)
+    r = oracle.qzo_step(m, tok, seed=1, eps=1e-3, eta=1e-5, Cthr=0.0)
+    assert r["d_clipped"] == 0.0 and np.array_equal(r["scales"], m.scales)
+    a = oracle.forward_loss(m, oracle.perturbed_scales(m, 1, +1e-3), tok)
+    b = oracle.forward_loss(m, oracle.perturbed_scales(m, 1, -1e-3), tok)
+    r = oracle.qzo_step(m, tok, seed=1, eps=1e-3, eta=1e-5, Cthr=100.0)
+    assert (r["loss_plus"], r["loss_minus"]) == (a, b) and a != b
+    assert r["d"] == oracle.spsa_d(np.float32(a), np.float32(b), np.float32(1e-3))
+    r2 = oracle.qzo_step(m, tok, seed=2, eps=1e-3, eta=1e-5, Cthr=100.0)
+    assert r2["loss_plus"] != r["loss_plus"]
+
+
+def test_clipped_steps_descend_on_a_quadratic_toy(oracle):
+    # l(s) = 1/2 || s (.) q - t ||^2 over one segment's scales: repeated QZO steps
+    # with clipping keep ||s|| bounded and reduce l.
+    rows, G = 64, 8
+    rng = np.random.default_rng(12)
+    q = rng.integers(1, 8, (rows, G)).astype(np.float64)
+    target = rng.uniform(0.005, 0.02, (rows, G)) * q
+
+    class Seg:
+        pass
+    sg = Seg()
+    sg.name, sg.offset, sg.rows, sg.G, sg.row_base = "toy", 0, rows, G, 0
+    m = oracle.Model(shape={}, tensors=[], names=[], scales=np.full(rows * G, 0.0125, np.float32), segments=[sg])
+    m.scales = oracle.bf16_rne(m.scales)
+
+    def loss(se):
+        return 0.5 * ((se.reshape(rows, G) * q - target) ** 2).sum()
+    l0 = loss(m.scales.astype(np.float64))
+    eps, eta, Cthr = 1e-3, 5e-5, 1.0
+    clipped = 0
+    for step in range(300):
+        lp = loss(oracle.perturbed_scales(m, step, +eps))
+        lm = loss(oracle.perturbed_scales(m, step, -eps))
+        d = oracle.spsa_d(np.float32(lp), np.float32(lm), np.float32(eps))
+        dc = oracle.clip(d, Cthr)
+        clipped += dc != d
+        m.scales = oracle.update_scales(m, step, eta, dc)
+        assert np.isfinite(m.scales).all() and m.scales.min() >= 0 and m.scales.max() < 0.05
+    assert clipped > 0
+    assert loss(m.scales.astype(np.float64)) < 0.8 * l0
