@@ -1,0 +1,193 @@
+/*
+ * qzo.h -- C ABI of the MI355X (gfx950) hot path of Quantized Zeroth-order
+ * Optimization (QZO): two perturbed forward passes through a weight-quantized
+ * decoder, the SPSA directional derivative, its clipping, and the in-place
+ * update of the quantization scales (paper Sec. 3.2: Def. 3.3 / Eq. 5
+ * "Q-SPSA", Eq. 6 "DDC", Algorithm 1).
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory owned by the caller; the
+ *    library borrows it for the duration of the call (model tensors and the
+ *    scale arena: for the lifetime of the model).  Pointers not so named are
+ *    host memory.  Device pointers must be 16-byte aligned.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and returns without synchronising.  Results stay on
+ *    the device.
+ *  - Every function returns QZO_OK or a negative qzo_status; on error nothing
+ *    has been enqueued and qzo_last_error() describes the reason (thread-local
+ *    string, valid until the next failing call on that thread).
+ *  - bf16 = upper 16 bits of an IEEE fp32, round-to-nearest-even on store.
+ *
+ * Data layout
+ *  - Quantized weight of a linear with N outputs and K inputs: packed int4,
+ *    uint8 [N, K/2], K contiguous; byte j of row n holds column 2j in its low
+ *    nibble and 2j+1 in its high nibble; stored nibble = integer weight + 8
+ *    (integer weight in [-8, 7], the paper's w-bar of Eq. 3).
+ *  - Its scales (the paper's Delta): bf16 [N, K/group], group = 128 consecutive
+ *    input features of one output row; dequantization is Eq. 4, w = Delta*w-bar.
+ *  - Perturbation noise z is never stored.  z for (row r, group g) is a pure
+ *    function of (seed, r, g): Philox4x32-10 with key = seed and counter =
+ *    (r, g/8, stream_id, 0); each 32-bit output word yields one Box-Muller
+ *    pair, so one counter serves groups 8*(g/8) .. 8*(g/8)+7 of row r.  r is
+ *    the row's index in the model-wide enumeration of quantized output rows
+ *    (`row_base` of a tensor + row within the tensor).
+ */
+#ifndef QZO_H_
+#define QZO_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  QZO_OK = 0,
+  QZO_ERR_ARG = -1,        /* null pointer, bad enum, negative clip, sign not +-1 ... */
+  QZO_ERR_SHAPE = -2,      /* dimension not supported by the kernels */
+  QZO_ERR_ALIGN = -3,      /* device pointer not 16-byte aligned */
+  QZO_ERR_WORKSPACE = -4,  /* workspace too small */
+  QZO_ERR_NONFINITE = -5,  /* reported in qzo_step_result.status only */
+  QZO_ERR_HIP = -6,        /* a HIP runtime call failed */
+  QZO_ERR_UNSUPPORTED = -7
+} qzo_status;
+
+typedef struct qzo_model qzo_model; /* opaque, host object owned by the library */
+
+typedef struct {
+  uint32_t struct_size; /* sizeof(qzo_model_config), for versioning */
+  uint32_t arch;        /* 0: Llama family (RMSNorm, RoPE, SwiGLU, no bias)
+                           1: OPT family (LayerNorm, learned positions, ReLU, biases) */
+  uint32_t n_layers, d_model, n_heads, d_ffn, vocab, max_seq;
+  uint32_t group_size;  /* 128 */
+  uint32_t quant;       /* 0: int4 + per-group bf16 scales */
+  float norm_eps;       /* 1e-5 */
+  float rope_theta;     /* 10000 (Llama only) */
+} qzo_model_config;
+
+typedef struct {
+  const void* ptr_dev;
+  uint64_t bytes;
+} qzo_buf;
+
+typedef struct {
+  float loss_plus, loss_minus; /* l+ and l- of Algorithm 1 */
+  float d;                     /* (l+ - l-) / (2 eps) */
+  float d_clipped;             /* Eq. 6 */
+  int32_t status;              /* QZO_OK, or QZO_ERR_NONFINITE: d not finite, update skipped */
+  uint32_t reserved[3];
+} qzo_step_result;
+
+/*
+ * Binds a model to caller-owned device tensors (Algorithm 1's inputs: scales
+ * Delta, quantized weights theta-bar).  `tensors` lists, in forward order:
+ *   Llama: tok_emb bf16[V,d]; per layer { attn_norm bf16[d], wqkv int4[3d,d/2],
+ *          wo int4[d,d/2], ffn_norm bf16[d], wgu int4[2F,d/2] (gate rows, then up
+ *          rows), wdown int4[d,F/2] }; final_norm bf16[d]; lm_head bf16[V,d].
+ *   OPT:   tok_emb; pos_emb bf16[max_seq,d]; per layer { ln1_g, ln1_b bf16[d],
+ *          wqkv int4[3d,d/2], bqkv bf16[3d], wo int4[d,d/2], bo bf16[d], ln2_g, ln2_b,
+ *          wfc1 int4[F,d/2], bfc1 bf16[F], wfc2 int4[d,F/2], bfc2 bf16[d] };
+ *          lnf_g, lnf_b; lm_head bf16[V,d].
+ * `scale_arena_dev` holds every quantized linear's bf16 scales back to back in
+ * the same order ([N, K/128] each); it is the only model memory the library
+ * writes.  Only the decoder-block linears are quantized and trained (their
+ * scale count is the paper's Table 2 "trainable parameters"); embeddings,
+ * norms, biases and lm_head are fixed bf16.  Row ids for the noise follow the
+ * arena order.  Requires d_model % 128 == 0, d_ffn % 128 == 0,
+ * d_model/n_heads in {64, 128}.  Allocates a few KB of device tables (RoPE
+ * angles, update segments) that qzo_model_destroy frees.
+ */
+qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
+                            uint32_t n_tensors, void* scale_arena_dev, uint64_t n_scales,
+                            qzo_model** out);
+qzo_status qzo_model_destroy(qzo_model* m);
+
+/* Number of quantization scales a config has (host arithmetic only). */
+qzo_status qzo_model_scale_count(const qzo_model_config* cfg, uint64_t* out);
+
+/* Bytes of device workspace qzo_forward_loss / qzo_step need for (batch, seq). */
+qzo_status qzo_workspace_bytes(const qzo_model* m, uint32_t batch, uint32_t seq, uint64_t* out);
+
+/*
+ * One perturbed forward pass: L((Delta + sign*eps*z) (.) theta-bar; B) of Eq. 5,
+ * next-token cross-entropy averaged over the batch*(seq-1) predicted positions.
+ * The stored scales are not modified: the perturbed scale is formed inside the
+ * GEMM's weight tile as one fp32 fma (the functional form of PERTURB_SCALES in
+ * Algorithm 1).  tokens_dev: int32 [batch, seq], values in [0, vocab).
+ * loss_dev: one fp32.  seq <= max_seq.  sign must be +1 or -1.
+ */
+qzo_status qzo_forward_loss(qzo_model* m, const int32_t* tokens_dev, uint32_t batch,
+                            uint32_t seq, uint64_t seed, float eps, int sign,
+                            void* workspace_dev, uint64_t workspace_bytes, float* loss_dev,
+                            void* stream);
+
+/*
+ * One iteration of Algorithm 1: l+ and l- from two perturbed forwards with the
+ * same seed, d = (l+ - l-)/(2 eps), d' = clip(d, -C, C) (Eq. 6), then
+ * Delta_i <- max(Delta_i - eta*d'*z_i, 0) over the whole arena with z
+ * regenerated from `seed`.  No host synchronisation inside; result_dev
+ * receives the scalars.  clip must be >= 0.  A non-finite d leaves the scales
+ * untouched and sets result.status = QZO_ERR_NONFINITE.
+ */
+qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                    uint64_t seed, float eps, float eta, float clip, void* workspace_dev,
+                    uint64_t workspace_bytes, qzo_step_result* result_dev, void* stream);
+
+/* The update loop of Algorithm 1 alone over the model's arena, with d' given by
+ * the host (eta*d' formed as one fp32 product). */
+qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float d_clipped,
+                                  void* stream);
+
+/*
+ * A single perturbed W4A16 linear (Eq. 4-5): Y = X * W_eff^T with
+ * W_eff[n,k] = (s[n,k/group] + sign*eps*z(row_base+n, k/group)) * wbar[n,k].
+ * x_dev bf16 [M,K] row-major; q_dev packed int4 [N,K/2]; s_dev bf16 [N,K/group];
+ * y_dev bf16 [M,N].  sumsq_dev (nullable): one fp32 receiving sum_{m,n} y^2 of
+ * the bf16-rounded outputs.  Requires group == 128, K % 128 == 0, N % 8 == 0.
+ * Uses a library-owned device scratch (per-tile partial sums, allocated on first
+ * use per device) when sumsq_dev is given.
+ */
+qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
+                            uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,
+                            uint32_t group, uint64_t seed, float eps, int sign, void* y_dev,
+                            float* sumsq_dev, void* stream);
+
+/* The update loop of Algorithm 1 on one tensor's scales: s_dev bf16 [n_rows, G],
+ * updated in place with c = eta*d_clipped. */
+qzo_status qzo_apply_update(void* s_dev, uint32_t n_rows, uint32_t G, uint32_t row_base,
+                            uint64_t seed, float eta, float d_clipped, void* stream);
+
+/* RTN quantizer of Eq. 3 with the k=4 absmax scale: w_dev fp32 [N,K] ->
+ * q_dev packed int4 [N,K/2], s_dev bf16 [N,K/group].  Model construction, not
+ * part of the timed step. */
+qzo_status qzo_rtn_quantize(const float* w_dev, uint32_t N, uint32_t K, uint32_t group,
+                            void* q_dev, void* s_dev, void* stream);
+
+/* Inspection entry points used by the parity tests. */
+/* out_dev fp32 [n_rows, G] = z(row0 + r, g), noise stream `stream_id` (0 = group scales). */
+qzo_status qzo_debug_normals(uint64_t seed, uint32_t stream_id, uint32_t row0, uint32_t n_rows,
+                             uint32_t G, float* out_dev, void* stream);
+/* out_dev uint32 [n,4] = Philox4x32-10(ctr = ctr_dev[i][0..3], key = seed). */
+qzo_status qzo_debug_philox(uint64_t seed, const uint32_t* ctr_dev, uint32_t n,
+                            uint32_t* out_dev, void* stream);
+/* out_dev fp32 [n,2] = the normal pair of each 32-bit word. */
+qzo_status qzo_debug_normal_pairs(const uint32_t* words_dev, uint32_t n, float* out_dev,
+                                  void* stream);
+/* w_eff_dev bf16 [N,K] = bf16((s + sign*eps*z) * wbar), the GEMM's B operand. */
+qzo_status qzo_debug_dequant(const void* q_dev, const void* s_dev, uint32_t row_base, uint32_t N,
+                             uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                             void* w_eff_dev, void* stream);
+
+/* qzo_forward_loss that also copies the final normalised hidden states (the lm_head's
+ * input, bf16 [batch*seq, d_model]) to hidden_dev. */
+qzo_status qzo_debug_forward(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                             uint64_t seed, float eps, int sign, void* workspace_dev,
+                             uint64_t workspace_bytes, float* loss_dev, void* hidden_dev,
+                             void* stream);
+
+const char* qzo_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QZO_H_ */

@@ -1,0 +1,193 @@
+"""Thin ctypes binding of libqzo.so (include/qzo.h): argument marshalling only.
+
+Every function has the name of the C entry point it calls and takes torch CUDA
+tensors for device memory.  PyTorch supplies memory and streams; every step of
+the QZO path runs in the library's HIP kernels.  There is no fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqzo.so")
+_lib = None
+
+QZO_OK = 0
+QZO_ERR_ARG, QZO_ERR_SHAPE, QZO_ERR_ALIGN, QZO_ERR_WORKSPACE = -1, -2, -3, -4
+QZO_ERR_NONFINITE, QZO_ERR_HIP, QZO_ERR_UNSUPPORTED = -5, -6, -7
+
+EXPORTS = [
+    "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
+    "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
+    "qzo_apply_update", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
+    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_last_error",
+]
+
+
+class QzoError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"qzo status {status}: {msg}")
+        self.status = status
+
+
+class qzo_model_config(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("arch", C.c_uint32), ("n_layers", C.c_uint32),
+                ("d_model", C.c_uint32), ("n_heads", C.c_uint32), ("d_ffn", C.c_uint32),
+                ("vocab", C.c_uint32), ("max_seq", C.c_uint32), ("group_size", C.c_uint32),
+                ("quant", C.c_uint32), ("norm_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class qzo_buf(C.Structure):
+    _fields_ = [("ptr_dev", C.c_void_p), ("bytes", C.c_uint64)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -c 'import __graft_entry__ as g; g.build()'`")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.qzo_last_error.restype = C.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _check(status):
+    if status != QZO_OK:
+        raise QzoError(status, lib().qzo_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def make_config(shape: dict) -> qzo_model_config:
+    return qzo_model_config(C.sizeof(qzo_model_config), 0 if shape["arch"] == "llama" else 1,
+                            shape["n_layers"], shape["d_model"], shape["n_heads"], shape["d_ffn"],
+                            shape["vocab"], shape["max_seq"], shape.get("group", 128), 0,
+                            shape.get("norm_eps", 1e-5), shape.get("rope_theta", 10000.0))
+
+
+def qzo_model_scale_count(shape: dict) -> int:
+    cfg = make_config(shape)
+    out = C.c_uint64(0)
+    _check(lib().qzo_model_scale_count(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def qzo_model_create(shape: dict, tensors, scale_arena):
+    cfg = make_config(shape)
+    bufs = (qzo_buf * len(tensors))(*[qzo_buf(t.data_ptr(), t.numel() * t.element_size())
+                                      for t in tensors])
+    handle = C.c_void_p(0)
+    _check(lib().qzo_model_create(C.byref(cfg), bufs, C.c_uint32(len(tensors)), _ptr(scale_arena),
+                                  C.c_uint64(scale_arena.numel()), C.byref(handle)))
+    return handle
+
+
+def qzo_model_destroy(model):
+    _check(lib().qzo_model_destroy(model))
+
+
+def qzo_workspace_bytes(model, batch, seq) -> int:
+    out = C.c_uint64(0)
+    _check(lib().qzo_workspace_bytes(model, C.c_uint32(batch), C.c_uint32(seq), C.byref(out)))
+    return out.value
+
+
+def qzo_forward_loss(model, tokens, seed, eps, sign, workspace, loss_out, stream=None):
+    B, S = tokens.shape
+    _check(lib().qzo_forward_loss(model, _ptr(tokens), C.c_uint32(B), C.c_uint32(S),
+                                  C.c_uint64(seed), C.c_float(eps), C.c_int(sign), _ptr(workspace),
+                                  C.c_uint64(workspace.numel() * workspace.element_size()),
+                                  _ptr(loss_out), _stream(stream)))
+
+
+def qzo_step(model, tokens, seed, eps, eta, clip, workspace, result, stream=None):
+    """result: 8 x 4-byte device tensor receiving qzo_step_result."""
+    B, S = tokens.shape
+    _check(lib().qzo_step(model, _ptr(tokens), C.c_uint32(B), C.c_uint32(S), C.c_uint64(seed),
+                          C.c_float(eps), C.c_float(eta), C.c_float(clip), _ptr(workspace),
+                          C.c_uint64(workspace.numel() * workspace.element_size()), _ptr(result),
+                          _stream(stream)))
+
+
+def read_step_result(result) -> dict:
+    """Host copy of a qzo_step_result (synchronises)."""
+    raw = result.cpu()
+    f = raw.view(torch.float32)
+    i = raw.view(torch.int32)
+    return dict(loss_plus=float(f[0]), loss_minus=float(f[1]), d=float(f[2]),
+                d_clipped=float(f[3]), status=int(i[4]))
+
+
+def qzo_model_apply_update(model, seed, eta, d_clipped, stream=None):
+    _check(lib().qzo_model_apply_update(model, C.c_uint64(seed), C.c_float(eta),
+                                        C.c_float(d_clipped), _stream(stream)))
+
+
+def qzo_dequant_gemm(x, q, s, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None):
+    M, K = x.shape
+    N = q.shape[0]
+    _check(lib().qzo_dequant_gemm(_ptr(x), _ptr(q), _ptr(s), C.c_uint32(row_base), C.c_uint32(M),
+                                  C.c_uint32(N), C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
+                                  C.c_float(eps), C.c_int(sign), _ptr(y), _ptr(sumsq),
+                                  _stream(stream)))
+
+
+def qzo_apply_update(s, row_base, seed, eta, d_clipped, stream=None):
+    n_rows, G = s.shape
+    _check(lib().qzo_apply_update(_ptr(s), C.c_uint32(n_rows), C.c_uint32(G), C.c_uint32(row_base),
+                                  C.c_uint64(seed), C.c_float(eta), C.c_float(d_clipped),
+                                  _stream(stream)))
+
+
+def qzo_rtn_quantize(w, q, s, group=128, stream=None):
+    N, K = w.shape
+    _check(lib().qzo_rtn_quantize(_ptr(w), C.c_uint32(N), C.c_uint32(K), C.c_uint32(group), _ptr(q),
+                                  _ptr(s), _stream(stream)))
+
+
+def qzo_debug_normals(seed, stream_id, row0, out, stream=None):
+    n_rows, G = out.shape
+    _check(lib().qzo_debug_normals(C.c_uint64(seed), C.c_uint32(stream_id), C.c_uint32(row0),
+                                   C.c_uint32(n_rows), C.c_uint32(G), _ptr(out), _stream(stream)))
+
+
+def qzo_debug_philox(seed, ctr, out, stream=None):
+    _check(lib().qzo_debug_philox(C.c_uint64(seed), _ptr(ctr), C.c_uint32(ctr.shape[0]), _ptr(out),
+                                  _stream(stream)))
+
+
+def qzo_debug_normal_pairs(words, out, stream=None):
+    _check(lib().qzo_debug_normal_pairs(_ptr(words), C.c_uint32(words.numel()), _ptr(out),
+                                        _stream(stream)))
+
+
+def qzo_debug_dequant(q, s, row_base, seed, eps, sign, w_eff, group=128, stream=None):
+    N, K = w_eff.shape
+    _check(lib().qzo_debug_dequant(_ptr(q), _ptr(s), C.c_uint32(row_base), C.c_uint32(N),
+                                   C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
+                                   C.c_float(eps), C.c_int(sign), _ptr(w_eff), _stream(stream)))
+
+
+def qzo_debug_forward(model, tokens, seed, eps, sign, workspace, loss_out, hidden_out, stream=None):
+    B, S = tokens.shape
+    _check(lib().qzo_debug_forward(model, _ptr(tokens), C.c_uint32(B), C.c_uint32(S),
+                                   C.c_uint64(seed), C.c_float(eps), C.c_int(sign), _ptr(workspace),
+                                   C.c_uint64(workspace.numel() * workspace.element_size()),
+                                   _ptr(loss_out), _ptr(hidden_out), _stream(stream)))

@@ -1,0 +1,480 @@
+// C ABI of the QZO hot path (include/qzo.h): argument checking, the decoder
+// forward as a sequence of kernel launches on the caller's stream, and the
+// step of Algorithm 1 (two perturbed forwards, SPSA scalar + clipping, update).
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+#include "../../include/qzo.h"
+#include "qzo_kernels.hpp"
+
+using namespace qzo;
+
+namespace {
+
+thread_local std::string g_err;
+
+qzo_status fail(qzo_status st, const std::string& msg) {
+  g_err = msg;
+  return st;
+}
+qzo_status hip_fail(hipError_t e, const char* what) {
+  return fail(QZO_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define QZO_HIP(call)                                         \
+  do {                                                        \
+    hipError_t e_ = (call);                                   \
+    if (e_ != hipSuccess) return hip_fail(e_, #call);         \
+  } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+uint64_t up256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
+
+struct Linear {           // one quantized linear of a layer
+  uint32_t N, K;
+  uint64_t s_off;         // first scale within the layer's arena slice
+  uint32_t row_base;      // first noise row within the layer
+};
+
+struct Workspace {
+  unsigned char *h, *a, *qkv, *att, *ff, *act;
+  float *ce_part, *tgt, *rowloss, *losses;
+  uint64_t total;
+};
+
+}  // namespace
+
+struct qzo_model {
+  qzo_model_config cfg;
+  std::vector<qzo_buf> T;
+  void* arena;
+  uint64_t n_scales;
+  Linear lin[4];
+  uint64_t scales_per_layer;
+  uint32_t rows_per_layer;
+  UpdPlan plan;
+  float* rope_table;      // device, Llama only
+  uint32_t tensors_per_layer, first_layer_tensor;
+};
+
+namespace {
+
+qzo_status check_cfg(const qzo_model_config* c) {
+  if (!c) return fail(QZO_ERR_ARG, "config is null");
+  if (c->struct_size != sizeof(qzo_model_config))
+    return fail(QZO_ERR_ARG, "config.struct_size does not match this library");
+  if (c->arch > 1) return fail(QZO_ERR_ARG, "config.arch must be 0 (Llama) or 1 (OPT)");
+  if (c->quant != 0) return fail(QZO_ERR_UNSUPPORTED, "only quant = 0 (int4 group scales) is built");
+  if (c->group_size != 128) return fail(QZO_ERR_SHAPE, "group_size must be 128");
+  if (!c->n_layers || !c->d_model || !c->n_heads || !c->d_ffn || !c->vocab || !c->max_seq)
+    return fail(QZO_ERR_SHAPE, "zero dimension in config");
+  if (c->d_model % 128 || c->d_ffn % 128)
+    return fail(QZO_ERR_SHAPE, "d_model and d_ffn must be multiples of 128");
+  if (c->d_model % c->n_heads) return fail(QZO_ERR_SHAPE, "d_model not divisible by n_heads");
+  uint32_t dh = c->d_model / c->n_heads;
+  if (dh != 64 && dh != 128) return fail(QZO_ERR_SHAPE, "head size must be 64 or 128");
+  return QZO_OK;
+}
+
+void layer_linears(const qzo_model_config& c, Linear lin[4]) {
+  const uint32_t d = c.d_model, F = c.d_ffn;
+  const uint32_t N[4] = {3 * d, d, c.arch == 0 ? 2 * F : F, d};
+  const uint32_t K[4] = {d, d, d, F};
+  uint64_t off = 0;
+  uint32_t row = 0;
+  for (int i = 0; i < 4; ++i) {
+    lin[i] = {N[i], K[i], off, row};
+    off += (uint64_t)N[i] * (K[i] / 128);
+    row += N[i];
+  }
+}
+
+// Merge a layer's consecutive linears with equal groups-per-row into update segments.
+qzo_status build_plan(const Linear* lin, int n_lin, uint32_t n_layers, UpdPlan& p) {
+  std::memset(&p, 0, sizeof(p));
+  uint32_t wg = 0;
+  for (int i = 0; i < n_lin; ++i) {
+    const uint32_t G = lin[i].K / 128;
+    if (p.n_seg && p.seg[p.n_seg - 1].G == G) {
+      p.seg[p.n_seg - 1].rows += lin[i].N;
+    } else {
+      if (lin[i].s_off > 0xffffffffull) return fail(QZO_ERR_SHAPE, "layer has too many scales");
+      p.seg[p.n_seg++] = {(uint32_t)lin[i].s_off, lin[i].N, G, lin[i].row_base, 0};
+    }
+    p.layer_stride = lin[i].s_off + (uint64_t)lin[i].N * G;
+    p.rows_per_layer = lin[i].row_base + lin[i].N;
+  }
+  for (uint32_t i = 0; i < p.n_seg; ++i) {
+    const uint64_t units = (uint64_t)p.seg[i].rows * ((p.seg[i].G + 7) / 8);
+    if (units >= (1u << 24)) return fail(QZO_ERR_SHAPE, "update segment exceeds 2^24 counters");
+    p.seg[i].first_wg = wg;
+    wg += (uint32_t)((units + 255) / 256);
+  }
+  p.wgs_per_layer = wg;
+  p.n_layers = n_layers;
+  return QZO_OK;
+}
+
+Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
+  const qzo_model_config& c = m->cfg;
+  const uint64_t M = (uint64_t)batch * seq, d = c.d_model, F = c.d_ffn;
+  const uint64_t n_slices = ((c.vocab + 255) / 256) * 4;
+  Workspace w;
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) {
+    unsigned char* p = base ? (unsigned char*)base + off : nullptr;
+    off += up256(bytes);
+    return p;
+  };
+  w.h = take(M * d * 2);
+  w.a = take(M * d * 2);
+  w.qkv = take(M * 3 * d * 2);
+  w.att = take(M * d * 2);
+  w.ff = take(M * (c.arch == 0 ? 2 * F : F) * 2);
+  w.act = take(c.arch == 0 ? M * F * 2 : 0);
+  w.ce_part = (float*)take(M * n_slices * 8);
+  w.tgt = (float*)take(M * 4);
+  w.rowloss = (float*)take(M * 4);
+  w.losses = (float*)take(256);
+  w.total = off;
+  return w;
+}
+
+qzo_status check_batch(const qzo_model* m, const void* tok, uint32_t batch, uint32_t seq,
+                       const void* ws, uint64_t ws_bytes) {
+  if (!m) return fail(QZO_ERR_ARG, "model is null");
+  if (!tok || !ws) return fail(QZO_ERR_ARG, "tokens or workspace is null");
+  if (!aligned16(tok) || !aligned16(ws)) return fail(QZO_ERR_ALIGN, "tokens/workspace not 16-byte aligned");
+  if (batch == 0 || seq < 2) return fail(QZO_ERR_SHAPE, "need batch >= 1 and seq >= 2");
+  if (seq > m->cfg.max_seq) return fail(QZO_ERR_SHAPE, "seq exceeds max_seq");
+  if ((uint64_t)batch * seq > 0x7fffffffull) return fail(QZO_ERR_SHAPE, "batch*seq too large");
+  Workspace w = carve(m, batch, seq, nullptr);
+  if (ws_bytes < w.total) return fail(QZO_ERR_WORKSPACE, "workspace smaller than qzo_workspace_bytes");
+  return QZO_OK;
+}
+
+// The decoder forward with every quantized linear perturbed by sign*eps*z.
+qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t seq, uint64_t seed,
+                   float eps_signed, const Workspace& w, float* loss_out, hipStream_t st,
+                   void* hidden_out = nullptr) {
+  const qzo_model_config& c = m->cfg;
+  const uint32_t M = batch * seq, d = c.d_model, F = c.d_ffn, H = c.n_heads, dh = d / H;
+  const bool llama = c.arch == 0;
+  const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
+  const unsigned char* arena = (const unsigned char*)m->arena;
+
+  QZO_HIP(launch_embed(tok, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
+  for (uint32_t l = 0; l < c.n_layers; ++l) {
+    const qzo_buf* T = &m->T[m->first_layer_tensor + (size_t)l * m->tensors_per_layer];
+    const uint64_t layer_off = (uint64_t)l * m->scales_per_layer;
+    auto gemm = [&](int li, const void* x, const void* wq, const void* bias, const void* resid,
+                    void* y, uint32_t epi) {
+      GemmArgs g = {};
+      g.x = x; g.w = wq; g.s = arena + (layer_off + m->lin[li].s_off) * 2;
+      g.bias = bias; g.resid = resid; g.y = y;
+      g.M = M; g.N = m->lin[li].N; g.K = m->lin[li].K;
+      g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
+      g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
+      return launch_w4a16_gemm(g, st);
+    };
+    if (llama) {
+      // attn_norm, wqkv, wo, ffn_norm, wgu, wdown
+      QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
+      QZO_HIP(gemm(0, w.a, T[1].ptr_dev, nullptr, nullptr, w.qkv, 0));
+      QZO_HIP(launch_rope(w.qkv, m->rope_table, batch, seq, d, H, st));
+      QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
+      QZO_HIP(gemm(1, w.att, T[2].ptr_dev, nullptr, w.h, w.h, EPI_RESIDUAL));
+      QZO_HIP(launch_rmsnorm(w.h, T[3].ptr_dev, M, d, c.norm_eps, w.a, st));
+      QZO_HIP(gemm(2, w.a, T[4].ptr_dev, nullptr, nullptr, w.ff, 0));
+      QZO_HIP(launch_swiglu(w.ff, M, F, w.act, st));
+      QZO_HIP(gemm(3, w.act, T[5].ptr_dev, nullptr, w.h, w.h, EPI_RESIDUAL));
+    } else {
+      // ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, wfc1, bfc1, wfc2, bfc2
+      QZO_HIP(launch_layernorm(w.h, T[0].ptr_dev, T[1].ptr_dev, M, d, c.norm_eps, w.a, st));
+      QZO_HIP(gemm(0, w.a, T[2].ptr_dev, T[3].ptr_dev, nullptr, w.qkv, EPI_BIAS));
+      QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
+      QZO_HIP(gemm(1, w.att, T[4].ptr_dev, T[5].ptr_dev, w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
+      QZO_HIP(launch_layernorm(w.h, T[6].ptr_dev, T[7].ptr_dev, M, d, c.norm_eps, w.a, st));
+      QZO_HIP(gemm(2, w.a, T[8].ptr_dev, T[9].ptr_dev, nullptr, w.ff, EPI_BIAS | EPI_RELU));
+      QZO_HIP(gemm(3, w.ff, T[10].ptr_dev, T[11].ptr_dev, w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
+    }
+  }
+  const size_t tail = m->first_layer_tensor + (size_t)c.n_layers * m->tensors_per_layer;
+  const void* lm_head;
+  if (llama) {
+    QZO_HIP(launch_rmsnorm(w.h, m->T[tail].ptr_dev, M, d, c.norm_eps, w.a, st));
+    lm_head = m->T[tail + 1].ptr_dev;
+  } else {
+    QZO_HIP(launch_layernorm(w.h, m->T[tail].ptr_dev, m->T[tail + 1].ptr_dev, M, d, c.norm_eps, w.a, st));
+    lm_head = m->T[tail + 2].ptr_dev;
+  }
+  if (hidden_out)
+    QZO_HIP(hipMemcpyAsync(hidden_out, w.a, (size_t)M * d * 2, hipMemcpyDeviceToDevice, st));
+  CeArgs ce = {};
+  ce.x = w.a; ce.w = lm_head; ce.tok = tok; ce.part = w.ce_part; ce.tgt = w.tgt;
+  ce.M = M; ce.V = c.vocab; ce.K = d; ce.S = seq; ce.n_slices = ((c.vocab + 255) / 256) * 4;
+  QZO_HIP(launch_lmhead_ce(ce, st));
+  QZO_HIP(launch_ce_reduce(w.ce_part, w.tgt, M, seq, ce.n_slices, w.rowloss, loss_out, st));
+  return QZO_OK;
+}
+
+float* g_partials = nullptr;     // library-owned scratch of qzo_dequant_gemm's sum of squares
+uint32_t g_partials_n = 0;
+
+}  // namespace
+
+extern "C" {
+
+const char* qzo_last_error(void) { return g_err.c_str(); }
+
+qzo_status qzo_model_scale_count(const qzo_model_config* cfg, uint64_t* out) {
+  qzo_status st = check_cfg(cfg);
+  if (st != QZO_OK) return st;
+  if (!out) return fail(QZO_ERR_ARG, "out is null");
+  Linear lin[4];
+  layer_linears(*cfg, lin);
+  *out = (lin[3].s_off + (uint64_t)lin[3].N * (lin[3].K / 128)) * cfg->n_layers;
+  return QZO_OK;
+}
+
+qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors, uint32_t n_tensors,
+                            void* scale_arena_dev, uint64_t n_scales, qzo_model** out) {
+  qzo_status st = check_cfg(cfg);
+  if (st != QZO_OK) return st;
+  if (!tensors || !scale_arena_dev || !out) return fail(QZO_ERR_ARG, "null argument");
+  if (!aligned16(scale_arena_dev)) return fail(QZO_ERR_ALIGN, "scale arena not 16-byte aligned");
+  const bool llama = cfg->arch == 0;
+  const uint32_t per_layer = llama ? 6 : 12, head = llama ? 1 : 2, tail = llama ? 2 : 3;
+  if (n_tensors != head + per_layer * cfg->n_layers + tail)
+    return fail(QZO_ERR_ARG, "tensor count does not match the architecture's table");
+  uint64_t want = 0;
+  qzo_model_scale_count(cfg, &want);
+  if (n_scales != want) return fail(QZO_ERR_SHAPE, "n_scales does not match the config");
+  if ((uint64_t)cfg->n_layers * (4 * (uint64_t)cfg->d_model + (llama ? 2 : 1) * (uint64_t)cfg->d_ffn) >
+      0xffffffffull)
+    return fail(QZO_ERR_SHAPE, "too many quantized rows");
+
+  const uint64_t d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab;
+  std::vector<uint64_t> need;
+  need.push_back(V * d * 2);
+  if (!llama) need.push_back((uint64_t)cfg->max_seq * d * 2);
+  for (uint32_t l = 0; l < cfg->n_layers; ++l) {
+    if (llama) {
+      const uint64_t b[6] = {d * 2, 3 * d * d / 2, d * d / 2, d * 2, 2 * F * d / 2, d * F / 2};
+      need.insert(need.end(), b, b + 6);
+    } else {
+      const uint64_t b[12] = {d * 2, d * 2, 3 * d * d / 2, 3 * d * 2, d * d / 2, d * 2,
+                              d * 2, d * 2, F * d / 2,     F * 2,     d * F / 2, d * 2};
+      need.insert(need.end(), b, b + 12);
+    }
+  }
+  need.push_back(d * 2);
+  if (!llama) need.push_back(d * 2);
+  need.push_back(V * d * 2);
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    if (!tensors[i].ptr_dev) return fail(QZO_ERR_ARG, "tensor " + std::to_string(i) + " is null");
+    if (!aligned16(tensors[i].ptr_dev))
+      return fail(QZO_ERR_ALIGN, "tensor " + std::to_string(i) + " not 16-byte aligned");
+    if (tensors[i].bytes != need[i])
+      return fail(QZO_ERR_SHAPE, "tensor " + std::to_string(i) + " has " +
+                                     std::to_string(tensors[i].bytes) + " bytes, expected " +
+                                     std::to_string(need[i]));
+  }
+
+  qzo_model* m = new qzo_model();
+  m->cfg = *cfg;
+  m->T.assign(tensors, tensors + n_tensors);
+  m->arena = scale_arena_dev;
+  m->n_scales = n_scales;
+  layer_linears(*cfg, m->lin);
+  m->scales_per_layer = m->lin[3].s_off + (uint64_t)m->lin[3].N * (m->lin[3].K / 128);
+  m->rows_per_layer = m->lin[3].row_base + m->lin[3].N;
+  m->tensors_per_layer = per_layer;
+  m->first_layer_tensor = head;
+  m->rope_table = nullptr;
+  st = build_plan(m->lin, 4, cfg->n_layers, m->plan);
+  if (st != QZO_OK) { delete m; return st; }
+  if (llama) {
+    const uint32_t dh = cfg->d_model / cfg->n_heads;
+    hipError_t e = hipMalloc((void**)&m->rope_table, (size_t)cfg->max_seq * (dh / 2) * 8);
+    if (e == hipSuccess) e = launch_rope_table(m->rope_table, cfg->max_seq, dh, cfg->rope_theta, nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) {
+      if (m->rope_table) (void)hipFree(m->rope_table);
+      delete m;
+      return hip_fail(e, "RoPE table");
+    }
+  }
+  *out = m;
+  return QZO_OK;
+}
+
+qzo_status qzo_model_destroy(qzo_model* m) {
+  if (!m) return QZO_OK;
+  if (m->rope_table) (void)hipFree(m->rope_table);
+  delete m;
+  return QZO_OK;
+}
+
+qzo_status qzo_workspace_bytes(const qzo_model* m, uint32_t batch, uint32_t seq, uint64_t* out) {
+  if (!m || !out) return fail(QZO_ERR_ARG, "null argument");
+  if (batch == 0 || seq < 2 || seq > m->cfg.max_seq) return fail(QZO_ERR_SHAPE, "bad batch/seq");
+  *out = carve(m, batch, seq, nullptr).total;
+  return QZO_OK;
+}
+
+qzo_status qzo_forward_loss(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                            uint64_t seed, float eps, int sign, void* workspace_dev,
+                            uint64_t workspace_bytes, float* loss_dev, void* stream) {
+  qzo_status st = check_batch(m, tokens_dev, batch, seq, workspace_dev, workspace_bytes);
+  if (st != QZO_OK) return st;
+  if (!loss_dev) return fail(QZO_ERR_ARG, "loss_dev is null");
+  if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
+  if (!std::isfinite(eps)) return fail(QZO_ERR_ARG, "eps not finite");
+  Workspace w = carve(m, batch, seq, workspace_dev);
+  return forward(m, tokens_dev, batch, seq, seed, sign > 0 ? eps : -eps, w, loss_dev,
+                 (hipStream_t)stream);
+}
+
+qzo_status qzo_debug_forward(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                             uint64_t seed, float eps, int sign, void* workspace_dev,
+                             uint64_t workspace_bytes, float* loss_dev, void* hidden_dev,
+                             void* stream) {
+  qzo_status st = check_batch(m, tokens_dev, batch, seq, workspace_dev, workspace_bytes);
+  if (st != QZO_OK) return st;
+  if (!loss_dev || !hidden_dev) return fail(QZO_ERR_ARG, "null output");
+  if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
+  Workspace w = carve(m, batch, seq, workspace_dev);
+  return forward(m, tokens_dev, batch, seq, seed, sign > 0 ? eps : -eps, w, loss_dev,
+                 (hipStream_t)stream, hidden_dev);
+}
+
+qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                    uint64_t seed, float eps, float eta, float clip, void* workspace_dev,
+                    uint64_t workspace_bytes, qzo_step_result* result_dev, void* stream) {
+  qzo_status st = check_batch(m, tokens_dev, batch, seq, workspace_dev, workspace_bytes);
+  if (st != QZO_OK) return st;
+  if (!result_dev) return fail(QZO_ERR_ARG, "result_dev is null");
+  if (!(clip >= 0.0f)) return fail(QZO_ERR_ARG, "clip must be >= 0");
+  if (!std::isfinite(eps) || !std::isfinite(eta)) return fail(QZO_ERR_ARG, "eps/eta not finite");
+  hipStream_t s = (hipStream_t)stream;
+  Workspace w = carve(m, batch, seq, workspace_dev);
+  st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s);
+  if (st != QZO_OK) return st;
+  st = forward(m, tokens_dev, batch, seq, seed, -eps, w, w.losses + 1, s);
+  if (st != QZO_OK) return st;
+  QZO_HIP(launch_spsa_clip(w.losses, eps, clip, result_dev, s));
+  QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta, 0.0f,
+                              result_dev, s));
+  return QZO_OK;
+}
+
+qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float d_clipped,
+                                  void* stream) {
+  if (!m) return fail(QZO_ERR_ARG, "model is null");
+  if (!std::isfinite(eta) || !std::isfinite(d_clipped)) return fail(QZO_ERR_ARG, "eta/d' not finite");
+  QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta,
+                              d_clipped, nullptr, (hipStream_t)stream));
+  return QZO_OK;
+}
+
+qzo_status qzo_apply_update(void* s_dev, uint32_t n_rows, uint32_t G, uint32_t row_base,
+                            uint64_t seed, float eta, float d_clipped, void* stream) {
+  if (!s_dev) return fail(QZO_ERR_ARG, "s_dev is null");
+  if (!aligned16(s_dev)) return fail(QZO_ERR_ALIGN, "s_dev not 16-byte aligned");
+  if (!std::isfinite(eta) || !std::isfinite(d_clipped)) return fail(QZO_ERR_ARG, "eta/d' not finite");
+  if (n_rows == 0 || G == 0) return QZO_OK;
+  Linear lin = {n_rows, G * 128, 0, row_base};
+  UpdPlan plan;
+  qzo_status st = build_plan(&lin, 1, 1, plan);
+  if (st != QZO_OK) return st;
+  QZO_HIP(launch_scale_update(s_dev, plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta, d_clipped,
+                              nullptr, (hipStream_t)stream));
+  return QZO_OK;
+}
+
+qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
+                            uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint32_t group,
+                            uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
+                            void* stream) {
+  if (!x_dev || !q_dev || !s_dev || !y_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(x_dev) || !aligned16(q_dev) || !aligned16(s_dev) || !aligned16(y_dev))
+    return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
+  if (group != 128) return fail(QZO_ERR_SHAPE, "group must be 128");
+  if (K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "K must be a positive multiple of 128");
+  if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
+  if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
+  if (!std::isfinite(eps)) return fail(QZO_ERR_ARG, "eps not finite");
+  hipStream_t st = (hipStream_t)stream;
+  if (M == 0 || N == 0) {
+    if (sumsq_dev) QZO_HIP(launch_sum_partials(nullptr, 0, sumsq_dev, st));
+    return QZO_OK;
+  }
+  GemmArgs g = {};
+  g.x = x_dev; g.w = q_dev; g.s = s_dev; g.y = y_dev;
+  g.M = M; g.N = N; g.K = K; g.row_base = row_base;
+  g.seed_lo = (uint32_t)seed; g.seed_hi = (uint32_t)(seed >> 32);
+  g.eps_signed = sign > 0 ? eps : -eps;
+  const uint32_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  if (sumsq_dev) {
+    if (g_partials_n < tiles) {
+      if (g_partials) (void)hipFree(g_partials);
+      g_partials = nullptr;
+      g_partials_n = 0;
+      QZO_HIP(hipMalloc((void**)&g_partials, (size_t)tiles * sizeof(float)));
+      g_partials_n = tiles;
+    }
+    g.epi = EPI_SUMSQ;
+    g.partials = g_partials;
+  }
+  QZO_HIP(launch_w4a16_gemm(g, st));
+  if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  return QZO_OK;
+}
+
+qzo_status qzo_rtn_quantize(const float* w_dev, uint32_t N, uint32_t K, uint32_t group, void* q_dev,
+                            void* s_dev, void* stream) {
+  if (!w_dev || !q_dev || !s_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(w_dev) || !aligned16(q_dev) || !aligned16(s_dev))
+    return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
+  if (group != 128 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
+  QZO_HIP(launch_rtn_quantize(w_dev, N, K, q_dev, s_dev, (hipStream_t)stream));
+  return QZO_OK;
+}
+
+qzo_status qzo_debug_normals(uint64_t seed, uint32_t stream_id, uint32_t row0, uint32_t n_rows,
+                             uint32_t G, float* out_dev, void* stream) {
+  if (!out_dev) return fail(QZO_ERR_ARG, "out_dev is null");
+  QZO_HIP(launch_debug_normals((uint32_t)seed, (uint32_t)(seed >> 32), stream_id, row0, n_rows, G,
+                               out_dev, (hipStream_t)stream));
+  return QZO_OK;
+}
+qzo_status qzo_debug_philox(uint64_t seed, const uint32_t* ctr_dev, uint32_t n, uint32_t* out_dev,
+                            void* stream) {
+  if (!ctr_dev || !out_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  QZO_HIP(launch_debug_philox((uint32_t)seed, (uint32_t)(seed >> 32), ctr_dev, n, out_dev,
+                              (hipStream_t)stream));
+  return QZO_OK;
+}
+qzo_status qzo_debug_normal_pairs(const uint32_t* words_dev, uint32_t n, float* out_dev,
+                                  void* stream) {
+  if (!words_dev || !out_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  QZO_HIP(launch_debug_normal_pairs(words_dev, n, out_dev, (hipStream_t)stream));
+  return QZO_OK;
+}
+qzo_status qzo_debug_dequant(const void* q_dev, const void* s_dev, uint32_t row_base, uint32_t N,
+                             uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                             void* w_eff_dev, void* stream) {
+  if (!q_dev || !s_dev || !w_eff_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(q_dev) || !aligned16(s_dev) || !aligned16(w_eff_dev))
+    return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
+  if (group != 128 || K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
+  if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
+  QZO_HIP(launch_debug_dequant(q_dev, s_dev, row_base, N, K, (uint32_t)seed, (uint32_t)(seed >> 32),
+                               sign > 0 ? eps : -eps, w_eff_dev, (hipStream_t)stream));
+  return QZO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,472 @@
+// Bandwidth-bound and scalar kernels of the QZO step for gfx950: the scale
+// update of Algorithm 1, the SPSA scalar with directional-derivative clipping
+// (Eq. 6), the RTN quantizer (Eq. 3), embedding, norms, RoPE, SwiGLU, the
+// cross-entropy reduction, and the inspection kernels of the parity tests.
+#include "qzo_device.hpp"
+#include "qzo_kernels.hpp"
+
+namespace qzo {
+
+// ------------------------------------------------------------ update ------
+// Delta_i <- max(Delta_i - eta*d'*z_i, 0) (Algorithm 1).  One thread owns the
+// eight scales that share a Philox counter: (row, 8*gb .. 8*gb+7).  The arena
+// is read and written once (4 B per scale); z costs no memory traffic.
+__global__ __launch_bounds__(256) void scale_update_kernel(bf16_t* __restrict__ arena, UpdPlan plan,
+                                                           uint32_t seed_lo, uint32_t seed_hi,
+                                                           float eta, float dclip_host,
+                                                           const qzo_step_result* __restrict__ res) {
+  float c;
+  if (res) {
+    if (res->status != 0) return;          // non-finite d: leave the scales alone
+    c = eta * res->d_clipped;
+  } else {
+    c = eta * dclip_host;
+  }
+  const uint32_t wg = blockIdx.x, layer = blockIdx.y;
+  UpdSeg sg = plan.seg[0];
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if ((uint32_t)i < plan.n_seg && wg >= plan.seg[i].first_wg) sg = plan.seg[i];
+  const uint32_t Gb = (sg.G + 7u) >> 3;
+  const uint32_t u = (wg - sg.first_wg) * 256u + threadIdx.x;
+  if (u >= sg.rows * Gb) return;
+  // row = u / Gb, gb = u % Gb for u < 2^24 (checked on the host)
+  uint32_t row = (uint32_t)((float)u * __builtin_amdgcn_rcpf((float)Gb));
+  int32_t gb = (int32_t)(u - __umul24(row, Gb));
+  if (gb < 0) { row -= 1; gb += (int32_t)Gb; }
+  else if (gb >= (int32_t)Gb) { row += 1; gb -= (int32_t)Gb; }
+
+  float z[8];
+  scale_normals8(seed_lo, seed_hi, 0u, layer * plan.rows_per_layer + sg.row_base + row,
+                 (uint32_t)gb, z);
+  bf16_t* p = arena + (uint64_t)layer * plan.layer_stride + sg.off + (uint64_t)row * sg.G +
+              (uint32_t)gb * 8u;
+  const float nc = -c;
+  if ((sg.G & 7u) == 0u) {
+    uint4 v = *reinterpret_cast<const uint4*>(p);
+    uint32_t in[4] = {v.x, v.y, v.z, v.w}, out[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float a = __uint_as_float(in[j] << 16), b = __uint_as_float(in[j] & 0xffff0000u);
+      a = fmaxf(__builtin_fmaf(nc, z[2 * j], a), 0.0f);
+      b = fmaxf(__builtin_fmaf(nc, z[2 * j + 1], b), 0.0f);
+      out[j] = pack_bf16x2(a, b);
+    }
+    *reinterpret_cast<uint4*>(p) = make_uint4(out[0], out[1], out[2], out[3]);
+  } else {
+    const uint32_t nv = min(8u, sg.G - (uint32_t)gb * 8u);
+    if ((sg.G & 1u) == 0u) {      // rows start 4-byte aligned: dword accesses
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (2u * j < nv) {
+          uint32_t w = reinterpret_cast<const uint32_t*>(p)[j];
+          float a = __uint_as_float(w << 16), b = __uint_as_float(w & 0xffff0000u);
+          a = fmaxf(__builtin_fmaf(nc, z[2 * j], a), 0.0f);
+          b = fmaxf(__builtin_fmaf(nc, z[2 * j + 1], b), 0.0f);
+          reinterpret_cast<uint32_t*>(p)[j] = pack_bf16x2(a, b);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if ((uint32_t)j < nv) {
+          float a = fmaxf(__builtin_fmaf(nc, z[j], bf16_to_f32(p[j])), 0.0f);
+          p[j] = (bf16_t)(pack_bf16x2(a, 0.0f) & 0xffffu);
+        }
+      }
+    }
+  }
+}
+
+hipError_t launch_scale_update(void* arena, const UpdPlan& plan, uint32_t seed_lo,
+                               uint32_t seed_hi, float eta, float d_clipped,
+                               const qzo_step_result* res, hipStream_t st) {
+  dim3 grid(plan.wgs_per_layer, plan.n_layers);
+  if (grid.x == 0 || grid.y == 0) return hipSuccess;
+  scale_update_kernel<<<grid, 256, 0, st>>>((bf16_t*)arena, plan, seed_lo, seed_hi, eta, d_clipped,
+                                            res);
+  return hipGetLastError();
+}
+
+// ------------------------------------------- SPSA scalar + DDC (Eq. 6) ----
+__global__ void spsa_clip_kernel(const float* __restrict__ losses, float eps, float clip,
+                                 qzo_step_result* __restrict__ res) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  float lp = losses[0], lm = losses[1];
+  float d = (lp - lm) / (2.0f * eps);
+  res->loss_plus = lp;
+  res->loss_minus = lm;
+  res->d = d;
+  if (!isfinite(d)) {
+    res->d_clipped = 0.0f;
+    res->status = QZO_ERR_NONFINITE;
+  } else {
+    float dc = d > clip ? clip : (d < -clip ? -clip : d);
+    res->d_clipped = dc;
+    res->status = QZO_OK;
+  }
+  res->reserved[0] = res->reserved[1] = res->reserved[2] = 0u;
+}
+hipError_t launch_spsa_clip(const float* losses, float eps, float clip, qzo_step_result* res,
+                            hipStream_t st) {
+  spsa_clip_kernel<<<1, 64, 0, st>>>(losses, eps, clip, res);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------ RTN (Eq. 3) -------
+// One wavefront per group of 128 weights: absmax, Delta = bf16(absmax/7),
+// wbar = clamp(rne(w/Delta), -8, 7), nibble = wbar + 8.
+__global__ __launch_bounds__(256) void rtn_quantize_kernel(const float* __restrict__ w, uint32_t N,
+                                                           uint32_t K, uint8_t* __restrict__ q,
+                                                           bf16_t* __restrict__ s) {
+  const uint32_t G = K >> 7;
+  const uint64_t grp = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (grp >= (uint64_t)N * G) return;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint64_t n = grp / G;
+  const uint32_t g = (uint32_t)(grp - n * G);
+  const float2 v = *reinterpret_cast<const float2*>(w + n * K + (uint64_t)g * 128 + lane * 2);
+  float amax = wave_max(fmaxf(fabsf(v.x), fabsf(v.y)));
+  float sc = bf16_to_f32(f32_to_bf16(amax / 7.0f));
+  int q0 = 0, q1 = 0;
+  if (sc > 0.0f) {
+    q0 = (int)fminf(7.0f, fmaxf(-8.0f, rintf(v.x / sc)));
+    q1 = (int)fminf(7.0f, fmaxf(-8.0f, rintf(v.y / sc)));
+  }
+  q[n * (K >> 1) + (uint64_t)g * 64 + lane] = (uint8_t)((q0 + 8) | ((q1 + 8) << 4));
+  if (lane == 0) s[grp] = f32_to_bf16(sc);
+}
+hipError_t launch_rtn_quantize(const float* w, uint32_t N, uint32_t K, void* q, void* s,
+                               hipStream_t st) {
+  uint64_t groups = (uint64_t)N * (K >> 7);
+  if (groups == 0) return hipSuccess;
+  rtn_quantize_kernel<<<(uint32_t)((groups + 3) / 4), 256, 0, st>>>(w, N, K, (uint8_t*)q,
+                                                                    (bf16_t*)s);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------- inspection -------
+__global__ void debug_normals_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
+                                     uint32_t row0, uint32_t n_rows, uint32_t G, float* out) {
+  const uint32_t Gb = (G + 7) >> 3;
+  const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= (uint64_t)n_rows * Gb) return;
+  const uint32_t r = (uint32_t)(u / Gb), gb = (uint32_t)(u % Gb);
+  float z[8];
+  scale_normals8(seed_lo, seed_hi, stream_id, row0 + r, gb, z);
+  for (int j = 0; j < 8; ++j)
+    if (gb * 8 + j < G) out[(uint64_t)r * G + gb * 8 + j] = z[j];
+}
+hipError_t launch_debug_normals(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
+                                uint32_t row0, uint32_t n_rows, uint32_t G, float* out,
+                                hipStream_t st) {
+  uint64_t units = (uint64_t)n_rows * ((G + 7) >> 3);
+  if (units == 0) return hipSuccess;
+  debug_normals_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(seed_lo, seed_hi, stream_id,
+                                                                       row0, n_rows, G, out);
+  return hipGetLastError();
+}
+
+__global__ void debug_philox_kernel(uint32_t seed_lo, uint32_t seed_hi, const uint32_t* ctr,
+                                    uint32_t n, uint32_t* out) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  u32x4 r = philox4x32_10(ctr[4 * i], ctr[4 * i + 1], ctr[4 * i + 2], ctr[4 * i + 3], seed_lo,
+                          seed_hi);
+  out[4 * i] = r.x; out[4 * i + 1] = r.y; out[4 * i + 2] = r.z; out[4 * i + 3] = r.w;
+}
+hipError_t launch_debug_philox(uint32_t seed_lo, uint32_t seed_hi, const uint32_t* ctr,
+                               uint32_t n, uint32_t* out, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  debug_philox_kernel<<<(n + 255) / 256, 256, 0, st>>>(seed_lo, seed_hi, ctr, n, out);
+  return hipGetLastError();
+}
+
+__global__ void debug_normal_pairs_kernel(const uint32_t* words, uint32_t n, float* out) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float a, b;
+  normal_pair(words[i], a, b);
+  out[2 * i] = a;
+  out[2 * i + 1] = b;
+}
+hipError_t launch_debug_normal_pairs(const uint32_t* words, uint32_t n, float* out,
+                                     hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  debug_normal_pairs_kernel<<<(n + 255) / 256, 256, 0, st>>>(words, n, out);
+  return hipGetLastError();
+}
+
+// bf16((s + sign*eps*z) * wbar) for every weight: thread = (n, 8 consecutive k).
+__global__ void debug_dequant_kernel(const uint8_t* __restrict__ q, const bf16_t* __restrict__ s,
+                                     uint32_t row_base, uint32_t N, uint32_t K, uint32_t seed_lo,
+                                     uint32_t seed_hi, float eps_signed, bf16_t* __restrict__ out) {
+  const uint32_t cpr = K >> 3;
+  const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= (uint64_t)N * cpr) return;
+  const uint32_t n = (uint32_t)(u / cpr), c = (uint32_t)(u % cpr);
+  const uint32_t g = c >> 4, G = K >> 7;
+  float z[8];
+  scale_normals8(seed_lo, seed_hi, 0u, row_base + n, g >> 3, z);
+  float zz = z[0];
+#pragma unroll
+  for (int j = 1; j < 8; ++j) zz = ((g & 7u) == (uint32_t)j) ? z[j] : zz;
+  const float se = __builtin_fmaf(eps_signed, zz, bf16_to_f32(s[(uint64_t)n * G + g]));
+  const uint32_t packed = *reinterpret_cast<const uint32_t*>(q + (uint64_t)n * (K >> 1) + c * 4);
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float a = se * (float)((int)((packed >> (8 * j)) & 15u) - 8);
+    float b = se * (float)((int)((packed >> (8 * j + 4)) & 15u) - 8);
+    o[j] = pack_bf16x2(a, b);
+  }
+  *reinterpret_cast<uint4*>(out + (uint64_t)n * K + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+hipError_t launch_debug_dequant(const void* q, const void* s, uint32_t row_base, uint32_t N,
+                                uint32_t K, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+                                void* w_eff, hipStream_t st) {
+  uint64_t units = (uint64_t)N * (K >> 3);
+  if (units == 0) return hipSuccess;
+  debug_dequant_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(
+      (const uint8_t*)q, (const bf16_t*)s, row_base, N, K, seed_lo, seed_hi, eps_signed,
+      (bf16_t*)w_eff);
+  return hipGetLastError();
+}
+
+// -------------------------------------------------------- embedding -------
+__global__ void embed_kernel(const int32_t* __restrict__ tok, const bf16_t* __restrict__ te,
+                             const bf16_t* __restrict__ pe, uint32_t M, uint32_t S, uint32_t d,
+                             bf16_t* __restrict__ h) {
+  const uint32_t cpr = d >> 3;
+  const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= (uint64_t)M * cpr) return;
+  const uint32_t m = (uint32_t)(u / cpr), c = (uint32_t)(u % cpr);
+  uint4 v = *reinterpret_cast<const uint4*>(te + (uint64_t)tok[m] * d + c * 8);
+  if (pe) {
+    uint4 p = *reinterpret_cast<const uint4*>(pe + (uint64_t)(m % S) * d + c * 8);
+    uint32_t a[4] = {v.x, v.y, v.z, v.w}, b[4] = {p.x, p.y, p.z, p.w}, o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      o[j] = pack_bf16x2(__uint_as_float(a[j] << 16) + __uint_as_float(b[j] << 16),
+                         __uint_as_float(a[j] & 0xffff0000u) + __uint_as_float(b[j] & 0xffff0000u));
+    v = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+  *reinterpret_cast<uint4*>(h + (uint64_t)m * d + c * 8) = v;
+}
+hipError_t launch_embed(const int32_t* tok, const void* tok_emb, const void* pos_emb, uint32_t M,
+                        uint32_t S, uint32_t d, void* h, hipStream_t st) {
+  uint64_t units = (uint64_t)M * (d >> 3);
+  embed_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(tok, (const bf16_t*)tok_emb,
+                                                               (const bf16_t*)pos_emb, M, S, d,
+                                                               (bf16_t*)h);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------ norms -------
+// One workgroup per row; fp32 statistics, wavefront-shuffle reduction, fixed
+// order across the four wavefronts.
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+template <bool LAYERNORM>
+__global__ __launch_bounds__(256) void norm_kernel(const bf16_t* __restrict__ x,
+                                                   const bf16_t* __restrict__ gain,
+                                                   const bf16_t* __restrict__ bias, uint32_t d,
+                                                   float eps, bf16_t* __restrict__ y) {
+  __shared__ float red[4];
+  const bf16_t* xr = x + (uint64_t)blockIdx.x * d;
+  bf16_t* yr = y + (uint64_t)blockIdx.x * d;
+  const uint32_t cpr = d >> 3;
+  float mu = 0.0f;
+  if (LAYERNORM) {
+    float acc = 0.0f;
+    for (uint32_t c = threadIdx.x; c < cpr; c += 256) {
+      uint4 v = *reinterpret_cast<const uint4*>(xr + c * 8);
+      uint32_t a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc += __uint_as_float(a[j] << 16) + __uint_as_float(a[j] & 0xffff0000u);
+    }
+    mu = block_sum(acc, red) / (float)d;
+  }
+  float ss = 0.0f;
+  for (uint32_t c = threadIdx.x; c < cpr; c += 256) {
+    uint4 v = *reinterpret_cast<const uint4*>(xr + c * 8);
+    uint32_t a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float lo = __uint_as_float(a[j] << 16) - mu, hi = __uint_as_float(a[j] & 0xffff0000u) - mu;
+      ss = __builtin_fmaf(lo, lo, ss);
+      ss = __builtin_fmaf(hi, hi, ss);
+    }
+  }
+  const float var = block_sum(ss, red) / (float)d;
+  const float inv = 1.0f / sqrtf(var + eps);
+  for (uint32_t c = threadIdx.x; c < cpr; c += 256) {
+    uint4 v = *reinterpret_cast<const uint4*>(xr + c * 8);
+    uint4 gq = *reinterpret_cast<const uint4*>(gain + c * 8);
+    uint32_t a[4] = {v.x, v.y, v.z, v.w}, g[4] = {gq.x, gq.y, gq.z, gq.w}, b[4] = {0, 0, 0, 0}, o[4];
+    if (LAYERNORM) {
+      uint4 bq = *reinterpret_cast<const uint4*>(bias + c * 8);
+      b[0] = bq.x; b[1] = bq.y; b[2] = bq.z; b[3] = bq.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float lo = (__uint_as_float(a[j] << 16) - mu) * inv * __uint_as_float(g[j] << 16);
+      float hi = (__uint_as_float(a[j] & 0xffff0000u) - mu) * inv * __uint_as_float(g[j] & 0xffff0000u);
+      if (LAYERNORM) {
+        lo += __uint_as_float(b[j] << 16);
+        hi += __uint_as_float(b[j] & 0xffff0000u);
+      }
+      o[j] = pack_bf16x2(lo, hi);
+    }
+    *reinterpret_cast<uint4*>(yr + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+hipError_t launch_rmsnorm(const void* x, const void* gain, uint32_t M, uint32_t d, float eps,
+                          void* y, hipStream_t st) {
+  norm_kernel<false><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, nullptr, d, eps,
+                                        (bf16_t*)y);
+  return hipGetLastError();
+}
+hipError_t launch_layernorm(const void* x, const void* gain, const void* bias, uint32_t M,
+                            uint32_t d, float eps, void* y, hipStream_t st) {
+  norm_kernel<true><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, (const bf16_t*)bias,
+                                       d, eps, (bf16_t*)y);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------- RoPE -------
+// table[t][i] = (cos, sin)(t * theta^(-2i/dh)), i < dh/2, evaluated in double.
+__global__ void rope_table_kernel(float2* table, uint32_t max_seq, uint32_t half, double theta,
+                                  double dh) {
+  uint32_t u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= max_seq * half) return;
+  uint32_t t = u / half, i = u % half;
+  double ang = (double)t * pow(theta, -2.0 * (double)i / dh);
+  table[u] = make_float2((float)cos(ang), (float)sin(ang));
+}
+hipError_t launch_rope_table(float* table, uint32_t max_seq, uint32_t dh, float theta,
+                             hipStream_t st) {
+  uint32_t n = max_seq * (dh / 2);
+  rope_table_kernel<<<(n + 255) / 256, 256, 0, st>>>((float2*)table, max_seq, dh / 2,
+                                                     (double)theta, (double)dh);
+  return hipGetLastError();
+}
+// rotate-half pairing (i, i+dh/2) on the q and k thirds of qkv [M, 3d], in place.
+__global__ void rope_kernel(bf16_t* __restrict__ qkv, const float2* __restrict__ table, uint32_t M,
+                            uint32_t S, uint32_t d, uint32_t n_heads) {
+  const uint32_t dh = d / n_heads, half = dh >> 1, cph = half >> 3;   // 8-wide chunks per half head
+  const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint64_t per_row = (uint64_t)2 * n_heads * cph;
+  if (u >= (uint64_t)M * per_row) return;
+  const uint32_t m = (uint32_t)(u / per_row);
+  uint32_t r = (uint32_t)(u % per_row);
+  const uint32_t c = r % cph; r /= cph;
+  const uint32_t h = r % n_heads, which = r / n_heads;
+  bf16_t* p = qkv + (uint64_t)m * 3 * d + (uint64_t)which * d + h * dh + c * 8;
+  const float2* tb = table + (uint64_t)(m % S) * half + c * 8;
+  uint4 va = *reinterpret_cast<const uint4*>(p), vb = *reinterpret_cast<const uint4*>(p + half);
+  uint32_t a[4] = {va.x, va.y, va.z, va.w}, b[4] = {vb.x, vb.y, vb.z, vb.w}, oa[4], ob[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float2 t0 = tb[2 * j], t1 = tb[2 * j + 1];
+    float a0 = __uint_as_float(a[j] << 16), a1 = __uint_as_float(a[j] & 0xffff0000u);
+    float b0 = __uint_as_float(b[j] << 16), b1 = __uint_as_float(b[j] & 0xffff0000u);
+    oa[j] = pack_bf16x2(a0 * t0.x - b0 * t0.y, a1 * t1.x - b1 * t1.y);
+    ob[j] = pack_bf16x2(b0 * t0.x + a0 * t0.y, b1 * t1.x + a1 * t1.y);
+  }
+  *reinterpret_cast<uint4*>(p) = make_uint4(oa[0], oa[1], oa[2], oa[3]);
+  *reinterpret_cast<uint4*>(p + half) = make_uint4(ob[0], ob[1], ob[2], ob[3]);
+}
+hipError_t launch_rope(void* qkv, const float* table, uint32_t B, uint32_t S, uint32_t d,
+                       uint32_t n_heads, hipStream_t st) {
+  const uint32_t dh = d / n_heads;
+  uint64_t units = (uint64_t)B * S * 2 * n_heads * (dh / 16);
+  rope_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>((bf16_t*)qkv, (const float2*)table,
+                                                              B * S, S, d, n_heads);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------- SwiGLU -------
+__global__ void swiglu_kernel(const bf16_t* __restrict__ gu, uint32_t M, uint32_t F,
+                              bf16_t* __restrict__ out) {
+  const uint32_t cpr = F >> 3;
+  const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= (uint64_t)M * cpr) return;
+  const uint32_t m = (uint32_t)(u / cpr), c = (uint32_t)(u % cpr);
+  uint4 vg = *reinterpret_cast<const uint4*>(gu + (uint64_t)m * 2 * F + c * 8);
+  uint4 vu = *reinterpret_cast<const uint4*>(gu + (uint64_t)m * 2 * F + F + c * 8);
+  uint32_t g[4] = {vg.x, vg.y, vg.z, vg.w}, up[4] = {vu.x, vu.y, vu.z, vu.w}, o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float g0 = __uint_as_float(g[j] << 16), g1 = __uint_as_float(g[j] & 0xffff0000u);
+    float u0 = __uint_as_float(up[j] << 16), u1 = __uint_as_float(up[j] & 0xffff0000u);
+    o[j] = pack_bf16x2(g0 / (1.0f + expf(-g0)) * u0, g1 / (1.0f + expf(-g1)) * u1);
+  }
+  *reinterpret_cast<uint4*>(out + (uint64_t)m * F + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+hipError_t launch_swiglu(const void* gu, uint32_t M, uint32_t F, void* out, hipStream_t st) {
+  uint64_t units = (uint64_t)M * (F >> 3);
+  swiglu_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>((const bf16_t*)gu, M, F,
+                                                                (bf16_t*)out);
+  return hipGetLastError();
+}
+
+// --------------------------------------------- cross-entropy reduction ----
+// part[m][slice] = (max, sum exp(l - max)) over the slice's columns.  One
+// wavefront merges a row: lse - target logit; rows at the last position of a
+// sequence predict nothing and contribute 0.
+__global__ __launch_bounds__(256) void ce_rows_kernel(const float* __restrict__ part,
+                                                      const float* __restrict__ tgt, uint32_t M,
+                                                      uint32_t S, uint32_t n_slices,
+                                                      float* __restrict__ rowloss) {
+  const uint32_t m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (m >= M) return;
+  if (m % S == S - 1) {
+    if (lane == 0) rowloss[m] = 0.0f;
+    return;
+  }
+  const float2* p = reinterpret_cast<const float2*>(part) + (uint64_t)m * n_slices;
+  float mx = -INFINITY;
+  for (uint32_t i = lane; i < n_slices; i += 64) mx = fmaxf(mx, p[i].x);
+  mx = wave_max(mx);
+  float sum = 0.0f;
+  for (uint32_t i = lane; i < n_slices; i += 64) {
+    float2 v = p[i];
+    if (v.y > 0.0f) sum += v.y * expf(v.x - mx);
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) rowloss[m] = (mx + logf(sum)) - tgt[m];
+}
+// Fixed-order sum of n floats in double by one workgroup; out = sum * scale.
+__global__ __launch_bounds__(256) void sum_kernel(const float* __restrict__ v, uint32_t n,
+                                                  double scale, float* __restrict__ out) {
+  __shared__ double red[256];
+  double acc = 0.0;
+  for (uint32_t i = threadIdx.x; i < n; i += 256) acc += (double)v[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = (float)(red[0] * scale);
+}
+hipError_t launch_ce_reduce(const float* part, const float* tgt, uint32_t M, uint32_t S,
+                            uint32_t n_slices, float* rowloss, float* loss_out, hipStream_t st) {
+  ce_rows_kernel<<<(M + 3) / 4, 256, 0, st>>>(part, tgt, M, S, n_slices, rowloss);
+  const uint32_t B = M / S;
+  sum_kernel<<<1, 256, 0, st>>>(rowloss, M, 1.0 / ((double)B * (double)(S - 1)), loss_out);
+  return hipGetLastError();
+}
+hipError_t launch_sum_partials(const float* partials, uint32_t n, float* out, hipStream_t st) {
+  sum_kernel<<<1, 256, 0, st>>>(partials, n, 1.0, out);
+  return hipGetLastError();
+}
+
+}  // namespace qzo

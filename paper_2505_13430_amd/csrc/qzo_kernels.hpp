@@ -1,0 +1,100 @@
+// Host-side launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/qzo.h"
+
+namespace qzo {
+
+// One run of consecutive rows with the same number of groups per row, inside
+// one decoder layer's slice of the scale arena.
+struct UpdSeg {
+  uint32_t off;        // first scale, relative to the layer's slice
+  uint32_t rows, G;    // rows x G scales
+  uint32_t row_base;   // noise row id of its first row, relative to the layer
+  uint32_t first_wg;   // first workgroup (of 256 units) serving this segment
+};
+struct UpdPlan {
+  UpdSeg seg[4];
+  uint32_t n_seg;
+  uint32_t wgs_per_layer;
+  uint32_t n_layers;
+  uint64_t layer_stride;     // scales per layer
+  uint32_t rows_per_layer;
+};
+
+// Epilogue selection of the GEMM.
+enum : uint32_t {
+  EPI_BIAS = 1u,       // + bias[n]
+  EPI_RESIDUAL = 2u,   // y = resid[m,n] + acc
+  EPI_RELU = 4u,
+  EPI_SUMSQ = 8u,      // per-workgroup sum of bf16(y)^2 into partials
+};
+
+struct GemmArgs {
+  const void* x;        // bf16 [M,K]
+  const void* w;        // packed int4 [N,K/2] (W4) or bf16 [N,K] (dense)
+  const void* s;        // bf16 [N,K/128] (W4 only)
+  const void* bias;     // bf16 [N] or null
+  const void* resid;    // bf16 [M,N] or null
+  void* y;              // bf16 [M,N]
+  float* partials;      // EPI_SUMSQ: one float per workgroup
+  uint32_t M, N, K;
+  uint32_t row_base;
+  uint32_t seed_lo, seed_hi;
+  float eps_signed;
+  uint32_t epi;
+};
+hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
+uint32_t gemm_workgroups(uint32_t M, uint32_t N);
+
+// lm_head GEMM with the cross-entropy folded into the epilogue: for every row
+// m and every 64-column slice it writes (max, sum exp(l - max)) and, where the
+// target column falls in the slice, the target logit.
+struct CeArgs {
+  const void* x;        // bf16 [M,K]  final hidden states
+  const void* w;        // bf16 [V,K]  lm_head
+  const int32_t* tok;   // [B,S]
+  float* part;          // [M, n_slices, 2]
+  float* tgt;           // [M]
+  uint32_t M, V, K, S;
+  uint32_t n_slices;    // ceil(V/256)*4
+};
+hipError_t launch_lmhead_ce(const CeArgs& a, hipStream_t st);
+hipError_t launch_ce_reduce(const float* part, const float* tgt, uint32_t M, uint32_t S,
+                            uint32_t n_slices, float* rowloss, float* loss_out, hipStream_t st);
+
+hipError_t launch_sum_partials(const float* partials, uint32_t n, float* out, hipStream_t st);
+
+hipError_t launch_embed(const int32_t* tok, const void* tok_emb, const void* pos_emb, uint32_t M,
+                        uint32_t S, uint32_t d, void* h, hipStream_t st);
+hipError_t launch_rmsnorm(const void* x, const void* gain, uint32_t M, uint32_t d, float eps,
+                          void* y, hipStream_t st);
+hipError_t launch_layernorm(const void* x, const void* gain, const void* bias, uint32_t M,
+                            uint32_t d, float eps, void* y, hipStream_t st);
+hipError_t launch_rope_table(float* table, uint32_t max_seq, uint32_t dh, float theta,
+                             hipStream_t st);
+hipError_t launch_rope(void* qkv, const float* table, uint32_t B, uint32_t S, uint32_t d,
+                       uint32_t n_heads, hipStream_t st);
+hipError_t launch_swiglu(const void* gu, uint32_t M, uint32_t F, void* out, hipStream_t st);
+hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_heads,
+                            uint32_t dh, void* out, hipStream_t st);
+hipError_t launch_spsa_clip(const float* losses, float eps, float clip, qzo_step_result* res,
+                            hipStream_t st);
+hipError_t launch_scale_update(void* arena, const UpdPlan& plan, uint32_t seed_lo,
+                               uint32_t seed_hi, float eta, float d_clipped,
+                               const qzo_step_result* res, hipStream_t st);
+hipError_t launch_rtn_quantize(const float* w, uint32_t N, uint32_t K, void* q, void* s,
+                               hipStream_t st);
+hipError_t launch_debug_normals(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
+                                uint32_t row0, uint32_t n_rows, uint32_t G, float* out,
+                                hipStream_t st);
+hipError_t launch_debug_philox(uint32_t seed_lo, uint32_t seed_hi, const uint32_t* ctr,
+                               uint32_t n, uint32_t* out, hipStream_t st);
+hipError_t launch_debug_normal_pairs(const uint32_t* words, uint32_t n, float* out,
+                                     hipStream_t st);
+hipError_t launch_debug_dequant(const void* q, const void* s, uint32_t row_base, uint32_t N,
+                                uint32_t K, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+                                void* w_eff, hipStream_t st);
+
+}  // namespace qzo

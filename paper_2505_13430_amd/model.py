@@ -1,0 +1,114 @@
+"""Device-memory plumbing around the C ABI: uploads a tensor table, owns the
+scale arena and the workspace, and forwards to the binding.  No arithmetic of
+the method happens here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as qb
+from . import synth
+
+
+class DeviceModel:
+    """A model bound to device tensors.  `tensors` follow qzo_model_create's
+    order: bf16 tensors for the fixed parts, uint8 [N, K/2] for packed int4."""
+
+    def __init__(self, shape: dict, tensors, scale_arena: torch.Tensor):
+        self.shape = dict(shape)
+        self.tensors = tensors
+        self.scales = scale_arena
+        self.handle = qb.qzo_model_create(shape, tensors, scale_arena)
+        self._ws = None
+        self._ws_key = None
+        self.result = torch.zeros(8, dtype=torch.int32, device=scale_arena.device)
+        self.loss = torch.zeros(2, dtype=torch.float32, device=scale_arena.device)
+
+    @classmethod
+    def from_host(cls, shape: dict, host_tensors, host_scales, device="cuda:0"):
+        """host_tensors: numpy fp32 arrays holding bf16-exact values, or uint8
+        packed weights; host_scales: fp32 array of bf16-exact scales."""
+        dev = []
+        for a in host_tensors:
+            t = torch.from_numpy(np.ascontiguousarray(a))
+            dev.append(t.to(device) if t.dtype == torch.uint8 else t.to(device).to(torch.bfloat16))
+        arena = torch.from_numpy(np.ascontiguousarray(host_scales, dtype=np.float32)).to(device).to(
+            torch.bfloat16)
+        return cls(shape, dev, arena)
+
+    @classmethod
+    def synthetic(cls, shape: dict, seed: int, device="cuda:0"):
+        """Random-init model built on the device: weights ~ N(0, 0.02) drawn by
+        torch, quantized by the library's RTN kernel (Eq. 3), tensor by tensor."""
+        gen = torch.Generator(device=device)
+        gen.manual_seed(seed)
+        d, V = shape["d_model"], shape["vocab"]
+        llama = shape["arch"] == "llama"
+        n_scales = qb.qzo_model_scale_count(shape)
+        arena = torch.empty(n_scales, dtype=torch.bfloat16, device=device)
+        off = 0
+
+        def fixed(*sz, mean=0.0, std=0.02):
+            return (torch.randn(*sz, generator=gen, device=device) * std + mean).to(torch.bfloat16)
+
+        def quant(N, K):
+            nonlocal off
+            w = torch.randn(N, K, generator=gen, device=device) * 0.02
+            q = torch.empty(N, K // 2, dtype=torch.uint8, device=device)
+            n = N * (K // 128)
+            qb.qzo_rtn_quantize(w, q, arena[off:off + n].view(N, K // 128))
+            off += n
+            return q
+
+        tensors = [fixed(V, d)]
+        if not llama:
+            tensors.append(fixed(shape["max_seq"], d))
+        lin = synth.quantized_linears(shape)
+        for _ in range(shape["n_layers"]):
+            if llama:
+                tensors += [fixed(d, mean=1.0, std=0.1), quant(*lin[0][1:]), quant(*lin[1][1:]),
+                            fixed(d, mean=1.0, std=0.1), quant(*lin[2][1:]), quant(*lin[3][1:])]
+            else:
+                tensors += [fixed(d, mean=1.0, std=0.1), fixed(d), quant(*lin[0][1:]),
+                            fixed(lin[0][1]), quant(*lin[1][1:]), fixed(d),
+                            fixed(d, mean=1.0, std=0.1), fixed(d), quant(*lin[2][1:]),
+                            fixed(lin[2][1]), quant(*lin[3][1:]), fixed(d)]
+        tensors.append(fixed(d, mean=1.0, std=0.1))
+        if not llama:
+            tensors.append(fixed(d))
+        tensors.append(fixed(V, d))
+        torch.cuda.synchronize()
+        assert off == n_scales
+        return cls(shape, tensors, arena)
+
+    def workspace(self, batch, seq):
+        if self._ws_key != (batch, seq):
+            n = qb.qzo_workspace_bytes(self.handle, batch, seq)
+            self._ws = torch.empty(n, dtype=torch.uint8, device=self.scales.device)
+            self._ws_key = (batch, seq)
+        return self._ws
+
+    def forward_loss(self, tokens, seed, eps, sign, stream=None) -> torch.Tensor:
+        ws = self.workspace(*tokens.shape)
+        out = self.loss[0:1] if sign > 0 else self.loss[1:2]
+        qb.qzo_forward_loss(self.handle, tokens, seed, eps, sign, ws, out, stream)
+        return out
+
+    def step(self, tokens, seed, eps, eta, clip, stream=None) -> torch.Tensor:
+        ws = self.workspace(*tokens.shape)
+        qb.qzo_step(self.handle, tokens, seed, eps, eta, clip, ws, self.result, stream)
+        return self.result
+
+    def apply_update(self, seed, eta, d_clipped, stream=None):
+        qb.qzo_model_apply_update(self.handle, seed, eta, d_clipped, stream)
+
+    def close(self):
+        if self.handle is not None:
+            qb.qzo_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,273 @@
+"""HIP path vs the CPU oracle, through the C ABI (needs an MI355X).
+
+Bit-exact: Philox words, the normal recipe, z(row, group), int4 unpack +
+indexing + perturbation (the bf16 weight tile), RTN, the update given d'.
+Floating point: |err| <= tol relative, tolerances stated per test (the bar for
+losses and updated scales is 2e-2 relative, bf16 operands with fp32 accumulate).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_13430_amd import binding as qb
+from paper_2505_13430_amd import synth
+from paper_2505_13430_amd.model import DeviceModel
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    return t.to(dtype) if dtype is not None else t
+
+
+def _bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+# ------------------------------------------------------------------ RNG ----
+def test_philox_words_bit_exact(oracle):
+    rng = np.random.default_rng(1)
+    ctr = rng.integers(0, 1 << 32, size=(4099, 4), dtype=np.uint64).astype(np.uint32)
+    ctr[0] = 0
+    ctr[1] = 0xFFFFFFFF
+    ctr[2] = [0x243F6A88, 0x85A308D3, 0x13198A2E, 0x03707344]
+    for seed in (0, 0xFFFFFFFFFFFFFFFF, 0x299F31D0A4093822, 1234):
+        out = torch.zeros(ctr.shape, dtype=torch.int32, device=DEV)
+        qb.qzo_debug_philox(seed, _dev(ctr.view(np.int32)), out)
+        got = out.cpu().numpy().view(np.uint32)
+        key = [seed & 0xFFFFFFFF, seed >> 32]
+        for i in list(range(8)) + list(range(8, 4099, 97)):
+            assert np.array_equal(got[i], oracle.philox4x32_10(ctr[i], key)), (seed, i)
+    # the published vectors, on the device
+    kat = {0: (0, "6627e8d5 e169c58d bc57ac4c 9b00dbd8"),
+           0xFFFFFFFFFFFFFFFF: (1, "408f276d 41c83b0e a20bc7c6 6d5451fd"),
+           0x299F31D0A4093822: (2, "d16cfe09 94fdcceb 5001e420 24126ea1")}
+    for seed, (row, words) in kat.items():
+        out = torch.zeros(ctr.shape, dtype=torch.int32, device=DEV)
+        qb.qzo_debug_philox(seed, _dev(ctr.view(np.int32)), out)
+        assert [f"{x:08x}" for x in out.cpu().numpy().view(np.uint32)[row]] == words.split()
+
+
+def test_normal_recipe_bit_exact_over_both_factors(oracle):
+    # the radius depends on the top 16 bits only, the angle and signs on the low
+    # 16 only, and the variate is one IEEE product of the two: every value of
+    # each factor, plus a stride through all 2^32 words.
+    ws = [np.arange(65536, dtype=np.uint64) << 16 | a for a in (0, 0x3FFF, 0x9ABC, 0x4001, 0xFFFF)]
+    ws += [np.arange(65536, dtype=np.uint64) | (h << 16) for h in (0, 1, 0x7FFF, 0xFFFF, 0x1234, 0x8000)]
+    ws.append(np.arange(0, 1 << 32, 1021, dtype=np.uint64))
+    w = np.concatenate(ws).astype(np.uint32)
+    out = torch.zeros((w.size, 2), dtype=torch.float32, device=DEV)
+    qb.qzo_debug_normal_pairs(_dev(w.view(np.int32)), out)
+    assert np.array_equal(_bits(out.cpu().numpy()), _bits(oracle.normal_pairs(w)))
+
+
+@pytest.mark.parametrize("rows,G,row0,seed", [(70, 86, 0, 1), (64, 32, 1000, 2), (5, 1, 7, 3),
+                                             (33, 3, 0xFFFFFF00, 0xDEADBEEF12345678),
+                                             (9, 108, 123456, 5), (300, 8, 0, 6)])
+def test_scale_noise_bit_exact(oracle, rows, G, row0, seed):
+    out = torch.zeros((rows, G), dtype=torch.float32, device=DEV)
+    qb.qzo_debug_normals(seed, 0, row0, out)
+    assert np.array_equal(_bits(out.cpu().numpy()), _bits(oracle.scale_normals(seed, row0, rows, G)))
+
+
+# --------------------------------------------- unpack + index + perturb ----
+@pytest.mark.parametrize("N,K,row_base,sign", [(24, 384, 0, 1), (40, 1024 + 128, 77, -1), (8, 128, 5, 1)])
+def test_weight_tile_bit_exact(oracle, N, K, row_base, sign):
+    _, qp, s = synth.linear_case(1, N, K, seed=N + K)
+    out = torch.zeros((N, K), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_debug_dequant(_dev(qp), _dev(s, torch.bfloat16), row_base, 99, 1e-3, sign, out)
+    want = oracle.dequant(qp, s, 99, row_base, sign * np.float32(1e-3), to_bf16=True)
+    assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
+
+
+def test_rtn_quantizer_bit_exact(oracle):
+    rng = np.random.default_rng(3)
+    w = (rng.standard_normal((136, 640)) * 0.02).astype(np.float32)
+    w[5, 128:256] = 0
+    q = torch.zeros((136, 320), dtype=torch.uint8, device=DEV)
+    s = torch.zeros((136, 5), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_rtn_quantize(_dev(w), q, s)
+    qp, sc = oracle.rtn_quantize(w)
+    assert np.array_equal(q.cpu().numpy(), qp)
+    assert np.array_equal(s.float().cpu().numpy(), sc)
+
+
+# --------------------------------------------------------------- update ----
+@pytest.mark.parametrize("rows,G", [(257, 32), (128, 86), (33, 3), (64, 8), (100, 108), (7, 1), (1, 16)])
+def test_update_given_d_bit_exact(oracle, rows, G):
+    rng = np.random.default_rng(rows * G)
+    s = synth.bf16_exact(rng.uniform(0.0, 0.02, (rows, G)).astype(np.float32))
+    s[0, 0] = 0.0
+    for eta, dc in ((1e-5, 37.5), (1e-3, -100.0), (0.0, 5.0), (1e-5, 0.0)):
+        sd = _dev(s, torch.bfloat16)
+        guard = sd.clone()
+        qb.qzo_apply_update(sd, 4242, 17, eta, dc)
+
+        class Seg:
+            pass
+        sg = Seg()
+        sg.name, sg.offset, sg.rows, sg.G, sg.row_base = "t", 0, rows, G, 4242
+        m = oracle.Model(shape={}, tensors=[], names=[], scales=s.reshape(-1).copy(), segments=[sg])
+        want = oracle.update_scales(m, 17, eta, dc).reshape(rows, G)
+        got = sd.float().cpu().numpy()
+        assert np.array_equal(_bits(got), _bits(want)), (eta, dc)
+        if eta == 0.0 or dc == 0.0:
+            assert torch.equal(sd, guard)
+        assert got.min() >= 0
+
+
+# ----------------------------------------------------- perturbed linear ----
+def _gemm_case(oracle, M, N, K, seed, eps, sign, row_base=0):
+    x, qp, s = synth.linear_case(M, N, K, seed)
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    ssq = torch.zeros(1, dtype=torch.float32, device=DEV)
+    qb.qzo_dequant_gemm(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), row_base, 31,
+                        eps, sign, y, ssq)
+    se = oracle.effective_scales(s, row_base, 31, sign * np.float32(eps))
+    ref = oracle.qlinear(x, qp, se)
+    return y.float().cpu().numpy().astype(np.float64), float(ssq.item()), ref
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 520, 384), (256, 256, 128), (1, 8, 128), (513, 264, 1280),
+                                   (64, 1024, 256)])
+def test_perturbed_linear_matches_oracle(oracle, M, N, K):
+    for sign in (1, -1):
+        got, ssq, ref = _gemm_case(oracle, M, N, K, seed=M + N, eps=1e-3, sign=sign, row_base=11)
+        rms = math.sqrt((ref ** 2).mean())
+        # bf16 weights (2^-9 each, averaging over K) and bf16 output rounding (2^-9)
+        assert (np.abs(got - ref) <= 8e-3 * np.abs(ref) + 8e-3 * rms).all(), np.abs(got - ref).max() / rms
+        assert abs(ssq - oracle.sumsq_bf16(ref)) <= 5e-3 * oracle.sumsq_bf16(ref)
+        assert abs(ssq - (got ** 2).sum()) <= 1e-4 * ssq      # the sum is of the stored outputs
+
+
+def test_perturbed_linear_sign_and_eps_identities(oracle):
+    x, qp, s = synth.linear_case(130, 264, 512, 8)
+    xd, qd, sd = _dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16)
+
+    def run(eps, sign, seed=5):
+        y = torch.zeros((130, 264), dtype=torch.bfloat16, device=DEV)
+        qb.qzo_dequant_gemm(xd, qd, sd, 0, seed, eps, sign, y, None)
+        return y
+    assert torch.equal(run(1e-3, 1), run(-1e-3, -1))          # only sign*eps matters
+    assert torch.equal(run(0.0, 1), run(0.0, -1))             # eps = 0: both passes coincide
+    assert torch.equal(run(0.0, 1), run(0.0, 1, seed=6))      # ... and the seed is irrelevant
+    assert not torch.equal(run(1e-3, 1), run(1e-3, -1))
+    assert torch.equal(run(1e-3, 1), run(1e-3, 1))            # run-to-run deterministic
+
+
+def test_boundary_rejects_bad_arguments():
+    x = torch.zeros((4, 128), dtype=torch.bfloat16, device=DEV)
+    q = torch.zeros((8, 64), dtype=torch.uint8, device=DEV)
+    s = torch.zeros((8, 1), dtype=torch.bfloat16, device=DEV)
+    y = torch.zeros((4, 8), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(qb.QzoError) as e:
+        qb.qzo_dequant_gemm(x, q, s, 0, 1, 1e-3, 2, y)
+    assert e.value.status == qb.QZO_ERR_ARG
+    with pytest.raises(qb.QzoError) as e:
+        qb.qzo_dequant_gemm(x, q, s, 0, 1, 1e-3, 1, y, group=64)
+    assert e.value.status == qb.QZO_ERR_SHAPE
+    with pytest.raises(qb.QzoError) as e:
+        qb.qzo_dequant_gemm(x.view(-1)[1:].view(-1)[:384].view(3, 128), q, s, 0, 1, 1e-3, 1, y)
+    assert e.value.status == qb.QZO_ERR_ALIGN
+
+
+# ------------------------------------------------------------ the model ----
+SHARP = dict(arch="llama", n_layers=2, d_model=256, n_heads=2, d_ffn=512, vocab=520, max_seq=96,
+             batch=3, seq=80)     # head size 128, ragged vocab, seq not a multiple of 32/128
+
+
+def _models(oracle, shape, seed, gain=1.0):
+    table = synth.tensor_table(shape, seed)
+    if gain != 1.0:   # larger weights: logits far from uniform, loss far from ln V
+        table = [(n, k, synth.bf16_exact(a * gain) if (k == "w" or n in ("tok_emb", "lm_head")) else a)
+                 for n, k, a in table]
+    om = oracle.build_model(shape, table)
+    return om, DeviceModel.from_host(shape, om.tensors, om.scales, DEV)
+
+
+@pytest.mark.parametrize("name,gain", [("tiny", 1.0), ("tiny_opt", 1.0), ("tiny", 4.0), ("tiny_opt", 4.0),
+                                       ("sharp", 4.0)])
+def test_forward_matches_oracle(oracle, name, gain):
+    shape = SHARP if name == "sharp" else synth.SHAPES[name]
+    om, dm = _models(oracle, shape, 1234, gain)
+    tok = synth.tokens(shape, 5678)
+    tokd = _dev(tok)
+    B, S = tok.shape
+    for sign in (1, -1):
+        se = oracle.perturbed_scales(om, 9, sign * np.float32(1e-3))
+        ref_loss, ref_hid = oracle.forward_loss(om, se, tok, act_bf16=True, want_hidden=True)
+        hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        qb.qzo_debug_forward(dm.handle, tokd, 9, 1e-3, sign, dm.workspace(B, S), loss, hid)
+        got_loss = float(loss.item())
+        assert abs(got_loss - ref_loss) <= 2e-2 * abs(ref_loss), (got_loss, ref_loss)
+        if gain > 1:
+            assert abs(ref_loss - math.log(shape["vocab"])) > 0.05      # the case is not degenerate
+        h = hid.float().cpu().numpy().astype(np.float64)
+        rms = math.sqrt((ref_hid ** 2).mean())
+        # final hidden states after 2 layers of bf16 storage: a few bf16 ulps of the row scale
+        assert np.abs(h - ref_hid).max() <= 6e-2 * rms, np.abs(h - ref_hid).max() / rms
+        assert math.sqrt(((h - ref_hid) ** 2).mean()) <= 1e-2 * rms
+        again = torch.zeros(1, dtype=torch.float32, device=DEV)
+        qb.qzo_forward_loss(dm.handle, tokd, 9, 1e-3, sign, dm.workspace(B, S), again)
+        assert again.item() == got_loss                                  # deterministic
+    dm.close()
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt"])
+def test_step_matches_oracle(oracle, name):
+    shape = synth.SHAPES[name]
+    om, dm = _models(oracle, shape, 1234)
+    tok = synth.tokens(shape, 5678)
+    tokd = _dev(tok)
+    ref = oracle.qzo_step(om, tok, seed=1, eps=1e-3, eta=1e-5, Cthr=100.0)
+    before = dm.scales.clone()
+    res = qb.read_step_result(dm.step(tokd, 1, 1e-3, 1e-5, 100.0))
+    assert res["status"] == 0
+    for k in ("loss_plus", "loss_minus"):
+        assert abs(res[k] - ref[k]) <= 2e-2 * abs(ref[k])
+    assert res["d"] == np.float32((np.float32(res["loss_plus"]) - np.float32(res["loss_minus"]))
+                                  / (np.float32(2) * np.float32(1e-3)))
+    assert res["d_clipped"] == max(-100.0, min(100.0, res["d"]))
+    got = dm.scales.float().cpu().numpy()
+    assert (np.abs(got - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-7).all()
+    assert not torch.equal(dm.scales, before)
+    # exactly the oracle's update for the d' the device found
+    want = oracle.update_scales(om, 1, 1e-5, res["d_clipped"])
+    assert np.array_equal(_bits(got), _bits(want))
+    print(name, "d gpu", res["d"], "d oracle", ref["d"])
+    dm.close()
+
+
+def test_step_special_cases(oracle):
+    shape = synth.SHAPES["tiny"]
+    om, dm = _models(oracle, shape, 1234)
+    tokd = _dev(synth.tokens(shape, 5678))
+    before = dm.scales.clone()
+    r = qb.read_step_result(dm.step(tokd, 1, 0.0, 1e-5, 100.0))          # eps = 0: 0/0, skipped
+    assert r["loss_plus"] == r["loss_minus"] and r["status"] == qb.QZO_ERR_NONFINITE
+    assert torch.equal(dm.scales, before)
+    r = qb.read_step_result(dm.step(tokd, 1, 1e-3, 1e-5, 0.0))           # C = 0: zero-shot
+    assert r["status"] == 0 and r["d_clipped"] == 0.0 and torch.equal(dm.scales, before)
+    r = qb.read_step_result(dm.step(tokd, 1, 1e-3, 0.0, 100.0))          # eta = 0
+    assert torch.equal(dm.scales, before)
+    with pytest.raises(qb.QzoError):
+        dm.step(tokd, 1, 1e-3, 1e-5, -1.0)                               # C must be >= 0
+    # update over the whole arena given the oracle's d', bit-exact
+    dm.apply_update(77, 1e-5, -12.5)
+    want = oracle.update_scales(om, 77, 1e-5, -12.5)
+    assert np.array_equal(_bits(dm.scales.float().cpu().numpy()), _bits(want))
+    dm.close()
+
+
+def test_device_built_model_runs_and_is_near_ln_vocab():
+    shape = synth.SHAPES["tiny"]
+    dm = DeviceModel.synthetic(shape, seed=3, device=DEV)
+    tokd = _dev(synth.tokens(shape, 5))
+    r = qb.read_step_result(dm.step(tokd, 2, 1e-3, 1e-5, 100.0))
+    assert r["status"] == 0 and abs(r["loss_plus"] - math.log(shape["vocab"])) < 0.3
+    dm.close()
