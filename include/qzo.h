@@ -185,6 +185,20 @@ qzo_status qzo_debug_forward(qzo_model* m, const int32_t* tokens_dev, uint32_t b
                              uint64_t workspace_bytes, float* loss_dev, void* hidden_dev,
                              void* stream);
 
+/*
+ * Measurement hooks (for benchmarks; not part of the method).  After
+ * qzo_profile_begin(max_records) every kernel launch of qzo_forward_loss /
+ * qzo_step is bracketed by a pair of HIP events recorded on the call's stream
+ * until max_records launches have been seen.  qzo_profile_collect stops the
+ * recording, waits for the recorded events and returns, for one kernel class,
+ * the summed elapsed milliseconds, the number of launches and the summed
+ * algorithmic work (flops for 0..2, bytes for 3).  Classes: 0 = perturbed
+ * W4A16 GEMM, 1 = lm_head GEMM + cross-entropy partials, 2 = attention,
+ * 3 = scale update, 4 = embedding.  Host pointers.  Not thread-safe.
+ */
+qzo_status qzo_profile_begin(uint32_t max_records);
+qzo_status qzo_profile_collect(uint32_t kind, double* total_ms, uint64_t* launches, double* work);
+
 const char* qzo_last_error(void);
 
 #ifdef __cplusplus

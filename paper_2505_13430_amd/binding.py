@@ -24,7 +24,8 @@ EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
     "qzo_apply_update", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
-    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_last_error",
+    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_profile_begin", "qzo_profile_collect",
+    "qzo_last_error",
 ]
 
 
@@ -191,3 +192,16 @@ def qzo_debug_forward(model, tokens, seed, eps, sign, workspace, loss_out, hidde
                                    C.c_uint64(seed), C.c_float(eps), C.c_int(sign), _ptr(workspace),
                                    C.c_uint64(workspace.numel() * workspace.element_size()),
                                    _ptr(loss_out), _ptr(hidden_out), _stream(stream)))
+
+
+PROFILE_KINDS = {"w4a16_gemm": 0, "lmhead_ce": 1, "attention": 2, "scale_update": 3, "embed": 4}
+
+
+def qzo_profile_begin(max_records: int):
+    _check(lib().qzo_profile_begin(C.c_uint32(max_records)))
+
+
+def qzo_profile_collect(kind: int) -> dict:
+    ms, n, work = C.c_double(0), C.c_uint64(0), C.c_double(0)
+    _check(lib().qzo_profile_collect(C.c_uint32(kind), C.byref(ms), C.byref(n), C.byref(work)))
+    return dict(total_ms=ms.value, launches=n.value, work=work.value)

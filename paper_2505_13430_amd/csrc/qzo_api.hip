@@ -155,6 +155,31 @@ qzo_status check_batch(const qzo_model* m, const void* tok, uint32_t batch, uint
   return QZO_OK;
 }
 
+// Optional per-kernel-class timing with HIP events recorded on the caller's
+// stream around each launch (qzo_profile_begin / qzo_profile_collect).
+struct ProfRec { hipEvent_t a, b; uint32_t kind; double work; };
+struct Profiler {
+  bool on = false;
+  std::vector<ProfRec> pool;
+  size_t used = 0;
+} g_prof;
+
+struct ProfScope {
+  ProfRec* r = nullptr;
+  hipStream_t st;
+  ProfScope(uint32_t kind, double work, hipStream_t s) : st(s) {
+    if (!g_prof.on || g_prof.used >= g_prof.pool.size()) return;
+    r = &g_prof.pool[g_prof.used++];
+    r->kind = kind;
+    r->work = work;
+    (void)hipEventRecord(r->a, st);
+  }
+  ~ProfScope() {
+    if (r) (void)hipEventRecord(r->b, st);
+  }
+};
+enum { PK_W4GEMM = 0, PK_LMHEAD = 1, PK_ATTN = 2, PK_UPDATE = 3, PK_OTHER = 4, PK_COUNT = 5 };
+
 // The decoder forward with every quantized linear perturbed by sign*eps*z.
 qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t seq, uint64_t seed,
                    float eps_signed, const Workspace& w, float* loss_out, hipStream_t st,
@@ -165,7 +190,13 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
   const unsigned char* arena = (const unsigned char*)m->arena;
 
-  QZO_HIP(launch_embed(tok, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
+  {
+    ProfScope ps(PK_OTHER, 0, st);
+    QZO_HIP(launch_embed(tok, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
+  }
+  const double attn_flops = 2.0 * batch * H * (double)seq * seq * dh;   // causal: half of 4 B H S^2 dh
+  auto other = [&](hipError_t e) { return e; };
+  (void)other;
   for (uint32_t l = 0; l < c.n_layers; ++l) {
     const qzo_buf* T = &m->T[m->first_layer_tensor + (size_t)l * m->tensors_per_layer];
     const uint64_t layer_off = (uint64_t)l * m->scales_per_layer;
@@ -177,6 +208,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
       g.M = M; g.N = m->lin[li].N; g.K = m->lin[li].K;
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
+      ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
       return launch_w4a16_gemm(g, st);
     };
     if (llama) {
@@ -184,7 +216,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
       QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(0, w.a, T[1].ptr_dev, nullptr, nullptr, w.qkv, 0));
       QZO_HIP(launch_rope(w.qkv, m->rope_table, batch, seq, d, H, st));
-      QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
+      {
+        ProfScope ps(PK_ATTN, attn_flops, st);
+        QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
+      }
       QZO_HIP(gemm(1, w.att, T[2].ptr_dev, nullptr, w.h, w.h, EPI_RESIDUAL));
       QZO_HIP(launch_rmsnorm(w.h, T[3].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(2, w.a, T[4].ptr_dev, nullptr, nullptr, w.ff, 0));
@@ -194,7 +229,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
       // ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, wfc1, bfc1, wfc2, bfc2
       QZO_HIP(launch_layernorm(w.h, T[0].ptr_dev, T[1].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(0, w.a, T[2].ptr_dev, T[3].ptr_dev, nullptr, w.qkv, EPI_BIAS));
-      QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
+      {
+        ProfScope ps(PK_ATTN, attn_flops, st);
+        QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
+      }
       QZO_HIP(gemm(1, w.att, T[4].ptr_dev, T[5].ptr_dev, w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
       QZO_HIP(launch_layernorm(w.h, T[6].ptr_dev, T[7].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(2, w.a, T[8].ptr_dev, T[9].ptr_dev, nullptr, w.ff, EPI_BIAS | EPI_RELU));
@@ -215,7 +253,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
   CeArgs ce = {};
   ce.x = w.a; ce.w = lm_head; ce.tok = tok; ce.part = w.ce_part; ce.tgt = w.tgt;
   ce.M = M; ce.V = c.vocab; ce.K = d; ce.S = seq; ce.n_slices = ((c.vocab + 255) / 256) * 4;
-  QZO_HIP(launch_lmhead_ce(ce, st));
+  {
+    ProfScope ps(PK_LMHEAD, 2.0 * M * (double)c.vocab * d, st);
+    QZO_HIP(launch_lmhead_ce(ce, st));
+  }
   QZO_HIP(launch_ce_reduce(w.ce_part, w.tgt, M, seq, ce.n_slices, w.rowloss, loss_out, st));
   return QZO_OK;
 }
@@ -366,8 +407,11 @@ qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uin
   st = forward(m, tokens_dev, batch, seq, seed, -eps, w, w.losses + 1, s);
   if (st != QZO_OK) return st;
   QZO_HIP(launch_spsa_clip(w.losses, eps, clip, result_dev, s));
-  QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta, 0.0f,
-                              result_dev, s));
+  {
+    ProfScope ps(PK_UPDATE, 4.0 * (double)m->n_scales, s);
+    QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta, 0.0f,
+                                result_dev, s));
+  }
   return QZO_OK;
 }
 
@@ -431,6 +475,38 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
   }
   QZO_HIP(launch_w4a16_gemm(g, st));
   if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  return QZO_OK;
+}
+
+qzo_status qzo_profile_begin(uint32_t max_records) {
+  while (g_prof.pool.size() < max_records) {
+    ProfRec r = {};
+    QZO_HIP(hipEventCreate(&r.a));
+    QZO_HIP(hipEventCreate(&r.b));
+    g_prof.pool.push_back(r);
+  }
+  g_prof.used = 0;
+  g_prof.on = true;
+  return QZO_OK;
+}
+
+qzo_status qzo_profile_collect(uint32_t kind, double* total_ms, uint64_t* launches, double* work) {
+  if (!total_ms || !launches || !work) return fail(QZO_ERR_ARG, "null output");
+  if (kind >= PK_COUNT) return fail(QZO_ERR_ARG, "unknown kernel class");
+  g_prof.on = false;
+  double ms = 0, wk = 0;
+  uint64_t n = 0;
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    ProfRec& r = g_prof.pool[i];
+    if (r.kind != kind) continue;
+    QZO_HIP(hipEventSynchronize(r.b));
+    float t = 0;
+    QZO_HIP(hipEventElapsedTime(&t, r.a, r.b));
+    ms += t;
+    wk += r.work;
+    ++n;
+  }
+  *total_ms = ms; *launches = n; *work = wk;
   return QZO_OK;
 }
 

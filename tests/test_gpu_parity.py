@@ -138,8 +138,11 @@ def test_perturbed_linear_matches_oracle(oracle, M, N, K):
     for sign in (1, -1):
         got, ssq, ref = _gemm_case(oracle, M, N, K, seed=M + N, eps=1e-3, sign=sign, row_base=11)
         rms = math.sqrt((ref ** 2).mean())
-        # bf16 weights (2^-9 each, averaging over K) and bf16 output rounding (2^-9)
-        assert (np.abs(got - ref) <= 8e-3 * np.abs(ref) + 8e-3 * rms).all(), np.abs(got - ref).max() / rms
+        # bf16 unit roundoff is 2^-8: the weight tile's rounding gives an error of std
+        # ~1.6e-3 rms (independent over K), the stored output one of <= 2^-8 |y|.
+        bad = np.abs(got - ref) > 6e-3 * np.abs(ref) + 1.2e-2 * rms
+        assert not bad.any(), (int(bad.sum()), np.abs(got - ref).max() / rms)
+        assert math.sqrt(((got - ref) ** 2).mean()) <= 4e-3 * rms
         assert abs(ssq - oracle.sumsq_bf16(ref)) <= 5e-3 * oracle.sumsq_bf16(ref)
         assert abs(ssq - (got ** 2).sum()) <= 1e-4 * ssq      # the sum is of the stored outputs
 
@@ -209,9 +212,16 @@ def test_forward_matches_oracle(oracle, name, gain):
             assert abs(ref_loss - math.log(shape["vocab"])) > 0.05      # the case is not degenerate
         h = hid.float().cpu().numpy().astype(np.float64)
         rms = math.sqrt((ref_hid ** 2).mean())
-        # final hidden states after 2 layers of bf16 storage: a few bf16 ulps of the row scale
-        assert np.abs(h - ref_hid).max() <= 6e-2 * rms, np.abs(h - ref_hid).max() / rms
-        assert math.sqrt(((h - ref_hid) ** 2).mean()) <= 1e-2 * rms
+        # final hidden states after 2 layers of bf16 storage.  The noise floor of 16-bit
+        # activations is what the oracle itself moves by when its A16 rounding is switched
+        # off (5e-3 .. 1.3e-2 rms here); the kernels round the weight tile and the attention
+        # probabilities to bf16 as well, so they may sit up to twice that floor away.
+        _, exact_hid = oracle.forward_loss(om, se, tok, act_bf16=False, want_hidden=True)
+        floor_rms = math.sqrt(((exact_hid - ref_hid) ** 2).mean())
+        floor_max = np.abs(exact_hid - ref_hid).max()
+        err = np.abs(h - ref_hid)
+        assert math.sqrt((err ** 2).mean()) <= 2 * floor_rms + 2e-3 * rms, (math.sqrt((err ** 2).mean()) / rms, floor_rms / rms)
+        assert err.max() <= 2 * floor_max + 2e-2 * rms, (err.max() / rms, floor_max / rms)
         again = torch.zeros(1, dtype=torch.float32, device=DEV)
         qb.qzo_forward_loss(dm.handle, tokd, 9, 1e-3, sign, dm.workspace(B, S), again)
         assert again.item() == got_loss                                  # deterministic
