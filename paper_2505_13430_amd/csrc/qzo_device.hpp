@@ -28,10 +28,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
-struct u32x4 { uint32_t x, y, z, w; };
+struct u32x4_t { uint32_t x, y, z, w; };
 
 // Philox4x32 with 10 rounds (Salmon et al., SC'11).
-__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+__device__ __forceinline__ u32x4_t philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                                uint32_t k0, uint32_t k1) {
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
@@ -104,7 +104,7 @@ __device__ __forceinline__ void normal_pair(uint32_t w, float& z0, float& z1) {
 // The eight variates z(row, 8*gblock .. 8*gblock+7) of one Philox counter.
 __device__ __forceinline__ void scale_normals8(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream,
                                                uint32_t row, uint32_t gblock, float z[8]) {
-  u32x4 w = philox4x32_10(row, gblock, stream, 0u, seed_lo, seed_hi);
+  u32x4_t w = philox4x32_10(row, gblock, stream, 0u, seed_lo, seed_hi);
   normal_pair(w.x, z[0], z[1]);
   normal_pair(w.y, z[2], z[3]);
   normal_pair(w.z, z[4], z[5]);

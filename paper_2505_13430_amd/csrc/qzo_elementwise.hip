@@ -171,7 +171,7 @@ __global__ void debug_philox_kernel(uint32_t seed_lo, uint32_t seed_hi, const ui
                                     uint32_t n, uint32_t* out) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  u32x4 r = philox4x32_10(ctr[4 * i], ctr[4 * i + 1], ctr[4 * i + 2], ctr[4 * i + 3], seed_lo,
+  u32x4_t r = philox4x32_10(ctr[4 * i], ctr[4 * i + 1], ctr[4 * i + 2], ctr[4 * i + 3], seed_lo,
                           seed_hi);
   out[4 * i] = r.x; out[4 * i + 1] = r.y; out[4 * i + 2] = r.z; out[4 * i + 3] = r.w;
 }

@@ -8,11 +8,16 @@
 // Tiling: 256x256 output tile per workgroup, BK = 64, eight wavefronts in a
 // 2 (M) x 4 (N) arrangement, each owning 128x64 = 4x2 MFMA tiles.  Both
 // operands are K-contiguous in LDS (128 B per row, 16-byte chunks XOR-swizzled
-// by row so that fragment reads and tile writes spread over all banks), double
+// by row pair so that 16 lanes of a fragment read hit all 64 banks), double
 // buffered.  int4 weights are unpacked, scaled by the perturbed scale and
-// rounded to bf16 once per workgroup while being written to LDS; the noise z
-// is regenerated per row every eight groups from the Philox counter
-// (row, g/8) and never touches memory.
+// rounded to bf16 once per workgroup while being written to LDS; the noise z is
+// regenerated per row every eight groups from the Philox counter (row, g/8)
+// and never touches memory.
+//
+// The weight tile is the MFMA's first operand and the activation tile its
+// second, so a lane of the result owns one token and four consecutive output
+// features per register group: stores are 8 bytes wide and the cross-entropy
+// reductions run over a lane's own registers.
 #include "qzo_device.hpp"
 #include "qzo_kernels.hpp"
 
@@ -24,27 +29,50 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int THREADS = 512;
 constexpr int TILE_BYTES = BM * BK * 2;            // 32 KB per operand per stage
-constexpr int LDS_BYTES = 4 * TILE_BYTES;          // A0 B0 A1 B1
+constexpr int LDS_BYTES = 4 * TILE_BYTES;          // A0 A1 B0 B1
 
 uint32_t gemm_workgroups(uint32_t M, uint32_t N) {
-  uint32_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  return ((tiles + 7) / 8) * 8;
+  static uint32_t n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 8)
+      cu = 256;
+    n_cu = (uint32_t)cu & ~7u;
+  }
+  const uint32_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  return min(((tiles + 7) / 8) * 8, n_cu);
 }
 
-// Workgroup id -> output tile.  Hardware deals consecutive workgroup ids to the
-// eight XCDs in turn; each XCD gets one contiguous eighth of a tile order in
-// which groups of 8 M-tiles sweep the N-tiles, so the tiles resident on one
-// XCD at a time share a few A row-panels and B row-panels in that XCD's L2.
-__device__ __forceinline__ bool tile_of_block(uint32_t tiles_m, uint32_t tiles_n, uint32_t& tm,
-                                              uint32_t& tn) {
-  const uint32_t total = tiles_m * tiles_n;
-  const uint32_t per = (total + 7) >> 3;
-  const uint32_t id = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
-  if (id >= total) return false;
-  const uint32_t width = 8u * tiles_n;
+// Persistent workgroups: the grid is one workgroup per compute unit (or fewer when
+// there are fewer tiles) and every workgroup walks a list of output tiles.
+// Hardware deals consecutive workgroup ids to the eight XCDs in turn; each XCD
+// gets one contiguous eighth of a tile order in which groups of 8 M-tiles sweep
+// the N-tiles, and its workgroups take consecutive entries of that eighth, so the
+// tiles in flight on one XCD share a few A and B row-panels in that XCD's L2.
+struct TileWalk {
+  uint32_t tiles_m, tiles_n, total, per, xcd, slot, stride;
+};
+__device__ __forceinline__ TileWalk tile_walk_init(uint32_t M, uint32_t N) {
+  TileWalk w;
+  w.tiles_m = (M + BM - 1) / BM;
+  w.tiles_n = (N + BN - 1) / BN;
+  w.total = w.tiles_m * w.tiles_n;
+  w.per = (w.total + 7) >> 3;
+  w.xcd = blockIdx.x & 7u;
+  w.slot = blockIdx.x >> 3;
+  w.stride = gridDim.x >> 3;
+  return w;
+}
+// Tile of the walk's current slot; false when the walk is over.
+__device__ __forceinline__ bool tile_walk_get(const TileWalk& w, uint32_t& tm, uint32_t& tn) {
+  if (w.slot >= w.per) return false;
+  const uint32_t id = w.xcd * w.per + w.slot;
+  if (id >= w.total) return false;
+  const uint32_t width = 8u * w.tiles_n;
   const uint32_t group = id / width;
   const uint32_t first = group * 8u;
-  const uint32_t gsz = min(tiles_m - first, 8u);
+  const uint32_t gsz = min(w.tiles_m - first, 8u);
   const uint32_t in = id - group * width;
   tm = first + in % gsz;
   tn = in / gsz;
@@ -52,20 +80,24 @@ __device__ __forceinline__ bool tile_of_block(uint32_t tiles_m, uint32_t tiles_n
 }
 
 __device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t chunk) {
-  return row * 128u + ((chunk ^ (row & 7u)) << 4);
+  return row * 128u + ((chunk ^ ((row >> 1) & 7u)) << 4);
 }
 
-// 8 nibbles of one dword -> 8 bf16 of (nibble-8)*se, in k order.
-__device__ __forceinline__ uint4 dequant8(uint32_t w, float se, float m8se) {
+// 8 nibbles of one dword -> 8 bf16 of (nibble-8)*se, in k order.  A byte holding
+// a nibble u (0..15) read as an fp8 E4M3 pattern is exactly u * 2^-9, so one
+// v_cvt_pk_f32_fp8 turns two nibbles into floats; fma(u 2^-9, 512 se, -8 se)
+// is (u-8)*se with a single rounding, the same bits as se * float(u-8).
+__device__ __forceinline__ uint4 dequant8(uint32_t w, float se512, float m8se) {
+  typedef float f2 __attribute__((ext_vector_type(2)));
   const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;
-  float e0 = __builtin_fmaf((float)(lo & 0xffu), se, m8se);
-  float e1 = __builtin_fmaf((float)(hi & 0xffu), se, m8se);
-  float e2 = __builtin_fmaf((float)((lo >> 8) & 0xffu), se, m8se);
-  float e3 = __builtin_fmaf((float)((hi >> 8) & 0xffu), se, m8se);
-  float e4 = __builtin_fmaf((float)((lo >> 16) & 0xffu), se, m8se);
-  float e5 = __builtin_fmaf((float)((hi >> 16) & 0xffu), se, m8se);
-  float e6 = __builtin_fmaf((float)(lo >> 24), se, m8se);
-  float e7 = __builtin_fmaf((float)(hi >> 24), se, m8se);
+  const f2 l01 = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false);   // nibbles 0, 2
+  const f2 l23 = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);    // nibbles 4, 6
+  const f2 h01 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false);   // nibbles 1, 3
+  const f2 h23 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);    // nibbles 5, 7
+  const float e0 = __builtin_fmaf(l01.x, se512, m8se), e1 = __builtin_fmaf(h01.x, se512, m8se);
+  const float e2 = __builtin_fmaf(l01.y, se512, m8se), e3 = __builtin_fmaf(h01.y, se512, m8se);
+  const float e4 = __builtin_fmaf(l23.x, se512, m8se), e5 = __builtin_fmaf(h23.x, se512, m8se);
+  const float e6 = __builtin_fmaf(l23.y, se512, m8se), e7 = __builtin_fmaf(h23.y, se512, m8se);
   return make_uint4(pack_bf16x2(e0, e1), pack_bf16x2(e2, e3), pack_bf16x2(e4, e5),
                     pack_bf16x2(e6, e7));
 }
@@ -80,200 +112,337 @@ struct CeEpilogue {
 template <bool W4, bool CE>
 __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue ce) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const uint32_t tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  TileWalk walk = tile_walk_init(a.M, a.N);
   uint32_t tile_m, tile_n;
-  if (!tile_of_block(tiles_m, tiles_n, tile_m, tile_n)) return;
-  const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
+  if (!tile_walk_get(walk, tile_m, tile_n)) return;
+  const uint32_t tiles_m = walk.tiles_m;
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t wm = wave >> 2, wn = wave & 3u;
   const uint32_t K = a.K;
 
   // ---- global -> register staging ---------------------------------------
+  // Operands are read with buffer loads: base address and size sit in scalar
+  // registers, a lane contributes a 32-bit byte offset fixed for the whole output
+  // tile, and the k advance is a scalar offset.
   // A (and dense B): 2048 16-byte chunks per tile, 4 per thread; 8 consecutive
   // threads cover one 128-byte row segment.
-  const unsigned char* xa[4];
-  uint32_t a_lds[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t cid = t + THREADS * i, row = cid >> 3, c = cid & 7u;
-    const uint32_t gm = min(m0 + row, a.M - 1);
-    xa[i] = (const unsigned char*)a.x + ((uint64_t)gm * K + c * 8) * 2;
-    a_lds[i] = lds_off(row, c);
-  }
-  const unsigned char* wb[4];
-  uint32_t b_lds[4];
   // W4: thread = (row t/2, half t%2): 16 bytes = 32 nibbles = 4 chunks.
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(a.x), 0, (int)((uint64_t)a.M * K * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(a.w), 0, (int)(W4 ? (uint64_t)a.N * (K >> 1) : (uint64_t)a.N * K * 2),
+      0x00020000);
+  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(W4 ? a.s : a.x), 0, (int)(W4 ? (uint64_t)a.N * (K >> 7) * 2 : 16), 0x00020000);
+  uint32_t xo[4], wo[4], so = 0, gn_w4 = 0;
   const uint32_t brow = t >> 1, bhalf = t & 1u;
-  const uint32_t gn_w4 = min(n0 + brow, a.N - 1);
-  const bf16_t* srow = nullptr;
-  if (W4) {
-    wb[0] = (const unsigned char*)a.w + (uint64_t)gn_w4 * (K >> 1) + bhalf * 16;
-    srow = (const bf16_t*)a.s + (uint64_t)gn_w4 * (K >> 7);
+  // LDS offsets: rows t/8 + 64 i share their swizzle, so chunk i is a_lds + i * 8 KB.
+  const uint32_t a_lds = lds_off(t >> 3, t & 7u);
+  uint32_t b_lds[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) b_lds[j] = lds_off(brow, bhalf * 4 + j);
-  } else {
+  for (int i = 0; i < 4; ++i) b_lds[i] = W4 ? lds_off(brow, bhalf * 4 + i) : a_lds + i * 8192u;
+// Operand offsets of output tile (TM, TN).
+#define QZO_TILE_PTRS(TM, TN)                                                                \
+  do {                                                                                       \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                          \
+      const uint32_t row = (t >> 3) + 64u * i, c = t & 7u;                                   \
+      xo[i] = (min((TM) * BM + row, a.M - 1) * K + c * 8) * 2;                               \
+      if (!W4) wo[i] = (min((TN) * BN + row, a.N - 1) * K + c * 8) * 2;                      \
+    }                                                                                        \
+    if (W4) {                                                                                \
+      gn_w4 = min((TN) * BN + brow, a.N - 1);                                                \
+      wo[0] = gn_w4 * (K >> 1) + bhalf * 16;                                                 \
+      so = gn_w4 * (K >> 7) * 2;                                                             \
+    }                                                                                        \
+  } while (0)
+  QZO_TILE_PTRS(tile_m, tile_n);
+
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
+  rb1 = rb2 = rb3 = (u32x4){0, 0, 0, 0};
+  uint32_t zw[4] = {0, 0, 0, 0};     // Philox words of the current 8 groups
+  float z_odd = 0.0f;                // second variate of the current pair
+  float se512 = 0.0f, m8se = 0.0f;
+  bf16_t s_next = 0;
+
+  // LDS: A stage 0 | A stage 1 | B stage 0 | B stage 1, 32 KB each.  The k-loop is
+  // unrolled by two so the stage is a compile-time constant and every LDS address is
+  // a loop-invariant register plus an immediate offset.
+  unsigned char* const lds_a = lds;
+  unsigned char* const lds_b = lds + 2 * TILE_BYTES;
+
+// Loads of k-tile KT into registers (KT is clamped by the caller, so the loads
+// are unconditional and are issued a whole k-tile ahead of their use).
+#define QZO_GLOAD(KT)                                                                        \
+  do {                                                                                       \
+    const int ko_ = (int)((KT) * (BK * 2));                                                  \
+    ra0 = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[0], ko_, 0);                     \
+    ra1 = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[1], ko_, 0);                     \
+    ra2 = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[2], ko_, 0);                     \
+    ra3 = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[3], ko_, 0);                     \
+    if (W4) {                                                                                \
+      rb0 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[0], (int)((KT) * (BK / 2)), 0); \
+    } else {                                                                                 \
+      rb0 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[0], ko_, 0);                   \
+      rb1 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[1], ko_, 0);                   \
+      rb2 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[2], ko_, 0);                   \
+      rb3 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[3], ko_, 0);                   \
+    }                                                                                        \
+  } while (0)
+
+// New perturbed scale for group G_ (every two k-tiles): s + (sigma*eps)*z as one
+// fp32 fma.  One Philox counter (row, G_/8) serves 8 groups; its four words are
+// kept and each word's Box-Muller pair is evaluated when its even group starts.
+// The stored scale itself was requested a tile earlier (QZO_SCALE_PREFETCH), ahead
+// of that tile's operand loads: memory returns in order, so a scale requested here
+// would make the wavefront wait for every operand load issued before it.
+#define QZO_SCALE_PREFETCH(G_)                                                               \
+  s_next = (bf16_t)__builtin_amdgcn_raw_buffer_load_b16(                                     \
+      rs, (int)so, (int)(min((uint32_t)(G_), (K >> 7) - 1u) * 2u), 0)
+#define QZO_NEW_GROUP(G_)                                                                    \
+  do {                                                                                       \
+    const uint32_t g_ = (G_);                                                                \
+    if ((g_ & 7u) == 0u) {                                                                   \
+      const u32x4_t pw_ = philox4x32_10(a.row_base + gn_w4, g_ >> 3, 0u, 0u, a.seed_lo, a.seed_hi); \
+      zw[0] = pw_.x; zw[1] = pw_.y; zw[2] = pw_.z; zw[3] = pw_.w;                            \
+    }                                                                                        \
+    float zz_ = z_odd;                                                                       \
+    if ((g_ & 1u) == 0u) {                                                                   \
+      const uint32_t p_ = (g_ & 7u) >> 1;                                                    \
+      const uint32_t w_ = p_ == 0 ? zw[0] : (p_ == 1 ? zw[1] : (p_ == 2 ? zw[2] : zw[3]));   \
+      normal_pair(w_, zz_, z_odd);                                                           \
+    }                                                                                        \
+    const float se_ = __builtin_fmaf(a.eps_signed, zz_, bf16_to_f32(s_next));                \
+    se512 = 512.0f * se_;                                                                    \
+    m8se = -8.0f * se_;                                                                      \
+  } while (0)
+
+// Registers -> LDS stage STAGE (compile-time); the int4 tile is unpacked, scaled
+// by the perturbed scale and rounded to bf16 on the way.
+#define QZO_LSTORE(STAGE)                                                                    \
+  do {                                                                                       \
+    *reinterpret_cast<u32x4*>(lds_a + a_lds + (0 * 8192 + (STAGE) * TILE_BYTES)) = ra0;      \
+    *reinterpret_cast<u32x4*>(lds_a + a_lds + (1 * 8192 + (STAGE) * TILE_BYTES)) = ra1;      \
+    *reinterpret_cast<u32x4*>(lds_a + a_lds + (2 * 8192 + (STAGE) * TILE_BYTES)) = ra2;      \
+    *reinterpret_cast<u32x4*>(lds_a + a_lds + (3 * 8192 + (STAGE) * TILE_BYTES)) = ra3;      \
+    if (W4) {                                                                                \
+      *reinterpret_cast<uint4*>(lds_b + b_lds[0] + (STAGE) * TILE_BYTES) = dequant8(rb0.x, se512, m8se); \
+      *reinterpret_cast<uint4*>(lds_b + b_lds[1] + (STAGE) * TILE_BYTES) = dequant8(rb0.y, se512, m8se); \
+      *reinterpret_cast<uint4*>(lds_b + b_lds[2] + (STAGE) * TILE_BYTES) = dequant8(rb0.z, se512, m8se); \
+      *reinterpret_cast<uint4*>(lds_b + b_lds[3] + (STAGE) * TILE_BYTES) = dequant8(rb0.w, se512, m8se); \
+    } else {                                                                                 \
+      *reinterpret_cast<u32x4*>(lds_b + b_lds[0] + (STAGE) * TILE_BYTES) = rb0;              \
+      *reinterpret_cast<u32x4*>(lds_b + b_lds[1] + (STAGE) * TILE_BYTES) = rb1;              \
+      *reinterpret_cast<u32x4*>(lds_b + b_lds[2] + (STAGE) * TILE_BYTES) = rb2;              \
+      *reinterpret_cast<u32x4*>(lds_b + b_lds[3] + (STAGE) * TILE_BYTES) = rb3;              \
+    }                                                                                        \
+  } while (0)
+
+  // acc[i][j]: output features 32 j .. 32 j + 31 (rows of the MFMA result) by
+  // tokens 32 i .. 32 i + 31 (columns) of the wavefront's sub-tile.
+  floatx16 acc[4][2];
+  const uint32_t frow = lane & 31u, fhalf = lane >> 5;
+  // fragment addresses: row base + swizzled chunk of k-step ks (chunk 2 ks + half);
+  // row tiles i / j and the stage are immediate offsets.
+  const uint32_t fsw = (frow >> 1) & 7u;
+  uint32_t fa_k[4], fb_k[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t cid = t + THREADS * i, row = cid >> 3, c = cid & 7u;
-      const uint32_t gn = min(n0 + row, a.N - 1);
-      wb[i] = (const unsigned char*)a.w + ((uint64_t)gn * K + c * 8) * 2;
-      b_lds[i] = lds_off(row, c);
-    }
+  for (int ks = 0; ks < 4; ++ks) {
+    const uint32_t co = ((uint32_t)(ks * 2 + fhalf) ^ fsw) << 4;
+    fa_k[ks] = (wm * 128 + frow) * 128u + co;
+    fb_k[ks] = (wn * 64 + frow) * 128u + co;
   }
 
-  uint4 ra[4], rb[4];
-  float z8[8];
-  float se = 0.0f, m8se = 0.0f;
+  // Fragment sets alternate between two register buffers.  The MFMAs of a tile's
+  // last k-step are issued only after the next barrier, behind the first fragment
+  // reads of the following tile, so the matrix pipe stays fed across the barrier.
+  bf16x8 fa_[2][4], fb_[2][2];
+#define QZO_FRAGS(BUF, KS, STAGE)                                                            \
+  do {                                                                                       \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) fa_[BUF][i] = *reinterpret_cast<const bf16x8*>( \
+        lds_a + fa_k[KS] + (i * 32 * 128 + (STAGE) * TILE_BYTES));                           \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) fb_[BUF][j] = *reinterpret_cast<const bf16x8*>( \
+        lds_b + fb_k[KS] + (j * 32 * 128 + (STAGE) * TILE_BYTES));                           \
+  } while (0)
+#define QZO_MFMA8(BUF)                                                                       \
+  do {                                                                                       \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                            \
+        _Pragma("unroll") for (int j = 0; j < 2; ++j) acc[i][j] =                            \
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb_[BUF][j], fa_[BUF][i], acc[i][j], 0, 0, 0); \
+  } while (0)
+// One k-tile.  LDS executes in order and its stores are several times slower than
+// its loads, so all fragment loads of the tile are issued first; a scheduling
+// fence keeps every LDS store (of the next tile, into STORE_STAGE) behind them,
+// while VALU, MFMA and global loads may move freely across the fence.
+#define QZO_TILE(STAGE, HOLD, STORE_STAGE, NEXT_KT, PREF_G)                                  \
+  do {                                                                                       \
+    QZO_FRAGS(0, 0, STAGE);                                                                  \
+    if (HOLD) QZO_MFMA8(1); /* k-step 3 of the previous tile */                              \
+    QZO_FRAGS(1, 1, STAGE);                                                                  \
+    QZO_MFMA8(0);                                                                            \
+    QZO_FRAGS(0, 2, STAGE);                                                                  \
+    QZO_MFMA8(1);                                                                            \
+    QZO_FRAGS(1, 3, STAGE);                                                                  \
+    __builtin_amdgcn_sched_barrier(0x047F);                                                  \
+    if ((STORE_STAGE) >= 0) {                                                                \
+      QZO_LSTORE((STORE_STAGE) & 1);                                                         \
+      if (W4 && (int)(PREF_G) >= 0) QZO_SCALE_PREFETCH(PREF_G);                              \
+      QZO_GLOAD(NEXT_KT);                                                                    \
+    }                                                                                        \
+    QZO_MFMA8(0);                                                                            \
+  } while (0)
 
-  auto gload = [&](uint32_t kt) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<const uint4*>(xa[i] + (uint64_t)kt * (BK * 2));
-    if (W4) {
-      rb[0] = *reinterpret_cast<const uint4*>(wb[0] + (uint64_t)kt * (BK / 2));
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        rb[i] = *reinterpret_cast<const uint4*>(wb[i] + (uint64_t)kt * (BK * 2));
-    }
-  };
-  auto lstore = [&](uint32_t kt, uint32_t stage) {
-    unsigned char* As = lds + stage * (2 * TILE_BYTES);
-    unsigned char* Bs = As + TILE_BYTES;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(As + a_lds[i]) = ra[i];
-    if (W4) {
-      if ((kt & 1u) == 0u) {             // a new group of 128 starts every two k-tiles
-        const uint32_t g = kt >> 1;
-        if ((g & 7u) == 0u)
-          scale_normals8(a.seed_lo, a.seed_hi, 0u, a.row_base + gn_w4, g >> 3, z8);
-        float zz = z8[0];
-#pragma unroll
-        for (int j = 1; j < 8; ++j) zz = ((g & 7u) == (uint32_t)j) ? z8[j] : zz;
-        se = __builtin_fmaf(a.eps_signed, zz, bf16_to_f32(srow[g]));
-        m8se = -8.0f * se;
-      }
-      const uint32_t w[4] = {rb[0].x, rb[0].y, rb[0].z, rb[0].w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        *reinterpret_cast<uint4*>(Bs + b_lds[j]) = dequant8(w[j], se, m8se);
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(Bs + b_lds[i]) = rb[i];
-    }
-  };
-
-  floatx16 acc[4][2];
+  // K is a multiple of 128, so the number of k-tiles is even.  Tile kt lives in
+  // LDS stage kt & 1; during tile kt the registers loaded one tile earlier (tile
+  // kt+1) go to the other stage and tile kt+2 is requested from memory.
+  const uint32_t nkt = K / BK, last = nkt - 1;
+  QZO_GLOAD(0);
+  for (;;) {
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-  const uint32_t frow = lane & 31u, fhalf = lane >> 5;
-  auto compute = [&](uint32_t stage) {
-    const unsigned char* As = lds + stage * (2 * TILE_BYTES);
-    const unsigned char* Bs = As + TILE_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 fa[4], fb[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8*>(As + lds_off(wm * 128 + i * 32 + frow, ks * 2 + fhalf));
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8*>(Bs + lds_off(wn * 64 + j * 32 + frow, ks * 2 + fhalf));
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-  };
-
-  const uint32_t nkt = K / BK;
-  gload(0);
-  lstore(0, 0);
+  if (W4) {
+    QZO_SCALE_PREFETCH(0u);
+    QZO_NEW_GROUP(0u);
+    QZO_SCALE_PREFETCH(1u);
+  }
+  QZO_LSTORE(0);
+  QZO_GLOAD(1u);
   __syncthreads();
-  for (uint32_t kt = 0; kt < nkt; ++kt) {
-    const uint32_t cur = kt & 1u;
-    if (kt + 1 < nkt) gload(kt + 1);
-    compute(cur);
-    if (kt + 1 < nkt) lstore(kt + 1, cur ^ 1u);
+  QZO_TILE(0, false, 1, min(2u, last), -1);
+  __syncthreads();
+  for (uint32_t kt = 1; kt + 1 < nkt; kt += 2) {
+    if (W4) QZO_NEW_GROUP((kt + 1) >> 1);
+    QZO_TILE(1, true, 0, min(kt + 2, last), -1);
     __syncthreads();
+    QZO_TILE(0, true, 1, min(kt + 3, last), (kt + 3) >> 1);
+    __syncthreads();
+  }
+  QZO_TILE(1, true, -1, 0u, -1);
+  QZO_MFMA8(1);
+
+  // The next tile's first loads are requested before this tile's results are
+  // written, and the stores are not waited for: the epilogue's memory traffic
+  // overlaps the next tile's main loop.
+  const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
+  const uint32_t done_m = tile_m, done_n = tile_n;
+  walk.slot += walk.stride;
+  const bool more = tile_walk_get(walk, tile_m, tile_n);
+  if (more) {
+    QZO_TILE_PTRS(tile_m, tile_n);
+    QZO_GLOAD(0);
   }
 
   // ---- epilogue ----------------------------------------------------------
-  // acc[i][j][r]: row = 32 i + 8 (r/4) + 4 (lane/32) + r%4, col = 32 j + lane%32
-  // of the wavefront's 128x64 sub-tile.
+  // acc[i][j][4 b + c]: token m = 32 i + lane%32, feature n = 32 j + 8 b + 4 (lane/32) + c
+  // of the wavefront's 128 (tokens) x 64 (features) sub-tile.
+  const uint32_t n_wave = n0 + wn * 64 + 4 * fhalf;
   if (!CE) {
     float ssq = 0.0f;
     const bf16_t* bias = (const bf16_t*)a.bias;
     const bf16_t* resid = (const bf16_t*)a.resid;
     bf16_t* y = (bf16_t*)a.y;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const uint32_t n = n0 + wn * 64 + j * 32 + frow;
-      const bool nok = n < a.N;
-      const float bv = ((a.epi & EPI_BIAS) && nok) ? bf16_to_f32(bias[n]) : 0.0f;
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t m = m0 + wm * 128 + i * 32 + frow;
+      if (m < a.M) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const uint32_t m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
-          if (nok && m < a.M) {
-            float v = acc[i][j][r] + bv;
-            const uint64_t o = (uint64_t)m * a.N + n;
-            if (a.epi & EPI_RESIDUAL) v += bf16_to_f32(resid[o]);
-            if (a.epi & EPI_RELU) v = fmaxf(v, 0.0f);
-            const bf16_t b = f32_to_bf16(v);
-            y[o] = b;
-            const float vb = bf16_to_f32(b);
-            ssq = __builtin_fmaf(vb, vb, ssq);
+          for (int b = 0; b < 4; ++b) {
+            const uint32_t n = n_wave + j * 32 + b * 8;      // 4 features n .. n+3 (N % 4 == 0)
+            if (n < a.N) {
+              float v[4];
+#pragma unroll
+              for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * b + c];
+              if (a.epi & EPI_BIAS) {
+                const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
+                v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
+                v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
+              }
+              const uint64_t o = (uint64_t)m * a.N + n;
+              if (a.epi & EPI_RESIDUAL) {
+                const uint2 rr = *reinterpret_cast<const uint2*>(resid + o);
+                v[0] += __uint_as_float(rr.x << 16); v[1] += __uint_as_float(rr.x & 0xffff0000u);
+                v[2] += __uint_as_float(rr.y << 16); v[3] += __uint_as_float(rr.y & 0xffff0000u);
+              }
+              if (a.epi & EPI_RELU) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[c] = fmaxf(v[c], 0.0f);
+              }
+              uint2 out;
+              out.x = pack_bf16x2(v[0], v[1]);
+              out.y = pack_bf16x2(v[2], v[3]);
+              *reinterpret_cast<uint2*>(y + o) = out;
+              if (a.epi & EPI_SUMSQ) {
+                const float q0 = __uint_as_float(out.x << 16), q1 = __uint_as_float(out.x & 0xffff0000u);
+                const float q2 = __uint_as_float(out.y << 16), q3 = __uint_as_float(out.y & 0xffff0000u);
+                ssq = __builtin_fmaf(q0, q0, ssq); ssq = __builtin_fmaf(q1, q1, ssq);
+                ssq = __builtin_fmaf(q2, q2, ssq); ssq = __builtin_fmaf(q3, q3, ssq);
+              }
+            }
           }
-        }
+      }
     }
     if (a.epi & EPI_SUMSQ) {
       float* red = reinterpret_cast<float*>(lds);
       ssq = wave_sum(ssq);
+      __syncthreads();
       if (lane == 0) red[wave] = ssq;
       __syncthreads();
       if (t == 0) {
         float s = 0.0f;
         for (int w = 0; w < THREADS / 64; ++w) s += red[w];
-        a.partials[tile_n * tiles_m + tile_m] = s;
+        a.partials[done_n * tiles_m + done_m] = s;
       }
+      __syncthreads();   // the next tile's LDS stores must not overtake the read of red[]
     }
   } else {
-    // Cross-entropy partials: for each row, (max, sum exp(l - max)) over this
-    // wavefront's 64 columns, and the target logit where it falls here.
-    const uint32_t slice = tile_n * 4 + wn;
+    // Cross-entropy partials: for each token, (max, sum exp(l - max)) over this
+    // wavefront's 64 vocabulary columns (32 in this lane's registers, 32 in the lane
+    // 32 away), and the target logit where it falls here.
+    const uint32_t slice = done_n * 4 + wn;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t m = m0 + wm * 128 + i * 32 + frow;
+      const bool has_target = m < a.M && (m % ce.S) != ce.S - 1;
+      const uint32_t target = has_target ? (uint32_t)ce.tok[m + 1] : 0xffffffffu;
+      float mx = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t m = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
-        const uint32_t c0 = n0 + wn * 64 + frow, c1 = c0 + 32;
-        const float l0 = c0 < a.N ? acc[i][0][r] : -INFINITY;
-        const float l1 = c1 < a.N ? acc[i][1][r] : -INFINITY;
-        float mx = fmaxf(l0, l1);
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-        float sum = 0.0f;
-        if (mx > -INFINITY) sum = expf(l0 - mx) + expf(l1 - mx);
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-        if (m < a.M) {
-          if (frow == 0)
-            reinterpret_cast<float2*>(ce.part)[(uint64_t)m * ce.n_slices + slice] = make_float2(mx, sum);
-          if ((m % ce.S) != ce.S - 1) {
-            const uint32_t target = (uint32_t)ce.tok[m + 1];
-            if (target == c0) ce.tgt[m] = l0;
-            if (target == c1) ce.tgt[m] = l1;
-          }
+        for (int r = 0; r < 16; ++r) {
+          const uint32_t n = n_wave + j * 32 + (r >> 2) * 8 + (r & 3);
+          if (n < a.N) mx = fmaxf(mx, acc[i][j][r]);
+          if (n == target) ce.tgt[m] = acc[i][j][r];
         }
-      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float sum = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const uint32_t n = n_wave + j * 32 + (r >> 2) * 8 + (r & 3);
+          if (n < a.N) sum += expf(acc[i][j][r] - mx);
+        }
+      sum += __shfl_xor(sum, 32, 64);
+      if (m < a.M && fhalf == 0)
+        reinterpret_cast<float2*>(ce.part)[(uint64_t)m * ce.n_slices + slice] = make_float2(mx, sum);
+    }
   }
+  if (!more) break;
+  }   // tile loop
+#undef QZO_TILE
+#undef QZO_MFMA8
+#undef QZO_FRAGS
+#undef QZO_LSTORE
+#undef QZO_NEW_GROUP
+#undef QZO_SCALE_PREFETCH
+#undef QZO_GLOAD
+#undef QZO_TILE_PTRS
 }
 
 static hipError_t set_lds_attr(const void* fn) {
@@ -288,6 +457,9 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
     ready = true;
   }
   if (a.M == 0 || a.N == 0) return hipSuccess;
+  // buffer loads address each operand with 32-bit byte offsets
+  if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
+    return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1};
   gemm_kernel<true, false><<<gemm_workgroups(a.M, a.N), THREADS, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
@@ -300,6 +472,8 @@ hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
     if (e != hipSuccess) return e;
     ready = true;
   }
+  if ((uint64_t)c.M * c.K * 2 >= (1ull << 31) || (uint64_t)c.V * c.K * 2 >= (1ull << 31))
+    return hipErrorInvalidValue;
   GemmArgs a = {};
   a.x = c.x; a.w = c.w; a.M = c.M; a.N = c.V; a.K = c.K;
   CeEpilogue ce = {c.tok, c.part, c.tgt, c.S, c.n_slices};
