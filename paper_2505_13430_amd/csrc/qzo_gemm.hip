@@ -27,7 +27,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int THREADS = 512;
 constexpr int TILE_BYTES = BM * BK * 2;            // 32 KB per operand per stage
 constexpr int LDS_BYTES = 4 * TILE_BYTES;          // A0 A1 B0 B1
 
@@ -109,15 +108,24 @@ struct CeEpilogue {
   uint32_t S, n_slices;
 };
 
-template <bool W4, bool CE>
-__global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue ce) {
+// NWN = wavefronts along N (2 along M): 4 -> 512 threads, each wavefront 128x64;
+// 2 -> 256 threads (one wavefront per SIMD, twice the registers), each 128x128.
+template <bool W4, bool CE, int NWN, bool SCHED>
+__global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilogue ce) {
+  constexpr int THREADS = 128 * NWN;
+  constexpr int TJ = 8 / NWN;                 // 32-wide feature tiles per wavefront
+  constexpr int NA = 2048 / THREADS;          // 16-byte chunks of a 256x64 bf16 tile per thread
+  constexpr int RSTEP = THREADS / 8;          // rows between a thread's consecutive chunks
+  constexpr int TPR = THREADS / 256;          // W4: threads per weight row
+  constexpr int NBQ = 2 / TPR;                // W4: 16-byte loads (32 nibbles) per thread
+  constexpr int NBC = 4 * NBQ;                // W4: bf16 chunks written per thread
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   TileWalk walk = tile_walk_init(a.M, a.N);
   uint32_t tile_m, tile_n;
   if (!tile_walk_get(walk, tile_m, tile_n)) return;
   const uint32_t tiles_m = walk.tiles_m;
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-  const uint32_t wm = wave >> 2, wn = wave & 3u;
+  const uint32_t wm = wave / NWN, wn = wave % NWN;
   const uint32_t K = a.K;
 
   // ---- global -> register staging ---------------------------------------
@@ -134,32 +142,33 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
       0x00020000);
   const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<void*>(W4 ? a.s : a.x), 0, (int)(W4 ? (uint64_t)a.N * (K >> 7) * 2 : 16), 0x00020000);
-  uint32_t xo[4], wo[4], so = 0, gn_w4 = 0;
-  const uint32_t brow = t >> 1, bhalf = t & 1u;
-  // LDS offsets: rows t/8 + 64 i share their swizzle, so chunk i is a_lds + i * 8 KB.
+  uint32_t xo[NA], wo[NA], so = 0, gn_w4 = 0;
+  const uint32_t brow = t / TPR, bpart = t % TPR;
+  // LDS offsets: rows t/8 + RSTEP i share their swizzle, so chunk i is a_lds + i * RSTEP rows.
   const uint32_t a_lds = lds_off(t >> 3, t & 7u);
-  uint32_t b_lds[4];
+  uint32_t b_lds[W4 ? NBC : 1];
+  if (W4) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) b_lds[i] = W4 ? lds_off(brow, bhalf * 4 + i) : a_lds + i * 8192u;
+    for (int c = 0; c < NBC; ++c) b_lds[c] = lds_off(brow, bpart * NBC + c);
+  }
 // Operand offsets of output tile (TM, TN).
 #define QZO_TILE_PTRS(TM, TN)                                                                \
   do {                                                                                       \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                          \
-      const uint32_t row = (t >> 3) + 64u * i, c = t & 7u;                                   \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i) {                                         \
+      const uint32_t row = (t >> 3) + RSTEP * i, c = t & 7u;                                 \
       xo[i] = (min((TM) * BM + row, a.M - 1) * K + c * 8) * 2;                               \
       if (!W4) wo[i] = (min((TN) * BN + row, a.N - 1) * K + c * 8) * 2;                      \
     }                                                                                        \
     if (W4) {                                                                                \
       gn_w4 = min((TN) * BN + brow, a.N - 1);                                                \
-      wo[0] = gn_w4 * (K >> 1) + bhalf * 16;                                                 \
+      wo[0] = gn_w4 * (K >> 1) + bpart * 16;                                                 \
       so = gn_w4 * (K >> 7) * 2;                                                             \
     }                                                                                        \
   } while (0)
   QZO_TILE_PTRS(tile_m, tile_n);
 
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  u32x4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
-  rb1 = rb2 = rb3 = (u32x4){0, 0, 0, 0};
+  u32x4 ra[NA], rb[W4 ? NBQ : NA];
   uint32_t zw[4] = {0, 0, 0, 0};     // Philox words of the current 8 groups
   float z_odd = 0.0f;                // second variate of the current pair
   float se512 = 0.0f, m8se = 0.0f;
@@ -176,17 +185,14 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
 #define QZO_GLOAD(KT)                                                                        \
   do {                                                                                       \
     const int ko_ = (int)((KT) * (BK * 2));                                                  \
-    ra0 = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[0], ko_, 0);                     \
-    ra1 = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[1], ko_, 0);                     \
-    ra2 = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[2], ko_, 0);                     \
-    ra3 = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[3], ko_, 0);                     \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i)                                           \
+        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[i], ko_, 0);               \
     if (W4) {                                                                                \
-      rb0 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[0], (int)((KT) * (BK / 2)), 0); \
+      _Pragma("unroll") for (int q = 0; q < NBQ; ++q) rb[q] = __builtin_amdgcn_raw_buffer_load_b128( \
+          rw, (int)wo[0] + q * 16, (int)((KT) * (BK / 2)), 0);                               \
     } else {                                                                                 \
-      rb0 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[0], ko_, 0);                   \
-      rb1 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[1], ko_, 0);                   \
-      rb2 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[2], ko_, 0);                   \
-      rb3 = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[3], ko_, 0);                   \
+      _Pragma("unroll") for (int i = 0; i < NA; ++i)                                         \
+          rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[i], ko_, 0);             \
     }                                                                                        \
   } while (0)
 
@@ -221,26 +227,24 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
 // by the perturbed scale and rounded to bf16 on the way.
 #define QZO_LSTORE(STAGE)                                                                    \
   do {                                                                                       \
-    *reinterpret_cast<u32x4*>(lds_a + a_lds + (0 * 8192 + (STAGE) * TILE_BYTES)) = ra0;      \
-    *reinterpret_cast<u32x4*>(lds_a + a_lds + (1 * 8192 + (STAGE) * TILE_BYTES)) = ra1;      \
-    *reinterpret_cast<u32x4*>(lds_a + a_lds + (2 * 8192 + (STAGE) * TILE_BYTES)) = ra2;      \
-    *reinterpret_cast<u32x4*>(lds_a + a_lds + (3 * 8192 + (STAGE) * TILE_BYTES)) = ra3;      \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(                \
+        lds_a + a_lds + (i * RSTEP * 128 + (STAGE) * TILE_BYTES)) = ra[i];                   \
     if (W4) {                                                                                \
-      *reinterpret_cast<uint4*>(lds_b + b_lds[0] + (STAGE) * TILE_BYTES) = dequant8(rb0.x, se512, m8se); \
-      *reinterpret_cast<uint4*>(lds_b + b_lds[1] + (STAGE) * TILE_BYTES) = dequant8(rb0.y, se512, m8se); \
-      *reinterpret_cast<uint4*>(lds_b + b_lds[2] + (STAGE) * TILE_BYTES) = dequant8(rb0.z, se512, m8se); \
-      *reinterpret_cast<uint4*>(lds_b + b_lds[3] + (STAGE) * TILE_BYTES) = dequant8(rb0.w, se512, m8se); \
+      _Pragma("unroll") for (int q = 0; q < NBQ; ++q) {                                      \
+        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 0] + (STAGE) * TILE_BYTES) = dequant8(rb[q].x, se512, m8se); \
+        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 1] + (STAGE) * TILE_BYTES) = dequant8(rb[q].y, se512, m8se); \
+        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 2] + (STAGE) * TILE_BYTES) = dequant8(rb[q].z, se512, m8se); \
+        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 3] + (STAGE) * TILE_BYTES) = dequant8(rb[q].w, se512, m8se); \
+      }                                                                                      \
     } else {                                                                                 \
-      *reinterpret_cast<u32x4*>(lds_b + b_lds[0] + (STAGE) * TILE_BYTES) = rb0;              \
-      *reinterpret_cast<u32x4*>(lds_b + b_lds[1] + (STAGE) * TILE_BYTES) = rb1;              \
-      *reinterpret_cast<u32x4*>(lds_b + b_lds[2] + (STAGE) * TILE_BYTES) = rb2;              \
-      *reinterpret_cast<u32x4*>(lds_b + b_lds[3] + (STAGE) * TILE_BYTES) = rb3;              \
+      _Pragma("unroll") for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(              \
+          lds_b + a_lds + (i * RSTEP * 128 + (STAGE) * TILE_BYTES)) = rb[i];                 \
     }                                                                                        \
   } while (0)
 
   // acc[i][j]: output features 32 j .. 32 j + 31 (rows of the MFMA result) by
   // tokens 32 i .. 32 i + 31 (columns) of the wavefront's sub-tile.
-  floatx16 acc[4][2];
+  floatx16 acc[4][TJ];
   const uint32_t frow = lane & 31u, fhalf = lane >> 5;
   // fragment addresses: row base + swizzled chunk of k-step ks (chunk 2 ks + half);
   // row tiles i / j and the stage are immediate offsets.
@@ -250,46 +254,65 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
   for (int ks = 0; ks < 4; ++ks) {
     const uint32_t co = ((uint32_t)(ks * 2 + fhalf) ^ fsw) << 4;
     fa_k[ks] = (wm * 128 + frow) * 128u + co;
-    fb_k[ks] = (wn * 64 + frow) * 128u + co;
+    fb_k[ks] = (wn * (32 * TJ) + frow) * 128u + co;
   }
 
   // Fragment sets alternate between two register buffers.  The MFMAs of a tile's
   // last k-step are issued only after the next barrier, behind the first fragment
   // reads of the following tile, so the matrix pipe stays fed across the barrier.
-  bf16x8 fa_[2][4], fb_[2][2];
+  bf16x8 fa_[2][4], fb_[2][TJ];
 #define QZO_FRAGS(BUF, KS, STAGE)                                                            \
   do {                                                                                       \
     _Pragma("unroll") for (int i = 0; i < 4; ++i) fa_[BUF][i] = *reinterpret_cast<const bf16x8*>( \
         lds_a + fa_k[KS] + (i * 32 * 128 + (STAGE) * TILE_BYTES));                           \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j) fb_[BUF][j] = *reinterpret_cast<const bf16x8*>( \
+    _Pragma("unroll") for (int j = 0; j < TJ; ++j) fb_[BUF][j] = *reinterpret_cast<const bf16x8*>( \
         lds_b + fb_k[KS] + (j * 32 * 128 + (STAGE) * TILE_BYTES));                           \
   } while (0)
-#define QZO_MFMA8(BUF)                                                                       \
+#define QZO_MFMAS(BUF)                                                                       \
   do {                                                                                       \
     _Pragma("unroll") for (int i = 0; i < 4; ++i)                                            \
-        _Pragma("unroll") for (int j = 0; j < 2; ++j) acc[i][j] =                            \
+        _Pragma("unroll") for (int j = 0; j < TJ; ++j) acc[i][j] =                           \
             __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb_[BUF][j], fa_[BUF][i], acc[i][j], 0, 0, 0); \
   } while (0)
-// One k-tile.  LDS executes in order and its stores are several times slower than
-// its loads, so all fragment loads of the tile are issued first; a scheduling
-// fence keeps every LDS store (of the next tile, into STORE_STAGE) behind them,
-// while VALU, MFMA and global loads may move freely across the fence.
+// One k-tile.  Source order: the four fragment loads, each a k-step ahead of the
+// MFMAs that use it; the MFMAs; the conversion and LDS stores of the next tile;
+// the global loads of the tile after that.  QZO_SCHED then fixes the issue order
+// inside the block: every MFMA is followed by a few conversion VALU operations,
+// the LDS stores are spread over the first three k-steps (they are several times
+// slower than LDS loads, the LDS executes in order and the barrier must wait for
+// them, so they may neither bunch up in front of the fragment loads nor sit at
+// the end), and the global loads go behind the last k-step's MFMAs.
 #define QZO_TILE(STAGE, HOLD, STORE_STAGE, NEXT_KT, PREF_G)                                  \
   do {                                                                                       \
     QZO_FRAGS(0, 0, STAGE);                                                                  \
-    if (HOLD) QZO_MFMA8(1); /* k-step 3 of the previous tile */                              \
+    if (HOLD) QZO_MFMAS(1); /* k-step 3 of the previous tile */                              \
     QZO_FRAGS(1, 1, STAGE);                                                                  \
-    QZO_MFMA8(0);                                                                            \
+    QZO_MFMAS(0);                                                                            \
     QZO_FRAGS(0, 2, STAGE);                                                                  \
-    QZO_MFMA8(1);                                                                            \
+    QZO_MFMAS(1);                                                                            \
     QZO_FRAGS(1, 3, STAGE);                                                                  \
-    __builtin_amdgcn_sched_barrier(0x047F);                                                  \
     if ((STORE_STAGE) >= 0) {                                                                \
       QZO_LSTORE((STORE_STAGE) & 1);                                                         \
       if (W4 && (int)(PREF_G) >= 0) QZO_SCALE_PREFETCH(PREF_G);                              \
       QZO_GLOAD(NEXT_KT);                                                                    \
     }                                                                                        \
-    QZO_MFMA8(0);                                                                            \
+    QZO_MFMAS(0);                                                                            \
+    if (SCHED) {                                                                             \
+      constexpr int MPK = 4 * TJ, RPK = 4 + TJ;                                              \
+      __builtin_amdgcn_sched_group_barrier(0x100, RPK, 0);                                   \
+      _Pragma("unroll") for (int g_ = (HOLD) ? 0 : 1; g_ < 3; ++g_) {                        \
+        _Pragma("unroll") for (int m_ = 0; m_ < MPK; ++m_) {                                 \
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                 \
+          __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);                                 \
+          if ((g_ * MPK + m_) % 3 == 2) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   \
+        }                                                                                    \
+        __builtin_amdgcn_sched_group_barrier(0x100, RPK, 0);                                 \
+      }                                                                                      \
+      _Pragma("unroll") for (int m_ = 0; m_ < MPK; ++m_) {                                   \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                   \
+      }                                                                                      \
+    }                                                                                        \
   } while (0)
 
   // K is a multiple of 128, so the number of k-tiles is even.  Tile kt lives in
@@ -301,7 +324,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
   if (W4) {
@@ -322,7 +345,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
     __syncthreads();
   }
   QZO_TILE(1, true, -1, 0u, -1);
-  QZO_MFMA8(1);
+  QZO_MFMAS(1);
 
   // The next tile's first loads are requested before this tile's results are
   // written, and the stores are not waited for: the epilogue's memory traffic
@@ -339,7 +362,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
   // ---- epilogue ----------------------------------------------------------
   // acc[i][j][4 b + c]: token m = 32 i + lane%32, feature n = 32 j + 8 b + 4 (lane/32) + c
   // of the wavefront's 128 (tokens) x 64 (features) sub-tile.
-  const uint32_t n_wave = n0 + wn * 64 + 4 * fhalf;
+  const uint32_t n_wave = n0 + wn * (32 * TJ) + 4 * fhalf;
   if (!CE) {
     float ssq = 0.0f;
     const bf16_t* bias = (const bf16_t*)a.bias;
@@ -350,7 +373,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
       const uint32_t m = m0 + wm * 128 + i * 32 + frow;
       if (m < a.M) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TJ; ++j)
 #pragma unroll
           for (int b = 0; b < 4; ++b) {
             const uint32_t n = n_wave + j * 32 + b * 8;      // 4 features n .. n+3 (N % 4 == 0)
@@ -404,7 +427,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
     // Cross-entropy partials: for each token, (max, sum exp(l - max)) over this
     // wavefront's 64 vocabulary columns (32 in this lane's registers, 32 in the lane
     // 32 away), and the target logit where it falls here.
-    const uint32_t slice = done_n * 4 + wn;
+    const uint32_t slice = done_n * NWN + wn;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t m = m0 + wm * 128 + i * 32 + frow;
@@ -412,7 +435,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
       const uint32_t target = has_target ? (uint32_t)ce.tok[m + 1] : 0xffffffffu;
       float mx = -INFINITY;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TJ; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const uint32_t n = n_wave + j * 32 + (r >> 2) * 8 + (r & 3);
@@ -422,7 +445,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       float sum = 0.0f;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TJ; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const uint32_t n = n_wave + j * 32 + (r >> 2) * 8 + (r & 3);
@@ -436,7 +459,7 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_kernel(GemmArgs a, CeEpilogue
   if (!more) break;
   }   // tile loop
 #undef QZO_TILE
-#undef QZO_MFMA8
+#undef QZO_MFMAS
 #undef QZO_FRAGS
 #undef QZO_LSTORE
 #undef QZO_NEW_GROUP
@@ -449,10 +472,17 @@ static hipError_t set_lds_attr(const void* fn) {
   return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
 }
 
+// Launch configuration of the perturbed W4A16 GEMM.  Measured on MI355X at the
+// Llama-2-7B layer shapes (M = 8192): 4 wavefronts along N (512 threads, two per
+// SIMD) with the explicit issue order is the fastest; 2 along N (256 threads, one
+// per SIMD, 128x128 per wavefront) is about 10 % slower.
+constexpr int W4_NWN = 4;
+constexpr bool W4_SCHED = true;
+
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = set_lds_attr((const void*)gemm_kernel<true, false>);
+    hipError_t e = set_lds_attr((const void*)gemm_kernel<true, false, W4_NWN, W4_SCHED>);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -461,14 +491,15 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1};
-  gemm_kernel<true, false><<<gemm_workgroups(a.M, a.N), THREADS, LDS_BYTES, st>>>(a, ce);
+  gemm_kernel<true, false, W4_NWN, W4_SCHED>
+      <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
 }
 
 hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = set_lds_attr((const void*)gemm_kernel<false, true>);
+    hipError_t e = set_lds_attr((const void*)gemm_kernel<false, true, 4, false>);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -477,7 +508,7 @@ hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   GemmArgs a = {};
   a.x = c.x; a.w = c.w; a.M = c.M; a.N = c.V; a.K = c.K;
   CeEpilogue ce = {c.tok, c.part, c.tgt, c.S, c.n_slices};
-  gemm_kernel<false, true><<<gemm_workgroups(c.M, c.V), THREADS, LDS_BYTES, st>>>(a, ce);
+  gemm_kernel<false, true, 4, false><<<gemm_workgroups(c.M, c.V), 512, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
 }
 
