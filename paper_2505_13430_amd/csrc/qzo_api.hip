@@ -132,7 +132,7 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   w.a = take(M * d * 2);
   w.qkv = take(M * 3 * d * 2);
   w.att = take(M * d * 2);
-  w.ff = take(M * (c.arch == 0 ? 2 * F : F) * 2);
+  w.ff = take(c.arch == 0 ? 0 : M * F * 2);     // Llama: SwiGLU is folded into the gate/up GEMM
   w.act = take(c.arch == 0 ? M * F * 2 : 0);
   w.ce_part = (float*)take(M * n_slices * 8);
   w.tgt = (float*)take(M * 4);
@@ -222,8 +222,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
       }
       QZO_HIP(gemm(1, w.att, T[2].ptr_dev, nullptr, w.h, w.h, EPI_RESIDUAL));
       QZO_HIP(launch_rmsnorm(w.h, T[3].ptr_dev, M, d, c.norm_eps, w.a, st));
-      QZO_HIP(gemm(2, w.a, T[4].ptr_dev, nullptr, nullptr, w.ff, 0));
-      QZO_HIP(launch_swiglu(w.ff, M, F, w.act, st));
+      QZO_HIP(gemm(2, w.a, T[4].ptr_dev, nullptr, nullptr, w.act, EPI_SWIGLU));
       QZO_HIP(gemm(3, w.act, T[5].ptr_dev, nullptr, w.h, w.h, EPI_RESIDUAL));
     } else {
       // ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, wfc1, bfc1, wfc2, bfc2

@@ -160,7 +160,11 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       if (!W4) wo[i] = (min((TN) * BN + row, a.N - 1) * K + c * 8) * 2;                      \
     }                                                                                        \
     if (W4) {                                                                                \
-      gn_w4 = min((TN) * BN + brow, a.N - 1);                                                \
+      /* fused SwiGLU: the tile's rows are 4 x (32 gate rows, 32 up rows of the same   */      \
+      /* features), so a lane's two accumulators hold gate and up of one feature      */      \
+      gn_w4 = (a.epi & EPI_SWIGLU)                                                           \
+                  ? ((brow >> 5) & 1u) * (a.N >> 1) + (TN) * 128u + (brow >> 6) * 32u + (brow & 31u) \
+                  : min((TN) * BN + brow, a.N - 1);                                          \
       wo[0] = gn_w4 * (K >> 1) + bpart * 16;                                                 \
       so = gn_w4 * (K >> 7) * 2;                                                             \
     }                                                                                        \
@@ -363,7 +367,32 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // acc[i][j][4 b + c]: token m = 32 i + lane%32, feature n = 32 j + 8 b + 4 (lane/32) + c
   // of the wavefront's 128 (tokens) x 64 (features) sub-tile.
   const uint32_t n_wave = n0 + wn * (32 * TJ) + 4 * fhalf;
-  if (!CE) {
+  if (!CE && TJ == 2 && (a.epi & EPI_SWIGLU)) {
+    // y[m, f] = silu(gate) * up, f = 128 tile_n + 32 wn + 8 b + 4 (lane/32) + c; y is [M, N/2]
+    bf16_t* y = (bf16_t*)a.y;
+    const uint32_t F = a.N >> 1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t m = m0 + wm * 128 + i * 32 + frow;
+      if (m < a.M) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const uint32_t f = done_n * 128u + wn * 32u + b * 8u + 4u * fhalf;
+          float v[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const float g = acc[i][0][4 * b + c];
+            v[c] = g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * g)) *
+                   acc[i][TJ - 1][4 * b + c];
+          }
+          uint2 out;
+          out.x = pack_bf16x2(v[0], v[1]);
+          out.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>(y + (uint64_t)m * F + f) = out;
+        }
+      }
+    }
+  } else if (!CE) {
     float ssq = 0.0f;
     const bf16_t* bias = (const bf16_t*)a.bias;
     const bf16_t* resid = (const bf16_t*)a.resid;

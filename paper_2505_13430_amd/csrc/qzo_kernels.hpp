@@ -29,6 +29,7 @@ enum : uint32_t {
   EPI_RESIDUAL = 2u,   // y = resid[m,n] + acc
   EPI_RELU = 4u,
   EPI_SUMSQ = 8u,      // per-workgroup sum of bf16(y)^2 into partials
+  EPI_SWIGLU = 16u,    // W is [gate rows | up rows] (N = 2F): y[M,F] = silu(gate) * up
 };
 
 struct GemmArgs {
