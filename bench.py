@@ -65,6 +65,44 @@ def cpu_baseline(shape, tokens_sample=384):
                       f"extrapolated x{L} layers x2 passes; attention/norms omitted"}
 
 
+def measured_traffic(key):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "w4a16_gemm_and_update_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith(key + ":"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def probe(torch, qb):
+    """Launches whose HBM counters calibrate and measure traffic: a plain copy of known
+    size (256 MiB read + 256 MiB written), the perturbed GEMM at the Llama-2-7B qkv shape
+    (M 8192, N 12288, K 4096) and the scale update over 50,593,792 scales."""
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    src = torch.randint(0, 256, (256 << 20,), generator=g, device=dev, dtype=torch.uint8)
+    dst = torch.empty_like(src)
+    M, N, K = 8192, 12288, 4096
+    x = torch.randn(M, K, generator=g, device=dev).to(torch.bfloat16)
+    q = torch.randint(0, 256, (N, K // 2), generator=g, device=dev, dtype=torch.uint8)
+    s = (torch.rand(N, K // 128, generator=g, device=dev) * 0.015 + 0.005).to(torch.bfloat16)
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=dev)
+    arena = (torch.rand(1581056, 32, generator=g, device=dev) * 0.01 + 0.003).to(torch.bfloat16)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        qb.qzo_dequant_gemm(x, q, s, 0, 7, 1e-3, 1, y)
+        torch.cuda.synchronize()
+        qb.qzo_apply_update(arena, 0, 7, 1e-7, 10.0)
+        torch.cuda.synchronize()
+    print(json.dumps({"probe": "copy 2x268435456 B, gemm 8192x12288x4096, update 50593792 scales"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,6 +110,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama-2-7b")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--probe", action="store_true",
+                    help="counter probe: a plain 256 MiB copy, the qkv-shaped W4A16 GEMM and the "
+                         "7B-sized scale update, three launches each (for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1",
@@ -83,6 +124,9 @@ def main():
     from paper_2505_13430_amd import synth
     from paper_2505_13430_amd.model import DeviceModel
 
+    if args.probe:
+        probe(torch, qb)
+        return
     shape = synth.SHAPES[args.workload]
     B, S = shape["batch"], shape["seq"]
     torch.cuda.set_device(0)
@@ -128,7 +172,10 @@ def main():
         "last_step": res,
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel<W4=true> (perturbed W4A16 GEMM)",
                      "achieved": gemm_flops_s / 1e12, "peak": PEAK_BF16_MFMA / 1e12,
-                     "unit": "TFLOP/s", "frac": gemm_flops_s / PEAK_BF16_MFMA, "traffic": None,
+                     "unit": "TFLOP/s", "frac": gemm_flops_s / PEAK_BF16_MFMA,
+                     "traffic": measured_traffic("traffic_bytes_per_launch_gemm_qkv"),
+                     "traffic_note": "HBM bytes of one qkv-shaped launch (8192x12288x4096), FETCH_SIZE + "
+                                     "WRITE_SIZE scaled by a plain copy; algorithmic 2.93e8",
                      "launches": g["launches"], "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
                      "flops_per_launch_avg": g["work"] / max(g["launches"], 1)},
         "kernels": {
@@ -137,7 +184,8 @@ def main():
         "scale_update": {"bound": "hbm", "achieved": upd_bytes_s / 1e9, "peak": PEAK_HBM / 1e9,
                          "unit": "GB/s", "frac": upd_bytes_s / PEAK_HBM,
                          "avg_launch_ms": u["total_ms"] / max(u["launches"], 1),
-                         "bytes_per_launch": u["work"] / max(u["launches"], 1)},
+                         "bytes_per_launch": u["work"] / max(u["launches"], 1),
+                         "traffic": measured_traffic("traffic_bytes_per_launch_scale_update")},
         "device_memory_GiB": torch.cuda.max_memory_allocated() / 2 ** 30,
     }
     dm.close()
