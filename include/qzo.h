@@ -60,7 +60,9 @@ typedef struct {
                            1: OPT family (LayerNorm, learned positions, ReLU, biases) */
   uint32_t n_layers, d_model, n_heads, d_ffn, vocab, max_seq;
   uint32_t group_size;  /* 128 */
-  uint32_t quant;       /* 0: int4 + per-group bf16 scales */
+  uint32_t quant;       /* 0: int4 + per-group bf16 scales
+                           1: codebook (Llama only): one uint16 code per 8 weights into a per-linear
+                              fp16 [65536,8] codebook, fp16 per-output-channel scales */
   float norm_eps;       /* 1e-5 */
   float rope_theta;     /* 10000 (Llama only) */
 } qzo_model_config;
@@ -88,6 +90,9 @@ typedef struct {
  *          wqkv int4[3d,d/2], bqkv bf16[3d], wo int4[d,d/2], bo bf16[d], ln2_g, ln2_b,
  *          wfc1 int4[F,d/2], bfc1 bf16[F], wfc2 int4[d,F/2], bfc2 bf16[d] };
  *          lnf_g, lnf_b; lm_head bf16[V,d].
+ *   Llama, quant = 1: per layer { attn_norm, codes_qkv uint16[3d,d/8], cb_qkv fp16[65536,8],
+ *          codes_o, cb_o, ffn_norm, codes_gu [2F,d/8], cb_gu, codes_down [d,F/8], cb_down };
+ *          the arena then holds one fp16 scale per output row, per layer [3d][d][2F][d].
  * `scale_arena_dev` holds every quantized linear's bf16 scales back to back in
  * the same order ([N, K/128] each); it is the only model memory the library
  * writes.  Only the decoder-block linears are quantized and trained (their
@@ -151,6 +156,23 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
                             uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,
                             uint32_t group, uint64_t seed, float eps, int sign, void* y_dev,
                             float* sumsq_dev, void* stream);
+
+/*
+ * Codebook variant of the perturbed linear (the paper's 2-bit setting, Sec. 3.2.1 last
+ * paragraph / Sec. 4.1: 1 codebook of 16 bits, channel-wise scales trained by QZO):
+ *   W[n,k] = c[n] * CB[codes[n,k/8]][k%8],  Y = (X * (CB-weights)^T) * diag(c + sign*eps*z)
+ * with z(row_base + n) from the flat noise stream 1 (counter ((row_base+n)/8, 0, 1, 0)).
+ * x_dev bf16 [M,K]; codes_dev uint16 [N,K/8]; codebook_dev fp16 [65536,8]; c_dev fp16 [N];
+ * y_dev bf16 [M,N]; sumsq_dev as in qzo_dequant_gemm.  K % 128 == 0, N % 8 == 0.  Codebook
+ * entries are rounded to bf16 for the MFMA; the scale multiplies the fp32 accumulators.
+ */
+qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const void* codebook_dev,
+                             const void* c_dev, uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,
+                             uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
+                             void* stream);
+/* c_n <- max(c_n - eta*d'*z_n, 0) on fp16 channel scales c_dev[n_rows], round-to-nearest-even. */
+qzo_status qzo_apply_update_channel(void* c_dev, uint32_t n_rows, uint32_t row_base, uint64_t seed,
+                                    float eta, float d_clipped, void* stream);
 
 /* The update loop of Algorithm 1 on one tensor's scales: s_dev bf16 [n_rows, G],
  * updated in place with c = eta*d_clipped. */

@@ -205,7 +205,7 @@ class _Cfg(C.Structure):
     _fields_ = [("arch", C.c_uint32), ("n_layers", C.c_uint32), ("d_model", C.c_uint32),
                 ("n_heads", C.c_uint32), ("d_ffn", C.c_uint32), ("vocab", C.c_uint32),
                 ("max_seq", C.c_uint32), ("group", C.c_uint32),
-                ("norm_eps", C.c_double), ("rope_theta", C.c_double)]
+                ("norm_eps", C.c_double), ("rope_theta", C.c_double), ("quant", C.c_uint32)]
 
 
 @dataclass
@@ -226,6 +226,7 @@ class Model:
     scales: np.ndarray       # flat fp32 arena of bf16-valued scales
     segments: list = field(default_factory=list)
     group: int = 128
+    quant: int = 0           # 0: int4 + group scales; 1: codebook + per-channel scales
 
     @property
     def n_rows(self):
@@ -252,9 +253,63 @@ def build_model(shape: dict, table, group=128) -> Model:
     return Model(shape, tensors, names, np.concatenate(scales).astype(np.float32), segs, group)
 
 
+def fp16_rne(x):
+    a = _f32(x).copy()
+    lib().orc_fp16_rne_array(_p(a), C.c_uint64(a.size))
+    return a
+
+
+def codebook_linear(x, idx, cb, c_eff, bias=None):
+    x = _f64(x)
+    idx = np.ascontiguousarray(idx, dtype=np.uint16)
+    cb = _f32(cb)
+    c_eff = _f64(c_eff)
+    M, K = x.shape
+    N = idx.shape[0]
+    y = np.zeros((M, N), dtype=np.float64)
+    b = _f32(bias) if bias is not None else None
+    lib().orc_codebook_linear(_p(x), C.c_uint64(M), C.c_uint64(K), _p(idx), _p(cb), _p(c_eff),
+                              C.c_uint64(N), _p(b) if b is not None else None, _p(y))
+    return y
+
+
+def channel_effective_scales(c, row_base, seed, eps_signed):
+    c = _f32(c).reshape(-1)
+    out = np.zeros(c.size, dtype=np.float64)
+    lib().orc_channel_effective_scales(_p(c), C.c_uint32(c.size), C.c_uint32(row_base),
+                                       C.c_uint64(seed), C.c_float(eps_signed), _p(out))
+    return out
+
+
+def update_channel_scales(c, row_base, seed, eta, d_clipped):
+    c = _f32(c).reshape(-1).copy()
+    lib().orc_update_channel_scales(_p(c), C.c_uint32(c.size), C.c_uint32(row_base), C.c_uint64(seed),
+                                    C.c_float(eta), C.c_float(d_clipped))
+    return c
+
+
+def build_codebook_model(shape: dict, table) -> Model:
+    """table entries: (name, 'bf16', array) | (name, 'codes', u16 [N,K/8]) |
+    (name, 'codebook', fp32 [65536,8] holding fp16 values) | (name, 'chscale', fp32 [N])."""
+    tensors, names, segs, scales = [], [], [], []
+    off = 0
+    for name, kind, arr in table:
+        if kind == "chscale":
+            n = arr.size
+            segs.append(Segment(name, off, n, 1, off))
+            scales.append(_f32(arr).reshape(-1))
+            off += n
+            continue
+        tensors.append(np.ascontiguousarray(arr, dtype=np.uint16) if kind == "codes" else _f32(arr))
+        names.append(name)
+    return Model(shape, tensors, names, np.concatenate(scales).astype(np.float32), segs, 128, 1)
+
+
 def perturbed_scales(model: Model, seed: int, eps_signed: float, scales=None) -> np.ndarray:
     """Delta + (sigma*eps) z over the whole arena (PERTURB_SCALES, functional form)."""
     sc = model.scales if scales is None else scales
+    if model.quant == 1:
+        return channel_effective_scales(sc, 0, seed, eps_signed)
     out = np.zeros(sc.size, dtype=np.float64)
     for sg in model.segments:
         sl = slice(sg.offset, sg.offset + sg.rows * sg.G)
@@ -267,7 +322,7 @@ def forward_loss(model: Model, s_eff, tok, act_bf16=True, want_hidden=False, wan
     sh = model.shape
     cfg = _Cfg(0 if sh["arch"] == "llama" else 1, sh["n_layers"], sh["d_model"], sh["n_heads"],
                sh["d_ffn"], sh["vocab"], sh["max_seq"], model.group,
-               sh.get("norm_eps", 1e-5), sh.get("rope_theta", 10000.0))
+               sh.get("norm_eps", 1e-5), sh.get("rope_theta", 10000.0), model.quant)
     tok = np.ascontiguousarray(tok, dtype=np.int32)
     B, S = tok.shape
     s_eff = _f64(s_eff)
@@ -292,6 +347,8 @@ def clip(d, Cthr):
 
 def update_scales(model: Model, seed: int, eta: float, d_clipped: float, scales=None) -> np.ndarray:
     """Returns the updated arena (Algorithm 1's update loop); input untouched."""
+    if model.quant == 1:
+        return update_channel_scales(model.scales if scales is None else scales, 0, seed, eta, d_clipped)
     sc = (model.scales if scales is None else scales).astype(np.float32).copy()
     for sg in model.segments:
         view = sc[sg.offset:sg.offset + sg.rows * sg.G]

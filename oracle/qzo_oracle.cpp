@@ -48,6 +48,24 @@ inline float bf16_rne(float f) {
   u &= 0xffff0000u;
   return u2f(u);
 }
+// Round-to-nearest-even of an fp32 value to the nearest IEEE binary16 value
+// (returned as fp32), subnormals and overflow to infinity included.
+inline float fp16_rne(float f) {
+  uint32_t u = f2u(f);
+  uint32_t sign = u & 0x80000000u;
+  uint32_t mag = u & 0x7fffffffu;
+  if (mag >= 0x7f800000u) return f;                       // inf / nan
+  if (mag >= 0x477ff000u) return u2f(sign | 0x7f800000u); // >= 65520 rounds to inf
+  if (mag < 0x38800000u) {                                // below 2^-14: subnormal half, step 2^-24
+    float a = u2f(mag);
+    float r = (a + 0x1p-1f) - 0x1p-1f;                    // rounds a to a multiple of 2^-24 (RNE) exactly
+    return u2f(sign | f2u(r));
+  }
+  uint32_t lsb = (mag >> 13) & 1u;
+  mag += 0xfffu + lsb;
+  mag &= 0xffffe000u;
+  return u2f(sign | mag);
+}
 inline double round_act(double v, int act_bf16) {
   return act_bf16 ? (double)bf16_rne((float)v) : v;
 }
@@ -406,11 +424,54 @@ double orc_next_token_ce(const double* logits, const int32_t* tok, uint64_t B, u
   return total / (double)(B * (S - 1));
 }
 
+// ------------------------------------------- codebook-quantized linear ----
+// Codebook variant (the paper's 2-bit setting: one 16-bit code per 8 weights, one
+// codebook of 65536 8-vectors per linear, a per-output-channel scale that Q-SPSA
+// perturbs and updates): W[n,k] = c[n] * CB[idx[n,k/8]][k%8], so
+// Y[m,n] = c_eff[n] * sum_k X[m,k] CB[idx[n,k/8]][k%8] (+ bias[n]).
+float orc_fp16_rne(float f) { return fp16_rne(f); }
+void orc_fp16_rne_array(float* x, uint64_t n) {
+  for (uint64_t i = 0; i < n; ++i) x[i] = fp16_rne(x[i]);
+}
+void orc_codebook_linear(const double* x, uint64_t M, uint64_t K, const uint16_t* idx,
+                         const float* cb, const double* c_eff, uint64_t N, const float* bias,
+                         double* y) {
+  const uint64_t KB = K / 8;
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < (int64_t)N; ++n) {
+    std::vector<double> wrow(K);
+    for (uint64_t k = 0; k < K; ++k) wrow[k] = (double)cb[(uint64_t)idx[n * KB + k / 8] * 8 + (k & 7)];
+    for (uint64_t m = 0; m < M; ++m) {
+      double acc = 0.0;
+      const double* xr = x + m * K;
+      for (uint64_t k = 0; k < K; ++k) acc += xr[k] * wrow[k];
+      y[m * N + n] = acc * c_eff[n] + (bias ? (double)bias[n] : 0.0);
+    }
+  }
+}
+// c_eff[n] = c[n] + (sigma*eps) * z(row_base + n) as one fp32 fma; z from the flat
+// counter stream 1 (one Philox counter per 8 channels).
+void orc_channel_effective_scales(const float* c, uint32_t n_rows, uint32_t row_base,
+                                  uint64_t seed, float eps_signed, double* out) {
+  for (uint32_t r = 0; r < n_rows; ++r)
+    out[r] = (double)std::fmaf(eps_signed, flat_normal(seed, 1u, (uint64_t)row_base + r), c[r]);
+}
+// c_n <- max(c_n - eta*d'*z_n, 0), fp16 storage (Algorithm 1's update on channel scales).
+void orc_update_channel_scales(float* c, uint32_t n_rows, uint32_t row_base, uint64_t seed,
+                               float eta, float d_clipped) {
+  const float cstep = eta * d_clipped;
+  for (uint32_t r = 0; r < n_rows; ++r) {
+    float z = flat_normal(seed, 1u, (uint64_t)row_base + r);
+    c[r] = fp16_rne(std::max(std::fmaf(-cstep, z, c[r]), 0.0f));
+  }
+}
+
 // ----------------------------------------------------- model forward -----
 struct orc_config {
   uint32_t arch;        // 0 = Llama family (RMSNorm, RoPE, SwiGLU, no bias), 1 = OPT family
   uint32_t n_layers, d_model, n_heads, d_ffn, vocab, max_seq, group;
   double norm_eps, rope_theta;
+  uint32_t quant;       // 0 = int4 + per-group scales, 1 = codebook + per-channel scales (Llama only)
 };
 
 // Tensor table, in this order (all fp32 arrays holding bf16 values unless noted):
@@ -420,6 +481,9 @@ struct orc_config {
 //  OPT:   tok_emb[V,d]; pos_emb[max_seq,d]; per layer { ln1_g[d], ln1_b[d], wqkv(u8), bqkv[3d],
 //         wo(u8), bo[d], ln2_g[d], ln2_b[d], wfc1(u8 [F,d/2]), bfc1[F], wfc2(u8 [d,F/2]),
 //         bfc2[d] }; lnf_g[d], lnf_b[d]; lm_head[V,d].
+//  Llama, quant = 1: every quantized weight is two entries, the codes (u16 [N,K/8]) followed by
+//         the codebook (fp32 holding fp16 values, [65536,8]); s_eff then holds one effective
+//         scale per output row, per layer [3d][d][2F][d].
 // s_eff: effective scales (double) in arena order: per layer [qkv: 3d x d/group]
 // [o: d x d/group][gu or fc1: (2F or F) x d/group][down or fc2: d x F/group].
 // Returns the loss L(Delta (.) theta_bar; B) of Algorithm 1.  Optional outputs
@@ -449,7 +513,29 @@ double orc_forward_loss(const orc_config* c, const void* const* T, const double*
     if (act_bf16) for (auto& v : x) v = (double)bf16_rne((float)v);
   };
   for (uint32_t l = 0; l < c->n_layers; ++l) {
-    if (llama) {
+    if (llama && c->quant == 1) {
+      const float* n1 = (const float*)T[ti++];
+      const uint16_t* iqkv = (const uint16_t*)T[ti++]; const float* cqkv = (const float*)T[ti++];
+      const uint16_t* io = (const uint16_t*)T[ti++]; const float* co = (const float*)T[ti++];
+      const float* n2 = (const float*)T[ti++];
+      const uint16_t* igu = (const uint16_t*)T[ti++]; const float* cgu = (const float*)T[ti++];
+      const uint16_t* idn = (const uint16_t*)T[ti++]; const float* cdn = (const float*)T[ti++];
+      orc_rmsnorm(h.data(), M, d, n1, c->norm_eps, a.data()); round_all(a);
+      orc_codebook_linear(a.data(), M, d, iqkv, cqkv, se, 3 * d, nullptr, qkv.data()); se += 3 * d;
+      round_all(qkv);
+      orc_rope(qkv.data(), B, S, 3 * d, 0, H, dh, c->rope_theta);
+      orc_rope(qkv.data(), B, S, 3 * d, d, H, dh, c->rope_theta);
+      round_all(qkv);
+      orc_attention(qkv.data(), B, S, H, dh, att.data()); round_all(att);
+      orc_codebook_linear(att.data(), M, d, io, co, se, d, nullptr, lin.data()); se += d;
+      for (uint64_t i = 0; i < M * d; ++i) h[i] = round_act(h[i] + lin[i], act_bf16);
+      orc_rmsnorm(h.data(), M, d, n2, c->norm_eps, a.data()); round_all(a);
+      orc_codebook_linear(a.data(), M, d, igu, cgu, se, 2 * F, nullptr, ff.data()); se += 2 * F;
+      round_all(ff);
+      orc_swiglu(ff.data(), M, F, act.data()); round_all(act);
+      orc_codebook_linear(act.data(), M, F, idn, cdn, se, d, nullptr, lin.data()); se += d;
+      for (uint64_t i = 0; i < M * d; ++i) h[i] = round_act(h[i] + lin[i], act_bf16);
+    } else if (llama) {
       const float* n1 = (const float*)T[ti++];
       const uint8_t* wqkv = (const uint8_t*)T[ti++];
       const uint8_t* wo = (const uint8_t*)T[ti++];

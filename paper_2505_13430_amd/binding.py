@@ -23,7 +23,7 @@ QZO_ERR_NONFINITE, QZO_ERR_HIP, QZO_ERR_UNSUPPORTED = -5, -6, -7
 EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
-    "qzo_apply_update", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
+    "qzo_apply_update", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
     "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_profile_begin", "qzo_profile_collect",
     "qzo_last_error",
 ]
@@ -79,7 +79,7 @@ def _stream(stream):
 def make_config(shape: dict) -> qzo_model_config:
     return qzo_model_config(C.sizeof(qzo_model_config), 0 if shape["arch"] == "llama" else 1,
                             shape["n_layers"], shape["d_model"], shape["n_heads"], shape["d_ffn"],
-                            shape["vocab"], shape["max_seq"], shape.get("group", 128), 0,
+                            shape["vocab"], shape["max_seq"], shape.get("group", 128), shape.get("quant", 0),
                             shape.get("norm_eps", 1e-5), shape.get("rope_theta", 10000.0))
 
 
@@ -205,3 +205,17 @@ def qzo_profile_collect(kind: int) -> dict:
     ms, n, work = C.c_double(0), C.c_uint64(0), C.c_double(0)
     _check(lib().qzo_profile_collect(C.c_uint32(kind), C.byref(ms), C.byref(n), C.byref(work)))
     return dict(total_ms=ms.value, launches=n.value, work=work.value)
+
+
+def qzo_codebook_gemm(x, codes, codebook, c, row_base, seed, eps, sign, y, sumsq=None, stream=None):
+    M, K = x.shape
+    N = codes.shape[0]
+    _check(lib().qzo_codebook_gemm(_ptr(x), _ptr(codes), _ptr(codebook), _ptr(c), C.c_uint32(row_base),
+                                   C.c_uint32(M), C.c_uint32(N), C.c_uint32(K), C.c_uint64(seed),
+                                   C.c_float(eps), C.c_int(sign), _ptr(y), _ptr(sumsq), _stream(stream)))
+
+
+def qzo_apply_update_channel(c, row_base, seed, eta, d_clipped, stream=None):
+    _check(lib().qzo_apply_update_channel(_ptr(c), C.c_uint32(c.numel()), C.c_uint32(row_base),
+                                          C.c_uint64(seed), C.c_float(eta), C.c_float(d_clipped),
+                                          _stream(stream)))

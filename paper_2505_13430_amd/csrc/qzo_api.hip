@@ -66,7 +66,9 @@ qzo_status check_cfg(const qzo_model_config* c) {
   if (c->struct_size != sizeof(qzo_model_config))
     return fail(QZO_ERR_ARG, "config.struct_size does not match this library");
   if (c->arch > 1) return fail(QZO_ERR_ARG, "config.arch must be 0 (Llama) or 1 (OPT)");
-  if (c->quant != 0) return fail(QZO_ERR_UNSUPPORTED, "only quant = 0 (int4 group scales) is built");
+  if (c->quant > 1) return fail(QZO_ERR_UNSUPPORTED, "quant must be 0 (int4 group scales) or 1 (codebook)");
+  if (c->quant == 1 && c->arch != 0)
+    return fail(QZO_ERR_UNSUPPORTED, "the codebook variant is built for the Llama family only");
   if (c->group_size != 128) return fail(QZO_ERR_SHAPE, "group_size must be 128");
   if (!c->n_layers || !c->d_model || !c->n_heads || !c->d_ffn || !c->vocab || !c->max_seq)
     return fail(QZO_ERR_SHAPE, "zero dimension in config");
@@ -211,7 +213,32 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
       ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
       return launch_w4a16_gemm(g, st);
     };
-    if (llama) {
+    auto cgemm = [&](int li, const void* x, const void* codes, const void* cb, const void* resid,
+                     void* y, uint32_t epi) {
+      GemmArgs g = {};
+      g.x = x; g.w = codes; g.cb = cb;
+      g.s = arena + ((uint64_t)l * m->rows_per_layer + m->lin[li].row_base) * 2;   // fp16 channel scales
+      g.resid = resid; g.y = y;
+      g.M = M; g.N = m->lin[li].N; g.K = m->lin[li].K;
+      g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
+      g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
+      ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+      return launch_codebook_gemm(g, st);
+    };
+    if (llama && c.quant == 1) {
+      // attn_norm, codes/cb qkv, codes/cb o, ffn_norm, codes/cb gate+up, codes/cb down
+      QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
+      QZO_HIP(cgemm(0, w.a, T[1].ptr_dev, T[2].ptr_dev, nullptr, w.qkv, 0));
+      QZO_HIP(launch_rope(w.qkv, m->rope_table, batch, seq, d, H, st));
+      {
+        ProfScope ps(PK_ATTN, attn_flops, st);
+        QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
+      }
+      QZO_HIP(cgemm(1, w.att, T[3].ptr_dev, T[4].ptr_dev, w.h, w.h, EPI_RESIDUAL));
+      QZO_HIP(launch_rmsnorm(w.h, T[5].ptr_dev, M, d, c.norm_eps, w.a, st));
+      QZO_HIP(cgemm(2, w.a, T[6].ptr_dev, T[7].ptr_dev, nullptr, w.act, EPI_SWIGLU));
+      QZO_HIP(cgemm(3, w.act, T[8].ptr_dev, T[9].ptr_dev, w.h, w.h, EPI_RESIDUAL));
+    } else if (llama) {
       // attn_norm, wqkv, wo, ffn_norm, wgu, wdown
       QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(0, w.a, T[1].ptr_dev, nullptr, nullptr, w.qkv, 0));
@@ -275,7 +302,10 @@ qzo_status qzo_model_scale_count(const qzo_model_config* cfg, uint64_t* out) {
   if (!out) return fail(QZO_ERR_ARG, "out is null");
   Linear lin[4];
   layer_linears(*cfg, lin);
-  *out = (lin[3].s_off + (uint64_t)lin[3].N * (lin[3].K / 128)) * cfg->n_layers;
+  if (cfg->quant == 1)
+    *out = (uint64_t)(lin[3].row_base + lin[3].N) * cfg->n_layers;     // one scale per output row
+  else
+    *out = (lin[3].s_off + (uint64_t)lin[3].N * (lin[3].K / 128)) * cfg->n_layers;
   return QZO_OK;
 }
 
@@ -286,7 +316,8 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
   if (!tensors || !scale_arena_dev || !out) return fail(QZO_ERR_ARG, "null argument");
   if (!aligned16(scale_arena_dev)) return fail(QZO_ERR_ALIGN, "scale arena not 16-byte aligned");
   const bool llama = cfg->arch == 0;
-  const uint32_t per_layer = llama ? 6 : 12, head = llama ? 1 : 2, tail = llama ? 2 : 3;
+  const bool codebook = cfg->quant == 1;
+  const uint32_t per_layer = codebook ? 10 : (llama ? 6 : 12), head = llama ? 1 : 2, tail = llama ? 2 : 3;
   if (n_tensors != head + per_layer * cfg->n_layers + tail)
     return fail(QZO_ERR_ARG, "tensor count does not match the architecture's table");
   uint64_t want = 0;
@@ -301,7 +332,11 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
   need.push_back(V * d * 2);
   if (!llama) need.push_back((uint64_t)cfg->max_seq * d * 2);
   for (uint32_t l = 0; l < cfg->n_layers; ++l) {
-    if (llama) {
+    if (codebook) {
+      const uint64_t cbb = 65536 * 16;
+      const uint64_t b[10] = {d * 2, 3 * d * d / 4, cbb, d * d / 4, cbb, d * 2, 2 * F * d / 4, cbb, d * F / 4, cbb};
+      need.insert(need.end(), b, b + 10);
+    } else if (llama) {
       const uint64_t b[6] = {d * 2, 3 * d * d / 2, d * d / 2, d * 2, 2 * F * d / 2, d * F / 2};
       need.insert(need.end(), b, b + 6);
     } else {
@@ -408,8 +443,12 @@ qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uin
   QZO_HIP(launch_spsa_clip(w.losses, eps, clip, result_dev, s));
   {
     ProfScope ps(PK_UPDATE, 4.0 * (double)m->n_scales, s);
-    QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta, 0.0f,
-                                result_dev, s));
+    if (m->cfg.quant == 1)
+      QZO_HIP(launch_channel_update(m->arena, (uint32_t)m->n_scales, 0u, (uint32_t)seed,
+                                    (uint32_t)(seed >> 32), eta, 0.0f, result_dev, s));
+    else
+      QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta, 0.0f,
+                                  result_dev, s));
   }
   return QZO_OK;
 }
@@ -418,8 +457,12 @@ qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float 
                                   void* stream) {
   if (!m) return fail(QZO_ERR_ARG, "model is null");
   if (!std::isfinite(eta) || !std::isfinite(d_clipped)) return fail(QZO_ERR_ARG, "eta/d' not finite");
-  QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta,
-                              d_clipped, nullptr, (hipStream_t)stream));
+  if (m->cfg.quant == 1)
+    QZO_HIP(launch_channel_update(m->arena, (uint32_t)m->n_scales, 0u, (uint32_t)seed,
+                                  (uint32_t)(seed >> 32), eta, d_clipped, nullptr, (hipStream_t)stream));
+  else
+    QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta,
+                                d_clipped, nullptr, (hipStream_t)stream));
   return QZO_OK;
 }
 
@@ -474,6 +517,54 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
   }
   QZO_HIP(launch_w4a16_gemm(g, st));
   if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  return QZO_OK;
+}
+
+qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const void* codebook_dev,
+                             const void* c_dev, uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,
+                             uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
+                             void* stream) {
+  if (!x_dev || !codes_dev || !codebook_dev || !c_dev || !y_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(x_dev) || !aligned16(codes_dev) || !aligned16(codebook_dev) || !aligned16(c_dev) ||
+      !aligned16(y_dev))
+    return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
+  if (K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "K must be a positive multiple of 128");
+  if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
+  if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
+  if (!std::isfinite(eps)) return fail(QZO_ERR_ARG, "eps not finite");
+  hipStream_t st = (hipStream_t)stream;
+  if (M == 0 || N == 0) {
+    if (sumsq_dev) QZO_HIP(launch_sum_partials(nullptr, 0, sumsq_dev, st));
+    return QZO_OK;
+  }
+  GemmArgs g = {};
+  g.x = x_dev; g.w = codes_dev; g.cb = codebook_dev; g.s = c_dev; g.y = y_dev;
+  g.M = M; g.N = N; g.K = K; g.row_base = row_base;
+  g.seed_lo = (uint32_t)seed; g.seed_hi = (uint32_t)(seed >> 32);
+  g.eps_signed = sign > 0 ? eps : -eps;
+  const uint32_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  if (sumsq_dev) {
+    if (g_partials_n < tiles) {
+      if (g_partials) (void)hipFree(g_partials);
+      g_partials = nullptr;
+      g_partials_n = 0;
+      QZO_HIP(hipMalloc((void**)&g_partials, (size_t)tiles * sizeof(float)));
+      g_partials_n = tiles;
+    }
+    g.epi = EPI_SUMSQ;
+    g.partials = g_partials;
+  }
+  QZO_HIP(launch_codebook_gemm(g, st));
+  if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  return QZO_OK;
+}
+
+qzo_status qzo_apply_update_channel(void* c_dev, uint32_t n_rows, uint32_t row_base, uint64_t seed,
+                                    float eta, float d_clipped, void* stream) {
+  if (!c_dev) return fail(QZO_ERR_ARG, "c_dev is null");
+  if (!std::isfinite(eta) || !std::isfinite(d_clipped)) return fail(QZO_ERR_ARG, "eta/d' not finite");
+  QZO_HIP(launch_channel_update(c_dev, n_rows, row_base, (uint32_t)seed, (uint32_t)(seed >> 32), eta,
+                                d_clipped, nullptr, (hipStream_t)stream));
   return QZO_OK;
 }
 

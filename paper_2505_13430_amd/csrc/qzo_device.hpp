@@ -111,6 +111,18 @@ __device__ __forceinline__ void scale_normals8(uint32_t seed_lo, uint32_t seed_h
   normal_pair(w.w, z[6], z[7]);
 }
 
+// z for entry i of a flat vector (per-output-channel scales): counter (i/8, 0, stream, 0),
+// word (i%8)/2, variate i%2.
+__device__ __forceinline__ float flat_normal(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream,
+                                             uint32_t i) {
+  const u32x4_t w = philox4x32_10(i >> 3, 0u, stream, 0u, seed_lo, seed_hi);
+  const uint32_t p = (i & 7u) >> 1;
+  const uint32_t word = p == 0 ? w.x : (p == 1 ? w.y : (p == 2 ? w.z : w.w));
+  float z0, z1;
+  normal_pair(word, z0, z1);
+  return (i & 1u) ? z1 : z0;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

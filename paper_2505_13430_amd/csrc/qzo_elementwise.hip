@@ -88,6 +88,31 @@ hipError_t launch_scale_update(void* arena, const UpdPlan& plan, uint32_t seed_l
   return hipGetLastError();
 }
 
+// Codebook variant: c_n <- max(c_n - eta*d'*z_n, 0) on fp16 per-channel scales.
+__global__ void channel_update_kernel(_Float16* __restrict__ c, uint32_t n, uint32_t row_base,
+                                      uint32_t seed_lo, uint32_t seed_hi, float eta, float dclip_host,
+                                      const qzo_step_result* __restrict__ res) {
+  float cs;
+  if (res) {
+    if (res->status != 0) return;
+    cs = eta * res->d_clipped;
+  } else {
+    cs = eta * dclip_host;
+  }
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float z = flat_normal(seed_lo, seed_hi, 1u, row_base + i);
+  c[i] = (_Float16)fmaxf(__builtin_fmaf(-cs, z, (float)c[i]), 0.0f);
+}
+hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,
+                                 uint32_t seed_hi, float eta, float d_clipped,
+                                 const qzo_step_result* res, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  channel_update_kernel<<<(n + 255) / 256, 256, 0, st>>>((_Float16*)c_fp16, n, row_base, seed_lo,
+                                                         seed_hi, eta, d_clipped, res);
+  return hipGetLastError();
+}
+
 // ------------------------------------------- SPSA scalar + DDC (Eq. 6) ----
 __global__ void spsa_clip_kernel(const float* __restrict__ losses, float eps, float clip,
                                  qzo_step_result* __restrict__ res) {

@@ -101,6 +101,15 @@ __device__ __forceinline__ uint4 dequant8(uint32_t w, float se512, float m8se) {
                     pack_bf16x2(e6, e7));
 }
 
+// 8 fp16 values -> 8 bf16 (round-to-nearest-even), same order.
+__device__ __forceinline__ uint4 half8_to_bf16(uint32_t __attribute__((ext_vector_type(4))) h) {
+  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+  const h2 p0 = __builtin_bit_cast(h2, (uint32_t)h.x), p1 = __builtin_bit_cast(h2, (uint32_t)h.y);
+  const h2 p2 = __builtin_bit_cast(h2, (uint32_t)h.z), p3 = __builtin_bit_cast(h2, (uint32_t)h.w);
+  return make_uint4(pack_bf16x2((float)p0.x, (float)p0.y), pack_bf16x2((float)p1.x, (float)p1.y),
+                    pack_bf16x2((float)p2.x, (float)p2.y), pack_bf16x2((float)p3.x, (float)p3.y));
+}
+
 struct CeEpilogue {
   const int32_t* tok;
   float* part;
@@ -110,8 +119,13 @@ struct CeEpilogue {
 
 // NWN = wavefronts along N (2 along M): 4 -> 512 threads, each wavefront 128x64;
 // 2 -> 256 threads (one wavefront per SIMD, twice the registers), each 128x128.
-template <bool W4, bool CE, int NWN, bool SCHED>
+// QM = weight format: 0 int4 + per-group scales (perturbed in the weight tile), 1 plain bf16,
+// 2 codebook (one 16-bit code per 8 weights into an fp16 [65536,8] codebook, gathered into the
+// weight tile; the perturbed per-output-channel scale multiplies the accumulators).
+template <int QM, bool CE, int NWN, bool SCHED>
 __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilogue ce) {
+  constexpr bool W4 = QM == 0, CB = QM == 2, ROWMAP = W4 || CB;
+  static_assert(!CB || NWN == 4, "codebook staging is written for 512 threads");
   constexpr int THREADS = 128 * NWN;
   constexpr int TJ = 8 / NWN;                 // 32-wide feature tiles per wavefront
   constexpr int NA = 2048 / THREADS;          // 16-byte chunks of a 256x64 bf16 tile per thread
@@ -138,16 +152,19 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<void*>(a.x), 0, (int)((uint64_t)a.M * K * 2), 0x00020000);
   const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<void*>(a.w), 0, (int)(W4 ? (uint64_t)a.N * (K >> 1) : (uint64_t)a.N * K * 2),
+      const_cast<void*>(a.w), 0,
+      (int)(W4 ? (uint64_t)a.N * (K >> 1) : (CB ? (uint64_t)a.N * (K >> 2) : (uint64_t)a.N * K * 2)),
       0x00020000);
+  const __amdgpu_buffer_rsrc_t rcb = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(CB ? a.cb : a.x), 0, CB ? (65536 * 16) : 16, 0x00020000);
   const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<void*>(W4 ? a.s : a.x), 0, (int)(W4 ? (uint64_t)a.N * (K >> 7) * 2 : 16), 0x00020000);
   uint32_t xo[NA], wo[NA], so = 0, gn_w4 = 0;
   const uint32_t brow = t / TPR, bpart = t % TPR;
   // LDS offsets: rows t/8 + RSTEP i share their swizzle, so chunk i is a_lds + i * RSTEP rows.
   const uint32_t a_lds = lds_off(t >> 3, t & 7u);
-  uint32_t b_lds[W4 ? NBC : 1];
-  if (W4) {
+  uint32_t b_lds[ROWMAP ? NBC : 1];
+  if (ROWMAP) {
 #pragma unroll
     for (int c = 0; c < NBC; ++c) b_lds[c] = lds_off(brow, bpart * NBC + c);
   }
@@ -157,15 +174,15 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     _Pragma("unroll") for (int i = 0; i < NA; ++i) {                                         \
       const uint32_t row = (t >> 3) + RSTEP * i, c = t & 7u;                                 \
       xo[i] = (min((TM) * BM + row, a.M - 1) * K + c * 8) * 2;                               \
-      if (!W4) wo[i] = (min((TN) * BN + row, a.N - 1) * K + c * 8) * 2;                      \
+      if (!ROWMAP) wo[i] = (min((TN) * BN + row, a.N - 1) * K + c * 8) * 2;                  \
     }                                                                                        \
-    if (W4) {                                                                                \
+    if (ROWMAP) {                                                                            \
       /* fused SwiGLU: the tile's rows are 4 x (32 gate rows, 32 up rows of the same   */      \
       /* features), so a lane's two accumulators hold gate and up of one feature      */      \
       gn_w4 = (a.epi & EPI_SWIGLU)                                                           \
                   ? ((brow >> 5) & 1u) * (a.N >> 1) + (TN) * 128u + (brow >> 6) * 32u + (brow & 31u) \
                   : min((TN) * BN + brow, a.N - 1);                                          \
-      wo[0] = gn_w4 * (K >> 1) + bpart * 16;                                                 \
+      wo[0] = W4 ? gn_w4 * (K >> 1) + bpart * 16 : gn_w4 * (K >> 2) + bpart * 8;             \
       so = gn_w4 * (K >> 7) * 2;                                                             \
     }                                                                                        \
   } while (0)
@@ -173,6 +190,8 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   u32x4 ra[NA], rb[W4 ? NBQ : NA];
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 rq = {0, 0};                 // codebook: the four codes of the next weight chunk
   uint32_t zw[4] = {0, 0, 0, 0};     // Philox words of the current 8 groups
   float z_odd = 0.0f;                // second variate of the current pair
   float se512 = 0.0f, m8se = 0.0f;
@@ -186,14 +205,23 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 
 // Loads of k-tile KT into registers (KT is clamped by the caller, so the loads
 // are unconditional and are issued a whole k-tile ahead of their use).
+#define QZO_CODES(KT) rq = __builtin_amdgcn_raw_buffer_load_b64(rw, (int)wo[0], (int)((KT) * 16), 0)
 #define QZO_GLOAD(KT)                                                                        \
   do {                                                                                       \
     const int ko_ = (int)((KT) * (BK * 2));                                                  \
+    if (CB) { /* gather the 8-vectors of the codes read one tile earlier */                  \
+      rb[0] = __builtin_amdgcn_raw_buffer_load_b128(rcb, (int)((rq.x & 0xffffu) << 4), 0, 0); \
+      rb[1] = __builtin_amdgcn_raw_buffer_load_b128(rcb, (int)((rq.x >> 16) << 4), 0, 0);    \
+      rb[2] = __builtin_amdgcn_raw_buffer_load_b128(rcb, (int)((rq.y & 0xffffu) << 4), 0, 0); \
+      rb[3] = __builtin_amdgcn_raw_buffer_load_b128(rcb, (int)((rq.y >> 16) << 4), 0, 0);    \
+    }                                                                                        \
     _Pragma("unroll") for (int i = 0; i < NA; ++i)                                           \
         ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[i], ko_, 0);               \
     if (W4) {                                                                                \
       _Pragma("unroll") for (int q = 0; q < NBQ; ++q) rb[q] = __builtin_amdgcn_raw_buffer_load_b128( \
           rw, (int)wo[0] + q * 16, (int)((KT) * (BK / 2)), 0);                               \
+    } else if (CB) {                                                                         \
+      QZO_CODES(min((uint32_t)(KT) + 1u, (K / BK) - 1u));                                    \
     } else {                                                                                 \
       _Pragma("unroll") for (int i = 0; i < NA; ++i)                                         \
           rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[i], ko_, 0);             \
@@ -240,6 +268,9 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
         *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 2] + (STAGE) * TILE_BYTES) = dequant8(rb[q].z, se512, m8se); \
         *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 3] + (STAGE) * TILE_BYTES) = dequant8(rb[q].w, se512, m8se); \
       }                                                                                      \
+    } else if (CB) {                                                                         \
+      _Pragma("unroll") for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4*>(               \
+          lds_b + b_lds[q] + (STAGE) * TILE_BYTES) = half8_to_bf16(rb[q]);                   \
     } else {                                                                                 \
       _Pragma("unroll") for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(              \
           lds_b + a_lds + (i * RSTEP * 128 + (STAGE) * TILE_BYTES)) = rb[i];                 \
@@ -323,6 +354,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // LDS stage kt & 1; during tile kt the registers loaded one tile earlier (tile
   // kt+1) go to the other stage and tile kt+2 is requested from memory.
   const uint32_t nkt = K / BK, last = nkt - 1;
+  if (CB) QZO_CODES(0u);
   QZO_GLOAD(0);
   for (;;) {
 #pragma unroll
@@ -360,6 +392,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   const bool more = tile_walk_get(walk, tile_m, tile_n);
   if (more) {
     QZO_TILE_PTRS(tile_m, tile_n);
+    if (CB) QZO_CODES(0u);
     QZO_GLOAD(0);
   }
 
@@ -367,6 +400,19 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // acc[i][j][4 b + c]: token m = 32 i + lane%32, feature n = 32 j + 8 b + 4 (lane/32) + c
   // of the wavefront's 128 (tokens) x 64 (features) sub-tile.
   const uint32_t n_wave = n0 + wn * (32 * TJ) + 4 * fhalf;
+  // codebook: perturbed per-output-channel scales of the tile's 256 rows,
+  // c + (sigma*eps) z(row id) as one fp32 fma, staged in LDS behind the tiles
+  float* const lds_c = reinterpret_cast<float*>(lds + LDS_BYTES);
+  if (CB) {
+    if (t < 256u) {
+      const uint32_t gn = (a.epi & EPI_SWIGLU)
+                              ? ((t >> 5) & 1u) * (a.N >> 1) + done_n * 128u + (t >> 6) * 32u + (t & 31u)
+                              : min(n0 + t, a.N - 1);
+      const float c0 = (float)reinterpret_cast<const _Float16*>(a.s)[gn];
+      lds_c[t] = __builtin_fmaf(a.eps_signed, flat_normal(a.seed_lo, a.seed_hi, 1u, a.row_base + gn), c0);
+    }
+    __syncthreads();
+  }
   if (!CE && TJ == 2 && (a.epi & EPI_SWIGLU)) {
     // y[m, f] = silu(gate) * up, f = 128 tile_n + 32 wn + 8 b + 4 (lane/32) + c; y is [M, N/2]
     bf16_t* y = (bf16_t*)a.y;
@@ -381,9 +427,12 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
           float v[4];
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            const float g = acc[i][0][4 * b + c];
-            v[c] = g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * g)) *
-                   acc[i][TJ - 1][4 * b + c];
+            float g = acc[i][0][4 * b + c], up = acc[i][TJ - 1][4 * b + c];
+            if (CB) {
+              g *= lds_c[wn * 64 + b * 8 + 4 * fhalf + c];
+              up *= lds_c[wn * 64 + 32 + b * 8 + 4 * fhalf + c];
+            }
+            v[c] = g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * g)) * up;
           }
           uint2 out;
           out.x = pack_bf16x2(v[0], v[1]);
@@ -410,6 +459,10 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
               float v[4];
 #pragma unroll
               for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * b + c];
+              if (CB) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[c] *= lds_c[wn * (32 * TJ) + j * 32 + b * 8 + 4 * fhalf + c];
+              }
               if (a.epi & EPI_BIAS) {
                 const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
                 v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
@@ -494,6 +547,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 #undef QZO_NEW_GROUP
 #undef QZO_SCALE_PREFETCH
 #undef QZO_GLOAD
+#undef QZO_CODES
 #undef QZO_TILE_PTRS
 }
 
@@ -511,7 +565,7 @@ constexpr bool W4_SCHED = true;
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = set_lds_attr((const void*)gemm_kernel<true, false, W4_NWN, W4_SCHED>);
+    hipError_t e = set_lds_attr((const void*)gemm_kernel<0, false, W4_NWN, W4_SCHED>);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -520,15 +574,31 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1};
-  gemm_kernel<true, false, W4_NWN, W4_SCHED>
+  gemm_kernel<0, false, W4_NWN, W4_SCHED>
       <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
+  return hipGetLastError();
+}
+
+hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st) {
+  static bool ready = false;
+  if (!ready) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<2, false, 4, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + 1024);
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
+  if (a.M == 0 || a.N == 0) return hipSuccess;
+  if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 4 >= (1ull << 31))
+    return hipErrorInvalidValue;
+  CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1};
+  gemm_kernel<2, false, 4, true><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES + 1024, st>>>(a, ce);
   return hipGetLastError();
 }
 
 hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = set_lds_attr((const void*)gemm_kernel<false, true, 4, false>);
+    hipError_t e = set_lds_attr((const void*)gemm_kernel<1, true, 4, false>);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -537,7 +607,7 @@ hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   GemmArgs a = {};
   a.x = c.x; a.w = c.w; a.M = c.M; a.N = c.V; a.K = c.K;
   CeEpilogue ce = {c.tok, c.part, c.tgt, c.S, c.n_slices};
-  gemm_kernel<false, true, 4, false><<<gemm_workgroups(c.M, c.V), 512, LDS_BYTES, st>>>(a, ce);
+  gemm_kernel<1, true, 4, false><<<gemm_workgroups(c.M, c.V), 512, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
 }
 

@@ -35,7 +35,8 @@ enum : uint32_t {
 struct GemmArgs {
   const void* x;        // bf16 [M,K]
   const void* w;        // packed int4 [N,K/2] (W4) or bf16 [N,K] (dense)
-  const void* s;        // bf16 [N,K/128] (W4 only)
+  const void* s;        // bf16 [N,K/128] (W4) or fp16 [N] per-channel scales (codebook)
+  const void* cb;       // fp16 [65536,8] codebook (codebook only)
   const void* bias;     // bf16 [N] or null
   const void* resid;    // bf16 [M,N] or null
   void* y;              // bf16 [M,N]
@@ -47,6 +48,11 @@ struct GemmArgs {
   uint32_t epi;
 };
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
+// w = uint16 codes [N,K/8]; cb and s as above; N % 8 == 0, K % 128 == 0.
+hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st);
+hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,
+                                 uint32_t seed_hi, float eta, float d_clipped,
+                                 const qzo_step_result* res, hipStream_t st);
 uint32_t gemm_workgroups(uint32_t M, uint32_t N);
 
 // lm_head GEMM with the cross-entropy folded into the epilogue: for every row

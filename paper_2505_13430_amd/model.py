@@ -37,6 +37,25 @@ class DeviceModel:
         return cls(shape, dev, arena)
 
     @classmethod
+    def from_host_codebook(cls, shape: dict, table, device="cuda:0"):
+        """Codebook variant.  table: (name, kind, array) with kind 'bf16' (fp32 holding bf16
+        values), 'codes' (uint16 [N,K/8]), 'codebook' (fp32 holding fp16 values, [65536,8]) or
+        'chscale' (fp32 holding fp16 values, [N]); channel scales form the fp16 arena."""
+        dev, scales = [], []
+        for _, kind, a in table:
+            a = np.ascontiguousarray(a)
+            if kind == "chscale":
+                scales.append(a.reshape(-1))
+            elif kind == "codes":
+                dev.append(torch.from_numpy(a.view(np.int16)).to(device))
+            elif kind == "codebook":
+                dev.append(torch.from_numpy(a).to(device).to(torch.float16))
+            else:
+                dev.append(torch.from_numpy(a).to(device).to(torch.bfloat16))
+        arena = torch.from_numpy(np.concatenate(scales).astype(np.float32)).to(device).to(torch.float16)
+        return cls(dict(shape, quant=1), dev, arena)
+
+    @classmethod
     def synthetic(cls, shape: dict, seed: int, device="cuda:0"):
         """Random-init model built on the device: weights ~ N(0, 0.02) drawn by
         torch, quantized by the library's RTN kernel (Eq. 3), tensor by tensor."""

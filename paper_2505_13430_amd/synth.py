@@ -114,3 +114,54 @@ def linear_case(M: int, N: int, K: int, seed: int, group: int = GROUP):
     qp = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
     s = bf16_exact(rng.uniform(0.005, 0.02, size=(N, K // group)).astype(np.float32))
     return x, qp, s
+
+
+def fp16_exact(x: np.ndarray) -> np.ndarray:
+    """Values exactly representable in IEEE binary16, as fp32."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def codebook_linear_case(M: int, N: int, K: int, seed: int):
+    """Single codebook-quantized linear: X ~ N(0,1) (bf16-exact) [M,K]; one 16-bit code per 8
+    weights, uniform [N,K/8]; codebook ~ N(0, 0.02) (fp16-exact) [65536,8]; per-output-channel
+    scales ~ U(0.5, 1.5) (fp16-exact) [N]."""
+    rng = np.random.default_rng(seed)
+    x = bf16_exact(rng.standard_normal((M, K), dtype=np.float32))
+    idx = rng.integers(0, 65536, size=(N, K // 8), dtype=np.uint16)
+    cb = fp16_exact(rng.standard_normal((65536, 8), dtype=np.float32) * np.float32(0.02))
+    c = fp16_exact(rng.uniform(0.5, 1.5, size=N).astype(np.float32))
+    return x, idx, cb, c
+
+
+def codebook_tensor_table(shape: dict, seed: int):
+    """Llama-shaped model in the codebook variant: (name, kind, array) with kind in
+    'bf16' | 'codes' | 'codebook' | 'chscale' (see the oracle's build_codebook_model)."""
+    assert shape["arch"] == "llama"
+    rng = np.random.default_rng(seed)
+    d, V = shape["d_model"], shape["vocab"]
+
+    def normal(*sz):
+        return bf16_exact(rng.standard_normal(sz, dtype=np.float32) * np.float32(0.02))
+
+    def gain(n):
+        return bf16_exact(1.0 + 0.1 * rng.standard_normal(n, dtype=np.float32))
+
+    def lin(name, N, K):
+        # codebook entries ~ N(0, 0.02) times channel scales ~ U(0.5, 1.5)
+        return [(name, "codes", rng.integers(0, 65536, size=(N, K // 8), dtype=np.uint16)),
+                (name + ".cb", "codebook",
+                 fp16_exact(rng.standard_normal((65536, 8), dtype=np.float32) * np.float32(0.02))),
+                (name + ".c", "chscale", fp16_exact(rng.uniform(0.5, 1.5, size=N).astype(np.float32)))]
+
+    out = [("tok_emb", "bf16", normal(V, d))]
+    for l in range(shape["n_layers"]):
+        ql = quantized_linears(shape)
+        out.append((f"l{l}.attn_norm", "bf16", gain(d)))
+        out += lin(f"l{l}.wqkv", *ql[0][1:])
+        out += lin(f"l{l}.wo", *ql[1][1:])
+        out.append((f"l{l}.ffn_norm", "bf16", gain(d)))
+        out += lin(f"l{l}.wgu", *ql[2][1:])
+        out += lin(f"l{l}.wdown", *ql[3][1:])
+    out.append(("final_norm", "bf16", gain(d)))
+    out.append(("lm_head", "bf16", normal(V, d)))
+    return out

@@ -352,3 +352,77 @@ def test_real_width_one_layer_step(oracle, name, seq, eta):
     assert np.array_equal(_bits(dm.scales.float().cpu().numpy()), _bits(want))
     print(name, "loss", res["loss_plus"], ref["loss_plus"], "d", res["d"], ref["d"])
     dm.close()
+
+
+# ------------------------------------------------------ codebook variant ----
+@pytest.mark.parametrize("n,row_base", [(1000, 0), (4096, 128), (37, 5), (8, 0xFFFFF000)])
+def test_channel_update_bit_exact(oracle, n, row_base):
+    rng = np.random.default_rng(n)
+    c = synth.fp16_exact(rng.uniform(0.0, 1.5, n).astype(np.float32))
+    c[0] = 0.0
+    for eta, dc in ((1e-3, 40.0), (1.0, -100.0), (0.0, 3.0)):
+        cd = _dev(c, torch.float16)
+        qb.qzo_apply_update_channel(cd, row_base, 11, eta, dc)
+        want = oracle.update_channel_scales(c, row_base, 11, eta, dc)
+        got = cd.float().cpu().numpy()
+        assert np.array_equal(_bits(got), _bits(want)), (eta, dc)
+        assert got.min() >= 0
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 520, 384), (256, 256, 128), (513, 264, 1280)])
+def test_codebook_linear_matches_oracle(oracle, M, N, K):
+    x, idx, cb, c = synth.codebook_linear_case(M, N, K, seed=M + K)
+    xd, cd = _dev(x, torch.bfloat16), _dev(c, torch.float16)
+    idxd, cbd = _dev(idx.view(np.int16)), _dev(cb, torch.float16)
+    outs = {}
+    for sign in (1, -1):
+        y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+        ssq = torch.zeros(1, dtype=torch.float32, device=DEV)
+        qb.qzo_codebook_gemm(xd, idxd, cbd, cd, 24, 5, 1e-2, sign, y, ssq)
+        ce = oracle.channel_effective_scales(c, 24, 5, sign * np.float32(1e-2))
+        ref = oracle.codebook_linear(x, idx, cb, ce)
+        got = y.float().cpu().numpy().astype(np.float64)
+        rms = math.sqrt((ref ** 2).mean())
+        assert (np.abs(got - ref) <= 6e-3 * np.abs(ref) + 1.2e-2 * rms).all(), np.abs(got - ref).max() / rms
+        assert abs(float(ssq.item()) - oracle.sumsq_bf16(ref)) <= 5e-3 * oracle.sumsq_bf16(ref)
+        outs[sign] = y
+    assert not torch.equal(outs[1], outs[-1])
+    y0 = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    y1 = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_codebook_gemm(xd, idxd, cbd, cd, 24, 5, 0.0, 1, y0)
+    qb.qzo_codebook_gemm(xd, idxd, cbd, cd, 24, 6, 0.0, -1, y1)
+    assert torch.equal(y0, y1)                      # eps = 0: seed and sign are irrelevant
+
+
+def test_codebook_model_step(oracle):
+    shape = dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48,
+                 batch=3, seq=40)
+    table = synth.codebook_tensor_table(shape, 31)
+    om = oracle.build_codebook_model(shape, table)
+    dm = DeviceModel.from_host_codebook(shape, table, DEV)
+    assert dm.scales.numel() == qb.qzo_model_scale_count(dict(shape, quant=1)) == om.scales.size
+    tok = synth.tokens(shape, 32)
+    # final hidden states of one perturbed forward, to twice the oracle's own 16-bit noise floor
+    B, S = tok.shape
+    se = oracle.perturbed_scales(om, 4, np.float32(1e-3))
+    ref_loss, ref_hid = oracle.forward_loss(om, se, tok, act_bf16=True, want_hidden=True)
+    _, exact_hid = oracle.forward_loss(om, se, tok, act_bf16=False, want_hidden=True)
+    hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    qb.qzo_debug_forward(dm.handle, _dev(tok), 4, 1e-3, 1, dm.workspace(B, S), loss, hid)
+    assert abs(loss.item() - ref_loss) <= 2e-2 * abs(ref_loss)
+    rms = math.sqrt((ref_hid ** 2).mean())
+    err = np.abs(hid.float().cpu().numpy().astype(np.float64) - ref_hid)
+    floor_rms = math.sqrt(((exact_hid - ref_hid) ** 2).mean())
+    assert math.sqrt((err ** 2).mean()) <= 2 * floor_rms + 2e-3 * rms, (math.sqrt((err ** 2).mean()) / rms, floor_rms / rms)
+    assert err.max() <= 2 * np.abs(exact_hid - ref_hid).max() + 2e-2 * rms
+    ref = oracle.qzo_step(om, tok, seed=4, eps=1e-3, eta=1e-3, Cthr=100.0)
+    res = qb.read_step_result(dm.step(_dev(tok), 4, 1e-3, 1e-3, 100.0))
+    assert res["status"] == 0
+    for k in ("loss_plus", "loss_minus"):
+        assert abs(res[k] - ref[k]) <= 2e-2 * abs(ref[k]), (k, res[k], ref[k])
+    got = dm.scales.float().cpu().numpy()
+    assert (np.abs(got - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-6).all()
+    assert np.array_equal(_bits(got), _bits(oracle.update_scales(om, 4, 1e-3, res["d_clipped"])))
+    print("codebook d gpu", res["d"], "oracle", ref["d"], "changed", float((got != om.scales).mean()))
+    dm.close()

@@ -357,3 +357,92 @@ def test_clipped_steps_descend_on_a_quadratic_toy(oracle):
         assert np.isfinite(m.scales).all() and m.scales.min() >= 0 and m.scales.max() < 0.05
     assert clipped > 0
     assert loss(m.scales.astype(np.float64)) < 0.8 * l0
+
+
+# ------------------------------------------- codebook variant (Sec. 4.2) ----
+def test_fp16_rounding_matches_torch(oracle):
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * s for s in (1e-7, 1e-4, 1.0, 300.0, 7e4)])
+    x = np.concatenate([x, np.float32([0.0, -0.0, 65504.0, 65519.9, 2.0 ** -24, 2.0 ** -25, 1.00048828125])])
+    want = torch.from_numpy(x).to(torch.float16).float().numpy()
+    got = oracle.fp16_rne(x)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_codebook_linear_is_matmul_of_the_gathered_weight(oracle):
+    x, idx, cb, c = synth.codebook_linear_case(9, 24, 256, seed=2)
+    ce = oracle.channel_effective_scales(c, 100, 3, np.float32(0.05))
+    W = cb[idx.astype(np.int64)].reshape(24, 256).astype(np.float64)         # entry j of code (n, b) is W[n, 8 b + j]
+    want = (_t(x) @ _t(W).T).numpy() * ce[None, :]
+    got = oracle.codebook_linear(x, idx, cb, ce)
+    assert np.abs(got - want).max() <= 1e-12 * np.abs(want).max()
+    # one code, one input column: the output picks a single codebook entry
+    e = np.zeros((1, 256)); e[0, 8 * 5 + 3] = 1.0
+    y = oracle.codebook_linear(e, idx, cb, np.ones(24))
+    assert np.array_equal(y[0], cb[idx[:, 5].astype(np.int64), 3].astype(np.float64))
+
+
+def test_channel_scales_perturbation_and_update(oracle):
+    c = synth.fp16_exact(np.random.default_rng(4).uniform(0.0, 1.5, 4000).astype(np.float32))
+    z = oracle.flat_normals(9, 64, 4000, stream=1).astype(np.float64)
+    assert abs(z.mean()) < 0.06 and abs(z.std() - 1) < 0.05
+    # the flat stream is not the group-scale stream of the same seed
+    assert not np.array_equal(oracle.flat_normals(9, 64, 8, stream=1), oracle.scale_normals(9, 64, 1, 8).ravel())
+    eps = np.float32(1e-2)
+    plus = oracle.channel_effective_scales(c, 64, 9, eps)
+    minus = oracle.channel_effective_scales(c, 64, 9, -eps)
+    assert np.abs(plus - (c + float(eps) * z)).max() <= 2.0 ** -22 and np.abs(plus + minus - 2 * c.astype(np.float64)).max() <= 2.0 ** -22
+    assert np.array_equal(oracle.channel_effective_scales(c, 64, 9, np.float32(0)), c.astype(np.float64))
+    # update: c <- fp16(max(c - eta d' z, 0)) with the same z (Algorithm 1's update on the trainable scales)
+    assert np.array_equal(oracle.update_channel_scales(c, 64, 9, 0.0, 30.0), c)
+    up = oracle.update_channel_scales(c, 64, 9, 1e-3, 40.0)
+    want = torch.from_numpy(np.maximum(c.astype(np.float64) - 1e-3 * 40.0 * z, 0)).to(torch.float16).float().numpy()
+    assert (up != want).mean() < 2e-3 and np.abs(up - want).max() <= 2.0 ** -10 * 2
+    assert np.array_equal(oracle.fp16_rne(up), up) and up.min() >= 0
+    big = oracle.update_channel_scales(c, 64, 9, 10.0, 100.0)
+    assert (big[z > 0.01] == 0).all() and (big[z < -0.01] > 0).all()
+
+
+def test_codebook_model_forward_matches_torch_composition(oracle):
+    """The codebook model's forward equals the int-free composition: gathered weights times
+    perturbed channel scales through the same Llama block (checked against plain torch)."""
+    sh = dict(arch="llama", n_layers=2, d_model=64, n_heads=2, d_ffn=128, vocab=96, max_seq=16, batch=2, seq=12)
+    table = synth.codebook_tensor_table(sh, 7)
+    m = oracle.build_codebook_model(sh, table)
+    tok = synth.tokens(sh, 8)
+    se = oracle.perturbed_scales(m, 3, np.float32(1e-2))
+    loss = oracle.forward_loss(m, se, tok, act_bf16=False)
+    t = {n: a for n, _, a in table}
+    d, H, Fd = sh["d_model"], sh["n_heads"], sh["d_ffn"]
+    dh = d // H
+    B, S = tok.shape
+    off = 0
+
+    def lin(x, name, N, K):
+        nonlocal off
+        W = _t(t[name + ".cb"][t[name].astype(np.int64)].reshape(N, K)) * _t(se[off:off + N])[:, None]
+        off += N
+        return x @ W.T
+
+    def rms(x, g):
+        return x / torch.sqrt((x * x).mean(-1, keepdim=True) + 1e-5) * _t(g)
+
+    def rope(x):   # [B,S,H,dh], rotate-half pairs (i, i + dh/2)
+        pos = torch.arange(S, dtype=torch.float64)[:, None]
+        ang = pos * (10000.0 ** (-torch.arange(0, dh, 2, dtype=torch.float64) / dh))[None, :]
+        cs, sn = torch.cos(ang)[None, :, None, :], torch.sin(ang)[None, :, None, :]
+        a, b = x[..., :dh // 2], x[..., dh // 2:]
+        return torch.cat([a * cs - b * sn, b * cs + a * sn], -1)
+
+    h = _t(t["tok_emb"])[torch.from_numpy(tok.astype(np.int64))]
+    for l in range(sh["n_layers"]):
+        qkv = lin(rms(h, t[f"l{l}.attn_norm"]), f"l{l}.wqkv", 3 * d, d)
+        q, k, v = (qkv[..., i * d:(i + 1) * d].reshape(B, S, H, dh) for i in range(3))
+        q, k = rope(q), rope(k)
+        att = F.scaled_dot_product_attention(q.transpose(1, 2), k.transpose(1, 2), v.transpose(1, 2), is_causal=True)
+        h = h + lin(att.transpose(1, 2).reshape(B, S, d), f"l{l}.wo", d, d)
+        gu = lin(rms(h, t[f"l{l}.ffn_norm"]), f"l{l}.wgu", 2 * Fd, d)
+        h = h + lin(F.silu(gu[..., :Fd]) * gu[..., Fd:], f"l{l}.wdown", d, Fd)
+    logits = rms(h, t["final_norm"]) @ _t(t["lm_head"]).T
+    want = F.cross_entropy(logits[:, :-1].reshape(-1, sh["vocab"]), torch.from_numpy(tok[:, 1:].astype(np.int64)).reshape(-1)).item()
+    assert abs(loss - want) <= 1e-9 * abs(want)
