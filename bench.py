@@ -22,7 +22,7 @@ PEAK_BF16_MFMA = 2.5e15     # MI355X dense bf16, flop/s
 PEAK_HBM = 8.0e12           # bytes/s
 
 
-def cpu_baseline(shape, tokens_sample=384):
+def cpu_baseline(shape, tokens_sample=1536):
     """The oracle on the host cores, on a bounded sample of the same workload:
     `tokens_sample` tokens through ONE decoder layer's four perturbed linears and
     the lm_head at the real widths, and the update of one layer's scales;
@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama-2-7b")
+    ap.add_argument("--variant", default="int4", choices=["int4", "codebook"],
+                    help="int4 group-128 scales (the metric's configuration) or the codebook variant "
+                         "with per-channel scales (no cpu_baseline leg)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: a plain 256 MiB copy, the qkv-shaped W4A16 GEMM and the "
@@ -130,7 +133,10 @@ def main():
     shape = synth.SHAPES[args.workload]
     B, S = shape["batch"], shape["seq"]
     torch.cuda.set_device(0)
-    dm = DeviceModel.synthetic(shape, seed=1234, device="cuda:0")
+    codebook = args.variant == "codebook"
+    main_cfg = args.workload == "llama-2-7b" and not codebook     # the counters were read on this one
+    build = DeviceModel.synthetic_codebook if codebook else DeviceModel.synthetic
+    dm = build(shape, seed=1234, device="cuda:0")
     tok = torch.from_numpy(synth.tokens(shape, 5678)).cuda()
     eps, eta, clip = 1e-3, 1e-7, 100.0
     stream = torch.cuda.current_stream()
@@ -164,16 +170,19 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}-shaped decoder, int4 g128 RTN, full QZO step "
+        "config": {"workload": f"{args.workload}-shaped decoder, "
+                               f"{'16-bit codes per 8 weights + fp16 channel scales' if codebook else 'int4 g128 RTN'}"
+                               f", full QZO step "
                                f"(2 perturbed forwards + DDC + scale update)",
                    "batch": B, "seq_len": S, "eps": eps, "eta": eta, "clip": clip},
         "steps_per_s": steps_per_s,
         "forward_tokens_per_s": 2 * B * S * steps_per_s,
         "last_step": res,
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<W4=true> (perturbed W4A16 GEMM)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<2,...> (codebook GEMM, perturbed channel scales)" if codebook
+                     else "gemm_kernel<0,...> (perturbed W4A16 GEMM)",
                      "achieved": gemm_flops_s / 1e12, "peak": PEAK_BF16_MFMA / 1e12,
                      "unit": "TFLOP/s", "frac": gemm_flops_s / PEAK_BF16_MFMA,
-                     "traffic": measured_traffic("traffic_bytes_per_launch_gemm_qkv"),
+                     "traffic": measured_traffic("traffic_bytes_per_launch_gemm_qkv") if main_cfg else None,
                      "traffic_note": "HBM bytes of one qkv-shaped launch (8192x12288x4096), FETCH_SIZE + "
                                      "WRITE_SIZE scaled by a plain copy; algorithmic 2.93e8",
                      "launches": g["launches"], "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
@@ -185,11 +194,12 @@ def main():
                          "unit": "GB/s", "frac": upd_bytes_s / PEAK_HBM,
                          "avg_launch_ms": u["total_ms"] / max(u["launches"], 1),
                          "bytes_per_launch": u["work"] / max(u["launches"], 1),
-                         "traffic": measured_traffic("traffic_bytes_per_launch_scale_update")},
+                         "traffic": measured_traffic("traffic_bytes_per_launch_scale_update")
+                         if main_cfg else None},
         "device_memory_GiB": torch.cuda.max_memory_allocated() / 2 ** 30,
     }
     dm.close()
-    if not args.no_cpu:
+    if not args.no_cpu and not codebook:
         out["cpu_baseline"] = cpu_baseline(shape)
     print(json.dumps(out))
 

@@ -100,6 +100,34 @@ class DeviceModel:
         assert off == n_scales
         return cls(shape, tensors, arena)
 
+    @classmethod
+    def synthetic_codebook(cls, shape: dict, seed: int, device="cuda:0"):
+        """Random-init codebook-variant model built on the device: uniform 16-bit codes,
+        one fp16 [65536, 8] codebook ~ N(0, 0.02) per linear, fp16 channel scales ~ U(0.5, 1.5)."""
+        assert shape["arch"] == "llama"
+        gen = torch.Generator(device=device)
+        gen.manual_seed(seed)
+        d, V = shape["d_model"], shape["vocab"]
+        cfg = dict(shape, quant=1)
+        arena = (torch.rand(qb.qzo_model_scale_count(cfg), generator=gen, device=device) + 0.5).to(torch.float16)
+
+        def fixed(*sz, mean=0.0, std=0.02):
+            return (torch.randn(*sz, generator=gen, device=device) * std + mean).to(torch.bfloat16)
+
+        def lin(N, K):
+            codes = torch.randint(-32768, 32768, (N, K // 8), generator=gen, device=device, dtype=torch.int16)
+            cb = (torch.randn(65536, 8, generator=gen, device=device) * 0.02).to(torch.float16)
+            return [codes, cb]
+
+        tensors = [fixed(V, d)]
+        ql = synth.quantized_linears(shape)
+        for _ in range(shape["n_layers"]):
+            tensors += [fixed(d, mean=1.0, std=0.1)] + lin(*ql[0][1:]) + lin(*ql[1][1:])
+            tensors += [fixed(d, mean=1.0, std=0.1)] + lin(*ql[2][1:]) + lin(*ql[3][1:])
+        tensors += [fixed(d, mean=1.0, std=0.1), fixed(V, d)]
+        torch.cuda.synchronize()
+        return cls(cfg, tensors, arena)
+
     def workspace(self, batch, seq):
         if self._ws_key != (batch, seq):
             n = qb.qzo_workspace_bytes(self.handle, batch, seq)
