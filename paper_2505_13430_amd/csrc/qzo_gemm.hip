@@ -122,10 +122,14 @@ struct CeEpilogue {
 // QM = weight format: 0 int4 + per-group scales (perturbed in the weight tile), 1 plain bf16,
 // 2 codebook (one 16-bit code per 8 weights into an fp16 [65536,8] codebook, gathered into the
 // weight tile; the perturbed per-output-channel scale multiplies the accumulators).
-template <int QM, bool CE, int NWN, bool SCHED>
+// PIPE = how a k-tile's instructions are ordered: 0 left to the compiler, 1 one interleaved
+// stream per wavefront with an explicit issue order, 2 alternating phases (see QZO_PP_TILE).
+template <int QM, bool CE, int NWN, int PIPE>
 __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilogue ce) {
   constexpr bool W4 = QM == 0, CB = QM == 2, ROWMAP = W4 || CB;
+  constexpr bool SCHED = PIPE == 1, PP = PIPE == 2;
   static_assert(!CB || NWN == 4, "codebook staging is written for 512 threads");
+  static_assert(!PP || (NWN == 4 && W4), "the phase schedule is written for int4 weights, 512 threads");
   constexpr int THREADS = 128 * NWN;
   constexpr int TJ = 8 / NWN;                 // 32-wide feature tiles per wavefront
   constexpr int NA = 2048 / THREADS;          // 16-byte chunks of a 256x64 bf16 tile per thread
@@ -191,6 +195,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   u32x4 ra[NA], rb[W4 ? NBQ : NA];
   typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  u32x4 rbp[2];                      // phase schedule: weight quads of the next two tiles
   u32x2 rq = {0, 0};                 // codebook: the four codes of the next weight chunk
   uint32_t zw[4] = {0, 0, 0, 0};     // Philox words of the current 8 groups
   float z_odd = 0.0f;                // second variate of the current pair
@@ -206,25 +211,35 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 // Loads of k-tile KT into registers (KT is clamped by the caller, so the loads
 // are unconditional and are issued a whole k-tile ahead of their use).
 #define QZO_CODES(KT) rq = __builtin_amdgcn_raw_buffer_load_b64(rw, (int)wo[0], (int)((KT) * 16), 0)
-#define QZO_GLOAD(KT)                                                                        \
+#define QZO_GLOAD_A(KT)                                                                      \
   do {                                                                                       \
-    const int ko_ = (int)((KT) * (BK * 2));                                                  \
-    if (CB) { /* gather the 8-vectors of the codes read one tile earlier */                  \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i)                                           \
+        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[i], (int)((KT) * (BK * 2)), 0); \
+  } while (0)
+#define QZO_GLOAD_B(KT)                                                                      \
+  do {                                                                                       \
+    if (W4) {                                                                                \
+      _Pragma("unroll") for (int q = 0; q < NBQ; ++q) rb[q] = __builtin_amdgcn_raw_buffer_load_b128( \
+          rw, (int)wo[0] + q * 16, (int)((KT) * (BK / 2)), 0);                               \
+    } else if (CB) { /* gather the 8-vectors of the codes read one tile earlier */           \
       rb[0] = __builtin_amdgcn_raw_buffer_load_b128(rcb, (int)((rq.x & 0xffffu) << 4), 0, 0); \
       rb[1] = __builtin_amdgcn_raw_buffer_load_b128(rcb, (int)((rq.x >> 16) << 4), 0, 0);    \
       rb[2] = __builtin_amdgcn_raw_buffer_load_b128(rcb, (int)((rq.y & 0xffffu) << 4), 0, 0); \
       rb[3] = __builtin_amdgcn_raw_buffer_load_b128(rcb, (int)((rq.y >> 16) << 4), 0, 0);    \
-    }                                                                                        \
-    _Pragma("unroll") for (int i = 0; i < NA; ++i)                                           \
-        ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[i], ko_, 0);               \
-    if (W4) {                                                                                \
-      _Pragma("unroll") for (int q = 0; q < NBQ; ++q) rb[q] = __builtin_amdgcn_raw_buffer_load_b128( \
-          rw, (int)wo[0] + q * 16, (int)((KT) * (BK / 2)), 0);                               \
-    } else if (CB) {                                                                         \
       QZO_CODES(min((uint32_t)(KT) + 1u, (K / BK) - 1u));                                    \
     } else {                                                                                 \
       _Pragma("unroll") for (int i = 0; i < NA; ++i)                                         \
-          rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[i], ko_, 0);             \
+          rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[i], (int)((KT) * (BK * 2)), 0); \
+    }                                                                                        \
+  } while (0)
+#define QZO_GLOAD(KT)                                                                        \
+  do {                                                                                       \
+    if (CB) {                                                                                \
+      QZO_GLOAD_B(KT);                                                                       \
+      QZO_GLOAD_A(KT);                                                                       \
+    } else {                                                                                 \
+      QZO_GLOAD_A(KT);                                                                       \
+      QZO_GLOAD_B(KT);                                                                       \
     }                                                                                        \
   } while (0)
 
@@ -257,10 +272,13 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 
 // Registers -> LDS stage STAGE (compile-time); the int4 tile is unpacked, scaled
 // by the perturbed scale and rounded to bf16 on the way.
-#define QZO_LSTORE(STAGE)                                                                    \
+#define QZO_LSTORE_A(STAGE)                                                                  \
   do {                                                                                       \
     _Pragma("unroll") for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(                \
         lds_a + a_lds + (i * RSTEP * 128 + (STAGE) * TILE_BYTES)) = ra[i];                   \
+  } while (0)
+#define QZO_LSTORE_B(STAGE)                                                                  \
+  do {                                                                                       \
     if (W4) {                                                                                \
       _Pragma("unroll") for (int q = 0; q < NBQ; ++q) {                                      \
         *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 0] + (STAGE) * TILE_BYTES) = dequant8(rb[q].x, se512, m8se); \
@@ -275,6 +293,11 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       _Pragma("unroll") for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(              \
           lds_b + a_lds + (i * RSTEP * 128 + (STAGE) * TILE_BYTES)) = rb[i];                 \
     }                                                                                        \
+  } while (0)
+#define QZO_LSTORE(STAGE)                                                                    \
+  do {                                                                                       \
+    QZO_LSTORE_A(STAGE);                                                                     \
+    QZO_LSTORE_B(STAGE);                                                                     \
   } while (0)
 
   // acc[i][j]: output features 32 j .. 32 j + 31 (rows of the MFMA result) by
@@ -350,12 +373,95 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     }                                                                                        \
   } while (0)
 
+// Phase schedule (int4 weights).  Wavefronts w and w + 4 share a SIMD.  A k-tile is cut
+// into two halves of two k-steps; for each half a wavefront runs a memory phase and then a
+// matrix phase of sixteen MFMAs whose operands are all in registers.  Phases are separated
+// by workgroup barriers and wavefronts 4..7 run one phase behind wavefronts 0..3, so on
+// every SIMD one wavefront feeds the matrix pipe while the other uses the LDS and the
+// vector ALU.  With t the current tile (LDS stage t & 1):
+//   memory A: 12 fragment reads (k-steps 0,1); while they are served, convert dwords 0,1
+//             of tile t+1's weight quad; store them and activation chunks 0,1 of tile t+1
+//   matrix A: 16 MFMAs; request activation chunks 0,1 of tile t+2 (and a scale)
+//   memory B: 12 fragment reads (k-steps 2,3); convert and store dwords 2,3 and chunks
+//             2,3 of tile t+1; then, before an even tile t+2, the scale of its group
+//   matrix B: 16 MFMAs; request chunks 2,3 of tile t+2 and the weight quad of tile t+3
+// Stage hazards: tile t+1 is written to the other stage during tile t's first three
+// phases, after the barrier that ends the last fragment read of tile t-1 and before the
+// barrier that precedes the first read of tile t+1 by the other half of the wavefronts.
+#define QZO_PHASE_SYNC()                                                                     \
+  do {                                                                                       \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    __syncthreads();                                                                         \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+  } while (0)
+#define QZO_PP_LOAD_B(KT, PAR)                                                               \
+  rbp[PAR] = __builtin_amdgcn_raw_buffer_load_b128(rw, (int)wo[0], (int)((KT) * (BK / 2)), 0)
+#define QZO_PP_LOAD_A(KT, I0)                                                                \
+  do {                                                                                       \
+    ra[I0] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[I0], (int)((KT) * (BK * 2)), 0); \
+    ra[(I0) + 1] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)xo[(I0) + 1], (int)((KT) * (BK * 2)), 0); \
+  } while (0)
+/* half H (0, 1) of the staging of one tile: two weight dwords and two activation chunks */ \
+
+#define QZO_PP_STAGE_HALF(PAR, STAGE, H)                                                     \
+  do {                                                                                       \
+    const uint4 c0_ = dequant8((H) ? rbp[PAR].z : rbp[PAR].x, se512, m8se);                  \
+    const uint4 c1_ = dequant8((H) ? rbp[PAR].w : rbp[PAR].y, se512, m8se);                  \
+    *reinterpret_cast<uint4*>(lds_b + b_lds[2 * (H)] + (STAGE) * TILE_BYTES) = c0_;          \
+    *reinterpret_cast<uint4*>(lds_b + b_lds[2 * (H) + 1] + (STAGE) * TILE_BYTES) = c1_;      \
+    *reinterpret_cast<u32x4*>(lds_a + a_lds + ((2 * (H)) * RSTEP * 128 + (STAGE) * TILE_BYTES)) = ra[2 * (H)]; \
+    *reinterpret_cast<u32x4*>(lds_a + a_lds + ((2 * (H) + 1) * RSTEP * 128 + (STAGE) * TILE_BYTES)) = ra[2 * (H) + 1]; \
+  } while (0)
+#define QZO_PP_MFMAS()                                                                       \
+  do {                                                                                       \
+    QZO_MFMAS(0);                                                                            \
+    QZO_MFMAS(1);                                                                            \
+  } while (0)
+#define QZO_PP_TILE(STAGE, STORE_STAGE, NEXT_KT, NEXT_B_KT, NEW_G, PREF_G)                   \
+  do {                                                                                       \
+    QZO_FRAGS(0, 0, STAGE);                                                                  \
+    QZO_FRAGS(1, 1, STAGE);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    if ((STORE_STAGE) >= 0) QZO_PP_STAGE_HALF((STORE_STAGE) & 1, (STORE_STAGE) & 1, 0);      \
+    QZO_PHASE_SYNC();                                                                        \
+    __builtin_amdgcn_s_setprio(1);                                                           \
+    QZO_PP_MFMAS();                                                                          \
+    if ((STORE_STAGE) >= 0) {                                                                \
+      if ((int)(PREF_G) >= 0) QZO_SCALE_PREFETCH(PREF_G);                                    \
+      QZO_PP_LOAD_A(NEXT_KT, 0);                                                             \
+    }                                                                                        \
+    __builtin_amdgcn_s_setprio(0);                                                           \
+    QZO_PHASE_SYNC();                                                                        \
+    QZO_FRAGS(0, 2, STAGE);                                                                  \
+    QZO_FRAGS(1, 3, STAGE);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    if ((STORE_STAGE) >= 0) {                                                                \
+      QZO_PP_STAGE_HALF((STORE_STAGE) & 1, (STORE_STAGE) & 1, 1);                            \
+      if ((int)(NEW_G) >= 0) QZO_NEW_GROUP((uint32_t)(NEW_G));                               \
+    }                                                                                        \
+    QZO_PHASE_SYNC();                                                                        \
+    __builtin_amdgcn_s_setprio(1);                                                           \
+    QZO_PP_MFMAS();                                                                          \
+    if ((STORE_STAGE) >= 0) {                                                                \
+      QZO_PP_LOAD_A(NEXT_KT, 2);                                                             \
+      QZO_PP_LOAD_B(NEXT_B_KT, (STORE_STAGE) & 1);                                           \
+    }                                                                                        \
+    __builtin_amdgcn_s_setprio(0);                                                           \
+    QZO_PHASE_SYNC();                                                                        \
+  } while (0)
+  const bool late_group = PP && __builtin_amdgcn_readfirstlane(wave) >= 4u;
+
   // K is a multiple of 128, so the number of k-tiles is even.  Tile kt lives in
   // LDS stage kt & 1; during tile kt the registers loaded one tile earlier (tile
   // kt+1) go to the other stage and tile kt+2 is requested from memory.
   const uint32_t nkt = K / BK, last = nkt - 1;
   if (CB) QZO_CODES(0u);
-  QZO_GLOAD(0);
+  if (PP) {
+    QZO_GLOAD_A(0);
+    QZO_PP_LOAD_B(0u, 0);
+  } else {
+    QZO_GLOAD(0);
+  }
   for (;;) {
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -368,9 +474,29 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     QZO_NEW_GROUP(0u);
     QZO_SCALE_PREFETCH(1u);
   }
-  QZO_LSTORE(0);
-  QZO_GLOAD(1u);
+  if (PP) {
+    QZO_PP_STAGE_HALF(0, 0, 0);
+    QZO_PP_STAGE_HALF(0, 0, 1);
+    QZO_GLOAD_A(1u);
+    QZO_PP_LOAD_B(1u, 1);
+    QZO_PP_LOAD_B(min(2u, last), 0);
+  } else {
+    QZO_LSTORE(0);
+    QZO_GLOAD(1u);
+  }
   __syncthreads();
+  if (PP) {
+    if (late_group) QZO_PHASE_SYNC();
+    /* tile t stores tile t+1, requests activations of t+2 and weights of t+3; an even   */
+    /* tile ends its staging with the scale of the group that tile t+2 starts            */
+    QZO_PP_TILE(0, 1, min(2u, last), min(3u, last), 1, -1);
+    for (uint32_t kt = 1; kt + 1 < nkt; kt += 2) {
+      QZO_PP_TILE(1, 0, min(kt + 2, last), min(kt + 3, last), -1, (kt + 3) >> 1);
+      QZO_PP_TILE(0, 1, min(kt + 3, last), min(kt + 4, last), (kt + 3) >> 1, -1);
+    }
+    QZO_PP_TILE(1, -1, 0u, 0u, -1, -1);
+    if (!late_group) QZO_PHASE_SYNC();
+  } else {
   QZO_TILE(0, false, 1, min(2u, last), -1);
   __syncthreads();
   for (uint32_t kt = 1; kt + 1 < nkt; kt += 2) {
@@ -382,6 +508,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   }
   QZO_TILE(1, true, -1, 0u, -1);
   QZO_MFMAS(1);
+  }
 
   // The next tile's first loads are requested before this tile's results are
   // written, and the stores are not waited for: the epilogue's memory traffic
@@ -393,7 +520,12 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   if (more) {
     QZO_TILE_PTRS(tile_m, tile_n);
     if (CB) QZO_CODES(0u);
-    QZO_GLOAD(0);
+    if (PP) {
+      QZO_GLOAD_A(0);
+      QZO_PP_LOAD_B(0u, 0);
+    } else {
+      QZO_GLOAD(0);
+    }
   }
 
   // ---- epilogue ----------------------------------------------------------
@@ -541,6 +673,16 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   if (!more) break;
   }   // tile loop
 #undef QZO_TILE
+#undef QZO_PP_TILE
+#undef QZO_PP_LOAD_A
+#undef QZO_PP_LOAD_B
+#undef QZO_PP_STAGE_HALF
+#undef QZO_PP_MFMAS
+#undef QZO_PHASE_SYNC
+#undef QZO_LSTORE_A
+#undef QZO_LSTORE_B
+#undef QZO_GLOAD_A
+#undef QZO_GLOAD_B
 #undef QZO_MFMAS
 #undef QZO_FRAGS
 #undef QZO_LSTORE
@@ -560,12 +702,12 @@ static hipError_t set_lds_attr(const void* fn) {
 // SIMD) with the explicit issue order is the fastest; 2 along N (256 threads, one
 // per SIMD, 128x128 per wavefront) is about 10 % slower.
 constexpr int W4_NWN = 4;
-constexpr bool W4_SCHED = true;
+constexpr int W4_PIPE = 2;
 
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = set_lds_attr((const void*)gemm_kernel<0, false, W4_NWN, W4_SCHED>);
+    hipError_t e = set_lds_attr((const void*)gemm_kernel<0, false, W4_NWN, W4_PIPE>);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -574,7 +716,7 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1};
-  gemm_kernel<0, false, W4_NWN, W4_SCHED>
+  gemm_kernel<0, false, W4_NWN, W4_PIPE>
       <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
 }
@@ -582,7 +724,7 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
 hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<2, false, 4, true>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<2, false, 4, 1>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + 1024);
     if (e != hipSuccess) return e;
     ready = true;
@@ -591,14 +733,14 @@ hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 4 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1};
-  gemm_kernel<2, false, 4, true><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES + 1024, st>>>(a, ce);
+  gemm_kernel<2, false, 4, 1><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES + 1024, st>>>(a, ce);
   return hipGetLastError();
 }
 
 hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = set_lds_attr((const void*)gemm_kernel<1, true, 4, false>);
+    hipError_t e = set_lds_attr((const void*)gemm_kernel<1, true, 4, 0>);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -607,7 +749,7 @@ hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   GemmArgs a = {};
   a.x = c.x; a.w = c.w; a.M = c.M; a.N = c.V; a.K = c.K;
   CeEpilogue ce = {c.tok, c.part, c.tgt, c.S, c.n_slices};
-  gemm_kernel<1, true, 4, false><<<gemm_workgroups(c.M, c.V), 512, LDS_BYTES, st>>>(a, ce);
+  gemm_kernel<1, true, 4, 0><<<gemm_workgroups(c.M, c.V), 512, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
 }
 
