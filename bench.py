@@ -77,10 +77,28 @@ def measured_traffic(key):
     return None
 
 
+def mfma_ceiling(torch, qb, iters=60000):
+    """bf16 MFMA rate the board sustains with nothing but MFMAs in flight (TFLOP/s), with
+    all-zero and with pseudo-random register operands; timed with events on the current stream."""
+    sink = torch.empty(512 * 512, dtype=torch.float32, device="cuda:0")
+    out = {}
+    for name, rnd in (("zero_operands", False), ("random_operands", True)):
+        qb.qzo_debug_mfma_rate(2000, rnd, sink)           # warm-up
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        wgs = qb.qzo_debug_mfma_rate(iters, rnd, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = wgs * 8 * 16 * 32768.0 * iters / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return out
+
+
 def probe(torch, qb):
-    """Launches whose HBM counters calibrate and measure traffic: a plain copy of known
-    size (256 MiB read + 256 MiB written), the perturbed GEMM at the Llama-2-7B qkv shape
-    (M 8192, N 12288, K 4096) and the scale update over 50,593,792 scales."""
+    """Launches for rocprofv3 counter runs: a plain copy of known size (256 MiB read +
+    256 MiB written) that calibrates the HBM counters, the perturbed GEMM at the Llama-2-7B
+    qkv shape (M 8192, N 12288, K 4096), the scale update over 50,593,792 scales, and the
+    matrix-pipe rate probe with zero and with random operands (engine-clock comparison)."""
     dev = "cuda:0"
     g = torch.Generator(device=dev)
     g.manual_seed(1)
@@ -100,7 +118,13 @@ def probe(torch, qb):
         torch.cuda.synchronize()
         qb.qzo_apply_update(arena, 0, 7, 1e-7, 10.0)
         torch.cuda.synchronize()
-    print(json.dumps({"probe": "copy 2x268435456 B, gemm 8192x12288x4096, update 50593792 scales"}))
+    sink = torch.empty(512 * 512, dtype=torch.float32, device=dev)
+    for rnd in (False, True):
+        for _ in range(3):
+            qb.qzo_debug_mfma_rate(20000, rnd, sink)
+            torch.cuda.synchronize()
+    print(json.dumps({"probe": "copy 2x268435456 B, gemm 8192x12288x4096, update 50593792 scales, "
+                               "mfma rate 20000 iters x 16 MFMAs per wavefront (zero, then random operands)"}))
 
 
 def main():
@@ -186,7 +210,8 @@ def main():
                      "traffic_note": "HBM bytes of one qkv-shaped launch (8192x12288x4096), FETCH_SIZE + "
                                      "WRITE_SIZE scaled by a plain copy; algorithmic 2.93e8",
                      "launches": g["launches"], "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
-                     "flops_per_launch_avg": g["work"] / max(g["launches"], 1)},
+                     "flops_per_launch_avg": g["work"] / max(g["launches"], 1),
+                     "mfma_only_measured_TFLOPs": mfma_ceiling(torch, qb)},
         "kernels": {
             k: {"total_ms_per_step": v["total_ms"] / args.steps, "launches_per_step": v["launches"] / args.steps}
             for k, v in prof.items()},

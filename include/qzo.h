@@ -200,6 +200,16 @@ qzo_status qzo_debug_dequant(const void* q_dev, const void* s_dev, uint32_t row_
                              uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
                              void* w_eff_dev, void* stream);
 
+/* Measurement aid, not part of the method: one 512-thread workgroup per compute unit, each
+ * wavefront issuing iters x 16 v_mfma_f32_32x32x16_bf16 (32768 flop each) on register operands
+ * that are all zero (random_operands = 0) or pseudo-random bf16 values, with no memory traffic.
+ * Timed by the caller on `stream`, it gives the bf16 MFMA rate the board sustains under its
+ * own clock and power management: flop = *workgroups_out * 8 * 16 * 32768 * iters.
+ * sink_dev: fp32 [*workgroups_out * 512] device scratch (at least 512 * 512 floats are
+ * enough for any device), overwritten.  iters in 1 .. 2^20. */
+qzo_status qzo_debug_mfma_rate(uint32_t iters, int random_operands, float* sink_dev,
+                               uint32_t* workgroups_out, void* stream);
+
 /* qzo_forward_loss that also copies the final normalised hidden states (the lm_head's
  * input, bf16 [batch*seq, d_model]) to hidden_dev. */
 qzo_status qzo_debug_forward(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,

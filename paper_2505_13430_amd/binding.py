@@ -24,7 +24,7 @@ EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
     "qzo_apply_update", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
-    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_profile_begin", "qzo_profile_collect",
+    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_profile_begin", "qzo_profile_collect",
     "qzo_last_error",
 ]
 
@@ -195,6 +195,15 @@ def qzo_debug_forward(model, tokens, seed, eps, sign, workspace, loss_out, hidde
 
 
 PROFILE_KINDS = {"w4a16_gemm": 0, "lmhead_ce": 1, "attention": 2, "scale_update": 3, "embed": 4}
+
+
+def qzo_debug_mfma_rate(iters: int, random_operands: bool, sink, stream=None) -> int:
+    """Launches the matrix-pipe rate probe; returns the number of workgroups (8 wavefronts each)."""
+    wgs = C.c_uint32(0)
+    assert sink.numel() >= 512 * 512
+    _check(lib().qzo_debug_mfma_rate(C.c_uint32(iters), C.c_int(int(random_operands)), _ptr(sink),
+                                     C.byref(wgs), _stream(stream)))
+    return wgs.value
 
 
 def qzo_profile_begin(max_records: int):

@@ -568,6 +568,16 @@ qzo_status qzo_apply_update_channel(void* c_dev, uint32_t n_rows, uint32_t row_b
   return QZO_OK;
 }
 
+qzo_status qzo_debug_mfma_rate(uint32_t iters, int random_operands, float* sink_dev,
+                               uint32_t* workgroups_out, void* stream) {
+  if (!sink_dev || !workgroups_out) return fail(QZO_ERR_ARG, "null pointer");
+  if (iters == 0 || iters > (1u << 20)) return fail(QZO_ERR_ARG, "iters must be 1 .. 2^20");
+  const uint32_t wgs = gemm_workgroups(1u << 20, 1u << 20);      // one per compute unit
+  *workgroups_out = wgs;
+  QZO_HIP(launch_mfma_rate(sink_dev, wgs, iters, random_operands != 0, (hipStream_t)stream));
+  return QZO_OK;
+}
+
 qzo_status qzo_profile_begin(uint32_t max_records) {
   while (g_prof.pool.size() < max_records) {
     ProfRec r = {};

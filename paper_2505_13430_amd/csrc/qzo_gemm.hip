@@ -753,4 +753,52 @@ hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Matrix-pipe rate probe: every wavefront of a 512-thread workgroup per compute unit
+// issues `iters` x 16 independent v_mfma_f32_32x32x16_bf16 on register operands (all zero,
+// or pseudo-random bf16 values) and nothing else.  What it sustains is the ceiling that
+// the board's clock and power management leave to any bf16 MFMA kernel.
+__global__ __launch_bounds__(512, 1) void mfma_rate_kernel(float* sink, uint32_t iters, int random_operands) {
+  floatx16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+  bf16x8 fa[4], fb[2];
+  const uint32_t t = threadIdx.x;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t h = (t * 2654435761u + (uint32_t)(i * 8 + e) * 40503u) >> 20;          // 0 .. 4095
+      fa[i][e] = (__bf16)(random_operands ? ((float)h - 2048.0f) * (1.0f / 1024.0f) : 0.0f);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const uint32_t h = (t * 2246822519u + (uint32_t)(j * 8 + e) * 668265263u) >> 20;
+      fb[j][e] = (__bf16)(random_operands ? ((float)h - 2048.0f) * (1.0f / 131072.0f) : 0.0f);
+    }
+  }
+  for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i * 2 + j], 0, 0, 0);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  sink[blockIdx.x * 512u + t] = s;
+}
+
+hipError_t launch_mfma_rate(float* sink, uint32_t workgroups, uint32_t iters, int random_operands,
+                            hipStream_t st) {
+  mfma_rate_kernel<<<workgroups, 512, 0, st>>>(sink, iters, random_operands);
+  return hipGetLastError();
+}
+
 }  // namespace qzo

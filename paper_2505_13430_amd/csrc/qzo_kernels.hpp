@@ -68,6 +68,8 @@ struct CeArgs {
   uint32_t n_slices;    // ceil(V/256)*4
 };
 hipError_t launch_lmhead_ce(const CeArgs& a, hipStream_t st);
+hipError_t launch_mfma_rate(float* sink, uint32_t workgroups, uint32_t iters, int random_operands,
+                            hipStream_t st);
 hipError_t launch_ce_reduce(const float* part, const float* tgt, uint32_t M, uint32_t S,
                             uint32_t n_slices, float* rowloss, float* loss_out, hipStream_t st);
 
