@@ -545,6 +545,19 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     }
     __syncthreads();
   }
+  // A lane holds 4 consecutive features per register group and the lane 32 away the next 4.
+  // Groups b and b+1 are exchanged between the two halves of the wavefront
+  // (v_permlane32_swap), after which lanes 0..31 own features 8b..8b+7 and lanes 32..63
+  // features 8(b+1)..8(b+1)+7 of their token: every access of the epilogue is 16 bytes.
+#define QZO_SWAP8(LO, HI)                                                                    \
+  do {                                                                                       \
+    _Pragma("unroll") for (int c_ = 0; c_ < 4; ++c_) {                                       \
+      const auto r_ = __builtin_amdgcn_permlane32_swap(__float_as_uint((LO)[c_]),            \
+                                                       __float_as_uint((HI)[c_]), false, false); \
+      (LO)[c_] = __uint_as_float(r_[0]);                                                     \
+      (HI)[c_] = __uint_as_float(r_[1]);                                                     \
+    }                                                                                        \
+  } while (0)
   if (!CE && TJ == 2 && (a.epi & EPI_SWIGLU)) {
     // y[m, f] = silu(gate) * up, f = 128 tile_n + 32 wn + 8 b + 4 (lane/32) + c; y is [M, N/2]
     bf16_t* y = (bf16_t*)a.y;
@@ -552,24 +565,28 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t m = m0 + wm * 128 + i * 32 + frow;
-      if (m < a.M) {
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const uint32_t f = done_n * 128u + wn * 32u + b * 8u + 4u * fhalf;
-          float v[4];
+      for (int bp = 0; bp < 2; ++bp) {
+        float v[2][4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
+            const int b = 2 * bp + h;
             float g = acc[i][0][4 * b + c], up = acc[i][TJ - 1][4 * b + c];
             if (CB) {
               g *= lds_c[wn * 64 + b * 8 + 4 * fhalf + c];
               up *= lds_c[wn * 64 + 32 + b * 8 + 4 * fhalf + c];
             }
-            v[c] = g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * g)) * up;
+            v[h][c] = g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * g)) * up;
           }
-          uint2 out;
-          out.x = pack_bf16x2(v[0], v[1]);
-          out.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2*>(y + (uint64_t)m * F + f) = out;
+        QZO_SWAP8(v[0], v[1]);
+        const uint32_t f = done_n * 128u + wn * 32u + (2u * bp + fhalf) * 8u;
+        if (m < a.M) {
+          uint4 out;
+          out.x = pack_bf16x2(v[0][0], v[0][1]); out.y = pack_bf16x2(v[0][2], v[0][3]);
+          out.z = pack_bf16x2(v[1][0], v[1][1]); out.w = pack_bf16x2(v[1][2], v[1][3]);
+          *reinterpret_cast<uint4*>(y + (uint64_t)m * F + f) = out;
         }
       }
     }
@@ -581,48 +598,58 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t m = m0 + wm * 128 + i * 32 + frow;
-      if (m < a.M) {
 #pragma unroll
-        for (int j = 0; j < TJ; ++j)
+      for (int j = 0; j < TJ; ++j)
 #pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const uint32_t n = n_wave + j * 32 + b * 8;      // 4 features n .. n+3 (N % 4 == 0)
-            if (n < a.N) {
-              float v[4];
+        for (int bp = 0; bp < 2; ++bp) {
+          float v[2][4];
 #pragma unroll
-              for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * b + c];
-              if (CB) {
+          for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int c = 0; c < 4; ++c) v[c] *= lds_c[wn * (32 * TJ) + j * 32 + b * 8 + 4 * fhalf + c];
-              }
-              if (a.epi & EPI_BIAS) {
-                const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
-                v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
-                v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
-              }
-              const uint64_t o = (uint64_t)m * a.N + n;
-              if (a.epi & EPI_RESIDUAL) {
-                const uint2 rr = *reinterpret_cast<const uint2*>(resid + o);
-                v[0] += __uint_as_float(rr.x << 16); v[1] += __uint_as_float(rr.x & 0xffff0000u);
-                v[2] += __uint_as_float(rr.y << 16); v[3] += __uint_as_float(rr.y & 0xffff0000u);
-              }
-              if (a.epi & EPI_RELU) {
+            for (int c = 0; c < 4; ++c) {
+              v[h][c] = acc[i][j][4 * (2 * bp + h) + c];
+              if (CB) v[h][c] *= lds_c[wn * (32 * TJ) + j * 32 + (2 * bp + h) * 8 + 4 * fhalf + c];
+            }
+          QZO_SWAP8(v[0], v[1]);
+          // 8 features n .. n+7 (N % 8 == 0)
+          const uint32_t n = n0 + wn * (32 * TJ) + j * 32 + (2u * bp + fhalf) * 8u;
+          if (m < a.M && n < a.N) {
+            if (a.epi & EPI_BIAS) {
+              const uint4 bb = *reinterpret_cast<const uint4*>(bias + n);
+              v[0][0] += __uint_as_float(bb.x << 16); v[0][1] += __uint_as_float(bb.x & 0xffff0000u);
+              v[0][2] += __uint_as_float(bb.y << 16); v[0][3] += __uint_as_float(bb.y & 0xffff0000u);
+              v[1][0] += __uint_as_float(bb.z << 16); v[1][1] += __uint_as_float(bb.z & 0xffff0000u);
+              v[1][2] += __uint_as_float(bb.w << 16); v[1][3] += __uint_as_float(bb.w & 0xffff0000u);
+            }
+            const uint64_t o = (uint64_t)m * a.N + n;
+            if (a.epi & EPI_RESIDUAL) {
+              const uint4 rr = *reinterpret_cast<const uint4*>(resid + o);
+              v[0][0] += __uint_as_float(rr.x << 16); v[0][1] += __uint_as_float(rr.x & 0xffff0000u);
+              v[0][2] += __uint_as_float(rr.y << 16); v[0][3] += __uint_as_float(rr.y & 0xffff0000u);
+              v[1][0] += __uint_as_float(rr.z << 16); v[1][1] += __uint_as_float(rr.z & 0xffff0000u);
+              v[1][2] += __uint_as_float(rr.w << 16); v[1][3] += __uint_as_float(rr.w & 0xffff0000u);
+            }
+            if (a.epi & EPI_RELU) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) v[c] = fmaxf(v[c], 0.0f);
-              }
-              uint2 out;
-              out.x = pack_bf16x2(v[0], v[1]);
-              out.y = pack_bf16x2(v[2], v[3]);
-              *reinterpret_cast<uint2*>(y + o) = out;
-              if (a.epi & EPI_SUMSQ) {
-                const float q0 = __uint_as_float(out.x << 16), q1 = __uint_as_float(out.x & 0xffff0000u);
-                const float q2 = __uint_as_float(out.y << 16), q3 = __uint_as_float(out.y & 0xffff0000u);
-                ssq = __builtin_fmaf(q0, q0, ssq); ssq = __builtin_fmaf(q1, q1, ssq);
-                ssq = __builtin_fmaf(q2, q2, ssq); ssq = __builtin_fmaf(q3, q3, ssq);
+              for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[h][c] = fmaxf(v[h][c], 0.0f);
+            }
+            uint4 out;
+            out.x = pack_bf16x2(v[0][0], v[0][1]); out.y = pack_bf16x2(v[0][2], v[0][3]);
+            out.z = pack_bf16x2(v[1][0], v[1][1]); out.w = pack_bf16x2(v[1][2], v[1][3]);
+            *reinterpret_cast<uint4*>(y + o) = out;
+            if (a.epi & EPI_SUMSQ) {
+              const uint32_t ow[4] = {out.x, out.y, out.z, out.w};
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const float q0 = __uint_as_float(ow[q] << 16), q1 = __uint_as_float(ow[q] & 0xffff0000u);
+                ssq = __builtin_fmaf(q0, q0, ssq);
+                ssq = __builtin_fmaf(q1, q1, ssq);
               }
             }
           }
-      }
+        }
     }
     if (a.epi & EPI_SUMSQ) {
       float* red = reinterpret_cast<float*>(lds);
@@ -672,6 +699,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   }
   if (!more) break;
   }   // tile loop
+#undef QZO_SWAP8
 #undef QZO_TILE
 #undef QZO_PP_TILE
 #undef QZO_PP_LOAD_A
