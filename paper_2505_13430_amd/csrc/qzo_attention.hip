@@ -7,7 +7,16 @@
 // so that a lane owns one query: the softmax row reductions are in-register
 // plus one cross-half shuffle, the probabilities are already in the B-operand
 // layout of the second MFMA, and O^T = V^T P^T accumulates with a per-lane
-// rescale.  K tiles (32 keys) sit row-major in LDS, V tiles transposed.
+// rescale.
+//
+// Keys are processed 64 at a time.  The K tile sits row-major in LDS (16-byte
+// chunks XOR-swizzled by row); the V tile is stored transposed (head dimension x
+// keys) with the keys of each group of 16 permuted so that the eight keys a lane
+// needs for one MFMA k-step are contiguous: one 16-byte read per operand.  A
+// thread transposes a 4-key x 8-feature block in registers (byte permutes) and
+// writes eight 8-byte rows.  Two LDS buffers: tile kb is computed from one while tile
+// kb+1 goes from registers to the other and tile kb+2 is requested from memory, so
+// there is one barrier per tile and the global loads have a whole tile to land.
 #include "qzo_device.hpp"
 #include "qzo_kernels.hpp"
 
@@ -17,22 +26,27 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 template <int DH>
-__global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict__ qkv, uint32_t S,
-                                                        uint32_t n_heads, bf16_t* __restrict__ out) {
+__global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restrict__ qkv, uint32_t S,
+                                                           uint32_t n_heads, bf16_t* __restrict__ out) {
+  constexpr int KB = 64;             // keys per tile
   constexpr int KT = DH / 16;        // k-steps of the score MFMA
   constexpr int DT = DH / 32;        // 32-wide slices of the head for the PV MFMA
   constexpr int CH = DH / 8;         // 16-byte chunks per K row
-  constexpr int VT_STRIDE = 40;      // padded keys per V^T row (bf16 units)
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[32 * DH];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[DH * VT_STRIDE];
+  constexpr int NK = KB * CH / 256;  // K chunks per thread and tile (4 or 2)
+  constexpr int VT_STRIDE = KB + 8;  // padded keys per V^T row (bf16 units): 144 B rows
+  constexpr uint32_t SWZ = CH - 1;   // chunk swizzle mask: DH 128 -> row & 15, DH 64 -> (row >> 1) & 7
+  __shared__ __attribute__((aligned(16))) bf16_t Ks2[2][KB * DH];
+  __shared__ __attribute__((aligned(16))) bf16_t Vt2[2][DH * VT_STRIDE];
 
   const uint32_t d = n_heads * DH, ld = 3 * d;
-  const uint32_t b = blockIdx.z, h = blockIdx.y, q0 = blockIdx.x * 128;
+  // heavy query blocks (late positions, many keys) are dispatched first
+  const uint32_t b = blockIdx.z, h = blockIdx.y, q0 = (gridDim.x - 1 - blockIdx.x) * 128;
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
   const bf16_t* base = qkv + (uint64_t)b * S * ld + h * DH;
   const uint32_t qq = q0 + wave * 32 + lrow;            // this lane's query
   const uint32_t qc = min(qq, S - 1);
+  auto swz = [](uint32_t row) { return DH == 128 ? (row & SWZ) : ((row >> 1) & SWZ); };
 
   bf16x8 qf[KT];
 #pragma unroll
@@ -48,56 +62,106 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
   const float sc = 1.44269504088896f / sqrtf((float)DH);   // log2(e)/sqrt(dh)
 
   const uint32_t q_hi = min(q0 + 127u, S - 1);
-  const uint32_t nkb = q_hi / 32 + 1;
+  const uint32_t nkb = q_hi / KB + 1;
   const uint32_t wave_q_hi = q0 + wave * 32 + 31;
 
-  for (uint32_t kb = 0; kb < nkb; ++kb) {
-    __syncthreads();
-    // K tile: 32 rows x CH chunks, swizzled; V tile transposed.
-    for (uint32_t c = t; c < 32u * CH; c += 256) {
-      const uint32_t row = c / CH, ch = c % CH;
-      const uint32_t key = min(kb * 32 + row, S - 1);
-      const bf16_t* src = base + (uint64_t)key * ld + ch * 8;
-      uint4 kv = *reinterpret_cast<const uint4*>(src + d);
-      *reinterpret_cast<uint4*>(Ks + row * DH + ((ch ^ (row & 7u)) * 8)) = kv;
-      uint4 vv = *reinterpret_cast<const uint4*>(src + 2 * d);
-      const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        Vt[(ch * 8 + 2 * j) * VT_STRIDE + row] = (bf16_t)(w[j] & 0xffffu);
-        Vt[(ch * 8 + 2 * j + 1) * VT_STRIDE + row] = (bf16_t)(w[j] >> 16);
-      }
-    }
-    __syncthreads();
-    if (kb * 32 > wave_q_hi) continue;          // every key of the tile is in this wave's future
+  // staging registers: K chunks (row kc / CH, chunk kc % CH) and one 4-key x 8-feature V block
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 kreg[NK], vreg[4];
+  // 16 consecutive lanes take the 16 key quads of one feature chunk: their 8-byte
+  // stores fill 128 contiguous bytes of one V^T row
+  const uint32_t v_ch = wave * 4 + (lane >> 4), v_kq = lane & 15u;
+  const bool v_on = v_ch < (uint32_t)CH;
+  // (macros, not lambdas: arrays captured by reference would be kept in scratch memory)
+#define QZO_ATT_GLOAD(KB_)                                                                   \
+  do {                                                                                       \
+    _Pragma("unroll") for (int i = 0; i < NK; ++i) {                                         \
+      const uint32_t c = t + 256u * i, row = c / CH, ch = c % CH;                            \
+      const uint32_t key = min((KB_) * KB + row, S - 1);                                     \
+      kreg[i] = *reinterpret_cast<const u32x4*>(base + (uint64_t)key * ld + d + ch * 8);     \
+    }                                                                                        \
+    if (v_on) {                                                                              \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                        \
+        const uint32_t key = min((KB_) * KB + v_kq * 4 + r, S - 1);                          \
+        vreg[r] = *reinterpret_cast<const u32x4*>(base + (uint64_t)key * ld + 2 * d + v_ch * 8); \
+      }                                                                                      \
+    }                                                                                        \
+  } while (0)
+  // key 8a + 4h + c of a group of 16 goes to position 8h + 4a + c of the V^T row
+  const uint32_t v_pos = (v_kq >> 2) * 16 + (v_kq & 1u) * 8 + ((v_kq & 3u) >> 1) * 4;
+#define QZO_ATT_VROW(J, SEL, BUF)                                                            \
+  do {                                                                                       \
+    uint2 o_;                                                                                \
+    o_.x = __builtin_amdgcn_perm(vreg[1][(J) >> 1], vreg[0][(J) >> 1], SEL);                 \
+    o_.y = __builtin_amdgcn_perm(vreg[3][(J) >> 1], vreg[2][(J) >> 1], SEL);                 \
+    *reinterpret_cast<uint2*>(Vt2[BUF] + (v_ch * 8 + (J)) * VT_STRIDE + v_pos) = o_;         \
+  } while (0)
+#define QZO_ATT_LSTORE(BUF)                                                                  \
+  do {                                                                                       \
+    _Pragma("unroll") for (int i = 0; i < NK; ++i) {                                         \
+      const uint32_t c = t + 256u * i, row = c / CH, ch = c % CH;                            \
+      *reinterpret_cast<u32x4*>(Ks2[BUF] + row * DH + ((ch ^ swz(row)) * 8)) = kreg[i];      \
+    }                                                                                        \
+    if (v_on) { /* features 2j take the low halves of dword j, 2j+1 the high halves */       \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                        \
+        QZO_ATT_VROW(2 * j, 0x05040100u, BUF);                                               \
+        QZO_ATT_VROW(2 * j + 1, 0x07060302u, BUF);                                           \
+      }                                                                                      \
+    }                                                                                        \
+  } while (0)
+  // Tile kb is computed from LDS buffer kb & 1 while tile kb+1 goes from registers to the
+  // other buffer and tile kb+2 is requested from memory: one barrier per tile.
+  QZO_ATT_GLOAD(0u);
+  QZO_ATT_LSTORE(0);
+  if (nkb > 1) QZO_ATT_GLOAD(1u);
+  __syncthreads();
 
-    // scores^T: rows = keys, cols = queries
-    floatx16 s;
+  for (uint32_t kb = 0; kb < nkb; ++kb) {
+    if (kb > 0) __syncthreads();                // tile kb is complete, tile kb-1 has been read
+    if (kb + 1 < nkb) {
+      if (kb & 1u) QZO_ATT_LSTORE(0); else QZO_ATT_LSTORE(1);
+      if (kb + 2 < nkb) QZO_ATT_GLOAD(kb + 2);
+    }
+    const bf16_t* Ks = Ks2[kb & 1u];
+    const bf16_t* Vt = Vt2[kb & 1u];
+    if (kb * KB > wave_q_hi) continue;          // every key of the tile is in this wave's future
+    const bool two = kb * KB + 32 <= wave_q_hi; // the tile's second half holds visible keys
+
+    // scores^T: rows = keys, cols = queries; sub-tile u covers keys 32 u .. 32 u + 31
+    floatx16 s[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+    for (int u = 0; u < 2; ++u) {
 #pragma unroll
-    for (int ks = 0; ks < KT; ++ks) {
-      const uint32_t ch = ks * 2 + lhalf;
-      bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + lrow * DH + ((ch ^ (lrow & 7u)) * 8));
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
+      for (int r = 0; r < 16; ++r) s[u][r] = 0.0f;
+      if (u == 0 || two) {
+#pragma unroll
+        for (int ks = 0; ks < KT; ++ks) {
+          const uint32_t row = u * 32 + lrow, ch = ks * 2 + lhalf;
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + row * DH + ((ch ^ swz(row)) * 8));
+          s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[u], 0, 0, 0);
+        }
+      }
     }
     float mx = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const uint32_t key = kb * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-      s[r] = key <= qq ? s[r] * sc : -INFINITY;
-      mx = fmaxf(mx, s[r]);
-    }
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t key = kb * KB + u * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+        s[u][r] = key <= qq ? s[u][r] * sc : -INFINITY;
+        mx = fmaxf(mx, s[u][r]);
+      }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     float psum = 0.0f;
-    float p[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      p[r] = __builtin_amdgcn_exp2f(s[r] - m_new);
-      psum += p[r];
-    }
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        s[u][r] = __builtin_amdgcn_exp2f(s[u][r] - m_new);
+        psum += s[u][r];
+      }
     psum += __shfl_xor(psum, 32, 64);
     l_run = l_run * alpha + psum;
     m_run = m_new;
@@ -105,20 +169,21 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
     for (int i = 0; i < DT; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
-    // P^T as the B operand: element e of k-step st is key 8(2 st + e/4) + 4 half + e%4,
-    // i.e. score register 8 st + e.
+    // P^T as the B operand: element e of k-step st (16 keys) is key 8 (e/4) + 4 half + e%4 of
+    // that group, i.e. score register 8 (st & 1) + e of sub-tile st / 2; the V^T tile holds the
+    // same eight keys contiguously at position 16 st + 8 half.
 #pragma unroll
-    for (int st = 0; st < 2; ++st) {
-      union { bf16x8 v; uint32_t u[4]; } pf;
+    for (int st = 0; st < 4; ++st) {
+      if (st < 2 || two) {
+        union { bf16x8 v; uint32_t u[4]; } pf;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) pf.u[e] = pack_bf16x2(p[8 * st + 2 * e], p[8 * st + 2 * e + 1]);
+        for (int e = 0; e < 4; ++e)
+          pf.u[e] = pack_bf16x2(s[st >> 1][8 * (st & 1) + 2 * e], s[st >> 1][8 * (st & 1) + 2 * e + 1]);
 #pragma unroll
-      for (int i = 0; i < DT; ++i) {
-        union { bf16x8 v; uint2 h[2]; } vf;
-        const bf16_t* vr = Vt + (i * 32 + lrow) * VT_STRIDE + 16 * st + 4 * lhalf;
-        vf.h[0] = *reinterpret_cast<const uint2*>(vr);
-        vf.h[1] = *reinterpret_cast<const uint2*>(vr + 8);
-        o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[i], 0, 0, 0);
+        for (int i = 0; i < DT; ++i) {
+          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(Vt + (i * 32 + lrow) * VT_STRIDE + 16 * st + 8 * lhalf);
+          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, o[i], 0, 0, 0);
+        }
       }
     }
   }
@@ -137,6 +202,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t* __restrict
       }
   }
 }
+
+#undef QZO_ATT_GLOAD
+#undef QZO_ATT_LSTORE
+#undef QZO_ATT_VROW
 
 hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_heads,
                             uint32_t dh, void* out, hipStream_t st) {
