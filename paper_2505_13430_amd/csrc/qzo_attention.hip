@@ -127,48 +127,80 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     if (kb * KB > wave_q_hi) continue;          // every key of the tile is in this wave's future
     const bool two = kb * KB + 32 <= wave_q_hi; // the tile's second half holds visible keys
 
-    // scores^T: rows = keys, cols = queries; sub-tile u covers keys 32 u .. 32 u + 31
+    // scores^T: rows = keys, cols = queries; sub-tile u covers keys 32 u .. 32 u + 31.
+    // The two sub-tiles are independent accumulators and alternate in the matrix pipe.
     floatx16 s[2];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[u][r] = 0.0f;
-      if (u == 0 || two) {
+    if (two) {
 #pragma unroll
-        for (int ks = 0; ks < KT; ++ks) {
-          const uint32_t row = u * 32 + lrow, ch = ks * 2 + lhalf;
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + row * DH + ((ch ^ swz(row)) * 8));
-          s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[u], 0, 0, 0);
-        }
+      for (int ks = 0; ks < KT; ++ks) {
+        const uint32_t ch = ks * 2 + lhalf;
+        const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(Ks + lrow * DH + ((ch ^ swz(lrow)) * 8));
+        const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(Ks + (32 + lrow) * DH + ((ch ^ swz(32 + lrow)) * 8));
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], s[1], 0, 0, 0);
       }
+      // issue order: six fragment reads ahead, then one pair of reads per pair of MFMAs
+      __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+      for (int ks = 0; ks < KT; ++ks) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        if (ks < KT - 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KT; ++ks) {
+        const uint32_t ch = ks * 2 + lhalf;
+        const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(Ks + lrow * DH + ((ch ^ swz(lrow)) * 8));
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], s[0], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int ks = 0; ks < KT; ++ks) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (ks < KT - 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+    }
+    // running maximum in raw score units; the 1/sqrt(dh) log2(e) factor is folded into the
+    // exponent: p = exp2(s * sc - m * sc).  Only tiles that touch the diagonal need the mask.
+    if (kb * KB + (KB - 1) > q0 + wave * 32) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const uint32_t key = kb * KB + u * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+          s[u][r] = key <= qq ? s[u][r] : -INFINITY;
+        }
     }
     float mx = -INFINITY;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t key = kb * KB + u * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-        s[u][r] = key <= qq ? s[u][r] * sc : -INFINITY;
-        mx = fmaxf(mx, s[u][r]);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[u][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+    const float nm = -m_new * sc;
     float psum = 0.0f;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        s[u][r] = __builtin_amdgcn_exp2f(s[u][r] - m_new);
+        s[u][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[u][r], sc, nm));
         psum += s[u][r];
       }
     psum += __shfl_xor(psum, 32, 64);
     l_run = l_run * alpha + psum;
     m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // some lane's maximum moved
 #pragma unroll
-    for (int i = 0; i < DT; ++i)
+      for (int i = 0; i < DT; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+    }
     // P^T as the B operand: element e of k-step st (16 keys) is key 8 (e/4) + 4 half + e%4 of
     // that group, i.e. score register 8 (st & 1) + e of sub-tile st / 2; the V^T tile holds the
     // same eight keys contiguously at position 16 st + 8 half.
