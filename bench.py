@@ -136,6 +136,8 @@ def main():
     ap.add_argument("--variant", default="int4", choices=["int4", "codebook"],
                     help="int4 group-128 scales (the metric's configuration) or the codebook variant "
                          "with per-channel scales (no cpu_baseline leg)")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--seq", type=int, default=0, help="override the workload's sequence length")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: a plain 256 MiB copy, the qkv-shaped W4A16 GEMM and the "
@@ -154,11 +156,17 @@ def main():
     if args.probe:
         probe(torch, qb)
         return
-    shape = synth.SHAPES[args.workload]
+    shape = dict(synth.SHAPES[args.workload])
+    if args.batch:
+        shape["batch"] = args.batch
+    if args.seq:
+        shape["seq"] = args.seq
     B, S = shape["batch"], shape["seq"]
     torch.cuda.set_device(0)
     codebook = args.variant == "codebook"
-    main_cfg = args.workload == "llama-2-7b" and not codebook     # the counters were read on this one
+    # the counters were read on this one
+    main_cfg = args.workload == "llama-2-7b" and not codebook and not args.batch and not args.seq
+    few_tokens = B * S <= 64 and not codebook      # the int4 GEMM takes its weight-streaming path
     build = DeviceModel.synthetic_codebook if codebook else DeviceModel.synthetic
     dm = build(shape, seed=1234, device="cuda:0")
     tok = torch.from_numpy(synth.tokens(shape, 5678)).cuda()
@@ -223,8 +231,19 @@ def main():
                          if main_cfg else None},
         "device_memory_GiB": torch.cuda.max_memory_allocated() / 2 ** 30,
     }
+    if few_tokens:
+        # every int4 weight and scale is read once per launch: the roof is HBM
+        wbytes = sum(N * K // 2 + N * K // 64 for _, N, K in synth.quantized_linears(shape))
+        per_launch = wbytes / 4.0
+        out["roofline"] = {"bound": "hbm", "kernel": "skinny_gemm_kernel + skinny_reduce_kernel (few-token W4A16 linear)",
+                           "achieved": per_launch / (g["total_ms"] / max(g["launches"], 1) * 1e-3) / 1e9,
+                           "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                           "frac": per_launch / (g["total_ms"] / max(g["launches"], 1) * 1e-3) / PEAK_HBM,
+                           "traffic": None, "launches": g["launches"],
+                           "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
+                           "bytes_per_launch_avg": per_launch}
     dm.close()
-    if not args.no_cpu and not codebook:
+    if not args.no_cpu and not codebook and main_cfg:
         out["cpu_baseline"] = cpu_baseline(shape)
     print(json.dumps(out))
 

@@ -151,6 +151,12 @@ qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float 
  * the bf16-rounded outputs.  Requires group == 128, K % 128 == 0, N % 8 == 0.
  * Uses a library-owned device scratch (per-tile partial sums, allocated on first
  * use per device) when sumsq_dev is given.
+ * With M <= 64 the call takes the few-token path (the paper's batch-1 memory
+ * profile and short-prompt batches, Sec. 4.3): the int4 weights are streamed once,
+ * K is split over workgroups and the fp32 partial sums are added in slice order by
+ * a second kernel (deterministic).  Its partial sums also live in a library-owned
+ * scratch, grown on demand (at most 8 * M * N floats); calls on one device share it
+ * and must not overlap.  Inside a model the same path uses the caller's workspace.
  */
 qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
                             uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,

@@ -9,6 +9,7 @@
 #include <vector>
 #include "../../include/qzo.h"
 #include "qzo_kernels.hpp"
+#include <algorithm>
 
 using namespace qzo;
 
@@ -40,7 +41,7 @@ struct Linear {           // one quantized linear of a layer
 
 struct Workspace {
   unsigned char *h, *a, *qkv, *att, *ff, *act;
-  float *ce_part, *tgt, *rowloss, *losses;
+  float *ce_part, *tgt, *rowloss, *losses, *skinny;
   uint64_t total;
 };
 
@@ -140,6 +141,13 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   w.tgt = (float*)take(M * 4);
   w.rowloss = (float*)take(M * 4);
   w.losses = (float*)take(256);
+  // few-token path of the int4 GEMM: fp32 partial sums of the K slices of the largest linear
+  uint64_t sk = 0;
+  if (M <= SKINNY_MAX_M && c.quant == 0)
+    for (int i = 0; i < 4; ++i)
+      sk = std::max<uint64_t>(sk, skinny_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
+  w.skinny = (float*)take(sk * 4);
+  if (sk == 0) w.skinny = nullptr;
   w.total = off;
   return w;
 }
@@ -210,6 +218,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
       g.M = M; g.N = m->lin[li].N; g.K = m->lin[li].K;
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
+      g.skinny_ws = w.skinny;
       ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
       return launch_w4a16_gemm(g, st);
     };
@@ -289,6 +298,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
 
 float* g_partials = nullptr;     // library-owned scratch of qzo_dequant_gemm's sum of squares
 uint32_t g_partials_n = 0;
+float* g_skinny = nullptr;       // library-owned scratch of qzo_dequant_gemm's few-token path
+uint64_t g_skinny_n = 0;
 
 }  // namespace
 
@@ -503,7 +514,19 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
   g.M = M; g.N = N; g.K = K; g.row_base = row_base;
   g.seed_lo = (uint32_t)seed; g.seed_hi = (uint32_t)(seed >> 32);
   g.eps_signed = sign > 0 ? eps : -eps;
-  const uint32_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  const bool skinny = M <= SKINNY_MAX_M;
+  const uint32_t tiles = skinny ? skinny_reduce_blocks(M, N, 0) : ((M + 255) / 256) * ((N + 255) / 256);
+  if (skinny) {     // library-owned scratch for the K-slice partial sums, grown on demand
+    const uint64_t need = skinny_ws_floats(M, N, K);
+    if (g_skinny_n < need) {
+      if (g_skinny) (void)hipFree(g_skinny);
+      g_skinny = nullptr;
+      g_skinny_n = 0;
+      QZO_HIP(hipMalloc((void**)&g_skinny, (size_t)need * sizeof(float)));
+      g_skinny_n = need;
+    }
+    g.skinny_ws = g_skinny;
+  }
   if (sumsq_dev) {
     if (g_partials_n < tiles) {
       if (g_partials) (void)hipFree(g_partials);

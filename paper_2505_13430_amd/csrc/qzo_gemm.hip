@@ -740,6 +740,7 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
     ready = true;
   }
   if (a.M == 0 || a.N == 0) return hipSuccess;
+  if (a.M <= SKINNY_MAX_M && a.skinny_ws) return launch_skinny_gemm(a, a.skinny_ws, st);
   // buffer loads address each operand with 32-bit byte offsets
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;

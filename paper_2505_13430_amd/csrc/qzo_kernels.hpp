@@ -41,6 +41,7 @@ struct GemmArgs {
   const void* resid;    // bf16 [M,N] or null
   void* y;              // bf16 [M,N]
   float* partials;      // EPI_SUMSQ: one float per workgroup
+  float* skinny_ws;     // fp32 scratch of skinny_ws_floats(M, N, K) floats: enables the few-token path (M <= 64)
   uint32_t M, N, K;
   uint32_t row_base;
   uint32_t seed_lo, seed_hi;
@@ -48,6 +49,12 @@ struct GemmArgs {
   uint32_t epi;
 };
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
+// Few-token path (M <= 64): weights streamed once, K split over workgroups, partial sums in ws.
+constexpr uint32_t SKINNY_MAX_M = 64;
+uint32_t skinny_ksplit(uint32_t N, uint32_t K);
+uint64_t skinny_ws_floats(uint32_t M, uint32_t N, uint32_t K);
+uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi);   // EPI_SUMSQ partial count
+hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st);
 // w = uint16 codes [N,K/8]; cb and s as above; N % 8 == 0, K % 128 == 0.
 hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st);
 hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,

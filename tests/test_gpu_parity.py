@@ -133,7 +133,10 @@ def _gemm_case(oracle, M, N, K, seed, eps, sign, row_base=0):
 
 
 @pytest.mark.parametrize("M,N,K", [(300, 520, 384), (256, 256, 128), (1, 8, 128), (513, 264, 1280),
-                                   (64, 1024, 256)])
+                                   (64, 1024, 256), (65, 136, 256),
+                                   # few-token path (M <= 64): ragged rows, odd group counts, K slices
+                                   (7, 264, 384), (16, 520, 1280), (33, 4104, 1152), (64, 136, 4096),
+                                   (32, 8, 128), (5, 12288, 512)])
 def test_perturbed_linear_matches_oracle(oracle, M, N, K):
     for sign in (1, -1):
         got, ssq, ref = _gemm_case(oracle, M, N, K, seed=M + N, eps=1e-3, sign=sign, row_base=11)
@@ -160,6 +163,23 @@ def test_perturbed_linear_sign_and_eps_identities(oracle):
     assert torch.equal(run(0.0, 1), run(0.0, 1, seed=6))      # ... and the seed is irrelevant
     assert not torch.equal(run(1e-3, 1), run(1e-3, -1))
     assert torch.equal(run(1e-3, 1), run(1e-3, 1))            # run-to-run deterministic
+
+
+def test_few_token_path_is_deterministic_and_close_to_the_tile_path(oracle):
+    """The same rows computed as a 64-token call (few-token kernel) and inside a 200-token call
+    (tile kernel) agree to bf16 rounding of the outputs; repeated calls are bit-identical."""
+    x, qp, s = synth.linear_case(200, 520, 1280, seed=9)
+    xd, qd, sd = _dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16)
+    big = torch.zeros((200, 520), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_dequant_gemm(xd, qd, sd, 3, 31, 1e-3, 1, big)
+    outs = []
+    for _ in range(2):
+        y = torch.zeros((64, 520), dtype=torch.bfloat16, device=DEV)
+        qb.qzo_dequant_gemm(xd[:64].contiguous(), qd, sd, 3, 31, 1e-3, 1, y)
+        outs.append(y)
+    assert torch.equal(outs[0], outs[1])
+    a, b = outs[0].float(), big[:64].float()
+    assert ((a - b).abs() <= 2.0 ** -7 * b.abs() + 1e-3 * b.abs().max()).all()
 
 
 def test_boundary_rejects_bad_arguments():
@@ -192,10 +212,14 @@ def _models(oracle, shape, seed, gain=1.0):
     return om, DeviceModel.from_host(shape, om.tensors, om.scales, DEV)
 
 
+FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tokens: one token tile
+       "few_opt": dict(synth.SHAPES["tiny_opt"], batch=2, seq=32)}      # 64 tokens: two token tiles
+
+
 @pytest.mark.parametrize("name,gain", [("tiny", 1.0), ("tiny_opt", 1.0), ("tiny", 4.0), ("tiny_opt", 4.0),
-                                       ("sharp", 4.0)])
+                                       ("sharp", 4.0), ("few_llama", 4.0), ("few_opt", 4.0)])
 def test_forward_matches_oracle(oracle, name, gain):
-    shape = SHARP if name == "sharp" else synth.SHAPES[name]
+    shape = SHARP if name == "sharp" else (FEW[name] if name in FEW else synth.SHAPES[name])
     om, dm = _models(oracle, shape, 1234, gain)
     tok = synth.tokens(shape, 5678)
     tokd = _dev(tok)
@@ -228,9 +252,9 @@ def test_forward_matches_oracle(oracle, name, gain):
     dm.close()
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_opt"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "few_llama", "few_opt"])
 def test_step_matches_oracle(oracle, name):
-    shape = synth.SHAPES[name]
+    shape = FEW[name] if name in FEW else synth.SHAPES[name]
     om, dm = _models(oracle, shape, 1234)
     tok = synth.tokens(shape, 5678)
     tokd = _dev(tok)
