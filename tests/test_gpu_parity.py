@@ -353,14 +353,16 @@ def test_update_at_real_tensor_sizes_bit_exact(oracle, rows, G, row_base):
     assert np.array_equal(_bits(sd.float().cpu().numpy()), _bits(want))
 
 
-@pytest.mark.parametrize("name,seq,eta", [("opt-1.3b", 24, 1e-5), ("llama-2-7b", 16, 1e-7)])
-def test_real_width_one_layer_step(oracle, name, seq, eta):
+@pytest.mark.parametrize("name,batch,seq,eta", [("opt-1.3b", 1, 24, 1e-5), ("llama-2-7b", 1, 16, 1e-7),
+                                                ("llama-2-13b", 1, 16, 1e-7),      # few-token path
+                                                ("opt-1.3b", 3, 24, 1e-5), ("llama-2-7b", 3, 24, 1e-7)])
+def test_real_width_one_layer_step(oracle, name, batch, seq, eta):
     # depth-reduced copy: real widths (incl. the ragged OPT vocabulary), one layer, short batch.
     # d = (l+ - l-)/(2 eps) amplifies the losses' rounding noise 500 times, so the 2e-2 bound on
     # the updated scales is checked at the paper's learning rate for the 7B width (eta 1e-7,
     # Sec. 4.1) and at 1e-5 for the narrower model; the update itself is checked bit for bit
     # against the oracle for the d' the device found.
-    shape = dict(synth.SHAPES[name], n_layers=1, batch=1, seq=seq, max_seq=32)
+    shape = dict(synth.SHAPES[name], n_layers=1, batch=batch, seq=seq, max_seq=32)
     om, dm = _models(oracle, shape, 77)
     tok = synth.tokens(shape, 78)
     ref = oracle.qzo_step(om, tok, seed=3, eps=1e-3, eta=eta, Cthr=100.0)
@@ -418,9 +420,11 @@ def test_codebook_linear_matches_oracle(oracle, M, N, K):
     assert torch.equal(y0, y1)                      # eps = 0: seed and sign are irrelevant
 
 
-def test_codebook_model_step(oracle):
-    shape = dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48,
-                 batch=3, seq=40)
+@pytest.mark.parametrize("shape,eta", [
+    (dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48, batch=3, seq=40), 1e-3),
+    # Llama-2-13B widths, one layer, short batch (a smaller step: d carries the losses' noise x 500)
+    (dict(synth.SHAPES["llama-2-13b"], n_layers=1, batch=1, seq=16, max_seq=32), 1e-5)], ids=["tiny", "13b-width"])
+def test_codebook_model_step(oracle, shape, eta):
     table = synth.codebook_tensor_table(shape, 31)
     om = oracle.build_codebook_model(shape, table)
     dm = DeviceModel.from_host_codebook(shape, table, DEV)
@@ -440,13 +444,13 @@ def test_codebook_model_step(oracle):
     floor_rms = math.sqrt(((exact_hid - ref_hid) ** 2).mean())
     assert math.sqrt((err ** 2).mean()) <= 2 * floor_rms + 2e-3 * rms, (math.sqrt((err ** 2).mean()) / rms, floor_rms / rms)
     assert err.max() <= 2 * np.abs(exact_hid - ref_hid).max() + 2e-2 * rms
-    ref = oracle.qzo_step(om, tok, seed=4, eps=1e-3, eta=1e-3, Cthr=100.0)
-    res = qb.read_step_result(dm.step(_dev(tok), 4, 1e-3, 1e-3, 100.0))
+    ref = oracle.qzo_step(om, tok, seed=4, eps=1e-3, eta=eta, Cthr=100.0)
+    res = qb.read_step_result(dm.step(_dev(tok), 4, 1e-3, eta, 100.0))
     assert res["status"] == 0
     for k in ("loss_plus", "loss_minus"):
         assert abs(res[k] - ref[k]) <= 2e-2 * abs(ref[k]), (k, res[k], ref[k])
     got = dm.scales.float().cpu().numpy()
     assert (np.abs(got - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-6).all()
-    assert np.array_equal(_bits(got), _bits(oracle.update_scales(om, 4, 1e-3, res["d_clipped"])))
+    assert np.array_equal(_bits(got), _bits(oracle.update_scales(om, 4, eta, res["d_clipped"])))
     print("codebook d gpu", res["d"], "oracle", ref["d"], "changed", float((got != om.scales).mean()))
     dm.close()
