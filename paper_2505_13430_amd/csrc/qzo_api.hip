@@ -122,7 +122,11 @@ qzo_status build_plan(const Linear* lin, int n_lin, uint32_t n_layers, UpdPlan& 
 
 Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   const qzo_model_config& c = m->cfg;
-  const uint64_t M = (uint64_t)batch * seq, d = c.d_model, F = c.d_ffn;
+  // With very few tokens qzo_step stacks its two perturbed passes into one forward
+  // over 2 * batch sequences (the int4 weights are then read once per step).
+  const uint64_t M1 = (uint64_t)batch * seq;
+  const bool stack = M1 <= SKINNY_MAX_M_DUAL && c.quant == 0;
+  const uint64_t M = stack ? 2 * M1 : M1, d = c.d_model, F = c.d_ffn;
   const uint64_t n_slices = ((c.vocab + 255) / 256) * 4;
   Workspace w;
   uint64_t off = 0;
@@ -143,7 +147,7 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   w.losses = (float*)take(256);
   // few-token path of the int4 GEMM: fp32 partial sums of the K slices of the largest linear
   uint64_t sk = 0;
-  if (M <= SKINNY_MAX_M && c.quant == 0)
+  if (M1 <= SKINNY_MAX_M && c.quant == 0)
     for (int i = 0; i < 4; ++i)
       sk = std::max<uint64_t>(sk, skinny_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.skinny = (float*)take(sk * 4);
@@ -191,10 +195,13 @@ struct ProfScope {
 enum { PK_W4GEMM = 0, PK_LMHEAD = 1, PK_ATTN = 2, PK_UPDATE = 3, PK_OTHER = 4, PK_COUNT = 5 };
 
 // The decoder forward with every quantized linear perturbed by sign*eps*z.
-qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t seq, uint64_t seed,
+// n_pass = 2 (few tokens, int4 only): both passes of a step stacked, rows [0,M1) perturbed by
+// +eps_signed and rows [M1, 2 M1) by -eps_signed; their losses go to loss_out and loss_out2.
+qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t seq, uint64_t seed,
                    float eps_signed, const Workspace& w, float* loss_out, hipStream_t st,
-                   void* hidden_out = nullptr) {
+                   void* hidden_out = nullptr, uint32_t n_pass = 1, float* loss_out2 = nullptr) {
   const qzo_model_config& c = m->cfg;
+  const uint32_t batch = batch1 * n_pass, M1 = batch1 * seq;
   const uint32_t M = batch * seq, d = c.d_model, F = c.d_ffn, H = c.n_heads, dh = d / H;
   const bool llama = c.arch == 0;
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
@@ -202,7 +209,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
 
   {
     ProfScope ps(PK_OTHER, 0, st);
-    QZO_HIP(launch_embed(tok, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
+    QZO_HIP(launch_embed(tok, M1, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
   }
   const double attn_flops = 2.0 * batch * H * (double)seq * seq * dh;   // causal: half of 4 B H S^2 dh
   auto other = [&](hipError_t e) { return e; };
@@ -215,7 +222,9 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
       GemmArgs g = {};
       g.x = x; g.w = wq; g.s = arena + (layer_off + m->lin[li].s_off) * 2;
       g.bias = bias; g.resid = resid; g.y = y;
-      g.M = M; g.N = m->lin[li].N; g.K = m->lin[li].K;
+      g.M = M1; g.N = m->lin[li].N; g.K = m->lin[li].K;
+      g.dual = n_pass == 2;
+      if (n_pass == 1) g.M = M;
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
       g.skinny_ws = w.skinny;
@@ -286,13 +295,16 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch, uint32_t se
   if (hidden_out)
     QZO_HIP(hipMemcpyAsync(hidden_out, w.a, (size_t)M * d * 2, hipMemcpyDeviceToDevice, st));
   CeArgs ce = {};
-  ce.x = w.a; ce.w = lm_head; ce.tok = tok; ce.part = w.ce_part; ce.tgt = w.tgt;
+  ce.x = w.a; ce.w = lm_head; ce.tok = tok; ce.tok_rows = M1; ce.part = w.ce_part; ce.tgt = w.tgt;
   ce.M = M; ce.V = c.vocab; ce.K = d; ce.S = seq; ce.n_slices = ((c.vocab + 255) / 256) * 4;
   {
     ProfScope ps(PK_LMHEAD, 2.0 * M * (double)c.vocab * d, st);
     QZO_HIP(launch_lmhead_ce(ce, st));
   }
-  QZO_HIP(launch_ce_reduce(w.ce_part, w.tgt, M, seq, ce.n_slices, w.rowloss, loss_out, st));
+  QZO_HIP(launch_ce_reduce(w.ce_part, w.tgt, M1, seq, ce.n_slices, w.rowloss, loss_out, st));
+  if (n_pass == 2)
+    QZO_HIP(launch_ce_reduce(w.ce_part + (size_t)M1 * ce.n_slices * 2, w.tgt + M1, M1, seq, ce.n_slices,
+                             w.rowloss + M1, loss_out2, st));
   return QZO_OK;
 }
 
@@ -447,10 +459,16 @@ qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uin
   if (!std::isfinite(eps) || !std::isfinite(eta)) return fail(QZO_ERR_ARG, "eps/eta not finite");
   hipStream_t s = (hipStream_t)stream;
   Workspace w = carve(m, batch, seq, workspace_dev);
-  st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s);
-  if (st != QZO_OK) return st;
-  st = forward(m, tokens_dev, batch, seq, seed, -eps, w, w.losses + 1, s);
-  if (st != QZO_OK) return st;
+  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && m->cfg.quant == 0) {
+    // few tokens: one forward over both passes, the weights are read once
+    st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s, nullptr, 2, w.losses + 1);
+    if (st != QZO_OK) return st;
+  } else {
+    st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s);
+    if (st != QZO_OK) return st;
+    st = forward(m, tokens_dev, batch, seq, seed, -eps, w, w.losses + 1, s);
+    if (st != QZO_OK) return st;
+  }
   QZO_HIP(launch_spsa_clip(w.losses, eps, clip, result_dev, s));
   {
     ProfScope ps(PK_UPDATE, 4.0 * (double)m->n_scales, s);

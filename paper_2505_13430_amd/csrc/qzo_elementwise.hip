@@ -259,14 +259,16 @@ hipError_t launch_debug_dequant(const void* q, const void* s, uint32_t row_base,
 }
 
 // -------------------------------------------------------- embedding -------
-__global__ void embed_kernel(const int32_t* __restrict__ tok, const bf16_t* __restrict__ te,
+// row m embeds tok[m % tok_rows] (the same batch may be stacked twice)
+__global__ void embed_kernel(const int32_t* __restrict__ tok, uint32_t tok_rows,
+                             const bf16_t* __restrict__ te,
                              const bf16_t* __restrict__ pe, uint32_t M, uint32_t S, uint32_t d,
                              bf16_t* __restrict__ h) {
   const uint32_t cpr = d >> 3;
   const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (u >= (uint64_t)M * cpr) return;
   const uint32_t m = (uint32_t)(u / cpr), c = (uint32_t)(u % cpr);
-  uint4 v = *reinterpret_cast<const uint4*>(te + (uint64_t)tok[m] * d + c * 8);
+  uint4 v = *reinterpret_cast<const uint4*>(te + (uint64_t)tok[m % tok_rows] * d + c * 8);
   if (pe) {
     uint4 p = *reinterpret_cast<const uint4*>(pe + (uint64_t)(m % S) * d + c * 8);
     uint32_t a[4] = {v.x, v.y, v.z, v.w}, b[4] = {p.x, p.y, p.z, p.w}, o[4];
@@ -278,10 +280,10 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, const bf16_t* __re
   }
   *reinterpret_cast<uint4*>(h + (uint64_t)m * d + c * 8) = v;
 }
-hipError_t launch_embed(const int32_t* tok, const void* tok_emb, const void* pos_emb, uint32_t M,
+hipError_t launch_embed(const int32_t* tok, uint32_t tok_rows, const void* tok_emb, const void* pos_emb, uint32_t M,
                         uint32_t S, uint32_t d, void* h, hipStream_t st) {
   uint64_t units = (uint64_t)M * (d >> 3);
-  embed_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(tok, (const bf16_t*)tok_emb,
+  embed_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(tok, tok_rows, (const bf16_t*)tok_emb,
                                                                (const bf16_t*)pos_emb, M, S, d,
                                                                (bf16_t*)h);
   return hipGetLastError();

@@ -114,7 +114,7 @@ struct CeEpilogue {
   const int32_t* tok;
   float* part;
   float* tgt;
-  uint32_t S, n_slices;
+  uint32_t S, n_slices, tok_rows;
 };
 
 // NWN = wavefronts along N (2 along M): 4 -> 512 threads, each wavefront 128x64;
@@ -673,7 +673,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     for (int i = 0; i < 4; ++i) {
       const uint32_t m = m0 + wm * 128 + i * 32 + frow;
       const bool has_target = m < a.M && (m % ce.S) != ce.S - 1;
-      const uint32_t target = has_target ? (uint32_t)ce.tok[m + 1] : 0xffffffffu;
+      const uint32_t target = has_target ? (uint32_t)ce.tok[(m % ce.tok_rows) + 1] : 0xffffffffu;
       float mx = -INFINITY;
 #pragma unroll
       for (int j = 0; j < TJ; ++j)
@@ -741,10 +741,11 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   }
   if (a.M == 0 || a.N == 0) return hipSuccess;
   if (a.M <= SKINNY_MAX_M && a.skinny_ws) return launch_skinny_gemm(a, a.skinny_ws, st);
+  if (a.dual) return hipErrorInvalidValue;          // only the few-token path stacks the two passes
   // buffer loads address each operand with 32-bit byte offsets
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;
-  CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1};
+  CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
   gemm_kernel<0, false, W4_NWN, W4_PIPE>
       <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
@@ -761,7 +762,7 @@ hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 4 >= (1ull << 31))
     return hipErrorInvalidValue;
-  CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1};
+  CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
   gemm_kernel<2, false, 4, 1><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES + 1024, st>>>(a, ce);
   return hipGetLastError();
 }
@@ -777,7 +778,7 @@ hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
     return hipErrorInvalidValue;
   GemmArgs a = {};
   a.x = c.x; a.w = c.w; a.M = c.M; a.N = c.V; a.K = c.K;
-  CeEpilogue ce = {c.tok, c.part, c.tgt, c.S, c.n_slices};
+  CeEpilogue ce = {c.tok, c.part, c.tgt, c.S, c.n_slices, c.tok_rows ? c.tok_rows : c.M};
   gemm_kernel<1, true, 4, 0><<<gemm_workgroups(c.M, c.V), 512, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
 }

@@ -41,7 +41,8 @@ struct GemmArgs {
   const void* resid;    // bf16 [M,N] or null
   void* y;              // bf16 [M,N]
   float* partials;      // EPI_SUMSQ: one float per workgroup
-  float* skinny_ws;     // fp32 scratch of skinny_ws_floats(M, N, K) floats: enables the few-token path (M <= 64)
+  float* skinny_ws;     // fp32 scratch of skinny_ws_floats(rows, N, K) floats: enables the few-token path (M <= 64)
+  uint32_t dual;        // few-token path only: x, y, resid hold 2 M rows; rows [0,M) use +eps_signed, [M,2M) -eps_signed
   uint32_t M, N, K;
   uint32_t row_base;
   uint32_t seed_lo, seed_hi;
@@ -51,6 +52,7 @@ struct GemmArgs {
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
 // Few-token path (M <= 64): weights streamed once, K split over workgroups, partial sums in ws.
 constexpr uint32_t SKINNY_MAX_M = 64;
+constexpr uint32_t SKINNY_MAX_M_DUAL = 32;   // per sign, when both perturbed passes share one launch
 uint32_t skinny_ksplit(uint32_t N, uint32_t K);
 uint64_t skinny_ws_floats(uint32_t M, uint32_t N, uint32_t K);
 uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi);   // EPI_SUMSQ partial count
@@ -68,7 +70,8 @@ uint32_t gemm_workgroups(uint32_t M, uint32_t N);
 struct CeArgs {
   const void* x;        // bf16 [M,K]  final hidden states
   const void* w;        // bf16 [V,K]  lm_head
-  const int32_t* tok;   // [B,S]
+  const int32_t* tok;   // [B,S]; row m takes its target from tok[(m % tok_rows) + 1]
+  uint32_t tok_rows;    // B*S (M is a multiple of it: the same batch may be stacked twice)
   float* part;          // [M, n_slices, 2]
   float* tgt;           // [M]
   uint32_t M, V, K, S;
@@ -82,7 +85,7 @@ hipError_t launch_ce_reduce(const float* part, const float* tgt, uint32_t M, uin
 
 hipError_t launch_sum_partials(const float* partials, uint32_t n, float* out, hipStream_t st);
 
-hipError_t launch_embed(const int32_t* tok, const void* tok_emb, const void* pos_emb, uint32_t M,
+hipError_t launch_embed(const int32_t* tok, uint32_t tok_rows, const void* tok_emb, const void* pos_emb, uint32_t M,
                         uint32_t S, uint32_t d, void* h, hipStream_t st);
 hipError_t launch_rmsnorm(const void* x, const void* gain, uint32_t M, uint32_t d, float eps,
                           void* y, hipStream_t st);

@@ -12,6 +12,11 @@
 // k-step is {64 half + 32 c + 8 j + e}: any order is fine as long as both operands
 // agree.  Partial sums of the K slices go to a scratch buffer in fp32 and a second
 // kernel adds them in a fixed order (deterministic) and applies the epilogue.
+//
+// Dual mode: the +eps and the -eps pass of one QZO step read the same int4 weights
+// and the same noise, so for very few tokens they share one launch.  X and Y then
+// hold the two passes stacked (rows [0,M) and [M,2M)); a weight dword is converted
+// twice (with s + eps z and s - eps z) and each token tile multiplies with its own.
 #include "qzo_device.hpp"
 #include "qzo_kernels.hpp"
 
@@ -46,10 +51,12 @@ __device__ __forceinline__ uint32_t x_lds_off(uint32_t row, uint32_t chunk) {   
   return row * 256u + ((chunk ^ (row & 15u)) << 4);
 }
 
-// MT = 32-token tiles (1 or 2).  grid = (ceil(N/128), ksplit); part is [ksplit, M, N] fp32.
-template <int MT>
+// MT = 32-token tiles (1 or 2).  grid = (ceil(N/128), ksplit); part is [ksplit, rows, N] fp32
+// with rows = M, or 2 M in dual mode (MT = 2: tile 0 is the +eps pass, tile 1 the -eps pass).
+template <int MT, bool DUAL>
 __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmArgs a, float* __restrict__ part,
                                                              uint32_t groups_per_split) {
+  static_assert(!DUAL || MT == 2, "dual mode: one token tile per pass");
   __shared__ __attribute__((aligned(16))) unsigned char xs[2][MT * 32 * 256];
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t lrow = lane & 31u, half = lane >> 5;
@@ -62,6 +69,10 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
   const bf16_t* x = (const bf16_t*)a.x;
 
   // activation staging: a group's block is MT*32 rows x 16 chunks; a thread moves MT*2 chunks
+  // LDS row -> row of x: clamped to the last token; in dual mode LDS rows 32.. are the second pass
+  auto xrow = [&](uint32_t row) {
+    return DUAL ? (row >> 5) * a.M + min(row & 31u, a.M - 1) : min(row, a.M - 1);
+  };
   // Memory returns in issue order, so whatever is consumed must be the oldest request in
   // flight: activations and weights are requested SK_DEPTH groups ahead, interleaved in
   // the order in which they are used (block g+1 goes to LDS, then the weights of group g).
@@ -72,7 +83,7 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
     const uint32_t gx_ = min((uint32_t)(G_), ngrp - 1);                                      \
     _Pragma("unroll") for (int i = 0; i < NX; ++i) {                                         \
       const uint32_t c = t + 256u * i, row = c >> 4, ch = c & 15u;                           \
-      xr[SLOT][i] = *reinterpret_cast<const u32x4*>(x + (uint64_t)min(row, a.M - 1) * K + gx_ * 128u + ch * 8); \
+      xr[SLOT][i] = *reinterpret_cast<const u32x4*>(x + (uint64_t)xrow(row) * K + gx_ * 128u + ch * 8); \
     }                                                                                        \
   } while (0)
 #define QZO_SK_XSTORE(SLOT, BUF)                                                             \
@@ -110,7 +121,7 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
 #pragma unroll
   for (int i = 0; i < NX; ++i) {
     const uint32_t c = t + 256u * i, row = c >> 4, ch = c & 15u;
-    x0[i] = *reinterpret_cast<const u32x4*>(x + (uint64_t)min(row, a.M - 1) * K + g0 * 128u + ch * 8);
+    x0[i] = *reinterpret_cast<const u32x4*>(x + (uint64_t)xrow(row) * K + g0 * 128u + ch * 8);
   }
 #pragma unroll
   for (int d = 0; d < SK_DEPTH; ++d) {        // slot of block g: (g - g0) % SK_DEPTH
@@ -145,17 +156,21 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
           normal_pair(p == 0 ? zw[0] : (p == 1 ? zw[1] : (p == 2 ? zw[2] : zw[3])), z_even, z_odd);
         }
         fresh = false;
-        const float se = __builtin_fmaf(a.eps_signed, (g & 1u) ? z_odd : z_even, __uint_as_float(sq[d] << 16));
+        const float zz = (g & 1u) ? z_odd : z_even, s0 = __uint_as_float(sq[d] << 16);
+        const float se = __builtin_fmaf(a.eps_signed, zz, s0);
         const float se512 = 512.0f * se, m8se = -8.0f * se;
+        const float sn = __builtin_fmaf(-a.eps_signed, zz, s0);     // dual mode: the other pass
+        const float sn512 = 512.0f * sn, m8sn = -8.0f * sn;
         const u32x4 w0 = wq[d][0], w1 = wq[d][1];
         const uint32_t wd[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
 #pragma unroll
         for (int j = 0; j < 8; ++j) {           // k-step j: k = 64 half + 8 j + e of the group
           const bf16x8 af = dequant8_frag(wd[j], se512, m8se);
+          const bf16x8 an = DUAL ? dequant8_frag(wd[j], sn512, m8sn) : af;
 #pragma unroll
           for (int m = 0; m < MT; ++m) {
             const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xs[buf] + x_lds_off(m * 32 + lrow, half * 8 + j));
-            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, xf, acc[m], 0, 0, 0);
+            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((DUAL && m == 1) ? an : af, xf, acc[m], 0, 0, 0);
           }
         }
         // refill the slot SK_DEPTH groups ahead, after its last use so that the loads can
@@ -172,9 +187,10 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
   const uint32_t nb = blockIdx.x * SK_ROWS + wave * 32 + 4 * half;
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
-    const uint32_t tok = m * 32 + lrow;
-    if (tok < a.M) {
-      float* dst = part + ((uint64_t)blockIdx.y * a.M + tok) * a.N;
+    const uint32_t rows = DUAL ? 2 * a.M : a.M;
+    const uint32_t tok = DUAL ? m * a.M + lrow : m * 32 + lrow;          // row of the stacked output
+    if (DUAL ? lrow < a.M : tok < a.M) {
+      float* dst = part + ((uint64_t)blockIdx.y * rows + tok) * a.N;
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         const uint32_t nn = nb + 8 * b;
@@ -254,8 +270,8 @@ uint32_t skinny_ksplit(uint32_t N, uint32_t K) {
   const uint32_t per = (ngrp + ks - 1) / ks;
   return (ngrp + per - 1) / per;                // drop empty slices
 }
-uint64_t skinny_ws_floats(uint32_t M, uint32_t N, uint32_t K) {
-  return (uint64_t)skinny_ksplit(N, K) * M * N;
+uint64_t skinny_ws_floats(uint32_t rows, uint32_t N, uint32_t K) {     // rows = M, or 2 M in dual mode
+  return (uint64_t)skinny_ksplit(N, K) * rows * N;
 }
 uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi) {
   const uint32_t NO = (epi & EPI_SWIGLU) ? N >> 1 : N;
@@ -266,16 +282,20 @@ uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi) {
 // floats; with EPI_SUMSQ a.partials holds skinny_reduce_blocks floats.
 hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
-  if (a.M > 64 || !ws) return hipErrorInvalidValue;
+  if (a.M > SKINNY_MAX_M || (a.dual && a.M > SKINNY_MAX_M_DUAL) || !ws) return hipErrorInvalidValue;
   const uint32_t ks = skinny_ksplit(a.N, a.K), ngrp = a.K >> 7, per = (ngrp + ks - 1) / ks;
   dim3 grid((a.N + SK_ROWS - 1) / SK_ROWS, ks);
-  if (a.M <= 32)
-    skinny_gemm_kernel<1><<<grid, 256, 0, st>>>(a, ws, per);
+  if (a.dual)
+    skinny_gemm_kernel<2, true><<<grid, 256, 0, st>>>(a, ws, per);
+  else if (a.M <= 32)
+    skinny_gemm_kernel<1, false><<<grid, 256, 0, st>>>(a, ws, per);
   else
-    skinny_gemm_kernel<2><<<grid, 256, 0, st>>>(a, ws, per);
+    skinny_gemm_kernel<2, false><<<grid, 256, 0, st>>>(a, ws, per);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  skinny_reduce_kernel<<<skinny_reduce_blocks(a.M, a.N, a.epi), 256, 0, st>>>(a, ws, ks);
+  GemmArgs r = a;                               // the reduction sees the stacked rows as one matrix
+  if (a.dual) r.M = 2 * a.M;
+  skinny_reduce_kernel<<<skinny_reduce_blocks(r.M, r.N, r.epi), 256, 0, st>>>(r, ws, ks);
   return hipGetLastError();
 }
 

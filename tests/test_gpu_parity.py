@@ -277,6 +277,20 @@ def test_step_matches_oracle(oracle, name):
     dm.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt"])
+def test_stacked_passes_equal_separate_passes(oracle, name):
+    """With at most 32 tokens qzo_step runs both perturbed passes as one stacked forward (the
+    weights are read once); its losses are bit-identical to two separate forward passes."""
+    shape = dict(synth.SHAPES[name], batch=2, seq=13)
+    om, dm = _models(oracle, shape, 1234, 4.0)
+    tokd = _dev(synth.tokens(shape, 5678))
+    res = qb.read_step_result(dm.step(tokd, 21, 1e-3, 0.0, 100.0))       # eta = 0: scales untouched
+    lp = float(dm.forward_loss(tokd, 21, 1e-3, 1).item())
+    lm = float(dm.forward_loss(tokd, 21, 1e-3, -1).item())
+    assert res["loss_plus"] == lp and res["loss_minus"] == lm and lp != lm
+    dm.close()
+
+
 def test_step_special_cases(oracle):
     shape = synth.SHAPES["tiny"]
     om, dm = _models(oracle, shape, 1234)
