@@ -216,7 +216,7 @@ def main():
                      "unit": "TFLOP/s", "frac": gemm_flops_s / PEAK_BF16_MFMA,
                      "traffic": measured_traffic("traffic_bytes_per_launch_gemm_qkv") if main_cfg else None,
                      "traffic_note": "HBM bytes of one qkv-shaped launch (8192x12288x4096), FETCH_SIZE + "
-                                     "WRITE_SIZE scaled by a plain copy; algorithmic 2.93e8",
+                                     "WRITE_SIZE scaled by a plain copy; algorithmic 2.94e8",
                      "launches": g["launches"], "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
                      "flops_per_launch_avg": g["work"] / max(g["launches"], 1),
                      "mfma_only_measured_TFLOPs": mfma_ceiling(torch, qb)},

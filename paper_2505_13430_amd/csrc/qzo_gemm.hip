@@ -46,9 +46,12 @@ uint32_t gemm_workgroups(uint32_t M, uint32_t N) {
 // Persistent workgroups: the grid is one workgroup per compute unit (or fewer when
 // there are fewer tiles) and every workgroup walks a list of output tiles.
 // Hardware deals consecutive workgroup ids to the eight XCDs in turn; each XCD
-// gets one contiguous eighth of a tile order in which groups of 8 M-tiles sweep
+// gets one contiguous eighth of a tile order in which groups of WALK_M M-tiles sweep
 // the N-tiles, and its workgroups take consecutive entries of that eighth, so the
 // tiles in flight on one XCD share a few A and B row-panels in that XCD's L2.
+// M-tiles per group of the walk.  With 32 tiles resident per XCD, groups of 4 (or 2) minimise
+// the bytes streamed from HBM (activation panel re-read 6 times, int4 panel 8 times).
+constexpr uint32_t WALK_M = 4;
 struct TileWalk {
   uint32_t tiles_m, tiles_n, total, per, xcd, slot, stride;
 };
@@ -68,10 +71,10 @@ __device__ __forceinline__ bool tile_walk_get(const TileWalk& w, uint32_t& tm, u
   if (w.slot >= w.per) return false;
   const uint32_t id = w.xcd * w.per + w.slot;
   if (id >= w.total) return false;
-  const uint32_t width = 8u * w.tiles_n;
+  const uint32_t width = WALK_M * w.tiles_n;
   const uint32_t group = id / width;
-  const uint32_t first = group * 8u;
-  const uint32_t gsz = min(w.tiles_m - first, 8u);
+  const uint32_t first = group * WALK_M;
+  const uint32_t gsz = min(w.tiles_m - first, WALK_M);
   const uint32_t in = id - group * width;
   tm = first + in % gsz;
   tn = in / gsz;
