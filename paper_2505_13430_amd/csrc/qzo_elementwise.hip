@@ -419,31 +419,6 @@ hipError_t launch_rope(void* qkv, const float* table, uint32_t B, uint32_t S, ui
   return hipGetLastError();
 }
 
-// ----------------------------------------------------------- SwiGLU -------
-__global__ void swiglu_kernel(const bf16_t* __restrict__ gu, uint32_t M, uint32_t F,
-                              bf16_t* __restrict__ out) {
-  const uint32_t cpr = F >> 3;
-  const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= (uint64_t)M * cpr) return;
-  const uint32_t m = (uint32_t)(u / cpr), c = (uint32_t)(u % cpr);
-  uint4 vg = *reinterpret_cast<const uint4*>(gu + (uint64_t)m * 2 * F + c * 8);
-  uint4 vu = *reinterpret_cast<const uint4*>(gu + (uint64_t)m * 2 * F + F + c * 8);
-  uint32_t g[4] = {vg.x, vg.y, vg.z, vg.w}, up[4] = {vu.x, vu.y, vu.z, vu.w}, o[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    float g0 = __uint_as_float(g[j] << 16), g1 = __uint_as_float(g[j] & 0xffff0000u);
-    float u0 = __uint_as_float(up[j] << 16), u1 = __uint_as_float(up[j] & 0xffff0000u);
-    o[j] = pack_bf16x2(g0 / (1.0f + expf(-g0)) * u0, g1 / (1.0f + expf(-g1)) * u1);
-  }
-  *reinterpret_cast<uint4*>(out + (uint64_t)m * F + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
-}
-hipError_t launch_swiglu(const void* gu, uint32_t M, uint32_t F, void* out, hipStream_t st) {
-  uint64_t units = (uint64_t)M * (F >> 3);
-  swiglu_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>((const bf16_t*)gu, M, F,
-                                                                (bf16_t*)out);
-  return hipGetLastError();
-}
-
 // --------------------------------------------- cross-entropy reduction ----
 // part[m][slice] = (max, sum exp(l - max)) over the slice's columns.  One
 // wavefront merges a row: lse - target logit; rows at the last position of a

@@ -95,7 +95,6 @@ hipError_t launch_rope_table(float* table, uint32_t max_seq, uint32_t dh, float 
                              hipStream_t st);
 hipError_t launch_rope(void* qkv, const float* table, uint32_t B, uint32_t S, uint32_t d,
                        uint32_t n_heads, hipStream_t st);
-hipError_t launch_swiglu(const void* gu, uint32_t M, uint32_t F, void* out, hipStream_t st);
 hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_heads,
                             uint32_t dh, void* out, hipStream_t st);
 hipError_t launch_spsa_clip(const float* losses, float eps, float clip, qzo_step_result* res,
