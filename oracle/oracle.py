@@ -121,6 +121,47 @@ def dequant(qp, s, seed, row_base, eps_signed, group=128, to_bf16=False):
     return out
 
 
+def dequant_zp(qp, s, zp, seed, row_base, eps_signed, group=128, to_bf16=False):
+    """Asymmetric groups: W_eff[n,k] = (s + eps z) * (u[n,k] - zp[n,k/group])."""
+    qp = np.ascontiguousarray(qp, dtype=np.uint8)
+    s = _f32(s)
+    zp = np.ascontiguousarray(zp, dtype=np.uint8)
+    N, K = qp.shape[0], qp.shape[1] * 2
+    out = np.zeros((N, K), dtype=np.float32)
+    lib().orc_dequant_zp(_p(qp), _p(s), _p(zp), C.c_uint64(N), C.c_uint64(K), C.c_uint32(group),
+                         C.c_uint64(seed), C.c_uint32(row_base), C.c_float(eps_signed),
+                         C.c_int(1 if to_bf16 else 0), _p(out))
+    return out
+
+
+def qlinear_zp(x, qp, s_eff, zp, group=128):
+    x = _f64(x)
+    qp = np.ascontiguousarray(qp, dtype=np.uint8)
+    s_eff = _f64(s_eff)
+    zp = np.ascontiguousarray(zp, dtype=np.uint8)
+    M, K = x.shape
+    N = qp.shape[0]
+    y = np.zeros((M, N), dtype=np.float64)
+    lib().orc_qlinear_zp(_p(x), C.c_uint64(M), C.c_uint64(K), _p(qp), _p(s_eff), _p(zp), C.c_uint64(N),
+                         C.c_uint32(group), _p(y))
+    return y
+
+
+def repack_kmajor(qweight, qzeros, scales_f16, zero_add, group=128):
+    """K-major checkpoint layout -> (nibbles [N,K/2], zero-points [N,G], bf16 scales [N,G])."""
+    qweight = np.ascontiguousarray(qweight, dtype=np.uint32)
+    qzeros = np.ascontiguousarray(qzeros, dtype=np.uint32)
+    sc = _f32(scales_f16)
+    K, N = qweight.shape[0] * 8, qweight.shape[1]
+    G = K // group
+    qp = np.zeros((N, K // 2), dtype=np.uint8)
+    zp = np.zeros((N, G), dtype=np.uint8)
+    s = np.zeros((N, G), dtype=np.float32)
+    lib().orc_repack_kmajor(_p(qweight), _p(qzeros), _p(sc), C.c_uint64(N), C.c_uint64(K), C.c_uint32(group),
+                            C.c_uint32(zero_add), _p(qp), _p(zp), _p(s))
+    return qp, zp, s
+
+
 def qlinear(x, qp, s_eff, group=128, bias=None):
     x = _f64(x)
     qp = np.ascontiguousarray(qp, dtype=np.uint8)

@@ -282,6 +282,65 @@ void orc_dequant(const uint8_t* qp, const float* s, uint64_t N, uint64_t K, uint
     }
 }
 
+// ---- asymmetric 4-bit groups (zero-points): the format of the 4-bit checkpoints the
+// paper fine-tunes (Sec. 4.1: GPTQ, group 128).  W[n,k] = s[n,g] * (u[n,k] - zp[n,g]) with the
+// stored nibble u in 0..15 and an integer zero-point zp in 0..15 per (row, group); Eq. 4-5 with
+// wbar = u - zp.  zp = 8 is the symmetric format above.
+void orc_dequant_zp(const uint8_t* qp, const float* s, const uint8_t* zp, uint64_t N, uint64_t K,
+                    uint32_t group, uint64_t seed, uint32_t row_base, float eps_signed, int to_bf16,
+                    float* w_eff) {
+  uint64_t G = K / group;
+  for (uint64_t n = 0; n < N; ++n)
+    for (uint64_t k = 0; k < K; ++k) {
+      uint64_t g = k / group;
+      float z = scale_normal(seed, 0u, (uint32_t)(row_base + n), (uint32_t)g);
+      float se = std::fmaf(eps_signed, z, s[n * G + g]);
+      int u = unpack_q(qp, K, n, k) + 8;                       // the stored nibble
+      float v = se * (float)(u - (int)zp[n * G + g]);
+      w_eff[n * K + k] = to_bf16 ? bf16_rne(v) : v;
+    }
+}
+void orc_qlinear_zp(const double* x, uint64_t M, uint64_t K, const uint8_t* qp, const double* s_eff,
+                    const uint8_t* zp, uint64_t N, uint32_t group, double* y) {
+  uint64_t G = K / group;
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < (int64_t)N; ++n) {
+    std::vector<double> wrow(K);
+    for (uint64_t k = 0; k < K; ++k) {
+      int u = unpack_q(qp, K, n, k) + 8;
+      wrow[k] = s_eff[n * G + k / group] * (double)(u - (int)zp[n * G + k / group]);
+    }
+    for (uint64_t m = 0; m < M; ++m) {
+      double acc = 0.0;
+      const double* xr = x + m * K;
+      for (uint64_t k = 0; k < K; ++k) acc += xr[k] * wrow[k];
+      y[m * N + n] = acc;
+    }
+  }
+}
+// Repacking from the K-major checkpoint layout: qweight int32 [K/8, N], word (kk, n) holding
+// the nibbles of k = 8 kk .. 8 kk + 7 of output n, lowest nibble first; qzeros int32 [G, N/8],
+// word (g, nn) holding the zero-points of n = 8 nn .. 8 nn + 7; scales fp16 values [G, N].
+// Out: nibbles [N, K/2] (low nibble = even k), zero-points [N, G] (stored value + zero_add,
+// masked to 4 bits), scales [N, G] rounded to bf16.
+void orc_repack_kmajor(const uint32_t* qweight, const uint32_t* qzeros, const float* scales_f16,
+                       uint64_t N, uint64_t K, uint32_t group, uint32_t zero_add, uint8_t* qp,
+                       uint8_t* zp, float* s_bf16) {
+  uint64_t G = K / group;
+  for (uint64_t n = 0; n < N; ++n) {
+    for (uint64_t k = 0; k < K; k += 2) {
+      uint32_t lo = (qweight[(k / 8) * N + n] >> (4 * (k % 8))) & 15u;
+      uint32_t hi = (qweight[((k + 1) / 8) * N + n] >> (4 * ((k + 1) % 8))) & 15u;
+      qp[n * (K / 2) + k / 2] = (uint8_t)(lo | (hi << 4));
+    }
+    for (uint64_t g = 0; g < G; ++g) {
+      uint32_t z = (qzeros[g * (N / 8) + n / 8] >> (4 * (n % 8))) & 15u;
+      zp[n * G + g] = (uint8_t)((z + zero_add) & 15u);
+      s_bf16[n * G + g] = bf16_rne(scales_f16[g * N + n]);
+    }
+  }
+}
+
 // Y[m,n] = sum_k X[m,k] * s_eff[n,k/group] * wbar[n,k] (+ bias[n]).
 void orc_qlinear(const double* x, uint64_t M, uint64_t K, const uint8_t* qp, const double* s_eff,
                  uint64_t N, uint32_t group, const float* bias, double* y) {

@@ -116,6 +116,18 @@ def linear_case(M: int, N: int, K: int, seed: int, group: int = GROUP):
     return x, qp, s
 
 
+def kmajor_case(N: int, K: int, seed: int, group: int = GROUP):
+    """An asymmetric 4-bit linear in the K-major checkpoint layout: qweight uint32 [K/8, N]
+    (8 consecutive k per word, lowest nibble first), qzeros uint32 [K/group, N/8] (8 consecutive
+    n per word), scales [K/group, N] ~ U(0.005, 0.02) exactly representable in fp16.  All nibbles
+    uniform."""
+    rng = np.random.default_rng(seed)
+    qweight = rng.integers(0, 1 << 32, size=(K // 8, N), dtype=np.uint64).astype(np.uint32)
+    qzeros = rng.integers(0, 1 << 32, size=(K // group, N // 8), dtype=np.uint64).astype(np.uint32)
+    scales = rng.uniform(0.005, 0.02, size=(K // group, N)).astype(np.float32).astype(np.float16).astype(np.float32)
+    return qweight, qzeros, scales
+
+
 def fp16_exact(x: np.ndarray) -> np.ndarray:
     """Values exactly representable in IEEE binary16, as fp32."""
     return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)

@@ -446,3 +446,51 @@ def test_codebook_model_forward_matches_torch_composition(oracle):
     logits = rms(h, t["final_norm"]) @ _t(t["lm_head"]).T
     want = F.cross_entropy(logits[:, :-1].reshape(-1, sh["vocab"]), torch.from_numpy(tok[:, 1:].astype(np.int64)).reshape(-1)).item()
     assert abs(loss - want) <= 1e-9 * abs(want)
+
+
+# ------------------------------------- asymmetric groups (zero-points) ----
+def test_zero_point_dequant_and_linear(oracle):
+    x, qp, s = synth.linear_case(5, 24, 384, seed=3)
+    rng = np.random.default_rng(4)
+    zp = rng.integers(0, 16, size=(24, 3), dtype=np.uint8)
+    eps = np.float32(2e-3)
+    # zero-point 8 everywhere is the symmetric format, bit for bit
+    w8 = oracle.dequant_zp(qp, s, np.full((24, 3), 8, np.uint8), 7, 5, eps, to_bf16=True)
+    assert np.array_equal(w8.view(np.uint32), oracle.dequant(qp, s, 7, 5, eps, to_bf16=True).view(np.uint32))
+    # against the definition written with numpy: s_eff * (u - zp)
+    u = np.stack([qp & 15, qp >> 4], axis=-1).reshape(24, 384).astype(np.float64)
+    se = oracle.effective_scales(s, 5, 7, eps)
+    want = np.repeat(se, 128, axis=1) * (u - np.repeat(zp.astype(np.float64), 128, axis=1))
+    got = oracle.dequant_zp(qp, s, zp, 7, 5, eps)
+    assert np.abs(got - want).max() <= 2.0 ** -23 * np.abs(want).max()
+    y = oracle.qlinear_zp(x, qp, se, zp)
+    assert np.abs(y - (_t(x) @ _t(want).T).numpy()).max() <= 1e-12 * np.abs(y).max()
+    # a zero-point shift moves every output by -dz * sum_g s_eff[n,g] * sum_{k in g} x[m,k]
+    zp2 = zp.copy(); zp2[:, 1] = (zp2[:, 1] + 3) % 16
+    dz = zp2[:, 1].astype(np.float64) - zp[:, 1]
+    xs = x[:, 128:256].astype(np.float64).sum(1)
+    y2 = oracle.qlinear_zp(x, qp, se, zp2)
+    assert np.abs((y2 - y) - (-xs[:, None] * (dz * se[:, 1])[None, :])).max() <= 1e-10
+
+
+def test_kmajor_repack_against_the_layout_definition(oracle):
+    N, K = 24, 384
+    qweight, qzeros, scales = synth.kmajor_case(N, K, seed=11)
+    qp, zp, s = oracle.repack_kmajor(qweight, qzeros, scales, zero_add=1)
+    # independent unpacking with numpy shifts: nibble j of word (kk, n) is k = 8 kk + j
+    u = np.zeros((N, K), np.uint8)
+    for j in range(8):
+        u[:, j::8] = ((qweight >> np.uint32(4 * j)) & np.uint32(15)).T.astype(np.uint8)
+    assert np.array_equal(qp & 15, u[:, 0::2]) and np.array_equal(qp >> 4, u[:, 1::2])
+    z = np.zeros((N, K // 128), np.uint8)
+    for j in range(8):
+        z[j::8, :] = ((qzeros >> np.uint32(4 * j)) & np.uint32(15)).T.astype(np.uint8)
+    assert np.array_equal(zp, (z + 1) & 15)
+    assert np.array_equal(oracle.repack_kmajor(qweight, qzeros, scales, zero_add=0)[1], z)
+    want_s = torch.from_numpy(scales.T.copy()).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(s, want_s)
+    # one word changed -> exactly eight nibbles of one row change
+    q2 = qweight.copy(); q2[5, 7] ^= np.uint32(0xFFFFFFFF)
+    qp2 = oracle.repack_kmajor(q2, qzeros, scales, 1)[0]
+    diff = np.argwhere(qp2 != qp)
+    assert set(diff[:, 0]) == {7} and sorted(diff[:, 1]) == [20, 21, 22, 23]
