@@ -164,6 +164,35 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
                             float* sumsq_dev, void* stream);
 
 /*
+ * The same linear for asymmetric 4-bit groups, the format of the 4-bit checkpoints the paper
+ * fine-tunes (Sec. 4.1: group-128 quantizer with zero-points):
+ *   W_eff[n,k] = (s[n,k/group] + sign*eps*z(row_base+n, k/group)) * (u[n,k] - zp[n,k/group])
+ * with the stored nibble u in 0..15 and zp_dev uint8 [N, K/group] holding integer zero-points
+ * 0..15 (zp = 8 everywhere is qzo_dequant_gemm).  The integer difference is formed exactly and
+ * multiplied once, so the bf16 weight tile equals the definition bit for bit.  Everything
+ * else (layouts, sumsq_dev, the few-token path, scratch) as in qzo_dequant_gemm.  The trained
+ * quantities are the scales; zero-points are fixed.
+ */
+qzo_status qzo_dequant_gemm_zp(const void* x_dev, const void* q_dev, const void* s_dev,
+                               const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
+                               uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                               void* y_dev, float* sumsq_dev, void* stream);
+
+/*
+ * Repacks an asymmetric 4-bit linear from the K-major layout such checkpoints are stored in:
+ *   qweight_dev int32 [K/8, N]   word (kk, n) = nibbles of k = 8 kk .. 8 kk + 7 of output n, lowest first
+ *   qzeros_dev  int32 [K/group, N/8]  word (g, nn) = zero-points of n = 8 nn .. 8 nn + 7, lowest first
+ *   scales_dev  fp16  [K/group, N]
+ * into this library's layout: q_dev bytes [N, K/2], zp_dev uint8 [N, K/group] = (stored zero-point
+ * + zero_add) & 15 (some writers store the zero-point minus one: zero_add = 1), s_dev bf16
+ * [N, K/group] = the fp16 scale rounded to nearest even.  group == 128, K % 128 == 0, N % 8 == 0.
+ * Activation reordering (a per-column group index) is not supported.
+ */
+qzo_status qzo_repack_kmajor(const void* qweight_dev, const void* qzeros_dev, const void* scales_dev,
+                             uint32_t N, uint32_t K, uint32_t group, uint32_t zero_add, void* q_dev,
+                             void* zp_dev, void* s_dev, void* stream);
+
+/*
  * Codebook variant of the perturbed linear (the paper's 2-bit setting, Sec. 3.2.1 last
  * paragraph / Sec. 4.1: 1 codebook of 16 bits, channel-wise scales trained by QZO):
  *   W[n,k] = c[n] * CB[codes[n,k/8]][k%8],  Y = (X * (CB-weights)^T) * diag(c + sign*eps*z)
@@ -205,6 +234,11 @@ qzo_status qzo_debug_normal_pairs(const uint32_t* words_dev, uint32_t n, float* 
 qzo_status qzo_debug_dequant(const void* q_dev, const void* s_dev, uint32_t row_base, uint32_t N,
                              uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
                              void* w_eff_dev, void* stream);
+/* The same with zero-points (zp_dev uint8 [N, K/group], nullable = 8): the B operand of
+ * qzo_dequant_gemm_zp. */
+qzo_status qzo_debug_dequant_zp(const void* q_dev, const void* s_dev, const void* zp_dev,
+                                uint32_t row_base, uint32_t N, uint32_t K, uint32_t group,
+                                uint64_t seed, float eps, int sign, void* w_eff_dev, void* stream);
 
 /* Measurement aid, not part of the method: one 512-thread workgroup per compute unit, each
  * wavefront issuing iters x 16 v_mfma_f32_32x32x16_bf16 (32768 flop each) on register operands

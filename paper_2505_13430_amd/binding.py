@@ -23,7 +23,7 @@ QZO_ERR_NONFINITE, QZO_ERR_HIP, QZO_ERR_UNSUPPORTED = -5, -6, -7
 EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
-    "qzo_apply_update", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
+    "qzo_apply_update", "qzo_dequant_gemm_zp", "qzo_repack_kmajor", "qzo_debug_dequant_zp", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
     "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_profile_begin", "qzo_profile_collect",
     "qzo_last_error",
 ]
@@ -150,6 +150,22 @@ def qzo_dequant_gemm(x, q, s, row_base, seed, eps, sign, y, sumsq=None, group=12
                                   _stream(stream)))
 
 
+def qzo_dequant_gemm_zp(x, q, s, zp, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None):
+    M, K = x.shape
+    N = q.shape[0]
+    _check(lib().qzo_dequant_gemm_zp(_ptr(x), _ptr(q), _ptr(s), _ptr(zp), C.c_uint32(row_base),
+                                     C.c_uint32(M), C.c_uint32(N), C.c_uint32(K), C.c_uint32(group),
+                                     C.c_uint64(seed), C.c_float(eps), C.c_int(sign), _ptr(y),
+                                     _ptr(sumsq), _stream(stream)))
+
+
+def qzo_repack_kmajor(qweight, qzeros, scales, zero_add, q, zp, s, group=128, stream=None):
+    K, N = qweight.shape[0] * 8, qweight.shape[1]
+    _check(lib().qzo_repack_kmajor(_ptr(qweight), _ptr(qzeros), _ptr(scales), C.c_uint32(N),
+                                   C.c_uint32(K), C.c_uint32(group), C.c_uint32(zero_add), _ptr(q),
+                                   _ptr(zp), _ptr(s), _stream(stream)))
+
+
 def qzo_apply_update(s, row_base, seed, eta, d_clipped, stream=None):
     n_rows, G = s.shape
     _check(lib().qzo_apply_update(_ptr(s), C.c_uint32(n_rows), C.c_uint32(G), C.c_uint32(row_base),
@@ -184,6 +200,13 @@ def qzo_debug_dequant(q, s, row_base, seed, eps, sign, w_eff, group=128, stream=
     _check(lib().qzo_debug_dequant(_ptr(q), _ptr(s), C.c_uint32(row_base), C.c_uint32(N),
                                    C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
                                    C.c_float(eps), C.c_int(sign), _ptr(w_eff), _stream(stream)))
+
+
+def qzo_debug_dequant_zp(q, s, zp, row_base, seed, eps, sign, w_eff, group=128, stream=None):
+    N, K = w_eff.shape
+    _check(lib().qzo_debug_dequant_zp(_ptr(q), _ptr(s), _ptr(zp), C.c_uint32(row_base), C.c_uint32(N),
+                                      C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
+                                      C.c_float(eps), C.c_int(sign), _ptr(w_eff), _stream(stream)))
 
 
 def qzo_debug_forward(model, tokens, seed, eps, sign, workspace, loss_out, hidden_out, stream=None):

@@ -510,10 +510,10 @@ qzo_status qzo_apply_update(void* s_dev, uint32_t n_rows, uint32_t G, uint32_t r
   return QZO_OK;
 }
 
-qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
-                            uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint32_t group,
-                            uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
-                            void* stream) {
+static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
+                               const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
+                               uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                               void* y_dev, float* sumsq_dev, void* stream) {
   if (!x_dev || !q_dev || !s_dev || !y_dev) return fail(QZO_ERR_ARG, "null device pointer");
   if (!aligned16(x_dev) || !aligned16(q_dev) || !aligned16(s_dev) || !aligned16(y_dev))
     return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
@@ -528,7 +528,7 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
     return QZO_OK;
   }
   GemmArgs g = {};
-  g.x = x_dev; g.w = q_dev; g.s = s_dev; g.y = y_dev;
+  g.x = x_dev; g.w = q_dev; g.s = s_dev; g.zp = zp_dev; g.y = y_dev;
   g.M = M; g.N = N; g.K = K; g.row_base = row_base;
   g.seed_lo = (uint32_t)seed; g.seed_hi = (uint32_t)(seed >> 32);
   g.eps_signed = sign > 0 ? eps : -eps;
@@ -558,6 +558,37 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
   }
   QZO_HIP(launch_w4a16_gemm(g, st));
   if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  return QZO_OK;
+}
+
+qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
+                            uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint32_t group,
+                            uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
+                            void* stream) {
+  return dequant_gemm(x_dev, q_dev, s_dev, nullptr, row_base, M, N, K, group, seed, eps, sign, y_dev,
+                      sumsq_dev, stream);
+}
+
+qzo_status qzo_dequant_gemm_zp(const void* x_dev, const void* q_dev, const void* s_dev,
+                               const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
+                               uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                               void* y_dev, float* sumsq_dev, void* stream) {
+  if (!zp_dev) return fail(QZO_ERR_ARG, "zp_dev is null");
+  return dequant_gemm(x_dev, q_dev, s_dev, zp_dev, row_base, M, N, K, group, seed, eps, sign, y_dev,
+                      sumsq_dev, stream);
+}
+
+qzo_status qzo_repack_kmajor(const void* qweight_dev, const void* qzeros_dev, const void* scales_dev,
+                             uint32_t N, uint32_t K, uint32_t group, uint32_t zero_add, void* q_dev,
+                             void* zp_dev, void* s_dev, void* stream) {
+  if (!qweight_dev || !qzeros_dev || !scales_dev || !q_dev || !zp_dev || !s_dev)
+    return fail(QZO_ERR_ARG, "null device pointer");
+  if (group != 128 || K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
+  if (N == 0 || N % 8) return fail(QZO_ERR_SHAPE, "N must be a positive multiple of 8");
+  if (zero_add > 15) return fail(QZO_ERR_ARG, "zero_add must be 0 .. 15");
+  if (!aligned16(q_dev) || !aligned16(s_dev)) return fail(QZO_ERR_ALIGN, "output not 16-byte aligned");
+  QZO_HIP(launch_repack_kmajor(qweight_dev, qzeros_dev, scales_dev, N, K, zero_add, q_dev, zp_dev, s_dev,
+                               (hipStream_t)stream));
   return QZO_OK;
 }
 
@@ -684,12 +715,19 @@ qzo_status qzo_debug_normal_pairs(const uint32_t* words_dev, uint32_t n, float* 
 qzo_status qzo_debug_dequant(const void* q_dev, const void* s_dev, uint32_t row_base, uint32_t N,
                              uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
                              void* w_eff_dev, void* stream) {
+  return qzo_debug_dequant_zp(q_dev, s_dev, nullptr, row_base, N, K, group, seed, eps, sign, w_eff_dev,
+                              stream);
+}
+
+qzo_status qzo_debug_dequant_zp(const void* q_dev, const void* s_dev, const void* zp_dev,
+                                uint32_t row_base, uint32_t N, uint32_t K, uint32_t group,
+                                uint64_t seed, float eps, int sign, void* w_eff_dev, void* stream) {
   if (!q_dev || !s_dev || !w_eff_dev) return fail(QZO_ERR_ARG, "null device pointer");
   if (!aligned16(q_dev) || !aligned16(s_dev) || !aligned16(w_eff_dev))
     return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
   if (group != 128 || K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
   if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
-  QZO_HIP(launch_debug_dequant(q_dev, s_dev, row_base, N, K, (uint32_t)seed, (uint32_t)(seed >> 32),
+  QZO_HIP(launch_debug_dequant(q_dev, s_dev, zp_dev, row_base, N, K, (uint32_t)seed, (uint32_t)(seed >> 32),
                                sign > 0 ? eps : -eps, w_eff_dev, (hipStream_t)stream));
   return QZO_OK;
 }

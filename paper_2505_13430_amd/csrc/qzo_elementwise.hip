@@ -223,7 +223,9 @@ hipError_t launch_debug_normal_pairs(const uint32_t* words, uint32_t n, float* o
 }
 
 // bf16((s + sign*eps*z) * wbar) for every weight: thread = (n, 8 consecutive k).
+// zp (nullable): one zero-point byte per (row, group); null = 8.
 __global__ void debug_dequant_kernel(const uint8_t* __restrict__ q, const bf16_t* __restrict__ s,
+                                     const uint8_t* __restrict__ zp,
                                      uint32_t row_base, uint32_t N, uint32_t K, uint32_t seed_lo,
                                      uint32_t seed_hi, float eps_signed, bf16_t* __restrict__ out) {
   const uint32_t cpr = K >> 3;
@@ -238,23 +240,59 @@ __global__ void debug_dequant_kernel(const uint8_t* __restrict__ q, const bf16_t
   for (int j = 1; j < 8; ++j) zz = ((g & 7u) == (uint32_t)j) ? z[j] : zz;
   const float se = __builtin_fmaf(eps_signed, zz, bf16_to_f32(s[(uint64_t)n * G + g]));
   const uint32_t packed = *reinterpret_cast<const uint32_t*>(q + (uint64_t)n * (K >> 1) + c * 4);
+  const int z0 = zp ? (int)zp[(uint64_t)n * G + g] : 8;
   uint32_t o[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    float a = se * (float)((int)((packed >> (8 * j)) & 15u) - 8);
-    float b = se * (float)((int)((packed >> (8 * j + 4)) & 15u) - 8);
+    float a = se * (float)((int)((packed >> (8 * j)) & 15u) - z0);
+    float b = se * (float)((int)((packed >> (8 * j + 4)) & 15u) - z0);
     o[j] = pack_bf16x2(a, b);
   }
   *reinterpret_cast<uint4*>(out + (uint64_t)n * K + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
-hipError_t launch_debug_dequant(const void* q, const void* s, uint32_t row_base, uint32_t N,
+hipError_t launch_debug_dequant(const void* q, const void* s, const void* zp, uint32_t row_base, uint32_t N,
                                 uint32_t K, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                                 void* w_eff, hipStream_t st) {
   uint64_t units = (uint64_t)N * (K >> 3);
   if (units == 0) return hipSuccess;
   debug_dequant_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(
-      (const uint8_t*)q, (const bf16_t*)s, row_base, N, K, seed_lo, seed_hi, eps_signed,
+      (const uint8_t*)q, (const bf16_t*)s, (const uint8_t*)zp, row_base, N, K, seed_lo, seed_hi, eps_signed,
       (bf16_t*)w_eff);
+  return hipGetLastError();
+}
+
+// Repack of an asymmetric 4-bit linear from the K-major checkpoint layout (qweight int32
+// [K/8, N]: word (kk, n) = nibbles of k = 8 kk .. 8 kk + 7, lowest first; qzeros int32
+// [G, N/8]: word (g, nn) = zero-points of n = 8 nn .. 8 nn + 7; scales fp16 [G, N]) into the
+// library's row-major layout.  One thread per (n, 8 k): a dword of nibbles in k order is the
+// source word itself; the first thread of a group also writes the zero-point and the scale.
+__global__ void repack_kmajor_kernel(const uint32_t* __restrict__ qweight,
+                                     const uint32_t* __restrict__ qzeros,
+                                     const _Float16* __restrict__ scales, uint32_t N, uint32_t K,
+                                     uint32_t zero_add, uint32_t* __restrict__ q_out,
+                                     uint8_t* __restrict__ zp_out, bf16_t* __restrict__ s_out) {
+  const uint32_t cpr = K >> 3, G = K >> 7;
+  const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= (uint64_t)N * cpr) return;
+  // consecutive threads take consecutive n of one kk: coalesced reads of the K-major words
+  const uint32_t kk = (uint32_t)(u / N), n = (uint32_t)(u % N);
+  q_out[(uint64_t)n * cpr + kk] = qweight[(uint64_t)kk * N + n];
+  if ((kk & 15u) == 0u) {
+    const uint32_t g = kk >> 4;
+    const uint32_t z = (qzeros[(uint64_t)g * (N >> 3) + (n >> 3)] >> (4 * (n & 7u))) & 15u;
+    zp_out[(uint64_t)n * G + g] = (uint8_t)((z + zero_add) & 15u);
+    const uint32_t packed = pack_bf16x2((float)scales[(uint64_t)g * N + n], 0.0f);
+    s_out[(uint64_t)n * G + g] = (bf16_t)(packed & 0xffffu);
+  }
+}
+hipError_t launch_repack_kmajor(const void* qweight, const void* qzeros, const void* scales,
+                                uint32_t N, uint32_t K, uint32_t zero_add, void* q_out, void* zp_out,
+                                void* s_out, hipStream_t st) {
+  const uint64_t units = (uint64_t)N * (K >> 3);
+  if (units == 0) return hipSuccess;
+  repack_kmajor_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(
+      (const uint32_t*)qweight, (const uint32_t*)qzeros, (const _Float16*)scales, N, K, zero_add,
+      (uint32_t*)q_out, (uint8_t*)zp_out, (bf16_t*)s_out);
   return hipGetLastError();
 }
 

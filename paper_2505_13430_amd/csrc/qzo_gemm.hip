@@ -89,6 +89,10 @@ __device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t chunk) {
 // a nibble u (0..15) read as an fp8 E4M3 pattern is exactly u * 2^-9, so one
 // v_cvt_pk_f32_fp8 turns two nibbles into floats; fma(u 2^-9, 512 se, -8 se)
 // is (u-8)*se with a single rounding, the same bits as se * float(u-8).
+// With zero-points (ZP) the two parameters are the scale se and the negated zero-point:
+// fma(u 2^-9, 512, -zp) is the integer u - zp exactly and its product with se is rounded
+// once, the same bits as se * float(u - zp).
+template <bool ZP = false>
 __device__ __forceinline__ uint4 dequant8(uint32_t w, float se512, float m8se) {
   typedef float f2 __attribute__((ext_vector_type(2)));
   const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;
@@ -96,10 +100,18 @@ __device__ __forceinline__ uint4 dequant8(uint32_t w, float se512, float m8se) {
   const f2 l23 = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);    // nibbles 4, 6
   const f2 h01 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false);   // nibbles 1, 3
   const f2 h23 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);    // nibbles 5, 7
-  const float e0 = __builtin_fmaf(l01.x, se512, m8se), e1 = __builtin_fmaf(h01.x, se512, m8se);
-  const float e2 = __builtin_fmaf(l01.y, se512, m8se), e3 = __builtin_fmaf(h01.y, se512, m8se);
-  const float e4 = __builtin_fmaf(l23.x, se512, m8se), e5 = __builtin_fmaf(h23.x, se512, m8se);
-  const float e6 = __builtin_fmaf(l23.y, se512, m8se), e7 = __builtin_fmaf(h23.y, se512, m8se);
+  float e0, e1, e2, e3, e4, e5, e6, e7;
+  if (ZP) {
+    e0 = __builtin_fmaf(l01.x, 512.0f, m8se) * se512; e1 = __builtin_fmaf(h01.x, 512.0f, m8se) * se512;
+    e2 = __builtin_fmaf(l01.y, 512.0f, m8se) * se512; e3 = __builtin_fmaf(h01.y, 512.0f, m8se) * se512;
+    e4 = __builtin_fmaf(l23.x, 512.0f, m8se) * se512; e5 = __builtin_fmaf(h23.x, 512.0f, m8se) * se512;
+    e6 = __builtin_fmaf(l23.y, 512.0f, m8se) * se512; e7 = __builtin_fmaf(h23.y, 512.0f, m8se) * se512;
+  } else {
+    e0 = __builtin_fmaf(l01.x, se512, m8se); e1 = __builtin_fmaf(h01.x, se512, m8se);
+    e2 = __builtin_fmaf(l01.y, se512, m8se); e3 = __builtin_fmaf(h01.y, se512, m8se);
+    e4 = __builtin_fmaf(l23.x, se512, m8se); e5 = __builtin_fmaf(h23.x, se512, m8se);
+    e6 = __builtin_fmaf(l23.y, se512, m8se); e7 = __builtin_fmaf(h23.y, se512, m8se);
+  }
   return make_uint4(pack_bf16x2(e0, e1), pack_bf16x2(e2, e3), pack_bf16x2(e4, e5),
                     pack_bf16x2(e6, e7));
 }
@@ -127,8 +139,10 @@ struct CeEpilogue {
 // weight tile; the perturbed per-output-channel scale multiplies the accumulators).
 // PIPE = how a k-tile's instructions are ordered: 0 left to the compiler, 1 one interleaved
 // stream per wavefront with an explicit issue order, 2 alternating phases (see QZO_PP_TILE).
-template <int QM, bool CE, int NWN, int PIPE>
+// ZP (int4 only) = asymmetric groups: a.zp holds one zero-point byte per (row, group).
+template <int QM, bool CE, int NWN, int PIPE, bool ZP = false>
 __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilogue ce) {
+  static_assert(!ZP || QM == 0, "zero-points belong to the int4 format");
   constexpr bool W4 = QM == 0, CB = QM == 2, ROWMAP = W4 || CB;
   constexpr bool SCHED = PIPE == 1, PP = PIPE == 2;
   static_assert(!CB || NWN == 4, "codebook staging is written for 512 threads");
@@ -166,6 +180,8 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       const_cast<void*>(CB ? a.cb : a.x), 0, CB ? (65536 * 16) : 16, 0x00020000);
   const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<void*>(W4 ? a.s : a.x), 0, (int)(W4 ? (uint64_t)a.N * (K >> 7) * 2 : 16), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(ZP ? a.zp : a.x), 0, (int)(ZP ? (uint64_t)a.N * (K >> 7) : 16), 0x00020000);
   uint32_t xo[NA], wo[NA], so = 0, gn_w4 = 0;
   const uint32_t brow = t / TPR, bpart = t % TPR;
   // LDS offsets: rows t/8 + RSTEP i share their swizzle, so chunk i is a_lds + i * RSTEP rows.
@@ -204,6 +220,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   float z_odd = 0.0f;                // second variate of the current pair
   float se512 = 0.0f, m8se = 0.0f;
   bf16_t s_next = 0;
+  uint8_t z_next = 8;
 
   // LDS: A stage 0 | A stage 1 | B stage 0 | B stage 1, 32 KB each.  The k-loop is
   // unrolled by two so the stage is a compile-time constant and every LDS address is
@@ -253,8 +270,11 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 // of that tile's operand loads: memory returns in order, so a scale requested here
 // would make the wavefront wait for every operand load issued before it.
 #define QZO_SCALE_PREFETCH(G_)                                                               \
-  s_next = (bf16_t)__builtin_amdgcn_raw_buffer_load_b16(                                     \
-      rs, (int)so, (int)(min((uint32_t)(G_), (K >> 7) - 1u) * 2u), 0)
+  do {                                                                                       \
+    const uint32_t gp_ = min((uint32_t)(G_), (K >> 7) - 1u);                                 \
+    s_next = (bf16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, (int)so, (int)(gp_ * 2u), 0);  \
+    if (ZP) z_next = __builtin_amdgcn_raw_buffer_load_b8(rz, (int)(so >> 1), (int)gp_, 0);   \
+  } while (0)
 #define QZO_NEW_GROUP(G_)                                                                    \
   do {                                                                                       \
     const uint32_t g_ = (G_);                                                                \
@@ -269,8 +289,8 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       normal_pair(w_, zz_, z_odd);                                                           \
     }                                                                                        \
     const float se_ = __builtin_fmaf(a.eps_signed, zz_, bf16_to_f32(s_next));                \
-    se512 = 512.0f * se_;                                                                    \
-    m8se = -8.0f * se_;                                                                      \
+    se512 = ZP ? se_ : 512.0f * se_;                  /* ZP: the scale itself          */    \
+    m8se = ZP ? -(float)z_next : -8.0f * se_;         /* ZP: the negated zero-point    */    \
   } while (0)
 
 // Registers -> LDS stage STAGE (compile-time); the int4 tile is unpacked, scaled
@@ -284,10 +304,10 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   do {                                                                                       \
     if (W4) {                                                                                \
       _Pragma("unroll") for (int q = 0; q < NBQ; ++q) {                                      \
-        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 0] + (STAGE) * TILE_BYTES) = dequant8(rb[q].x, se512, m8se); \
-        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 1] + (STAGE) * TILE_BYTES) = dequant8(rb[q].y, se512, m8se); \
-        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 2] + (STAGE) * TILE_BYTES) = dequant8(rb[q].z, se512, m8se); \
-        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 3] + (STAGE) * TILE_BYTES) = dequant8(rb[q].w, se512, m8se); \
+        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 0] + (STAGE) * TILE_BYTES) = dequant8<ZP>(rb[q].x, se512, m8se); \
+        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 1] + (STAGE) * TILE_BYTES) = dequant8<ZP>(rb[q].y, se512, m8se); \
+        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 2] + (STAGE) * TILE_BYTES) = dequant8<ZP>(rb[q].z, se512, m8se); \
+        *reinterpret_cast<uint4*>(lds_b + b_lds[4 * q + 3] + (STAGE) * TILE_BYTES) = dequant8<ZP>(rb[q].w, se512, m8se); \
       }                                                                                      \
     } else if (CB) {                                                                         \
       _Pragma("unroll") for (int q = 0; q < 4; ++q) *reinterpret_cast<uint4*>(               \
@@ -408,8 +428,8 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 
 #define QZO_PP_STAGE_HALF(PAR, STAGE, H)                                                     \
   do {                                                                                       \
-    const uint4 c0_ = dequant8((H) ? rbp[PAR].z : rbp[PAR].x, se512, m8se);                  \
-    const uint4 c1_ = dequant8((H) ? rbp[PAR].w : rbp[PAR].y, se512, m8se);                  \
+    const uint4 c0_ = dequant8<ZP>((H) ? rbp[PAR].z : rbp[PAR].x, se512, m8se);                  \
+    const uint4 c1_ = dequant8<ZP>((H) ? rbp[PAR].w : rbp[PAR].y, se512, m8se);                  \
     *reinterpret_cast<uint4*>(lds_b + b_lds[2 * (H)] + (STAGE) * TILE_BYTES) = c0_;          \
     *reinterpret_cast<uint4*>(lds_b + b_lds[2 * (H) + 1] + (STAGE) * TILE_BYTES) = c1_;      \
     *reinterpret_cast<u32x4*>(lds_a + a_lds + ((2 * (H)) * RSTEP * 128 + (STAGE) * TILE_BYTES)) = ra[2 * (H)]; \
@@ -739,6 +759,7 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
     hipError_t e = set_lds_attr((const void*)gemm_kernel<0, false, W4_NWN, W4_PIPE>);
+    if (e == hipSuccess) e = set_lds_attr((const void*)gemm_kernel<0, false, W4_NWN, W4_PIPE, true>);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -749,8 +770,12 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
-  gemm_kernel<0, false, W4_NWN, W4_PIPE>
-      <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
+  if (a.zp)
+    gemm_kernel<0, false, W4_NWN, W4_PIPE, true>
+        <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
+  else
+    gemm_kernel<0, false, W4_NWN, W4_PIPE>
+        <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
   return hipGetLastError();
 }
 

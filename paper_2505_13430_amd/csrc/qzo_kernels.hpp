@@ -37,6 +37,7 @@ struct GemmArgs {
   const void* w;        // packed int4 [N,K/2] (W4) or bf16 [N,K] (dense)
   const void* s;        // bf16 [N,K/128] (W4) or fp16 [N] per-channel scales (codebook)
   const void* cb;       // fp16 [65536,8] codebook (codebook only)
+  const void* zp;       // uint8 [N,K/128] zero-points (int4 only; null = symmetric, zero-point 8)
   const void* bias;     // bf16 [N] or null
   const void* resid;    // bf16 [M,N] or null
   void* y;              // bf16 [M,N]
@@ -111,7 +112,10 @@ hipError_t launch_debug_philox(uint32_t seed_lo, uint32_t seed_hi, const uint32_
                                uint32_t n, uint32_t* out, hipStream_t st);
 hipError_t launch_debug_normal_pairs(const uint32_t* words, uint32_t n, float* out,
                                      hipStream_t st);
-hipError_t launch_debug_dequant(const void* q, const void* s, uint32_t row_base, uint32_t N,
+hipError_t launch_repack_kmajor(const void* qweight, const void* qzeros, const void* scales,
+                                uint32_t N, uint32_t K, uint32_t zero_add, void* q_out, void* zp_out,
+                                void* s_out, hipStream_t st);
+hipError_t launch_debug_dequant(const void* q, const void* s, const void* zp, uint32_t row_base, uint32_t N,
                                 uint32_t K, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                                 void* w_eff, hipStream_t st);
 

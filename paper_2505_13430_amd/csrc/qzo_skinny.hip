@@ -32,15 +32,25 @@ constexpr int SK_ROWS = 128;      // output rows per workgroup
 constexpr int SK_DEPTH = 4;       // groups of weights in flight per lane
 
 // 8 nibbles of one dword -> 8 bf16 of (nibble-8)*se in k order (see the tile GEMM).
+// ZP: the parameters are the scale and the negated zero-point (u - zp exact, one rounding).
+template <bool ZP>
 __device__ __forceinline__ bf16x8 dequant8_frag(uint32_t w, float se512, float m8se) {
   typedef float f2 __attribute__((ext_vector_type(2)));
   const uint32_t lo = w & 0x0f0f0f0fu, hi = (w >> 4) & 0x0f0f0f0fu;
   const f2 l01 = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), l23 = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
   const f2 h01 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), h23 = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
-  const float e0 = __builtin_fmaf(l01.x, se512, m8se), e1 = __builtin_fmaf(h01.x, se512, m8se);
-  const float e2 = __builtin_fmaf(l01.y, se512, m8se), e3 = __builtin_fmaf(h01.y, se512, m8se);
-  const float e4 = __builtin_fmaf(l23.x, se512, m8se), e5 = __builtin_fmaf(h23.x, se512, m8se);
-  const float e6 = __builtin_fmaf(l23.y, se512, m8se), e7 = __builtin_fmaf(h23.y, se512, m8se);
+  float e0, e1, e2, e3, e4, e5, e6, e7;
+  if (ZP) {
+    e0 = __builtin_fmaf(l01.x, 512.0f, m8se) * se512; e1 = __builtin_fmaf(h01.x, 512.0f, m8se) * se512;
+    e2 = __builtin_fmaf(l01.y, 512.0f, m8se) * se512; e3 = __builtin_fmaf(h01.y, 512.0f, m8se) * se512;
+    e4 = __builtin_fmaf(l23.x, 512.0f, m8se) * se512; e5 = __builtin_fmaf(h23.x, 512.0f, m8se) * se512;
+    e6 = __builtin_fmaf(l23.y, 512.0f, m8se) * se512; e7 = __builtin_fmaf(h23.y, 512.0f, m8se) * se512;
+  } else {
+    e0 = __builtin_fmaf(l01.x, se512, m8se); e1 = __builtin_fmaf(h01.x, se512, m8se);
+    e2 = __builtin_fmaf(l01.y, se512, m8se); e3 = __builtin_fmaf(h01.y, se512, m8se);
+    e4 = __builtin_fmaf(l23.x, se512, m8se); e5 = __builtin_fmaf(h23.x, se512, m8se);
+    e6 = __builtin_fmaf(l23.y, se512, m8se); e7 = __builtin_fmaf(h23.y, se512, m8se);
+  }
   union { bf16x8 v; uint32_t u[4]; } r;
   r.u[0] = pack_bf16x2(e0, e1); r.u[1] = pack_bf16x2(e2, e3);
   r.u[2] = pack_bf16x2(e4, e5); r.u[3] = pack_bf16x2(e6, e7);
@@ -53,7 +63,7 @@ __device__ __forceinline__ uint32_t x_lds_off(uint32_t row, uint32_t chunk) {   
 
 // MT = 32-token tiles (1 or 2).  grid = (ceil(N/128), ksplit); part is [ksplit, rows, N] fp32
 // with rows = M, or 2 M in dual mode (MT = 2: tile 0 is the +eps pass, tile 1 the -eps pass).
-template <int MT, bool DUAL>
+template <int MT, bool DUAL, bool ZP>
 __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmArgs a, float* __restrict__ part,
                                                              uint32_t groups_per_split) {
   static_assert(!DUAL || MT == 2, "dual mode: one token tile per pass");
@@ -66,6 +76,7 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
   const uint32_t n = min(blockIdx.x * SK_ROWS + wave * 32 + lrow, a.N - 1);      // this lane's weight row
   const unsigned char* wrow = (const unsigned char*)a.w + (uint64_t)n * (K >> 1) + half * 32;
   const bf16_t* srow = (const bf16_t*)a.s + (uint64_t)n * ngrp;
+  const uint8_t* zrow = ZP ? (const uint8_t*)a.zp + (uint64_t)n * ngrp : nullptr;
   const bf16_t* x = (const bf16_t*)a.x;
 
   // activation staging: a group's block is MT*32 rows x 16 chunks; a thread moves MT*2 chunks
@@ -96,6 +107,7 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
 
   // weights and scales in flight: slot g % SK_DEPTH
   u32x4 wq[SK_DEPTH][2];
+  uint32_t zq[SK_DEPTH];     // zero-points (ZP)
   uint32_t sq[SK_DEPTH];     // one register each: 16-bit loads into shared registers would chain the slots
 #define QZO_SK_WLOAD(SLOT, G_)                                                               \
   do {                                                                                       \
@@ -103,6 +115,7 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
     wq[SLOT][0] = *reinterpret_cast<const u32x4*>(wrow + (uint64_t)gg_ * 64);                \
     wq[SLOT][1] = *reinterpret_cast<const u32x4*>(wrow + (uint64_t)gg_ * 64 + 16);           \
     sq[SLOT] = (uint32_t)srow[gg_];                                                          \
+    if (ZP) zq[SLOT] = (uint32_t)zrow[gg_];                                                  \
   } while (0)
 
   floatx16 acc[MT];
@@ -158,15 +171,16 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
         fresh = false;
         const float zz = (g & 1u) ? z_odd : z_even, s0 = __uint_as_float(sq[d] << 16);
         const float se = __builtin_fmaf(a.eps_signed, zz, s0);
-        const float se512 = 512.0f * se, m8se = -8.0f * se;
+        const float nzp = ZP ? -(float)zq[d] : 0.0f;
+        const float se512 = ZP ? se : 512.0f * se, m8se = ZP ? nzp : -8.0f * se;
         const float sn = __builtin_fmaf(-a.eps_signed, zz, s0);     // dual mode: the other pass
-        const float sn512 = 512.0f * sn, m8sn = -8.0f * sn;
+        const float sn512 = ZP ? sn : 512.0f * sn, m8sn = ZP ? nzp : -8.0f * sn;
         const u32x4 w0 = wq[d][0], w1 = wq[d][1];
         const uint32_t wd[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
 #pragma unroll
         for (int j = 0; j < 8; ++j) {           // k-step j: k = 64 half + 8 j + e of the group
-          const bf16x8 af = dequant8_frag(wd[j], se512, m8se);
-          const bf16x8 an = DUAL ? dequant8_frag(wd[j], sn512, m8sn) : af;
+          const bf16x8 af = dequant8_frag<ZP>(wd[j], se512, m8se);
+          const bf16x8 an = DUAL ? dequant8_frag<ZP>(wd[j], sn512, m8sn) : af;
 #pragma unroll
           for (int m = 0; m < MT; ++m) {
             const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xs[buf] + x_lds_off(m * 32 + lrow, half * 8 + j));
@@ -285,12 +299,20 @@ hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st) {
   if (a.M > SKINNY_MAX_M || (a.dual && a.M > SKINNY_MAX_M_DUAL) || !ws) return hipErrorInvalidValue;
   const uint32_t ks = skinny_ksplit(a.N, a.K), ngrp = a.K >> 7, per = (ngrp + ks - 1) / ks;
   dim3 grid((a.N + SK_ROWS - 1) / SK_ROWS, ks);
-  if (a.dual)
-    skinny_gemm_kernel<2, true><<<grid, 256, 0, st>>>(a, ws, per);
-  else if (a.M <= 32)
-    skinny_gemm_kernel<1, false><<<grid, 256, 0, st>>>(a, ws, per);
-  else
-    skinny_gemm_kernel<2, false><<<grid, 256, 0, st>>>(a, ws, per);
+  if (a.zp) {
+    if (a.dual)
+      skinny_gemm_kernel<2, true, true><<<grid, 256, 0, st>>>(a, ws, per);
+    else if (a.M <= 32)
+      skinny_gemm_kernel<1, false, true><<<grid, 256, 0, st>>>(a, ws, per);
+    else
+      skinny_gemm_kernel<2, false, true><<<grid, 256, 0, st>>>(a, ws, per);
+  } else if (a.dual) {
+    skinny_gemm_kernel<2, true, false><<<grid, 256, 0, st>>>(a, ws, per);
+  } else if (a.M <= 32) {
+    skinny_gemm_kernel<1, false, false><<<grid, 256, 0, st>>>(a, ws, per);
+  } else {
+    skinny_gemm_kernel<2, false, false><<<grid, 256, 0, st>>>(a, ws, per);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   GemmArgs r = a;                               // the reduction sees the stacked rows as one matrix

@@ -394,6 +394,57 @@ def test_real_width_one_layer_step(oracle, name, batch, seq, eta):
     dm.close()
 
 
+# ----------------------------------- asymmetric groups (zero-points) ----
+def _zp_case(oracle, N, K, seed):
+    qweight, qzeros, scales = synth.kmajor_case(N, K, seed)
+    q = torch.zeros((N, K // 2), dtype=torch.uint8, device=DEV)
+    zp = torch.zeros((N, K // 128), dtype=torch.uint8, device=DEV)
+    s = torch.zeros((N, K // 128), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_repack_kmajor(_dev(qweight.view(np.int32)), _dev(qzeros.view(np.int32)),
+                         _dev(scales, torch.float16), 1, q, zp, s)
+    return (qweight, qzeros, scales), (q, zp, s)
+
+
+@pytest.mark.parametrize("N,K", [(24, 384), (264, 1280), (8, 128)])
+def test_kmajor_repack_and_zero_point_tile_bit_exact(oracle, N, K):
+    host, (q, zp, s) = _zp_case(oracle, N, K, seed=N + K)
+    qp, zpo, so = oracle.repack_kmajor(*host, zero_add=1)
+    assert np.array_equal(q.cpu().numpy(), qp) and np.array_equal(zp.cpu().numpy(), zpo)
+    assert np.array_equal(_bits(s.float().cpu().numpy()), _bits(so))
+    for sign in (1, -1):
+        out = torch.zeros((N, K), dtype=torch.bfloat16, device=DEV)
+        qb.qzo_debug_dequant_zp(q, s, zp, 9, 99, 1e-3, sign, out)
+        want = oracle.dequant_zp(qp, so, zpo, 99, 9, sign * np.float32(1e-3), to_bf16=True)
+        assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 520, 384), (256, 264, 1280), (16, 520, 1280), (64, 136, 512),
+                                   (1, 8, 128)])
+def test_zero_point_linear_matches_oracle(oracle, M, N, K):
+    host, (q, zp, s) = _zp_case(oracle, N, K, seed=M + N + K)
+    qp, zpo, so = oracle.repack_kmajor(*host, zero_add=1)
+    x = synth.linear_case(M, 8, K, seed=M)[0]
+    xd = _dev(x, torch.bfloat16)
+    for sign in (1, -1):
+        y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+        ssq = torch.zeros(1, dtype=torch.float32, device=DEV)
+        qb.qzo_dequant_gemm_zp(xd, q, s, zp, 11, 31, 1e-3, sign, y, ssq)
+        se = oracle.effective_scales(so, 11, 31, sign * np.float32(1e-3))
+        ref = oracle.qlinear_zp(x, qp, se, zpo)
+        got = y.float().cpu().numpy().astype(np.float64)
+        rms = math.sqrt((ref ** 2).mean())
+        bad = np.abs(got - ref) > 6e-3 * np.abs(ref) + 1.2e-2 * rms
+        assert not bad.any(), (int(bad.sum()), np.abs(got - ref).max() / rms)
+        assert abs(float(ssq.item()) - oracle.sumsq_bf16(ref)) <= 5e-3 * oracle.sumsq_bf16(ref)
+    # zero-point 8 everywhere reproduces the symmetric entry point bit for bit
+    zp8 = torch.full_like(zp, 8)
+    a = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    b = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_dequant_gemm_zp(xd, q, s, zp8, 11, 31, 1e-3, 1, a)
+    qb.qzo_dequant_gemm(xd, q, s, 11, 31, 1e-3, 1, b)
+    assert torch.equal(a, b)
+
+
 # ------------------------------------------------------ codebook variant ----
 @pytest.mark.parametrize("n,row_base", [(1000, 0), (4096, 128), (37, 5), (8, 0xFFFFF000)])
 def test_channel_update_bit_exact(oracle, n, row_base):
