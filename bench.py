@@ -187,6 +187,14 @@ def main():
     dt = time.perf_counter() - t0
     prof = {k: qb.qzo_profile_collect(v) for k, v in qb.PROFILE_KINDS.items()}
     res = qb.read_step_result(dm.result)
+    peak_bytes = torch.cuda.max_memory_allocated()
+    # outside the timed region: one more step, to report how many stored scales it moved
+    # (16-bit storage rounds most of the paper-sized updates away)
+    before = dm.scales.clone()
+    dm.step(tok, 10_000, eps, eta, clip)
+    torch.cuda.synchronize()
+    changed = float((dm.scales.view(torch.int16) != before.view(torch.int16)).float().mean().item())
+    del before
 
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
@@ -210,6 +218,7 @@ def main():
         "steps_per_s": steps_per_s,
         "forward_tokens_per_s": 2 * B * S * steps_per_s,
         "last_step": res,
+        "scales_changed_frac": changed,
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel<2,...> (codebook GEMM, perturbed channel scales)" if codebook
                      else "gemm_kernel<0,...> (perturbed W4A16 GEMM)",
                      "achieved": gemm_flops_s / 1e12, "peak": PEAK_BF16_MFMA / 1e12,
@@ -229,7 +238,7 @@ def main():
                          "bytes_per_launch": u["work"] / max(u["launches"], 1),
                          "traffic": measured_traffic("traffic_bytes_per_launch_scale_update")
                          if main_cfg else None},
-        "device_memory_GiB": torch.cuda.max_memory_allocated() / 2 ** 30,
+        "device_memory_GiB": peak_bytes / 2 ** 30,
     }
     if few_tokens:
         # every int4 weight and scale is read once per launch: the roof is HBM
