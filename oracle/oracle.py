@@ -143,8 +143,19 @@ def qlinear_zp(x, qp, s_eff, zp, group=128):
     N = qp.shape[0]
     y = np.zeros((M, N), dtype=np.float64)
     lib().orc_qlinear_zp(_p(x), C.c_uint64(M), C.c_uint64(K), _p(qp), _p(s_eff), _p(zp), C.c_uint64(N),
-                         C.c_uint32(group), _p(y))
+                         C.c_uint32(group), None, _p(y))
     return y
+
+
+def rtn_quantize_asym(w, group=128):
+    """Asymmetric RTN groups: (nibbles [N,K/2], zero-points [N,G], bf16 scales [N,G])."""
+    w = _f32(w)
+    N, K = w.shape
+    qp = np.zeros((N, K // 2), dtype=np.uint8)
+    zp = np.zeros((N, K // group), dtype=np.uint8)
+    s = np.zeros((N, K // group), dtype=np.float32)
+    lib().orc_rtn_quantize_asym(_p(w), C.c_uint64(N), C.c_uint64(K), C.c_uint32(group), _p(qp), _p(zp), _p(s))
+    return qp, zp, s
 
 
 def repack_kmajor(qweight, qzeros, scales_f16, zero_add, group=128):
@@ -267,31 +278,39 @@ class Model:
     scales: np.ndarray       # flat fp32 arena of bf16-valued scales
     segments: list = field(default_factory=list)
     group: int = 128
-    quant: int = 0           # 0: int4 + group scales; 1: codebook + per-channel scales
+    quant: int = 0           # 0: int4 + group scales; 1: codebook + per-channel scales; 2: int4 + zero-points
 
     @property
     def n_rows(self):
         return sum(s.rows for s in self.segments)
 
 
-def build_model(shape: dict, table, group=128) -> Model:
+def build_model(shape: dict, table, group=128, asym=False) -> Model:
     """Quantize the 'w' entries of a (name, kind, array) table with RTN
-    (Eq. 3 with the absmax scale) and lay the scales out in arena order."""
+    (Eq. 3 with the absmax scale; asym: with zero-points, each packed weight then followed by
+    its zero-point tensor) and lay the scales out in arena order."""
     tensors, names, segs, scales = [], [], [], []
     off = 0
     row = 0
     for name, kind, arr in table:
         if kind == "w":
-            qp, s = rtn_quantize(arr, group)
-            tensors.append(qp)
+            if asym:
+                qp, zp, s = rtn_quantize_asym(arr, group)
+                tensors += [qp, zp]
+                names += [name, name + ".zp"]
+            else:
+                qp, s = rtn_quantize(arr, group)
+                tensors.append(qp)
+                names.append(name)
             segs.append(Segment(name, off, s.shape[0], s.shape[1], row))
             scales.append(s.reshape(-1))
             off += s.size
             row += s.shape[0]
         else:
             tensors.append(_f32(arr))
-        names.append(name)
-    return Model(shape, tensors, names, np.concatenate(scales).astype(np.float32), segs, group)
+            names.append(name)
+    return Model(shape, tensors, names, np.concatenate(scales).astype(np.float32), segs, group,
+                 2 if asym else 0)
 
 
 def fp16_rne(x):

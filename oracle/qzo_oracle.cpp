@@ -247,6 +247,33 @@ void orc_rtn_quantize(const float* w, uint64_t N, uint64_t K, uint32_t group,
   }
 }
 
+// Asymmetric round-to-nearest groups (Eq. 3 with a zero-point): the range [min(w,0), max(w,0)]
+// of a group is mapped on the 16 levels, s = bf16((hi - lo) / 15), zp = rne(-lo / s) clamped to
+// 0..15, u = clamp(rne(w / s) + zp, 0, 15); an all-zero group gives s = 0, zp = 8, u = 8.
+void orc_rtn_quantize_asym(const float* w, uint64_t N, uint64_t K, uint32_t group, uint8_t* qp,
+                           uint8_t* zp, float* s) {
+  uint64_t G = K / group;
+  for (uint64_t n = 0; n < N; ++n)
+    for (uint64_t g = 0; g < G; ++g) {
+      const float* wg = w + n * K + g * group;
+      float lo = 0.f, hi = 0.f;
+      for (uint32_t k = 0; k < group; ++k) { lo = std::min(lo, wg[k]); hi = std::max(hi, wg[k]); }
+      float sc = bf16_rne((hi - lo) / 15.0f);
+      int z0 = 8;
+      if (sc > 0.f) z0 = (int)std::min(15.0f, std::max(0.0f, std::nearbyintf(-lo / sc)));
+      s[n * G + g] = sc;
+      zp[n * G + g] = (uint8_t)z0;
+      for (uint32_t k = 0; k < group; ++k) {
+        int u = 8;
+        if (sc > 0.f) u = (int)std::min(15.0f, std::max(0.0f, std::nearbyintf(wg[k] / sc) + (float)z0));
+        uint64_t kk = g * group + k;
+        uint8_t* b = qp + n * (K / 2) + kk / 2;
+        if (kk & 1) *b = (uint8_t)((*b & 0x0f) | (u << 4));
+        else *b = (uint8_t)((*b & 0xf0) | u);
+      }
+    }
+}
+
 void orc_unpack_int4(const uint8_t* qp, uint64_t N, uint64_t K, int8_t* q) {
   for (uint64_t n = 0; n < N; ++n)
     for (uint64_t k = 0; k < K; ++k) q[n * K + k] = (int8_t)unpack_q(qp, K, n, k);
@@ -301,7 +328,7 @@ void orc_dequant_zp(const uint8_t* qp, const float* s, const uint8_t* zp, uint64
     }
 }
 void orc_qlinear_zp(const double* x, uint64_t M, uint64_t K, const uint8_t* qp, const double* s_eff,
-                    const uint8_t* zp, uint64_t N, uint32_t group, double* y) {
+                    const uint8_t* zp, uint64_t N, uint32_t group, const float* bias, double* y) {
   uint64_t G = K / group;
 #pragma omp parallel for schedule(static)
   for (int64_t n = 0; n < (int64_t)N; ++n) {
@@ -314,7 +341,7 @@ void orc_qlinear_zp(const double* x, uint64_t M, uint64_t K, const uint8_t* qp, 
       double acc = 0.0;
       const double* xr = x + m * K;
       for (uint64_t k = 0; k < K; ++k) acc += xr[k] * wrow[k];
-      y[m * N + n] = acc;
+      y[m * N + n] = acc + (bias ? (double)bias[n] : 0.0);
     }
   }
 }
@@ -530,7 +557,8 @@ struct orc_config {
   uint32_t arch;        // 0 = Llama family (RMSNorm, RoPE, SwiGLU, no bias), 1 = OPT family
   uint32_t n_layers, d_model, n_heads, d_ffn, vocab, max_seq, group;
   double norm_eps, rope_theta;
-  uint32_t quant;       // 0 = int4 + per-group scales, 1 = codebook + per-channel scales (Llama only)
+  uint32_t quant;       // 0 = int4 + per-group scales, 1 = codebook + per-channel scales (Llama only),
+                        // 2 = int4 with zero-points: every packed weight is followed by u8 [N, K/group]
 };
 
 // Tensor table, in this order (all fp32 arrays holding bf16 values unless noted):
@@ -571,6 +599,17 @@ double orc_forward_loss(const orc_config* c, const void* const* T, const double*
   auto round_all = [&](std::vector<double>& x) {
     if (act_bf16) for (auto& v : x) v = (double)bf16_rne((float)v);
   };
+  const bool asym = c->quant == 2;
+  // a packed int4 weight and, in the asymmetric format, the zero-point tensor that follows it
+  auto take_w = [&](const uint8_t*& w, const uint8_t*& z) {
+    w = (const uint8_t*)T[ti++];
+    z = asym ? (const uint8_t*)T[ti++] : nullptr;
+  };
+  auto qlin = [&](const double* x, uint64_t K, const uint8_t* w, const uint8_t* z, const double* sc,
+                  uint64_t N, const float* bias, double* y) {
+    if (z) orc_qlinear_zp(x, M, K, w, sc, z, N, c->group, bias, y);
+    else orc_qlinear(x, M, K, w, sc, N, c->group, bias, y);
+  };
   for (uint32_t l = 0; l < c->n_layers; ++l) {
     if (llama && c->quant == 1) {
       const float* n1 = (const float*)T[ti++];
@@ -595,44 +634,46 @@ double orc_forward_loss(const orc_config* c, const void* const* T, const double*
       orc_codebook_linear(act.data(), M, F, idn, cdn, se, d, nullptr, lin.data()); se += d;
       for (uint64_t i = 0; i < M * d; ++i) h[i] = round_act(h[i] + lin[i], act_bf16);
     } else if (llama) {
+      const uint8_t *wqkv, *zqkv, *wo, *zo, *wgu, *zgu, *wdn, *zdn;
       const float* n1 = (const float*)T[ti++];
-      const uint8_t* wqkv = (const uint8_t*)T[ti++];
-      const uint8_t* wo = (const uint8_t*)T[ti++];
+      take_w(wqkv, zqkv);
+      take_w(wo, zo);
       const float* n2 = (const float*)T[ti++];
-      const uint8_t* wgu = (const uint8_t*)T[ti++];
-      const uint8_t* wdn = (const uint8_t*)T[ti++];
+      take_w(wgu, zgu);
+      take_w(wdn, zdn);
       orc_rmsnorm(h.data(), M, d, n1, c->norm_eps, a.data()); round_all(a);
-      orc_qlinear(a.data(), M, d, wqkv, se, 3 * d, c->group, nullptr, qkv.data()); se += 3 * d * Gd;
+      qlin(a.data(), d, wqkv, zqkv, se, 3 * d, nullptr, qkv.data()); se += 3 * d * Gd;
       round_all(qkv);
       orc_rope(qkv.data(), B, S, 3 * d, 0, H, dh, c->rope_theta);
       orc_rope(qkv.data(), B, S, 3 * d, d, H, dh, c->rope_theta);
       round_all(qkv);
       orc_attention(qkv.data(), B, S, H, dh, att.data()); round_all(att);
-      orc_qlinear(att.data(), M, d, wo, se, d, c->group, nullptr, lin.data()); se += d * Gd;
+      qlin(att.data(), d, wo, zo, se, d, nullptr, lin.data()); se += d * Gd;
       for (uint64_t i = 0; i < M * d; ++i) h[i] = round_act(h[i] + lin[i], act_bf16);
       orc_rmsnorm(h.data(), M, d, n2, c->norm_eps, a.data()); round_all(a);
-      orc_qlinear(a.data(), M, d, wgu, se, 2 * F, c->group, nullptr, ff.data()); se += 2 * F * Gd;
+      qlin(a.data(), d, wgu, zgu, se, 2 * F, nullptr, ff.data()); se += 2 * F * Gd;
       round_all(ff);
       orc_swiglu(ff.data(), M, F, act.data()); round_all(act);
-      orc_qlinear(act.data(), M, F, wdn, se, d, c->group, nullptr, lin.data()); se += d * GF;
+      qlin(act.data(), F, wdn, zdn, se, d, nullptr, lin.data()); se += d * GF;
       for (uint64_t i = 0; i < M * d; ++i) h[i] = round_act(h[i] + lin[i], act_bf16);
     } else {
+      const uint8_t *wqkv, *zqkv, *wo, *zo, *w1, *z1, *w2, *z2;
       const float* g1 = (const float*)T[ti++]; const float* b1 = (const float*)T[ti++];
-      const uint8_t* wqkv = (const uint8_t*)T[ti++]; const float* bqkv = (const float*)T[ti++];
-      const uint8_t* wo = (const uint8_t*)T[ti++]; const float* bo = (const float*)T[ti++];
+      take_w(wqkv, zqkv); const float* bqkv = (const float*)T[ti++];
+      take_w(wo, zo); const float* bo = (const float*)T[ti++];
       const float* g2 = (const float*)T[ti++]; const float* b2 = (const float*)T[ti++];
-      const uint8_t* w1 = (const uint8_t*)T[ti++]; const float* bf1 = (const float*)T[ti++];
-      const uint8_t* w2 = (const uint8_t*)T[ti++]; const float* bf2 = (const float*)T[ti++];
+      take_w(w1, z1); const float* bf1 = (const float*)T[ti++];
+      take_w(w2, z2); const float* bf2 = (const float*)T[ti++];
       orc_layernorm(h.data(), M, d, g1, b1, c->norm_eps, a.data()); round_all(a);
-      orc_qlinear(a.data(), M, d, wqkv, se, 3 * d, c->group, bqkv, qkv.data()); se += 3 * d * Gd;
+      qlin(a.data(), d, wqkv, zqkv, se, 3 * d, bqkv, qkv.data()); se += 3 * d * Gd;
       round_all(qkv);
       orc_attention(qkv.data(), B, S, H, dh, att.data()); round_all(att);
-      orc_qlinear(att.data(), M, d, wo, se, d, c->group, bo, lin.data()); se += d * Gd;
+      qlin(att.data(), d, wo, zo, se, d, bo, lin.data()); se += d * Gd;
       for (uint64_t i = 0; i < M * d; ++i) h[i] = round_act(h[i] + lin[i], act_bf16);
       orc_layernorm(h.data(), M, d, g2, b2, c->norm_eps, a.data()); round_all(a);
-      orc_qlinear(a.data(), M, d, w1, se, F, c->group, bf1, ff.data()); se += F * Gd;
+      qlin(a.data(), d, w1, z1, se, F, bf1, ff.data()); se += F * Gd;
       for (uint64_t i = 0; i < M * F; ++i) act[i] = round_act(std::max(ff[i], 0.0), act_bf16);
-      orc_qlinear(act.data(), M, F, w2, se, d, c->group, bf2, lin.data()); se += d * GF;
+      qlin(act.data(), F, w2, z2, se, d, bf2, lin.data()); se += d * GF;
       for (uint64_t i = 0; i < M * d; ++i) h[i] = round_act(h[i] + lin[i], act_bf16);
     }
   }

@@ -134,6 +134,8 @@ def _torch_forward(model, s_eff, tok, oracle):
         s = seg[name]
         K = T[name].shape[1] * 2
         qi = oracle.unpack_int4(T[name], K).astype(np.float64)
+        if name + ".zp" in T:       # asymmetric groups: integer is (stored nibble - zero-point)
+            qi = qi + 8.0 - np.repeat(T[name + ".zp"].astype(np.float64), 128, axis=1)
         se = s_eff[s.offset:s.offset + s.rows * s.G].reshape(s.rows, s.G)
         return _t(np.repeat(se, 128, axis=1) * qi)
 
@@ -494,3 +496,59 @@ def test_kmajor_repack_against_the_layout_definition(oracle):
     qp2 = oracle.repack_kmajor(q2, qzeros, scales, 1)[0]
     diff = np.argwhere(qp2 != qp)
     assert set(diff[:, 0]) == {7} and sorted(diff[:, 1]) == [20, 21, 22, 23]
+
+
+def test_asymmetric_rtn_quantizer_invariants(oracle):
+    """Sec. 4.1 (zero-point form of Eq. 3-4): the grid {s*(u-zp)} contains 0 and covers [min,max] of the
+    group, so every weight is reproduced to within half a step (plus the bf16 rounding of the step)."""
+    rng = np.random.default_rng(21)
+    N, K = 6, 512
+    w = (rng.standard_normal((N, K)) * 0.05 + 0.02).astype(np.float32)
+    w[0, :128] = np.abs(w[0, :128])            # all-positive group: zero-point must be 0
+    w[1, :128] = -np.abs(w[1, :128])           # all-negative group: zero-point must be 15
+    w[2, 128:256] = 0.0                        # empty group
+    qp, zp, s = oracle.rtn_quantize_asym(w)
+    u = oracle.unpack_int4(qp, K) + 8          # stored nibbles 0..15
+    assert u.min() >= 0 and u.max() <= 15 and zp.min() >= 0 and zp.max() <= 15
+    assert zp[0, 0] == 0 and zp[1, 0] == 15
+    assert s[2, 1] == 0 and zp[2, 1] == 8 and (u[2, 128:256] == 8).all()
+    # scales are bf16-representable: low 16 bits of the fp32 pattern are zero
+    assert (s.view(np.uint32) & 0xFFFF == 0).all()
+    wg = w.reshape(N, K // 128, 128).astype(np.float64)
+    lo, hi = np.minimum(wg.min(-1), 0), np.maximum(wg.max(-1), 0)
+    step = (hi - lo) / 15
+    nz = step > 0
+    assert np.allclose(s[nz], step[nz], rtol=2.0 ** -8)
+    rec = (s[:, :, None].astype(np.float64) * (u.reshape(N, -1, 128) - zp[:, :, None].astype(np.float64)))
+    # half a step, plus 15 steps' worth of the bf16 rounding of s at the far end of the range
+    bound = (0.5 + 15 * 2.0 ** -8) * s[:, :, None] + 1e-12
+    assert (np.abs(rec - wg) <= bound).all()
+    # the library routine agrees with the reconstruction
+    assert np.array_equal(oracle.dequant_zp(qp, s, zp, 0, 0, 0.0), rec.reshape(N, K).astype(np.float32))
+    # a symmetric-range group (min = -max) needs no shift beyond the midpoint: zp in {7, 8}
+    ws = np.linspace(-1, 1, 128, dtype=np.float32)[None]
+    _, zps, _ = oracle.rtn_quantize_asym(ws)
+    assert zps[0, 0] in (7, 8)
+
+
+@pytest.mark.parametrize("arch", ["llama", "opt"])
+def test_asymmetric_forward_matches_torch_composition(oracle, arch):
+    sh = dict(MINI, arch=arch)
+    m = oracle.build_model(sh, synth.tensor_table(sh, 3), asym=True)
+    assert m.quant == 2
+    tok = synth.tokens(sh, 4)
+    se = oracle.perturbed_scales(m, seed=5, eps_signed=1e-3)
+    got = oracle.forward_loss(m, se, tok, act_bf16=False)
+    assert math.isclose(got, _torch_forward(m, se, tok, oracle), rel_tol=1e-10)
+    assert abs(got - math.log(sh["vocab"])) < 0.2
+    # a model whose zero-points all equal 8 is the symmetric model (same nibbles, same scales)
+    ms = oracle.build_model(sh, synth.tensor_table(sh, 3))
+    tensors, names = [], []
+    for n, t in zip(ms.names, ms.tensors):
+        tensors.append(t); names.append(n)
+        if any(sg.name == n for sg in ms.segments):
+            sg = next(sg for sg in ms.segments if sg.name == n)
+            tensors.append(np.full((sg.rows, sg.G), 8, dtype=np.uint8)); names.append(n + ".zp")
+    m8 = type(ms)(ms.shape, tensors, names, ms.scales, ms.segments, ms.group, 2)
+    se_s = oracle.perturbed_scales(ms, seed=5, eps_signed=1e-3)
+    assert oracle.forward_loss(m8, se_s, tok, act_bf16=True) == oracle.forward_loss(ms, se_s, tok, act_bf16=True)
