@@ -62,7 +62,9 @@ typedef struct {
   uint32_t group_size;  /* 128 */
   uint32_t quant;       /* 0: int4 + per-group bf16 scales
                            1: codebook (Llama only): one uint16 code per 8 weights into a per-linear
-                              fp16 [65536,8] codebook, fp16 per-output-channel scales */
+                              fp16 [65536,8] codebook, fp16 per-output-channel scales
+                           2: int4 + per-group bf16 scales + per-group zero-points,
+                              W = s * (u - zp) (Sec. 4.1, quantizers that keep a zero-point) */
   float norm_eps;       /* 1e-5 */
   float rope_theta;     /* 10000 (Llama only) */
 } qzo_model_config;
@@ -93,6 +95,9 @@ typedef struct {
  *   Llama, quant = 1: per layer { attn_norm, codes_qkv uint16[3d,d/8], cb_qkv fp16[65536,8],
  *          codes_o, cb_o, ffn_norm, codes_gu [2F,d/8], cb_gu, codes_down [d,F/8], cb_down };
  *          the arena then holds one fp16 scale per output row, per layer [3d][d][2F][d].
+ *   quant = 2 (either family): the quant = 0 table with every int4 weight [N,K/2] directly
+ *          followed by its zero-points uint8 [N,K/128], values 0..15; scales and the arena as
+ *          for quant = 0.
  * `scale_arena_dev` holds every quantized linear's bf16 scales back to back in
  * the same order ([N, K/128] each); it is the only model memory the library
  * writes.  Only the decoder-block linears are quantized and trained (their

@@ -67,7 +67,8 @@ qzo_status check_cfg(const qzo_model_config* c) {
   if (c->struct_size != sizeof(qzo_model_config))
     return fail(QZO_ERR_ARG, "config.struct_size does not match this library");
   if (c->arch > 1) return fail(QZO_ERR_ARG, "config.arch must be 0 (Llama) or 1 (OPT)");
-  if (c->quant > 1) return fail(QZO_ERR_UNSUPPORTED, "quant must be 0 (int4 group scales) or 1 (codebook)");
+  if (c->quant > 2)
+    return fail(QZO_ERR_UNSUPPORTED, "quant must be 0 (int4 group scales), 1 (codebook) or 2 (int4 with zero-points)");
   if (c->quant == 1 && c->arch != 0)
     return fail(QZO_ERR_UNSUPPORTED, "the codebook variant is built for the Llama family only");
   if (c->group_size != 128) return fail(QZO_ERR_SHAPE, "group_size must be 128");
@@ -125,7 +126,7 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   // With very few tokens qzo_step stacks its two perturbed passes into one forward
   // over 2 * batch sequences (the int4 weights are then read once per step).
   const uint64_t M1 = (uint64_t)batch * seq;
-  const bool stack = M1 <= SKINNY_MAX_M_DUAL && c.quant == 0;
+  const bool stack = M1 <= SKINNY_MAX_M_DUAL && c.quant != 1;
   const uint64_t M = stack ? 2 * M1 : M1, d = c.d_model, F = c.d_ffn;
   const uint64_t n_slices = ((c.vocab + 255) / 256) * 4;
   Workspace w;
@@ -147,7 +148,7 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   w.losses = (float*)take(256);
   // few-token path of the int4 GEMM: fp32 partial sums of the K slices of the largest linear
   uint64_t sk = 0;
-  if (M1 <= SKINNY_MAX_M && c.quant == 0)
+  if (M1 <= SKINNY_MAX_M && c.quant != 1)
     for (int i = 0; i < 4; ++i)
       sk = std::max<uint64_t>(sk, skinny_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.skinny = (float*)take(sk * 4);
@@ -203,7 +204,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   const qzo_model_config& c = m->cfg;
   const uint32_t batch = batch1 * n_pass, M1 = batch1 * seq;
   const uint32_t M = batch * seq, d = c.d_model, F = c.d_ffn, H = c.n_heads, dh = d / H;
-  const bool llama = c.arch == 0;
+  const bool llama = c.arch == 0, asym = c.quant == 2;
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
   const unsigned char* arena = (const unsigned char*)m->arena;
 
@@ -217,10 +218,21 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   for (uint32_t l = 0; l < c.n_layers; ++l) {
     const qzo_buf* T = &m->T[m->first_layer_tensor + (size_t)l * m->tensors_per_layer];
     const uint64_t layer_off = (uint64_t)l * m->scales_per_layer;
-    auto gemm = [&](int li, const void* x, const void* wq, const void* bias, const void* resid,
-                    void* y, uint32_t epi) {
+    // Position of a tensor of the symmetric table (and of the li-th weight) within this layer: with
+    // zero-points every packed weight is followed by one more tensor.
+    static const uint32_t wpos_llama[4] = {1, 2, 4, 5}, wpos_opt[4] = {2, 4, 8, 10};
+    const uint32_t* wpos = llama ? wpos_llama : wpos_opt;
+    auto tpos = [&](uint32_t k) {
+      uint32_t shift = 0;
+      if (asym)
+        for (int i = 0; i < 4; ++i) shift += wpos[i] < k;
+      return k + shift;
+    };
+    auto ti = [&](uint32_t k) { return T[tpos(k)].ptr_dev; };
+    auto gemm = [&](int li, const void* x, const void* bias, const void* resid, void* y, uint32_t epi) {
       GemmArgs g = {};
-      g.x = x; g.w = wq; g.s = arena + (layer_off + m->lin[li].s_off) * 2;
+      g.x = x; g.w = ti(wpos[li]); g.zp = asym ? T[tpos(wpos[li]) + 1].ptr_dev : nullptr;
+      g.s = arena + (layer_off + m->lin[li].s_off) * 2;
       g.bias = bias; g.resid = resid; g.y = y;
       g.M = M1; g.N = m->lin[li].N; g.K = m->lin[li].K;
       g.dual = n_pass == 2;
@@ -257,30 +269,30 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       QZO_HIP(cgemm(2, w.a, T[6].ptr_dev, T[7].ptr_dev, nullptr, w.act, EPI_SWIGLU));
       QZO_HIP(cgemm(3, w.act, T[8].ptr_dev, T[9].ptr_dev, w.h, w.h, EPI_RESIDUAL));
     } else if (llama) {
-      // attn_norm, wqkv, wo, ffn_norm, wgu, wdown
-      QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
-      QZO_HIP(gemm(0, w.a, T[1].ptr_dev, nullptr, nullptr, w.qkv, 0));
+      // attn_norm, wqkv, wo, ffn_norm, wgu, wdown (symmetric-table positions)
+      QZO_HIP(launch_rmsnorm(w.h, ti(0), M, d, c.norm_eps, w.a, st));
+      QZO_HIP(gemm(0, w.a, nullptr, nullptr, w.qkv, 0));
       QZO_HIP(launch_rope(w.qkv, m->rope_table, batch, seq, d, H, st));
       {
         ProfScope ps(PK_ATTN, attn_flops, st);
         QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
       }
-      QZO_HIP(gemm(1, w.att, T[2].ptr_dev, nullptr, w.h, w.h, EPI_RESIDUAL));
-      QZO_HIP(launch_rmsnorm(w.h, T[3].ptr_dev, M, d, c.norm_eps, w.a, st));
-      QZO_HIP(gemm(2, w.a, T[4].ptr_dev, nullptr, nullptr, w.act, EPI_SWIGLU));
-      QZO_HIP(gemm(3, w.act, T[5].ptr_dev, nullptr, w.h, w.h, EPI_RESIDUAL));
+      QZO_HIP(gemm(1, w.att, nullptr, w.h, w.h, EPI_RESIDUAL));
+      QZO_HIP(launch_rmsnorm(w.h, ti(3), M, d, c.norm_eps, w.a, st));
+      QZO_HIP(gemm(2, w.a, nullptr, nullptr, w.act, EPI_SWIGLU));
+      QZO_HIP(gemm(3, w.act, nullptr, w.h, w.h, EPI_RESIDUAL));
     } else {
-      // ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, wfc1, bfc1, wfc2, bfc2
-      QZO_HIP(launch_layernorm(w.h, T[0].ptr_dev, T[1].ptr_dev, M, d, c.norm_eps, w.a, st));
-      QZO_HIP(gemm(0, w.a, T[2].ptr_dev, T[3].ptr_dev, nullptr, w.qkv, EPI_BIAS));
+      // ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, wfc1, bfc1, wfc2, bfc2 (symmetric-table positions)
+      QZO_HIP(launch_layernorm(w.h, ti(0), ti(1), M, d, c.norm_eps, w.a, st));
+      QZO_HIP(gemm(0, w.a, ti(3), nullptr, w.qkv, EPI_BIAS));
       {
         ProfScope ps(PK_ATTN, attn_flops, st);
         QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
       }
-      QZO_HIP(gemm(1, w.att, T[4].ptr_dev, T[5].ptr_dev, w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
-      QZO_HIP(launch_layernorm(w.h, T[6].ptr_dev, T[7].ptr_dev, M, d, c.norm_eps, w.a, st));
-      QZO_HIP(gemm(2, w.a, T[8].ptr_dev, T[9].ptr_dev, nullptr, w.ff, EPI_BIAS | EPI_RELU));
-      QZO_HIP(gemm(3, w.ff, T[10].ptr_dev, T[11].ptr_dev, w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
+      QZO_HIP(gemm(1, w.att, ti(5), w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
+      QZO_HIP(launch_layernorm(w.h, ti(6), ti(7), M, d, c.norm_eps, w.a, st));
+      QZO_HIP(gemm(2, w.a, ti(9), nullptr, w.ff, EPI_BIAS | EPI_RELU));
+      QZO_HIP(gemm(3, w.ff, ti(11), w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
     }
   }
   const size_t tail = m->first_layer_tensor + (size_t)c.n_layers * m->tensors_per_layer;
@@ -340,7 +352,8 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
   if (!aligned16(scale_arena_dev)) return fail(QZO_ERR_ALIGN, "scale arena not 16-byte aligned");
   const bool llama = cfg->arch == 0;
   const bool codebook = cfg->quant == 1;
-  const uint32_t per_layer = codebook ? 10 : (llama ? 6 : 12), head = llama ? 1 : 2, tail = llama ? 2 : 3;
+  const bool asym = cfg->quant == 2;
+  const uint32_t per_layer = codebook ? 10 : (llama ? 6 : 12) + (asym ? 4 : 0), head = llama ? 1 : 2, tail = llama ? 2 : 3;
   if (n_tensors != head + per_layer * cfg->n_layers + tail)
     return fail(QZO_ERR_ARG, "tensor count does not match the architecture's table");
   uint64_t want = 0;
@@ -359,13 +372,21 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
       const uint64_t cbb = 65536 * 16;
       const uint64_t b[10] = {d * 2, 3 * d * d / 4, cbb, d * d / 4, cbb, d * 2, 2 * F * d / 4, cbb, d * F / 4, cbb};
       need.insert(need.end(), b, b + 10);
-    } else if (llama) {
-      const uint64_t b[6] = {d * 2, 3 * d * d / 2, d * d / 2, d * 2, 2 * F * d / 2, d * F / 2};
-      need.insert(need.end(), b, b + 6);
     } else {
-      const uint64_t b[12] = {d * 2, d * 2, 3 * d * d / 2, 3 * d * 2, d * d / 2, d * 2,
-                              d * 2, d * 2, F * d / 2,     F * 2,     d * F / 2, d * 2};
-      need.insert(need.end(), b, b + 12);
+      // a packed weight [N,K/2]; with zero-points, followed by its uint8 [N,K/128] tensor
+      auto weight = [&](uint64_t N, uint64_t K) {
+        need.push_back(N * K / 2);
+        if (asym) need.push_back(N * K / 128);
+      };
+      if (llama) {
+        need.push_back(d * 2); weight(3 * d, d); weight(d, d);
+        need.push_back(d * 2); weight(2 * F, d); weight(d, F);
+      } else {
+        need.push_back(d * 2); need.push_back(d * 2);
+        weight(3 * d, d); need.push_back(3 * d * 2); weight(d, d); need.push_back(d * 2);
+        need.push_back(d * 2); need.push_back(d * 2);
+        weight(F, d); need.push_back(F * 2); weight(d, F); need.push_back(d * 2);
+      }
     }
   }
   need.push_back(d * 2);
@@ -459,7 +480,7 @@ qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uin
   if (!std::isfinite(eps) || !std::isfinite(eta)) return fail(QZO_ERR_ARG, "eps/eta not finite");
   hipStream_t s = (hipStream_t)stream;
   Workspace w = carve(m, batch, seq, workspace_dev);
-  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && m->cfg.quant == 0) {
+  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && m->cfg.quant != 1) {
     // few tokens: one forward over both passes, the weights are read once
     st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s, nullptr, 2, w.losses + 1);
     if (st != QZO_OK) return st;

@@ -56,9 +56,14 @@ class DeviceModel:
         return cls(dict(shape, quant=1), dev, arena)
 
     @classmethod
-    def synthetic(cls, shape: dict, seed: int, device="cuda:0"):
+    def synthetic(cls, shape: dict, seed: int, device="cuda:0", asym=False):
         """Random-init model built on the device: weights ~ N(0, 0.02) drawn by
-        torch, quantized by the library's RTN kernel (Eq. 3), tensor by tensor."""
+        torch, quantized by the library's RTN kernel (Eq. 3), tensor by tensor.
+        asym: the zero-point variant (quant = 2); each group then also gets a zero-point drawn
+        from 6..10 (the weights it stands for are shifted by a few steps; shapes, sizes and
+        the work per step are those of a zero-point checkpoint)."""
+        if asym:
+            shape = dict(shape, quant=2)
         gen = torch.Generator(device=device)
         gen.manual_seed(seed)
         d, V = shape["d_model"], shape["vocab"]
@@ -77,7 +82,9 @@ class DeviceModel:
             n = N * (K // 128)
             qb.qzo_rtn_quantize(w, q, arena[off:off + n].view(N, K // 128))
             off += n
-            return q
+            if asym:
+                return [q, torch.randint(6, 11, (N, K // 128), generator=gen, device=device, dtype=torch.uint8)]
+            return [q]
 
         tensors = [fixed(V, d)]
         if not llama:
@@ -85,13 +92,13 @@ class DeviceModel:
         lin = synth.quantized_linears(shape)
         for _ in range(shape["n_layers"]):
             if llama:
-                tensors += [fixed(d, mean=1.0, std=0.1), quant(*lin[0][1:]), quant(*lin[1][1:]),
-                            fixed(d, mean=1.0, std=0.1), quant(*lin[2][1:]), quant(*lin[3][1:])]
+                tensors += ([fixed(d, mean=1.0, std=0.1)] + quant(*lin[0][1:]) + quant(*lin[1][1:]) +
+                            [fixed(d, mean=1.0, std=0.1)] + quant(*lin[2][1:]) + quant(*lin[3][1:]))
             else:
-                tensors += [fixed(d, mean=1.0, std=0.1), fixed(d), quant(*lin[0][1:]),
-                            fixed(lin[0][1]), quant(*lin[1][1:]), fixed(d),
-                            fixed(d, mean=1.0, std=0.1), fixed(d), quant(*lin[2][1:]),
-                            fixed(lin[2][1]), quant(*lin[3][1:]), fixed(d)]
+                tensors += ([fixed(d, mean=1.0, std=0.1), fixed(d)] + quant(*lin[0][1:]) +
+                            [fixed(lin[0][1])] + quant(*lin[1][1:]) + [fixed(d)] +
+                            [fixed(d, mean=1.0, std=0.1), fixed(d)] + quant(*lin[2][1:]) +
+                            [fixed(lin[2][1])] + quant(*lin[3][1:]) + [fixed(d)])
         tensors.append(fixed(d, mean=1.0, std=0.1))
         if not llama:
             tensors.append(fixed(d))

@@ -203,13 +203,23 @@ SHARP = dict(arch="llama", n_layers=2, d_model=256, n_heads=2, d_ffn=512, vocab=
              batch=3, seq=80)     # head size 128, ragged vocab, seq not a multiple of 32/128
 
 
-def _models(oracle, shape, seed, gain=1.0):
+def _models(oracle, shape, seed, gain=1.0, asym=False):
     table = synth.tensor_table(shape, seed)
     if gain != 1.0:   # larger weights: logits far from uniform, loss far from ln V
         table = [(n, k, synth.bf16_exact(a * gain) if (k == "w" or n in ("tok_emb", "lm_head")) else a)
                  for n, k, a in table]
-    om = oracle.build_model(shape, table)
-    return om, DeviceModel.from_host(shape, om.tensors, om.scales, DEV)
+    if asym:          # rows with off-centre weights, so that the zero-points spread over 2..13
+        table = [(n, k, (a + 0.03 * gain * np.sin(np.arange(a.shape[0]))[:, None]).astype(np.float32)
+                  if k == "w" else a) for n, k, a in table]
+    om = oracle.build_model(shape, table, asym=asym)
+    return om, DeviceModel.from_host(dict(shape, quant=om.quant), om.tensors, om.scales, DEV)
+
+
+def _case(name):
+    """'<shape>' or '<shape>+zp' (the zero-point variant) -> (shape, asym)."""
+    base, _, zp = name.partition("+")
+    shape = SHARP if base == "sharp" else (FEW[base] if base in FEW else synth.SHAPES[base])
+    return shape, zp == "zp"
 
 
 FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tokens: one token tile
@@ -217,10 +227,15 @@ FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tok
 
 
 @pytest.mark.parametrize("name,gain", [("tiny", 1.0), ("tiny_opt", 1.0), ("tiny", 4.0), ("tiny_opt", 4.0),
-                                       ("sharp", 4.0), ("few_llama", 4.0), ("few_opt", 4.0)])
+                                       ("sharp", 4.0), ("few_llama", 4.0), ("few_opt", 4.0),
+                                       ("tiny+zp", 4.0), ("tiny_opt+zp", 4.0), ("sharp+zp", 4.0),
+                                       ("few_llama+zp", 4.0), ("few_opt+zp", 1.0)])
 def test_forward_matches_oracle(oracle, name, gain):
-    shape = SHARP if name == "sharp" else (FEW[name] if name in FEW else synth.SHAPES[name])
-    om, dm = _models(oracle, shape, 1234, gain)
+    shape, asym = _case(name)
+    om, dm = _models(oracle, shape, 1234, gain, asym)
+    if asym:
+        zps = np.concatenate([t.reshape(-1) for n, t in zip(om.names, om.tensors) if n.endswith(".zp")])
+        assert zps.min() <= 3 and zps.max() >= 12
     tok = synth.tokens(shape, 5678)
     tokd = _dev(tok)
     B, S = tok.shape
@@ -252,16 +267,20 @@ def test_forward_matches_oracle(oracle, name, gain):
     dm.close()
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "few_llama", "few_opt"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "few_llama", "few_opt",
+                                  "tiny+zp", "tiny_opt+zp", "few_llama+zp", "few_opt+zp"])
 def test_step_matches_oracle(oracle, name):
-    shape = FEW[name] if name in FEW else synth.SHAPES[name]
-    om, dm = _models(oracle, shape, 1234)
+    shape, asym = _case(name)
+    om, dm = _models(oracle, shape, 1234, asym=asym)
     tok = synth.tokens(shape, 5678)
     tokd = _dev(tok)
-    ref = oracle.qzo_step(om, tok, seed=1, eps=1e-3, eta=1e-5, Cthr=100.0)
+    eta = 1e-5
+    seed = 3 if asym else 1           # a direction whose |d| is large enough to move the scales
+    ref = oracle.qzo_step(om, tok, seed=seed, eps=1e-3, eta=eta, Cthr=100.0)
     before = dm.scales.clone()
-    res = qb.read_step_result(dm.step(tokd, 1, 1e-3, 1e-5, 100.0))
+    res = qb.read_step_result(dm.step(tokd, seed, 1e-3, eta, 100.0))
     assert res["status"] == 0
+    print(name, "d gpu", res["d"], "d oracle", ref["d"], "losses", res["loss_plus"], ref["loss_plus"])
     for k in ("loss_plus", "loss_minus"):
         assert abs(res[k] - ref[k]) <= 2e-2 * abs(ref[k])
     assert res["d"] == np.float32((np.float32(res["loss_plus"]) - np.float32(res["loss_minus"]))
@@ -271,18 +290,18 @@ def test_step_matches_oracle(oracle, name):
     assert (np.abs(got - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-7).all()
     assert not torch.equal(dm.scales, before)
     # exactly the oracle's update for the d' the device found
-    want = oracle.update_scales(om, 1, 1e-5, res["d_clipped"])
+    want = oracle.update_scales(om, seed, eta, res["d_clipped"])
     assert np.array_equal(_bits(got), _bits(want))
-    print(name, "d gpu", res["d"], "d oracle", ref["d"])
     dm.close()
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_opt"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "tiny+zp"])
 def test_stacked_passes_equal_separate_passes(oracle, name):
     """With at most 32 tokens qzo_step runs both perturbed passes as one stacked forward (the
     weights are read once); its losses are bit-identical to two separate forward passes."""
-    shape = dict(synth.SHAPES[name], batch=2, seq=13)
-    om, dm = _models(oracle, shape, 1234, 4.0)
+    base, asym = _case(name)
+    shape = dict(base, batch=2, seq=13)
+    om, dm = _models(oracle, shape, 1234, 4.0, asym)
     tokd = _dev(synth.tokens(shape, 5678))
     res = qb.read_step_result(dm.step(tokd, 21, 1e-3, 0.0, 100.0))       # eta = 0: scales untouched
     lp = float(dm.forward_loss(tokd, 21, 1e-3, 1).item())
