@@ -397,6 +397,64 @@ def forward_loss(model: Model, s_eff, tok, act_bf16=True, want_hidden=False, wan
     return (float(loss),) + extra if extra else float(loss)
 
 
+# ---- joint SPSA on the un-quantized parameters (Sec. 3.2, Sec. 4.1 2-bit runs) ----
+def dense_slots(model: Model):
+    """(tensor index, first flat index, size, format) of every 16-bit tensor of the table, in table
+    order: together they are the un-quantized parameters theta_u.  Codebooks hold fp16 values."""
+    out, first = [], 0
+    for i, (name, t) in enumerate(zip(model.names, model.tensors)):
+        if t.dtype != np.float32:
+            continue
+        fmt = 1 if name.endswith(".cb") else 0
+        out.append((i, first, t.size, fmt))
+        first += t.size
+    return out
+
+
+def dense_master(model: Model) -> np.ndarray:
+    """fp32 master vector initialised from the 16-bit tensors."""
+    return np.concatenate([model.tensors[i].reshape(-1) for i, _, _, _ in dense_slots(model)]).astype(np.float32)
+
+
+def dense_effective(master, first, seed, eps_signed, fmt=0):
+    master = _f32(master).reshape(-1)
+    out = np.zeros(master.size, dtype=np.float32)
+    lib().orc_dense_effective(_p(master), C.c_uint64(first), C.c_uint64(master.size), C.c_uint64(seed),
+                              C.c_float(eps_signed), C.c_int(fmt), _p(out))
+    return out
+
+
+def dense_update(master, first, seed, eta, d_clipped):
+    master = _f32(master).reshape(-1).copy()
+    lib().orc_dense_update(_p(master), C.c_uint64(first), C.c_uint64(master.size), C.c_uint64(seed),
+                           C.c_float(eta), C.c_float(d_clipped))
+    return master
+
+
+def with_dense(model: Model, master, seed, eps_signed) -> Model:
+    """The model a perturbed pass sees: every 16-bit tensor replaced by round16(theta_u + eps z)."""
+    tensors = list(model.tensors)
+    for i, first, n, fmt in dense_slots(model):
+        tensors[i] = dense_effective(master[first:first + n], first, seed, eps_signed, fmt).reshape(
+            model.tensors[i].shape)
+    return Model(model.shape, tensors, model.names, model.scales, model.segments, model.group, model.quant)
+
+
+def qzo_step_joint(model: Model, master, tok, seed, eps, eta, eta_dense, Cthr, act_bf16=True):
+    """One iteration of Algorithm 1 with the scales (Q-SPSA) and the un-quantized parameters (SPSA)
+    perturbed together: one direction z over both, one scalar d', two updates."""
+    lp = forward_loss(with_dense(model, master, seed, +eps), perturbed_scales(model, seed, +eps), tok, act_bf16)
+    lm = forward_loss(with_dense(model, master, seed, -eps), perturbed_scales(model, seed, -eps), tok, act_bf16)
+    d = spsa_d(np.float32(lp), np.float32(lm), np.float32(eps))
+    if not np.isfinite(d):
+        return dict(loss_plus=lp, loss_minus=lm, d=d, d_clipped=0.0, status=1,
+                    scales=model.scales.copy(), master=_f32(master).copy())
+    dc = clip(d, Cthr)
+    return dict(loss_plus=lp, loss_minus=lm, d=d, d_clipped=dc, status=0,
+                scales=update_scales(model, seed, eta, dc),
+                master=dense_update(master, 0, seed, eta_dense, dc))
+
+
 def spsa_d(loss_plus, loss_minus, eps):
     return float(lib().orc_spsa_d(loss_plus, loss_minus, eps))
 

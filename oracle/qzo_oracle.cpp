@@ -552,6 +552,28 @@ void orc_update_channel_scales(float* c, uint32_t n_rows, uint32_t row_base, uin
   }
 }
 
+// ---- joint SPSA on the un-quantized parameters (Sec. 3.2: Q-SPSA on the scales may be combined
+// with plain SPSA, Def. 3.1, on the parameters that were never quantized; Sec. 4.1 does so in the
+// 2-bit runs).  These parameters form one flat fp32 master vector theta_u; entry i draws
+// z_i = flat_normal(seed, stream 2, i), the same seed as the scales but a stream of its own.
+// The model computes with 16-bit tensors, so a pass sees round16(theta_u + sigma*eps*z): one fp32
+// fma, then one round-to-nearest-even to the tensor's storage format (0: bf16, 1: fp16).
+void orc_dense_effective(const float* master, uint64_t first, uint64_t n, uint64_t seed,
+                         float eps_signed, int fmt, float* out) {
+  for (uint64_t i = 0; i < n; ++i) {
+    float v = std::fmaf(eps_signed, flat_normal(seed, 2u, first + i), master[i]);
+    out[i] = fmt == 1 ? fp16_rne(v) : bf16_rne(v);
+  }
+}
+// theta_u <- theta_u - eta_u * d' * z (ZO-SGD with the SPSA estimate, Eq. 2 with the clipped
+// scalar of Eq. 6; no clamp: these parameters may have either sign).  fp32 master: one fma.
+void orc_dense_update(float* master, uint64_t first, uint64_t n, uint64_t seed, float eta,
+                      float d_clipped) {
+  const float cstep = eta * d_clipped;
+  for (uint64_t i = 0; i < n; ++i)
+    master[i] = std::fmaf(-cstep, flat_normal(seed, 2u, first + i), master[i]);
+}
+
 // ----------------------------------------------------- model forward -----
 struct orc_config {
   uint32_t arch;        // 0 = Llama family (RMSNorm, RoPE, SwiGLU, no bias), 1 = OPT family

@@ -552,3 +552,112 @@ def test_asymmetric_forward_matches_torch_composition(oracle, arch):
     m8 = type(ms)(ms.shape, tensors, names, ms.scales, ms.segments, ms.group, 2)
     se_s = oracle.perturbed_scales(ms, seed=5, eps_signed=1e-3)
     assert oracle.forward_loss(m8, se_s, tok, act_bf16=True) == oracle.forward_loss(ms, se_s, tok, act_bf16=True)
+
+
+# --------------------------- joint SPSA on the un-quantized parameters (Sec. 3.2 / 4.1) ----
+def test_dense_stream_is_its_own_standard_normal_stream(oracle):
+    n = 1 << 18
+    z2 = oracle.flat_normals(11, 0, n, stream=2).astype(np.float64)
+    z1 = oracle.flat_normals(11, 0, n, stream=1).astype(np.float64)
+    assert abs(z2.mean()) < 4 / math.sqrt(n) and abs(z2.var() - 1) < 4 * math.sqrt(2 / n)
+    assert abs(np.mean(z2 ** 4) - 3) < 0.1
+    assert abs(np.corrcoef(z1, z2)[0, 1]) < 4 / math.sqrt(n)
+    # entry i does not depend on where the request starts (flat index = identity of the parameter)
+    assert np.array_equal(oracle.flat_normals(11, 1000, 64, stream=2), z2[1000:1064].astype(np.float32))
+
+
+@pytest.mark.parametrize("fmt,tdt", [(0, torch.bfloat16), (1, torch.float16)])
+def test_dense_effective_and_update_values(oracle, fmt, tdt):
+    rng = np.random.default_rng(31)
+    n, first, seed = 4096, 8 * 977, 5
+    master = (rng.standard_normal(n) * 0.05).astype(np.float32)
+    z = oracle.flat_normals(seed, first, n, stream=2).astype(np.float64)
+    # eps = 0: the pass sees the 16-bit rounding of the master (torch's own conversion)
+    want0 = torch.from_numpy(master).to(tdt).float().numpy()
+    assert np.array_equal(oracle.dense_effective(master, first, seed, 0.0, fmt), want0)
+    for eps in (1e-3, -1e-3):
+        e32 = float(np.float32(eps))
+        v32 = (master.astype(np.float64) + e32 * z).astype(np.float32)     # the one fp32 fma
+        want = torch.from_numpy(v32).to(tdt).float().numpy()
+        got = oracle.dense_effective(master, first, seed, eps, fmt)
+        assert np.array_equal(got, want)
+        assert (got != want0).mean() > 0.5
+    # update: theta <- theta - (eta d') z, fp32, no clamp
+    eta, d = np.float32(1e-4), np.float32(-37.5)
+    c = float(np.float32(eta * d))
+    want = (master.astype(np.float64) - c * z).astype(np.float32)
+    got = oracle.dense_update(master, first, seed, float(eta), float(d))
+    assert np.array_equal(got, want)
+    assert (got < 0).any() and (got > 0).any()
+
+
+@pytest.mark.parametrize("arch", ["llama", "opt"])
+def test_dense_slots_cover_every_16_bit_tensor_in_table_order(oracle, arch):
+    sh = dict(MINI, arch=arch)
+    m = oracle.build_model(sh, synth.tensor_table(sh, 3))
+    slots = oracle.dense_slots(m)
+    names = [m.names[i] for i, _, _, _ in slots]
+    assert names == [n for n, t in zip(m.names, m.tensors) if t.dtype == np.float32]
+    assert "tok_emb" in names and "lm_head" in names and not any(n.startswith("l0.w") for n in names)
+    master = oracle.dense_master(m)
+    assert master.size == sum(t.size for t in m.tensors if t.dtype == np.float32)
+    # a master made of 16-bit values passes through eps = 0 unchanged: same model, same loss
+    same = oracle.with_dense(m, master, 3, 0.0)
+    assert all(np.array_equal(a, b) for a, b in zip(same.tensors, m.tensors))
+    # each tensor's noise is the arena's flat stream at the tensor's offset
+    zall = oracle.flat_normals(3, 0, master.size, stream=2).astype(np.float64)
+    pert = oracle.with_dense(m, master, 3, 1e-3)
+    for i, first, n, fmt in slots:
+        v32 = (master[first:first + n].astype(np.float64) + float(np.float32(1e-3)) * zall[first:first + n]).astype(np.float32)
+        assert np.array_equal(pert.tensors[i].reshape(-1), torch.from_numpy(v32).to(torch.bfloat16).float().numpy())
+    for i, (a, b) in enumerate(zip(pert.tensors, m.tensors)):
+        if b.dtype != np.float32:
+            assert a is b                                   # quantized tensors are shared, untouched
+
+
+def test_joint_scalar_is_the_directional_derivative_over_both_parts(oracle):
+    # d of the joint pass ~ z_s . grad_s l + z_u . grad_u l, gradients by brute-force central differences
+    # in double.  The pass itself sees 16-bit tensors, whose rounding adds a few percent of noise to d.
+    sh = dict(arch="llama", n_layers=1, d_model=128, n_heads=2, d_ffn=128, vocab=16, max_seq=6,
+              batch=2, seq=6)
+    table = [(n, k, a * 3 if n in ("tok_emb", "lm_head") else a) for n, k, a in synth.tensor_table(sh, 9)]
+    m = oracle.build_model(sh, table)
+    tok = synth.tokens(sh, 10)
+    master = oracle.dense_master(m).astype(np.float64)
+    slots = oracle.dense_slots(m)
+    base_s = m.scales.astype(np.float64)
+
+    def loss(s, mu):
+        tensors = list(m.tensors)
+        for i, first, n, _ in slots:
+            tensors[i] = mu[first:first + n].astype(np.float32).reshape(m.tensors[i].shape)
+        mm = type(m)(m.shape, tensors, m.names, m.scales, m.segments, m.group, m.quant)
+        return oracle.forward_loss(mm, s, tok, False)
+
+    h = 1e-3                      # fp32 tensors: a step well above their resolution
+    gu = np.zeros(master.size)
+    for i in range(master.size):
+        e = np.zeros(master.size)
+        e[i] = h * max(abs(master[i]), 0.02)
+        gu[i] = (loss(base_s, master + e) - loss(base_s, master - e)) / (2 * e[i])
+    gs = np.zeros(base_s.size)
+    for i in range(base_s.size):
+        e = np.zeros(base_s.size)
+        e[i] = 1e-5
+        gs[i] = (loss(base_s + e, master) - loss(base_s - e, master)) / 2e-5
+    seed, eps = 21, 1e-3
+    zs = np.concatenate([oracle.scale_normals(seed, sg.row_base, sg.rows, sg.G).ravel() for sg in m.segments])
+    zu = oracle.flat_normals(seed, 0, master.size, stream=2).astype(np.float64)
+    want_s, want_u = gs @ zs, gu @ zu
+    m32 = master.astype(np.float32)
+    lp = oracle.forward_loss(oracle.with_dense(m, m32, seed, +eps), oracle.perturbed_scales(m, seed, +eps), tok, False)
+    lm = oracle.forward_loss(oracle.with_dense(m, m32, seed, -eps), oracle.perturbed_scales(m, seed, -eps), tok, False)
+    d = (lp - lm) / (2 * float(np.float32(eps)))
+    assert abs(want_u) > 0.2 * abs(want_s) > 0           # both parts matter in this case
+    print('joint d', d, 'scales part', want_s, 'dense part', want_u)
+    assert abs(d - (want_s + want_u)) < 0.04 * (abs(want_s) + abs(want_u))
+    # and the step composes its parts: same d, both updates from the one clipped scalar
+    r = oracle.qzo_step_joint(m, m32, tok, seed, eps, 1e-5, 1e-4, 100.0, act_bf16=False)
+    assert r["status"] == 0 and math.isclose(r["d"], d, rel_tol=1e-4)
+    assert np.array_equal(r["scales"], oracle.update_scales(m, seed, 1e-5, r["d_clipped"]))
+    assert np.array_equal(r["master"], oracle.dense_update(m32, 0, seed, 1e-4, r["d_clipped"]))
