@@ -133,9 +133,11 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama-2-7b")
-    ap.add_argument("--variant", default="int4", choices=["int4", "codebook"],
-                    help="int4 group-128 scales (the metric's configuration) or the codebook variant "
-                         "with per-channel scales (no cpu_baseline leg)")
+    ap.add_argument("--variant", default="int4", choices=["int4", "int4-zp", "codebook"],
+                    help="int4 group-128 scales (the metric's configuration), the same with per-group "
+                         "zero-points, or the codebook variant with per-channel scales (no cpu_baseline leg)")
+    ap.add_argument("--joint", action="store_true",
+                    help="joint mode: the un-quantized parameters are perturbed and updated too (SPSA)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--seq", type=int, default=0, help="override the workload's sequence length")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -165,13 +167,20 @@ def main():
     torch.cuda.set_device(0)
     codebook = args.variant == "codebook"
     # the counters were read on this one
-    main_cfg = args.workload == "llama-2-7b" and not codebook and not args.batch and not args.seq
+    main_cfg = (args.workload == "llama-2-7b" and args.variant == "int4" and not args.joint
+                and not args.batch and not args.seq)
     few_tokens = B * S <= 64 and not codebook      # the int4 GEMM takes its weight-streaming path
-    build = DeviceModel.synthetic_codebook if codebook else DeviceModel.synthetic
-    dm = build(shape, seed=1234, device="cuda:0")
+    if codebook:
+        dm = DeviceModel.synthetic_codebook(shape, seed=1234, device="cuda:0")
+    else:
+        dm = DeviceModel.synthetic(shape, seed=1234, device="cuda:0", asym=args.variant == "int4-zp")
     tok = torch.from_numpy(synth.tokens(shape, 5678)).cuda()
     eps, eta, clip = 1e-3, 1e-7, 100.0
     stream = torch.cuda.current_stream()
+    if args.joint:
+        dm.enable_joint()
+        plain_step = dm.step_joint
+        dm.step = lambda tok, seed, eps, eta, clip: plain_step(tok, seed, eps, eta, eta, clip)
 
     for i in range(args.warmup):
         dm.step(tok, 1 + i, eps, eta, clip)
@@ -212,8 +221,10 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}-shaped decoder, "
                                f"{'16-bit codes per 8 weights + fp16 channel scales' if codebook else 'int4 g128 RTN'}"
+                               f"{' with zero-points' if args.variant == 'int4-zp' else ''}"
                                f", full QZO step "
-                               f"(2 perturbed forwards + DDC + scale update)",
+                               f"(2 perturbed forwards + DDC + scale update"
+                               f"{'; un-quantized parameters perturbed and updated jointly' if args.joint else ''})",
                    "batch": B, "seq_len": S, "eps": eps, "eta": eta, "clip": clip},
         "steps_per_s": steps_per_s,
         "forward_tokens_per_s": 2 * B * S * steps_per_s,
@@ -240,6 +251,8 @@ def main():
                          if main_cfg else None},
         "device_memory_GiB": peak_bytes / 2 ** 30,
     }
+    if args.joint:
+        out["dense_parameters"] = int(dm.dense_master.numel())
     if few_tokens:
         # every int4 weight and scale is read once per launch: the roof is HBM
         wbytes = sum(N * K // 2 + N * K // 64 for _, N, K in synth.quantized_linears(shape))

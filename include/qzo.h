@@ -143,6 +143,33 @@ qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uin
                     uint64_t seed, float eps, float eta, float clip, void* workspace_dev,
                     uint64_t workspace_bytes, qzo_step_result* result_dev, void* stream);
 
+/*
+ * Joint mode (Sec. 3.2: Q-SPSA on the scales combined with SPSA, Def. 3.1, on the parameters that
+ * were never quantized; the 2-bit runs of Sec. 4.1 train both).  The un-quantized parameters
+ * theta_u are every 16-bit tensor of the model table (embeddings, norm gains and biases, lm_head;
+ * with quant = 1 also the fp16 codebooks), concatenated in table order into one caller-owned
+ * fp32 master vector dense_master_dev [n_dense], n_dense = qzo_model_dense_count(cfg).  Entry i
+ * draws z_i from the step's seed on a stream of its own (stream 2, Philox counter (i/8, 0)).
+ *
+ * After qzo_model_enable_joint the table's 16-bit tensors are derived data that the library
+ * WRITES: every forward first sets each of them to round16(theta_u + sign*eps*z) (one fp32 fma, one
+ * round-to-nearest-even to the tensor's bf16 or fp16), and qzo_step_joint ends by
+ *   theta_u <- theta_u - eta_dense * d' * z   (fp32, one fma, no clamp at zero)
+ * next to the scale update, and by bringing the 16-bit tensors back to round16(theta_u).  The
+ * master and the tensors must stay valid and unaliased for the model's lifetime; the caller
+ * initialises the master (normally from the 16-bit tensors).  The two perturbed passes are never
+ * stacked in joint mode.  Allocates a small device table (one entry per 16-bit tensor).
+ * Errors: QZO_ERR_SHAPE if n_dense is not the config's count, QZO_ERR_ALIGN if the master is not
+ * 16-byte aligned, QZO_ERR_ARG if joint mode is already on; qzo_step refuses a model in joint mode
+ * and qzo_step_joint one that is not.
+ */
+qzo_status qzo_model_dense_count(const qzo_model_config* cfg, uint64_t* out);
+qzo_status qzo_model_enable_joint(qzo_model* m, float* dense_master_dev, uint64_t n_dense);
+qzo_status qzo_step_joint(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                          uint64_t seed, float eps, float eta, float eta_dense, float clip,
+                          void* workspace_dev, uint64_t workspace_bytes,
+                          qzo_step_result* result_dev, void* stream);
+
 /* The update loop of Algorithm 1 alone over the model's arena, with d' given by
  * the host (eta*d' formed as one fp32 product). */
 qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float d_clipped,

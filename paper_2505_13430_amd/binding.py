@@ -23,6 +23,7 @@ QZO_ERR_NONFINITE, QZO_ERR_HIP, QZO_ERR_UNSUPPORTED = -5, -6, -7
 EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
+    "qzo_model_dense_count", "qzo_model_enable_joint", "qzo_step_joint",
     "qzo_apply_update", "qzo_dequant_gemm_zp", "qzo_repack_kmajor", "qzo_debug_dequant_zp", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
     "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_profile_begin", "qzo_profile_collect",
     "qzo_last_error",
@@ -125,6 +126,26 @@ def qzo_step(model, tokens, seed, eps, eta, clip, workspace, result, stream=None
                           C.c_float(eps), C.c_float(eta), C.c_float(clip), _ptr(workspace),
                           C.c_uint64(workspace.numel() * workspace.element_size()), _ptr(result),
                           _stream(stream)))
+
+
+def qzo_model_dense_count(shape: dict) -> int:
+    cfg = make_config(shape)
+    out = C.c_uint64(0)
+    _check(lib().qzo_model_dense_count(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def qzo_model_enable_joint(model, dense_master):
+    assert dense_master.dtype == torch.float32
+    _check(lib().qzo_model_enable_joint(model, _ptr(dense_master), C.c_uint64(dense_master.numel())))
+
+
+def qzo_step_joint(model, tokens, seed, eps, eta, eta_dense, clip, workspace, result, stream=None):
+    B, S = tokens.shape
+    _check(lib().qzo_step_joint(model, _ptr(tokens), C.c_uint32(B), C.c_uint32(S), C.c_uint64(seed),
+                                C.c_float(eps), C.c_float(eta), C.c_float(eta_dense), C.c_float(clip),
+                                _ptr(workspace), C.c_uint64(workspace.numel() * workspace.element_size()),
+                                _ptr(result), _stream(stream)))
 
 
 def read_step_result(result) -> dict:

@@ -58,6 +58,11 @@ struct qzo_model {
   UpdPlan plan;
   float* rope_table;      // device, Llama only
   uint32_t tensors_per_layer, first_layer_tensor;
+  // joint SPSA on the un-quantized parameters (off until qzo_model_enable_joint)
+  float* dense_master = nullptr;       // caller-owned fp32 [n_dense]
+  uint64_t n_dense = 0;
+  DenseSeg* dense_segs = nullptr;      // device, library-owned
+  uint32_t n_dense_segs = 0;
 };
 
 namespace {
@@ -121,12 +126,47 @@ qzo_status build_plan(const Linear* lin, int n_lin, uint32_t n_layers, UpdPlan& 
   return QZO_OK;
 }
 
+// Bytes and kind (0: bf16, 1: fp16, 2: packed integers) of every tensor of the model table.
+void table_layout(const qzo_model_config& c, std::vector<uint64_t>& need, std::vector<uint8_t>& kind) {
+  const bool llama = c.arch == 0, codebook = c.quant == 1, asym = c.quant == 2;
+  const uint64_t d = c.d_model, F = c.d_ffn, V = c.vocab;
+  auto b16 = [&](uint64_t n) { need.push_back(n * 2); kind.push_back(0); };
+  auto packed = [&](uint64_t bytes) { need.push_back(bytes); kind.push_back(2); };
+  b16(V * d);
+  if (!llama) b16((uint64_t)c.max_seq * d);
+  // a packed weight [N,K/2]; with zero-points, followed by its uint8 [N,K/128] tensor;
+  // codebook variant: uint16 codes [N,K/8], then the linear's fp16 [65536,8] codebook
+  auto weight = [&](uint64_t N, uint64_t K) {
+    if (codebook) {
+      packed(N * K / 4);
+      need.push_back(65536 * 16); kind.push_back(1);
+      return;
+    }
+    packed(N * K / 2);
+    if (asym) packed(N * K / 128);
+  };
+  for (uint32_t l = 0; l < c.n_layers; ++l) {
+    if (llama) {
+      b16(d); weight(3 * d, d); weight(d, d);
+      b16(d); weight(2 * F, d); weight(d, F);
+    } else {
+      b16(d); b16(d);
+      weight(3 * d, d); b16(3 * d); weight(d, d); b16(d);
+      b16(d); b16(d);
+      weight(F, d); b16(F); weight(d, F); b16(d);
+    }
+  }
+  b16(d);
+  if (!llama) b16(d);
+  b16(V * d);
+}
+
 Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   const qzo_model_config& c = m->cfg;
   // With very few tokens qzo_step stacks its two perturbed passes into one forward
   // over 2 * batch sequences (the int4 weights are then read once per step).
   const uint64_t M1 = (uint64_t)batch * seq;
-  const bool stack = M1 <= SKINNY_MAX_M_DUAL && c.quant != 1;
+  const bool stack = M1 <= SKINNY_MAX_M_DUAL && c.quant != 1 && !m->dense_master;
   const uint64_t M = stack ? 2 * M1 : M1, d = c.d_model, F = c.d_ffn;
   const uint64_t n_slices = ((c.vocab + 255) / 256) * 4;
   Workspace w;
@@ -208,6 +248,11 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
   const unsigned char* arena = (const unsigned char*)m->arena;
 
+  if (m->dense_master) {      // joint mode: the 16-bit tensors become round16(theta_u + eps_signed z)
+    ProfScope ps(PK_OTHER, 0, st);
+    QZO_HIP(launch_dense_perturb(m->dense_master, m->dense_segs, m->n_dense_segs, m->n_dense, seed_lo,
+                                 seed_hi, eps_signed, st));
+  }
   {
     ProfScope ps(PK_OTHER, 0, st);
     QZO_HIP(launch_embed(tok, M1, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
@@ -363,35 +408,9 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
       0xffffffffull)
     return fail(QZO_ERR_SHAPE, "too many quantized rows");
 
-  const uint64_t d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab;
   std::vector<uint64_t> need;
-  need.push_back(V * d * 2);
-  if (!llama) need.push_back((uint64_t)cfg->max_seq * d * 2);
-  for (uint32_t l = 0; l < cfg->n_layers; ++l) {
-    if (codebook) {
-      const uint64_t cbb = 65536 * 16;
-      const uint64_t b[10] = {d * 2, 3 * d * d / 4, cbb, d * d / 4, cbb, d * 2, 2 * F * d / 4, cbb, d * F / 4, cbb};
-      need.insert(need.end(), b, b + 10);
-    } else {
-      // a packed weight [N,K/2]; with zero-points, followed by its uint8 [N,K/128] tensor
-      auto weight = [&](uint64_t N, uint64_t K) {
-        need.push_back(N * K / 2);
-        if (asym) need.push_back(N * K / 128);
-      };
-      if (llama) {
-        need.push_back(d * 2); weight(3 * d, d); weight(d, d);
-        need.push_back(d * 2); weight(2 * F, d); weight(d, F);
-      } else {
-        need.push_back(d * 2); need.push_back(d * 2);
-        weight(3 * d, d); need.push_back(3 * d * 2); weight(d, d); need.push_back(d * 2);
-        need.push_back(d * 2); need.push_back(d * 2);
-        weight(F, d); need.push_back(F * 2); weight(d, F); need.push_back(d * 2);
-      }
-    }
-  }
-  need.push_back(d * 2);
-  if (!llama) need.push_back(d * 2);
-  need.push_back(V * d * 2);
+  std::vector<uint8_t> kind;
+  table_layout(*cfg, need, kind);
   for (uint32_t i = 0; i < n_tensors; ++i) {
     if (!tensors[i].ptr_dev) return fail(QZO_ERR_ARG, "tensor " + std::to_string(i) + " is null");
     if (!aligned16(tensors[i].ptr_dev))
@@ -433,7 +452,58 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
 qzo_status qzo_model_destroy(qzo_model* m) {
   if (!m) return QZO_OK;
   if (m->rope_table) (void)hipFree(m->rope_table);
+  if (m->dense_segs) (void)hipFree(m->dense_segs);
   delete m;
+  return QZO_OK;
+}
+
+qzo_status qzo_model_dense_count(const qzo_model_config* cfg, uint64_t* out) {
+  qzo_status st = check_cfg(cfg);
+  if (st != QZO_OK) return st;
+  if (!out) return fail(QZO_ERR_ARG, "out is null");
+  std::vector<uint64_t> need;
+  std::vector<uint8_t> kind;
+  table_layout(*cfg, need, kind);
+  uint64_t n = 0;
+  for (size_t i = 0; i < need.size(); ++i)
+    if (kind[i] != 2) n += need[i] / 2;
+  *out = n;
+  return QZO_OK;
+}
+
+qzo_status qzo_model_enable_joint(qzo_model* m, float* dense_master_dev, uint64_t n_dense) {
+  if (!m || !dense_master_dev) return fail(QZO_ERR_ARG, "null argument");
+  if (m->dense_master) return fail(QZO_ERR_ARG, "joint mode is already on");
+  if (!aligned16(dense_master_dev)) return fail(QZO_ERR_ALIGN, "dense master not 16-byte aligned");
+  uint64_t want = 0;
+  qzo_model_dense_count(&m->cfg, &want);
+  if (n_dense != want) return fail(QZO_ERR_SHAPE, "n_dense does not match the config");
+  std::vector<uint64_t> need;
+  std::vector<uint8_t> kind;
+  table_layout(m->cfg, need, kind);
+  std::vector<DenseSeg> segs;
+  uint64_t first = 0;
+  for (size_t i = 0; i < need.size(); ++i) {
+    if (kind[i] == 2) continue;
+    const uint64_t n = need[i] / 2;
+    if (n % 8) return fail(QZO_ERR_SHAPE, "a 16-bit tensor's size is not a multiple of 8");
+    DenseSeg sg = {};
+    sg.first8 = first / 8;
+    sg.out = const_cast<void*>(m->T[i].ptr_dev);
+    sg.fmt = kind[i];
+    segs.push_back(sg);
+    first += n;
+  }
+  QZO_HIP(hipMalloc((void**)&m->dense_segs, segs.size() * sizeof(DenseSeg)));
+  hipError_t e = hipMemcpy(m->dense_segs, segs.data(), segs.size() * sizeof(DenseSeg), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(m->dense_segs);
+    m->dense_segs = nullptr;
+    return hip_fail(e, "dense segment table");
+  }
+  m->n_dense_segs = (uint32_t)segs.size();
+  m->n_dense = n_dense;
+  m->dense_master = dense_master_dev;
   return QZO_OK;
 }
 
@@ -470,17 +540,19 @@ qzo_status qzo_debug_forward(qzo_model* m, const int32_t* tokens_dev, uint32_t b
                  (hipStream_t)stream, hidden_dev);
 }
 
-qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
-                    uint64_t seed, float eps, float eta, float clip, void* workspace_dev,
-                    uint64_t workspace_bytes, qzo_step_result* result_dev, void* stream) {
+static qzo_status step_impl(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                            uint64_t seed, float eps, float eta, float eta_dense, float clip,
+                            void* workspace_dev, uint64_t workspace_bytes, qzo_step_result* result_dev,
+                            void* stream) {
   qzo_status st = check_batch(m, tokens_dev, batch, seq, workspace_dev, workspace_bytes);
   if (st != QZO_OK) return st;
   if (!result_dev) return fail(QZO_ERR_ARG, "result_dev is null");
   if (!(clip >= 0.0f)) return fail(QZO_ERR_ARG, "clip must be >= 0");
-  if (!std::isfinite(eps) || !std::isfinite(eta)) return fail(QZO_ERR_ARG, "eps/eta not finite");
+  if (!std::isfinite(eps) || !std::isfinite(eta) || !std::isfinite(eta_dense))
+    return fail(QZO_ERR_ARG, "eps/eta not finite");
   hipStream_t s = (hipStream_t)stream;
   Workspace w = carve(m, batch, seq, workspace_dev);
-  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && m->cfg.quant != 1) {
+  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && m->cfg.quant != 1 && !m->dense_master) {
     // few tokens: one forward over both passes, the weights are read once
     st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s, nullptr, 2, w.losses + 1);
     if (st != QZO_OK) return st;
@@ -500,7 +572,32 @@ qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uin
       QZO_HIP(launch_scale_update(m->arena, m->plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta, 0.0f,
                                   result_dev, s));
   }
+  if (m->dense_master) {
+    // SPSA part of the joint step, then the 16-bit tensors are brought back to round16(theta_u)
+    ProfScope ps(PK_OTHER, 0, s);
+    QZO_HIP(launch_dense_update(m->dense_master, m->n_dense, (uint32_t)seed, (uint32_t)(seed >> 32),
+                                eta_dense, 0.0f, result_dev, s));
+    QZO_HIP(launch_dense_perturb(m->dense_master, m->dense_segs, m->n_dense_segs, m->n_dense,
+                                 (uint32_t)seed, (uint32_t)(seed >> 32), 0.0f, s));
+  }
   return QZO_OK;
+}
+
+qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                    uint64_t seed, float eps, float eta, float clip, void* workspace_dev,
+                    uint64_t workspace_bytes, qzo_step_result* result_dev, void* stream) {
+  if (m && m->dense_master) return fail(QZO_ERR_ARG, "the model is in joint mode: call qzo_step_joint");
+  return step_impl(m, tokens_dev, batch, seq, seed, eps, eta, 0.0f, clip, workspace_dev, workspace_bytes,
+                   result_dev, stream);
+}
+
+qzo_status qzo_step_joint(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
+                          uint64_t seed, float eps, float eta, float eta_dense, float clip,
+                          void* workspace_dev, uint64_t workspace_bytes, qzo_step_result* result_dev,
+                          void* stream) {
+  if (m && !m->dense_master) return fail(QZO_ERR_ARG, "joint mode is off: call qzo_model_enable_joint first");
+  return step_impl(m, tokens_dev, batch, seq, seed, eps, eta, eta_dense, clip, workspace_dev,
+                   workspace_bytes, result_dev, stream);
 }
 
 qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float d_clipped,

@@ -113,6 +113,92 @@ hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, ui
   return hipGetLastError();
 }
 
+// ---- joint SPSA on the un-quantized parameters (Sec. 3.2; the 2-bit setup of Sec. 4.1) ----
+// theta_u is one flat fp32 master vector; entry i draws z_i from stream 2 at counter (i/8, 0)
+// (eight consecutive entries share a Philox counter).  A thread owns eight entries.
+//
+// Perturbation: the model's 16-bit tensor that entry i belongs to receives
+// round16(theta_i + sigma*eps*z_i) (one fp32 fma, one RNE to bf16 or fp16).  Tensors start at
+// multiples of 8 entries; `segs` is sorted by first entry and searched per thread.
+__global__ __launch_bounds__(256) void dense_perturb_kernel(const float* __restrict__ master,
+                                                            const DenseSeg* __restrict__ segs,
+                                                            uint32_t n_seg, uint64_t n8,
+                                                            uint32_t seed_lo, uint32_t seed_hi,
+                                                            float eps_signed) {
+  const uint64_t t = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  if (t >= n8) return;
+  uint32_t lo = 0, hi = n_seg;            // last segment with first8 <= t
+  while (hi - lo > 1) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (segs[mid].first8 <= t) lo = mid; else hi = mid;
+  }
+  const DenseSeg sg = segs[lo];
+  float z[8];
+  scale_normals8(seed_lo, seed_hi, 2u, (uint32_t)t, (uint32_t)(t >> 32), z);
+  const float4 a = reinterpret_cast<const float4*>(master)[2 * t];
+  const float4 b = reinterpret_cast<const float4*>(master)[2 * t + 1];
+  const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  uint32_t out[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float e0 = __builtin_fmaf(eps_signed, z[2 * j], v[2 * j]);
+    const float e1 = __builtin_fmaf(eps_signed, z[2 * j + 1], v[2 * j + 1]);
+    if (sg.fmt == 1) {
+      const _Float16 h0 = (_Float16)e0, h1 = (_Float16)e1;
+      out[j] = (uint32_t)__builtin_bit_cast(uint16_t, h0) | ((uint32_t)__builtin_bit_cast(uint16_t, h1) << 16);
+    } else {
+      out[j] = pack_bf16x2(e0, e1);
+    }
+  }
+  reinterpret_cast<uint4*>(sg.out)[t - sg.first8] = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+hipError_t launch_dense_perturb(const float* master, const DenseSeg* segs_dev, uint32_t n_seg,
+                                uint64_t n_dense, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+                                hipStream_t st) {
+  const uint64_t n8 = n_dense / 8;
+  if (n8 == 0) return hipSuccess;
+  dense_perturb_kernel<<<(uint32_t)((n8 + 255) / 256), 256, 0, st>>>(master, segs_dev, n_seg, n8, seed_lo,
+                                                                     seed_hi, eps_signed);
+  return hipGetLastError();
+}
+
+// Update: theta_i <- theta_i - eta_u * d' * z_i (fp32, one fma, no clamp).
+__global__ __launch_bounds__(256) void dense_update_kernel(float* __restrict__ master, uint64_t n8,
+                                                           uint32_t seed_lo, uint32_t seed_hi, float eta,
+                                                           float dclip_host,
+                                                           const qzo_step_result* __restrict__ res) {
+  float c;
+  if (res) {
+    if (res->status != 0) return;
+    c = eta * res->d_clipped;
+  } else {
+    c = eta * dclip_host;
+  }
+  const uint64_t t = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  if (t >= n8) return;
+  float z[8];
+  scale_normals8(seed_lo, seed_hi, 2u, (uint32_t)t, (uint32_t)(t >> 32), z);
+  float4* p = reinterpret_cast<float4*>(master) + 2 * t;
+  float4 a = p[0], b = p[1];
+  const float nc = -c;
+  a.x = __builtin_fmaf(nc, z[0], a.x); a.y = __builtin_fmaf(nc, z[1], a.y);
+  a.z = __builtin_fmaf(nc, z[2], a.z); a.w = __builtin_fmaf(nc, z[3], a.w);
+  b.x = __builtin_fmaf(nc, z[4], b.x); b.y = __builtin_fmaf(nc, z[5], b.y);
+  b.z = __builtin_fmaf(nc, z[6], b.z); b.w = __builtin_fmaf(nc, z[7], b.w);
+  p[0] = a;
+  p[1] = b;
+}
+
+hipError_t launch_dense_update(float* master, uint64_t n_dense, uint32_t seed_lo, uint32_t seed_hi,
+                               float eta, float d_clipped, const qzo_step_result* res, hipStream_t st) {
+  const uint64_t n8 = n_dense / 8;
+  if (n8 == 0) return hipSuccess;
+  dense_update_kernel<<<(uint32_t)((n8 + 255) / 256), 256, 0, st>>>(master, n8, seed_lo, seed_hi, eta,
+                                                                    d_clipped, res);
+  return hipGetLastError();
+}
+
 // ------------------------------------------- SPSA scalar + DDC (Eq. 6) ----
 __global__ void spsa_clip_kernel(const float* __restrict__ losses, float eps, float clip,
                                  qzo_step_result* __restrict__ res) {

@@ -63,6 +63,18 @@ hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st);
 hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,
                                  uint32_t seed_hi, float eta, float d_clipped,
                                  const qzo_step_result* res, hipStream_t st);
+// One 16-bit tensor of the model table inside the flat vector of un-quantized parameters.
+struct DenseSeg {
+  uint64_t first8;     // first entry / 8
+  void* out;           // the tensor (device), written by the perturbation
+  uint32_t fmt;        // 0: bf16, 1: fp16
+  uint32_t pad;
+};
+hipError_t launch_dense_perturb(const float* master, const DenseSeg* segs_dev, uint32_t n_seg,
+                                uint64_t n_dense, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+                                hipStream_t st);
+hipError_t launch_dense_update(float* master, uint64_t n_dense, uint32_t seed_lo, uint32_t seed_hi,
+                               float eta, float d_clipped, const qzo_step_result* res, hipStream_t st);
 uint32_t gemm_workgroups(uint32_t M, uint32_t N);
 
 // lm_head GEMM with the cross-entropy folded into the epilogue: for every row

@@ -23,6 +23,7 @@ class DeviceModel:
         self._ws_key = None
         self.result = torch.zeros(8, dtype=torch.int32, device=scale_arena.device)
         self.loss = torch.zeros(2, dtype=torch.float32, device=scale_arena.device)
+        self.dense_master = None
 
     @classmethod
     def from_host(cls, shape: dict, host_tensors, host_scales, device="cuda:0"):
@@ -151,6 +152,22 @@ class DeviceModel:
     def step(self, tokens, seed, eps, eta, clip, stream=None) -> torch.Tensor:
         ws = self.workspace(*tokens.shape)
         qb.qzo_step(self.handle, tokens, seed, eps, eta, clip, ws, self.result, stream)
+        return self.result
+
+    def enable_joint(self):
+        """Joint mode: an fp32 master of every 16-bit tensor (table order), copied from the tensors;
+        from here on the library rewrites those tensors from the master."""
+        parts = [t.reshape(-1) for t in self.tensors if t.dtype in (torch.bfloat16, torch.float16)]
+        self.dense_master = torch.cat(parts).to(torch.float32)       # a copy: dtype conversion only
+        assert self.dense_master.numel() == qb.qzo_model_dense_count(self.shape)
+        qb.qzo_model_enable_joint(self.handle, self.dense_master)
+        self._ws = None                                              # the workspace layout may differ
+        self._ws_key = None
+        return self.dense_master
+
+    def step_joint(self, tokens, seed, eps, eta, eta_dense, clip, stream=None) -> torch.Tensor:
+        ws = self.workspace(*tokens.shape)
+        qb.qzo_step_joint(self.handle, tokens, seed, eps, eta, eta_dense, clip, ws, self.result, stream)
         return self.result
 
     def apply_update(self, seed, eta, d_clipped, stream=None):

@@ -538,3 +538,66 @@ def test_codebook_model_step(oracle, shape, eta):
     assert np.array_equal(_bits(got), _bits(oracle.update_scales(om, 4, eta, res["d_clipped"])))
     print("codebook d gpu", res["d"], "oracle", ref["d"], "changed", float((got != om.scales).mean()))
     dm.close()
+
+
+# ------------------- joint SPSA on the un-quantized parameters (Sec. 3.2 / 4.1) ----
+def _t16_bits(t):
+    return t.view(torch.int16).cpu().numpy()
+
+
+def _host16_bits(a, fmt):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(torch.float16 if fmt == 1 else torch.bfloat16).view(torch.int16).numpy()
+
+
+def _joint_models(oracle, name):
+    if name == "codebook":
+        shape = dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48,
+                     batch=3, seq=40)
+        table = synth.codebook_tensor_table(shape, 31)
+        return shape, oracle.build_codebook_model(shape, table), DeviceModel.from_host_codebook(shape, table, DEV)
+    shape, asym = _case(name)
+    om, dm = _models(oracle, shape, 1234, asym=asym)
+    return shape, om, dm
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "few_llama", "tiny+zp", "codebook"])
+def test_joint_step_matches_oracle(oracle, name):
+    shape, om, dm = _joint_models(oracle, name)
+    tok = synth.tokens(shape, 5678)
+    tokd = _dev(tok)
+    slots = oracle.dense_slots(om)
+    master0 = oracle.dense_master(om)
+    md = dm.enable_joint()
+    assert md.numel() == master0.size and np.array_equal(_bits(md.cpu().numpy()), _bits(master0))
+    dev16 = [t for t in dm.tensors if t.dtype in (torch.bfloat16, torch.float16)]
+    assert len(dev16) == len(slots)
+    seed, eps, eta, eta_u = 3, 1e-3, 1e-5, 1e-4
+    # one perturbed pass: the 16-bit tensors it leaves behind are the oracle's, bit for bit
+    for sign in (1, -1):
+        loss = float(dm.forward_loss(tokd, seed, eps, sign).item())
+        pert = oracle.with_dense(om, master0, seed, sign * np.float32(eps))
+        for t, (i, first, n, fmt) in zip(dev16, slots):
+            assert np.array_equal(_t16_bits(t).reshape(-1), _host16_bits(pert.tensors[i], fmt).reshape(-1)), om.names[i]
+        ref_loss = oracle.forward_loss(pert, oracle.perturbed_scales(om, seed, sign * np.float32(eps)), tok)
+        assert abs(loss - ref_loss) <= 2e-2 * abs(ref_loss)
+    with pytest.raises(qb.QzoError):
+        dm.step(tokd, seed, eps, eta, 100.0)                      # plain step refused in joint mode
+    ref = oracle.qzo_step_joint(om, master0, tok, seed, eps, eta, eta_u, 100.0)
+    res = qb.read_step_result(dm.step_joint(tokd, seed, eps, eta, eta_u, 100.0))
+    assert res["status"] == 0
+    print(name, "joint d gpu", res["d"], "oracle", ref["d"])
+    for k in ("loss_plus", "loss_minus"):
+        assert abs(res[k] - ref[k]) <= 2e-2 * abs(ref[k])
+    got_s = dm.scales.float().cpu().numpy()
+    assert (np.abs(got_s - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-6).all()
+    assert np.array_equal(_bits(got_s), _bits(oracle.update_scales(om, seed, eta, res["d_clipped"])))
+    # the master: exactly the oracle's update for the d' the device found, and close to the oracle's own
+    got_m = md.cpu().numpy()
+    assert np.array_equal(_bits(got_m), _bits(oracle.dense_update(master0, 0, seed, eta_u, res["d_clipped"])))
+    assert not np.array_equal(got_m, master0)
+    assert np.abs(got_m - ref["master"]).max() <= eta_u * abs(res["d_clipped"] - ref["d_clipped"]) * 6 + 1e-7
+    # and the 16-bit tensors are back at round16(master)
+    for t, (i, first, n, fmt) in zip(dev16, slots):
+        assert np.array_equal(_t16_bits(t).reshape(-1), _host16_bits(got_m[first:first + n], fmt))
+    dm.close()
