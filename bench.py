@@ -187,7 +187,7 @@ def main():
     torch.cuda.synchronize()
 
     n_lin = 4 * shape["n_layers"] * 2
-    qb.qzo_profile_begin(args.steps * (n_lin + 2 * shape["n_layers"] + 8))
+    qb.qzo_profile_begin(args.steps * (2 * n_lin + 2 * shape["n_layers"] + 16))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):

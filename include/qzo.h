@@ -272,6 +272,14 @@ qzo_status qzo_debug_dequant_zp(const void* q_dev, const void* s_dev, const void
                                 uint32_t row_base, uint32_t N, uint32_t K, uint32_t group,
                                 uint64_t seed, float eps, int sign, void* w_eff_dev, void* stream);
 
+/* Inspection: the second stage of the expand-then-multiply paths on its own, Y = X W^T with a plain
+ * bf16 weight matrix w_dev [N,K] (x_dev bf16 [M,K], y_dev bf16 [M,N], fp32 accumulation, no epilogue).
+ * pipe: 0 or 1, the two instruction orders of the 512-thread kernel (1 is the one the model uses);
+ * 2 or 3, the same with 256 threads.  K a positive multiple of 128, N a multiple of 8, pointers
+ * 16-byte aligned, M*K and N*K below 2^30 elements. */
+qzo_status qzo_debug_bf16_gemm(const void* x_dev, const void* w_dev, uint32_t M, uint32_t N, uint32_t K,
+                               int pipe, void* y_dev, void* stream);
+
 /* Measurement aid, not part of the method: one 512-thread workgroup per compute unit, each
  * wavefront issuing iters x 16 v_mfma_f32_32x32x16_bf16 (32768 flop each) on register operands
  * that are all zero (random_operands = 0) or pseudo-random bf16 values, with no memory traffic.

@@ -25,7 +25,7 @@ EXPORTS = [
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
     "qzo_model_dense_count", "qzo_model_enable_joint", "qzo_step_joint",
     "qzo_apply_update", "qzo_dequant_gemm_zp", "qzo_repack_kmajor", "qzo_debug_dequant_zp", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
-    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_profile_begin", "qzo_profile_collect",
+    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_debug_bf16_gemm", "qzo_profile_begin", "qzo_profile_collect",
     "qzo_last_error",
 ]
 
@@ -221,6 +221,13 @@ def qzo_debug_dequant(q, s, row_base, seed, eps, sign, w_eff, group=128, stream=
     _check(lib().qzo_debug_dequant(_ptr(q), _ptr(s), C.c_uint32(row_base), C.c_uint32(N),
                                    C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
                                    C.c_float(eps), C.c_int(sign), _ptr(w_eff), _stream(stream)))
+
+
+def qzo_debug_bf16_gemm(x, w, y, pipe=1, stream=None):
+    M, K = x.shape
+    N = w.shape[0]
+    _check(lib().qzo_debug_bf16_gemm(_ptr(x), _ptr(w), C.c_uint32(M), C.c_uint32(N), C.c_uint32(K),
+                                     C.c_int(pipe), _ptr(y), _stream(stream)))
 
 
 def qzo_debug_dequant_zp(q, s, zp, row_base, seed, eps, sign, w_eff, group=128, stream=None):

@@ -42,6 +42,7 @@ struct Linear {           // one quantized linear of a layer
 struct Workspace {
   unsigned char *h, *a, *qkv, *att, *ff, *act;
   float *ce_part, *tgt, *rowloss, *losses, *skinny;
+  unsigned char* wexp;      // one linear's expanded bf16 weights (expand-then-multiply paths)
   uint64_t total;
 };
 
@@ -193,6 +194,12 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
       sk = std::max<uint64_t>(sk, skinny_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.skinny = (float*)take(sk * 4);
   if (sk == 0) w.skinny = nullptr;
+  // codebook variant with many tokens: the largest linear written out as bf16
+  uint64_t ex = 0;
+  if (M1 >= EXPAND_MIN_M && c.quant == 1)
+    for (int i = 0; i < 4; ++i) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
+  w.wexp = take(ex);
+  if (ex == 0) w.wexp = nullptr;
   w.total = off;
   return w;
 }
@@ -297,6 +304,18 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.M = M; g.N = m->lin[li].N; g.K = m->lin[li].K;
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
+      if (w.wexp) {
+        // many tokens: reconstruct the perturbed matrix once, then a plain bf16 GEMM
+        {
+          ProfScope pe(PK_OTHER, 0, st);
+          hipError_t e = launch_expand_codebook(codes, cb, g.s, g.N, g.K, g.row_base, seed_lo, seed_hi,
+                                                eps_signed, (epi & EPI_SWIGLU) != 0, w.wexp, st);
+          if (e != hipSuccess) return e;
+        }
+        g.w = w.wexp; g.cb = nullptr; g.s = nullptr;
+        ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+        return launch_bf16_gemm(g, 1, st);
+      }
       ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
       return launch_codebook_gemm(g, st);
     };
@@ -746,6 +765,20 @@ qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const voi
   }
   QZO_HIP(launch_codebook_gemm(g, st));
   if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  return QZO_OK;
+}
+
+qzo_status qzo_debug_bf16_gemm(const void* x_dev, const void* w_dev, uint32_t M, uint32_t N, uint32_t K,
+                               int pipe, void* y_dev, void* stream) {
+  if (!x_dev || !w_dev || !y_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(x_dev) || !aligned16(w_dev) || !aligned16(y_dev))
+    return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
+  if (K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "K must be a positive multiple of 128");
+  if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
+  if (pipe < 0 || pipe > 3) return fail(QZO_ERR_ARG, "pipe must be 0..3");
+  GemmArgs g = {};
+  g.x = x_dev; g.w = w_dev; g.y = y_dev; g.M = M; g.N = N; g.K = K;
+  QZO_HIP(launch_bf16_gemm(g, pipe, (hipStream_t)stream));
   return QZO_OK;
 }
 

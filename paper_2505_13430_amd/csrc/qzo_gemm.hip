@@ -795,6 +795,39 @@ hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Plain GEMM on a bf16 weight matrix [N,K] (the second stage of the expand-then-multiply
+// paths): same tiling, no conversion in the loop.
+hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st) {
+  static bool ready = false;
+  if (!ready) {
+    hipError_t e = set_lds_attr((const void*)gemm_kernel<1, false, 4, 0>);
+    if (e == hipSuccess) e = set_lds_attr((const void*)gemm_kernel<1, false, 4, 1>);
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
+  if (a.M == 0 || a.N == 0) return hipSuccess;
+  if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K * 2 >= (1ull << 31))
+    return hipErrorInvalidValue;
+  CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
+  if (pipe == 2 || pipe == 3) {        // one wavefront per SIMD, 128 x 128 per wavefront
+    static bool ready2 = false;
+    if (!ready2) {
+      hipError_t e = set_lds_attr((const void*)gemm_kernel<1, false, 2, 0>);
+      if (e == hipSuccess) e = set_lds_attr((const void*)gemm_kernel<1, false, 2, 1>);
+      if (e != hipSuccess) return e;
+      ready2 = true;
+    }
+    if (pipe == 3)
+      gemm_kernel<1, false, 2, 1><<<gemm_workgroups(a.M, a.N), 256, LDS_BYTES, st>>>(a, ce);
+    else
+      gemm_kernel<1, false, 2, 0><<<gemm_workgroups(a.M, a.N), 256, LDS_BYTES, st>>>(a, ce);
+  } else if (pipe == 1)
+    gemm_kernel<1, false, 4, 1><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES, st>>>(a, ce);
+  else
+    gemm_kernel<1, false, 4, 0><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES, st>>>(a, ce);
+  return hipGetLastError();
+}
+
 hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   static bool ready = false;
   if (!ready) {

@@ -60,6 +60,13 @@ uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi);   // EPI_SU
 hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st);
 // w = uint16 codes [N,K/8]; cb and s as above; N % 8 == 0, K % 128 == 0.
 hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st);
+hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st);
+// One linear's perturbed weights written out as bf16 [N,K] (rows in the GEMM's tile order
+// when the consumer fuses SwiGLU), for launch_bf16_gemm.
+hipError_t launch_expand_codebook(const void* codes, const void* cb, const void* c_fp16, uint32_t N,
+                                  uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi,
+                                  float eps_signed, bool swiglu, void* out_bf16, hipStream_t st);
+constexpr uint32_t EXPAND_MIN_M = 512;   // fewer tokens: the fused kernels read less than an expansion writes
 hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,
                                  uint32_t seed_hi, float eta, float d_clipped,
                                  const qzo_step_result* res, hipStream_t st);

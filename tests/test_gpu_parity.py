@@ -505,9 +505,12 @@ def test_codebook_linear_matches_oracle(oracle, M, N, K):
 
 
 @pytest.mark.parametrize("shape,eta", [
-    (dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48, batch=3, seq=40), 1e-3),
+    (dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48, batch=3, seq=40), 1e-1),
     # Llama-2-13B widths, one layer, short batch (a smaller step: d carries the losses' noise x 500)
-    (dict(synth.SHAPES["llama-2-13b"], n_layers=1, batch=1, seq=16, max_seq=32), 1e-5)], ids=["tiny", "13b-width"])
+    # 576 tokens: every linear is first written out as a perturbed bf16 matrix (expand-then-multiply)
+    (dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48, batch=12, seq=48), 1e-1),
+    (dict(synth.SHAPES["llama-2-13b"], n_layers=1, batch=1, seq=16, max_seq=32), 1e-5)],
+    ids=["tiny", "tiny-576-tokens", "13b-width"])
 def test_codebook_model_step(oracle, shape, eta):
     table = synth.codebook_tensor_table(shape, 31)
     om = oracle.build_codebook_model(shape, table)
@@ -601,3 +604,16 @@ def test_joint_step_matches_oracle(oracle, name):
     for t, (i, first, n, fmt) in zip(dev16, slots):
         assert np.array_equal(_t16_bits(t).reshape(-1), _host16_bits(got_m[first:first + n], fmt))
     dm.close()
+
+
+@pytest.mark.parametrize("M,N,K,pipe", [(300, 520, 384, 1), (513, 264, 1280, 0), (300, 520, 384, 3), (64, 136, 512, 2)])
+def test_plain_bf16_gemm_matches_oracle(oracle, M, N, K, pipe):
+    rng = np.random.default_rng(M + N + K)
+    x = synth.bf16_exact(rng.standard_normal((M, K), dtype=np.float32))
+    w = synth.bf16_exact(rng.standard_normal((N, K), dtype=np.float32) * np.float32(0.05))
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_debug_bf16_gemm(_dev(x, torch.bfloat16), _dev(w, torch.bfloat16), y, pipe)
+    ref = oracle.linear(x.astype(np.float64), w)
+    err = np.abs(y.float().cpu().numpy() - ref)
+    assert (err <= 2e-2 * np.abs(ref) + 2e-2 * math.sqrt(K) * 0.05).all()
+    assert err.max() <= 1e-2 * np.abs(ref).max()
