@@ -158,6 +158,45 @@ def rtn_quantize_asym(w, group=128):
     return qp, zp, s
 
 
+def nf4_levels():
+    out = np.zeros(16, dtype=np.float32)
+    lib().orc_nf4_levels(_p(out))
+    return out
+
+
+def nf4_quantize(w, block=64):
+    """NormalFloat-4 blocks: (indices [N,K/2], bf16 absmax scales [N,K/block])."""
+    w = _f32(w)
+    N, K = w.shape
+    qp = np.zeros((N, K // 2), dtype=np.uint8)
+    s = np.zeros((N, K // block), dtype=np.float32)
+    lib().orc_nf4_quantize(_p(w), C.c_uint64(N), C.c_uint64(K), C.c_uint32(block), _p(qp), _p(s))
+    return qp, s
+
+
+def dequant_nf4(qp, s, seed, row_base, eps_signed, block=64, to_bf16=False):
+    qp = np.ascontiguousarray(qp, dtype=np.uint8)
+    s = _f32(s)
+    N, K = qp.shape[0], qp.shape[1] * 2
+    out = np.zeros((N, K), dtype=np.float32)
+    lib().orc_dequant_nf4(_p(qp), _p(s), C.c_uint64(N), C.c_uint64(K), C.c_uint32(block), C.c_uint64(seed),
+                          C.c_uint32(row_base), C.c_float(eps_signed), C.c_int(1 if to_bf16 else 0), _p(out))
+    return out
+
+
+def qlinear_nf4(x, qp, s_eff, block=64, bias=None):
+    x = _f64(x)
+    qp = np.ascontiguousarray(qp, dtype=np.uint8)
+    s_eff = _f64(s_eff)
+    M, K = x.shape
+    N = qp.shape[0]
+    y = np.zeros((M, N), dtype=np.float64)
+    b = _f32(bias) if bias is not None else None
+    lib().orc_qlinear_nf4(_p(x), C.c_uint64(M), C.c_uint64(K), _p(qp), _p(s_eff), C.c_uint64(N),
+                          C.c_uint32(block), _p(b) if b is not None else None, _p(y))
+    return y
+
+
 def repack_kmajor(qweight, qzeros, scales_f16, zero_add, group=128):
     """K-major checkpoint layout -> (nibbles [N,K/2], zero-points [N,G], bf16 scales [N,G])."""
     qweight = np.ascontiguousarray(qweight, dtype=np.uint32)
@@ -278,17 +317,20 @@ class Model:
     scales: np.ndarray       # flat fp32 arena of bf16-valued scales
     segments: list = field(default_factory=list)
     group: int = 128
-    quant: int = 0           # 0: int4 + group scales; 1: codebook + per-channel scales; 2: int4 + zero-points
+    quant: int = 0           # 0: int4 + group scales; 1: codebook + per-channel scales; 2: int4 + zero-points;
+                             # 3: NormalFloat-4 blocks of 64
 
     @property
     def n_rows(self):
         return sum(s.rows for s in self.segments)
 
 
-def build_model(shape: dict, table, group=128, asym=False) -> Model:
+def build_model(shape: dict, table, group=128, asym=False, nf4=False) -> Model:
     """Quantize the 'w' entries of a (name, kind, array) table with RTN
     (Eq. 3 with the absmax scale; asym: with zero-points, each packed weight then followed by
-    its zero-point tensor) and lay the scales out in arena order."""
+    its zero-point tensor; nf4: NormalFloat-4 blocks of 64) and lay the scales out in arena order."""
+    if nf4:
+        group = 64
     tensors, names, segs, scales = [], [], [], []
     off = 0
     row = 0
@@ -298,6 +340,10 @@ def build_model(shape: dict, table, group=128, asym=False) -> Model:
                 qp, zp, s = rtn_quantize_asym(arr, group)
                 tensors += [qp, zp]
                 names += [name, name + ".zp"]
+            elif nf4:
+                qp, s = nf4_quantize(arr, group)
+                tensors.append(qp)
+                names.append(name)
             else:
                 qp, s = rtn_quantize(arr, group)
                 tensors.append(qp)
@@ -310,7 +356,7 @@ def build_model(shape: dict, table, group=128, asym=False) -> Model:
             tensors.append(_f32(arr))
             names.append(name)
     return Model(shape, tensors, names, np.concatenate(scales).astype(np.float32), segs, group,
-                 2 if asym else 0)
+                 3 if nf4 else (2 if asym else 0))
 
 
 def fp16_rne(x):

@@ -345,6 +345,83 @@ void orc_qlinear_zp(const double* x, uint64_t M, uint64_t K, const uint8_t* qp, 
     }
   }
 }
+// ---- 4-bit NormalFloat blocks (the quantizer of the text-to-image experiment, Sec. 4.3): a
+// block of `block` (64) consecutive input features of a row shares one scale, the block's
+// absmax; a weight is stored as the index u of the nearest of 16 fixed levels in [-1, 1]:
+// W[n,k] = s[n, k/block] * level[u[n,k]], Eq. 4-5 with wbar = level[u].  The levels are the
+// published NormalFloat-4 code book (Dettmers et al. 2023, App. E): the normal quantiles
+// Phi^-1 at 8 evenly spaced probabilities from delta = 0.9677083 down to (not including) 1/2
+// on the positive side, 7 on the negative side, and 0, divided by the largest.
+const float NF4_LEVEL[16] = {
+    -1.0f, -0.6961928009986877f, -0.5250730514526367f, -0.39491748809814453f,
+    -0.28444138169288635f, -0.18477343022823334f, -0.09105003625154495f, 0.0f,
+    0.07958029955625534f, 0.16093020141124725f, 0.24611230194568634f, 0.33791524171829224f,
+    0.44070982933044434f, 0.5626170039176941f, 0.7229568362236023f, 1.0f};
+void orc_nf4_levels(float* out) { for (int i = 0; i < 16; ++i) out[i] = NF4_LEVEL[i]; }
+
+// s = bf16(absmax of the block) (the scale's storage type), u = index of the level nearest
+// to w / s (the lower index on a tie); an all-zero block gives s = 0, u = 7 (level 0).
+// Stored like the int4 format: two indices per byte, even k in the low nibble.
+void orc_nf4_quantize(const float* w, uint64_t N, uint64_t K, uint32_t block, uint8_t* qp, float* s) {
+  const uint64_t G = K / block;
+  for (uint64_t n = 0; n < N; ++n)
+    for (uint64_t g = 0; g < G; ++g) {
+      float amax = 0.0f;
+      for (uint32_t j = 0; j < block; ++j) amax = std::max(amax, std::fabs(w[n * K + g * block + j]));
+      const float sc = bf16_rne(amax);
+      s[n * G + g] = sc;
+      for (uint32_t j = 0; j < block; ++j) {
+        const uint64_t k = g * block + j;
+        int u = 7;
+        if (sc > 0.0f) {
+          const double r = (double)w[n * K + k] / (double)sc;
+          double best = 1e300;
+          for (int i = 0; i < 16; ++i) {
+            const double e = std::fabs(r - (double)NF4_LEVEL[i]);
+            if (e < best) { best = e; u = i; }
+          }
+        }
+        uint8_t& byte = qp[n * (K / 2) + k / 2];
+        byte = (k & 1) ? (uint8_t)((byte & 0x0f) | (u << 4)) : (uint8_t)((byte & 0xf0) | u);
+      }
+    }
+}
+inline int nf4_index(const uint8_t* qp, uint64_t K, uint64_t n, uint64_t k) {
+  const uint8_t b = qp[n * (K / 2) + k / 2];
+  return (k & 1) ? (b >> 4) : (b & 0x0f);
+}
+// W_eff[n,k] = (s + sigma*eps*z)[n, k/block] * level[u[n,k]]: one fp32 fma, one fp32 product,
+// optionally viewed in bf16.
+void orc_dequant_nf4(const uint8_t* qp, const float* s, uint64_t N, uint64_t K, uint32_t block,
+                     uint64_t seed, uint32_t row_base, float eps_signed, int to_bf16, float* w_eff) {
+  const uint64_t G = K / block;
+  for (uint64_t n = 0; n < N; ++n)
+    for (uint64_t k = 0; k < K; ++k) {
+      const uint64_t g = k / block;
+      const float z = scale_normal(seed, 0u, (uint32_t)(row_base + n), (uint32_t)g);
+      const float se = std::fmaf(eps_signed, z, s[n * G + g]);
+      const float v = se * NF4_LEVEL[nf4_index(qp, K, n, k)];
+      w_eff[n * K + k] = to_bf16 ? bf16_rne(v) : v;
+    }
+}
+// Y[m,n] = sum_k X[m,k] * s_eff[n,k/block] * level[u[n,k]] (+ bias[n]).
+void orc_qlinear_nf4(const double* x, uint64_t M, uint64_t K, const uint8_t* qp, const double* s_eff,
+                     uint64_t N, uint32_t block, const float* bias, double* y) {
+  const uint64_t G = K / block;
+#pragma omp parallel for schedule(static)
+  for (int64_t n = 0; n < (int64_t)N; ++n) {
+    std::vector<double> wrow(K);
+    for (uint64_t k = 0; k < K; ++k)
+      wrow[k] = s_eff[n * G + k / block] * (double)NF4_LEVEL[nf4_index(qp, K, n, k)];
+    for (uint64_t m = 0; m < M; ++m) {
+      double acc = 0.0;
+      const double* xr = x + m * K;
+      for (uint64_t k = 0; k < K; ++k) acc += xr[k] * wrow[k];
+      y[m * N + n] = acc + (bias ? (double)bias[n] : 0.0);
+    }
+  }
+}
+
 // Repacking from the K-major checkpoint layout: qweight int32 [K/8, N], word (kk, n) holding
 // the nibbles of k = 8 kk .. 8 kk + 7 of output n, lowest nibble first; qzeros int32 [G, N/8],
 // word (g, nn) holding the zero-points of n = 8 nn .. 8 nn + 7; scales fp16 values [G, N].
@@ -581,6 +658,7 @@ struct orc_config {
   double norm_eps, rope_theta;
   uint32_t quant;       // 0 = int4 + per-group scales, 1 = codebook + per-channel scales (Llama only),
                         // 2 = int4 with zero-points: every packed weight is followed by u8 [N, K/group]
+                        // 3 = NormalFloat-4 indices + per-block scales (group = block = 64)
 };
 
 // Tensor table, in this order (all fp32 arrays holding bf16 values unless noted):
@@ -629,7 +707,8 @@ double orc_forward_loss(const orc_config* c, const void* const* T, const double*
   };
   auto qlin = [&](const double* x, uint64_t K, const uint8_t* w, const uint8_t* z, const double* sc,
                   uint64_t N, const float* bias, double* y) {
-    if (z) orc_qlinear_zp(x, M, K, w, sc, z, N, c->group, bias, y);
+    if (c->quant == 3) orc_qlinear_nf4(x, M, K, w, sc, N, c->group, bias, y);
+    else if (z) orc_qlinear_zp(x, M, K, w, sc, z, N, c->group, bias, y);
     else orc_qlinear(x, M, K, w, sc, N, c->group, bias, y);
   };
   for (uint32_t l = 0; l < c->n_layers; ++l) {

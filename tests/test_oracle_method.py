@@ -134,10 +134,12 @@ def _torch_forward(model, s_eff, tok, oracle):
         s = seg[name]
         K = T[name].shape[1] * 2
         qi = oracle.unpack_int4(T[name], K).astype(np.float64)
+        if model.quant == 3:        # NormalFloat-4: the stored nibble indexes the level table
+            qi = oracle.nf4_levels().astype(np.float64)[(qi + 8).astype(np.int64)]
         if name + ".zp" in T:       # asymmetric groups: integer is (stored nibble - zero-point)
             qi = qi + 8.0 - np.repeat(T[name + ".zp"].astype(np.float64), 128, axis=1)
         se = s_eff[s.offset:s.offset + s.rows * s.G].reshape(s.rows, s.G)
-        return _t(np.repeat(se, 128, axis=1) * qi)
+        return _t(np.repeat(se, model.group, axis=1) * qi)
 
     tk = torch.from_numpy(tok.astype(np.int64))
     h = _t(T["tok_emb"])[tk]                                   # [B,S,d]
@@ -661,3 +663,63 @@ def test_joint_scalar_is_the_directional_derivative_over_both_parts(oracle):
     assert r["status"] == 0 and math.isclose(r["d"], d, rel_tol=1e-4)
     assert np.array_equal(r["scales"], oracle.update_scales(m, seed, 1e-5, r["d_clipped"]))
     assert np.array_equal(r["master"], oracle.dense_update(m32, 0, seed, 1e-4, r["d_clipped"]))
+
+
+# ------------------------------------- NormalFloat-4 blocks (the quantizer of Sec. 4.3) ----
+def test_nf4_levels_are_the_normal_quantile_code_book(oracle):
+    from scipy.stats import norm
+    delta = 0.5 * ((1 - 1 / 30) + (1 - 1 / 32))
+    pos = norm.ppf(np.linspace(delta, 0.5, 9)[:-1])
+    neg = -norm.ppf(np.linspace(delta, 0.5, 8)[:-1])
+    want = np.sort(np.concatenate([pos, [0.0], neg]))
+    want = want / want.max()
+    got = oracle.nf4_levels().astype(np.float64)
+    assert got.shape == (16,) and got[0] == -1 and got[15] == 1 and got[7] == 0
+    assert np.all(np.diff(got) > 0)
+    assert np.abs(got - want).max() < 2e-7
+
+
+def test_nf4_quantizer_dequant_and_linear(oracle):
+    rng = np.random.default_rng(41)
+    N, K = 9, 384
+    w = (rng.standard_normal((N, K)) * 0.03).astype(np.float32)
+    w[3, 64:128] = 0.0
+    qp, s = oracle.nf4_quantize(w)
+    assert s.shape == (N, K // 64) and (s.view(np.uint32) & 0xFFFF == 0).all()
+    u = oracle.unpack_int4(qp, K).astype(np.int64) + 8                  # same nibble layout as int4
+    L = oracle.nf4_levels().astype(np.float64)
+    amax = np.abs(w.reshape(N, -1, 64)).max(-1)
+    assert np.allclose(s, amax, rtol=2.0 ** -8) and s[3, 1] == 0 and (u[3, 64:128] == 7).all()
+    nz = np.repeat(s, 64, axis=1) > 0
+    r = np.where(nz, w.astype(np.float64) / np.where(nz, np.repeat(s, 64, axis=1), 1), 0.0)
+    assert np.array_equal(u[nz], np.abs(r[..., None] - L).argmin(-1)[nz])      # nearest level, brute force
+    # the block's largest weight sits on an end level (its ratio to the bf16 scale is within 2^-8 of +-1)
+    assert (u[(np.abs(w) == np.repeat(amax, 64, axis=1)) & nz] % 15 == 0).all()
+    # dequantization: s * level, and with a perturbation (s + eps z) * level, one fp32 product
+    w0 = oracle.dequant_nf4(qp, s, 0, 0, 0.0)
+    assert np.array_equal(w0, (np.repeat(s, 64, axis=1) * L.astype(np.float32)[u]).astype(np.float32))
+    z = oracle.scale_normals(13, 5, N, K // 64)
+    se = (s.astype(np.float64) + float(np.float32(1e-3)) * z.astype(np.float64)).astype(np.float32)
+    w1 = oracle.dequant_nf4(qp, s, 13, 5, 1e-3)
+    assert np.array_equal(w1, np.repeat(se, 64, axis=1) * L.astype(np.float32)[u])
+    assert np.array_equal(oracle.dequant_nf4(qp, s, 13, 5, 1e-3, to_bf16=True),
+                          torch.from_numpy(w1).to(torch.bfloat16).float().numpy())
+    # the reconstruction error is at most half the widest gap between levels, times the scale
+    assert (np.abs(w0 - w) <= 0.5 * np.diff(L).max() * np.repeat(s, 64, axis=1) * (1 + 2.0 ** -7) + 1e-12).all()
+    # linear = matmul with the dequantized weight
+    x = rng.standard_normal((5, K))
+    se64 = oracle.effective_scales(s, 5, 13, 1e-3)
+    y = oracle.qlinear_nf4(x, qp, se64)
+    assert np.allclose(y, x @ (np.repeat(se64, 64, axis=1) * L[u]).T, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("arch", ["llama", "opt"])
+def test_nf4_forward_matches_torch_composition(oracle, arch):
+    sh = dict(MINI, arch=arch)
+    m = oracle.build_model(sh, synth.tensor_table(sh, 3), nf4=True)
+    assert m.quant == 3 and m.group == 64 and m.scales.size == 2 * oracle.build_model(sh, synth.tensor_table(sh, 3)).scales.size
+    tok = synth.tokens(sh, 4)
+    se = oracle.perturbed_scales(m, seed=5, eps_signed=1e-3)
+    got = oracle.forward_loss(m, se, tok, act_bf16=False)
+    assert math.isclose(got, _torch_forward(m, se, tok, oracle), rel_tol=1e-10)
+    assert abs(got - math.log(sh["vocab"])) < 0.2
