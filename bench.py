@@ -96,8 +96,9 @@ def mfma_ceiling(torch, qb, iters=60000):
 
 def probe(torch, qb):
     """Launches for rocprofv3 counter runs: a plain copy of known size (256 MiB read +
-    256 MiB written) that calibrates the HBM counters, the perturbed GEMM at the Llama-2-7B
-    qkv shape (M 8192, N 12288, K 4096), the scale update over 50,593,792 scales, and the
+    256 MiB written) that calibrates the HBM counters, the perturbed linear at the Llama-2-7B
+    qkv shape (M 8192, N 12288, K 4096) three ways (the fused dequantizing GEMM; the expansion
+    of the perturbed weights to bf16; the plain bf16 GEMM on them), the scale update over 50,593,792 scales, and the
     matrix-pipe rate probe with zero and with random operands (engine-clock comparison)."""
     dev = "cuda:0"
     g = torch.Generator(device=dev)
@@ -110,11 +111,17 @@ def probe(torch, qb):
     s = (torch.rand(N, K // 128, generator=g, device=dev) * 0.015 + 0.005).to(torch.bfloat16)
     y = torch.empty(M, N, dtype=torch.bfloat16, device=dev)
     arena = (torch.rand(1581056, 32, generator=g, device=dev) * 0.01 + 0.003).to(torch.bfloat16)
+    se = torch.empty(N, K // 128, dtype=torch.float32, device=dev)
+    wexp = torch.empty(N, K, dtype=torch.bfloat16, device=dev)
     torch.cuda.synchronize()
     for _ in range(3):
         dst.copy_(src)
         torch.cuda.synchronize()
         qb.qzo_dequant_gemm(x, q, s, 0, 7, 1e-3, 1, y)
+        torch.cuda.synchronize()
+        qb.qzo_int4_expand(q, s, None, 0, 7, 1e-3, 1, se, wexp)
+        torch.cuda.synchronize()
+        qb.qzo_debug_bf16_gemm(x, wexp, y, 1)
         torch.cuda.synchronize()
         qb.qzo_apply_update(arena, 0, 7, 1e-7, 10.0)
         torch.cuda.synchronize()
@@ -123,7 +130,7 @@ def probe(torch, qb):
         for _ in range(3):
             qb.qzo_debug_mfma_rate(20000, rnd, sink)
             torch.cuda.synchronize()
-    print(json.dumps({"probe": "copy 2x268435456 B, gemm 8192x12288x4096, update 50593792 scales, "
+    print(json.dumps({"probe": "copy 2x268435456 B, fused gemm / expansion / plain gemm 8192x12288x4096, update 50593792 scales, "
                                "mfma rate 20000 iters x 16 MFMAs per wavefront (zero, then random operands)"}))
 
 
@@ -133,9 +140,13 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="llama-2-7b")
-    ap.add_argument("--variant", default="int4", choices=["int4", "int4-zp", "codebook"],
+    ap.add_argument("--variant", default="int4", choices=["int4", "int4-zp", "nf4", "codebook"],
                     help="int4 group-128 scales (the metric's configuration), the same with per-group "
-                         "zero-points, or the codebook variant with per-channel scales (no cpu_baseline leg)")
+                         "zero-points, NormalFloat-4 blocks of 64, or the codebook variant with per-channel "
+                         "scales (no cpu_baseline leg)")
+    ap.add_argument("--fused", action="store_true",
+                    help="int4 variants: always the fused dequantizing GEMM (default: expand-then-multiply "
+                         "from 512 tokens per pass on)")
     ap.add_argument("--joint", action="store_true",
                     help="joint mode: the un-quantized parameters are perturbed and updated too (SPSA)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
@@ -169,14 +180,16 @@ def main():
     # the counters were read on this one
     main_cfg = (args.workload == "llama-2-7b" and args.variant == "int4" and not args.joint
                 and not args.batch and not args.seq)
-    few_tokens = B * S <= 64 and not codebook      # the int4 GEMM takes its weight-streaming path
+    few_tokens = B * S <= 64 and args.variant in ("int4", "int4-zp")   # the weight-streaming path
     if codebook:
         dm = DeviceModel.synthetic_codebook(shape, seed=1234, device="cuda:0")
     else:
-        dm = DeviceModel.synthetic(shape, seed=1234, device="cuda:0", asym=args.variant == "int4-zp")
+        dm = DeviceModel.synthetic(shape, seed=1234, device="cuda:0", asym=args.variant == "int4-zp",
+                                   nf4=args.variant == "nf4")
     tok = torch.from_numpy(synth.tokens(shape, 5678)).cuda()
     eps, eta, clip = 1e-3, 1e-7, 100.0
     stream = torch.cuda.current_stream()
+    qb.qzo_set_int4_path(1 if args.fused else 0)
     if args.joint:
         dm.enable_joint()
         plain_step = dm.step_joint
@@ -205,6 +218,8 @@ def main():
     changed = float((dm.scales.view(torch.int16) != before.view(torch.int16)).float().mean().item())
     del before
 
+    # 512 tokens per pass or more: the linears are written out as perturbed bf16 matrices first
+    expanded = (B * S >= 512 and not (args.fused and not codebook)) or args.variant == "nf4"
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
     g = prof["w4a16_gemm"]
@@ -222,6 +237,7 @@ def main():
         "config": {"workload": f"{args.workload}-shaped decoder, "
                                f"{'16-bit codes per 8 weights + fp16 channel scales' if codebook else 'int4 g128 RTN'}"
                                f"{' with zero-points' if args.variant == 'int4-zp' else ''}"
+                               f"{' -> NormalFloat-4 blocks of 64 instead' if args.variant == 'nf4' else ''}"
                                f", full QZO step "
                                f"(2 perturbed forwards + DDC + scale update"
                                f"{'; un-quantized parameters perturbed and updated jointly' if args.joint else ''})",
@@ -230,13 +246,21 @@ def main():
         "forward_tokens_per_s": 2 * B * S * steps_per_s,
         "last_step": res,
         "scales_changed_frac": changed,
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<2,...> (codebook GEMM, perturbed channel scales)" if codebook
-                     else "gemm_kernel<0,...> (perturbed W4A16 GEMM)",
+        "roofline": {"bound": "mfma",
+                     "kernel": "gemm_kernel<1,false,4,1> (plain bf16 GEMM on the expanded perturbed weights)"
+                     if expanded
+                     else ("gemm_kernel<2,...> (codebook GEMM, perturbed channel scales)" if codebook
+                           else "gemm_kernel<0,false,4,2> (fused perturbed W4A16 GEMM)"),
                      "achieved": gemm_flops_s / 1e12, "peak": PEAK_BF16_MFMA / 1e12,
                      "unit": "TFLOP/s", "frac": gemm_flops_s / PEAK_BF16_MFMA,
-                     "traffic": measured_traffic("traffic_bytes_per_launch_gemm_qkv") if main_cfg else None,
-                     "traffic_note": "HBM bytes of one qkv-shaped launch (8192x12288x4096), FETCH_SIZE + "
-                                     "WRITE_SIZE scaled by a plain copy; algorithmic 2.94e8",
+                     "traffic": measured_traffic("traffic_bytes_per_launch_gemm_qkv" if expanded else
+                                                 "traffic_bytes_per_launch_gemm_qkv_fused")
+                     if args.workload == "llama-2-7b" and args.variant == "int4" and not args.batch and not args.seq
+                     else None,
+                     "traffic_note": "bytes of one qkv-shaped launch (8192x12288x4096), FETCH_SIZE + WRITE_SIZE "
+                                     "scaled by a plain copy; algorithmic " + ("3.69e8" if expanded else "2.94e8"),
+                     # the whole W4A16 linear: the GEMM plus, when expanded, the pass that writes the weights out
+                     "w4a16_linear_effective_TFLOPs": g["work"] / ((g["total_ms"] + prof["expand"]["total_ms"]) * 1e-3) / 1e12,
                      "launches": g["launches"], "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
                      "flops_per_launch_avg": g["work"] / max(g["launches"], 1),
                      "mfma_only_measured_TFLOPs": mfma_ceiling(torch, qb)},

@@ -59,12 +59,14 @@ typedef struct {
   uint32_t arch;        /* 0: Llama family (RMSNorm, RoPE, SwiGLU, no bias)
                            1: OPT family (LayerNorm, learned positions, ReLU, biases) */
   uint32_t n_layers, d_model, n_heads, d_ffn, vocab, max_seq;
-  uint32_t group_size;  /* 128 */
+  uint32_t group_size;  /* 128; 64 with quant = 3 */
   uint32_t quant;       /* 0: int4 + per-group bf16 scales
                            1: codebook (Llama only): one uint16 code per 8 weights into a per-linear
                               fp16 [65536,8] codebook, fp16 per-output-channel scales
                            2: int4 + per-group bf16 scales + per-group zero-points,
-                              W = s * (u - zp) (Sec. 4.1, quantizers that keep a zero-point) */
+                              W = s * (u - zp) (Sec. 4.1, quantizers that keep a zero-point)
+                           3: 4-bit NormalFloat indices + one bf16 scale per block of 64
+                              (group_size = 64), W = s * level[u] (Sec. 4.3's quantizer) */
   float norm_eps;       /* 1e-5 */
   float rope_theta;     /* 10000 (Llama only) */
 } qzo_model_config;
@@ -98,6 +100,10 @@ typedef struct {
  *   quant = 2 (either family): the quant = 0 table with every int4 weight [N,K/2] directly
  *          followed by its zero-points uint8 [N,K/128], values 0..15; scales and the arena as
  *          for quant = 0.
+ *   quant = 3 (either family): the quant = 0 table with NormalFloat-4 indices in place of the int4
+ *          nibbles (same [N,K/2] layout, even k in the low nibble); the arena holds [N, K/64] scales
+ *          per linear.  Every linear is first written out as a perturbed bf16 matrix in the workspace
+ *          and multiplied by a plain bf16 GEMM.
  * `scale_arena_dev` holds every quantized linear's bf16 scales back to back in
  * the same order ([N, K/128] each); it is the only model memory the library
  * writes.  Only the decoder-block linears are quantized and trained (their
@@ -272,6 +278,46 @@ qzo_status qzo_debug_dequant_zp(const void* q_dev, const void* s_dev, const void
                                 uint32_t row_base, uint32_t N, uint32_t K, uint32_t group,
                                 uint64_t seed, float eps, int sign, void* w_eff_dev, void* stream);
 
+/*
+ * NormalFloat-4 blocks (the quantizer of the text-to-image experiment, Sec. 4.3): a block of 64
+ * consecutive input features of a row shares one scale (its absmax) and each weight is the index u
+ * of one of the 16 NormalFloat-4 levels in [-1, 1]:  W[n,k] = s[n, k/64] * level[u[n,k]], and a
+ * perturbed pass uses (s + sign*eps*z)[n, k/64] (Eq. 4-5 with wbar = level[u]).
+ *   q_dev: uint8 [N, K/2], index of even k in the low nibble; s_dev: bf16 [N, K/64];
+ *   z as for qzo_dequant_gemm: counter (row_base + n, g/8), stream 0.
+ * qzo_nf4_expand writes the perturbed scales (se_dev, fp32 [N, K/64], one fma each) and the perturbed
+ * matrix (w_dev, bf16 [N,K], the fp32 product se * level rounded to nearest even).
+ * qzo_nf4_gemm does the same into scratch_dev (qzo_nf4_scratch_bytes(N, K) bytes, 256-byte aligned,
+ * contents undefined afterwards) and then Y = X W^T with the plain bf16 GEMM: x_dev bf16 [M,K],
+ * y_dev bf16 [M,N].  The table lookup is done once per weight and pass, not once per token tile.
+ * block must be 64, K a positive multiple of 128, N a multiple of 8, pointers 16-byte aligned.
+ */
+qzo_status qzo_nf4_expand(const void* q_dev, const void* s_dev, uint32_t row_base, uint32_t N,
+                          uint32_t K, uint32_t block, uint64_t seed, float eps, int sign,
+                          float* se_dev, void* w_dev, void* stream);
+qzo_status qzo_nf4_scratch_bytes(uint32_t N, uint32_t K, uint64_t* out);
+qzo_status qzo_nf4_gemm(const void* x_dev, const void* q_dev, const void* s_dev, uint32_t row_base,
+                        uint32_t M, uint32_t N, uint32_t K, uint32_t block, uint64_t seed, float eps,
+                        int sign, void* y_dev, void* scratch_dev, uint64_t scratch_bytes,
+                        void* stream);
+
+/*
+ * First stage of expand-then-multiply for int4 groups (Eq. 4-5): the perturbed scales
+ * se = s + sign*eps*z (se_dev, fp32 [N, K/128], one fma each) and the perturbed weight matrix
+ * (w_dev, bf16 [N,K]) = se[n, k/128] * (u[n,k] - zp[n, k/128]) rounded once to bf16; zp_dev may be
+ * null (every zero-point 8: the symmetric format).  Operand layouts as for qzo_dequant_gemm /
+ * qzo_dequant_gemm_zp; the result has the same bits as the fused kernel's weight tile.
+ */
+qzo_status qzo_int4_expand(const void* q_dev, const void* s_dev, const void* zp_dev, uint32_t row_base,
+                           uint32_t N, uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                           float* se_dev, void* w_dev, void* stream);
+
+/* How the model's int4 linears (quant 0 and 2) run when a pass has at least 512 tokens:
+ * mode 0 (default): the perturbed weights of a linear are first written out as a bf16 matrix in the
+ * workspace (same bits as the fused kernel's weight tile), then multiplied by the plain bf16 GEMM;
+ * mode 1: always the fused dequantizing GEMM.  Process-wide, not thread-safe; for comparisons. */
+qzo_status qzo_set_int4_path(int mode);
+
 /* Inspection: the second stage of the expand-then-multiply paths on its own, Y = X W^T with a plain
  * bf16 weight matrix w_dev [N,K] (x_dev bf16 [M,K], y_dev bf16 [M,N], fp32 accumulation, no epilogue).
  * pipe: 0 or 1, the two instruction orders of the 512-thread kernel (1 is the one the model uses);
@@ -306,7 +352,8 @@ qzo_status qzo_debug_forward(qzo_model* m, const int32_t* tokens_dev, uint32_t b
  * the summed elapsed milliseconds, the number of launches and the summed
  * algorithmic work (flops for 0..2, bytes for 3).  Classes: 0 = perturbed
  * W4A16 GEMM, 1 = lm_head GEMM + cross-entropy partials, 2 = attention,
- * 3 = scale update, 4 = embedding.  Host pointers.  Not thread-safe.
+ * 3 = scale update, 4 = embedding and the joint mode's kernels, 5 = weight expansion (bytes:
+ * packed weights in + bf16 out).  Host pointers.  Not thread-safe.
  */
 qzo_status qzo_profile_begin(uint32_t max_records);
 qzo_status qzo_profile_collect(uint32_t kind, double* total_ms, uint64_t* launches, double* work);

@@ -24,6 +24,7 @@ EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
     "qzo_model_dense_count", "qzo_model_enable_joint", "qzo_step_joint",
+    "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm", "qzo_set_int4_path", "qzo_int4_expand",
     "qzo_apply_update", "qzo_dequant_gemm_zp", "qzo_repack_kmajor", "qzo_debug_dequant_zp", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
     "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_debug_bf16_gemm", "qzo_profile_begin", "qzo_profile_collect",
     "qzo_last_error",
@@ -223,6 +224,39 @@ def qzo_debug_dequant(q, s, row_base, seed, eps, sign, w_eff, group=128, stream=
                                    C.c_float(eps), C.c_int(sign), _ptr(w_eff), _stream(stream)))
 
 
+def qzo_int4_expand(q, s, zp, row_base, seed, eps, sign, se_out, w_out, stream=None):
+    N, K = q.shape[0], q.shape[1] * 2
+    _check(lib().qzo_int4_expand(_ptr(q), _ptr(s), _ptr(zp), C.c_uint32(row_base), C.c_uint32(N), C.c_uint32(K),
+                                 C.c_uint32(128), C.c_uint64(seed), C.c_float(eps), C.c_int(sign),
+                                 _ptr(se_out), _ptr(w_out), _stream(stream)))
+
+
+def qzo_nf4_expand(q, s, row_base, seed, eps, sign, se_out, w_out, stream=None):
+    N, K = q.shape[0], q.shape[1] * 2
+    _check(lib().qzo_nf4_expand(_ptr(q), _ptr(s), C.c_uint32(row_base), C.c_uint32(N), C.c_uint32(K),
+                                C.c_uint32(64), C.c_uint64(seed), C.c_float(eps), C.c_int(sign),
+                                _ptr(se_out), _ptr(w_out), _stream(stream)))
+
+
+def qzo_nf4_scratch_bytes(N, K) -> int:
+    out = C.c_uint64(0)
+    _check(lib().qzo_nf4_scratch_bytes(C.c_uint32(N), C.c_uint32(K), C.byref(out)))
+    return out.value
+
+
+def qzo_nf4_gemm(x, q, s, row_base, seed, eps, sign, y, scratch, stream=None):
+    M, K = x.shape
+    N = q.shape[0]
+    _check(lib().qzo_nf4_gemm(_ptr(x), _ptr(q), _ptr(s), C.c_uint32(row_base), C.c_uint32(M), C.c_uint32(N),
+                              C.c_uint32(K), C.c_uint32(64), C.c_uint64(seed), C.c_float(eps), C.c_int(sign),
+                              _ptr(y), _ptr(scratch), C.c_uint64(scratch.numel() * scratch.element_size()),
+                              _stream(stream)))
+
+
+def qzo_set_int4_path(mode: int):
+    _check(lib().qzo_set_int4_path(C.c_int(mode)))
+
+
 def qzo_debug_bf16_gemm(x, w, y, pipe=1, stream=None):
     M, K = x.shape
     N = w.shape[0]
@@ -245,7 +279,7 @@ def qzo_debug_forward(model, tokens, seed, eps, sign, workspace, loss_out, hidde
                                    _ptr(loss_out), _ptr(hidden_out), _stream(stream)))
 
 
-PROFILE_KINDS = {"w4a16_gemm": 0, "lmhead_ce": 1, "attention": 2, "scale_update": 3, "embed": 4}
+PROFILE_KINDS = {"w4a16_gemm": 0, "lmhead_ce": 1, "attention": 2, "scale_update": 3, "embed": 4, "expand": 5}
 
 
 def qzo_debug_mfma_rate(iters: int, random_operands: bool, sink, stream=None) -> int:

@@ -43,6 +43,7 @@ struct Workspace {
   unsigned char *h, *a, *qkv, *att, *ff, *act;
   float *ce_part, *tgt, *rowloss, *losses, *skinny;
   unsigned char* wexp;      // one linear's expanded bf16 weights (expand-then-multiply paths)
+  float* se;                // NormalFloat-4: that linear's perturbed block scales
   uint64_t total;
 };
 
@@ -73,11 +74,13 @@ qzo_status check_cfg(const qzo_model_config* c) {
   if (c->struct_size != sizeof(qzo_model_config))
     return fail(QZO_ERR_ARG, "config.struct_size does not match this library");
   if (c->arch > 1) return fail(QZO_ERR_ARG, "config.arch must be 0 (Llama) or 1 (OPT)");
-  if (c->quant > 2)
-    return fail(QZO_ERR_UNSUPPORTED, "quant must be 0 (int4 group scales), 1 (codebook) or 2 (int4 with zero-points)");
+  if (c->quant > 3)
+    return fail(QZO_ERR_UNSUPPORTED,
+                "quant must be 0 (int4 group scales), 1 (codebook), 2 (int4 with zero-points) or 3 (NormalFloat-4)");
   if (c->quant == 1 && c->arch != 0)
     return fail(QZO_ERR_UNSUPPORTED, "the codebook variant is built for the Llama family only");
-  if (c->group_size != 128) return fail(QZO_ERR_SHAPE, "group_size must be 128");
+  if (c->quant == 3 ? c->group_size != 64 : c->group_size != 128)
+    return fail(QZO_ERR_SHAPE, "group_size must be 128 (64 for the NormalFloat-4 format)");
   if (!c->n_layers || !c->d_model || !c->n_heads || !c->d_ffn || !c->vocab || !c->max_seq)
     return fail(QZO_ERR_SHAPE, "zero dimension in config");
   if (c->d_model % 128 || c->d_ffn % 128)
@@ -96,17 +99,17 @@ void layer_linears(const qzo_model_config& c, Linear lin[4]) {
   uint32_t row = 0;
   for (int i = 0; i < 4; ++i) {
     lin[i] = {N[i], K[i], off, row};
-    off += (uint64_t)N[i] * (K[i] / 128);
+    off += (uint64_t)N[i] * (K[i] / c.group_size);
     row += N[i];
   }
 }
 
 // Merge a layer's consecutive linears with equal groups-per-row into update segments.
-qzo_status build_plan(const Linear* lin, int n_lin, uint32_t n_layers, UpdPlan& p) {
+qzo_status build_plan(const Linear* lin, int n_lin, uint32_t n_layers, UpdPlan& p, uint32_t group = 128) {
   std::memset(&p, 0, sizeof(p));
   uint32_t wg = 0;
   for (int i = 0; i < n_lin; ++i) {
-    const uint32_t G = lin[i].K / 128;
+    const uint32_t G = lin[i].K / group;
     if (p.n_seg && p.seg[p.n_seg - 1].G == G) {
       p.seg[p.n_seg - 1].rows += lin[i].N;
     } else {
@@ -167,7 +170,8 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   // With very few tokens qzo_step stacks its two perturbed passes into one forward
   // over 2 * batch sequences (the int4 weights are then read once per step).
   const uint64_t M1 = (uint64_t)batch * seq;
-  const bool stack = M1 <= SKINNY_MAX_M_DUAL && c.quant != 1 && !m->dense_master;
+  const bool int4 = c.quant == 0 || c.quant == 2;
+  const bool stack = M1 <= SKINNY_MAX_M_DUAL && int4 && !m->dense_master;
   const uint64_t M = stack ? 2 * M1 : M1, d = c.d_model, F = c.d_ffn;
   const uint64_t n_slices = ((c.vocab + 255) / 256) * 4;
   Workspace w;
@@ -189,17 +193,22 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   w.losses = (float*)take(256);
   // few-token path of the int4 GEMM: fp32 partial sums of the K slices of the largest linear
   uint64_t sk = 0;
-  if (M1 <= SKINNY_MAX_M && c.quant != 1)
+  if (M1 <= SKINNY_MAX_M && int4)
     for (int i = 0; i < 4; ++i)
       sk = std::max<uint64_t>(sk, skinny_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.skinny = (float*)take(sk * 4);
   if (sk == 0) w.skinny = nullptr;
   // codebook variant with many tokens: the largest linear written out as bf16
-  uint64_t ex = 0;
-  if (M1 >= EXPAND_MIN_M && c.quant == 1)
+  // and the NormalFloat-4 format at any token count (with its perturbed block scales, fp32)
+  uint64_t ex = 0, sx = 0;
+  if (M1 >= EXPAND_MIN_M || c.quant == 3)
     for (int i = 0; i < 4; ++i) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
+  if (ex && c.quant != 1)
+    for (int i = 0; i < 4; ++i)
+      sx = std::max<uint64_t>(sx, (uint64_t)m->lin[i].N * (m->lin[i].K / c.group_size) * 4);
   w.wexp = take(ex);
   if (ex == 0) w.wexp = nullptr;
+  w.se = (float*)take(sx);
   w.total = off;
   return w;
 }
@@ -240,7 +249,9 @@ struct ProfScope {
     if (r) (void)hipEventRecord(r->b, st);
   }
 };
-enum { PK_W4GEMM = 0, PK_LMHEAD = 1, PK_ATTN = 2, PK_UPDATE = 3, PK_OTHER = 4, PK_COUNT = 5 };
+enum { PK_W4GEMM = 0, PK_LMHEAD = 1, PK_ATTN = 2, PK_UPDATE = 3, PK_OTHER = 4, PK_EXPAND = 5, PK_COUNT = 6 };
+// int4 linears with at least EXPAND_MIN_M tokens: 0 = expand-then-multiply, 1 = always the fused kernel
+int g_int4_path = 0;
 
 // The decoder forward with every quantized linear perturbed by sign*eps*z.
 // n_pass = 2 (few tokens, int4 only): both passes of a step stacked, rows [0,M1) perturbed by
@@ -292,6 +303,30 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
       g.skinny_ws = w.skinny;
+      if (c.quant == 3) {
+        // NormalFloat-4: table lookup and scaling once per weight, then a plain bf16 GEMM
+        {
+          ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
+          hipError_t e = launch_expand_nf4(g.w, g.s, g.N, g.K, g.row_base, seed_lo, seed_hi, eps_signed,
+                                           (epi & EPI_SWIGLU) != 0, w.se, w.wexp, st);
+          if (e != hipSuccess) return e;
+        }
+        g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr;
+        ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+        return launch_bf16_gemm(g, 1, st);
+      }
+      if (w.wexp && g_int4_path != 1 && n_pass == 1) {
+        // many tokens: write the perturbed matrix out once, then a plain bf16 GEMM
+        {
+          ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
+          hipError_t e = launch_expand_int4(g.w, g.s, g.zp, g.N, g.K, g.row_base, seed_lo, seed_hi,
+                                            eps_signed, (epi & EPI_SWIGLU) != 0, w.se, w.wexp, st);
+          if (e != hipSuccess) return e;
+        }
+        g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr;
+        ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+        return launch_bf16_gemm(g, 1, st);
+      }
       ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
       return launch_w4a16_gemm(g, st);
     };
@@ -307,7 +342,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       if (w.wexp) {
         // many tokens: reconstruct the perturbed matrix once, then a plain bf16 GEMM
         {
-          ProfScope pe(PK_OTHER, 0, st);
+          ProfScope pe(PK_EXPAND, 2.25 * (double)g.N * g.K, st);
           hipError_t e = launch_expand_codebook(codes, cb, g.s, g.N, g.K, g.row_base, seed_lo, seed_hi,
                                                 eps_signed, (epi & EPI_SWIGLU) != 0, w.wexp, st);
           if (e != hipSuccess) return e;
@@ -404,7 +439,7 @@ qzo_status qzo_model_scale_count(const qzo_model_config* cfg, uint64_t* out) {
   if (cfg->quant == 1)
     *out = (uint64_t)(lin[3].row_base + lin[3].N) * cfg->n_layers;     // one scale per output row
   else
-    *out = (lin[3].s_off + (uint64_t)lin[3].N * (lin[3].K / 128)) * cfg->n_layers;
+    *out = (lin[3].s_off + (uint64_t)lin[3].N * (lin[3].K / cfg->group_size)) * cfg->n_layers;
   return QZO_OK;
 }
 
@@ -446,12 +481,12 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
   m->arena = scale_arena_dev;
   m->n_scales = n_scales;
   layer_linears(*cfg, m->lin);
-  m->scales_per_layer = m->lin[3].s_off + (uint64_t)m->lin[3].N * (m->lin[3].K / 128);
+  m->scales_per_layer = m->lin[3].s_off + (uint64_t)m->lin[3].N * (m->lin[3].K / cfg->group_size);
   m->rows_per_layer = m->lin[3].row_base + m->lin[3].N;
   m->tensors_per_layer = per_layer;
   m->first_layer_tensor = head;
   m->rope_table = nullptr;
-  st = build_plan(m->lin, 4, cfg->n_layers, m->plan);
+  st = build_plan(m->lin, 4, cfg->n_layers, m->plan, cfg->group_size);
   if (st != QZO_OK) { delete m; return st; }
   if (llama) {
     const uint32_t dh = cfg->d_model / cfg->n_heads;
@@ -571,7 +606,7 @@ static qzo_status step_impl(qzo_model* m, const int32_t* tokens_dev, uint32_t ba
     return fail(QZO_ERR_ARG, "eps/eta not finite");
   hipStream_t s = (hipStream_t)stream;
   Workspace w = carve(m, batch, seq, workspace_dev);
-  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && m->cfg.quant != 1 && !m->dense_master) {
+  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && (m->cfg.quant == 0 || m->cfg.quant == 2) && !m->dense_master) {
     // few tokens: one forward over both passes, the weights are read once
     st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s, nullptr, 2, w.losses + 1);
     if (st != QZO_OK) return st;
@@ -765,6 +800,78 @@ qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const voi
   }
   QZO_HIP(launch_codebook_gemm(g, st));
   if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  return QZO_OK;
+}
+
+qzo_status qzo_int4_expand(const void* q_dev, const void* s_dev, const void* zp_dev, uint32_t row_base,
+                           uint32_t N, uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                           float* se_dev, void* w_dev, void* stream) {
+  if (!q_dev || !s_dev || !se_dev || !w_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(q_dev) || !aligned16(s_dev) || !aligned16(se_dev) || !aligned16(w_dev))
+    return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
+  if (group != 128 || K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
+  if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
+  if (!std::isfinite(eps)) return fail(QZO_ERR_ARG, "eps not finite");
+  QZO_HIP(launch_expand_int4(q_dev, s_dev, zp_dev, N, K, row_base, (uint32_t)seed, (uint32_t)(seed >> 32),
+                             sign > 0 ? eps : -eps, false, se_dev, w_dev, (hipStream_t)stream));
+  return QZO_OK;
+}
+
+static qzo_status nf4_check(const void* q_dev, const void* s_dev, uint32_t N, uint32_t K, uint32_t block,
+                            float eps, int sign) {
+  if (!q_dev || !s_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(q_dev) || !aligned16(s_dev)) return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
+  if (block != 64 || K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "block must be 64 and K a positive multiple of 128");
+  if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
+  if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
+  if (!std::isfinite(eps)) return fail(QZO_ERR_ARG, "eps not finite");
+  return QZO_OK;
+}
+
+qzo_status qzo_nf4_expand(const void* q_dev, const void* s_dev, uint32_t row_base, uint32_t N, uint32_t K,
+                          uint32_t block, uint64_t seed, float eps, int sign, float* se_dev, void* w_dev,
+                          void* stream) {
+  qzo_status st = nf4_check(q_dev, s_dev, N, K, block, eps, sign);
+  if (st != QZO_OK) return st;
+  if (!se_dev || !w_dev) return fail(QZO_ERR_ARG, "null output");
+  if (!aligned16(se_dev) || !aligned16(w_dev)) return fail(QZO_ERR_ALIGN, "output not 16-byte aligned");
+  QZO_HIP(launch_expand_nf4(q_dev, s_dev, N, K, row_base, (uint32_t)seed, (uint32_t)(seed >> 32),
+                            sign > 0 ? eps : -eps, false, se_dev, w_dev, (hipStream_t)stream));
+  return QZO_OK;
+}
+
+qzo_status qzo_nf4_scratch_bytes(uint32_t N, uint32_t K, uint64_t* out) {
+  if (!out) return fail(QZO_ERR_ARG, "out is null");
+  *out = up256((uint64_t)N * K * 2) + up256((uint64_t)N * (K / 64) * 4);
+  return QZO_OK;
+}
+
+qzo_status qzo_nf4_gemm(const void* x_dev, const void* q_dev, const void* s_dev, uint32_t row_base,
+                        uint32_t M, uint32_t N, uint32_t K, uint32_t block, uint64_t seed, float eps,
+                        int sign, void* y_dev, void* scratch_dev, uint64_t scratch_bytes, void* stream) {
+  qzo_status st = nf4_check(q_dev, s_dev, N, K, block, eps, sign);
+  if (st != QZO_OK) return st;
+  if (!x_dev || !y_dev || !scratch_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(x_dev) || !aligned16(y_dev) || ((uintptr_t)scratch_dev & 255u))
+    return fail(QZO_ERR_ALIGN, "x/y need 16-byte, scratch 256-byte alignment");
+  uint64_t need = 0;
+  qzo_nf4_scratch_bytes(N, K, &need);
+  if (scratch_bytes < need) return fail(QZO_ERR_WORKSPACE, "scratch too small: see qzo_nf4_scratch_bytes");
+  if (M == 0 || N == 0) return QZO_OK;
+  hipStream_t s = (hipStream_t)stream;
+  unsigned char* wexp = (unsigned char*)scratch_dev;
+  float* se = (float*)(wexp + up256((uint64_t)N * K * 2));
+  QZO_HIP(launch_expand_nf4(q_dev, s_dev, N, K, row_base, (uint32_t)seed, (uint32_t)(seed >> 32),
+                            sign > 0 ? eps : -eps, false, se, wexp, s));
+  GemmArgs g = {};
+  g.x = x_dev; g.w = wexp; g.y = y_dev; g.M = M; g.N = N; g.K = K;
+  QZO_HIP(launch_bf16_gemm(g, 1, s));
+  return QZO_OK;
+}
+
+qzo_status qzo_set_int4_path(int mode) {
+  if (mode != 0 && mode != 1) return fail(QZO_ERR_ARG, "mode must be 0 (expand-then-multiply) or 1 (fused)");
+  g_int4_path = mode;
   return QZO_OK;
 }
 

@@ -67,4 +67,104 @@ hipError_t launch_expand_codebook(const void* codes, const void* cb, const void*
   return hipGetLastError();
 }
 
+// ---- NormalFloat-4 blocks (Sec. 4.3's quantizer): W = (s + sigma*eps*z)[n, k/64] * level[u] ----
+// The 16 levels of the published NormalFloat-4 code book (normal quantiles scaled to [-1, 1]).
+__device__ const float NF4_LEVELS_DEV[16] = {
+    -1.0f, -0.6961928009986877f, -0.5250730514526367f, -0.39491748809814453f,
+    -0.28444138169288635f, -0.18477343022823334f, -0.09105003625154495f, 0.0f,
+    0.07958029955625534f, 0.16093020141124725f, 0.24611230194568634f, 0.33791524171829224f,
+    0.44070982933044434f, 0.5626170039176941f, 0.7229568362236023f, 1.0f};
+
+// Perturbed block scales of one linear as fp32 [N, G]: s + (sigma*eps) z, one fma each.  A thread
+// owns the eight scales of one Philox counter (row, 8 gb .. 8 gb + 7), as the update does.
+__global__ __launch_bounds__(256) void perturbed_scales_kernel(const bf16_t* __restrict__ s, uint32_t N,
+                                                               uint32_t G, uint32_t row_base,
+                                                               uint32_t seed_lo, uint32_t seed_hi,
+                                                               float eps_signed, float* __restrict__ se) {
+  const uint32_t Gb = (G + 7u) >> 3;
+  const uint64_t u = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+  if (u >= (uint64_t)N * Gb) return;
+  const uint32_t row = (uint32_t)(u / Gb), gb = (uint32_t)(u - (uint64_t)row * Gb);
+  float z[8];
+  scale_normals8(seed_lo, seed_hi, 0u, row_base + row, gb, z);
+  const uint32_t nv = min(8u, G - gb * 8u);
+  const uint64_t base = (uint64_t)row * G + gb * 8u;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if ((uint32_t)j < nv) se[base + j] = __builtin_fmaf(eps_signed, z[j], bf16_to_f32(s[base + j]));
+}
+
+// bf16 [N,K] from the indices and the perturbed scales: a thread turns one dword (eight
+// indices, k = 8c .. 8c+7, lowest nibble first) into 16 bytes; the level table sits in LDS
+// (16 words in 16 banks: any mix of indices is served without a conflict).
+__global__ __launch_bounds__(256) void expand_nf4_kernel(const uint32_t* __restrict__ q,
+                                                         const float* __restrict__ se, uint32_t N,
+                                                         uint32_t K, int swiglu, uint4* __restrict__ out) {
+  __shared__ float lut[16];
+  if (threadIdx.x < 16) lut[threadIdx.x] = NF4_LEVELS_DEV[threadIdx.x];
+  __syncthreads();
+  const uint32_t p = blockIdx.x, nc = K >> 3, kc = blockIdx.y * 256u + threadIdx.x;
+  if (kc >= nc) return;
+  const uint32_t gn = expand_source_row(p, N, swiglu != 0);
+  const uint32_t w = q[(uint64_t)gn * nc + kc];
+  const float sc = se[(uint64_t)gn * (K >> 6) + (kc >> 3)];
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    o[j] = pack_bf16x2(sc * lut[(w >> (8 * j)) & 15u], sc * lut[(w >> (8 * j + 4)) & 15u]);
+  out[(uint64_t)p * nc + kc] = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// int4 groups of 128 (Eq. 4-5): W = (s + sigma*eps*z)[n, k/128] * (u - zp), zp = 8 without a
+// zero-point tensor.  u - zp is an exact small integer, so the one rounding is that of the product
+// to bf16: the same bits as the weight tile of the fused GEMM.
+__global__ __launch_bounds__(256) void expand_int4_kernel(const uint32_t* __restrict__ q,
+                                                          const float* __restrict__ se,
+                                                          const uint8_t* __restrict__ zp, uint32_t N,
+                                                          uint32_t K, int swiglu, uint4* __restrict__ out) {
+  const uint32_t p = blockIdx.x, nc = K >> 3, kc = blockIdx.y * 256u + threadIdx.x;
+  if (kc >= nc) return;
+  const uint32_t gn = expand_source_row(p, N, swiglu != 0);
+  const uint32_t w = q[(uint64_t)gn * nc + kc];
+  const uint64_t gi = (uint64_t)gn * (K >> 7) + (kc >> 4);
+  const float sc = se[gi];
+  const int z0 = zp ? (int)zp[gi] : 8;
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    o[j] = pack_bf16x2(sc * (float)((int)((w >> (8 * j)) & 15u) - z0),
+                       sc * (float)((int)((w >> (8 * j + 4)) & 15u) - z0));
+  out[(uint64_t)p * nc + kc] = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, uint32_t N, uint32_t K,
+                              uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+                              bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st) {
+  if (N == 0) return hipSuccess;
+  const uint32_t G = K >> 7, Gb = (G + 7u) >> 3;
+  const uint64_t units = (uint64_t)N * Gb;
+  perturbed_scales_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(
+      (const bf16_t*)s_bf16, N, G, row_base, seed_lo, seed_hi, eps_signed, se_scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  expand_int4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>(
+      (const uint32_t*)q, se_scratch, (const uint8_t*)zp, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand_nf4(const void* q, const void* s_bf16, uint32_t N, uint32_t K, uint32_t row_base,
+                             uint32_t seed_lo, uint32_t seed_hi, float eps_signed, bool swiglu,
+                             float* se_scratch, void* out_bf16, hipStream_t st) {
+  if (N == 0) return hipSuccess;
+  const uint32_t G = K >> 6, Gb = (G + 7u) >> 3;
+  const uint64_t units = (uint64_t)N * Gb;
+  perturbed_scales_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(
+      (const bf16_t*)s_bf16, N, G, row_base, seed_lo, seed_hi, eps_signed, se_scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  expand_nf4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>((const uint32_t*)q, se_scratch, N, K,
+                                                                   swiglu ? 1 : 0, (uint4*)out_bf16);
+  return hipGetLastError();
+}
+
 }  // namespace qzo

@@ -66,6 +66,14 @@ hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st);
 hipError_t launch_expand_codebook(const void* codes, const void* cb, const void* c_fp16, uint32_t N,
                                   uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi,
                                   float eps_signed, bool swiglu, void* out_bf16, hipStream_t st);
+// NormalFloat-4 blocks of 64: se_scratch receives the perturbed scales, fp32 [N, K/64].
+hipError_t launch_expand_nf4(const void* q, const void* s_bf16, uint32_t N, uint32_t K, uint32_t row_base,
+                             uint32_t seed_lo, uint32_t seed_hi, float eps_signed, bool swiglu,
+                             float* se_scratch, void* out_bf16, hipStream_t st);
+// int4 groups of 128 (zp: uint8 [N, K/128] or null = 8): se_scratch fp32 [N, K/128].
+hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, uint32_t N, uint32_t K,
+                              uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+                              bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st);
 constexpr uint32_t EXPAND_MIN_M = 512;   // fewer tokens: the fused kernels read less than an expansion writes
 hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,
                                  uint32_t seed_hi, float eta, float d_clipped,

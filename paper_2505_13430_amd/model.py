@@ -57,7 +57,7 @@ class DeviceModel:
         return cls(dict(shape, quant=1), dev, arena)
 
     @classmethod
-    def synthetic(cls, shape: dict, seed: int, device="cuda:0", asym=False):
+    def synthetic(cls, shape: dict, seed: int, device="cuda:0", asym=False, nf4=False):
         """Random-init model built on the device: weights ~ N(0, 0.02) drawn by
         torch, quantized by the library's RTN kernel (Eq. 3), tensor by tensor.
         asym: the zero-point variant (quant = 2); each group then also gets a zero-point drawn
@@ -65,6 +65,10 @@ class DeviceModel:
         the work per step are those of a zero-point checkpoint)."""
         if asym:
             shape = dict(shape, quant=2)
+        if nf4:
+            # NormalFloat-4: uniform random level indices, block-64 scales ~ U(0.03, 0.09) (the absmax
+            # of 64 weights ~ N(0, 0.02)): the shapes, sizes and work of such a checkpoint
+            shape = dict(shape, quant=3, group=64)
         gen = torch.Generator(device=device)
         gen.manual_seed(seed)
         d, V = shape["d_model"], shape["vocab"]
@@ -78,6 +82,11 @@ class DeviceModel:
 
         def quant(N, K):
             nonlocal off
+            if nf4:
+                n = N * (K // 64)
+                arena[off:off + n] = (torch.rand(n, generator=gen, device=device) * 0.06 + 0.03).to(torch.bfloat16)
+                off += n
+                return [torch.randint(0, 256, (N, K // 2), generator=gen, device=device, dtype=torch.uint8)]
             w = torch.randn(N, K, generator=gen, device=device) * 0.02
             q = torch.empty(N, K // 2, dtype=torch.uint8, device=device)
             n = N * (K // 128)

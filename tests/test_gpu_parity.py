@@ -203,7 +203,7 @@ SHARP = dict(arch="llama", n_layers=2, d_model=256, n_heads=2, d_ffn=512, vocab=
              batch=3, seq=80)     # head size 128, ragged vocab, seq not a multiple of 32/128
 
 
-def _models(oracle, shape, seed, gain=1.0, asym=False):
+def _models(oracle, shape, seed, gain=1.0, asym=False, nf4=False):
     table = synth.tensor_table(shape, seed)
     if gain != 1.0:   # larger weights: logits far from uniform, loss far from ln V
         table = [(n, k, synth.bf16_exact(a * gain) if (k == "w" or n in ("tok_emb", "lm_head")) else a)
@@ -211,17 +211,20 @@ def _models(oracle, shape, seed, gain=1.0, asym=False):
     if asym:          # rows with off-centre weights, so that the zero-points spread over 2..13
         table = [(n, k, (a + 0.03 * gain * np.sin(np.arange(a.shape[0]))[:, None]).astype(np.float32)
                   if k == "w" else a) for n, k, a in table]
-    om = oracle.build_model(shape, table, asym=asym)
-    return om, DeviceModel.from_host(dict(shape, quant=om.quant), om.tensors, om.scales, DEV)
+    om = oracle.build_model(shape, table, asym=asym, nf4=nf4)
+    return om, DeviceModel.from_host(dict(shape, quant=om.quant, group=om.group), om.tensors, om.scales, DEV)
 
 
 def _case(name):
-    """'<shape>' or '<shape>+zp' (the zero-point variant) -> (shape, asym)."""
-    base, _, zp = name.partition("+")
-    shape = SHARP if base == "sharp" else (FEW[base] if base in FEW else synth.SHAPES[base])
-    return shape, zp == "zp"
+    """'<shape>', '<shape>+zp' (zero-points) or '<shape>+nf4' (NormalFloat-4) -> (shape, variant flag)."""
+    base, _, var = name.partition("+")
+    shape = SHARP if base == "sharp" else (FEW.get(base) or MANY.get(base) or synth.SHAPES[base])
+    return shape, {"": False, "zp": True, "nf4": "nf4"}[var]
 
 
+# 576 tokens: from 512 tokens on the int4 linears run expand-then-multiply
+MANY = {"many_llama": dict(synth.SHAPES["tiny"], batch=9, seq=64),
+        "many_opt": dict(synth.SHAPES["tiny_opt"], batch=9, seq=64)}
 FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tokens: one token tile
        "few_opt": dict(synth.SHAPES["tiny_opt"], batch=2, seq=32)}      # 64 tokens: two token tiles
 
@@ -229,11 +232,14 @@ FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tok
 @pytest.mark.parametrize("name,gain", [("tiny", 1.0), ("tiny_opt", 1.0), ("tiny", 4.0), ("tiny_opt", 4.0),
                                        ("sharp", 4.0), ("few_llama", 4.0), ("few_opt", 4.0),
                                        ("tiny+zp", 4.0), ("tiny_opt+zp", 4.0), ("sharp+zp", 4.0),
-                                       ("few_llama+zp", 4.0), ("few_opt+zp", 1.0)])
+                                       ("few_llama+zp", 4.0), ("few_opt+zp", 1.0),
+                                       ("tiny+nf4", 4.0), ("tiny_opt+nf4", 4.0), ("sharp+nf4", 4.0),
+                                       ("few_llama+nf4", 1.0),
+                                       ("many_llama", 4.0), ("many_opt", 4.0), ("many_llama+zp", 4.0)])
 def test_forward_matches_oracle(oracle, name, gain):
     shape, asym = _case(name)
-    om, dm = _models(oracle, shape, 1234, gain, asym)
-    if asym:
+    om, dm = _models(oracle, shape, 1234, gain, asym is True, asym == "nf4")
+    if asym is True:
         zps = np.concatenate([t.reshape(-1) for n, t in zip(om.names, om.tensors) if n.endswith(".zp")])
         assert zps.min() <= 3 and zps.max() >= 12
     tok = synth.tokens(shape, 5678)
@@ -268,13 +274,16 @@ def test_forward_matches_oracle(oracle, name, gain):
 
 
 @pytest.mark.parametrize("name", ["tiny", "tiny_opt", "few_llama", "few_opt",
-                                  "tiny+zp", "tiny_opt+zp", "few_llama+zp", "few_opt+zp"])
+                                  "tiny+zp", "tiny_opt+zp", "few_llama+zp", "few_opt+zp",
+                                  "tiny+nf4", "tiny_opt+nf4", "few_llama+nf4",
+                                  "many_llama", "many_opt", "many_llama+zp"])
 def test_step_matches_oracle(oracle, name):
     shape, asym = _case(name)
-    om, dm = _models(oracle, shape, 1234, asym=asym)
+    om, dm = _models(oracle, shape, 1234, asym=asym is True, nf4=asym == "nf4")
     tok = synth.tokens(shape, 5678)
     tokd = _dev(tok)
-    eta = 1e-5
+    # NormalFloat-4 scales are a block's absmax, ten times larger (the 24-token case has a larger |d|)
+    eta = (1e-4 if name.startswith("few") else 3e-4) if asym == "nf4" else 1e-5
     seed = 3 if asym else 1           # a direction whose |d| is large enough to move the scales
     ref = oracle.qzo_step(om, tok, seed=seed, eps=1e-3, eta=eta, Cthr=100.0)
     before = dm.scales.clone()
@@ -301,7 +310,7 @@ def test_stacked_passes_equal_separate_passes(oracle, name):
     weights are read once); its losses are bit-identical to two separate forward passes."""
     base, asym = _case(name)
     shape = dict(base, batch=2, seq=13)
-    om, dm = _models(oracle, shape, 1234, 4.0, asym)
+    om, dm = _models(oracle, shape, 1234, 4.0, asym is True)
     tokd = _dev(synth.tokens(shape, 5678))
     res = qb.read_step_result(dm.step(tokd, 21, 1e-3, 0.0, 100.0))       # eta = 0: scales untouched
     lp = float(dm.forward_loss(tokd, 21, 1e-3, 1).item())
@@ -560,11 +569,11 @@ def _joint_models(oracle, name):
         table = synth.codebook_tensor_table(shape, 31)
         return shape, oracle.build_codebook_model(shape, table), DeviceModel.from_host_codebook(shape, table, DEV)
     shape, asym = _case(name)
-    om, dm = _models(oracle, shape, 1234, asym=asym)
+    om, dm = _models(oracle, shape, 1234, asym=asym is True, nf4=asym == "nf4")
     return shape, om, dm
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "few_llama", "tiny+zp", "codebook"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "few_llama", "tiny+zp", "tiny+nf4", "codebook"])
 def test_joint_step_matches_oracle(oracle, name):
     shape, om, dm = _joint_models(oracle, name)
     tok = synth.tokens(shape, 5678)
@@ -617,3 +626,83 @@ def test_plain_bf16_gemm_matches_oracle(oracle, M, N, K, pipe):
     err = np.abs(y.float().cpu().numpy() - ref)
     assert (err <= 2e-2 * np.abs(ref) + 2e-2 * math.sqrt(K) * 0.05).all()
     assert err.max() <= 1e-2 * np.abs(ref).max()
+
+
+# ------------------------------------- NormalFloat-4 blocks (the quantizer of Sec. 4.3) ----
+@pytest.mark.parametrize("N,K,row_base", [(24, 384, 0), (264, 1280, 77), (8, 128, 5), (40, 11008, 3)])
+def test_nf4_perturbed_scales_and_matrix_bit_exact(oracle, N, K, row_base):
+    rng = np.random.default_rng(N + K)
+    w = (rng.standard_normal((N, K)) * 0.03).astype(np.float32)
+    qp, s = oracle.nf4_quantize(w)
+    q, sd = _dev(qp), _dev(s, torch.bfloat16)
+    for sign in (1, -1):
+        se = torch.zeros((N, K // 64), dtype=torch.float32, device=DEV)
+        out = torch.zeros((N, K), dtype=torch.bfloat16, device=DEV)
+        qb.qzo_nf4_expand(q, sd, row_base, 99, 1e-3, sign, se, out)
+        want_se = oracle.effective_scales(s, row_base, 99, sign * np.float32(1e-3)).astype(np.float32)
+        assert np.array_equal(_bits(se.cpu().numpy()), _bits(want_se))
+        want = oracle.dequant_nf4(qp, s, 99, row_base, sign * np.float32(1e-3), to_bf16=True)
+        assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 520, 384), (256, 264, 1280), (16, 136, 512), (513, 256, 128)])
+def test_nf4_linear_matches_oracle(oracle, M, N, K):
+    rng = np.random.default_rng(M * 7 + N + K)
+    x = synth.bf16_exact(rng.standard_normal((M, K), dtype=np.float32))
+    w = (rng.standard_normal((N, K)) * 0.03).astype(np.float32)
+    qp, s = oracle.nf4_quantize(w)
+    scratch = torch.empty(qb.qzo_nf4_scratch_bytes(N, K), dtype=torch.uint8, device=DEV)
+    for sign in (1, -1):
+        y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+        qb.qzo_nf4_gemm(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), 11, 31, 1e-3, sign, y, scratch)
+        se = oracle.effective_scales(s, 11, 31, sign * np.float32(1e-3))
+        ref = oracle.qlinear_nf4(x.astype(np.float64), qp, se)
+        err = np.abs(y.float().cpu().numpy() - ref)
+        scale = math.sqrt(K) * 0.03
+        assert (err <= 2e-2 * np.abs(ref) + 2e-2 * scale).all()
+        assert err.max() <= 1e-2 * np.abs(ref).max() + 4e-3 * scale
+    with pytest.raises(qb.QzoError):
+        qb.qzo_nf4_gemm(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), 11, 31, 1e-3, 1, y, scratch[:256])
+
+
+@pytest.mark.parametrize("name", ["many_llama", "many_opt+zp"])
+def test_int4_expand_then_multiply_equals_the_fused_path(oracle, name):
+    """Both routes form the same bf16 weights (one rounding of scale x integer) and accumulate each
+    output over k in the same order, so losses and hidden states agree bit for bit."""
+    shape, asym = _case(name)
+    om, dm = _models(oracle, shape, 1234, 4.0, asym is True)
+    tok = synth.tokens(shape, 5678)
+    B, S = tok.shape
+    outs = []
+    try:
+        for mode in (0, 1):
+            qb.qzo_set_int4_path(mode)
+            hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+            loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+            qb.qzo_debug_forward(dm.handle, _dev(tok), 9, 1e-3, -1, dm.workspace(B, S), loss, hid)
+            outs.append((float(loss.item()), hid.float().cpu().numpy()))
+    finally:
+        qb.qzo_set_int4_path(0)
+    assert outs[0][0] == outs[1][0]
+    assert np.array_equal(outs[0][1], outs[1][1])
+    dm.close()
+
+
+@pytest.mark.parametrize("N,K,row_base,with_zp", [(24, 384, 0, False), (40, 1024 + 128, 77, True), (8, 128, 5, False),
+                                                  (16, 11008, 3, True)])
+def test_int4_expanded_matrix_bit_exact(oracle, N, K, row_base, with_zp):
+    rng = np.random.default_rng(N + K)
+    qp = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    s = synth.bf16_exact(rng.uniform(0.002, 0.02, (N, K // 128)).astype(np.float32))
+    zp = rng.integers(0, 16, (N, K // 128), dtype=np.uint8) if with_zp else None
+    for sign in (1, -1):
+        se = torch.zeros((N, K // 128), dtype=torch.float32, device=DEV)
+        out = torch.zeros((N, K), dtype=torch.bfloat16, device=DEV)
+        qb.qzo_int4_expand(_dev(qp), _dev(s, torch.bfloat16), _dev(zp) if with_zp else None, row_base, 99, 1e-3,
+                           sign, se, out)
+        e = sign * np.float32(1e-3)
+        assert np.array_equal(_bits(se.cpu().numpy()),
+                              _bits(oracle.effective_scales(s, row_base, 99, e).astype(np.float32)))
+        want = (oracle.dequant_zp(qp, s, zp, 99, row_base, e, to_bf16=True) if with_zp
+                else oracle.dequant(qp, s, 99, row_base, e, to_bf16=True))
+        assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
