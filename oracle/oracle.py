@@ -121,8 +121,9 @@ def dequant(qp, s, seed, row_base, eps_signed, group=128, to_bf16=False):
     return out
 
 
-def dequant_zp(qp, s, zp, seed, row_base, eps_signed, group=128, to_bf16=False):
-    """Asymmetric groups: W_eff[n,k] = (s + eps z) * (u[n,k] - zp[n,k/group])."""
+def dequant_zp(qp, s, zp, seed, row_base, eps_signed, group=128, to_bf16=False, g_idx=None):
+    """Asymmetric groups: W_eff[n,k] = (s + eps z) * (u[n,k] - zp[n,g(k)]), g(k) = k/group or g_idx[k]."""
+    gi = None if g_idx is None else np.ascontiguousarray(g_idx, dtype=np.int32)
     qp = np.ascontiguousarray(qp, dtype=np.uint8)
     s = _f32(s)
     zp = np.ascontiguousarray(zp, dtype=np.uint8)
@@ -130,7 +131,7 @@ def dequant_zp(qp, s, zp, seed, row_base, eps_signed, group=128, to_bf16=False):
     out = np.zeros((N, K), dtype=np.float32)
     lib().orc_dequant_zp(_p(qp), _p(s), _p(zp), C.c_uint64(N), C.c_uint64(K), C.c_uint32(group),
                          C.c_uint64(seed), C.c_uint32(row_base), C.c_float(eps_signed),
-                         C.c_int(1 if to_bf16 else 0), _p(out))
+                         C.c_int(1 if to_bf16 else 0), _p(gi) if gi is not None else None, _p(out))
     return out
 
 

@@ -312,14 +312,16 @@ void orc_dequant(const uint8_t* qp, const float* s, uint64_t N, uint64_t K, uint
 // ---- asymmetric 4-bit groups (zero-points): the format of the 4-bit checkpoints the
 // paper fine-tunes (Sec. 4.1: GPTQ, group 128).  W[n,k] = s[n,g] * (u[n,k] - zp[n,g]) with the
 // stored nibble u in 0..15 and an integer zero-point zp in 0..15 per (row, group); Eq. 4-5 with
-// wbar = u - zp.  zp = 8 is the symmetric format above.
+// wbar = u - zp.  zp = 8 is the symmetric format above.  With activation reordering the
+// quantizer assigns input columns to groups in an order of its own: g_idx[k] (when given) is the
+// group of column k instead of k / group; scales, zero-points and their noise stay per (row, group).
 void orc_dequant_zp(const uint8_t* qp, const float* s, const uint8_t* zp, uint64_t N, uint64_t K,
                     uint32_t group, uint64_t seed, uint32_t row_base, float eps_signed, int to_bf16,
-                    float* w_eff) {
+                    const int32_t* g_idx, float* w_eff) {
   uint64_t G = K / group;
   for (uint64_t n = 0; n < N; ++n)
     for (uint64_t k = 0; k < K; ++k) {
-      uint64_t g = k / group;
+      uint64_t g = g_idx ? (uint64_t)g_idx[k] : k / group;
       float z = scale_normal(seed, 0u, (uint32_t)(row_base + n), (uint32_t)g);
       float se = std::fmaf(eps_signed, z, s[n * G + g]);
       int u = unpack_q(qp, K, n, k) + 8;                       // the stored nibble

@@ -723,3 +723,21 @@ def test_nf4_forward_matches_torch_composition(oracle, arch):
     got = oracle.forward_loss(m, se, tok, act_bf16=False)
     assert math.isclose(got, _torch_forward(m, se, tok, oracle), rel_tol=1e-10)
     assert abs(got - math.log(sh["vocab"])) < 0.2
+
+
+def test_zero_point_dequant_with_activation_reordering(oracle):
+    rng = np.random.default_rng(51)
+    N, K, G = 7, 512, 4
+    qp = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    s = synth.bf16_exact(rng.uniform(0.002, 0.02, (N, G)).astype(np.float32))
+    zp = rng.integers(0, 16, (N, G), dtype=np.uint8)
+    # the identity assignment is the plain format
+    ident = np.arange(K) // 128
+    assert np.array_equal(oracle.dequant_zp(qp, s, zp, 9, 3, 1e-3, g_idx=ident), oracle.dequant_zp(qp, s, zp, 9, 3, 1e-3))
+    # a scattered assignment (every group still gets 128 columns): gather per column
+    g_idx = rng.permutation(ident).astype(np.int32)
+    u = (oracle.unpack_int4(qp, K) + 8).astype(np.float32)
+    se = oracle.effective_scales(s, 3, 9, np.float32(1e-3)).astype(np.float32)
+    want = se[:, g_idx] * (u - zp[:, g_idx].astype(np.float32))
+    got = oracle.dequant_zp(qp, s, zp, 9, 3, 1e-3, g_idx=g_idx)
+    assert np.array_equal(got, want) and not np.array_equal(got, oracle.dequant_zp(qp, s, zp, 9, 3, 1e-3))
