@@ -302,15 +302,28 @@ qzo_status qzo_nf4_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
                         void* stream);
 
 /*
- * First stage of expand-then-multiply for int4 groups (Eq. 4-5): the perturbed scales
- * se = s + sign*eps*z (se_dev, fp32 [N, K/128], one fma each) and the perturbed weight matrix
- * (w_dev, bf16 [N,K]) = se[n, k/128] * (u[n,k] - zp[n, k/128]) rounded once to bf16; zp_dev may be
- * null (every zero-point 8: the symmetric format).  Operand layouts as for qzo_dequant_gemm /
- * qzo_dequant_gemm_zp; the result has the same bits as the fused kernel's weight tile.
+ * Expand-then-multiply for int4 groups (Eq. 4-5) on a single linear.
+ * qzo_int4_expand, the first stage: the perturbed scales se = s + sign*eps*z (se_dev, fp32 [N, K/128],
+ * one fma each) and the perturbed weight matrix (w_dev, bf16 [N,K]) =
+ * se[n, g(k)] * (u[n,k] - zp[n, g(k)]) rounded once to bf16.  zp_dev may be null (every zero-point 8:
+ * the symmetric format).  g_idx_dev may be null (g(k) = k / 128) or point to int32 [K], the group of
+ * every input column (activation reordering of the Sec. 4.1 checkpoints; values outside 0 .. K/128 - 1
+ * are clamped); the noise stays per (row, group).  Other operands as for qzo_dequant_gemm_zp; without
+ * g_idx the result has the same bits as the fused kernel's weight tile.
+ * qzo_int4_gemm_expanded: the same into scratch_dev (qzo_int4_scratch_bytes(N, K) bytes, 256-byte
+ * aligned, contents undefined afterwards), then Y = X W^T with the plain bf16 GEMM (x_dev bf16 [M,K],
+ * y_dev bf16 [M,N]); the only GEMM entry point that takes g_idx.
  */
-qzo_status qzo_int4_expand(const void* q_dev, const void* s_dev, const void* zp_dev, uint32_t row_base,
-                           uint32_t N, uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
-                           float* se_dev, void* w_dev, void* stream);
+qzo_status qzo_int4_expand(const void* q_dev, const void* s_dev, const void* zp_dev,
+                           const int32_t* g_idx_dev, uint32_t row_base, uint32_t N, uint32_t K,
+                           uint32_t group, uint64_t seed, float eps, int sign, float* se_dev,
+                           void* w_dev, void* stream);
+qzo_status qzo_int4_scratch_bytes(uint32_t N, uint32_t K, uint64_t* out);
+qzo_status qzo_int4_gemm_expanded(const void* x_dev, const void* q_dev, const void* s_dev,
+                                  const void* zp_dev, const int32_t* g_idx_dev, uint32_t row_base,
+                                  uint32_t M, uint32_t N, uint32_t K, uint32_t group, uint64_t seed,
+                                  float eps, int sign, void* y_dev, void* scratch_dev,
+                                  uint64_t scratch_bytes, void* stream);
 
 /* How the model's int4 linears (quant 0 and 2) run when a pass has at least 512 tokens:
  * mode 0 (default): the perturbed weights of a linear are first written out as a bf16 matrix in the

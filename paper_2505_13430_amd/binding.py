@@ -24,7 +24,7 @@ EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
     "qzo_model_dense_count", "qzo_model_enable_joint", "qzo_step_joint",
-    "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm", "qzo_set_int4_path", "qzo_int4_expand",
+    "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm", "qzo_set_int4_path", "qzo_int4_expand", "qzo_int4_scratch_bytes", "qzo_int4_gemm_expanded",
     "qzo_apply_update", "qzo_dequant_gemm_zp", "qzo_repack_kmajor", "qzo_debug_dequant_zp", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
     "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_debug_bf16_gemm", "qzo_profile_begin", "qzo_profile_collect",
     "qzo_last_error",
@@ -224,11 +224,26 @@ def qzo_debug_dequant(q, s, row_base, seed, eps, sign, w_eff, group=128, stream=
                                    C.c_float(eps), C.c_int(sign), _ptr(w_eff), _stream(stream)))
 
 
-def qzo_int4_expand(q, s, zp, row_base, seed, eps, sign, se_out, w_out, stream=None):
+def qzo_int4_expand(q, s, zp, row_base, seed, eps, sign, se_out, w_out, g_idx=None, stream=None):
     N, K = q.shape[0], q.shape[1] * 2
-    _check(lib().qzo_int4_expand(_ptr(q), _ptr(s), _ptr(zp), C.c_uint32(row_base), C.c_uint32(N), C.c_uint32(K),
-                                 C.c_uint32(128), C.c_uint64(seed), C.c_float(eps), C.c_int(sign),
+    _check(lib().qzo_int4_expand(_ptr(q), _ptr(s), _ptr(zp), _ptr(g_idx), C.c_uint32(row_base), C.c_uint32(N),
+                                 C.c_uint32(K), C.c_uint32(128), C.c_uint64(seed), C.c_float(eps), C.c_int(sign),
                                  _ptr(se_out), _ptr(w_out), _stream(stream)))
+
+
+def qzo_int4_scratch_bytes(N, K) -> int:
+    out = C.c_uint64(0)
+    _check(lib().qzo_int4_scratch_bytes(C.c_uint32(N), C.c_uint32(K), C.byref(out)))
+    return out.value
+
+
+def qzo_int4_gemm_expanded(x, q, s, zp, g_idx, row_base, seed, eps, sign, y, scratch, stream=None):
+    M, K = x.shape
+    N = q.shape[0]
+    _check(lib().qzo_int4_gemm_expanded(_ptr(x), _ptr(q), _ptr(s), _ptr(zp), _ptr(g_idx), C.c_uint32(row_base),
+                                        C.c_uint32(M), C.c_uint32(N), C.c_uint32(K), C.c_uint32(128),
+                                        C.c_uint64(seed), C.c_float(eps), C.c_int(sign), _ptr(y), _ptr(scratch),
+                                        C.c_uint64(scratch.numel() * scratch.element_size()), _stream(stream)))
 
 
 def qzo_nf4_expand(q, s, row_base, seed, eps, sign, se_out, w_out, stream=None):

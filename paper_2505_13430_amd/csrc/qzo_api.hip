@@ -319,7 +319,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         // many tokens: write the perturbed matrix out once, then a plain bf16 GEMM
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
-          hipError_t e = launch_expand_int4(g.w, g.s, g.zp, g.N, g.K, g.row_base, seed_lo, seed_hi,
+          hipError_t e = launch_expand_int4(g.w, g.s, g.zp, nullptr, g.N, g.K, g.row_base, seed_lo, seed_hi,
                                             eps_signed, (epi & EPI_SWIGLU) != 0, w.se, w.wexp, st);
           if (e != hipSuccess) return e;
         }
@@ -803,17 +803,59 @@ qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const voi
   return QZO_OK;
 }
 
-qzo_status qzo_int4_expand(const void* q_dev, const void* s_dev, const void* zp_dev, uint32_t row_base,
-                           uint32_t N, uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
-                           float* se_dev, void* w_dev, void* stream) {
-  if (!q_dev || !s_dev || !se_dev || !w_dev) return fail(QZO_ERR_ARG, "null device pointer");
-  if (!aligned16(q_dev) || !aligned16(s_dev) || !aligned16(se_dev) || !aligned16(w_dev))
+static qzo_status int4_expand_check(const void* q_dev, const void* s_dev, const int32_t* g_idx_dev,
+                                    uint32_t K, uint32_t group, float eps, int sign) {
+  if (!q_dev || !s_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(q_dev) || !aligned16(s_dev) || !aligned16(g_idx_dev))
     return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
   if (group != 128 || K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
   if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
   if (!std::isfinite(eps)) return fail(QZO_ERR_ARG, "eps not finite");
-  QZO_HIP(launch_expand_int4(q_dev, s_dev, zp_dev, N, K, row_base, (uint32_t)seed, (uint32_t)(seed >> 32),
-                             sign > 0 ? eps : -eps, false, se_dev, w_dev, (hipStream_t)stream));
+  return QZO_OK;
+}
+
+qzo_status qzo_int4_expand(const void* q_dev, const void* s_dev, const void* zp_dev,
+                           const int32_t* g_idx_dev, uint32_t row_base, uint32_t N, uint32_t K,
+                           uint32_t group, uint64_t seed, float eps, int sign, float* se_dev, void* w_dev,
+                           void* stream) {
+  qzo_status st = int4_expand_check(q_dev, s_dev, g_idx_dev, K, group, eps, sign);
+  if (st != QZO_OK) return st;
+  if (!se_dev || !w_dev) return fail(QZO_ERR_ARG, "null output");
+  if (!aligned16(se_dev) || !aligned16(w_dev)) return fail(QZO_ERR_ALIGN, "output not 16-byte aligned");
+  QZO_HIP(launch_expand_int4(q_dev, s_dev, zp_dev, g_idx_dev, N, K, row_base, (uint32_t)seed,
+                             (uint32_t)(seed >> 32), sign > 0 ? eps : -eps, false, se_dev, w_dev,
+                             (hipStream_t)stream));
+  return QZO_OK;
+}
+
+qzo_status qzo_int4_scratch_bytes(uint32_t N, uint32_t K, uint64_t* out) {
+  if (!out) return fail(QZO_ERR_ARG, "out is null");
+  *out = up256((uint64_t)N * K * 2) + up256((uint64_t)N * (K / 128) * 4);
+  return QZO_OK;
+}
+
+qzo_status qzo_int4_gemm_expanded(const void* x_dev, const void* q_dev, const void* s_dev, const void* zp_dev,
+                                  const int32_t* g_idx_dev, uint32_t row_base, uint32_t M, uint32_t N,
+                                  uint32_t K, uint32_t group, uint64_t seed, float eps, int sign, void* y_dev,
+                                  void* scratch_dev, uint64_t scratch_bytes, void* stream) {
+  qzo_status st = int4_expand_check(q_dev, s_dev, g_idx_dev, K, group, eps, sign);
+  if (st != QZO_OK) return st;
+  if (!x_dev || !y_dev || !scratch_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(x_dev) || !aligned16(y_dev) || ((uintptr_t)scratch_dev & 255u))
+    return fail(QZO_ERR_ALIGN, "x/y need 16-byte, scratch 256-byte alignment");
+  if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
+  uint64_t need = 0;
+  qzo_int4_scratch_bytes(N, K, &need);
+  if (scratch_bytes < need) return fail(QZO_ERR_WORKSPACE, "scratch too small: see qzo_int4_scratch_bytes");
+  if (M == 0 || N == 0) return QZO_OK;
+  hipStream_t s = (hipStream_t)stream;
+  unsigned char* wexp = (unsigned char*)scratch_dev;
+  float* se = (float*)(wexp + up256((uint64_t)N * K * 2));
+  QZO_HIP(launch_expand_int4(q_dev, s_dev, zp_dev, g_idx_dev, N, K, row_base, (uint32_t)seed,
+                             (uint32_t)(seed >> 32), sign > 0 ? eps : -eps, false, se, wexp, s));
+  GemmArgs g = {};
+  g.x = x_dev; g.w = wexp; g.y = y_dev; g.M = M; g.N = N; g.K = K;
+  QZO_HIP(launch_bf16_gemm(g, 1, s));
   return QZO_OK;
 }
 

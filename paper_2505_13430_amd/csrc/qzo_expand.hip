@@ -118,27 +118,44 @@ __global__ __launch_bounds__(256) void expand_nf4_kernel(const uint32_t* __restr
 // int4 groups of 128 (Eq. 4-5): W = (s + sigma*eps*z)[n, k/128] * (u - zp), zp = 8 without a
 // zero-point tensor.  u - zp is an exact small integer, so the one rounding is that of the product
 // to bf16: the same bits as the weight tile of the fused GEMM.
+// With activation reordering (g_idx, int32 [K]) column k belongs to group g_idx[k] instead of
+// k / 128: scale and zero-point are then looked up per weight.
 __global__ __launch_bounds__(256) void expand_int4_kernel(const uint32_t* __restrict__ q,
                                                           const float* __restrict__ se,
-                                                          const uint8_t* __restrict__ zp, uint32_t N,
+                                                          const uint8_t* __restrict__ zp,
+                                                          const int32_t* __restrict__ g_idx, uint32_t N,
                                                           uint32_t K, int swiglu, uint4* __restrict__ out) {
   const uint32_t p = blockIdx.x, nc = K >> 3, kc = blockIdx.y * 256u + threadIdx.x;
   if (kc >= nc) return;
   const uint32_t gn = expand_source_row(p, N, swiglu != 0);
   const uint32_t w = q[(uint64_t)gn * nc + kc];
-  const uint64_t gi = (uint64_t)gn * (K >> 7) + (kc >> 4);
-  const float sc = se[gi];
-  const int z0 = zp ? (int)zp[gi] : 8;
+  const uint64_t g0 = (uint64_t)gn * (K >> 7);
   uint32_t o[4];
+  if (g_idx) {
+    const int4 ga = reinterpret_cast<const int4*>(g_idx)[2 * kc], gb = reinterpret_cast<const int4*>(g_idx)[2 * kc + 1];
+    const int g[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+    float v[8];
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
-    o[j] = pack_bf16x2(sc * (float)((int)((w >> (8 * j)) & 15u) - z0),
-                       sc * (float)((int)((w >> (8 * j + 4)) & 15u) - z0));
+    for (int i = 0; i < 8; ++i) {
+      const uint64_t gi = g0 + min((uint32_t)g[i], (K >> 7) - 1u);   // an index outside 0..G-1 is clamped
+      v[i] = se[gi] * (float)((int)((w >> (4 * i)) & 15u) - (zp ? (int)zp[gi] : 8));
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = pack_bf16x2(v[2 * j], v[2 * j + 1]);
+  } else {
+    const uint64_t gi = g0 + (kc >> 4);
+    const float sc = se[gi];
+    const int z0 = zp ? (int)zp[gi] : 8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      o[j] = pack_bf16x2(sc * (float)((int)((w >> (8 * j)) & 15u) - z0),
+                         sc * (float)((int)((w >> (8 * j + 4)) & 15u) - z0));
+  }
   out[(uint64_t)p * nc + kc] = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, uint32_t N, uint32_t K,
-                              uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, const int32_t* g_idx,
+                              uint32_t N, uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                               bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st) {
   if (N == 0) return hipSuccess;
   const uint32_t G = K >> 7, Gb = (G + 7u) >> 3;
@@ -148,7 +165,7 @@ hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   expand_int4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>(
-      (const uint32_t*)q, se_scratch, (const uint8_t*)zp, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
+      (const uint32_t*)q, se_scratch, (const uint8_t*)zp, g_idx, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
   return hipGetLastError();
 }
 

@@ -70,9 +70,10 @@ hipError_t launch_expand_codebook(const void* codes, const void* cb, const void*
 hipError_t launch_expand_nf4(const void* q, const void* s_bf16, uint32_t N, uint32_t K, uint32_t row_base,
                              uint32_t seed_lo, uint32_t seed_hi, float eps_signed, bool swiglu,
                              float* se_scratch, void* out_bf16, hipStream_t st);
-// int4 groups of 128 (zp: uint8 [N, K/128] or null = 8): se_scratch fp32 [N, K/128].
-hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, uint32_t N, uint32_t K,
-                              uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+// int4 groups of 128 (zp: uint8 [N, K/128] or null = 8; g_idx: int32 [K] group of each column, or
+// null = k / 128): se_scratch fp32 [N, K/128].
+hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, const int32_t* g_idx,
+                              uint32_t N, uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                               bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st);
 constexpr uint32_t EXPAND_MIN_M = 512;   // fewer tokens: the fused kernels read less than an expansion writes
 hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,

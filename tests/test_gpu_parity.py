@@ -699,10 +699,42 @@ def test_int4_expanded_matrix_bit_exact(oracle, N, K, row_base, with_zp):
         se = torch.zeros((N, K // 128), dtype=torch.float32, device=DEV)
         out = torch.zeros((N, K), dtype=torch.bfloat16, device=DEV)
         qb.qzo_int4_expand(_dev(qp), _dev(s, torch.bfloat16), _dev(zp) if with_zp else None, row_base, 99, 1e-3,
-                           sign, se, out)
+                           sign, se, out)     # no activation reordering
         e = sign * np.float32(1e-3)
         assert np.array_equal(_bits(se.cpu().numpy()),
                               _bits(oracle.effective_scales(s, row_base, 99, e).astype(np.float32)))
         want = (oracle.dequant_zp(qp, s, zp, 99, row_base, e, to_bf16=True) if with_zp
                 else oracle.dequant(qp, s, 99, row_base, e, to_bf16=True))
         assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
+
+
+@pytest.mark.parametrize("M,N,K", [(300, 520, 384), (64, 136, 1280)])
+def test_activation_reordering_matrix_bit_exact_and_linear(oracle, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    G = K // 128
+    qp = rng.integers(0, 256, (N, K // 2), dtype=np.uint8)
+    s = synth.bf16_exact(rng.uniform(0.002, 0.02, (N, G)).astype(np.float32))
+    zp = rng.integers(0, 16, (N, G), dtype=np.uint8)
+    g_idx = rng.permutation(np.arange(K) // 128).astype(np.int32)      # every group keeps 128 columns
+    x = synth.bf16_exact(rng.standard_normal((M, K), dtype=np.float32))
+    gd = _dev(g_idx)
+    se = torch.zeros((N, G), dtype=torch.float32, device=DEV)
+    out = torch.zeros((N, K), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_int4_expand(_dev(qp), _dev(s, torch.bfloat16), _dev(zp), 11, 31, 1e-3, -1, se, out, g_idx=gd)
+    want = oracle.dequant_zp(qp, s, zp, 31, 11, -np.float32(1e-3), to_bf16=True, g_idx=g_idx)
+    assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
+    scratch = torch.empty(qb.qzo_int4_scratch_bytes(N, K), dtype=torch.uint8, device=DEV)
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_int4_gemm_expanded(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), _dev(zp), gd, 11, 31,
+                              1e-3, -1, y, scratch)
+    ref = oracle.linear(x.astype(np.float64), oracle.dequant_zp(qp, s, zp, 31, 11, -np.float32(1e-3), g_idx=g_idx))
+    err = np.abs(y.float().cpu().numpy() - ref)
+    scale = math.sqrt(K) * 0.011 * 4.6
+    assert (err <= 2e-2 * np.abs(ref) + 2e-2 * scale).all() and err.max() <= 1e-2 * np.abs(ref).max() + 4e-3 * scale
+    # without a group index the entry point is the plain zero-point linear
+    qb.qzo_int4_gemm_expanded(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), _dev(zp), None, 11, 31,
+                              1e-3, -1, y, scratch)
+    y2 = torch.zeros_like(y)
+    qb.qzo_dequant_gemm_zp(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), _dev(zp), 11, 31, 1e-3, -1, y2)
+    if M > 64:          # the tile kernel accumulates in the same order; the few-token kernel does not
+        assert torch.equal(y, y2)
