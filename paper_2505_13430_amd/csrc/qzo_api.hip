@@ -924,7 +924,7 @@ qzo_status qzo_debug_bf16_gemm(const void* x_dev, const void* w_dev, uint32_t M,
     return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
   if (K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "K must be a positive multiple of 128");
   if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
-  if (pipe < 0 || pipe > 3) return fail(QZO_ERR_ARG, "pipe must be 0..3");
+  if (pipe < 0 || pipe > 4) return fail(QZO_ERR_ARG, "pipe must be 0..4");
   GemmArgs g = {};
   g.x = x_dev; g.w = w_dev; g.y = y_dev; g.M = M; g.N = N; g.K = K;
   QZO_HIP(launch_bf16_gemm(g, pipe, (hipStream_t)stream));

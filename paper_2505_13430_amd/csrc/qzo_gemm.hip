@@ -145,6 +145,10 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   static_assert(!ZP || QM == 0, "zero-points belong to the int4 format");
   constexpr bool W4 = QM == 0, CB = QM == 2, ROWMAP = W4 || CB;
   constexpr bool SCHED = PIPE == 1, PP = PIPE == 2;
+  // PIPE == 3 (plain bf16 weights): both operand tiles go from memory straight into the LDS
+  // (buffer loads with the lds modifier); no staging registers, no LDS store instructions
+  constexpr bool DTL = PIPE == 3;
+  static_assert(!DTL || (QM == 1 && !CE), "direct-to-LDS staging is written for the plain bf16 GEMM");
   static_assert(!CB || NWN == 4, "codebook staging is written for 512 threads");
   static_assert(!PP || (NWN == 4 && W4), "the phase schedule is written for int4 weights, 512 threads");
   constexpr int THREADS = 128 * NWN;
@@ -182,6 +186,16 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       const_cast<void*>(W4 ? a.s : a.x), 0, (int)(W4 ? (uint64_t)a.N * (K >> 7) * 2 : 16), 0x00020000);
   const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<void*>(ZP ? a.zp : a.x), 0, (int)(ZP ? (uint64_t)a.N * (K >> 7) : 16), 0x00020000);
+  // Direct-to-LDS: a wavefront's load instruction fills 1 KB of LDS in lane order (8 rows of
+  // 128 bytes), so the XOR swizzle is applied on the memory side: the lane that fills position
+  // p of row r fetches chunk p ^ swizzle(r).
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  const i32x4 rx4 = {(int)(uint32_t)(uintptr_t)a.x, (int)(uint32_t)((uintptr_t)a.x >> 32),
+                     (int)((uint64_t)a.M * K * 2), 0x00020000};
+  const i32x4 rw4 = {(int)(uint32_t)(uintptr_t)a.w, (int)(uint32_t)((uintptr_t)a.w >> 32),
+                     (int)((uint64_t)a.N * K * 2), 0x00020000};
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds +
+                            __builtin_amdgcn_readfirstlane(wave) * 1024u;
   uint32_t xo[NA], wo[NA], so = 0, gn_w4 = 0;
   const uint32_t brow = t / TPR, bpart = t % TPR;
   // LDS offsets: rows t/8 + RSTEP i share their swizzle, so chunk i is a_lds + i * RSTEP rows.
@@ -195,7 +209,8 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 #define QZO_TILE_PTRS(TM, TN)                                                                \
   do {                                                                                       \
     _Pragma("unroll") for (int i = 0; i < NA; ++i) {                                         \
-      const uint32_t row = (t >> 3) + RSTEP * i, c = t & 7u;                                 \
+      const uint32_t row = (t >> 3) + RSTEP * i;                                             \
+      const uint32_t c = DTL ? ((t & 7u) ^ ((row >> 1) & 7u)) : (t & 7u);                    \
       xo[i] = (min((TM) * BM + row, a.M - 1) * K + c * 8) * 2;                               \
       if (!ROWMAP) wo[i] = (min((TN) * BN + row, a.N - 1) * K + c * 8) * 2;                  \
     }                                                                                        \
@@ -261,6 +276,26 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       QZO_GLOAD_A(KT);                                                                       \
       QZO_GLOAD_B(KT);                                                                       \
     }                                                                                        \
+  } while (0)
+
+// Direct-to-LDS: k-tile KT of both operands into LDS stage STAGE.  M0 carries the LDS address of
+// the wavefront's 1 KB; the hardware adds 16 bytes per lane.  The compiler does not see these
+// LDS writes: every read of the stage is separated from them by an explicit vmcnt(0) and a barrier.
+#define QZO_DTL16(RSRC, LDSADDR, VOFF, SOFF)                                                 \
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"                \
+               : : "s"(LDSADDR), "v"(VOFF), "s"(RSRC), "s"(SOFF) : "memory")
+#define QZO_DTL(KT, STAGE)                                                                   \
+  do {                                                                                       \
+    const uint32_t so_ = (uint32_t)(KT) * (BK * 2);                                          \
+    _Pragma("unroll") for (int i = 0; i < NA; ++i) {                                         \
+      QZO_DTL16(rx4, lds_wave + (uint32_t)((STAGE) * TILE_BYTES + i * RSTEP * 128), xo[i], so_); \
+      QZO_DTL16(rw4, lds_wave + (uint32_t)((2 + (STAGE)) * TILE_BYTES + i * RSTEP * 128), wo[i], so_); \
+    }                                                                                        \
+  } while (0)
+#define QZO_DTL_LANDED()                                                                     \
+  do {                                                                                       \
+    __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */                                       \
+    __syncthreads();                                                                         \
   } while (0)
 
 // New perturbed scale for group G_ (every two k-tiles): s + (sigma*eps)*z as one
@@ -396,6 +431,23 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     }                                                                                        \
   } while (0)
 
+// One k-tile with direct-to-LDS staging: fragments and MFMAs as above; then, once every
+// wavefront has read the stage and the other stage's loads have landed, the stage is refilled
+// with the tile after next (NEXT_KT < 0: nothing left to load).
+#define QZO_TILE_D(STAGE, HOLD, NEXT_KT)                                                     \
+  do {                                                                                       \
+    QZO_FRAGS(0, 0, STAGE);                                                                  \
+    if (HOLD) QZO_MFMAS(1);                                                                  \
+    QZO_FRAGS(1, 1, STAGE);                                                                  \
+    QZO_MFMAS(0);                                                                            \
+    QZO_FRAGS(0, 2, STAGE);                                                                  \
+    QZO_MFMAS(1);                                                                            \
+    QZO_FRAGS(1, 3, STAGE);                                                                  \
+    QZO_MFMAS(0);                                                                            \
+    QZO_DTL_LANDED();                                                                        \
+    if ((int)(NEXT_KT) >= 0) QZO_DTL(NEXT_KT, STAGE);                                        \
+  } while (0)
+
 // Phase schedule (int4 weights).  Wavefronts w and w + 4 share a SIMD.  A k-tile is cut
 // into two halves of two k-steps; for each half a wavefront runs a memory phase and then a
 // matrix phase of sixteen MFMAs whose operands are all in registers.  Phases are separated
@@ -482,6 +534,9 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   if (PP) {
     QZO_GLOAD_A(0);
     QZO_PP_LOAD_B(0u, 0);
+  } else if (DTL) {
+    QZO_DTL(0u, 0);
+    QZO_DTL(1u, 1);
   } else {
     QZO_GLOAD(0);
   }
@@ -503,11 +558,11 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     QZO_GLOAD_A(1u);
     QZO_PP_LOAD_B(1u, 1);
     QZO_PP_LOAD_B(min(2u, last), 0);
-  } else {
+  } else if (!DTL) {
     QZO_LSTORE(0);
     QZO_GLOAD(1u);
   }
-  __syncthreads();
+  if (DTL) QZO_DTL_LANDED(); else __syncthreads();
   if (PP) {
     if (late_group) QZO_PHASE_SYNC();
     /* tile t stores tile t+1, requests activations of t+2 and weights of t+3; an even   */
@@ -519,6 +574,14 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     }
     QZO_PP_TILE(1, -1, 0u, 0u, -1, -1);
     if (!late_group) QZO_PHASE_SYNC();
+  } else if (DTL) {
+    QZO_TILE_D(0, false, nkt > 2 ? 2 : -1);
+    for (uint32_t kt = 1; kt + 1 < nkt; kt += 2) {
+      QZO_TILE_D(1, true, kt + 2 <= last ? (int)(kt + 2) : -1);
+      QZO_TILE_D(0, true, kt + 3 <= last ? (int)(kt + 3) : -1);
+    }
+    QZO_TILE_D(1, true, -1);
+    QZO_MFMAS(1);
   } else {
   QZO_TILE(0, false, 1, min(2u, last), -1);
   __syncthreads();
@@ -546,6 +609,9 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     if (PP) {
       QZO_GLOAD_A(0);
       QZO_PP_LOAD_B(0u, 0);
+    } else if (DTL) {       /* every wavefront is past the barrier that ends the last k-tile */
+      QZO_DTL(0u, 0);
+      QZO_DTL(1u, 1);
     } else {
       QZO_GLOAD(0);
     }
@@ -675,7 +741,8 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
         }
     }
     if (a.epi & EPI_SUMSQ) {
-      float* red = reinterpret_cast<float*>(lds);
+      // direct-to-LDS staging: the next tile's loads are already landing in the stages
+      float* red = reinterpret_cast<float*>(lds + (DTL ? LDS_BYTES : 0));
       ssq = wave_sum(ssq);
       __syncthreads();
       if (lane == 0) red[wave] = ssq;
@@ -724,6 +791,10 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   }   // tile loop
 #undef QZO_SWAP8
 #undef QZO_TILE
+#undef QZO_TILE_D
+#undef QZO_DTL
+#undef QZO_DTL16
+#undef QZO_DTL_LANDED
 #undef QZO_PP_TILE
 #undef QZO_PP_LOAD_A
 #undef QZO_PP_LOAD_B
@@ -809,7 +880,16 @@ hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K * 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
-  if (pipe == 2 || pipe == 3) {        // one wavefront per SIMD, 128 x 128 per wavefront
+  if (pipe == 4) {                     // both operand tiles straight from memory into the LDS
+    static bool ready4 = false;
+    if (!ready4) {
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<1, false, 4, 3>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + 1024);
+      if (e != hipSuccess) return e;
+      ready4 = true;
+    }
+    gemm_kernel<1, false, 4, 3><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES + 1024, st>>>(a, ce);
+  } else if (pipe == 2 || pipe == 3) {        // one wavefront per SIMD, 128 x 128 per wavefront
     static bool ready2 = false;
     if (!ready2) {
       hipError_t e = set_lds_attr((const void*)gemm_kernel<1, false, 2, 0>);
