@@ -377,6 +377,28 @@ def test_single_linear_full_size_sampled(oracle):
     assert losses[1] != losses[-1]
 
 
+def test_expand_then_multiply_full_size_sampled(oracle):
+    # the route the benchmark's linears take (8192 tokens per pass), at a real layer shape
+    # (8192 x 11008 x 4096): sampled outputs recomputed by the oracle, and equality with the fused kernel
+    M, N, K = 8192, synth.LINEAR_SHAPE["N"], synth.LINEAR_SHAPE["K"]
+    x, qp, s = synth.linear_case(M, N, K, seed=3)
+    xd, qd, sd = _dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16)
+    rng = np.random.default_rng(1)
+    ms = np.sort(np.concatenate([rng.choice(M, 20, replace=False), [0, 255, 256, M - 1]]))
+    ns = np.sort(np.concatenate([rng.choice(N, 60, replace=False), [0, 255, 256, N - 1]]))
+    scratch = torch.empty(qb.qzo_int4_scratch_bytes(N, K), dtype=torch.uint8, device=DEV)
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_int4_gemm_expanded(xd, qd, sd, None, None, 5, 1, 1e-3, -1, y, scratch)
+    se = oracle.effective_scales(s, 5, 1, -np.float32(1e-3))
+    ref = oracle.qlinear(x[ms], qp[ns], se[ns])
+    got = y.float().cpu().numpy().astype(np.float64)[np.ix_(ms, ns)]
+    rms = math.sqrt((ref ** 2).mean())
+    assert (np.abs(got - ref) <= 6e-3 * np.abs(ref) + 1.2e-2 * rms).all()
+    y2 = torch.zeros_like(y)
+    qb.qzo_dequant_gemm(xd, qd, sd, 5, 1, 1e-3, -1, y2)
+    assert torch.equal(y, y2)
+
+
 @pytest.mark.parametrize("rows,G,row_base", [(38400, 32, 31 * 42496), (4096, 86, 31 * 42496 + 38400),
                                              (48128, 40, 0), (5120, 108, 1877000)])
 def test_update_at_real_tensor_sizes_bit_exact(oracle, rows, G, row_base):
