@@ -283,7 +283,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 // LDS writes: every read of the stage is separated from them by an explicit vmcnt(0) and a barrier.
 #define QZO_DTL16(RSRC, LDSADDR, VOFF, SOFF)                                                 \
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"                \
-               : : "s"(LDSADDR), "v"(VOFF), "s"(RSRC), "s"(SOFF) : "memory")
+               : : "s"(LDSADDR), "v"(VOFF), "s"(RSRC), "s"(SOFF) : "memory", "m0")
 #define QZO_DTL(KT, STAGE)                                                                   \
   do {                                                                                       \
     const uint32_t so_ = (uint32_t)(KT) * (BK * 2);                                          \
