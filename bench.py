@@ -146,7 +146,7 @@ def main():
                          "scales (no cpu_baseline leg)")
     ap.add_argument("--fused", action="store_true",
                     help="int4 variants: always the fused dequantizing GEMM (default: expand-then-multiply "
-                         "from 512 tokens per pass on)")
+                         "from 6144 tokens per pass on)")
     ap.add_argument("--joint", action="store_true",
                     help="joint mode: the un-quantized parameters are perturbed and updated too (SPSA)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
@@ -218,8 +218,8 @@ def main():
     changed = float((dm.scales.view(torch.int16) != before.view(torch.int16)).float().mean().item())
     del before
 
-    # 512 tokens per pass or more: the linears are written out as perturbed bf16 matrices first
-    expanded = (B * S >= 512 and not (args.fused and not codebook)) or args.variant == "nf4"
+    # many tokens per pass: the linears are written out as perturbed bf16 matrices first
+    expanded = ((B * S >= 1024 if codebook else (B * S >= 6144 and not args.fused))) or args.variant == "nf4"
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
     g = prof["w4a16_gemm"]

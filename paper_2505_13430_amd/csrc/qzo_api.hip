@@ -39,6 +39,10 @@ struct Linear {           // one quantized linear of a layer
   uint32_t row_base;      // first noise row within the layer
 };
 
+// int4 linears: 0 = expand-then-multiply from EXPAND_MIN_M_INT4 tokens on, 1 = always the fused
+// kernel, 2 = always expand-then-multiply
+int g_int4_path = 0;
+
 struct Workspace {
   unsigned char *h, *a, *qkv, *att, *ff, *act;
   float *ce_part, *tgt, *rowloss, *losses, *skinny;
@@ -201,7 +205,8 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   // codebook variant with many tokens: the largest linear written out as bf16
   // and the NormalFloat-4 format at any token count (with its perturbed block scales, fp32)
   uint64_t ex = 0, sx = 0;
-  if (M1 >= EXPAND_MIN_M || c.quant == 3)
+  if (M1 >= (c.quant == 1 ? EXPAND_MIN_M_CODEBOOK : EXPAND_MIN_M_INT4) || c.quant == 3 ||
+      (g_int4_path == 2 && int4))
     for (int i = 0; i < 4; ++i) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
   if (ex && c.quant != 1)
     for (int i = 0; i < 4; ++i)
@@ -250,8 +255,7 @@ struct ProfScope {
   }
 };
 enum { PK_W4GEMM = 0, PK_LMHEAD = 1, PK_ATTN = 2, PK_UPDATE = 3, PK_OTHER = 4, PK_EXPAND = 5, PK_COUNT = 6 };
-// int4 linears with at least EXPAND_MIN_M tokens: 0 = expand-then-multiply, 1 = always the fused kernel
-int g_int4_path = 0;
+
 
 // The decoder forward with every quantized linear perturbed by sign*eps*z.
 // n_pass = 2 (few tokens, int4 only): both passes of a step stacked, rows [0,M1) perturbed by
@@ -912,7 +916,7 @@ qzo_status qzo_nf4_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
 }
 
 qzo_status qzo_set_int4_path(int mode) {
-  if (mode != 0 && mode != 1) return fail(QZO_ERR_ARG, "mode must be 0 (expand-then-multiply) or 1 (fused)");
+  if (mode < 0 || mode > 2) return fail(QZO_ERR_ARG, "mode must be 0 (by token count), 1 (fused) or 2 (expanded)");
   g_int4_path = mode;
   return QZO_OK;
 }
