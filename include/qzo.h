@@ -195,6 +195,9 @@ qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float 
  * a second kernel (deterministic).  Its partial sums also live in a library-owned
  * scratch, grown on demand (at most 8 * M * N floats); calls on one device share it
  * and must not overlap.  Inside a model the same path uses the caller's workspace.
+ * With more tokens but fewer than half as many 256 x 256 output tiles as the chip has compute units,
+ * the tile kernel also splits K (slices of a multiple of 256 input features, at most
+ * compute units / tiles of them) and the same second kernel adds the slices, with the same scratch.
  */
 qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
                             uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,

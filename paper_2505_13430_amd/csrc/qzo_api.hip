@@ -46,6 +46,7 @@ int g_int4_path = 0;
 struct Workspace {
   unsigned char *h, *a, *qkv, *att, *ff, *act;
   float *ce_part, *tgt, *rowloss, *losses, *skinny;
+  float* split;             // K-slice partial sums of the int4 tile kernel (too few tiles for the chip)
   unsigned char* wexp;      // one linear's expanded bf16 weights (expand-then-multiply paths)
   float* se;                // NormalFloat-4: that linear's perturbed block scales
   uint64_t total;
@@ -202,6 +203,13 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
       sk = std::max<uint64_t>(sk, skinny_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.skinny = (float*)take(sk * 4);
   if (sk == 0) w.skinny = nullptr;
+  // more tokens than that but still too few output tiles for the chip: split-K partial sums
+  uint64_t sp = 0;
+  if (M1 > SKINNY_MAX_M && int4)
+    for (int i = 0; i < 4; ++i)
+      sp = std::max<uint64_t>(sp, tile_split_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
+  w.split = (float*)take(sp * 4);
+  if (sp == 0) w.split = nullptr;
   // codebook variant with many tokens: the largest linear written out as bf16
   // and the NormalFloat-4 format at any token count (with its perturbed block scales, fp32)
   uint64_t ex = 0, sx = 0;
@@ -307,6 +315,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
       g.skinny_ws = w.skinny;
+      g.split_ws = w.split;
       if (c.quant == 3) {
         // NormalFloat-4: table lookup and scaling once per weight, then a plain bf16 GEMM
         {
@@ -315,7 +324,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
                                            (epi & EPI_SWIGLU) != 0, w.se, w.wexp, st);
           if (e != hipSuccess) return e;
         }
-        g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr;
+        g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, 1, st);
       }
@@ -327,7 +336,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
                                             eps_signed, (epi & EPI_SWIGLU) != 0, w.se, w.wexp, st);
           if (e != hipSuccess) return e;
         }
-        g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr;
+        g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, 1, st);
       }
@@ -709,9 +718,10 @@ static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void*
   g.seed_lo = (uint32_t)seed; g.seed_hi = (uint32_t)(seed >> 32);
   g.eps_signed = sign > 0 ? eps : -eps;
   const bool skinny = M <= SKINNY_MAX_M;
-  const uint32_t tiles = skinny ? skinny_reduce_blocks(M, N, 0) : ((M + 255) / 256) * ((N + 255) / 256);
-  if (skinny) {     // library-owned scratch for the K-slice partial sums, grown on demand
-    const uint64_t need = skinny_ws_floats(M, N, K);
+  const bool split = !skinny && tile_ksplit(M, N, K, nullptr) > 1;     // too few tiles for the chip
+  const uint32_t tiles = (skinny || split) ? skinny_reduce_blocks(M, N, 0) : ((M + 255) / 256) * ((N + 255) / 256);
+  if (skinny || split) {     // library-owned scratch for the K-slice partial sums, grown on demand
+    const uint64_t need = skinny ? skinny_ws_floats(M, N, K) : tile_split_ws_floats(M, N, K);
     if (g_skinny_n < need) {
       if (g_skinny) (void)hipFree(g_skinny);
       g_skinny = nullptr;
@@ -719,7 +729,7 @@ static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void*
       QZO_HIP(hipMalloc((void**)&g_skinny, (size_t)need * sizeof(float)));
       g_skinny_n = need;
     }
-    g.skinny_ws = g_skinny;
+    if (skinny) g.skinny_ws = g_skinny; else g.split_ws = g_skinny;
   }
   if (sumsq_dev) {
     if (g_partials_n < tiles) {

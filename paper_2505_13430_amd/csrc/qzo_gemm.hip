@@ -43,6 +43,24 @@ uint32_t gemm_workgroups(uint32_t M, uint32_t N) {
   return min(((tiles + 7) / 8) * 8, n_cu);
 }
 
+// Split-K of the int4 tile kernel: with fewer than half as many output tiles as compute units the K
+// dimension is cut into slices of a multiple of 4 k-tiles (256 input features: whole groups, and an
+// even first group so the noise pairs line up), enough of them to give every compute unit a slice.
+uint32_t tile_ksplit(uint32_t M, uint32_t N, uint32_t K, uint32_t* kt_per) {
+  const uint32_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN), nkt = K / BK;
+  const uint32_t cus = gemm_workgroups(1u << 20, 1u << 20);            // compute units
+  uint32_t ks = tiles ? cus / tiles : 1;
+  ks = min(ks, nkt / 4u);
+  if (ks < 2) { if (kt_per) *kt_per = nkt; return 1; }
+  const uint32_t per = ((nkt + ks - 1) / ks + 3u) & ~3u;
+  if (kt_per) *kt_per = per;
+  return (nkt + per - 1) / per;
+}
+uint64_t tile_split_ws_floats(uint32_t M, uint32_t N, uint32_t K) {
+  const uint32_t ks = tile_ksplit(M, N, K, nullptr);
+  return ks > 1 ? (uint64_t)ks * M * N : 0;
+}
+
 // Persistent workgroups: the grid is one workgroup per compute unit (or fewer when
 // there are fewer tiles) and every workgroup walks a list of output tiles.
 // Hardware deals consecutive workgroup ids to the eight XCDs in turn; each XCD
@@ -55,10 +73,12 @@ constexpr uint32_t WALK_M = 4;
 struct TileWalk {
   uint32_t tiles_m, tiles_n, total, per, xcd, slot, stride;
 };
-__device__ __forceinline__ TileWalk tile_walk_init(uint32_t M, uint32_t N) {
+// With K slices (split-K) the walk runs over feature-tiles x slices: entry tn of the walk is feature
+// tile tn % real_tiles_n, slice tn / real_tiles_n.
+__device__ __forceinline__ TileWalk tile_walk_init(uint32_t M, uint32_t N, uint32_t ksplit = 1) {
   TileWalk w;
   w.tiles_m = (M + BM - 1) / BM;
-  w.tiles_n = (N + BN - 1) / BN;
+  w.tiles_n = ((N + BN - 1) / BN) * ksplit;
   w.total = w.tiles_m * w.tiles_n;
   w.per = (w.total + 7) >> 3;
   w.xcd = blockIdx.x & 7u;
@@ -159,9 +179,15 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   constexpr int NBQ = 2 / TPR;                // W4: 16-byte loads (32 nibbles) per thread
   constexpr int NBC = 4 * NBQ;                // W4: bf16 chunks written per thread
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  TileWalk walk = tile_walk_init(a.M, a.N);
-  uint32_t tile_m, tile_n;
+  // Split-K (int4 only; a.ksplit > 1): a workgroup's unit of work is one K slice of an output tile,
+  // a.kt_per k-tiles (a multiple of 4, so slices start on an even group) from k-tile kt0 on; its
+  // fp32 accumulators go to a.split_ws[slice][M][N] and a second kernel adds the slices.
+  const uint32_t ksplit = W4 ? a.ksplit : 1u;
+  const uint32_t real_tiles_n = (a.N + BN - 1) / BN;
+  TileWalk walk = tile_walk_init(a.M, a.N, ksplit);
+  uint32_t tile_m, tile_n, kslice = 0, kt0 = 0;
   if (!tile_walk_get(walk, tile_m, tile_n)) return;
+  if (W4 && ksplit > 1) { kslice = tile_n / real_tiles_n; tile_n -= kslice * real_tiles_n; kt0 = kslice * a.kt_per; }
   const uint32_t tiles_m = walk.tiles_m;
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t wm = wave / NWN, wn = wave % NWN;
@@ -222,6 +248,11 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
                   : min((TN) * BN + brow, a.N - 1);                                          \
       wo[0] = W4 ? gn_w4 * (K >> 1) + bpart * 16 : gn_w4 * (K >> 2) + bpart * 8;             \
       so = gn_w4 * (K >> 7) * 2;                                                             \
+    }                                                                                        \
+    if (W4 && kt0) { /* this slice's first k-tile: 128 B of activations, 32 B of nibbles, half a group */ \
+      _Pragma("unroll") for (int i = 0; i < NA; ++i) xo[i] += kt0 * (BK * 2);                \
+      wo[0] += kt0 * (BK / 2);                                                               \
+      so += (kt0 >> 1) * 2;                                                                  \
     }                                                                                        \
   } while (0)
   QZO_TILE_PTRS(tile_m, tile_n);
@@ -306,14 +337,14 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 // would make the wavefront wait for every operand load issued before it.
 #define QZO_SCALE_PREFETCH(G_)                                                               \
   do {                                                                                       \
-    const uint32_t gp_ = min((uint32_t)(G_), (K >> 7) - 1u);                                 \
+    const uint32_t gp_ = min((uint32_t)(G_), (nkt >> 1) - 1u);                               \
     s_next = (bf16_t)__builtin_amdgcn_raw_buffer_load_b16(rs, (int)so, (int)(gp_ * 2u), 0);  \
     if (ZP) z_next = __builtin_amdgcn_raw_buffer_load_b8(rz, (int)(so >> 1), (int)gp_, 0);   \
   } while (0)
 #define QZO_NEW_GROUP(G_)                                                                    \
   do {                                                                                       \
-    const uint32_t g_ = (G_);                                                                \
-    if ((g_ & 7u) == 0u) {                                                                   \
+    const uint32_t g_ = (G_) + (kt0 >> 1);      /* group index within the row */             \
+    if ((g_ & 7u) == 0u || (G_) == 0u) {        /* a slice may start inside a counter */     \
       const u32x4_t pw_ = philox4x32_10(a.row_base + gn_w4, g_ >> 3, 0u, 0u, a.seed_lo, a.seed_hi); \
       zw[0] = pw_.x; zw[1] = pw_.y; zw[2] = pw_.z; zw[3] = pw_.w;                            \
     }                                                                                        \
@@ -529,7 +560,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // K is a multiple of 128, so the number of k-tiles is even.  Tile kt lives in
   // LDS stage kt & 1; during tile kt the registers loaded one tile earlier (tile
   // kt+1) go to the other stage and tile kt+2 is requested from memory.
-  const uint32_t nkt = K / BK, last = nkt - 1;
+  uint32_t nkt = (W4 && ksplit > 1) ? min(a.kt_per, K / BK - kt0) : K / BK, last = nkt - 1;
   if (CB) QZO_CODES(0u);
   if (PP) {
     QZO_GLOAD_A(0);
@@ -600,10 +631,17 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // written, and the stores are not waited for: the epilogue's memory traffic
   // overlaps the next tile's main loop.
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
-  const uint32_t done_m = tile_m, done_n = tile_n;
+  const uint32_t done_m = tile_m, done_n = tile_n, done_slice = kslice;
   walk.slot += walk.stride;
   const bool more = tile_walk_get(walk, tile_m, tile_n);
   if (more) {
+    if (W4 && ksplit > 1) {
+      kslice = tile_n / real_tiles_n;
+      tile_n -= kslice * real_tiles_n;
+      kt0 = kslice * a.kt_per;
+      nkt = min(a.kt_per, K / BK - kt0);
+      last = nkt - 1;
+    }
     QZO_TILE_PTRS(tile_m, tile_n);
     if (CB) QZO_CODES(0u);
     if (PP) {
@@ -647,7 +685,31 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       (HI)[c_] = __uint_as_float(r_[1]);                                                     \
     }                                                                                        \
   } while (0)
-  if (!CE && TJ == 2 && (a.epi & EPI_SWIGLU)) {
+  if (W4 && ksplit > 1) {
+    // split-K: this slice's fp32 sums, [slice][M][N]; the epilogue proper runs in the reduction
+    float* part = a.split_ws + (uint64_t)done_slice * a.M * a.N;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t m = m0 + wm * 128 + i * 32 + frow;
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int bp = 0; bp < 2; ++bp) {
+          float v[2][4];
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) v[h][c] = acc[i][j][4 * (2 * bp + h) + c];
+          QZO_SWAP8(v[0], v[1]);
+          const uint32_t n = n0 + wn * (32 * TJ) + j * 32 + (2u * bp + fhalf) * 8u;
+          if (m < a.M && n < a.N) {
+            float4* dst = reinterpret_cast<float4*>(part + (uint64_t)m * a.N + n);
+            dst[0] = make_float4(v[0][0], v[0][1], v[0][2], v[0][3]);
+            dst[1] = make_float4(v[1][0], v[1][1], v[1][2], v[1][3]);
+          }
+        }
+    }
+  } else if (!CE && TJ == 2 && (a.epi & EPI_SWIGLU)) {
     // y[m, f] = silu(gate) * up, f = 128 tile_n + 32 wn + 8 b + 4 (lane/32) + c; y is [M, N/2]
     bf16_t* y = (bf16_t*)a.y;
     const uint32_t F = a.N >> 1;
@@ -841,13 +903,19 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
+  GemmArgs g = a;
+  g.ksplit = 1;
+  g.kt_per = a.K / BK;
+  if (a.split_ws) g.ksplit = tile_ksplit(a.M, a.N, a.K, &g.kt_per);
+  if (g.ksplit > 1) g.epi = 0;       // natural row order, fp32 partial sums; the reduction applies a.epi
+  const uint32_t wgs = gemm_workgroups(a.M, ((a.N + BN - 1) / BN) * g.ksplit * BN);
   if (a.zp)
-    gemm_kernel<0, false, W4_NWN, W4_PIPE, true>
-        <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
+    gemm_kernel<0, false, W4_NWN, W4_PIPE, true><<<wgs, 128 * W4_NWN, LDS_BYTES, st>>>(g, ce);
   else
-    gemm_kernel<0, false, W4_NWN, W4_PIPE>
-        <<<gemm_workgroups(a.M, a.N), 128 * W4_NWN, LDS_BYTES, st>>>(a, ce);
-  return hipGetLastError();
+    gemm_kernel<0, false, W4_NWN, W4_PIPE><<<wgs, 128 * W4_NWN, LDS_BYTES, st>>>(g, ce);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || g.ksplit == 1) return e;
+  return launch_partial_reduce(a, a.split_ws, g.ksplit, st);
 }
 
 hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st) {

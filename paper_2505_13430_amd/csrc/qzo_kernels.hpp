@@ -43,6 +43,8 @@ struct GemmArgs {
   void* y;              // bf16 [M,N]
   float* partials;      // EPI_SUMSQ: one float per workgroup
   float* skinny_ws;     // fp32 scratch of skinny_ws_floats(rows, N, K) floats: enables the few-token path (M <= 64)
+  float* split_ws;      // fp32 scratch of tile_split_ws_floats(M, N, K) floats: enables split-K of the int4 tile kernel
+  uint32_t ksplit, kt_per;   // set by the launcher: K slices and k-tiles per slice
   uint32_t dual;        // few-token path only: x, y, resid hold 2 M rows; rows [0,M) use +eps_signed, [M,2M) -eps_signed
   uint32_t M, N, K;
   uint32_t row_base;
@@ -58,6 +60,12 @@ uint32_t skinny_ksplit(uint32_t N, uint32_t K);
 uint64_t skinny_ws_floats(uint32_t M, uint32_t N, uint32_t K);
 uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi);   // EPI_SUMSQ partial count
 hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st);
+// Adds K-slice partial sums part[slice][M][N] in slice order and applies a's epilogue.
+hipError_t launch_partial_reduce(const GemmArgs& a, const float* part, uint32_t ksplit, hipStream_t st);
+// Split-K of the int4 tile kernel when an M x N output has too few 256 x 256 tiles for the chip:
+// number of K slices (1: none) and k-tiles per slice.
+uint32_t tile_ksplit(uint32_t M, uint32_t N, uint32_t K, uint32_t* kt_per);
+uint64_t tile_split_ws_floats(uint32_t M, uint32_t N, uint32_t K);
 // w = uint16 codes [N,K/8]; cb and s as above; N % 8 == 0, K % 128 == 0.
 hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st);
 hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st);

@@ -321,4 +321,10 @@ hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st) {
   return hipGetLastError();
 }
 
+hipError_t launch_partial_reduce(const GemmArgs& a, const float* part, uint32_t ksplit, hipStream_t st) {
+  if (a.M == 0 || a.N == 0) return hipSuccess;
+  skinny_reduce_kernel<<<skinny_reduce_blocks(a.M, a.N, a.epi), 256, 0, st>>>(a, part, ksplit);
+  return hipGetLastError();
+}
+
 }  // namespace qzo
