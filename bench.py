@@ -219,7 +219,7 @@ def main():
     del before
 
     # many tokens per pass: the linears are written out as perturbed bf16 matrices first
-    expanded = ((B * S >= 1024 if codebook else (B * S >= 6144 and not args.fused))) or args.variant == "nf4"
+    expanded = codebook or args.variant == "nf4" or (B * S >= 6144 and not args.fused)
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
     g = prof["w4a16_gemm"]

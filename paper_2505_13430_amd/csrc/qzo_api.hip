@@ -205,7 +205,7 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   if (sk == 0) w.skinny = nullptr;
   // more tokens than that but still too few output tiles for the chip: split-K partial sums
   uint64_t sp = 0;
-  if (M1 > SKINNY_MAX_M && int4)
+  if ((M1 > SKINNY_MAX_M && int4) || c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK))
     for (int i = 0; i < 4; ++i)
       sp = std::max<uint64_t>(sp, tile_split_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.split = (float*)take(sp * 4);
@@ -318,13 +318,14 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.split_ws = w.split;
       if (c.quant == 3) {
         // NormalFloat-4: table lookup and scaling once per weight, then a plain bf16 GEMM
+        const bool split = w.split && tile_ksplit(g.M, g.N, g.K, nullptr) > 1;
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
           hipError_t e = launch_expand_nf4(g.w, g.s, g.N, g.K, g.row_base, seed_lo, seed_hi, eps_signed,
-                                           (epi & EPI_SWIGLU) != 0, w.se, w.wexp, st);
+                                           (epi & EPI_SWIGLU) != 0 && !split, w.se, w.wexp, st);
           if (e != hipSuccess) return e;
         }
-        g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;
+        g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, 1, st);
       }
@@ -354,13 +355,15 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
       if (w.wexp) {
         // many tokens: reconstruct the perturbed matrix once, then a plain bf16 GEMM
+        // (rows in natural order when the GEMM will split K: its reduction applies SwiGLU)
+        const bool split = w.split && tile_ksplit(g.M, g.N, g.K, nullptr) > 1;
         {
           ProfScope pe(PK_EXPAND, 2.25 * (double)g.N * g.K, st);
           hipError_t e = launch_expand_codebook(codes, cb, g.s, g.N, g.K, g.row_base, seed_lo, seed_hi,
-                                                eps_signed, (epi & EPI_SWIGLU) != 0, w.wexp, st);
+                                                eps_signed, (epi & EPI_SWIGLU) != 0 && !split, w.wexp, st);
           if (e != hipSuccess) return e;
         }
-        g.w = w.wexp; g.cb = nullptr; g.s = nullptr;
+        g.w = w.wexp; g.cb = nullptr; g.s = nullptr; g.split_ws = split ? w.split : nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, 1, st);
       }

@@ -179,15 +179,16 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   constexpr int NBQ = 2 / TPR;                // W4: 16-byte loads (32 nibbles) per thread
   constexpr int NBC = 4 * NBQ;                // W4: bf16 chunks written per thread
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  // Split-K (int4 only; a.ksplit > 1): a workgroup's unit of work is one K slice of an output tile,
+  // Split-K (int4 and plain bf16 weights; a.ksplit > 1): a workgroup's unit of work is one K slice of an output tile,
   // a.kt_per k-tiles (a multiple of 4, so slices start on an even group) from k-tile kt0 on; its
   // fp32 accumulators go to a.split_ws[slice][M][N] and a second kernel adds the slices.
-  const uint32_t ksplit = W4 ? a.ksplit : 1u;
+  constexpr bool SPLITK = (W4 || QM == 1) && !CE;
+  const uint32_t ksplit = SPLITK ? max(a.ksplit, 1u) : 1u;
   const uint32_t real_tiles_n = (a.N + BN - 1) / BN;
   TileWalk walk = tile_walk_init(a.M, a.N, ksplit);
   uint32_t tile_m, tile_n, kslice = 0, kt0 = 0;
   if (!tile_walk_get(walk, tile_m, tile_n)) return;
-  if (W4 && ksplit > 1) { kslice = tile_n / real_tiles_n; tile_n -= kslice * real_tiles_n; kt0 = kslice * a.kt_per; }
+  if (SPLITK && ksplit > 1) { kslice = tile_n / real_tiles_n; tile_n -= kslice * real_tiles_n; kt0 = kslice * a.kt_per; }
   const uint32_t tiles_m = walk.tiles_m;
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t wm = wave / NWN, wn = wave % NWN;
@@ -249,10 +250,14 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       wo[0] = W4 ? gn_w4 * (K >> 1) + bpart * 16 : gn_w4 * (K >> 2) + bpart * 8;             \
       so = gn_w4 * (K >> 7) * 2;                                                             \
     }                                                                                        \
-    if (W4 && kt0) { /* this slice's first k-tile: 128 B of activations, 32 B of nibbles, half a group */ \
+    if (SPLITK && kt0) { /* this slice's first k-tile: 128 B of activations, 32 B of nibbles, half a group */ \
       _Pragma("unroll") for (int i = 0; i < NA; ++i) xo[i] += kt0 * (BK * 2);                \
-      wo[0] += kt0 * (BK / 2);                                                               \
-      so += (kt0 >> 1) * 2;                                                                  \
+      if (W4) {                                                                              \
+        wo[0] += kt0 * (BK / 2);                                                             \
+        so += (kt0 >> 1) * 2;                                                                \
+      } else {                                                                               \
+        _Pragma("unroll") for (int i = 0; i < NA; ++i) wo[i] += kt0 * (BK * 2);              \
+      }                                                                                      \
     }                                                                                        \
   } while (0)
   QZO_TILE_PTRS(tile_m, tile_n);
@@ -560,7 +565,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // K is a multiple of 128, so the number of k-tiles is even.  Tile kt lives in
   // LDS stage kt & 1; during tile kt the registers loaded one tile earlier (tile
   // kt+1) go to the other stage and tile kt+2 is requested from memory.
-  uint32_t nkt = (W4 && ksplit > 1) ? min(a.kt_per, K / BK - kt0) : K / BK, last = nkt - 1;
+  uint32_t nkt = (SPLITK && ksplit > 1) ? min(a.kt_per, K / BK - kt0) : K / BK, last = nkt - 1;
   if (CB) QZO_CODES(0u);
   if (PP) {
     QZO_GLOAD_A(0);
@@ -635,7 +640,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   walk.slot += walk.stride;
   const bool more = tile_walk_get(walk, tile_m, tile_n);
   if (more) {
-    if (W4 && ksplit > 1) {
+    if (SPLITK && ksplit > 1) {
       kslice = tile_n / real_tiles_n;
       tile_n -= kslice * real_tiles_n;
       kt0 = kslice * a.kt_per;
@@ -685,7 +690,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       (HI)[c_] = __uint_as_float(r_[1]);                                                     \
     }                                                                                        \
   } while (0)
-  if (W4 && ksplit > 1) {
+  if (SPLITK && ksplit > 1) {
     // split-K: this slice's fp32 sums, [slice][M][N]; the epilogue proper runs in the reduction
     float* part = a.split_ws + (uint64_t)done_slice * a.M * a.N;
 #pragma unroll
@@ -948,6 +953,18 @@ hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K * 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
+  if (pipe == 1 && a.split_ws) {       // the model's route: split K when the output has too few tiles
+    GemmArgs g = a;
+    g.ksplit = tile_ksplit(a.M, a.N, a.K, &g.kt_per);
+    if (g.ksplit > 1) {
+      g.epi = 0;
+      gemm_kernel<1, false, 4, 1><<<gemm_workgroups(a.M, ((a.N + BN - 1) / BN) * g.ksplit * BN), 512,
+                                    LDS_BYTES, st>>>(g, ce);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      return launch_partial_reduce(a, a.split_ws, g.ksplit, st);
+    }
+  }
   if (pipe == 4) {                     // both operand tiles straight from memory into the LDS
     static bool ready4 = false;
     if (!ready4) {

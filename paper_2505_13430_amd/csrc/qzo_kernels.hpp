@@ -83,12 +83,12 @@ hipError_t launch_expand_nf4(const void* q, const void* s_bf16, uint32_t N, uint
 hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, const int32_t* g_idx,
                               uint32_t N, uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                               bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st);
-// Tokens per pass from which a linear is expanded first.  The expansion costs a fixed 2.3-2.5 bytes
-// per weight, the fused kernels lose a fixed share of a time that grows with the tokens: measured
-// break-even near 6000 tokens for int4 (fused kernel 8 % slower than the plain GEMM) and under 1000
-// for the codebook format (fused kernel 45 % slower).
+// Tokens per pass from which an int4 linear is expanded first.  The expansion costs a fixed 2.5 bytes
+// per weight, the fused kernel loses a fixed share (about 8 %) of a time that grows with the tokens:
+// measured break-even near 6000 tokens.  The codebook format is always expanded inside a model: its
+// fused kernel is 45 % slower than the plain GEMM and cannot split K.
 constexpr uint32_t EXPAND_MIN_M_INT4 = 6144;
-constexpr uint32_t EXPAND_MIN_M_CODEBOOK = 1024;
+constexpr uint32_t EXPAND_MIN_M_CODEBOOK = 1;
 hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,
                                  uint32_t seed_hi, float eta, float d_clipped,
                                  const qzo_step_result* res, hipStream_t st);

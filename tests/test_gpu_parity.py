@@ -551,10 +551,10 @@ def test_codebook_linear_matches_oracle(oracle, M, N, K):
 @pytest.mark.parametrize("shape,eta", [
     (dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48, batch=3, seq=40), 1e-1),
     # Llama-2-13B widths, one layer, short batch (a smaller step: d carries the losses' noise x 500)
-    # 1056 tokens: every linear is first written out as a perturbed bf16 matrix (expand-then-multiply)
-    (dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48, batch=22, seq=48), 1e-1),
+    # more tokens (several token tiles)
+    (dict(arch="llama", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=48, batch=12, seq=48), 1e-1),
     (dict(synth.SHAPES["llama-2-13b"], n_layers=1, batch=1, seq=16, max_seq=32), 1e-5)],
-    ids=["tiny", "tiny-1056-tokens", "13b-width"])
+    ids=["tiny", "tiny-576-tokens", "13b-width"])
 def test_codebook_model_step(oracle, shape, eta):
     table = synth.codebook_tensor_table(shape, 31)
     om = oracle.build_codebook_model(shape, table)
