@@ -373,7 +373,12 @@ qzo_status qzo_debug_forward(qzo_model* m, const int32_t* tokens_dev, uint32_t b
  * W4A16 GEMM, 1 = lm_head GEMM + cross-entropy partials, 2 = attention,
  * 3 = scale update, 4 = embedding and the joint mode's kernels, 5 = weight expansion (bytes:
  * packed weights in + bf16 out).  Host pointers.  Not thread-safe.
+ * qzo_profile_stride(n): from the next qzo_profile_begin on only every n-th launch of each class is
+ * bracketed (the first, the n+1-th, ...), which keeps the cost of the events (a few microseconds of
+ * GPU time per bracketed launch) out of a timed run; launches, time and work then cover the bracketed
+ * launches only.  A layer's four linears have different shapes: use a stride that is odd.  Default 1.
  */
+qzo_status qzo_profile_stride(uint32_t stride);
 qzo_status qzo_profile_begin(uint32_t max_records);
 qzo_status qzo_profile_collect(uint32_t kind, double* total_ms, uint64_t* launches, double* work);
 

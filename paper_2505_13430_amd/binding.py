@@ -26,7 +26,7 @@ EXPORTS = [
     "qzo_model_dense_count", "qzo_model_enable_joint", "qzo_step_joint",
     "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm", "qzo_set_int4_path", "qzo_int4_expand", "qzo_int4_scratch_bytes", "qzo_int4_gemm_expanded",
     "qzo_apply_update", "qzo_dequant_gemm_zp", "qzo_repack_kmajor", "qzo_debug_dequant_zp", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
-    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_debug_bf16_gemm", "qzo_profile_begin", "qzo_profile_collect",
+    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_debug_bf16_gemm", "qzo_profile_begin", "qzo_profile_collect", "qzo_profile_stride",
     "qzo_last_error",
 ]
 
@@ -295,6 +295,10 @@ def qzo_debug_forward(model, tokens, seed, eps, sign, workspace, loss_out, hidde
 
 
 PROFILE_KINDS = {"w4a16_gemm": 0, "lmhead_ce": 1, "attention": 2, "scale_update": 3, "embed": 4, "expand": 5}
+
+
+def qzo_profile_stride(stride: int):
+    _check(lib().qzo_profile_stride(C.c_uint32(stride)))
 
 
 def qzo_debug_mfma_rate(iters: int, random_operands: bool, sink, stream=None) -> int:

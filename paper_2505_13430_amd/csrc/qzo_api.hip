@@ -246,6 +246,8 @@ struct Profiler {
   bool on = false;
   std::vector<ProfRec> pool;
   size_t used = 0;
+  uint32_t stride = 1;          // every stride-th launch of a class is bracketed
+  uint32_t seen[8] = {};
 } g_prof;
 
 struct ProfScope {
@@ -253,6 +255,7 @@ struct ProfScope {
   hipStream_t st;
   ProfScope(uint32_t kind, double work, hipStream_t s) : st(s) {
     if (!g_prof.on || g_prof.used >= g_prof.pool.size()) return;
+    if (g_prof.seen[kind & 7u]++ % g_prof.stride) return;
     r = &g_prof.pool[g_prof.used++];
     r->kind = kind;
     r->work = work;
@@ -975,7 +978,14 @@ qzo_status qzo_profile_begin(uint32_t max_records) {
     g_prof.pool.push_back(r);
   }
   g_prof.used = 0;
+  for (uint32_t& c : g_prof.seen) c = 0;
   g_prof.on = true;
+  return QZO_OK;
+}
+
+qzo_status qzo_profile_stride(uint32_t stride) {
+  if (stride == 0) return fail(QZO_ERR_ARG, "stride must be >= 1");
+  g_prof.stride = stride;
   return QZO_OK;
 }
 

@@ -777,3 +777,40 @@ def test_activation_reordering_matrix_bit_exact_and_linear(oracle, M, N, K):
     qb.qzo_dequant_gemm_zp(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), _dev(zp), 11, 31, 1e-3, -1, y2)
     if M > 64:          # the tile kernel accumulates in the same order; the few-token kernel does not
         assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("name", ["tiny", "few_llama"])
+def test_step_replays_from_a_captured_graph(oracle, name):
+    """qzo_step allocates nothing and never synchronises, so after one eager call (which sets the
+    kernels' LDS attributes) it can be captured into a HIP graph.  Every replay, with eager work and
+    synchronisations in between, gives the eager step's scalars; a replay with eta > 0 leaves the
+    eager step's scales."""
+    shape, _ = _case(name)
+    om, dm = _models(oracle, shape, 1234)
+    tokd = _dev(synth.tokens(shape, 5678))
+    start = dm.scales.clone()
+    eager0 = qb.read_step_result(dm.step(tokd, 7, 1e-3, 0.0, 100.0))          # eta = 0: scales untouched
+    dm.step(tokd, 7, 1e-3, 1e-5, 100.0)
+    torch.cuda.synchronize()
+    eager_scales = dm.scales.clone()
+    dm.scales.copy_(start)
+    side = torch.cuda.Stream()
+    graphs = {}
+    for eta in (0.0, 1e-5):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            dm.step(tokd, 7, 1e-3, eta, 100.0)
+        graphs[eta] = g
+    for rep in range(3):
+        graphs[0.0].replay()
+        torch.cuda.synchronize()
+        got = qb.read_step_result(dm.result)
+        assert got == eager0, (rep, got, eager0)
+        assert torch.equal(dm.scales, start)
+        # eager work between the replays
+        again = qb.read_step_result(dm.step(tokd, 7, 1e-3, 0.0, 100.0))
+        assert again == eager0
+    graphs[1e-5].replay()
+    torch.cuda.synchronize()
+    assert torch.equal(dm.scales, eager_scales) and not torch.equal(dm.scales, start)
+    dm.close()
