@@ -147,7 +147,9 @@ def main():
                          "scales (no cpu_baseline leg)")
     ap.add_argument("--fused", action="store_true",
                     help="int4 variants: always the fused dequantizing GEMM (default: expand-then-multiply "
-                         "from 6144 tokens per pass on)")
+                         "for linears with enough tokens per pass, about 3500-5600 at the 7B widths)")
+    ap.add_argument("--expanded", action="store_true",
+                    help="int4 variants: always expand-then-multiply, whatever the token count")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (every replay repeats the "
                          "same seed; no per-kernel events, so the roofline fields are null)")
@@ -193,7 +195,7 @@ def main():
     tok = torch.from_numpy(synth.tokens(shape, 5678)).cuda()
     eps, eta, clip = 1e-3, 1e-7, 100.0
     stream = torch.cuda.current_stream()
-    qb.qzo_set_int4_path(1 if args.fused else 0)
+    qb.qzo_set_int4_path(1 if args.fused else (2 if args.expanded else 0))
     if args.joint:
         dm.enable_joint()
         plain_step = dm.step_joint
@@ -249,8 +251,8 @@ def main():
     changed = float((dm.scales.view(torch.int16) != before.view(torch.int16)).float().mean().item())
     del before
 
-    # many tokens per pass: the linears are written out as perturbed bf16 matrices first
-    expanded = codebook or args.variant == "nf4" or (B * S >= 6144 and not args.fused)
+    # whether the linears were written out as perturbed bf16 matrices first (most of them, when mixed)
+    expanded = prof["expand"]["launches"] * 2 > prof["w4a16_gemm"]["launches"]
     ms_per_step = dt / args.steps * 1e3
     steps_per_s = args.steps / dt
     g = prof["w4a16_gemm"]

@@ -328,11 +328,11 @@ qzo_status qzo_int4_gemm_expanded(const void* x_dev, const void* q_dev, const vo
                                   float eps, int sign, void* y_dev, void* scratch_dev,
                                   uint64_t scratch_bytes, void* stream);
 
-/* How the model's int4 linears (quant 0 and 2) run.  mode 0 (default): by token count; with at least
- * 6144 tokens in a pass the perturbed weights of a linear are first written out as a bf16 matrix in the
- * workspace (same bits as the fused kernel's weight tile) and multiplied by the plain bf16 GEMM, with
- * fewer the fused dequantizing GEMM runs (below the break-even an expansion costs more than the fused
- * kernel's extra work).  mode 1: always the fused kernel.  mode 2: always expand-then-multiply.
+/* How the model's int4 linears (quant 0 and 2) run.  mode 0 (default): by size; a linear [N,K] with at
+ * least 3022 + 4.35e10 / (N K) tokens in a pass (3900 for 12288 x 4096) has its perturbed weights first
+ * written out as a bf16 matrix in the workspace (same bits as the fused kernel's weight tile) and multiplied
+ * by the plain bf16 GEMM, with fewer the fused dequantizing GEMM runs (below the break-even an expansion
+ * costs more than the fused kernel's extra work).  mode 1: always the fused kernel.  mode 2: always expand-then-multiply.
  * Process-wide, not thread-safe; call it before qzo_workspace_bytes (the workspace layout depends on it). */
 qzo_status qzo_set_int4_path(int mode);
 

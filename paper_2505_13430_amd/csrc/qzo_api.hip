@@ -39,7 +39,7 @@ struct Linear {           // one quantized linear of a layer
   uint32_t row_base;      // first noise row within the layer
 };
 
-// int4 linears: 0 = expand-then-multiply from EXPAND_MIN_M_INT4 tokens on, 1 = always the fused
+// int4 linears: 0 = expand-then-multiply from expand_min_m_int4(N, K) tokens on, 1 = always the fused
 // kernel, 2 = always expand-then-multiply
 int g_int4_path = 0;
 
@@ -213,9 +213,11 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   // codebook variant with many tokens: the largest linear written out as bf16
   // and the NormalFloat-4 format at any token count (with its perturbed block scales, fp32)
   uint64_t ex = 0, sx = 0;
-  if (M1 >= (c.quant == 1 ? EXPAND_MIN_M_CODEBOOK : EXPAND_MIN_M_INT4) || c.quant == 3 ||
-      (g_int4_path == 2 && int4))
-    for (int i = 0; i < 4; ++i) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
+  for (int i = 0; i < 4; ++i) {
+    const bool expanded = c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK) ||
+                          (int4 && (g_int4_path == 2 || M1 >= expand_min_m_int4(m->lin[i].N, m->lin[i].K)));
+    if (expanded) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
+  }
   if (ex && c.quant != 1)
     for (int i = 0; i < 4; ++i)
       sx = std::max<uint64_t>(sx, (uint64_t)m->lin[i].N * (m->lin[i].K / c.group_size) * 4);
@@ -332,7 +334,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, 1, st);
       }
-      if (w.wexp && g_int4_path != 1 && n_pass == 1) {
+      if (w.wexp && g_int4_path != 1 && n_pass == 1 &&
+          (g_int4_path == 2 || M >= expand_min_m_int4(g.N, g.K))) {
         // many tokens: write the perturbed matrix out once, then a plain bf16 GEMM
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);

@@ -235,7 +235,7 @@ def _case(name):
 
 
 # 576 tokens with qzo_set_int4_path(2): the int4 linears run expand-then-multiply (by default only
-# from 6144 tokens on, more than the oracle handles in a test)
+# from several thousand tokens on, more than the oracle handles in a test)
 MANY = {"many_llama": dict(synth.SHAPES["tiny"], batch=9, seq=64),
         "many_opt": dict(synth.SHAPES["tiny_opt"], batch=9, seq=64)}
 FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tokens: one token tile
