@@ -22,11 +22,15 @@ QZO_ERR_NONFINITE, QZO_ERR_HIP, QZO_ERR_UNSUPPORTED = -5, -6, -7
 
 EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
-    "qzo_forward_loss", "qzo_step", "qzo_model_apply_update", "qzo_dequant_gemm",
+    "qzo_forward_loss", "qzo_step", "qzo_model_apply_update",
     "qzo_model_dense_count", "qzo_model_enable_joint", "qzo_step_joint",
-    "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm", "qzo_set_int4_path", "qzo_int4_expand", "qzo_int4_scratch_bytes", "qzo_int4_gemm_expanded",
-    "qzo_apply_update", "qzo_dequant_gemm_zp", "qzo_repack_kmajor", "qzo_debug_dequant_zp", "qzo_codebook_gemm", "qzo_apply_update_channel", "qzo_rtn_quantize", "qzo_debug_normals", "qzo_debug_philox",
-    "qzo_debug_normal_pairs", "qzo_debug_dequant", "qzo_debug_forward", "qzo_debug_mfma_rate", "qzo_debug_bf16_gemm", "qzo_profile_begin", "qzo_profile_collect", "qzo_profile_stride",
+    "qzo_dequant_gemm", "qzo_dequant_gemm_zp", "qzo_apply_update", "qzo_rtn_quantize", "qzo_repack_kmajor",
+    "qzo_int4_expand", "qzo_int4_scratch_bytes", "qzo_int4_gemm_expanded", "qzo_set_int4_path",
+    "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm",
+    "qzo_codebook_gemm", "qzo_apply_update_channel",
+    "qzo_debug_philox", "qzo_debug_normal_pairs", "qzo_debug_normals", "qzo_debug_dequant", "qzo_debug_dequant_zp",
+    "qzo_debug_forward", "qzo_debug_bf16_gemm", "qzo_debug_mfma_rate",
+    "qzo_profile_begin", "qzo_profile_collect", "qzo_profile_stride",
     "qzo_last_error",
 ]
 

@@ -54,3 +54,62 @@ def test_config_errors_are_reported():
                                      C.c_float(0), 1, None, None, None) == qb.QZO_ERR_ARG
     assert qb.lib().qzo_step(None, None, 1, 2, C.c_uint64(0), C.c_float(0), C.c_float(0),
                              C.c_float(1), None, C.c_uint64(0), None, None) == qb.QZO_ERR_ARG
+
+
+def test_counts_of_the_other_formats(oracle):
+    tiny = synth.SHAPES["tiny"]
+    n0 = qb.qzo_model_scale_count(tiny)
+    # zero-points do not change the scales; NormalFloat-4 blocks of 64 double them; the codebook
+    # format has one scale per quantized output row
+    assert qb.qzo_model_scale_count(dict(tiny, quant=2)) == n0
+    assert qb.qzo_model_scale_count(dict(tiny, quant=3, group=64)) == 2 * n0
+    rows = tiny["n_layers"] * (5 * tiny["d_model"] + 2 * tiny["d_ffn"])      # qkv 3d, o d, gate+up 2F, down d
+    assert qb.qzo_model_scale_count(dict(tiny, quant=1)) == rows
+    with pytest.raises(qb.QzoError) as e:
+        qb.qzo_model_scale_count(dict(tiny, quant=3))              # NormalFloat-4 needs group_size 64
+    assert e.value.status == qb.QZO_ERR_SHAPE
+    with pytest.raises(qb.QzoError):
+        qb.qzo_model_scale_count(dict(tiny, quant=0, group=64))
+    with pytest.raises(qb.QzoError) as e:
+        qb.qzo_model_scale_count(dict(tiny, quant=4))
+    assert e.value.status == qb.QZO_ERR_UNSUPPORTED
+    with pytest.raises(qb.QzoError):
+        qb.qzo_model_scale_count(dict(synth.SHAPES["tiny_opt"], quant=1))   # codebook: Llama family only
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "llama-2-7b"])
+def test_dense_count_is_the_16_bit_part_of_the_table(oracle, name):
+    sh = synth.SHAPES[name]
+    d, F, V, L = sh["d_model"], sh["d_ffn"], sh["vocab"], sh["n_layers"]
+    if sh["arch"] == "llama":
+        want = 2 * V * d + L * 2 * d + d
+    else:
+        want = 2 * V * d + sh["max_seq"] * d + L * (4 * d + 3 * d + d + F + d) + 2 * d
+    assert qb.qzo_model_dense_count(sh) == want
+    assert qb.qzo_model_dense_count(dict(sh, quant=2)) == want
+    if sh["arch"] == "llama":
+        assert qb.qzo_model_dense_count(dict(sh, quant=1)) == want + L * 4 * 65536 * 8
+    if name != "llama-2-7b":
+        from oracle import oracle as O
+        m = O.build_model(sh, synth.tensor_table(sh, 3))
+        assert O.dense_master(m).size == want
+
+
+def test_scratch_sizes_and_mode_switches():
+    assert qb.qzo_nf4_scratch_bytes(512, 1024) >= 512 * 1024 * 2 + 512 * 16 * 4
+    assert qb.qzo_int4_scratch_bytes(512, 1024) >= 512 * 1024 * 2 + 512 * 8 * 4
+    assert qb.qzo_nf4_scratch_bytes(512, 1024) % 256 == 0
+    for mode in (1, 2, 0):
+        qb.qzo_set_int4_path(mode)
+    with pytest.raises(qb.QzoError):
+        qb.qzo_set_int4_path(3)
+    with pytest.raises(qb.QzoError):
+        qb.qzo_profile_stride(0)
+    qb.qzo_profile_stride(1)
+    # argument errors of the single-linear expand entry points are found on the host
+    lib = qb.lib()
+    assert lib.qzo_nf4_expand(None, None, 0, 8, 128, 64, C.c_uint64(0), C.c_float(0), 1, None, None, None) == qb.QZO_ERR_ARG
+    assert lib.qzo_int4_expand(None, None, None, None, 0, 8, 128, 128, C.c_uint64(0), C.c_float(0), 1, None, None,
+                               None) == qb.QZO_ERR_ARG
+    assert lib.qzo_step_joint(None, None, 1, 2, C.c_uint64(0), C.c_float(0), C.c_float(0), C.c_float(0),
+                              C.c_float(1), None, C.c_uint64(0), None, None) == qb.QZO_ERR_ARG
