@@ -122,7 +122,7 @@ def probe(torch, qb):
         torch.cuda.synchronize()
         qb.qzo_int4_expand(q, s, None, 0, 7, 1e-3, 1, se, wexp)
         torch.cuda.synchronize()
-        qb.qzo_debug_bf16_gemm(x, wexp, y, 1)
+        qb.qzo_debug_bf16_gemm(x, wexp, y, 2)
         torch.cuda.synchronize()
         qb.qzo_apply_update(arena, 0, 7, 1e-7, 10.0)
         torch.cuda.synchronize()
@@ -280,7 +280,7 @@ def main():
         "last_step": res,
         "scales_changed_frac": changed,
         "roofline": {"bound": "mfma",
-                     "kernel": "gemm_kernel<1,false,4,1> (plain bf16 GEMM on the expanded perturbed weights)"
+                     "kernel": "gemm_kernel<1,false,4,3> (plain bf16 GEMM on the expanded perturbed weights)"
                      if expanded
                      else ("gemm_kernel<2,...> (codebook GEMM, perturbed channel scales)" if codebook
                            else "gemm_kernel<0,false,4,2> (fused perturbed W4A16 GEMM)"),

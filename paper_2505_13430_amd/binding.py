@@ -276,7 +276,7 @@ def qzo_set_int4_path(mode: int):
     _check(lib().qzo_set_int4_path(C.c_int(mode)))
 
 
-def qzo_debug_bf16_gemm(x, w, y, pipe=1, stream=None):
+def qzo_debug_bf16_gemm(x, w, y, pipe=2, stream=None):
     M, K = x.shape
     N = w.shape[0]
     _check(lib().qzo_debug_bf16_gemm(_ptr(x), _ptr(w), C.c_uint32(M), C.c_uint32(N), C.c_uint32(K),

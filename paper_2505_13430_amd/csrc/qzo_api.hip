@@ -332,7 +332,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         }
         g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
-        return launch_bf16_gemm(g, 1, st);
+        return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
       if (w.wexp && g_int4_path != 1 && n_pass == 1 &&
           (g_int4_path == 2 || M >= expand_min_m_int4(g.N, g.K))) {
@@ -345,7 +345,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         }
         g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
-        return launch_bf16_gemm(g, 1, st);
+        return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
       ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
       return launch_w4a16_gemm(g, st);
@@ -371,7 +371,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         }
         g.w = w.wexp; g.cb = nullptr; g.s = nullptr; g.split_ws = split ? w.split : nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
-        return launch_bf16_gemm(g, 1, st);
+        return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
       ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
       return launch_codebook_gemm(g, st);
@@ -878,7 +878,7 @@ qzo_status qzo_int4_gemm_expanded(const void* x_dev, const void* q_dev, const vo
                              (uint32_t)(seed >> 32), sign > 0 ? eps : -eps, false, se, wexp, s));
   GemmArgs g = {};
   g.x = x_dev; g.w = wexp; g.y = y_dev; g.M = M; g.N = N; g.K = K;
-  QZO_HIP(launch_bf16_gemm(g, 1, s));
+  QZO_HIP(launch_bf16_gemm(g, PLAIN_GEMM_PIPE, s));
   return QZO_OK;
 }
 
@@ -930,7 +930,7 @@ qzo_status qzo_nf4_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
                             sign > 0 ? eps : -eps, false, se, wexp, s));
   GemmArgs g = {};
   g.x = x_dev; g.w = wexp; g.y = y_dev; g.M = M; g.N = N; g.K = K;
-  QZO_HIP(launch_bf16_gemm(g, 1, s));
+  QZO_HIP(launch_bf16_gemm(g, PLAIN_GEMM_PIPE, s));
   return QZO_OK;
 }
 
@@ -947,7 +947,7 @@ qzo_status qzo_debug_bf16_gemm(const void* x_dev, const void* w_dev, uint32_t M,
     return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
   if (K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "K must be a positive multiple of 128");
   if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
-  if (pipe < 0 || pipe > 4) return fail(QZO_ERR_ARG, "pipe must be 0..4");
+  if (pipe < 0 || pipe > 2) return fail(QZO_ERR_ARG, "pipe must be 0, 1 or 2");
   GemmArgs g = {};
   g.x = x_dev; g.w = w_dev; g.y = y_dev; g.M = M; g.N = N; g.K = K;
   QZO_HIP(launch_bf16_gemm(g, pipe, (hipStream_t)stream));

@@ -472,14 +472,24 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 // with the tile after next (NEXT_KT < 0: nothing left to load).
 #define QZO_TILE_D(STAGE, HOLD, NEXT_KT)                                                     \
   do {                                                                                       \
+    /* the fences keep the source order: each k-step's fragment reads are issued before the */ \
+    /* MFMAs of the k-step before it (the compiler would otherwise sink them to their use)  */ \
     QZO_FRAGS(0, 0, STAGE);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
     if (HOLD) QZO_MFMAS(1);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_FRAGS(1, 1, STAGE);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_MFMAS(0);                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_FRAGS(0, 2, STAGE);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_MFMAS(1);                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_FRAGS(1, 3, STAGE);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_MFMAS(0);                                                                            \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_DTL_LANDED();                                                                        \
     if ((int)(NEXT_KT) >= 0) QZO_DTL(NEXT_KT, STAGE);                                        \
   } while (0)
@@ -946,6 +956,9 @@ hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st) {
   if (!ready) {
     hipError_t e = set_lds_attr((const void*)gemm_kernel<1, false, 4, 0>);
     if (e == hipSuccess) e = set_lds_attr((const void*)gemm_kernel<1, false, 4, 1>);
+    if (e == hipSuccess)     // + 1 KB: the sum-of-squares scratch sits behind the stages
+      e = hipFuncSetAttribute((const void*)gemm_kernel<1, false, 4, 3>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + 1024);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -953,44 +966,21 @@ hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st) {
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K * 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
-  if (pipe == 1 && a.split_ws) {       // the model's route: split K when the output has too few tiles
-    GemmArgs g = a;
-    g.ksplit = tile_ksplit(a.M, a.N, a.K, &g.kt_per);
-    if (g.ksplit > 1) {
-      g.epi = 0;
-      gemm_kernel<1, false, 4, 1><<<gemm_workgroups(a.M, ((a.N + BN - 1) / BN) * g.ksplit * BN), 512,
-                                    LDS_BYTES, st>>>(g, ce);
-      hipError_t e = hipGetLastError();
-      if (e != hipSuccess) return e;
-      return launch_partial_reduce(a, a.split_ws, g.ksplit, st);
-    }
-  }
-  if (pipe == 4) {                     // both operand tiles straight from memory into the LDS
-    static bool ready4 = false;
-    if (!ready4) {
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<1, false, 4, 3>,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + 1024);
-      if (e != hipSuccess) return e;
-      ready4 = true;
-    }
-    gemm_kernel<1, false, 4, 3><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES + 1024, st>>>(a, ce);
-  } else if (pipe == 2 || pipe == 3) {        // one wavefront per SIMD, 128 x 128 per wavefront
-    static bool ready2 = false;
-    if (!ready2) {
-      hipError_t e = set_lds_attr((const void*)gemm_kernel<1, false, 2, 0>);
-      if (e == hipSuccess) e = set_lds_attr((const void*)gemm_kernel<1, false, 2, 1>);
-      if (e != hipSuccess) return e;
-      ready2 = true;
-    }
-    if (pipe == 3)
-      gemm_kernel<1, false, 2, 1><<<gemm_workgroups(a.M, a.N), 256, LDS_BYTES, st>>>(a, ce);
-    else
-      gemm_kernel<1, false, 2, 0><<<gemm_workgroups(a.M, a.N), 256, LDS_BYTES, st>>>(a, ce);
-  } else if (pipe == 1)
-    gemm_kernel<1, false, 4, 1><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES, st>>>(a, ce);
-  else
-    gemm_kernel<1, false, 4, 0><<<gemm_workgroups(a.M, a.N), 512, LDS_BYTES, st>>>(a, ce);
-  return hipGetLastError();
+  GemmArgs g = a;
+  g.ksplit = 1;
+  g.kt_per = a.K / BK;
+  if (a.split_ws) g.ksplit = tile_ksplit(a.M, a.N, a.K, &g.kt_per);   // too few tiles for the chip: split K
+  if (g.ksplit > 1) g.epi = 0;       // natural row order, fp32 partial sums; the reduction applies a.epi
+  const uint32_t wgs = gemm_workgroups(a.M, ((a.N + BN - 1) / BN) * g.ksplit * BN);
+  if (pipe == 2)         // both operand tiles straight from memory into the LDS (the model's route)
+    gemm_kernel<1, false, 4, 3><<<wgs, 512, LDS_BYTES + 1024, st>>>(g, ce);
+  else if (pipe == 1)    // staged through registers, explicit issue order
+    gemm_kernel<1, false, 4, 1><<<wgs, 512, LDS_BYTES, st>>>(g, ce);
+  else                   // staged through registers, compiler's order
+    gemm_kernel<1, false, 4, 0><<<wgs, 512, LDS_BYTES, st>>>(g, ce);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || g.ksplit == 1) return e;
+  return launch_partial_reduce(a, a.split_ws, g.ksplit, st);
 }
 
 hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {

@@ -68,7 +68,10 @@ uint32_t tile_ksplit(uint32_t M, uint32_t N, uint32_t K, uint32_t* kt_per);
 uint64_t tile_split_ws_floats(uint32_t M, uint32_t N, uint32_t K);
 // w = uint16 codes [N,K/8]; cb and s as above; N % 8 == 0, K % 128 == 0.
 hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st);
+// pipe: 0 / 1 = operand tiles staged through registers (compiler's / explicit issue order),
+// 2 = loaded from memory straight into the LDS.
 hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st);
+constexpr int PLAIN_GEMM_PIPE = 2;     // the route the models take: 3 % faster than 1 on a full step
 // One linear's perturbed weights written out as bf16 [N,K] (rows in the GEMM's tile order
 // when the consumer fuses SwiGLU), for launch_bf16_gemm.
 hipError_t launch_expand_codebook(const void* codes, const void* cb, const void* c_fp16, uint32_t N,

@@ -650,8 +650,8 @@ def test_joint_step_matches_oracle(oracle, name):
     dm.close()
 
 
-@pytest.mark.parametrize("M,N,K,pipe", [(300, 520, 384, 1), (513, 264, 1280, 0), (300, 520, 384, 3), (64, 136, 512, 2),
-                                          (300, 520, 384, 4), (513, 264, 1280, 4), (1, 8, 128, 4), (700, 776, 256, 4)])
+@pytest.mark.parametrize("M,N,K,pipe", [(300, 520, 384, 1), (513, 264, 1280, 0), (64, 136, 512, 1),
+                                          (300, 520, 384, 2), (513, 264, 1280, 2), (1, 8, 128, 2), (700, 776, 256, 2)])
 def test_plain_bf16_gemm_matches_oracle(oracle, M, N, K, pipe):
     rng = np.random.default_rng(M + N + K)
     x = synth.bf16_exact(rng.standard_normal((M, K), dtype=np.float32))
