@@ -168,7 +168,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // PIPE == 3 (plain bf16 weights): both operand tiles go from memory straight into the LDS
   // (buffer loads with the lds modifier); no staging registers, no LDS store instructions
   constexpr bool DTL = PIPE == 3;
-  static_assert(!DTL || (QM == 1 && !CE), "direct-to-LDS staging is written for the plain bf16 GEMM");
+  static_assert(!DTL || QM == 1, "direct-to-LDS staging is written for plain bf16 weights");
   static_assert(!CB || NWN == 4, "codebook staging is written for 512 threads");
   static_assert(!PP || (NWN == 4 && W4), "the phase schedule is written for int4 weights, 512 threads");
   constexpr int THREADS = 128 * NWN;
@@ -986,7 +986,8 @@ hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st) {
 hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
-    hipError_t e = set_lds_attr((const void*)gemm_kernel<1, true, 4, 0>);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_kernel<1, true, 4, 3>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + 1024);
     if (e != hipSuccess) return e;
     ready = true;
   }
@@ -995,7 +996,7 @@ hipError_t launch_lmhead_ce(const CeArgs& c, hipStream_t st) {
   GemmArgs a = {};
   a.x = c.x; a.w = c.w; a.M = c.M; a.N = c.V; a.K = c.K;
   CeEpilogue ce = {c.tok, c.part, c.tgt, c.S, c.n_slices, c.tok_rows ? c.tok_rows : c.M};
-  gemm_kernel<1, true, 4, 0><<<gemm_workgroups(c.M, c.V), 512, LDS_BYTES, st>>>(a, ce);
+  gemm_kernel<1, true, 4, 3><<<gemm_workgroups(c.M, c.V), 512, LDS_BYTES + 1024, st>>>(a, ce);
   return hipGetLastError();
 }
 
