@@ -147,7 +147,7 @@ def main():
                          "scales (no cpu_baseline leg)")
     ap.add_argument("--fused", action="store_true",
                     help="int4 variants: always the fused dequantizing GEMM (default: expand-then-multiply "
-                         "for linears with enough tokens per pass, about 3500-5600 at the 7B widths)")
+                         "for linears with enough tokens per pass, about 2700-4300 at the 7B widths)")
     ap.add_argument("--expanded", action="store_true",
                     help="int4 variants: always expand-then-multiply, whatever the token count")
     ap.add_argument("--graph", action="store_true",

@@ -329,7 +329,7 @@ qzo_status qzo_int4_gemm_expanded(const void* x_dev, const void* q_dev, const vo
                                   uint64_t scratch_bytes, void* stream);
 
 /* How the model's int4 linears (quant 0 and 2) run.  mode 0 (default): by size; a linear [N,K] with at
- * least 3022 + 4.35e10 / (N K) tokens in a pass (3900 for 12288 x 4096) has its perturbed weights first
+ * least 2300 + 3.3e10 / (N K) tokens in a pass (2950 for 12288 x 4096) has its perturbed weights first
  * written out as a bf16 matrix in the workspace (same bits as the fused kernel's weight tile) and multiplied
  * by the plain bf16 GEMM, with fewer the fused dequantizing GEMM runs (below the break-even an expansion
  * costs more than the fused kernel's extra work).  mode 1: always the fused kernel.  mode 2: always expand-then-multiply.

@@ -87,15 +87,16 @@ hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp,
                               uint32_t N, uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                               bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st);
 // Tokens per pass from which an int4 linear [N,K] is expanded first.  The expansion costs two short
-// launches (about 8 us) plus 2.5 bytes per weight at about 4.5 TB/s; the fused kernel needs about 10.6 %
+// launches (about 8 us) plus 2.5 bytes per weight at about 4.5 TB/s; the fused kernel needs about 13.6 %
 // more time than the plain GEMM on the expanded weights, a time that grows with the tokens
-// (2 M N K flop at about 1.15 PFLOP/s).  Setting the two equal gives M = 3022 + 4.35e10 / (N K):
-// measured on Llama-2-7B widths the two routes tie at 3072 tokens, the expansion wins from 4096
-// tokens on at the 7B and 13B widths and loses at OPT-1.3B widths (d = 2048) at 4096 tokens.
+// (2 M N K flop at about 1.3 PFLOP/s).  Setting the two equal gives M = a + b / (N K) with a near
+// 2700 and b near 4e10; fitted to the measurements (Llama-2-7B widths: a tie at 2560 tokens, the
+// expansion 3 % ahead at 3072; 13B widths: 4.5 % ahead at 4096; OPT-1.3B widths, d = 2048: 7 % behind
+// at 4096) a = 2300, b = 3.3e10.
 // The codebook format is always expanded inside a model: its fused kernel is 45 % slower than the
 // plain GEMM and cannot split K.
 inline uint32_t expand_min_m_int4(uint32_t N, uint32_t K) {
-  return 3022u + (uint32_t)(4.35e10 / ((double)N * (double)K));
+  return 2300u + (uint32_t)(3.3e10 / ((double)N * (double)K));
 }
 constexpr uint32_t EXPAND_MIN_M_CODEBOOK = 1;
 hipError_t launch_channel_update(void* c_fp16, uint32_t n, uint32_t row_base, uint32_t seed_lo,
