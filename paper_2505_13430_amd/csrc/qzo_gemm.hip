@@ -320,14 +320,15 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 #define QZO_DTL16(RSRC, LDSADDR, VOFF, SOFF)                                                 \
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"                \
                : : "s"(LDSADDR), "v"(VOFF), "s"(RSRC), "s"(SOFF) : "memory", "m0")
-#define QZO_DTL(KT, STAGE)                                                                   \
+#define QZO_DTL_PART(KT, STAGE, I0, I1)                                                      \
   do {                                                                                       \
     const uint32_t so_ = (uint32_t)(KT) * (BK * 2);                                          \
-    _Pragma("unroll") for (int i = 0; i < NA; ++i) {                                         \
+    _Pragma("unroll") for (int i = (I0); i < (I1); ++i) {                                    \
       QZO_DTL16(rx4, lds_wave + (uint32_t)((STAGE) * TILE_BYTES + i * RSTEP * 128), xo[i], so_); \
       QZO_DTL16(rw4, lds_wave + (uint32_t)((2 + (STAGE)) * TILE_BYTES + i * RSTEP * 128), wo[i], so_); \
     }                                                                                        \
   } while (0)
+#define QZO_DTL(KT, STAGE) QZO_DTL_PART(KT, STAGE, 0, NA)
 #define QZO_DTL_LANDED()                                                                     \
   do {                                                                                       \
     __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */                                       \
@@ -467,18 +468,23 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     }                                                                                        \
   } while (0)
 
-// One k-tile with direct-to-LDS staging: fragments and MFMAs as above; then, once every
-// wavefront has read the stage and the other stage's loads have landed, the stage is refilled
-// with the tile after next (NEXT_KT < 0: nothing left to load).
-#define QZO_TILE_D(STAGE, HOLD, NEXT_KT)                                                     \
+// One k-tile with direct-to-LDS staging: fragments and MFMAs as above.  The other stage was
+// read last in the tile before this one (every wavefront is past that tile's closing barrier),
+// so it is refilled with tile LOAD_KT, the one after this (< 0: nothing left to load), while
+// this tile computes: half of the loads before the first MFMA group and half before the second
+// (a little faster than all eight at once; spreading them further leaves the last ones too
+// little time to land).  The tile closes once those loads have landed in every wavefront.
+#define QZO_TILE_D(STAGE, HOLD, LOAD_KT)                                                     \
   do {                                                                                       \
     /* the fences keep the source order: each k-step's fragment reads are issued before the */ \
     /* MFMAs of the k-step before it (the compiler would otherwise sink them to their use)  */ \
     QZO_FRAGS(0, 0, STAGE);                                                                  \
+    if ((int)(LOAD_KT) >= 0) QZO_DTL_PART(LOAD_KT, 1 - (STAGE), 0, NA / 2);                  \
     __builtin_amdgcn_sched_barrier(0);                                                       \
     if (HOLD) QZO_MFMAS(1);                                                                  \
     __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_FRAGS(1, 1, STAGE);                                                                  \
+    if ((int)(LOAD_KT) >= 0) QZO_DTL_PART(LOAD_KT, 1 - (STAGE), NA / 2, NA);                 \
     __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_MFMAS(0);                                                                            \
     __builtin_amdgcn_sched_barrier(0);                                                       \
@@ -491,7 +497,6 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     QZO_MFMAS(0);                                                                            \
     __builtin_amdgcn_sched_barrier(0);                                                       \
     QZO_DTL_LANDED();                                                                        \
-    if ((int)(NEXT_KT) >= 0) QZO_DTL(NEXT_KT, STAGE);                                        \
   } while (0)
 
 // Phase schedule (int4 weights).  Wavefronts w and w + 4 share a SIMD.  A k-tile is cut
@@ -621,10 +626,10 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     QZO_PP_TILE(1, -1, 0u, 0u, -1, -1);
     if (!late_group) QZO_PHASE_SYNC();
   } else if (DTL) {
-    QZO_TILE_D(0, false, nkt > 2 ? 2 : -1);
+    QZO_TILE_D(0, false, -1);                 /* tiles 0 and 1 were requested ahead of the loop */
     for (uint32_t kt = 1; kt + 1 < nkt; kt += 2) {
-      QZO_TILE_D(1, true, kt + 2 <= last ? (int)(kt + 2) : -1);
-      QZO_TILE_D(0, true, kt + 3 <= last ? (int)(kt + 3) : -1);
+      QZO_TILE_D(1, true, (int)(kt + 1));
+      QZO_TILE_D(0, true, kt + 2 <= last ? (int)(kt + 2) : -1);
     }
     QZO_TILE_D(1, true, -1);
     QZO_MFMAS(1);
@@ -870,6 +875,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 #undef QZO_TILE
 #undef QZO_TILE_D
 #undef QZO_DTL
+#undef QZO_DTL_PART
 #undef QZO_DTL16
 #undef QZO_DTL_LANDED
 #undef QZO_PP_TILE
