@@ -398,6 +398,16 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // acc[i][j]: output features 32 j .. 32 j + 31 (rows of the MFMA result) by
   // tokens 32 i .. 32 i + 31 (columns) of the wavefront's sub-tile.
   floatx16 acc[4][TJ];
+  // Direct-to-LDS plain kernel: the output stores are buffer stores that every lane issues (a lane
+  // outside the matrix gets an offset beyond the buffer, which drops the store), so the number of
+  // memory instructions a wavefront issues behind the next tile's first loads is known, and the
+  // wait for those loads at the top of the next k-loop can leave that many instructions, the
+  // stores, in flight: vmcnt counts in issue order.  Waiting for the stores as well would expose
+  // the time the memory system needs to take in 128 KB from every CU at once.
+  constexpr bool TRAIL = DTL && !CE && TJ == 2;
+  uint32_t trail_stores = 0;                       // stores issued by the last epilogue: 0, 8 or 16
+  const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
+      a.y, 0, (int)((uint64_t)a.M * ((a.epi & EPI_SWIGLU) ? (a.N >> 1) : a.N) * 2), 0x00020000);
   const uint32_t frow = lane & 31u, fhalf = lane >> 5;
   // fragment addresses: row base + swizzled chunk of k-step ks (chunk 2 ks + half);
   // row tiles i / j and the stage are immediate offsets.
@@ -613,7 +623,17 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     QZO_LSTORE(0);
     QZO_GLOAD(1u);
   }
-  if (DTL) QZO_DTL_LANDED(); else __syncthreads();
+  if (TRAIL && trail_stores == 16) {
+    __builtin_amdgcn_s_waitcnt(0x4F70);   /* vmcnt(16) */
+    __syncthreads();
+  } else if (TRAIL && trail_stores == 8) {
+    __builtin_amdgcn_s_waitcnt(0x0F78);   /* vmcnt(8) */
+    __syncthreads();
+  } else if (DTL) {
+    QZO_DTL_LANDED();
+  } else {
+    __syncthreads();
+  }
   if (PP) {
     if (late_group) QZO_PHASE_SYNC();
     /* tile t stores tile t+1, requests activations of t+2 and weights of t+3; an even   */
@@ -696,6 +716,12 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   // Groups b and b+1 are exchanged between the two halves of the wavefront
   // (v_permlane32_swap), after which lanes 0..31 own features 8b..8b+7 and lanes 32..63
   // features 8(b+1)..8(b+1)+7 of their token: every access of the epilogue is 16 bytes.
+#define QZO_STORE_OUT(PTR, V) (*reinterpret_cast<uint4*>(PTR) = (V))
+// Default cache policy on purpose: non-temporal stores keep the output out of the L2 and are
+// 20 % faster in a loop of this structure on synthetic addresses, but the whole step gets 1.8 %
+// slower with them.
+#define QZO_STORE_OUT_ALWAYS(BYTE_OFF, V)                                                    \
+  __builtin_amdgcn_raw_buffer_store_b128(u32x4{(V).x, (V).y, (V).z, (V).w}, ry, (int)(BYTE_OFF), 0, 0)
 #define QZO_SWAP8(LO, HI)                                                                    \
   do {                                                                                       \
     _Pragma("unroll") for (int c_ = 0; c_ < 4; ++c_) {                                       \
@@ -706,6 +732,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
     }                                                                                        \
   } while (0)
   if (SPLITK && ksplit > 1) {
+    trail_stores = 0;
     // split-K: this slice's fp32 sums, [slice][M][N]; the epilogue proper runs in the reduction
     float* part = a.split_ws + (uint64_t)done_slice * a.M * a.N;
 #pragma unroll
@@ -753,14 +780,14 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
           }
         QZO_SWAP8(v[0], v[1]);
         const uint32_t f = done_n * 128u + wn * 32u + (2u * bp + fhalf) * 8u;
-        if (m < a.M) {
-          uint4 out;
-          out.x = pack_bf16x2(v[0][0], v[0][1]); out.y = pack_bf16x2(v[0][2], v[0][3]);
-          out.z = pack_bf16x2(v[1][0], v[1][1]); out.w = pack_bf16x2(v[1][2], v[1][3]);
-          *reinterpret_cast<uint4*>(y + (uint64_t)m * F + f) = out;
-        }
+        uint4 out;
+        out.x = pack_bf16x2(v[0][0], v[0][1]); out.y = pack_bf16x2(v[0][2], v[0][3]);
+        out.z = pack_bf16x2(v[1][0], v[1][1]); out.w = pack_bf16x2(v[1][2], v[1][3]);
+        if (TRAIL) QZO_STORE_OUT_ALWAYS(m < a.M ? (m * F + f) * 2u : 0x80000000u, out);
+        else if (m < a.M) QZO_STORE_OUT(y + (uint64_t)m * F + f, out);
       }
     }
+    trail_stores = TRAIL ? 8 : 0;
   } else if (!CE) {
     float ssq = 0.0f;
     const bf16_t* bias = (const bf16_t*)a.bias;
@@ -784,7 +811,10 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
           QZO_SWAP8(v[0], v[1]);
           // 8 features n .. n+7 (N % 8 == 0)
           const uint32_t n = n0 + wn * (32 * TJ) + j * 32 + (2u * bp + fhalf) * 8u;
-          if (m < a.M && n < a.N) {
+          const bool inside = m < a.M && n < a.N;
+          uint4 out = {0u, 0u, 0u, 0u};
+          const uint64_t o = (uint64_t)m * a.N + n;
+          if (inside) {
             if (a.epi & EPI_BIAS) {
               const uint4 bb = *reinterpret_cast<const uint4*>(bias + n);
               v[0][0] += __uint_as_float(bb.x << 16); v[0][1] += __uint_as_float(bb.x & 0xffff0000u);
@@ -792,7 +822,6 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
               v[1][0] += __uint_as_float(bb.z << 16); v[1][1] += __uint_as_float(bb.z & 0xffff0000u);
               v[1][2] += __uint_as_float(bb.w << 16); v[1][3] += __uint_as_float(bb.w & 0xffff0000u);
             }
-            const uint64_t o = (uint64_t)m * a.N + n;
             if (a.epi & EPI_RESIDUAL) {
               const uint4 rr = *reinterpret_cast<const uint4*>(resid + o);
               v[0][0] += __uint_as_float(rr.x << 16); v[0][1] += __uint_as_float(rr.x & 0xffff0000u);
@@ -806,10 +835,9 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
 #pragma unroll
                 for (int c = 0; c < 4; ++c) v[h][c] = fmaxf(v[h][c], 0.0f);
             }
-            uint4 out;
             out.x = pack_bf16x2(v[0][0], v[0][1]); out.y = pack_bf16x2(v[0][2], v[0][3]);
             out.z = pack_bf16x2(v[1][0], v[1][1]); out.w = pack_bf16x2(v[1][2], v[1][3]);
-            *reinterpret_cast<uint4*>(y + o) = out;
+            if (!TRAIL) QZO_STORE_OUT(y + o, out);
             if (a.epi & EPI_SUMSQ) {
               const uint32_t ow[4] = {out.x, out.y, out.z, out.w};
 #pragma unroll
@@ -820,8 +848,10 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
               }
             }
           }
+          if (TRAIL) QZO_STORE_OUT_ALWAYS(inside ? (uint32_t)o * 2u : 0x80000000u, out);
         }
     }
+    trail_stores = TRAIL ? 16 : 0;
     if (a.epi & EPI_SUMSQ) {
       // direct-to-LDS staging: the next tile's loads are already landing in the stages
       float* red = reinterpret_cast<float*>(lds + (DTL ? LDS_BYTES : 0));
@@ -872,6 +902,8 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   if (!more) break;
   }   // tile loop
 #undef QZO_SWAP8
+#undef QZO_STORE_OUT
+#undef QZO_STORE_OUT_ALWAYS
 #undef QZO_TILE
 #undef QZO_TILE_D
 #undef QZO_DTL
@@ -969,7 +1001,9 @@ hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st) {
     ready = true;
   }
   if (a.M == 0 || a.N == 0) return hipSuccess;
-  if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K * 2 >= (1ull << 31))
+  // buffer loads and stores address the operands and the output with 32-bit byte offsets
+  if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K * 2 >= (1ull << 31) ||
+      (uint64_t)a.M * a.N * 2 >= (1ull << 31))
     return hipErrorInvalidValue;
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
   GemmArgs g = a;
