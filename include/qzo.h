@@ -340,7 +340,7 @@ qzo_status qzo_set_int4_path(int mode);
  * bf16 weight matrix w_dev [N,K] (x_dev bf16 [M,K], y_dev bf16 [M,N], fp32 accumulation, no epilogue).
  * pipe: 0 or 1, operand tiles staged through registers (compiler's / explicit issue order); 2, both
  * operand tiles loaded from memory straight into the LDS (no staging registers; the one the models use).  K a positive multiple of 128, N a multiple of 8, pointers
- * 16-byte aligned, M*K and N*K below 2^30 elements. */
+ * 16-byte aligned, M*K, N*K and M*N below 2^30 elements. */
 qzo_status qzo_debug_bf16_gemm(const void* x_dev, const void* w_dev, uint32_t M, uint32_t N, uint32_t K,
                                int pipe, void* y_dev, void* stream);
 

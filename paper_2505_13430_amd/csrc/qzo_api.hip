@@ -48,7 +48,7 @@ struct Workspace {
   float *ce_part, *tgt, *rowloss, *losses, *skinny;
   float* split;             // K-slice partial sums of the int4 tile kernel (too few tiles for the chip)
   unsigned char* wexp;      // one linear's expanded bf16 weights (expand-then-multiply paths)
-  float* se;                // NormalFloat-4: that linear's perturbed block scales
+  float* se;                // expand-then-multiply of int4 / NormalFloat-4: every perturbed scale of the model, fp32
   uint64_t total;
 };
 
@@ -218,12 +218,11 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
                           (int4 && (g_int4_path == 2 || M1 >= expand_min_m_int4(m->lin[i].N, m->lin[i].K)));
     if (expanded) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
   }
-  if (ex && c.quant != 1)
-    for (int i = 0; i < 4; ++i)
-      sx = std::max<uint64_t>(sx, (uint64_t)m->lin[i].N * (m->lin[i].K / c.group_size) * 4);
+  if (ex && c.quant != 1) sx = m->n_scales * 4;     // every perturbed scale of the model, fp32
   w.wexp = take(ex);
   if (ex == 0) w.wexp = nullptr;
   w.se = (float*)take(sx);
+  if (sx == 0) w.se = nullptr;
   w.total = off;
   return w;
 }
@@ -288,6 +287,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
     QZO_HIP(launch_dense_perturb(m->dense_master, m->dense_segs, m->n_dense_segs, m->n_dense, seed_lo,
                                  seed_hi, eps_signed, st));
   }
+  if (w.se) {   // some linear takes the expansion route: one launch perturbs every scale of the model
+    ProfScope ps(PK_EXPAND, 0, st);
+    QZO_HIP(launch_perturbed_scales_all(m->arena, m->plan, seed_lo, seed_hi, eps_signed, w.se, st));
+  }
   {
     ProfScope ps(PK_OTHER, 0, st);
     QZO_HIP(launch_embed(tok, M1, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
@@ -326,8 +329,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         const bool split = w.split && tile_ksplit(g.M, g.N, g.K, nullptr) > 1;
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
-          hipError_t e = launch_expand_nf4(g.w, g.s, g.N, g.K, g.row_base, seed_lo, seed_hi, eps_signed,
-                                           (epi & EPI_SWIGLU) != 0 && !split, w.se, w.wexp, st);
+          hipError_t e = launch_expand_nf4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.N, g.K,
+                                                (epi & EPI_SWIGLU) != 0 && !split, w.wexp, st);
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
@@ -339,8 +342,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         // many tokens: write the perturbed matrix out once, then a plain bf16 GEMM
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
-          hipError_t e = launch_expand_int4(g.w, g.s, g.zp, nullptr, g.N, g.K, g.row_base, seed_lo, seed_hi,
-                                            eps_signed, (epi & EPI_SWIGLU) != 0, w.se, w.wexp, st);
+          hipError_t e = launch_expand_int4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.zp, g.N, g.K,
+                                                 (epi & EPI_SWIGLU) != 0, w.wexp, st);
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;

@@ -94,6 +94,29 @@ __global__ __launch_bounds__(256) void perturbed_scales_kernel(const bf16_t* __r
     if ((uint32_t)j < nv) se[base + j] = __builtin_fmaf(eps_signed, z[j], bf16_to_f32(s[base + j]));
 }
 
+// The same for every scale of a model in one launch, laid out like the scale arena (the update's
+// plan: grid = (workgroups per layer, layers), a thread owns the eight scales of one counter).
+__global__ __launch_bounds__(256) void perturbed_scales_all_kernel(const bf16_t* __restrict__ arena, UpdPlan plan,
+                                                                   uint32_t seed_lo, uint32_t seed_hi,
+                                                                   float eps_signed, float* __restrict__ se) {
+  const uint32_t wg = blockIdx.x, layer = blockIdx.y;
+  UpdSeg sg = plan.seg[0];
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if ((uint32_t)i < plan.n_seg && wg >= plan.seg[i].first_wg) sg = plan.seg[i];
+  const uint32_t Gb = (sg.G + 7u) >> 3;
+  const uint32_t u = (wg - sg.first_wg) * 256u + threadIdx.x;
+  if (u >= sg.rows * Gb) return;
+  const uint32_t row = u / Gb, gb = u - row * Gb;
+  float z[8];
+  scale_normals8(seed_lo, seed_hi, 0u, layer * plan.rows_per_layer + sg.row_base + row, gb, z);
+  const uint64_t base = (uint64_t)layer * plan.layer_stride + sg.off + (uint64_t)row * sg.G + gb * 8u;
+  const uint32_t nv = min(8u, sg.G - gb * 8u);
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if ((uint32_t)j < nv) se[base + j] = __builtin_fmaf(eps_signed, z[j], bf16_to_f32(arena[base + j]));
+}
+
 // bf16 [N,K] from the indices and the perturbed scales: a thread turns one dword (eight
 // indices, k = 8c .. 8c+7, lowest nibble first) into 16 bytes; the level table sits in LDS
 // (16 words in 16 banks: any mix of indices is served without a conflict).
@@ -166,6 +189,30 @@ hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp,
   if (e != hipSuccess) return e;
   expand_int4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>(
       (const uint32_t*)q, se_scratch, (const uint8_t*)zp, g_idx, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
+  return hipGetLastError();
+}
+
+hipError_t launch_perturbed_scales_all(const void* arena, const UpdPlan& plan, uint32_t seed_lo, uint32_t seed_hi,
+                                       float eps_signed, float* se_all, hipStream_t st) {
+  dim3 grid(plan.wgs_per_layer, plan.n_layers);
+  if (grid.x == 0 || grid.y == 0) return hipSuccess;
+  perturbed_scales_all_kernel<<<grid, 256, 0, st>>>((const bf16_t*)arena, plan, seed_lo, seed_hi, eps_signed, se_all);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand_int4_from(const void* q, const float* se, const void* zp, uint32_t N, uint32_t K,
+                                   bool swiglu, void* out_bf16, hipStream_t st) {
+  if (N == 0) return hipSuccess;
+  expand_int4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>(
+      (const uint32_t*)q, se, (const uint8_t*)zp, nullptr, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand_nf4_from(const void* q, const float* se, uint32_t N, uint32_t K, bool swiglu,
+                                  void* out_bf16, hipStream_t st) {
+  if (N == 0) return hipSuccess;
+  expand_nf4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>((const uint32_t*)q, se, N, K, swiglu ? 1 : 0,
+                                                                   (uint4*)out_bf16);
   return hipGetLastError();
 }
 

@@ -86,6 +86,14 @@ hipError_t launch_expand_nf4(const void* q, const void* s_bf16, uint32_t N, uint
 hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, const int32_t* g_idx,
                               uint32_t N, uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                               bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st);
+// Inside a model the perturbed scales of every linear are written by one launch per pass (fp32, laid
+// out like the scale arena) and the expansions read them from there.
+hipError_t launch_perturbed_scales_all(const void* arena, const UpdPlan& plan, uint32_t seed_lo, uint32_t seed_hi,
+                                       float eps_signed, float* se_all, hipStream_t st);
+hipError_t launch_expand_int4_from(const void* q, const float* se, const void* zp, uint32_t N, uint32_t K,
+                                   bool swiglu, void* out_bf16, hipStream_t st);
+hipError_t launch_expand_nf4_from(const void* q, const float* se, uint32_t N, uint32_t K, bool swiglu,
+                                  void* out_bf16, hipStream_t st);
 // Tokens per pass from which an int4 linear [N,K] is expanded first.  The expansion costs two short
 // launches (about 8 us) plus 2.5 bytes per weight at about 4.5 TB/s; the fused kernel needs about 13.6 %
 // more time than the plain GEMM on the expanded weights, a time that grows with the tokens
