@@ -215,7 +215,8 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   uint64_t ex = 0, sx = 0;
   for (int i = 0; i < 4; ++i) {
     const bool expanded = c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK) ||
-                          (int4 && (g_int4_path == 2 || M1 >= expand_min_m_int4(m->lin[i].N, m->lin[i].K)));
+                          (int4 && g_int4_path != 1 && !stack &&
+                           (g_int4_path == 2 || M1 >= expand_min_m_int4(m->lin[i].N, m->lin[i].K)));
     if (expanded) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
   }
   if (ex && c.quant != 1) sx = m->n_scales * 4;     // every perturbed scale of the model, fp32
