@@ -711,11 +711,12 @@ def test_int4_expand_then_multiply_equals_the_fused_path(oracle, name):
     om, dm = _models(oracle, shape, 1234, 4.0, asym is True)
     tok = synth.tokens(shape, 5678)
     B, S = tok.shape
-    outs = []
+    outs, ws_bytes = [], []
     try:
         for mode in (2, 1):
             qb.qzo_set_int4_path(mode)
             dm._ws = dm._ws_key = None           # the workspace layout depends on the route
+            ws_bytes.append(qb.qzo_workspace_bytes(dm.handle, B, S))
             hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
             loss = torch.zeros(1, dtype=torch.float32, device=DEV)
             qb.qzo_debug_forward(dm.handle, _dev(tok), 9, 1e-3, -1, dm.workspace(B, S), loss, hid)
@@ -724,6 +725,9 @@ def test_int4_expand_then_multiply_equals_the_fused_path(oracle, name):
         qb.qzo_set_int4_path(0)
     assert outs[0][0] == outs[1][0]
     assert np.array_equal(outs[0][1], outs[1][1])
+    # the expanded route adds one linear in bf16 and every perturbed scale in fp32 to the workspace
+    n_scales = qb.qzo_model_scale_count(dict(shape, quant=2) if asym is True else shape)
+    assert ws_bytes[0] >= ws_bytes[1] + 4 * n_scales
     dm.close()
 
 
