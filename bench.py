@@ -195,7 +195,8 @@ def main():
     tok = torch.from_numpy(synth.tokens(shape, 5678)).cuda()
     eps, eta, clip = 1e-3, 1e-7, 100.0
     stream = torch.cuda.current_stream()
-    qb.qzo_set_int4_path(1 if args.fused else (2 if args.expanded else 0))
+    if not codebook and args.variant != "nf4":
+        dm.set_int4_path(1 if args.fused else (2 if args.expanded else 0))
     if args.joint:
         dm.enable_joint()
         plain_step = dm.step_joint

@@ -13,9 +13,15 @@
  *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream) and returns without synchronising.  Results stay on
  *    the device.
- *  - Every function returns QZO_OK or a negative qzo_status; on error nothing
- *    has been enqueued and qzo_last_error() describes the reason (thread-local
- *    string, valid until the next failing call on that thread).
+ *  - Every function returns QZO_OK or a negative qzo_status and qzo_last_error()
+ *    describes the reason (thread-local string, valid until the next failing call
+ *    on that thread).  Arguments, shapes, alignment, workspace and scratch sizes and
+ *    the kernels' 32-bit addressing limits are all checked before the first launch:
+ *    a call that fails with any status other than QZO_ERR_HIP has enqueued nothing.
+ *    QZO_ERR_HIP reports a failing HIP runtime call (a launch the runtime refused);
+ *    launches issued before it stay enqueued.
+ *  - The library allocates no device memory: every buffer, including scratch, is the
+ *    caller's.  The measurement hooks create HIP events.
  *  - bf16 = upper 16 bits of an IEEE fp32, round-to-nearest-even on store.
  *
  * Data layout
@@ -110,8 +116,10 @@ typedef struct {
  * scale count is the paper's Table 2 "trainable parameters"); embeddings,
  * norms, biases and lm_head are fixed bf16.  Row ids for the noise follow the
  * arena order.  Requires d_model % 128 == 0, d_ffn % 128 == 0,
- * d_model/n_heads in {64, 128}.  Allocates a few KB of device tables (RoPE
- * angles, update segments) that qzo_model_destroy frees.
+ * d_model/n_heads in {64, 128}.  Host work only: nothing is allocated or enqueued on
+ * the device (the RoPE angle table lives in the workspace and is rebuilt by every pass).
+ * QZO_ERR_SHAPE also when a linear of the model is too large for the kernels' 32-bit
+ * byte offsets (N*K*2 bytes of one expanded linear must stay below 2^31).
  */
 qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
                             uint32_t n_tensors, void* scale_arena_dev, uint64_t n_scales,
@@ -121,15 +129,24 @@ qzo_status qzo_model_destroy(qzo_model* m);
 /* Number of quantization scales a config has (host arithmetic only). */
 qzo_status qzo_model_scale_count(const qzo_model_config* cfg, uint64_t* out);
 
-/* Bytes of device workspace qzo_forward_loss / qzo_step need for (batch, seq). */
+/* Bytes of device workspace qzo_forward_loss / qzo_step need for (batch, seq): activations,
+ * cross-entropy partials, the RoPE angle table, K-slice partial sums, and for the
+ * expand-then-multiply route (see qzo_model_set_int4_path) one linear's perturbed weights in
+ * bf16 plus every perturbed scale of the model in fp32.  Depends on the model's int4 route and
+ * on joint mode: query it after setting those. */
 qzo_status qzo_workspace_bytes(const qzo_model* m, uint32_t batch, uint32_t seq, uint64_t* out);
 
 /*
  * One perturbed forward pass: L((Delta + sign*eps*z) (.) theta-bar; B) of Eq. 5,
  * next-token cross-entropy averaged over the batch*(seq-1) predicted positions.
- * The stored scales are not modified: the perturbed scale is formed inside the
- * GEMM's weight tile as one fp32 fma (the functional form of PERTURB_SCALES in
- * Algorithm 1).  tokens_dev: int32 [batch, seq], values in [0, vocab).
+ * The stored scales are not modified: the perturbed scale s + sign*eps*z is one fp32
+ * fma (the functional form of PERTURB_SCALES in Algorithm 1), formed inside the GEMM's
+ * weight tile on the fused route.  On the expand-then-multiply route (the default from a
+ * few thousand tokens per pass on, see qzo_model_set_int4_path) a pass first writes the
+ * perturbed scales of the whole model (fp32) and then, linear by linear, the perturbed
+ * weights (bf16) into the workspace, where they live until the next linear / pass
+ * overwrites them; z itself is never written anywhere.
+ * tokens_dev: int32 [batch, seq], values in [0, vocab).
  * loss_dev: one fp32.  seq <= max_seq.  sign must be +1 or -1.
  */
 qzo_status qzo_forward_loss(qzo_model* m, const int32_t* tokens_dev, uint32_t batch,
@@ -164,13 +181,18 @@ qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uin
  * next to the scale update, and by bringing the 16-bit tensors back to round16(theta_u).  The
  * master and the tensors must stay valid and unaliased for the model's lifetime; the caller
  * initialises the master (normally from the 16-bit tensors).  The two perturbed passes are never
- * stacked in joint mode.  Allocates a small device table (one entry per 16-bit tensor).
- * Errors: QZO_ERR_SHAPE if n_dense is not the config's count, QZO_ERR_ALIGN if the master is not
- * 16-byte aligned, QZO_ERR_ARG if joint mode is already on; qzo_step refuses a model in joint mode
- * and qzo_step_joint one that is not.
+ * stacked in joint mode.  table_dev: qzo_model_joint_table_bytes(cfg) bytes of caller-owned device
+ * memory (16-byte aligned) that receives one entry per 16-bit tensor and must stay valid and
+ * untouched for the model's lifetime; qzo_model_enable_joint fills it with a synchronous
+ * host-to-device copy (a set-up call: the only one in this library that synchronises).
+ * Errors: QZO_ERR_SHAPE if n_dense is not the config's count, QZO_ERR_ALIGN if the master or the
+ * table is not 16-byte aligned, QZO_ERR_WORKSPACE if the table is too small, QZO_ERR_ARG if joint
+ * mode is already on; qzo_step refuses a model in joint mode and qzo_step_joint one that is not.
  */
 qzo_status qzo_model_dense_count(const qzo_model_config* cfg, uint64_t* out);
-qzo_status qzo_model_enable_joint(qzo_model* m, float* dense_master_dev, uint64_t n_dense);
+qzo_status qzo_model_joint_table_bytes(const qzo_model_config* cfg, uint64_t* out);
+qzo_status qzo_model_enable_joint(qzo_model* m, float* dense_master_dev, uint64_t n_dense,
+                                  void* table_dev, uint64_t table_bytes);
 qzo_status qzo_step_joint(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
                           uint64_t seed, float eps, float eta, float eta_dense, float clip,
                           void* workspace_dev, uint64_t workspace_bytes,
@@ -187,22 +209,26 @@ qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float 
  * x_dev bf16 [M,K] row-major; q_dev packed int4 [N,K/2]; s_dev bf16 [N,K/group];
  * y_dev bf16 [M,N].  sumsq_dev (nullable): one fp32 receiving sum_{m,n} y^2 of
  * the bf16-rounded outputs.  Requires group == 128, K % 128 == 0, N % 8 == 0.
- * Uses a library-owned device scratch (per-tile partial sums, allocated on first
- * use per device) when sumsq_dev is given.
+ * scratch_dev: qzo_linear_scratch_bytes(M, N, K, sumsq_dev != NULL) bytes of caller-owned
+ * device memory, 256-byte aligned (may be NULL when that size is 0), contents undefined
+ * afterwards; calls that share a scratch buffer must not overlap.  It holds the per-tile
+ * partial sums of sum y^2 and the K-slice partial sums of the two paths below.
  * With M <= 64 the call takes the few-token path (the paper's batch-1 memory
  * profile and short-prompt batches, Sec. 4.3): the int4 weights are streamed once,
- * K is split over workgroups and the fp32 partial sums are added in slice order by
- * a second kernel (deterministic).  Its partial sums also live in a library-owned
- * scratch, grown on demand (at most 8 * M * N floats); calls on one device share it
- * and must not overlap.  Inside a model the same path uses the caller's workspace.
+ * K is split over workgroups and the fp32 partial sums (at most 8 * M * N floats) are
+ * added in slice order (deterministic).  Inside a model the same path uses the workspace.
  * With more tokens but fewer than half as many 256 x 256 output tiles as the chip has compute units,
  * the tile kernel also splits K (slices of a multiple of 256 input features, at most
- * compute units / tiles of them) and the same second kernel adds the slices, with the same scratch.
+ * compute units / tiles of them) and a second kernel adds the slices in slice order.
+ * QZO_ERR_WORKSPACE if scratch_bytes is too small, QZO_ERR_SHAPE if an operand exceeds
+ * the kernels' 32-bit byte offsets (M*K*2, N*K/2 or M*N*2 bytes >= 2^31).
  */
+qzo_status qzo_linear_scratch_bytes(uint32_t M, uint32_t N, uint32_t K, int with_sumsq, uint64_t* out);
 qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
                             uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,
                             uint32_t group, uint64_t seed, float eps, int sign, void* y_dev,
-                            float* sumsq_dev, void* stream);
+                            float* sumsq_dev, void* scratch_dev, uint64_t scratch_bytes,
+                            void* stream);
 
 /*
  * The same linear for asymmetric 4-bit groups, the format of the 4-bit checkpoints the paper
@@ -217,7 +243,8 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
 qzo_status qzo_dequant_gemm_zp(const void* x_dev, const void* q_dev, const void* s_dev,
                                const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
                                uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
-                               void* y_dev, float* sumsq_dev, void* stream);
+                               void* y_dev, float* sumsq_dev, void* scratch_dev,
+                               uint64_t scratch_bytes, void* stream);
 
 /*
  * Repacks an asymmetric 4-bit linear from the K-major layout such checkpoints are stored in:
@@ -241,11 +268,14 @@ qzo_status qzo_repack_kmajor(const void* qweight_dev, const void* qzeros_dev, co
  * x_dev bf16 [M,K]; codes_dev uint16 [N,K/8]; codebook_dev fp16 [65536,8]; c_dev fp16 [N];
  * y_dev bf16 [M,N]; sumsq_dev as in qzo_dequant_gemm.  K % 128 == 0, N % 8 == 0.  Codebook
  * entries are rounded to bf16 for the MFMA; the scale multiplies the fp32 accumulators.
+ * scratch_dev: qzo_codebook_scratch_bytes(M, N, sumsq_dev != NULL) bytes (256-byte aligned,
+ * NULL allowed when 0): one float per output tile for sum y^2.
  */
+qzo_status qzo_codebook_scratch_bytes(uint32_t M, uint32_t N, int with_sumsq, uint64_t* out);
 qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const void* codebook_dev,
                              const void* c_dev, uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,
                              uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
-                             void* stream);
+                             void* scratch_dev, uint64_t scratch_bytes, void* stream);
 /* c_n <- max(c_n - eta*d'*z_n, 0) on fp16 channel scales c_dev[n_rows], round-to-nearest-even. */
 qzo_status qzo_apply_update_channel(void* c_dev, uint32_t n_rows, uint32_t row_base, uint64_t seed,
                                     float eta, float d_clipped, void* stream);
@@ -328,13 +358,14 @@ qzo_status qzo_int4_gemm_expanded(const void* x_dev, const void* q_dev, const vo
                                   float eps, int sign, void* y_dev, void* scratch_dev,
                                   uint64_t scratch_bytes, void* stream);
 
-/* How the model's int4 linears (quant 0 and 2) run.  mode 0 (default): by size; a linear [N,K] with at
+/* How a model's int4 linears (quant 0 and 2) run.  mode 0 (default): by size; a linear [N,K] with at
  * least 2300 + 3.3e10 / (N K) tokens in a pass (2950 for 12288 x 4096) has its perturbed weights first
  * written out as a bf16 matrix in the workspace (same bits as the fused kernel's weight tile) and multiplied
  * by the plain bf16 GEMM, with fewer the fused dequantizing GEMM runs (below the break-even an expansion
  * costs more than the fused kernel's extra work).  mode 1: always the fused kernel.  mode 2: always expand-then-multiply.
- * Process-wide, not thread-safe; call it before qzo_workspace_bytes (the workspace layout depends on it). */
-qzo_status qzo_set_int4_path(int mode);
+ * A field of the model; call it before qzo_workspace_bytes (the workspace layout depends on it).
+ * QZO_ERR_ARG for another mode, QZO_ERR_UNSUPPORTED for a model whose format is not int4. */
+qzo_status qzo_model_set_int4_path(qzo_model* m, int mode);
 
 /* Inspection: the second stage of the expand-then-multiply paths on its own, Y = X W^T with a plain
  * bf16 weight matrix w_dev [N,K] (x_dev bf16 [M,K], y_dev bf16 [M,N], fp32 accumulation, no epilogue).

@@ -23,11 +23,12 @@ QZO_ERR_NONFINITE, QZO_ERR_HIP, QZO_ERR_UNSUPPORTED = -5, -6, -7
 EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update",
-    "qzo_model_dense_count", "qzo_model_enable_joint", "qzo_step_joint",
-    "qzo_dequant_gemm", "qzo_dequant_gemm_zp", "qzo_apply_update", "qzo_rtn_quantize", "qzo_repack_kmajor",
-    "qzo_int4_expand", "qzo_int4_scratch_bytes", "qzo_int4_gemm_expanded", "qzo_set_int4_path",
+    "qzo_model_dense_count", "qzo_model_joint_table_bytes", "qzo_model_enable_joint", "qzo_step_joint",
+    "qzo_linear_scratch_bytes", "qzo_dequant_gemm", "qzo_dequant_gemm_zp", "qzo_apply_update",
+    "qzo_rtn_quantize", "qzo_repack_kmajor",
+    "qzo_int4_expand", "qzo_int4_scratch_bytes", "qzo_int4_gemm_expanded", "qzo_model_set_int4_path",
     "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm",
-    "qzo_codebook_gemm", "qzo_apply_update_channel",
+    "qzo_codebook_scratch_bytes", "qzo_codebook_gemm", "qzo_apply_update_channel",
     "qzo_debug_philox", "qzo_debug_normal_pairs", "qzo_debug_normals", "qzo_debug_dequant", "qzo_debug_dequant_zp",
     "qzo_debug_forward", "qzo_debug_bf16_gemm", "qzo_debug_mfma_rate",
     "qzo_profile_begin", "qzo_profile_collect", "qzo_profile_stride",
@@ -140,9 +141,18 @@ def qzo_model_dense_count(shape: dict) -> int:
     return out.value
 
 
-def qzo_model_enable_joint(model, dense_master):
+def qzo_model_joint_table_bytes(shape: dict) -> int:
+    cfg = make_config(shape)
+    out = C.c_uint64(0)
+    _check(lib().qzo_model_joint_table_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def qzo_model_enable_joint(model, dense_master, table):
+    """table: uint8 device tensor of qzo_model_joint_table_bytes bytes, kept alive by the caller."""
     assert dense_master.dtype == torch.float32
-    _check(lib().qzo_model_enable_joint(model, _ptr(dense_master), C.c_uint64(dense_master.numel())))
+    _check(lib().qzo_model_enable_joint(model, _ptr(dense_master), C.c_uint64(dense_master.numel()),
+                                        _ptr(table), C.c_uint64(table.numel() * table.element_size())))
 
 
 def qzo_step_joint(model, tokens, seed, eps, eta, eta_dense, clip, workspace, result, stream=None):
@@ -167,22 +177,53 @@ def qzo_model_apply_update(model, seed, eta, d_clipped, stream=None):
                                         C.c_float(d_clipped), _stream(stream)))
 
 
-def qzo_dequant_gemm(x, q, s, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None):
+def qzo_linear_scratch_bytes(M, N, K, with_sumsq) -> int:
+    out = C.c_uint64(0)
+    _check(lib().qzo_linear_scratch_bytes(C.c_uint32(M), C.c_uint32(N), C.c_uint32(K), C.c_int(int(with_sumsq)),
+                                          C.byref(out)))
+    return out.value
+
+
+_scratch = {}
+
+
+def scratch_for(device, nbytes):
+    """Device-memory plumbing for the single-linear calls: one cached uint8 tensor per device, grown
+    on demand (torch allocations are 256-byte aligned).  Calls that use it must not overlap."""
+    t = _scratch.get(device)
+    if t is None or t.numel() < nbytes:
+        t = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        _scratch[device] = t
+    return t
+
+
+def _scratch_args(scratch):
+    if scratch is None:
+        return C.c_void_p(0), C.c_uint64(0)
+    return _ptr(scratch), C.c_uint64(scratch.numel() * scratch.element_size())
+
+
+def qzo_dequant_gemm(x, q, s, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None, scratch="auto"):
     M, K = x.shape
     N = q.shape[0]
+    if isinstance(scratch, str):
+        scratch = scratch_for(x.device, qzo_linear_scratch_bytes(M, N, K, sumsq is not None)) if K % 128 == 0 and K else None
     _check(lib().qzo_dequant_gemm(_ptr(x), _ptr(q), _ptr(s), C.c_uint32(row_base), C.c_uint32(M),
                                   C.c_uint32(N), C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
                                   C.c_float(eps), C.c_int(sign), _ptr(y), _ptr(sumsq),
-                                  _stream(stream)))
+                                  *_scratch_args(scratch), _stream(stream)))
 
 
-def qzo_dequant_gemm_zp(x, q, s, zp, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None):
+def qzo_dequant_gemm_zp(x, q, s, zp, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None,
+                        scratch="auto"):
     M, K = x.shape
     N = q.shape[0]
+    if isinstance(scratch, str):
+        scratch = scratch_for(x.device, qzo_linear_scratch_bytes(M, N, K, sumsq is not None)) if K % 128 == 0 and K else None
     _check(lib().qzo_dequant_gemm_zp(_ptr(x), _ptr(q), _ptr(s), _ptr(zp), C.c_uint32(row_base),
                                      C.c_uint32(M), C.c_uint32(N), C.c_uint32(K), C.c_uint32(group),
                                      C.c_uint64(seed), C.c_float(eps), C.c_int(sign), _ptr(y),
-                                     _ptr(sumsq), _stream(stream)))
+                                     _ptr(sumsq), *_scratch_args(scratch), _stream(stream)))
 
 
 def qzo_repack_kmajor(qweight, qzeros, scales, zero_add, q, zp, s, group=128, stream=None):
@@ -272,8 +313,8 @@ def qzo_nf4_gemm(x, q, s, row_base, seed, eps, sign, y, scratch, stream=None):
                               _stream(stream)))
 
 
-def qzo_set_int4_path(mode: int):
-    _check(lib().qzo_set_int4_path(C.c_int(mode)))
+def qzo_model_set_int4_path(model, mode: int):
+    _check(lib().qzo_model_set_int4_path(model, C.c_int(mode)))
 
 
 def qzo_debug_bf16_gemm(x, w, y, pipe=2, stream=None):
@@ -324,12 +365,22 @@ def qzo_profile_collect(kind: int) -> dict:
     return dict(total_ms=ms.value, launches=n.value, work=work.value)
 
 
-def qzo_codebook_gemm(x, codes, codebook, c, row_base, seed, eps, sign, y, sumsq=None, stream=None):
+def qzo_codebook_scratch_bytes(M, N, with_sumsq) -> int:
+    out = C.c_uint64(0)
+    _check(lib().qzo_codebook_scratch_bytes(C.c_uint32(M), C.c_uint32(N), C.c_int(int(with_sumsq)), C.byref(out)))
+    return out.value
+
+
+def qzo_codebook_gemm(x, codes, codebook, c, row_base, seed, eps, sign, y, sumsq=None, stream=None,
+                      scratch="auto"):
     M, K = x.shape
     N = codes.shape[0]
+    if isinstance(scratch, str):
+        scratch = scratch_for(x.device, qzo_codebook_scratch_bytes(M, N, sumsq is not None))
     _check(lib().qzo_codebook_gemm(_ptr(x), _ptr(codes), _ptr(codebook), _ptr(c), C.c_uint32(row_base),
                                    C.c_uint32(M), C.c_uint32(N), C.c_uint32(K), C.c_uint64(seed),
-                                   C.c_float(eps), C.c_int(sign), _ptr(y), _ptr(sumsq), _stream(stream)))
+                                   C.c_float(eps), C.c_int(sign), _ptr(y), _ptr(sumsq),
+                                   *_scratch_args(scratch), _stream(stream)))
 
 
 def qzo_apply_update_channel(c, row_base, seed, eta, d_clipped, stream=None):

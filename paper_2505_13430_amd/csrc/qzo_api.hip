@@ -31,6 +31,10 @@ qzo_status hip_fail(hipError_t e, const char* what) {
   } while (0)
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// The GEMM kernels address X [M,K], a bf16 W [N,K] and Y [M,N] with 32-bit byte offsets.
+bool bf16_gemm_fits(uint64_t M, uint64_t N, uint64_t K) {
+  return M * K * 2 < (1ull << 31) && N * K * 2 < (1ull << 31) && M * N * 2 < (1ull << 31);
+}
 uint64_t up256(uint64_t x) { return (x + 255u) & ~uint64_t(255); }
 
 struct Linear {           // one quantized linear of a layer
@@ -39,16 +43,13 @@ struct Linear {           // one quantized linear of a layer
   uint32_t row_base;      // first noise row within the layer
 };
 
-// int4 linears: 0 = expand-then-multiply from expand_min_m_int4(N, K) tokens on, 1 = always the fused
-// kernel, 2 = always expand-then-multiply
-int g_int4_path = 0;
-
 struct Workspace {
   unsigned char *h, *a, *qkv, *att, *ff, *act;
   float *ce_part, *tgt, *rowloss, *losses, *skinny;
   float* split;             // K-slice partial sums of the int4 tile kernel (too few tiles for the chip)
   unsigned char* wexp;      // one linear's expanded bf16 weights (expand-then-multiply paths)
   float* se;                // expand-then-multiply of int4 / NormalFloat-4: every perturbed scale of the model, fp32
+  float* rope;              // Llama: (cos, sin) of every (position < seq, pair of the head), rebuilt by every pass
   uint64_t total;
 };
 
@@ -63,12 +64,14 @@ struct qzo_model {
   uint64_t scales_per_layer;
   uint32_t rows_per_layer;
   UpdPlan plan;
-  float* rope_table;      // device, Llama only
   uint32_t tensors_per_layer, first_layer_tensor;
+  // int4 linears: 0 = expand-then-multiply from expand_min_m_int4(N, K) tokens on, 1 = always the
+  // fused kernel, 2 = always expand-then-multiply
+  int int4_path = 0;
   // joint SPSA on the un-quantized parameters (off until qzo_model_enable_joint)
   float* dense_master = nullptr;       // caller-owned fp32 [n_dense]
   uint64_t n_dense = 0;
-  DenseSeg* dense_segs = nullptr;      // device, library-owned
+  DenseSeg* dense_segs = nullptr;      // device, caller-owned (qzo_model_enable_joint's table_dev)
   uint32_t n_dense_segs = 0;
 };
 
@@ -215,8 +218,8 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   uint64_t ex = 0, sx = 0;
   for (int i = 0; i < 4; ++i) {
     const bool expanded = c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK) ||
-                          (int4 && g_int4_path != 1 && !stack &&
-                           (g_int4_path == 2 || M1 >= expand_min_m_int4(m->lin[i].N, m->lin[i].K)));
+                          (int4 && m->int4_path != 1 && !stack &&
+                           (m->int4_path == 2 || M1 >= expand_min_m_int4(m->lin[i].N, m->lin[i].K)));
     if (expanded) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
   }
   if (ex && c.quant != 1) sx = m->n_scales * 4;     // every perturbed scale of the model, fp32
@@ -224,6 +227,7 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   if (ex == 0) w.wexp = nullptr;
   w.se = (float*)take(sx);
   if (sx == 0) w.se = nullptr;
+  w.rope = c.arch == 0 ? (float*)take((uint64_t)seq * (c.d_model / c.n_heads / 2) * 8) : nullptr;
   w.total = off;
   return w;
 }
@@ -236,6 +240,15 @@ qzo_status check_batch(const qzo_model* m, const void* tok, uint32_t batch, uint
   if (batch == 0 || seq < 2) return fail(QZO_ERR_SHAPE, "need batch >= 1 and seq >= 2");
   if (seq > m->cfg.max_seq) return fail(QZO_ERR_SHAPE, "seq exceeds max_seq");
   if ((uint64_t)batch * seq > 0x7fffffffull) return fail(QZO_ERR_SHAPE, "batch*seq too large");
+  {
+    // the kernels address every operand with 32-bit byte offsets: tokens x widest tensor row, in
+    // bf16, must stay below 2^31 bytes (stacked passes have at most 64 tokens)
+    const qzo_model_config& c = m->cfg;
+    const uint64_t M1 = (uint64_t)batch * seq;
+    const uint64_t widest = std::max<uint64_t>({3ull * c.d_model, (c.arch == 0 ? 2ull : 1ull) * c.d_ffn});
+    if (M1 * widest * 2 >= (1ull << 31))
+      return fail(QZO_ERR_SHAPE, "batch*seq too large for this model: an activation tensor would exceed 2^31 bytes");
+  }
   Workspace w = carve(m, batch, seq, nullptr);
   if (ws_bytes < w.total) return fail(QZO_ERR_WORKSPACE, "workspace smaller than qzo_workspace_bytes");
   return QZO_OK;
@@ -294,6 +307,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   }
   {
     ProfScope ps(PK_OTHER, 0, st);
+    if (llama) QZO_HIP(launch_rope_table(w.rope, seq, dh, c.rope_theta, st));
     QZO_HIP(launch_embed(tok, M1, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
   }
   const double attn_flops = 2.0 * batch * H * (double)seq * seq * dh;   // causal: half of 4 B H S^2 dh
@@ -338,8 +352,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
-      if (w.wexp && g_int4_path != 1 && n_pass == 1 &&
-          (g_int4_path == 2 || M >= expand_min_m_int4(g.N, g.K))) {
+      if (w.wexp && m->int4_path != 1 && n_pass == 1 &&
+          (m->int4_path == 2 || M >= expand_min_m_int4(g.N, g.K))) {
         // many tokens: write the perturbed matrix out once, then a plain bf16 GEMM
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
@@ -384,7 +398,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       // attn_norm, codes/cb qkv, codes/cb o, ffn_norm, codes/cb gate+up, codes/cb down
       QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(cgemm(0, w.a, T[1].ptr_dev, T[2].ptr_dev, nullptr, w.qkv, 0));
-      QZO_HIP(launch_rope(w.qkv, m->rope_table, batch, seq, d, H, st));
+      QZO_HIP(launch_rope(w.qkv, w.rope, batch, seq, d, H, st));
       {
         ProfScope ps(PK_ATTN, attn_flops, st);
         QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
@@ -397,7 +411,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       // attn_norm, wqkv, wo, ffn_norm, wgu, wdown (symmetric-table positions)
       QZO_HIP(launch_rmsnorm(w.h, ti(0), M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(0, w.a, nullptr, nullptr, w.qkv, 0));
-      QZO_HIP(launch_rope(w.qkv, m->rope_table, batch, seq, d, H, st));
+      QZO_HIP(launch_rope(w.qkv, w.rope, batch, seq, d, H, st));
       {
         ProfScope ps(PK_ATTN, attn_flops, st);
         QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
@@ -444,11 +458,6 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
                              w.rowloss + M1, loss_out2, st));
   return QZO_OK;
 }
-
-float* g_partials = nullptr;     // library-owned scratch of qzo_dequant_gemm's sum of squares
-uint32_t g_partials_n = 0;
-float* g_skinny = nullptr;       // library-owned scratch of qzo_dequant_gemm's few-token path
-uint64_t g_skinny_n = 0;
 
 }  // namespace
 
@@ -511,19 +520,16 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
   m->rows_per_layer = m->lin[3].row_base + m->lin[3].N;
   m->tensors_per_layer = per_layer;
   m->first_layer_tensor = head;
-  m->rope_table = nullptr;
   st = build_plan(m->lin, 4, cfg->n_layers, m->plan, cfg->group_size);
   if (st != QZO_OK) { delete m; return st; }
-  if (llama) {
-    const uint32_t dh = cfg->d_model / cfg->n_heads;
-    hipError_t e = hipMalloc((void**)&m->rope_table, (size_t)cfg->max_seq * (dh / 2) * 8);
-    if (e == hipSuccess) e = launch_rope_table(m->rope_table, cfg->max_seq, dh, cfg->rope_theta, nullptr);
-    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
-    if (e != hipSuccess) {
-      if (m->rope_table) (void)hipFree(m->rope_table);
+  for (int i = 0; i < 4; ++i)       // one linear written out in bf16 must fit 32-bit byte offsets
+    if ((uint64_t)m->lin[i].N * m->lin[i].K * 2 >= (1ull << 31)) {
       delete m;
-      return hip_fail(e, "RoPE table");
+      return fail(QZO_ERR_SHAPE, "a linear of this model exceeds 2^31 bytes in bf16");
     }
+  if ((uint64_t)cfg->vocab * cfg->d_model * 2 >= (1ull << 31)) {
+    delete m;
+    return fail(QZO_ERR_SHAPE, "lm_head exceeds 2^31 bytes");
   }
   *out = m;
   return QZO_OK;
@@ -531,8 +537,6 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
 
 qzo_status qzo_model_destroy(qzo_model* m) {
   if (!m) return QZO_OK;
-  if (m->rope_table) (void)hipFree(m->rope_table);
-  if (m->dense_segs) (void)hipFree(m->dense_segs);
   delete m;
   return QZO_OK;
 }
@@ -551,10 +555,25 @@ qzo_status qzo_model_dense_count(const qzo_model_config* cfg, uint64_t* out) {
   return QZO_OK;
 }
 
-qzo_status qzo_model_enable_joint(qzo_model* m, float* dense_master_dev, uint64_t n_dense) {
-  if (!m || !dense_master_dev) return fail(QZO_ERR_ARG, "null argument");
+qzo_status qzo_model_joint_table_bytes(const qzo_model_config* cfg, uint64_t* out) {
+  qzo_status st = check_cfg(cfg);
+  if (st != QZO_OK) return st;
+  if (!out) return fail(QZO_ERR_ARG, "out is null");
+  std::vector<uint64_t> need;
+  std::vector<uint8_t> kind;
+  table_layout(*cfg, need, kind);
+  uint64_t n = 0;
+  for (size_t i = 0; i < need.size(); ++i) n += kind[i] != 2;
+  *out = up256(n * sizeof(DenseSeg));
+  return QZO_OK;
+}
+
+qzo_status qzo_model_enable_joint(qzo_model* m, float* dense_master_dev, uint64_t n_dense, void* table_dev,
+                                  uint64_t table_bytes) {
+  if (!m || !dense_master_dev || !table_dev) return fail(QZO_ERR_ARG, "null argument");
   if (m->dense_master) return fail(QZO_ERR_ARG, "joint mode is already on");
-  if (!aligned16(dense_master_dev)) return fail(QZO_ERR_ALIGN, "dense master not 16-byte aligned");
+  if (!aligned16(dense_master_dev) || !aligned16(table_dev))
+    return fail(QZO_ERR_ALIGN, "dense master or table not 16-byte aligned");
   uint64_t want = 0;
   qzo_model_dense_count(&m->cfg, &want);
   if (n_dense != want) return fail(QZO_ERR_SHAPE, "n_dense does not match the config");
@@ -574,13 +593,10 @@ qzo_status qzo_model_enable_joint(qzo_model* m, float* dense_master_dev, uint64_
     segs.push_back(sg);
     first += n;
   }
-  QZO_HIP(hipMalloc((void**)&m->dense_segs, segs.size() * sizeof(DenseSeg)));
-  hipError_t e = hipMemcpy(m->dense_segs, segs.data(), segs.size() * sizeof(DenseSeg), hipMemcpyHostToDevice);
-  if (e != hipSuccess) {
-    (void)hipFree(m->dense_segs);
-    m->dense_segs = nullptr;
-    return hip_fail(e, "dense segment table");
-  }
+  if (table_bytes < segs.size() * sizeof(DenseSeg))
+    return fail(QZO_ERR_WORKSPACE, "table smaller than qzo_model_joint_table_bytes");
+  QZO_HIP(hipMemcpy(table_dev, segs.data(), segs.size() * sizeof(DenseSeg), hipMemcpyHostToDevice));
+  m->dense_segs = (DenseSeg*)table_dev;
   m->n_dense_segs = (uint32_t)segs.size();
   m->n_dense = n_dense;
   m->dense_master = dense_master_dev;
@@ -708,10 +724,23 @@ qzo_status qzo_apply_update(void* s_dev, uint32_t n_rows, uint32_t G, uint32_t r
   return QZO_OK;
 }
 
-static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
-                               const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
-                               uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
-                               void* y_dev, float* sumsq_dev, void* stream) {
+// Scratch of a single perturbed linear: [per-tile sums of y^2][K-slice partial sums], each part
+// rounded up to 256 bytes.
+struct LinearScratch { uint32_t tiles; uint64_t part_floats; uint64_t part_off, total; bool skinny, split; };
+static LinearScratch linear_scratch(uint32_t M, uint32_t N, uint32_t K, bool with_sumsq) {
+  LinearScratch ls = {};
+  if (M == 0 || N == 0) return ls;
+  ls.skinny = M <= SKINNY_MAX_M;
+  ls.split = !ls.skinny && tile_ksplit(M, N, K, nullptr) > 1;     // too few tiles for the chip
+  ls.tiles = (ls.skinny || ls.split) ? skinny_reduce_blocks(M, N, 0) : ((M + 255) / 256) * ((N + 255) / 256);
+  ls.part_floats = ls.skinny ? skinny_ws_floats(M, N, K) : (ls.split ? tile_split_ws_floats(M, N, K) : 0);
+  ls.part_off = with_sumsq ? up256((uint64_t)ls.tiles * 4) : 0;
+  ls.total = ls.part_off + up256(ls.part_floats * 4);
+  return ls;
+}
+
+static qzo_status linear_check(const void* x_dev, const void* q_dev, const void* s_dev, const void* y_dev,
+                               uint32_t M, uint32_t N, uint32_t K, uint32_t group, float eps, int sign) {
   if (!x_dev || !q_dev || !s_dev || !y_dev) return fail(QZO_ERR_ARG, "null device pointer");
   if (!aligned16(x_dev) || !aligned16(q_dev) || !aligned16(s_dev) || !aligned16(y_dev))
     return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
@@ -720,7 +749,18 @@ static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void*
   if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
   if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
   if (!std::isfinite(eps)) return fail(QZO_ERR_ARG, "eps not finite");
-  hipStream_t st = (hipStream_t)stream;
+  // buffer loads and stores address each operand with 32-bit byte offsets
+  if ((uint64_t)M * K * 2 >= (1ull << 31) || (uint64_t)N * K / 2 >= (1ull << 31) ||
+      (uint64_t)M * N * 2 >= (1ull << 31))
+    return fail(QZO_ERR_SHAPE, "an operand exceeds 2^31 bytes");
+  return QZO_OK;
+}
+
+// The launches of a single perturbed linear; scratch (ls.total bytes) is known to be large enough.
+static qzo_status dequant_gemm_run(const void* x_dev, const void* q_dev, const void* s_dev, const void* zp_dev,
+                                   uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint64_t seed,
+                                   float eps, int sign, void* y_dev, float* sumsq_dev, void* scratch,
+                                   const LinearScratch& ls, hipStream_t st) {
   if (M == 0 || N == 0) {
     if (sumsq_dev) QZO_HIP(launch_sum_partials(nullptr, 0, sumsq_dev, st));
     return QZO_OK;
@@ -730,51 +770,58 @@ static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void*
   g.M = M; g.N = N; g.K = K; g.row_base = row_base;
   g.seed_lo = (uint32_t)seed; g.seed_hi = (uint32_t)(seed >> 32);
   g.eps_signed = sign > 0 ? eps : -eps;
-  const bool skinny = M <= SKINNY_MAX_M;
-  const bool split = !skinny && tile_ksplit(M, N, K, nullptr) > 1;     // too few tiles for the chip
-  const uint32_t tiles = (skinny || split) ? skinny_reduce_blocks(M, N, 0) : ((M + 255) / 256) * ((N + 255) / 256);
-  if (skinny || split) {     // library-owned scratch for the K-slice partial sums, grown on demand
-    const uint64_t need = skinny ? skinny_ws_floats(M, N, K) : tile_split_ws_floats(M, N, K);
-    if (g_skinny_n < need) {
-      if (g_skinny) (void)hipFree(g_skinny);
-      g_skinny = nullptr;
-      g_skinny_n = 0;
-      QZO_HIP(hipMalloc((void**)&g_skinny, (size_t)need * sizeof(float)));
-      g_skinny_n = need;
-    }
-    if (skinny) g.skinny_ws = g_skinny; else g.split_ws = g_skinny;
-  }
+  float* part = (float*)((unsigned char*)scratch + ls.part_off);
+  if (ls.skinny) g.skinny_ws = part;
+  if (ls.split) g.split_ws = part;
   if (sumsq_dev) {
-    if (g_partials_n < tiles) {
-      if (g_partials) (void)hipFree(g_partials);
-      g_partials = nullptr;
-      g_partials_n = 0;
-      QZO_HIP(hipMalloc((void**)&g_partials, (size_t)tiles * sizeof(float)));
-      g_partials_n = tiles;
-    }
     g.epi = EPI_SUMSQ;
-    g.partials = g_partials;
+    g.partials = (float*)scratch;
   }
   QZO_HIP(launch_w4a16_gemm(g, st));
-  if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  if (sumsq_dev) QZO_HIP(launch_sum_partials((const float*)scratch, ls.tiles, sumsq_dev, st));
+  return QZO_OK;
+}
+
+static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
+                               const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
+                               uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                               void* y_dev, float* sumsq_dev, void* scratch_dev, uint64_t scratch_bytes,
+                               void* stream) {
+  qzo_status st = linear_check(x_dev, q_dev, s_dev, y_dev, M, N, K, group, eps, sign);
+  if (st != QZO_OK) return st;
+  const LinearScratch ls = linear_scratch(M, N, K, sumsq_dev != nullptr);
+  if (ls.total) {
+    if (!scratch_dev) return fail(QZO_ERR_ARG, "scratch_dev is null");
+    if ((uintptr_t)scratch_dev & 255u) return fail(QZO_ERR_ALIGN, "scratch not 256-byte aligned");
+    if (scratch_bytes < ls.total) return fail(QZO_ERR_WORKSPACE, "scratch too small: see qzo_linear_scratch_bytes");
+  }
+  return dequant_gemm_run(x_dev, q_dev, s_dev, zp_dev, row_base, M, N, K, seed, eps, sign, y_dev, sumsq_dev,
+                          scratch_dev, ls, (hipStream_t)stream);
+}
+
+qzo_status qzo_linear_scratch_bytes(uint32_t M, uint32_t N, uint32_t K, int with_sumsq, uint64_t* out) {
+  if (!out) return fail(QZO_ERR_ARG, "out is null");
+  if (K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "K must be a positive multiple of 128");
+  *out = linear_scratch(M, N, K, with_sumsq != 0).total;
   return QZO_OK;
 }
 
 qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
                             uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint32_t group,
                             uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
-                            void* stream) {
+                            void* scratch_dev, uint64_t scratch_bytes, void* stream) {
   return dequant_gemm(x_dev, q_dev, s_dev, nullptr, row_base, M, N, K, group, seed, eps, sign, y_dev,
-                      sumsq_dev, stream);
+                      sumsq_dev, scratch_dev, scratch_bytes, stream);
 }
 
 qzo_status qzo_dequant_gemm_zp(const void* x_dev, const void* q_dev, const void* s_dev,
                                const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
                                uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
-                               void* y_dev, float* sumsq_dev, void* stream) {
+                               void* y_dev, float* sumsq_dev, void* scratch_dev, uint64_t scratch_bytes,
+                               void* stream) {
   if (!zp_dev) return fail(QZO_ERR_ARG, "zp_dev is null");
   return dequant_gemm(x_dev, q_dev, s_dev, zp_dev, row_base, M, N, K, group, seed, eps, sign, y_dev,
-                      sumsq_dev, stream);
+                      sumsq_dev, scratch_dev, scratch_bytes, stream);
 }
 
 qzo_status qzo_repack_kmajor(const void* qweight_dev, const void* qzeros_dev, const void* scales_dev,
@@ -791,10 +838,16 @@ qzo_status qzo_repack_kmajor(const void* qweight_dev, const void* qzeros_dev, co
   return QZO_OK;
 }
 
+qzo_status qzo_codebook_scratch_bytes(uint32_t M, uint32_t N, int with_sumsq, uint64_t* out) {
+  if (!out) return fail(QZO_ERR_ARG, "out is null");
+  *out = (with_sumsq && M && N) ? up256((uint64_t)((M + 255) / 256) * ((N + 255) / 256) * 4) : 0;
+  return QZO_OK;
+}
+
 qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const void* codebook_dev,
                              const void* c_dev, uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,
                              uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
-                             void* stream) {
+                             void* scratch_dev, uint64_t scratch_bytes, void* stream) {
   if (!x_dev || !codes_dev || !codebook_dev || !c_dev || !y_dev) return fail(QZO_ERR_ARG, "null device pointer");
   if (!aligned16(x_dev) || !aligned16(codes_dev) || !aligned16(codebook_dev) || !aligned16(c_dev) ||
       !aligned16(y_dev))
@@ -803,6 +856,16 @@ qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const voi
   if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
   if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
   if (!std::isfinite(eps)) return fail(QZO_ERR_ARG, "eps not finite");
+  if ((uint64_t)M * K * 2 >= (1ull << 31) || (uint64_t)N * K / 4 >= (1ull << 31) ||
+      (uint64_t)M * N * 2 >= (1ull << 31))
+    return fail(QZO_ERR_SHAPE, "an operand exceeds 2^31 bytes");
+  uint64_t need = 0;
+  qzo_codebook_scratch_bytes(M, N, sumsq_dev != nullptr, &need);
+  if (need) {
+    if (!scratch_dev) return fail(QZO_ERR_ARG, "scratch_dev is null");
+    if ((uintptr_t)scratch_dev & 255u) return fail(QZO_ERR_ALIGN, "scratch not 256-byte aligned");
+    if (scratch_bytes < need) return fail(QZO_ERR_WORKSPACE, "scratch too small: see qzo_codebook_scratch_bytes");
+  }
   hipStream_t st = (hipStream_t)stream;
   if (M == 0 || N == 0) {
     if (sumsq_dev) QZO_HIP(launch_sum_partials(nullptr, 0, sumsq_dev, st));
@@ -815,18 +878,11 @@ qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const voi
   g.eps_signed = sign > 0 ? eps : -eps;
   const uint32_t tiles = ((M + 255) / 256) * ((N + 255) / 256);
   if (sumsq_dev) {
-    if (g_partials_n < tiles) {
-      if (g_partials) (void)hipFree(g_partials);
-      g_partials = nullptr;
-      g_partials_n = 0;
-      QZO_HIP(hipMalloc((void**)&g_partials, (size_t)tiles * sizeof(float)));
-      g_partials_n = tiles;
-    }
     g.epi = EPI_SUMSQ;
-    g.partials = g_partials;
+    g.partials = (float*)scratch_dev;
   }
   QZO_HIP(launch_codebook_gemm(g, st));
-  if (sumsq_dev) QZO_HIP(launch_sum_partials(g_partials, tiles, sumsq_dev, st));
+  if (sumsq_dev) QZO_HIP(launch_sum_partials((const float*)scratch_dev, tiles, sumsq_dev, st));
   return QZO_OK;
 }
 
@@ -874,6 +930,7 @@ qzo_status qzo_int4_gemm_expanded(const void* x_dev, const void* q_dev, const vo
   uint64_t need = 0;
   qzo_int4_scratch_bytes(N, K, &need);
   if (scratch_bytes < need) return fail(QZO_ERR_WORKSPACE, "scratch too small: see qzo_int4_scratch_bytes");
+  if (!bf16_gemm_fits(M, N, K)) return fail(QZO_ERR_SHAPE, "an operand exceeds 2^31 bytes");
   if (M == 0 || N == 0) return QZO_OK;
   hipStream_t s = (hipStream_t)stream;
   unsigned char* wexp = (unsigned char*)scratch_dev;
@@ -926,6 +983,7 @@ qzo_status qzo_nf4_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
   uint64_t need = 0;
   qzo_nf4_scratch_bytes(N, K, &need);
   if (scratch_bytes < need) return fail(QZO_ERR_WORKSPACE, "scratch too small: see qzo_nf4_scratch_bytes");
+  if (!bf16_gemm_fits(M, N, K)) return fail(QZO_ERR_SHAPE, "an operand exceeds 2^31 bytes");
   if (M == 0 || N == 0) return QZO_OK;
   hipStream_t s = (hipStream_t)stream;
   unsigned char* wexp = (unsigned char*)scratch_dev;
@@ -938,9 +996,11 @@ qzo_status qzo_nf4_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
   return QZO_OK;
 }
 
-qzo_status qzo_set_int4_path(int mode) {
+qzo_status qzo_model_set_int4_path(qzo_model* m, int mode) {
+  if (!m) return fail(QZO_ERR_ARG, "model is null");
   if (mode < 0 || mode > 2) return fail(QZO_ERR_ARG, "mode must be 0 (by token count), 1 (fused) or 2 (expanded)");
-  g_int4_path = mode;
+  if (m->cfg.quant != 0 && m->cfg.quant != 2) return fail(QZO_ERR_UNSUPPORTED, "the model's format is not int4");
+  m->int4_path = mode;
   return QZO_OK;
 }
 
@@ -952,6 +1012,7 @@ qzo_status qzo_debug_bf16_gemm(const void* x_dev, const void* w_dev, uint32_t M,
   if (K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "K must be a positive multiple of 128");
   if (N % 8) return fail(QZO_ERR_SHAPE, "N must be a multiple of 8");
   if (pipe < 0 || pipe > 2) return fail(QZO_ERR_ARG, "pipe must be 0, 1 or 2");
+  if (!bf16_gemm_fits(M, N, K)) return fail(QZO_ERR_SHAPE, "an operand exceeds 2^31 bytes");
   GemmArgs g = {};
   g.x = x_dev; g.w = w_dev; g.y = y_dev; g.M = M; g.N = N; g.K = K;
   QZO_HIP(launch_bf16_gemm(g, pipe, (hipStream_t)stream));

@@ -169,7 +169,9 @@ class DeviceModel:
         parts = [t.reshape(-1) for t in self.tensors if t.dtype in (torch.bfloat16, torch.float16)]
         self.dense_master = torch.cat(parts).to(torch.float32)       # a copy: dtype conversion only
         assert self.dense_master.numel() == qb.qzo_model_dense_count(self.shape)
-        qb.qzo_model_enable_joint(self.handle, self.dense_master)
+        self.joint_table = torch.empty(qb.qzo_model_joint_table_bytes(self.shape), dtype=torch.uint8,
+                                       device=self.scales.device)
+        qb.qzo_model_enable_joint(self.handle, self.dense_master, self.joint_table)
         self._ws = None                                              # the workspace layout may differ
         self._ws_key = None
         return self.dense_master
@@ -178,6 +180,12 @@ class DeviceModel:
         ws = self.workspace(*tokens.shape)
         qb.qzo_step_joint(self.handle, tokens, seed, eps, eta, eta_dense, clip, ws, self.result, stream)
         return self.result
+
+    def set_int4_path(self, mode: int):
+        """0: by token count, 1: always the fused kernel, 2: always expand-then-multiply."""
+        qb.qzo_model_set_int4_path(self.handle, mode)
+        self._ws = None                                              # the workspace layout depends on it
+        self._ws_key = None
 
     def apply_update(self, seed, eta, d_clipped, stream=None):
         qb.qzo_model_apply_update(self.handle, seed, eta, d_clipped, stream)

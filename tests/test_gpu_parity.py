@@ -203,7 +203,8 @@ SHARP = dict(arch="llama", n_layers=2, d_model=256, n_heads=2, d_ffn=512, vocab=
              batch=3, seq=80)     # head size 128, ragged vocab, seq not a multiple of 32/128
 
 
-def _models(oracle, shape, seed, gain=1.0, asym=False, nf4=False):
+def _models(oracle, shape, seed, gain=1.0, asym=False, nf4=False, route=None):
+    """route: None = the library's choice by token count, 1 = fused kernel, 2 = expand-then-multiply."""
     table = synth.tensor_table(shape, seed)
     if gain != 1.0:   # larger weights: logits far from uniform, loss far from ln V
         table = [(n, k, synth.bf16_exact(a * gain) if (k == "w" or n in ("tok_emb", "lm_head")) else a)
@@ -212,32 +213,39 @@ def _models(oracle, shape, seed, gain=1.0, asym=False, nf4=False):
         table = [(n, k, (a + 0.03 * gain * np.sin(np.arange(a.shape[0]))[:, None]).astype(np.float32)
                   if k == "w" else a) for n, k, a in table]
     om = oracle.build_model(shape, table, asym=asym, nf4=nf4)
-    return om, DeviceModel.from_host(dict(shape, quant=om.quant, group=om.group), om.tensors, om.scales, DEV)
+    dm = DeviceModel.from_host(dict(shape, quant=om.quant, group=om.group), om.tensors, om.scales, DEV)
+    if route is not None:
+        dm.set_int4_path(route)
+    return om, dm
 
-
-@pytest.fixture(autouse=True)
-def _int4_route(request):
-    """Cases named many_* take the expand-then-multiply route at their 576 tokens."""
-    cid = getattr(getattr(request.node, "callspec", None), "id", "") or ""
-    if "many_" in cid:
-        qb.qzo_set_int4_path(2)
-        yield
-        qb.qzo_set_int4_path(0)
-    else:
-        yield
 
 
 def _case(name):
     """'<shape>', '<shape>+zp' (zero-points) or '<shape>+nf4' (NormalFloat-4) -> (shape, variant flag)."""
     base, _, var = name.partition("+")
-    shape = SHARP if base == "sharp" else (FEW.get(base) or MANY.get(base) or synth.SHAPES[base])
+    shape = SHARP if base == "sharp" else (FEW.get(base) or MANY.get(base) or LONG.get(base) or synth.SHAPES[base])
     return shape, {"": False, "zp": True, "nf4": "nf4"}[var]
 
 
-# 576 tokens with qzo_set_int4_path(2): the int4 linears run expand-then-multiply (by default only
-# from several thousand tokens on, more than the oracle handles in a test)
+def _route(name):
+    """Cases named many_* force the expand-then-multiply route (mode 2) on their model."""
+    return 2 if name.startswith("many_") else None
+
+
+# 576 tokens with the model's int4 route set to 2: the int4 linears run expand-then-multiply (by default
+# only from several thousand tokens on, more than the oracle handles in a test)
 MANY = {"many_llama": dict(synth.SHAPES["tiny"], batch=9, seq=64),
         "many_opt": dict(synth.SHAPES["tiny_opt"], batch=9, seq=64)}
+# Sequences as long as the benchmark's: the attention kernel's steady state (a key tile refills an LDS
+# buffer that was already read, loads run two tiles ahead, several 128-query blocks per sequence that
+# are dispatched last-first).  long_llama: head size 128, 512 positions = 8 key tiles, 4 query blocks;
+# long_opt: head size 64, 256 positions; long_ragged: 300 positions (a ragged last query block and key tile)
+LONG = {"long_llama": dict(arch="llama", n_layers=2, d_model=256, n_heads=2, d_ffn=512, vocab=520, max_seq=512,
+                           batch=2, seq=512),
+        "long_opt": dict(arch="opt", n_layers=2, d_model=256, n_heads=4, d_ffn=512, vocab=520, max_seq=256,
+                         batch=3, seq=256),
+        "long_ragged": dict(arch="llama", n_layers=1, d_model=256, n_heads=2, d_ffn=512, vocab=520, max_seq=320,
+                            batch=2, seq=300)}
 FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tokens: one token tile
        "few_opt": dict(synth.SHAPES["tiny_opt"], batch=2, seq=32)}      # 64 tokens: two token tiles
 
@@ -248,10 +256,12 @@ FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tok
                                        ("few_llama+zp", 4.0), ("few_opt+zp", 1.0),
                                        ("tiny+nf4", 4.0), ("tiny_opt+nf4", 4.0), ("sharp+nf4", 4.0),
                                        ("few_llama+nf4", 1.0),
-                                       ("many_llama", 4.0), ("many_opt", 4.0), ("many_llama+zp", 4.0)])
+                                       ("many_llama", 4.0), ("many_opt", 4.0), ("many_llama+zp", 4.0),
+                                       ("long_llama", 4.0), ("long_opt", 4.0), ("long_ragged", 4.0),
+                                       ("long_llama+zp", 1.0)])
 def test_forward_matches_oracle(oracle, name, gain):
     shape, asym = _case(name)
-    om, dm = _models(oracle, shape, 1234, gain, asym is True, asym == "nf4")
+    om, dm = _models(oracle, shape, 1234, gain, asym is True, asym == "nf4", route=_route(name))
     if asym is True:
         zps = np.concatenate([t.reshape(-1) for n, t in zip(om.names, om.tensors) if n.endswith(".zp")])
         assert zps.min() <= 3 and zps.max() >= 12
@@ -286,13 +296,23 @@ def test_forward_matches_oracle(oracle, name, gain):
     dm.close()
 
 
+def _d_noise_floor(oracle, om, tok, seeds, eps=1e-3):
+    """What the oracle's own projected gradient d = (l+ - l-)/(2 eps) (Eq. 5, Algorithm 1) moves by when
+    its 16-bit activation rounding is switched off, largest over a few directions: the size of the
+    rounding noise that 1/(2 eps) = 500 amplifies into d."""
+    return max(abs(oracle.qzo_step(om, tok, seed=sd, eps=eps, eta=0.0, Cthr=1e9)["d"] -
+                   oracle.qzo_step(om, tok, seed=sd, eps=eps, eta=0.0, Cthr=1e9, act_bf16=False)["d"])
+               for sd in seeds)
+
+
 @pytest.mark.parametrize("name", ["tiny", "tiny_opt", "few_llama", "few_opt",
                                   "tiny+zp", "tiny_opt+zp", "few_llama+zp", "few_opt+zp",
                                   "tiny+nf4", "tiny_opt+nf4", "few_llama+nf4",
-                                  "many_llama", "many_opt", "many_llama+zp"])
+                                  "many_llama", "many_opt", "many_llama+zp",
+                                  "long_llama", "long_opt", "long_ragged"])
 def test_step_matches_oracle(oracle, name):
     shape, asym = _case(name)
-    om, dm = _models(oracle, shape, 1234, asym=asym is True, nf4=asym == "nf4")
+    om, dm = _models(oracle, shape, 1234, asym=asym is True, nf4=asym == "nf4", route=_route(name))
     tok = synth.tokens(shape, 5678)
     tokd = _dev(tok)
     # NormalFloat-4 scales are a block's absmax, ten times larger (the 24-token case has a larger |d|)
@@ -308,6 +328,10 @@ def test_step_matches_oracle(oracle, name):
     assert res["d"] == np.float32((np.float32(res["loss_plus"]) - np.float32(res["loss_minus"]))
                                   / (np.float32(2) * np.float32(1e-3)))
     assert res["d_clipped"] == max(-100.0, min(100.0, res["d"]))
+    # the projected gradient itself: within three times the 16-bit noise floor of the oracle's own d
+    floor = _d_noise_floor(oracle, om, tok, (seed, seed + 100, seed + 200))
+    print(name, "d error", abs(res["d"] - ref["d"]), "floor", floor)
+    assert abs(res["d"] - ref["d"]) <= 3 * floor + 1e-3 * abs(ref["d"]), (res["d"], ref["d"], floor)
     got = dm.scales.float().cpu().numpy()
     assert (np.abs(got - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-7).all()
     assert not torch.equal(dm.scales, before)
@@ -454,6 +478,124 @@ def test_real_width_one_layer_step(oracle, name, batch, seq, eta):
     want = oracle.update_scales(om, 9, 1e-5, 55.0, scales=got)
     assert np.array_equal(_bits(dm.scales.float().cpu().numpy()), _bits(want))
     print(name, "loss", res["loss_plus"], ref["loss_plus"], "d", res["d"], ref["d"])
+    dm.close()
+
+
+@pytest.mark.parametrize("name,asym", [("llama-2-7b", False), ("llama-2-13b", False), ("opt-1.3b", False),
+                                       ("llama-2-7b", True)])
+def test_real_width_one_layer_expanded_route(oracle, name, asym):
+    """The route the benchmark's linears take (perturbed scales of the whole arena in one launch, the
+    perturbed bf16 matrix written out, plain GEMM), at real widths: 86 / 108 groups per row in the
+    down projection, the gate/up row interleave at 11008 / 13824 features, K = 11008 / 13824 in the
+    plain GEMM, two token tiles (272 tokens).  One layer, a short vocabulary for the Llama shapes."""
+    shape = dict(synth.SHAPES[name], n_layers=1, batch=2, seq=136, max_seq=136)
+    if shape["arch"] == "llama":
+        shape["vocab"] = 1000
+    om, dm = _models(oracle, shape, 77, asym=asym, route=2)
+    tok = synth.tokens(shape, 78)
+    B, S = tok.shape
+    se = oracle.perturbed_scales(om, 3, np.float32(1e-3))
+    ref_loss, ref_hid = oracle.forward_loss(om, se, tok, act_bf16=True, want_hidden=True)
+    _, exact_hid = oracle.forward_loss(om, se, tok, act_bf16=False, want_hidden=True)
+    hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    qb.qzo_debug_forward(dm.handle, _dev(tok), 3, 1e-3, 1, dm.workspace(B, S), loss, hid)
+    assert abs(loss.item() - ref_loss) <= 2e-2 * abs(ref_loss), (loss.item(), ref_loss)
+    rms = math.sqrt((ref_hid ** 2).mean())
+    err = np.abs(hid.float().cpu().numpy().astype(np.float64) - ref_hid)
+    floor_rms = math.sqrt(((exact_hid - ref_hid) ** 2).mean())
+    print(name, "hidden rms err", math.sqrt((err ** 2).mean()) / rms, "floor", floor_rms / rms)
+    assert math.sqrt((err ** 2).mean()) <= 2 * floor_rms + 2e-3 * rms
+    assert err.max() <= 2 * np.abs(exact_hid - ref_hid).max() + 2e-2 * rms
+    eta = 1e-5 if name == "opt-1.3b" else 1e-7
+    ref = oracle.qzo_step(om, tok, seed=3, eps=1e-3, eta=eta, Cthr=100.0)
+    res = qb.read_step_result(dm.step(_dev(tok), 3, 1e-3, eta, 100.0))
+    assert res["status"] == 0
+    assert res["loss_plus"] == loss.item()                   # the step's first pass is that forward
+    for k in ("loss_plus", "loss_minus"):
+        assert abs(res[k] - ref[k]) <= 2e-2 * abs(ref[k]), (k, res[k], ref[k])
+    got = dm.scales.float().cpu().numpy()
+    assert (np.abs(got - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-7).all()
+    assert np.array_equal(_bits(got), _bits(oracle.update_scales(om, 3, eta, res["d_clipped"])))
+    print(name, "loss", res["loss_plus"], ref["loss_plus"], "d", res["d"], ref["d"])
+    dm.close()
+
+
+def test_failing_calls_enqueue_nothing(oracle):
+    """Every error that the library finds itself (anything but a failing HIP call) is found before
+    the first launch: outputs, workspace and scales are untouched afterwards."""
+    import ctypes as C
+    shape = synth.SHAPES["tiny"]
+    om, dm = _models(oracle, shape, 1234)
+    tok = synth.tokens(shape, 5678)
+    tokd = _dev(tok)
+    B, S = tok.shape
+    ws = dm.workspace(B, S)
+    ws.fill_(0x5A)
+    dm.result.fill_(0x7B7B7B7B)
+    scales0 = dm.scales.clone()
+    lib = qb.lib()
+
+    def step(tokens=tokd, batch=B, seq=S, ws_bytes=ws.numel(), wsp=ws.data_ptr(), clip=100.0, eps=1e-3):
+        return lib.qzo_step(dm.handle, C.c_void_p(tokens.data_ptr()), C.c_uint32(batch), C.c_uint32(seq),
+                            C.c_uint64(1), C.c_float(eps), C.c_float(1e-5), C.c_float(clip), C.c_void_p(wsp),
+                            C.c_uint64(ws_bytes), C.c_void_p(dm.result.data_ptr()), None)
+    assert step(ws_bytes=ws.numel() - 256) == qb.QZO_ERR_WORKSPACE
+    assert step(seq=S + 1) == qb.QZO_ERR_SHAPE                     # beyond max_seq
+    assert step(seq=1) == qb.QZO_ERR_SHAPE
+    assert step(batch=0) == qb.QZO_ERR_SHAPE
+    assert step(wsp=ws.data_ptr() + 4) == qb.QZO_ERR_ALIGN
+    assert step(clip=-1.0) == qb.QZO_ERR_ARG
+    assert step(eps=float("nan")) == qb.QZO_ERR_ARG
+    assert step(batch=1 << 20, seq=S) == qb.QZO_ERR_SHAPE          # activations beyond 32-bit byte offsets
+    assert "2^31" in lib.qzo_last_error().decode()
+    loss = torch.full((1,), 7.0, device=DEV)
+    assert lib.qzo_forward_loss(dm.handle, C.c_void_p(tokd.data_ptr()), C.c_uint32(B), C.c_uint32(S), C.c_uint64(1),
+                                C.c_float(1e-3), C.c_int(0), C.c_void_p(ws.data_ptr()), C.c_uint64(ws.numel()),
+                                C.c_void_p(loss.data_ptr()), None) == qb.QZO_ERR_ARG      # sign 0
+    torch.cuda.synchronize()
+    assert bool((ws == 0x5A).all()) and bool((dm.result == 0x7B7B7B7B).all()) and loss.item() == 7.0
+    assert torch.equal(dm.scales, scales0)
+    # a single linear: scratch too small / missing / misaligned, operands too large
+    x, qp, s = synth.linear_case(16, 520, 1280, seed=4)
+    xd, qd, sd = _dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16)
+    y = torch.full((16, 520), 3.0, dtype=torch.bfloat16, device=DEV)
+    need = qb.qzo_linear_scratch_bytes(16, 520, 1280, True)
+    scratch = torch.full((need + 256,), 0x33, dtype=torch.uint8, device=DEV)
+    ssq = torch.full((1,), -1.0, device=DEV)
+    for bad, status in ((scratch[:need - 256], qb.QZO_ERR_WORKSPACE), (None, qb.QZO_ERR_ARG),
+                        (scratch[16:], qb.QZO_ERR_ALIGN)):
+        with pytest.raises(qb.QzoError) as e:
+            qb.qzo_dequant_gemm(xd, qd, sd, 0, 1, 1e-3, 1, y, ssq, scratch=bad)
+        assert e.value.status == status
+    assert lib.qzo_dequant_gemm(C.c_void_p(xd.data_ptr()), C.c_void_p(qd.data_ptr()), C.c_void_p(sd.data_ptr()),
+                                C.c_uint32(0), C.c_uint32(1 << 20), C.c_uint32(520), C.c_uint32(1280),
+                                C.c_uint32(128), C.c_uint64(1), C.c_float(1e-3), C.c_int(1),
+                                C.c_void_p(y.data_ptr()), None, C.c_void_p(scratch.data_ptr()),
+                                C.c_uint64(scratch.numel()), None) == qb.QZO_ERR_SHAPE
+    torch.cuda.synchronize()
+    assert bool((y == 3.0).all()) and bool((scratch == 0x33).all()) and ssq.item() == -1.0
+    qb.qzo_dequant_gemm(xd, qd, sd, 0, 1, 1e-3, 1, y, ssq, scratch=scratch[:need])      # exactly enough
+    torch.cuda.synchronize()
+    assert not bool((y == 3.0).all()) and ssq.item() > 0 and bool((scratch[need:] == 0x33).all())
+    # joint mode: a wrong count and a table that is too small are refused, the model stays usable
+    n_dense = qb.qzo_model_dense_count(dm.shape)
+    master = torch.zeros(n_dense, dtype=torch.float32, device=DEV)
+    table = torch.zeros(qb.qzo_model_joint_table_bytes(dm.shape), dtype=torch.uint8, device=DEV)
+    with pytest.raises(qb.QzoError) as e:
+        qb.qzo_model_enable_joint(dm.handle, master[:-8], table)
+    assert e.value.status == qb.QZO_ERR_SHAPE
+    with pytest.raises(qb.QzoError) as e:
+        qb.qzo_model_enable_joint(dm.handle, master, table[:64])
+    assert e.value.status == qb.QZO_ERR_WORKSPACE
+    with pytest.raises(qb.QzoError) as e:
+        dm.step_joint(tokd, 1, 1e-3, 1e-5, 1e-5, 100.0)
+    assert e.value.status == qb.QZO_ERR_ARG
+    assert bool((table == 0).all())
+    assert qb.read_step_result(dm.step(tokd, 1, 1e-3, 0.0, 100.0))["status"] == 0
+    with pytest.raises(qb.QzoError) as e:
+        dm.set_int4_path(3)
+    assert e.value.status == qb.QZO_ERR_ARG
     dm.close()
 
 
@@ -712,17 +854,13 @@ def test_int4_expand_then_multiply_equals_the_fused_path(oracle, name):
     tok = synth.tokens(shape, 5678)
     B, S = tok.shape
     outs, ws_bytes = [], []
-    try:
-        for mode in (2, 1):
-            qb.qzo_set_int4_path(mode)
-            dm._ws = dm._ws_key = None           # the workspace layout depends on the route
-            ws_bytes.append(qb.qzo_workspace_bytes(dm.handle, B, S))
-            hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
-            loss = torch.zeros(1, dtype=torch.float32, device=DEV)
-            qb.qzo_debug_forward(dm.handle, _dev(tok), 9, 1e-3, -1, dm.workspace(B, S), loss, hid)
-            outs.append((float(loss.item()), hid.float().cpu().numpy()))
-    finally:
-        qb.qzo_set_int4_path(0)
+    for mode in (2, 1):
+        dm.set_int4_path(mode)                   # the workspace layout depends on the route
+        ws_bytes.append(qb.qzo_workspace_bytes(dm.handle, B, S))
+        hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        qb.qzo_debug_forward(dm.handle, _dev(tok), 9, 1e-3, -1, dm.workspace(B, S), loss, hid)
+        outs.append((float(loss.item()), hid.float().cpu().numpy()))
     assert outs[0][0] == outs[1][0]
     assert np.array_equal(outs[0][1], outs[1][1])
     # the expanded route adds one linear in bf16 and every perturbed scale in fp32 to the workspace

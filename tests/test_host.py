@@ -51,7 +51,7 @@ def test_config_errors_are_reported():
     assert qb.lib().qzo_model_scale_count(C.byref(cfg), C.byref(out)) == qb.QZO_ERR_ARG
     # null pointers never reach a kernel
     assert qb.lib().qzo_dequant_gemm(None, None, None, 0, 1, 8, 128, 128, C.c_uint64(0),
-                                     C.c_float(0), 1, None, None, None) == qb.QZO_ERR_ARG
+                                     C.c_float(0), 1, None, None, None, C.c_uint64(0), None) == qb.QZO_ERR_ARG
     assert qb.lib().qzo_step(None, None, 1, 2, C.c_uint64(0), C.c_float(0), C.c_float(0),
                              C.c_float(1), None, C.c_uint64(0), None, None) == qb.QZO_ERR_ARG
 
@@ -99,10 +99,21 @@ def test_scratch_sizes_and_mode_switches():
     assert qb.qzo_nf4_scratch_bytes(512, 1024) >= 512 * 1024 * 2 + 512 * 16 * 4
     assert qb.qzo_int4_scratch_bytes(512, 1024) >= 512 * 1024 * 2 + 512 * 8 * 4
     assert qb.qzo_nf4_scratch_bytes(512, 1024) % 256 == 0
-    for mode in (1, 2, 0):
-        qb.qzo_set_int4_path(mode)
+    with pytest.raises(qb.QzoError) as e:
+        qb.qzo_model_set_int4_path(None, 1)                    # a field of a model: no model, no switch
+    assert e.value.status == qb.QZO_ERR_ARG
+    # scratch of a single perturbed linear: nothing for a many-tile call without the loss, one float per
+    # tile with it, K-slice partial sums on the few-token path (at most 8 M N floats)
+    assert qb.qzo_linear_scratch_bytes(2048, 11008, 4096, False) == 0
+    assert 344 * 4 <= qb.qzo_linear_scratch_bytes(2048, 11008, 4096, True) <= 344 * 4 + 256
+    few = qb.qzo_linear_scratch_bytes(16, 4096, 4096, False)
+    assert 16 * 4096 * 4 <= few <= 8 * 16 * 4096 * 4 + 256 and few % 256 == 0
+    assert qb.qzo_linear_scratch_bytes(0, 4096, 4096, True) == 0
+    assert qb.qzo_codebook_scratch_bytes(300, 520, True) == 256 and qb.qzo_codebook_scratch_bytes(300, 520, False) == 0
     with pytest.raises(qb.QzoError):
-        qb.qzo_set_int4_path(3)
+        qb.qzo_linear_scratch_bytes(16, 4096, 100, False)
+    tiny = synth.SHAPES["tiny"]
+    assert qb.qzo_model_joint_table_bytes(tiny) >= (3 + 2 * tiny["n_layers"]) * 24
     with pytest.raises(qb.QzoError):
         qb.qzo_profile_stride(0)
     qb.qzo_profile_stride(1)

@@ -44,6 +44,31 @@ def test_qlinear_special_cases_and_matmul(oracle):
     assert np.allclose(oracle.linear(x, w), (_t(x) @ _t(w).T).numpy(), rtol=1e-12, atol=1e-12)
 
 
+def test_sumsq_loss_rounds_outputs_to_bf16_first(oracle):
+    """The single-linear workload's loss is the sum of squares of the outputs as stored (bf16)."""
+    # values whose bf16 rounding is known by hand (8 significant bits): 1 + 2^-8 and 2 + 2^-7 are
+    # ties that go to the even neighbours 1 and 2, 1 + 3*2^-8 is a tie that goes up to 1 + 2^-6,
+    # 1 + 2^-7 is exact; without the rounding the sum would differ in the 3rd digit
+    y = np.array([1.0 + 2.0 ** -8, 2.0 + 2.0 ** -7, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -7, -3.0, 0.0])
+    want = 1.0 + 4.0 + (1.0 + 2.0 ** -6) ** 2 + (1.0 + 2.0 ** -7) ** 2 + 9.0
+    assert oracle.sumsq_bf16(y) == want
+    assert abs((y ** 2).sum() - want) > 1e-3
+    # against the library's rounding and an fp64 sum
+    rng = np.random.default_rng(11)
+    y = rng.standard_normal(200001) * 37.0
+    ref = float((torch.from_numpy(y.astype(np.float32)).to(torch.bfloat16).to(torch.float64) ** 2).sum())
+    assert abs(oracle.sumsq_bf16(y) - ref) <= 1e-12 * ref
+    assert abs(oracle.sumsq_bf16(y) - float((y ** 2).sum())) > 1e-7 * ref      # the rounding is visible
+    # closed form on a sample shaped like the single-linear workload (q uniform on -8..7, E[q^2] = 21.5;
+    # s ~ U(0.005, 0.02); X ~ N(0,1)): E[loss] = M N K E[q^2] (E[s^2] + eps^2)
+    M, N, K = 96, 64, 4096
+    x, qp, s = synth.linear_case(M, N, K, seed=5)
+    eps = np.float32(1e-3)
+    loss = oracle.sumsq_bf16(oracle.qlinear(x, qp, oracle.effective_scales(s, 0, 7, eps)))
+    closed = M * N * K * 21.5 * ((0.005 ** 2 + 0.005 * 0.02 + 0.02 ** 2) / 3 + 1e-6)
+    assert abs(loss - closed) <= 5e-2 * closed
+
+
 def test_dequant_is_scale_times_integer(oracle):
     rng = np.random.default_rng(3)
     N, K = 9, 384
