@@ -317,6 +317,8 @@ def test_step_matches_oracle(oracle, name):
     tokd = _dev(tok)
     # NormalFloat-4 scales are a block's absmax, ten times larger (the 24-token case has a larger |d|)
     eta = (1e-4 if name.startswith("few") else 3e-4) if asym == "nf4" else 1e-5
+    if name.startswith("long"):       # 1024 / 768 / 600 tokens: |d| is below 2, a larger step makes it visible
+        eta = 1e-4
     seed = 3 if asym else 1           # a direction whose |d| is large enough to move the scales
     ref = oracle.qzo_step(om, tok, seed=seed, eps=1e-3, eta=eta, Cthr=100.0)
     before = dm.scales.clone()
@@ -328,10 +330,12 @@ def test_step_matches_oracle(oracle, name):
     assert res["d"] == np.float32((np.float32(res["loss_plus"]) - np.float32(res["loss_minus"]))
                                   / (np.float32(2) * np.float32(1e-3)))
     assert res["d_clipped"] == max(-100.0, min(100.0, res["d"]))
-    # the projected gradient itself: within three times the 16-bit noise floor of the oracle's own d
-    floor = _d_noise_floor(oracle, om, tok, (seed, seed + 100, seed + 200))
+    # the projected gradient itself: within four times the 16-bit noise floor of the oracle's own d
+    # (the floor holds the rounding of the activations; the kernels also round the weight tile to bf16,
+    # an error of the same size per linear)
+    floor = _d_noise_floor(oracle, om, tok, [seed + 100 * i for i in range(5)])
     print(name, "d error", abs(res["d"] - ref["d"]), "floor", floor)
-    assert abs(res["d"] - ref["d"]) <= 3 * floor + 1e-3 * abs(ref["d"]), (res["d"], ref["d"], floor)
+    assert abs(res["d"] - ref["d"]) <= 4 * floor + 1e-3 * abs(ref["d"]), (res["d"], ref["d"], floor)
     got = dm.scales.float().cpu().numpy()
     assert (np.abs(got - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-7).all()
     assert not torch.equal(dm.scales, before)
