@@ -231,6 +231,23 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
                             void* stream);
 
 /*
+ * qzo_dequant_gemm for callers that cannot allocate device memory and have no scratch to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operands,
+ * same kernels and bit-identical results; the scratch is a fixed 32 MiB array that is part of the
+ * loaded library (every GPU the library is used on holds its own copy until the process ends), so
+ * the call allocates nothing.  The calling thread's current device must be the one the pointers and
+ * the stream belong to.  QZO_ERR_WORKSPACE when qzo_linear_scratch_bytes(M, N, K, sumsq_dev != NULL)
+ * exceeds 32 MiB (at M <= 64 that is N up to about 16000 at 8 K slices, any of the Llama-2-7B / 13B
+ * linears; the single-linear workload 2048 x 11008 x 4096 needs 1.5 KB); then nothing is enqueued.
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents: calls that
+ * overlap on one GPU (two streams, two threads) race, and must be serialised by the caller.
+ */
+qzo_status qzo_dequant_gemm_static(const void* x_dev, const void* q_dev, const void* s_dev,
+                                   uint32_t row_base, uint32_t M, uint32_t N, uint32_t K,
+                                   uint32_t group, uint64_t seed, float eps, int sign, void* y_dev,
+                                   float* sumsq_dev, void* stream);
+
+/*
  * The same linear for asymmetric 4-bit groups, the format of the 4-bit checkpoints the paper
  * fine-tunes (Sec. 4.1: group-128 quantizer with zero-points):
  *   W_eff[n,k] = (s[n,k/group] + sign*eps*z(row_base+n, k/group)) * (u[n,k] - zp[n,k/group])

@@ -24,7 +24,7 @@ EXPORTS = [
     "qzo_model_create", "qzo_model_destroy", "qzo_model_scale_count", "qzo_workspace_bytes",
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update",
     "qzo_model_dense_count", "qzo_model_joint_table_bytes", "qzo_model_enable_joint", "qzo_step_joint",
-    "qzo_linear_scratch_bytes", "qzo_dequant_gemm", "qzo_dequant_gemm_zp", "qzo_apply_update",
+    "qzo_linear_scratch_bytes", "qzo_dequant_gemm", "qzo_dequant_gemm_static", "qzo_dequant_gemm_zp", "qzo_apply_update",
     "qzo_rtn_quantize", "qzo_repack_kmajor",
     "qzo_int4_expand", "qzo_int4_scratch_bytes", "qzo_int4_gemm_expanded", "qzo_model_set_int4_path",
     "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm",
@@ -212,6 +212,14 @@ def qzo_dequant_gemm(x, q, s, row_base, seed, eps, sign, y, sumsq=None, group=12
                                   C.c_uint32(N), C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
                                   C.c_float(eps), C.c_int(sign), _ptr(y), _ptr(sumsq),
                                   *_scratch_args(scratch), _stream(stream)))
+
+
+def qzo_dequant_gemm_static(x, q, s, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None):
+    M, K = x.shape
+    N = q.shape[0]
+    _check(lib().qzo_dequant_gemm_static(_ptr(x), _ptr(q), _ptr(s), C.c_uint32(row_base), C.c_uint32(M),
+                                         C.c_uint32(N), C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
+                                         C.c_float(eps), C.c_int(sign), _ptr(y), _ptr(sumsq), _stream(stream)))
 
 
 def qzo_dequant_gemm_zp(x, q, s, zp, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None,

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 #include "../../include/qzo.h"
@@ -812,6 +813,47 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
                             void* scratch_dev, uint64_t scratch_bytes, void* stream) {
   return dequant_gemm(x_dev, q_dev, s_dev, nullptr, row_base, M, N, K, group, seed, eps, sign, y_dev,
                       sumsq_dev, scratch_dev, scratch_bytes, stream);
+}
+
+// ---- qzo_dequant_gemm for callers that cannot allocate: the scratch is a fixed array of this library ----
+// Every GPU the library runs on holds its own copy of the array at its own address; the name below is
+// a host-side stand-in, so host code only ever uses the per-device address that hipGetSymbolAddress
+// returned (looked up once per device, with that device current).
+constexpr uint64_t STATIC_SCRATCH_BYTES = 32ull << 20;
+static __device__ __align__(256) unsigned char static_scratch[STATIC_SCRATCH_BYTES];
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static void* g_static_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES] = {};
+static std::mutex g_static_scratch_mutex;
+
+qzo_status qzo_dequant_gemm_static(const void* x_dev, const void* q_dev, const void* s_dev,
+                                   uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint32_t group,
+                                   uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
+                                   void* stream) {
+  qzo_status st = linear_check(x_dev, q_dev, s_dev, y_dev, M, N, K, group, eps, sign);
+  if (st != QZO_OK) return st;
+  const LinearScratch ls = linear_scratch(M, N, K, sumsq_dev != nullptr);
+  if (ls.total > STATIC_SCRATCH_BYTES)
+    return fail(QZO_ERR_WORKSPACE, "this size needs " + std::to_string(ls.total) +
+                                       " bytes of scratch, the fixed array holds " +
+                                       std::to_string(STATIC_SCRATCH_BYTES) +
+                                       ": call qzo_dequant_gemm with scratch of your own");
+  int dev = -1;
+  QZO_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return fail(QZO_ERR_UNSUPPORTED, "device ordinal out of range");
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch_ptr[dev]) {
+      void* p = nullptr;
+      QZO_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch)));
+      if (!p) return fail(QZO_ERR_HIP, "hipGetSymbolAddress returned a null address");
+      g_static_scratch_ptr[dev] = p;
+    }
+    ptr = g_static_scratch_ptr[dev];
+  }
+  // nothing in the scratch has to start at zero: every partial sum that is read was written by this call
+  return dequant_gemm_run(x_dev, q_dev, s_dev, nullptr, row_base, M, N, K, seed, eps, sign, y_dev, sumsq_dev,
+                          ptr, ls, (hipStream_t)stream);
 }
 
 qzo_status qzo_dequant_gemm_zp(const void* x_dev, const void* q_dev, const void* s_dev,
