@@ -78,6 +78,56 @@ def measured_traffic(key):
     return None
 
 
+def other_config_memory(torch, qb, synth, DeviceModel, tok_seed=5678):
+    """Total device memory of the Llama-2-13B-shaped workload (batch 8 x 512), both quantizer variants:
+    two full QZO steps each, outside any timed region; peak bytes torch's allocator handed out
+    (weights, scales, workspace, tokens)."""
+    out = {}
+    shape = dict(synth.SHAPES["llama-2-13b"])
+    tok = torch.from_numpy(synth.tokens(shape, tok_seed)).cuda()
+    for name in ("int4_g128", "codebook_16bit_per_8"):
+        torch.cuda.empty_cache()
+        torch.cuda.reset_peak_memory_stats()
+        base = torch.cuda.memory_allocated()
+        dm = (DeviceModel.synthetic_codebook(shape, seed=1234, device="cuda:0") if name.startswith("codebook")
+              else DeviceModel.synthetic(shape, seed=1234, device="cuda:0"))
+        resident = torch.cuda.memory_allocated() - base
+        t0 = time.perf_counter()
+        for i in range(2):
+            dm.step(tok, 1 + i, 1e-3, 1e-7, 100.0)
+        torch.cuda.synchronize()
+        res = qb.read_step_result(dm.result)
+        out[name] = {"peak_GiB": torch.cuda.max_memory_allocated() / 2 ** 30,
+                     "model_GiB": resident / 2 ** 30, "ms_per_step_untimed": (time.perf_counter() - t0) / 2 * 1e3,
+                     "loss_plus": res["loss_plus"], "status": res["status"]}
+        dm.close()
+        del dm
+    return out
+
+
+def fused_leg(torch, qb, dm, tok, steps, n_lin, eps, eta, clip):
+    """The same workload with every int4 linear on the fused dequantizing GEMM (int4 unpack and scale
+    perturbation inside the LDS-staged weight tile): a short timed leg of its own."""
+    dm.set_int4_path(1)
+    dm.step(tok, 50, eps, eta, clip)
+    torch.cuda.synchronize()
+    qb.qzo_profile_stride(PROF_STRIDE)
+    qb.qzo_profile_begin(steps * (n_lin + 64))
+    t0 = time.perf_counter()
+    for i in range(steps):
+        dm.step(tok, 60 + i, eps, eta, clip)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    g = qb.qzo_profile_collect(qb.PROFILE_KINDS["w4a16_gemm"])
+    rate = g["work"] / (g["total_ms"] * 1e-3)
+    dm.set_int4_path(0)
+    return {"bound": "mfma", "kernel": "gemm_kernel<0,false,4,2> (fused perturbed W4A16 GEMM)",
+            "achieved": rate / 1e12, "peak": PEAK_BF16_MFMA / 1e12, "unit": "TFLOP/s", "frac": rate / PEAK_BF16_MFMA,
+            "traffic": measured_traffic("traffic_bytes_per_launch_gemm_qkv_fused"),
+            "launches": g["launches"], "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
+            "steps": steps, "ms_per_step": dt / steps * 1e3}
+
+
 def mfma_ceiling(torch, qb, iters=60000):
     """bf16 MFMA rate the board sustains with nothing but MFMAs in flight (TFLOP/s), with
     all-zero and with pseudo-random register operands; timed with events on the current stream."""
@@ -158,6 +208,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--seq", type=int, default=0, help="override the workload's sequence length")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-other", action="store_true",
+                    help="skip the untimed Llama-2-13B-shaped memory report (two variants, two steps each)")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: a plain 256 MiB copy, the qkv-shaped W4A16 GEMM and the "
                          "7B-sized scale update, three launches each (for rocprofv3 --pmc)")
@@ -258,6 +310,9 @@ def main():
     steps_per_s = args.steps / dt
     g = prof["w4a16_gemm"]
     gemm_flops_s = g["work"] / (g["total_ms"] * 1e-3)
+    # the W4A16 linear as a whole: the matrix kernel plus, on the expanded route, the passes that write the
+    # perturbed scales and the perturbed weights out
+    linear_flops_s = g["work"] / ((g["total_ms"] + prof["expand"]["total_ms"]) * 1e-3)
     u = prof["scale_update"]
     upd_bytes_s = u["work"] / (u["total_ms"] * 1e-3) if u["total_ms"] > 0 else 0.0
     out = {
@@ -285,16 +340,17 @@ def main():
                      if expanded
                      else ("gemm_kernel<2,...> (codebook GEMM, perturbed channel scales)" if codebook
                            else "gemm_kernel<0,false,4,2> (fused perturbed W4A16 GEMM)"),
-                     "achieved": gemm_flops_s / 1e12, "peak": PEAK_BF16_MFMA / 1e12,
-                     "unit": "TFLOP/s", "frac": gemm_flops_s / PEAK_BF16_MFMA,
+                     "achieved": linear_flops_s / 1e12, "peak": PEAK_BF16_MFMA / 1e12,
+                     "unit": "TFLOP/s", "frac": linear_flops_s / PEAK_BF16_MFMA,
+                     "achieved_note": "2MNK of the perturbed linears over the time of their matrix kernel PLUS "
+                                      "the expansion passes (perturbed scales, perturbed bf16 weights) they depend on",
+                     "matrix_kernel_alone_TFLOPs": gemm_flops_s / 1e12,
                      "traffic": measured_traffic("traffic_bytes_per_launch_gemm_qkv" if expanded else
                                                  "traffic_bytes_per_launch_gemm_qkv_fused")
                      if args.workload == "llama-2-7b" and args.variant == "int4" and not args.batch and not args.seq
                      else None,
                      "traffic_note": "bytes of one qkv-shaped launch (8192x12288x4096), FETCH_SIZE + WRITE_SIZE "
                                      "scaled by a plain copy; algorithmic " + ("3.69e8" if expanded else "2.94e8"),
-                     # the whole W4A16 linear: the GEMM plus, when expanded, the pass that writes the weights out
-                     "w4a16_linear_effective_TFLOPs": g["work"] / ((g["total_ms"] + prof["expand"]["total_ms"]) * 1e-3) / 1e12,
                      "launches": g["launches"], "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
                      "flops_per_launch_avg": g["work"] / max(g["launches"], 1),
                      "mfma_only_measured_TFLOPs": mfma_ceiling(torch, qb)},
@@ -324,7 +380,12 @@ def main():
                            "traffic": None, "launches": g["launches"],
                            "avg_launch_ms": g["total_ms"] / max(g["launches"], 1),
                            "bytes_per_launch_avg": per_launch}
+    if main_cfg and not args.fused and not args.expanded:
+        out["roofline_fused_kernel"] = fused_leg(torch, qb, dm, tok, max(2, args.steps // 4), n_lin, eps, eta, clip)
     dm.close()
+    del dm
+    if main_cfg and not args.no_other:
+        out["llama_2_13b_shape_memory"] = other_config_memory(torch, qb, synth, DeviceModel)
     if not args.no_cpu and not codebook and main_cfg:
         out["cpu_baseline"] = cpu_baseline(shape)
     print(json.dumps(out))
