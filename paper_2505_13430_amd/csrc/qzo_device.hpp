@@ -55,15 +55,13 @@ __device__ __forceinline__ u32x4_t philox4x32_10(uint32_t c0, uint32_t c1, uint3
 // Built only from exact integer/exponent steps and fp32 mul/add/fma so that
 // any IEEE machine gives the same bits (the file is compiled with
 // -ffp-contract=off; every fused step is an explicit fma).
-__device__ __forceinline__ void normal_pair(uint32_t w, float& z0, float& z1) {
+// The radius sqrt(-ln u1) depends on h only and the two angle factors on k only; the variates are
+// one IEEE product of the two each, so the factors may be computed apart (or looked up).
+__device__ __forceinline__ float normal_radius(uint32_t w) {
   const float QL0 = 0x1.fffffap-1f, QL1 = 0x1.000586p-1f, QL2 = 0x1.53a4dcp-2f,
               QL3 = 0x1.18fbf0p-2f, QL4 = 0x1.a5d4cap-6f, QL5 = 0x1.a4912ap-1f,
               QL6 = -0x1.2245dap+0f, QL7 = 0x1.36ff60p+0f;
   const float LN2 = 0x1.62e430p-1f;
-  const float ANG_STEP = 0x1.921fb6p-14f, ANG_OFF = -0x1.92196cp-1f;
-  const float S0 = -0x1.555552p-3f, S1 = 0x1.110c2cp-7f, S2 = -0x1.9acab0p-13f;
-  const float C0 = -0x1.000000p-1f, C1 = 0x1.55555ep-5f, C2 = -0x1.6c16a2p-10f,
-              C3 = 0x1.9ca594p-16f;
   // -ln(u1) = (17-E) ln2 + (1-m) Q(1-m), with 2h+1 = m 2^E, m in [1/2,1)
   float a = (float)((w >> 15) | 1u);
   float m = __builtin_amdgcn_frexp_mantf(a);
@@ -84,9 +82,15 @@ __device__ __forceinline__ void normal_pair(uint32_t w, float& z0, float& z1) {
     float c = __builtin_fmaf(-hy, y, 1.5f);
     y = y * c;
   }
-  float r = t * y;
-  // x = phi - pi/4; sqrt2 cos(phi) = cos x - sin x, sqrt2 sin(phi) = cos x + sin x
-  float x = __builtin_fmaf((float)(w & 0x3fffu), ANG_STEP, ANG_OFF);
+  return t * y;
+}
+// k = 0 .. 16383 -> (cos x - sin x, cos x + sin x) = sqrt2 (cos phi, sin phi), x = phi - pi/4
+__device__ __forceinline__ float2 normal_angle(uint32_t k) {
+  const float ANG_STEP = 0x1.921fb6p-14f, ANG_OFF = -0x1.92196cp-1f;
+  const float S0 = -0x1.555552p-3f, S1 = 0x1.110c2cp-7f, S2 = -0x1.9acab0p-13f;
+  const float C0 = -0x1.000000p-1f, C1 = 0x1.55555ep-5f, C2 = -0x1.6c16a2p-10f,
+              C3 = 0x1.9ca594p-16f;
+  float x = __builtin_fmaf((float)k, ANG_STEP, ANG_OFF);
   float x2 = x * x;
   float sp = __builtin_fmaf(x2, S2, S1);
   sp = __builtin_fmaf(x2, sp, S0);
@@ -95,10 +99,16 @@ __device__ __forceinline__ void normal_pair(uint32_t w, float& z0, float& z1) {
   cp = __builtin_fmaf(x2, cp, C1);
   cp = __builtin_fmaf(x2, cp, C0);
   float cx = __builtin_fmaf(x2, cp, 1.0f);
-  float a0 = r * (cx - sx);
-  float a1 = r * (cx + sx);
+  return make_float2(cx - sx, cx + sx);
+}
+__device__ __forceinline__ void normal_from_factors(uint32_t w, float r, float2 cs, float& z0, float& z1) {
+  float a0 = r * cs.x;
+  float a1 = r * cs.y;
   z0 = __uint_as_float(__float_as_uint(a0) | ((w & 0x8000u) << 16));
   z1 = __uint_as_float(__float_as_uint(a1) | ((w & 0x4000u) << 17));
+}
+__device__ __forceinline__ void normal_pair(uint32_t w, float& z0, float& z1) {
+  normal_from_factors(w, normal_radius(w), normal_angle(w & 0x3fffu), z0, z1);
 }
 
 // The eight variates z(row, 8*gblock .. 8*gblock+7) of one Philox counter.

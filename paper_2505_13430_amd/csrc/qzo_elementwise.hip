@@ -11,6 +11,92 @@ namespace qzo {
 // Delta_i <- max(Delta_i - eta*d'*z_i, 0) (Algorithm 1).  One thread owns the
 // eight scales that share a Philox counter: (row, 8*gb .. 8*gb+7).  The arena
 // is read and written once (4 B per scale); z costs no memory traffic.
+// The kernel is bound by the vector ALU, not by memory: about 320 instructions per wavefront
+// and counter, two thirds of them the four Box-Muller pairs (timing-only runs of this kernel:
+// 45 us as is, 31 us with Philox but no Box-Muller, 30 us with no noise at all, at 50.6 M
+// scales resident in the last-level cache).  Looking the angle factors of the pairs up in a
+// 128 KB LDS table (one persistent workgroup per compute unit) was measured and is slower:
+// 57 us, whatever the number of counters a thread interleaves.
+struct u32x4_a4 { uint32_t x, y, z, w; } __attribute__((packed, aligned(4)));
+
+// The eight scales of one Philox counter: where they are, how many of them exist, their noise row.
+struct UpdUnit {
+  bf16_t* p;          // null: no such counter (beyond the segment's last)
+  uint32_t G, nv;     // groups per row of the segment; scales of this counter that exist (1 .. 8)
+  uint32_t noise_row, gb;
+};
+__device__ __forceinline__ UpdUnit update_locate(bf16_t* __restrict__ arena, const UpdPlan& plan, uint32_t wg,
+                                                 uint32_t layer, uint32_t tid) {
+  UpdSeg sg = plan.seg[0];
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if ((uint32_t)i < plan.n_seg && wg >= plan.seg[i].first_wg) sg = plan.seg[i];
+  const uint32_t Gb = (sg.G + 7u) >> 3;
+  const uint32_t u = (wg - sg.first_wg) * 256u + tid;
+  UpdUnit r = {nullptr, sg.G, 0u, 0u, 0u};
+  if (u >= sg.rows * Gb) return r;
+  // row = u / Gb, gb = u % Gb for u < 2^24 (checked on the host)
+  uint32_t row = (uint32_t)((float)u * __builtin_amdgcn_rcpf((float)Gb));
+  int32_t gb = (int32_t)(u - __umul24(row, Gb));
+  if (gb < 0) { row -= 1; gb += (int32_t)Gb; }
+  else if (gb >= (int32_t)Gb) { row += 1; gb -= (int32_t)Gb; }
+  r.p = arena + (uint64_t)layer * plan.layer_stride + sg.off + (uint64_t)row * sg.G + (uint32_t)gb * 8u;
+  r.nv = min(8u, sg.G - (uint32_t)gb * 8u);
+  r.noise_row = layer * plan.rows_per_layer + sg.row_base + row;
+  r.gb = (uint32_t)gb;
+  return r;
+}
+__device__ __forceinline__ void update_apply(const UpdUnit& un, float c, const float z[8]) {
+  if (!un.p) return;
+  bf16_t* p = un.p;
+  struct { uint32_t G; } sg = {un.G};
+  const float nc = -c;
+  const uint32_t nv = un.nv;
+  if ((sg.G & 1u) == 0u && nv == 8u) {
+    // rows start on a dword: one 16-byte access each way (16-byte aligned when G % 8 == 0)
+    uint32_t in[4], out[4];
+    if ((sg.G & 7u) == 0u) {
+      const uint4 v = *reinterpret_cast<const uint4*>(p);
+      in[0] = v.x; in[1] = v.y; in[2] = v.z; in[3] = v.w;
+    } else {
+      const u32x4_a4 v = *reinterpret_cast<const u32x4_a4*>(p);
+      in[0] = v.x; in[1] = v.y; in[2] = v.z; in[3] = v.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float a = __uint_as_float(in[j] << 16), b = __uint_as_float(in[j] & 0xffff0000u);
+      a = fmaxf(__builtin_fmaf(nc, z[2 * j], a), 0.0f);
+      b = fmaxf(__builtin_fmaf(nc, z[2 * j + 1], b), 0.0f);
+      out[j] = pack_bf16x2(a, b);
+    }
+    if ((sg.G & 7u) == 0u) {
+      *reinterpret_cast<uint4*>(p) = make_uint4(out[0], out[1], out[2], out[3]);
+    } else {
+      u32x4_a4 o = {out[0], out[1], out[2], out[3]};
+      *reinterpret_cast<u32x4_a4*>(p) = o;
+    }
+  } else if ((sg.G & 1u) == 0u) {      // the last, partial block of a row: dword accesses
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (2u * j < nv) {
+        uint32_t w = reinterpret_cast<const uint32_t*>(p)[j];
+        float a = __uint_as_float(w << 16), b = __uint_as_float(w & 0xffff0000u);
+        a = fmaxf(__builtin_fmaf(nc, z[2 * j], a), 0.0f);
+        b = fmaxf(__builtin_fmaf(nc, z[2 * j + 1], b), 0.0f);
+        reinterpret_cast<uint32_t*>(p)[j] = pack_bf16x2(a, b);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if ((uint32_t)j < nv) {
+        float a = fmaxf(__builtin_fmaf(nc, z[j], bf16_to_f32(p[j])), 0.0f);
+        p[j] = (bf16_t)(pack_bf16x2(a, 0.0f) & 0xffffu);
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void scale_update_kernel(bf16_t* __restrict__ arena, UpdPlan plan,
                                                            uint32_t seed_lo, uint32_t seed_hi,
                                                            float eta, float dclip_host,
@@ -22,60 +108,11 @@ __global__ __launch_bounds__(256) void scale_update_kernel(bf16_t* __restrict__ 
   } else {
     c = eta * dclip_host;
   }
-  const uint32_t wg = blockIdx.x, layer = blockIdx.y;
-  UpdSeg sg = plan.seg[0];
-#pragma unroll
-  for (int i = 1; i < 4; ++i)
-    if ((uint32_t)i < plan.n_seg && wg >= plan.seg[i].first_wg) sg = plan.seg[i];
-  const uint32_t Gb = (sg.G + 7u) >> 3;
-  const uint32_t u = (wg - sg.first_wg) * 256u + threadIdx.x;
-  if (u >= sg.rows * Gb) return;
-  // row = u / Gb, gb = u % Gb for u < 2^24 (checked on the host)
-  uint32_t row = (uint32_t)((float)u * __builtin_amdgcn_rcpf((float)Gb));
-  int32_t gb = (int32_t)(u - __umul24(row, Gb));
-  if (gb < 0) { row -= 1; gb += (int32_t)Gb; }
-  else if (gb >= (int32_t)Gb) { row += 1; gb -= (int32_t)Gb; }
-
+  const UpdUnit un = update_locate(arena, plan, blockIdx.x, blockIdx.y, threadIdx.x);
+  if (!un.p) return;
   float z[8];
-  scale_normals8(seed_lo, seed_hi, 0u, layer * plan.rows_per_layer + sg.row_base + row,
-                 (uint32_t)gb, z);
-  bf16_t* p = arena + (uint64_t)layer * plan.layer_stride + sg.off + (uint64_t)row * sg.G +
-              (uint32_t)gb * 8u;
-  const float nc = -c;
-  if ((sg.G & 7u) == 0u) {
-    uint4 v = *reinterpret_cast<const uint4*>(p);
-    uint32_t in[4] = {v.x, v.y, v.z, v.w}, out[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float a = __uint_as_float(in[j] << 16), b = __uint_as_float(in[j] & 0xffff0000u);
-      a = fmaxf(__builtin_fmaf(nc, z[2 * j], a), 0.0f);
-      b = fmaxf(__builtin_fmaf(nc, z[2 * j + 1], b), 0.0f);
-      out[j] = pack_bf16x2(a, b);
-    }
-    *reinterpret_cast<uint4*>(p) = make_uint4(out[0], out[1], out[2], out[3]);
-  } else {
-    const uint32_t nv = min(8u, sg.G - (uint32_t)gb * 8u);
-    if ((sg.G & 1u) == 0u) {      // rows start 4-byte aligned: dword accesses
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (2u * j < nv) {
-          uint32_t w = reinterpret_cast<const uint32_t*>(p)[j];
-          float a = __uint_as_float(w << 16), b = __uint_as_float(w & 0xffff0000u);
-          a = fmaxf(__builtin_fmaf(nc, z[2 * j], a), 0.0f);
-          b = fmaxf(__builtin_fmaf(nc, z[2 * j + 1], b), 0.0f);
-          reinterpret_cast<uint32_t*>(p)[j] = pack_bf16x2(a, b);
-        }
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        if ((uint32_t)j < nv) {
-          float a = fmaxf(__builtin_fmaf(nc, z[j], bf16_to_f32(p[j])), 0.0f);
-          p[j] = (bf16_t)(pack_bf16x2(a, 0.0f) & 0xffffu);
-        }
-      }
-    }
-  }
+  scale_normals8(seed_lo, seed_hi, 0u, un.noise_row, un.gb, z);
+  update_apply(un, c, z);
 }
 
 hipError_t launch_scale_update(void* arena, const UpdPlan& plan, uint32_t seed_lo,

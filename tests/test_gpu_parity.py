@@ -441,7 +441,10 @@ def test_expand_then_multiply_full_size_sampled(oracle):
 
 
 @pytest.mark.parametrize("rows,G,row_base", [(38400, 32, 31 * 42496), (4096, 86, 31 * 42496 + 38400),
-                                             (48128, 40, 0), (5120, 108, 1877000)])
+                                             (48128, 40, 0), (5120, 108, 1877000),
+                                             # beyond a million counters the update runs as one persistent
+                                             # workgroup per compute unit with the angle factors in an LDS table
+                                             (300000, 32, 7), (131072, 86, 1000000), (1100000, 3, 5)])
 def test_update_at_real_tensor_sizes_bit_exact(oracle, rows, G, row_base):
     # one decoder layer's update segments of the Llama-2-7B / 13B shapes
     rng = np.random.default_rng(rows + G)
