@@ -135,7 +135,8 @@ def dequant_zp(qp, s, zp, seed, row_base, eps_signed, group=128, to_bf16=False, 
     return out
 
 
-def qlinear_zp(x, qp, s_eff, zp, group=128):
+def qlinear_zp(x, qp, s_eff, zp, group=128, g_idx=None):
+    gi = None if g_idx is None else np.ascontiguousarray(g_idx, dtype=np.int32)
     x = _f64(x)
     qp = np.ascontiguousarray(qp, dtype=np.uint8)
     s_eff = _f64(s_eff)
@@ -144,18 +145,21 @@ def qlinear_zp(x, qp, s_eff, zp, group=128):
     N = qp.shape[0]
     y = np.zeros((M, N), dtype=np.float64)
     lib().orc_qlinear_zp(_p(x), C.c_uint64(M), C.c_uint64(K), _p(qp), _p(s_eff), _p(zp), C.c_uint64(N),
-                         C.c_uint32(group), None, _p(y))
+                         C.c_uint32(group), None, _p(gi) if gi is not None else None, _p(y))
     return y
 
 
-def rtn_quantize_asym(w, group=128):
-    """Asymmetric RTN groups: (nibbles [N,K/2], zero-points [N,G], bf16 scales [N,G])."""
+def rtn_quantize_asym(w, group=128, scale_fmt=0, g_idx=None):
+    """Asymmetric RTN groups: (nibbles [N,K/2], zero-points [N,G], scales [N,G] rounded to bf16
+    (scale_fmt 0) or fp16 (1)).  g_idx: int32 [K], the group of every input column (None: k // group)."""
     w = _f32(w)
     N, K = w.shape
+    gi = None if g_idx is None else np.ascontiguousarray(g_idx, dtype=np.int32)
     qp = np.zeros((N, K // 2), dtype=np.uint8)
     zp = np.zeros((N, K // group), dtype=np.uint8)
     s = np.zeros((N, K // group), dtype=np.float32)
-    lib().orc_rtn_quantize_asym(_p(w), C.c_uint64(N), C.c_uint64(K), C.c_uint32(group), _p(qp), _p(zp), _p(s))
+    lib().orc_rtn_quantize_asym(_p(w), C.c_uint64(N), C.c_uint64(K), C.c_uint32(group), C.c_int(scale_fmt),
+                                _p(gi) if gi is not None else None, _p(qp), _p(zp), _p(s))
     return qp, zp, s
 
 
@@ -297,7 +301,8 @@ class _Cfg(C.Structure):
     _fields_ = [("arch", C.c_uint32), ("n_layers", C.c_uint32), ("d_model", C.c_uint32),
                 ("n_heads", C.c_uint32), ("d_ffn", C.c_uint32), ("vocab", C.c_uint32),
                 ("max_seq", C.c_uint32), ("group", C.c_uint32),
-                ("norm_eps", C.c_double), ("rope_theta", C.c_double), ("quant", C.c_uint32)]
+                ("norm_eps", C.c_double), ("rope_theta", C.c_double), ("quant", C.c_uint32),
+                ("act_order", C.c_uint32)]
 
 
 @dataclass
@@ -320,27 +325,37 @@ class Model:
     group: int = 128
     quant: int = 0           # 0: int4 + group scales; 1: codebook + per-channel scales; 2: int4 + zero-points;
                              # 3: NormalFloat-4 blocks of 64
+    scale_fmt: int = 0       # storage type of the group scales: 0 bf16, 1 fp16 (quant = 2 checkpoints)
+    act_order: bool = False  # quant = 2: every zero-point tensor is followed by g_idx int32 [K]
 
     @property
     def n_rows(self):
         return sum(s.rows for s in self.segments)
 
 
-def build_model(shape: dict, table, group=128, asym=False, nf4=False) -> Model:
+def build_model(shape: dict, table, group=128, asym=False, nf4=False, fp16_scales=False, g_idx=None) -> Model:
     """Quantize the 'w' entries of a (name, kind, array) table with RTN
     (Eq. 3 with the absmax scale; asym: with zero-points, each packed weight then followed by
-    its zero-point tensor; nf4: NormalFloat-4 blocks of 64) and lay the scales out in arena order."""
+    its zero-point tensor; nf4: NormalFloat-4 blocks of 64) and lay the scales out in arena order.
+    fp16_scales (asym only): the scales are stored in fp16, as in the 4-bit checkpoints of Sec. 4.1.
+    g_idx (asym only): a function K -> int32 [K] giving the group of every input column of a linear with
+    K inputs (activation reordering); each zero-point tensor is then followed by that array."""
     if nf4:
         group = 64
+    assert asym or (not fp16_scales and g_idx is None)
     tensors, names, segs, scales = [], [], [], []
     off = 0
     row = 0
     for name, kind, arr in table:
         if kind == "w":
             if asym:
-                qp, zp, s = rtn_quantize_asym(arr, group)
+                gi = None if g_idx is None else np.ascontiguousarray(g_idx(arr.shape[1]), dtype=np.int32)
+                qp, zp, s = rtn_quantize_asym(arr, group, 1 if fp16_scales else 0, gi)
                 tensors += [qp, zp]
                 names += [name, name + ".zp"]
+                if gi is not None:
+                    tensors.append(gi)
+                    names.append(name + ".g_idx")
             elif nf4:
                 qp, s = nf4_quantize(arr, group)
                 tensors.append(qp)
@@ -357,7 +372,7 @@ def build_model(shape: dict, table, group=128, asym=False, nf4=False) -> Model:
             tensors.append(_f32(arr))
             names.append(name)
     return Model(shape, tensors, names, np.concatenate(scales).astype(np.float32), segs, group,
-                 3 if nf4 else (2 if asym else 0))
+                 3 if nf4 else (2 if asym else 0), 1 if fp16_scales else 0, g_idx is not None)
 
 
 def fp16_rne(x):
@@ -429,7 +444,8 @@ def forward_loss(model: Model, s_eff, tok, act_bf16=True, want_hidden=False, wan
     sh = model.shape
     cfg = _Cfg(0 if sh["arch"] == "llama" else 1, sh["n_layers"], sh["d_model"], sh["n_heads"],
                sh["d_ffn"], sh["vocab"], sh["max_seq"], model.group,
-               sh.get("norm_eps", 1e-5), sh.get("rope_theta", 10000.0), model.quant)
+               sh.get("norm_eps", 1e-5), sh.get("rope_theta", 10000.0), model.quant,
+               1 if model.act_order else 0)
     tok = np.ascontiguousarray(tok, dtype=np.int32)
     B, S = tok.shape
     s_eff = _f64(s_eff)
@@ -519,7 +535,7 @@ def update_scales(model: Model, seed: int, eta: float, d_clipped: float, scales=
         view = sc[sg.offset:sg.offset + sg.rows * sg.G]
         lib().orc_update_scales(_p(view), C.c_uint32(sg.rows), C.c_uint32(sg.G),
                                 C.c_uint32(sg.row_base), C.c_uint64(seed), C.c_float(eta),
-                                C.c_float(d_clipped))
+                                C.c_float(d_clipped), C.c_int(model.scale_fmt))
     return sc
 
 

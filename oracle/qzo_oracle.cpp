@@ -29,6 +29,7 @@
 #include <cstdint>
 #include <cstring>
 #include <cstdlib>
+#include <map>
 #include <vector>
 #include <algorithm>
 
@@ -248,30 +249,41 @@ void orc_rtn_quantize(const float* w, uint64_t N, uint64_t K, uint32_t group,
 }
 
 // Asymmetric round-to-nearest groups (Eq. 3 with a zero-point): the range [min(w,0), max(w,0)]
-// of a group is mapped on the 16 levels, s = bf16((hi - lo) / 15), zp = rne(-lo / s) clamped to
+// of a group is mapped on the 16 levels, s = round16((hi - lo) / 15), zp = rne(-lo / s) clamped to
 // 0..15, u = clamp(rne(w / s) + zp, 0, 15); an all-zero group gives s = 0, zp = 8, u = 8.
-void orc_rtn_quantize_asym(const float* w, uint64_t N, uint64_t K, uint32_t group, uint8_t* qp,
-                           uint8_t* zp, float* s) {
+// scale_fmt: the storage type of the scale, 0 = bf16, 1 = fp16 (what the 4-bit checkpoints of
+// Sec. 4.1 hold).  g_idx (optional, int32 [K]): the group of every input column (activation
+// reordering: the quantizer visits columns in an order of its own, so a group is any 128 columns,
+// not 128 consecutive ones); null = k / group.
+void orc_rtn_quantize_asym(const float* w, uint64_t N, uint64_t K, uint32_t group, int scale_fmt,
+                           const int32_t* g_idx, uint8_t* qp, uint8_t* zp, float* s) {
   uint64_t G = K / group;
-  for (uint64_t n = 0; n < N; ++n)
+  auto grp = [&](uint64_t k) { return g_idx ? (uint64_t)g_idx[k] : k / group; };
+  for (uint64_t n = 0; n < N; ++n) {
+    std::vector<float> lo(G, 0.f), hi(G, 0.f);
+    for (uint64_t k = 0; k < K; ++k) {
+      const float v = w[n * K + k];
+      lo[grp(k)] = std::min(lo[grp(k)], v);
+      hi[grp(k)] = std::max(hi[grp(k)], v);
+    }
     for (uint64_t g = 0; g < G; ++g) {
-      const float* wg = w + n * K + g * group;
-      float lo = 0.f, hi = 0.f;
-      for (uint32_t k = 0; k < group; ++k) { lo = std::min(lo, wg[k]); hi = std::max(hi, wg[k]); }
-      float sc = bf16_rne((hi - lo) / 15.0f);
+      const float raw = (hi[g] - lo[g]) / 15.0f;
+      const float sc = scale_fmt == 1 ? fp16_rne(raw) : bf16_rne(raw);
       int z0 = 8;
-      if (sc > 0.f) z0 = (int)std::min(15.0f, std::max(0.0f, std::nearbyintf(-lo / sc)));
+      if (sc > 0.f) z0 = (int)std::min(15.0f, std::max(0.0f, std::nearbyintf(-lo[g] / sc)));
       s[n * G + g] = sc;
       zp[n * G + g] = (uint8_t)z0;
-      for (uint32_t k = 0; k < group; ++k) {
-        int u = 8;
-        if (sc > 0.f) u = (int)std::min(15.0f, std::max(0.0f, std::nearbyintf(wg[k] / sc) + (float)z0));
-        uint64_t kk = g * group + k;
-        uint8_t* b = qp + n * (K / 2) + kk / 2;
-        if (kk & 1) *b = (uint8_t)((*b & 0x0f) | (u << 4));
-        else *b = (uint8_t)((*b & 0xf0) | u);
-      }
     }
+    for (uint64_t k = 0; k < K; ++k) {
+      const float sc = s[n * G + grp(k)];
+      const int z0 = zp[n * G + grp(k)];
+      int u = 8;
+      if (sc > 0.f) u = (int)std::min(15.0f, std::max(0.0f, std::nearbyintf(w[n * K + k] / sc) + (float)z0));
+      uint8_t* b = qp + n * (K / 2) + k / 2;
+      if (k & 1) *b = (uint8_t)((*b & 0x0f) | (u << 4));
+      else *b = (uint8_t)((*b & 0xf0) | u);
+    }
+  }
 }
 
 void orc_unpack_int4(const uint8_t* qp, uint64_t N, uint64_t K, int8_t* q) {
@@ -330,14 +342,16 @@ void orc_dequant_zp(const uint8_t* qp, const float* s, const uint8_t* zp, uint64
     }
 }
 void orc_qlinear_zp(const double* x, uint64_t M, uint64_t K, const uint8_t* qp, const double* s_eff,
-                    const uint8_t* zp, uint64_t N, uint32_t group, const float* bias, double* y) {
+                    const uint8_t* zp, uint64_t N, uint32_t group, const float* bias,
+                    const int32_t* g_idx, double* y) {
   uint64_t G = K / group;
 #pragma omp parallel for schedule(static)
   for (int64_t n = 0; n < (int64_t)N; ++n) {
     std::vector<double> wrow(K);
     for (uint64_t k = 0; k < K; ++k) {
       int u = unpack_q(qp, K, n, k) + 8;
-      wrow[k] = s_eff[n * G + k / group] * (double)(u - (int)zp[n * G + k / group]);
+      const uint64_t g = g_idx ? (uint64_t)g_idx[k] : k / group;
+      wrow[k] = s_eff[n * G + g] * (double)(u - (int)zp[n * G + g]);
     }
     for (uint64_t m = 0; m < M; ++m) {
       double acc = 0.0;
@@ -661,6 +675,8 @@ struct orc_config {
   uint32_t quant;       // 0 = int4 + per-group scales, 1 = codebook + per-channel scales (Llama only),
                         // 2 = int4 with zero-points: every packed weight is followed by u8 [N, K/group]
                         // 3 = NormalFloat-4 indices + per-block scales (group = block = 64)
+  uint32_t act_order;   // quant = 2 only: every zero-point tensor is followed by g_idx, int32 [K], the
+                        // group of each input column (activation reordering of the Sec. 4.1 checkpoints)
 };
 
 // Tensor table, in this order (all fp32 arrays holding bf16 values unless noted):
@@ -703,14 +719,17 @@ double orc_forward_loss(const orc_config* c, const void* const* T, const double*
   };
   const bool asym = c->quant == 2;
   // a packed int4 weight and, in the asymmetric format, the zero-point tensor that follows it
+  std::map<const uint8_t*, const int32_t*> group_index;     // of the weights that carry one
   auto take_w = [&](const uint8_t*& w, const uint8_t*& z) {
     w = (const uint8_t*)T[ti++];
     z = asym ? (const uint8_t*)T[ti++] : nullptr;
+    if (asym && c->act_order) group_index[w] = (const int32_t*)T[ti++];
   };
   auto qlin = [&](const double* x, uint64_t K, const uint8_t* w, const uint8_t* z, const double* sc,
                   uint64_t N, const float* bias, double* y) {
     if (c->quant == 3) orc_qlinear_nf4(x, M, K, w, sc, N, c->group, bias, y);
-    else if (z) orc_qlinear_zp(x, M, K, w, sc, z, N, c->group, bias, y);
+    else if (z) orc_qlinear_zp(x, M, K, w, sc, z, N, c->group, bias,
+                               group_index.count(w) ? group_index[w] : nullptr, y);
     else orc_qlinear(x, M, K, w, sc, N, c->group, bias, y);
   };
   for (uint32_t l = 0; l < c->n_layers; ++l) {
@@ -809,16 +828,17 @@ float orc_clip(float d, float C) {
 }
 // Delta_i <- max(Delta_i - eta*d'*z_i, 0) with z regenerated from the seed
 // (Algorithm 1), in the scales' storage arithmetic: c = eta*d' (one fp32
-// multiply), fp32 fma, clamp, bf16 round-to-nearest-even.
+// multiply), fp32 fma, clamp, round-to-nearest-even to the storage type
+// (scale_fmt 0: bf16, 1: fp16).
 void orc_update_scales(float* s, uint32_t n_rows, uint32_t G, uint32_t row_base, uint64_t seed,
-                       float eta, float d_clipped) {
+                       float eta, float d_clipped, int scale_fmt) {
   float cstep = eta * d_clipped;
   for (uint32_t r = 0; r < n_rows; ++r)
     for (uint32_t g = 0; g < G; ++g) {
       size_t i = (size_t)r * G + g;
       float z = scale_normal(seed, 0u, row_base + r, g);
       float v = std::fmaf(-cstep, z, s[i]);
-      s[i] = bf16_rne(std::max(v, 0.0f));
+      s[i] = scale_fmt == 1 ? fp16_rne(std::max(v, 0.0f)) : bf16_rne(std::max(v, 0.0f));
     }
 }
 

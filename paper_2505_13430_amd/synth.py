@@ -128,6 +128,12 @@ def kmajor_case(N: int, K: int, seed: int, group: int = GROUP):
     return qweight, qzeros, scales
 
 
+def act_order_g_idx(K: int, seed: int = 0, group: int = GROUP) -> np.ndarray:
+    """A group assignment as activation-reordering quantizers produce it: int32 [K], every group
+    of `group` columns scattered over the input dimension (a random permutation of k // group)."""
+    return np.random.default_rng(seed + K).permutation(np.arange(K) // group).astype(np.int32)
+
+
 def fp16_exact(x: np.ndarray) -> np.ndarray:
     """Values exactly representable in IEEE binary16, as fp32."""
     return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)

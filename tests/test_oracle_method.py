@@ -161,9 +161,12 @@ def _torch_forward(model, s_eff, tok, oracle):
         qi = oracle.unpack_int4(T[name], K).astype(np.float64)
         if model.quant == 3:        # NormalFloat-4: the stored nibble indexes the level table
             qi = oracle.nf4_levels().astype(np.float64)[(qi + 8).astype(np.int64)]
+        se = s_eff[s.offset:s.offset + s.rows * s.G].reshape(s.rows, s.G)
+        if name + ".g_idx" in T:    # activation reordering: column k belongs to group g_idx[k]
+            gi = T[name + ".g_idx"].astype(np.int64)
+            return _t(se[:, gi] * (qi + 8.0 - T[name + ".zp"].astype(np.float64)[:, gi]))
         if name + ".zp" in T:       # asymmetric groups: integer is (stored nibble - zero-point)
             qi = qi + 8.0 - np.repeat(T[name + ".zp"].astype(np.float64), 128, axis=1)
-        se = s_eff[s.offset:s.offset + s.rows * s.G].reshape(s.rows, s.G)
         return _t(np.repeat(se, model.group, axis=1) * qi)
 
     tk = torch.from_numpy(tok.astype(np.int64))
@@ -579,6 +582,90 @@ def test_asymmetric_forward_matches_torch_composition(oracle, arch):
     m8 = type(ms)(ms.shape, tensors, names, ms.scales, ms.segments, ms.group, 2)
     se_s = oracle.perturbed_scales(ms, seed=5, eps_signed=1e-3)
     assert oracle.forward_loss(m8, se_s, tok, act_bf16=True) == oracle.forward_loss(ms, se_s, tok, act_bf16=True)
+
+
+def test_fp16_group_scales_quantizer_and_update(oracle):
+    """The 4-bit checkpoints of Sec. 4.1 hold fp16 scales: the asymmetric quantizer and the update of
+    Algorithm 1 in that storage type."""
+    rng = np.random.default_rng(21)
+    N, K = 12, 512
+    w = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    qp, zp, s = oracle.rtn_quantize_asym(w, scale_fmt=1)
+    # the scale is the fp16 rounding (library's) of the range / 15, with 0 inside the range
+    wg = w.reshape(N, K // 128, 128)
+    lo, hi = np.minimum(wg.min(-1), 0), np.maximum(wg.max(-1), 0)
+    want = torch.from_numpy(((hi - lo) / np.float32(15)).astype(np.float32)).half().float().numpy()
+    assert np.array_equal(s, want)
+    assert not np.array_equal(s, oracle.rtn_quantize_asym(w)[2])          # bf16 scales differ
+    u = oracle.unpack_int4(qp, K) + 8
+    rec = s[:, :, None].astype(np.float64) * (u.reshape(N, -1, 128) - zp[:, :, None].astype(np.float64))
+    assert (np.abs(rec - wg) <= (0.5 + 15 * 2.0 ** -11) * s[:, :, None] + 1e-12).all()
+    # the update: fp16(max(s - eta d' z, 0)) with z of (row_base + r, g), against torch's rounding
+    class Seg:
+        pass
+    sg = Seg()
+    sg.name, sg.offset, sg.rows, sg.G, sg.row_base = "t", 0, N, K // 128, 40
+    z = oracle.scale_normals(9, 40, N, K // 128).astype(np.float64)
+    for eta, dc in ((1e-7, 100.0), (1e-5, -37.5), (1.0, 1.0)):
+        m = oracle.Model(shape={}, tensors=[], names=[], scales=s.reshape(-1).copy(), segments=[sg], scale_fmt=1)
+        got = oracle.update_scales(m, 9, eta, dc).reshape(N, -1)
+        c = np.float64(np.float32(eta) * np.float32(dc))
+        exact = np.maximum(s.astype(np.float64) - c * z, 0.0).astype(np.float32)    # the fp32 fma, via fp64
+        assert np.array_equal(got, torch.from_numpy(exact).half().float().numpy()), (eta, dc)
+        assert got.min() >= 0
+    # at the paper's learning rate and clipping threshold (eta 1e-7, |d'| = 100: steps of 1e-5 |z|)
+    # fp16 storage (half-ulp 1.9e-6 at these scales) moves most scales, bf16 storage (1.5e-5) very few
+    big = (rng.uniform(0.005, 0.01, (400, 32))).astype(np.float32)
+    sg.rows, sg.G = 400, 32
+    h16 = torch.from_numpy(big).half().float().numpy()
+    b16 = synth.bf16_exact(big)
+    m16 = oracle.Model(shape={}, tensors=[], names=[], scales=h16.reshape(-1).copy(), segments=[sg], scale_fmt=1)
+    mb = oracle.Model(shape={}, tensors=[], names=[], scales=b16.reshape(-1).copy(), segments=[sg])
+    moved16 = (oracle.update_scales(m16, 3, 1e-7, 100.0) != h16.reshape(-1)).mean()
+    movedb = (oracle.update_scales(mb, 3, 1e-7, 100.0) != b16.reshape(-1)).mean()
+    assert moved16 > 0.5 and movedb < 0.1, (moved16, movedb)
+
+
+def test_act_order_quantizer_linear_and_forward(oracle):
+    """Activation reordering: column k belongs to group g_idx[k].  Quantizing with a group index is
+    quantizing the column-sorted matrix with consecutive groups."""
+    rng = np.random.default_rng(22)
+    N, K = 10, 512
+    w = (rng.standard_normal((N, K)) * 0.02 + 0.01 * np.sin(np.arange(N))[:, None]).astype(np.float32)
+    gi = synth.act_order_g_idx(K, seed=1)
+    assert sorted(np.bincount(gi)) == [128] * 4 and not np.array_equal(gi, np.arange(K) // 128)
+    P = np.argsort(gi, kind="stable")                    # columns grouped by their group
+    qp, zp, s = oracle.rtn_quantize_asym(w, g_idx=gi)
+    qs, zs, ss = oracle.rtn_quantize_asym(w[:, P])
+    assert np.array_equal(s, ss) and np.array_equal(zp, zs)
+    assert np.array_equal(oracle.unpack_int4(qp, K)[:, P], oracle.unpack_int4(qs, K))
+    # the identity assignment is the plain quantizer
+    plain = oracle.rtn_quantize_asym(w)
+    ident = oracle.rtn_quantize_asym(w, g_idx=np.arange(K) // 128)
+    assert all(np.array_equal(a, b) for a, b in zip(plain, ident))
+    # linear = library matmul of the reordered dequantized matrix
+    x = rng.standard_normal((7, K))
+    se = oracle.effective_scales(s, 5, 11, 1e-3)
+    wd = oracle.dequant_zp(qp, s, zp, 11, 5, 1e-3, g_idx=gi).astype(np.float64)
+    u = oracle.unpack_int4(qp, K).astype(np.float64) + 8.0
+    assert np.allclose(wd, se[:, gi] * (u - zp[:, gi]), rtol=1e-6, atol=1e-12)
+    y = oracle.qlinear_zp(x, qp, se, zp, g_idx=gi)
+    assert np.allclose(y, (_t(x) @ _t(se[:, gi] * (u - zp[:, gi])).T).numpy(), rtol=1e-12, atol=1e-12)
+    assert not np.allclose(y, oracle.qlinear_zp(x, qp, se, zp))          # the index matters
+    # whole forward, both families, against the torch composition; fp16 scales at the same time
+    for arch in ("llama", "opt"):
+        sh = dict(MINI, arch=arch)
+        m = oracle.build_model(sh, synth.tensor_table(sh, 3), asym=True, fp16_scales=True,
+                               g_idx=lambda K: synth.act_order_g_idx(K, seed=2))
+        assert m.act_order and m.scale_fmt == 1 and any(n.endswith(".g_idx") for n in m.names)
+        tok = synth.tokens(sh, 4)
+        sef = oracle.perturbed_scales(m, seed=5, eps_signed=1e-3)
+        got = oracle.forward_loss(m, sef, tok, act_bf16=False)
+        assert math.isclose(got, _torch_forward(m, sef, tok, oracle), rel_tol=1e-10)
+        assert abs(got - math.log(sh["vocab"])) < 0.2
+        st = oracle.qzo_step(m, tok, seed=5, eps=1e-3, eta=1e-5, Cthr=100.0)
+        assert np.array_equal(st["scales"], torch.from_numpy(st["scales"]).half().float().numpy())
+        assert (st["scales"] != m.scales).mean() > 0.2 and abs(st["d"]) > 0.1
 
 
 # --------------------------- joint SPSA on the un-quantized parameters (Sec. 3.2 / 4.1) ----
