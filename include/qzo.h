@@ -75,6 +75,12 @@ typedef struct {
                               (group_size = 64), W = s * level[u] (Sec. 4.3's quantizer) */
   float norm_eps;       /* 1e-5 */
   float rope_theta;     /* 10000 (Llama only) */
+  uint32_t scale_fp16;  /* quant 0 and 2: 0 = the group scales of the arena are bf16, 1 = fp16 (the scale
+                           type of the 4-bit checkpoints of Sec. 4.1; with the paper's eta = 1e-7 a bf16
+                           arena rounds nearly every update away, an fp16 arena does not) */
+  uint32_t act_order;   /* quant 2 only: 1 = every zero-point tensor of the table is followed by g_idx,
+                           int32 [K], the group of each input column (activation reordering); such a
+                           linear always runs expand-then-multiply */
 } qzo_model_config;
 
 typedef struct {
@@ -104,15 +110,17 @@ typedef struct {
  *          codes_o, cb_o, ffn_norm, codes_gu [2F,d/8], cb_gu, codes_down [d,F/8], cb_down };
  *          the arena then holds one fp16 scale per output row, per layer [3d][d][2F][d].
  *   quant = 2 (either family): the quant = 0 table with every int4 weight [N,K/2] directly
- *          followed by its zero-points uint8 [N,K/128], values 0..15; scales and the arena as
- *          for quant = 0.
+ *          followed by its zero-points uint8 [N,K/128], values 0..15, and with act_order = 1 by its
+ *          group index int32 [K] (values 0 .. K/128 - 1; column k of the linear belongs to group
+ *          g_idx[k] instead of k/128; scales, zero-points and noise stay per (row, group)); scales
+ *          and the arena as for quant = 0.
  *   quant = 3 (either family): the quant = 0 table with NormalFloat-4 indices in place of the int4
  *          nibbles (same [N,K/2] layout, even k in the low nibble); the arena holds [N, K/64] scales
  *          per linear.  Every linear is first written out as a perturbed bf16 matrix in the workspace
  *          and multiplied by a plain bf16 GEMM.
- * `scale_arena_dev` holds every quantized linear's bf16 scales back to back in
- * the same order ([N, K/128] each); it is the only model memory the library
- * writes.  Only the decoder-block linears are quantized and trained (their
+ * `scale_arena_dev` holds every quantized linear's scales (bf16, or fp16 with
+ * scale_fp16 = 1) back to back in the same order ([N, K/128] each); it is the only
+ * model memory the library writes.  Only the decoder-block linears are quantized and trained (their
  * scale count is the paper's Table 2 "trainable parameters"); embeddings,
  * norms, biases and lm_head are fixed bf16.  Row ids for the noise follow the
  * arena order.  Requires d_model % 128 == 0, d_ffn % 128 == 0,
@@ -255,11 +263,11 @@ qzo_status qzo_dequant_gemm_static(const void* x_dev, const void* q_dev, const v
  * 0..15 (zp = 8 everywhere is qzo_dequant_gemm).  The integer difference is formed exactly and
  * multiplied once, so the bf16 weight tile equals the definition bit for bit.  Everything
  * else (layouts, sumsq_dev, the few-token path, scratch) as in qzo_dequant_gemm.  The trained
- * quantities are the scales; zero-points are fixed.
+ * quantities are the scales; zero-points are fixed.  scale_fp16: 0 = s_dev holds bf16, 1 = fp16.
  */
 qzo_status qzo_dequant_gemm_zp(const void* x_dev, const void* q_dev, const void* s_dev,
-                               const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
-                               uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                               const void* zp_dev, uint32_t scale_fp16, uint32_t row_base, uint32_t M,
+                               uint32_t N, uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
                                void* y_dev, float* sumsq_dev, void* scratch_dev,
                                uint64_t scratch_bytes, void* stream);
 
@@ -269,13 +277,14 @@ qzo_status qzo_dequant_gemm_zp(const void* x_dev, const void* q_dev, const void*
  *   qzeros_dev  int32 [K/group, N/8]  word (g, nn) = zero-points of n = 8 nn .. 8 nn + 7, lowest first
  *   scales_dev  fp16  [K/group, N]
  * into this library's layout: q_dev bytes [N, K/2], zp_dev uint8 [N, K/group] = (stored zero-point
- * + zero_add) & 15 (some writers store the zero-point minus one: zero_add = 1), s_dev bf16
- * [N, K/group] = the fp16 scale rounded to nearest even.  group == 128, K % 128 == 0, N % 8 == 0.
- * Activation reordering (a per-column group index) is not supported.
+ * + zero_add) & 15 (some writers store the zero-point minus one: zero_add = 1), s_dev
+ * [N, K/group] = the fp16 scale itself (scale_fp16 = 1) or rounded to nearest even to bf16 (0).
+ * group == 128, K % 128 == 0, N % 8 == 0.  A checkpoint's group index (activation reordering) needs
+ * no repacking: it is handed to the model table as it is.
  */
 qzo_status qzo_repack_kmajor(const void* qweight_dev, const void* qzeros_dev, const void* scales_dev,
-                             uint32_t N, uint32_t K, uint32_t group, uint32_t zero_add, void* q_dev,
-                             void* zp_dev, void* s_dev, void* stream);
+                             uint32_t N, uint32_t K, uint32_t group, uint32_t zero_add,
+                             uint32_t scale_fp16, void* q_dev, void* zp_dev, void* s_dev, void* stream);
 
 /*
  * Codebook variant of the perturbed linear (the paper's 2-bit setting, Sec. 3.2.1 last
@@ -297,16 +306,23 @@ qzo_status qzo_codebook_gemm(const void* x_dev, const void* codes_dev, const voi
 qzo_status qzo_apply_update_channel(void* c_dev, uint32_t n_rows, uint32_t row_base, uint64_t seed,
                                     float eta, float d_clipped, void* stream);
 
-/* The update loop of Algorithm 1 on one tensor's scales: s_dev bf16 [n_rows, G],
- * updated in place with c = eta*d_clipped. */
+/* The update loop of Algorithm 1 on one tensor's scales: s_dev [n_rows, G], bf16 (scale_fp16 = 0) or
+ * fp16 (1), updated in place with c = eta*d_clipped and rounded to nearest even in that type. */
 qzo_status qzo_apply_update(void* s_dev, uint32_t n_rows, uint32_t G, uint32_t row_base,
-                            uint64_t seed, float eta, float d_clipped, void* stream);
+                            uint64_t seed, float eta, float d_clipped, uint32_t scale_fp16, void* stream);
 
 /* RTN quantizer of Eq. 3 with the k=4 absmax scale: w_dev fp32 [N,K] ->
  * q_dev packed int4 [N,K/2], s_dev bf16 [N,K/group].  Model construction, not
  * part of the timed step. */
 qzo_status qzo_rtn_quantize(const float* w_dev, uint32_t N, uint32_t K, uint32_t group,
                             void* q_dev, void* s_dev, void* stream);
+/* The same with a zero-point (Eq. 3 on the group's range, which always includes 0): the scale is
+ * round16((max - min) / 15), the zero-point rne(-min / scale) clamped to 0..15, the nibble
+ * clamp(rne(w / scale) + zero-point, 0, 15); an all-zero group gets scale 0, zero-point 8, nibbles 8.
+ * q_dev packed nibbles [N,K/2], zp_dev uint8 [N,K/group], s_dev [N,K/group] in bf16 (scale_fp16 = 0)
+ * or fp16 (1).  group == 128. */
+qzo_status qzo_rtn_quantize_asym(const float* w_dev, uint32_t N, uint32_t K, uint32_t group,
+                                 uint32_t scale_fp16, void* q_dev, void* zp_dev, void* s_dev, void* stream);
 
 /* Inspection entry points used by the parity tests. */
 /* out_dev fp32 [n_rows, G] = z(row0 + r, g), noise stream `stream_id` (0 = group scales). */
@@ -322,11 +338,12 @@ qzo_status qzo_debug_normal_pairs(const uint32_t* words_dev, uint32_t n, float* 
 qzo_status qzo_debug_dequant(const void* q_dev, const void* s_dev, uint32_t row_base, uint32_t N,
                              uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
                              void* w_eff_dev, void* stream);
-/* The same with zero-points (zp_dev uint8 [N, K/group], nullable = 8): the B operand of
- * qzo_dequant_gemm_zp. */
+/* The same with zero-points (zp_dev uint8 [N, K/group], nullable = 8) and bf16 or fp16 scales: the B
+ * operand of qzo_dequant_gemm_zp. */
 qzo_status qzo_debug_dequant_zp(const void* q_dev, const void* s_dev, const void* zp_dev,
-                                uint32_t row_base, uint32_t N, uint32_t K, uint32_t group,
-                                uint64_t seed, float eps, int sign, void* w_eff_dev, void* stream);
+                                uint32_t scale_fp16, uint32_t row_base, uint32_t N, uint32_t K,
+                                uint32_t group, uint64_t seed, float eps, int sign, void* w_eff_dev,
+                                void* stream);
 
 /*
  * NormalFloat-4 blocks (the quantizer of the text-to-image experiment, Sec. 4.3): a block of 64

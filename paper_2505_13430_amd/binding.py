@@ -25,7 +25,7 @@ EXPORTS = [
     "qzo_forward_loss", "qzo_step", "qzo_model_apply_update",
     "qzo_model_dense_count", "qzo_model_joint_table_bytes", "qzo_model_enable_joint", "qzo_step_joint",
     "qzo_linear_scratch_bytes", "qzo_dequant_gemm", "qzo_dequant_gemm_static", "qzo_dequant_gemm_zp", "qzo_apply_update",
-    "qzo_rtn_quantize", "qzo_repack_kmajor",
+    "qzo_rtn_quantize", "qzo_rtn_quantize_asym", "qzo_repack_kmajor",
     "qzo_int4_expand", "qzo_int4_scratch_bytes", "qzo_int4_gemm_expanded", "qzo_model_set_int4_path",
     "qzo_nf4_expand", "qzo_nf4_scratch_bytes", "qzo_nf4_gemm",
     "qzo_codebook_scratch_bytes", "qzo_codebook_gemm", "qzo_apply_update_channel",
@@ -46,7 +46,8 @@ class qzo_model_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("arch", C.c_uint32), ("n_layers", C.c_uint32),
                 ("d_model", C.c_uint32), ("n_heads", C.c_uint32), ("d_ffn", C.c_uint32),
                 ("vocab", C.c_uint32), ("max_seq", C.c_uint32), ("group_size", C.c_uint32),
-                ("quant", C.c_uint32), ("norm_eps", C.c_float), ("rope_theta", C.c_float)]
+                ("quant", C.c_uint32), ("norm_eps", C.c_float), ("rope_theta", C.c_float),
+                ("scale_fp16", C.c_uint32), ("act_order", C.c_uint32)]
 
 
 class qzo_buf(C.Structure):
@@ -87,7 +88,8 @@ def make_config(shape: dict) -> qzo_model_config:
     return qzo_model_config(C.sizeof(qzo_model_config), 0 if shape["arch"] == "llama" else 1,
                             shape["n_layers"], shape["d_model"], shape["n_heads"], shape["d_ffn"],
                             shape["vocab"], shape["max_seq"], shape.get("group", 128), shape.get("quant", 0),
-                            shape.get("norm_eps", 1e-5), shape.get("rope_theta", 10000.0))
+                            shape.get("norm_eps", 1e-5), shape.get("rope_theta", 10000.0),
+                            int(shape.get("scale_fp16", 0)), int(shape.get("act_order", 0)))
 
 
 def qzo_model_scale_count(shape: dict) -> int:
@@ -223,13 +225,16 @@ def qzo_dequant_gemm_static(x, q, s, row_base, seed, eps, sign, y, sumsq=None, g
 
 
 def qzo_dequant_gemm_zp(x, q, s, zp, row_base, seed, eps, sign, y, sumsq=None, group=128, stream=None,
-                        scratch="auto"):
+                        scratch="auto", scale_fp16=None):
+    """s: bf16 or fp16 scales (scale_fp16 defaults to the tensor's dtype)."""
+    if scale_fp16 is None:
+        scale_fp16 = s.dtype == torch.float16
     M, K = x.shape
     N = q.shape[0]
     if isinstance(scratch, str):
         scratch = scratch_for(x.device, qzo_linear_scratch_bytes(M, N, K, sumsq is not None)) if K % 128 == 0 and K else None
-    _check(lib().qzo_dequant_gemm_zp(_ptr(x), _ptr(q), _ptr(s), _ptr(zp), C.c_uint32(row_base),
-                                     C.c_uint32(M), C.c_uint32(N), C.c_uint32(K), C.c_uint32(group),
+    _check(lib().qzo_dequant_gemm_zp(_ptr(x), _ptr(q), _ptr(s), _ptr(zp), C.c_uint32(int(scale_fp16)),
+                                     C.c_uint32(row_base), C.c_uint32(M), C.c_uint32(N), C.c_uint32(K), C.c_uint32(group),
                                      C.c_uint64(seed), C.c_float(eps), C.c_int(sign), _ptr(y),
                                      _ptr(sumsq), *_scratch_args(scratch), _stream(stream)))
 
@@ -237,7 +242,8 @@ def qzo_dequant_gemm_zp(x, q, s, zp, row_base, seed, eps, sign, y, sumsq=None, g
 def qzo_repack_kmajor(qweight, qzeros, scales, zero_add, q, zp, s, group=128, stream=None):
     K, N = qweight.shape[0] * 8, qweight.shape[1]
     _check(lib().qzo_repack_kmajor(_ptr(qweight), _ptr(qzeros), _ptr(scales), C.c_uint32(N),
-                                   C.c_uint32(K), C.c_uint32(group), C.c_uint32(zero_add), _ptr(q),
+                                   C.c_uint32(K), C.c_uint32(group), C.c_uint32(zero_add),
+                                   C.c_uint32(int(s.dtype == torch.float16)), _ptr(q),
                                    _ptr(zp), _ptr(s), _stream(stream)))
 
 
@@ -245,13 +251,21 @@ def qzo_apply_update(s, row_base, seed, eta, d_clipped, stream=None):
     n_rows, G = s.shape
     _check(lib().qzo_apply_update(_ptr(s), C.c_uint32(n_rows), C.c_uint32(G), C.c_uint32(row_base),
                                   C.c_uint64(seed), C.c_float(eta), C.c_float(d_clipped),
-                                  _stream(stream)))
+                                  C.c_uint32(int(s.dtype == torch.float16)), _stream(stream)))
 
 
 def qzo_rtn_quantize(w, q, s, group=128, stream=None):
     N, K = w.shape
     _check(lib().qzo_rtn_quantize(_ptr(w), C.c_uint32(N), C.c_uint32(K), C.c_uint32(group), _ptr(q),
                                   _ptr(s), _stream(stream)))
+
+
+def qzo_rtn_quantize_asym(w, q, zp, s, group=128, stream=None):
+    """s: bf16 or fp16 output tensor; its dtype selects the scale's storage type."""
+    N, K = w.shape
+    _check(lib().qzo_rtn_quantize_asym(_ptr(w), C.c_uint32(N), C.c_uint32(K), C.c_uint32(group),
+                                       C.c_uint32(int(s.dtype == torch.float16)), _ptr(q), _ptr(zp), _ptr(s),
+                                       _stream(stream)))
 
 
 def qzo_debug_normals(seed, stream_id, row0, out, stream=None):
@@ -334,7 +348,8 @@ def qzo_debug_bf16_gemm(x, w, y, pipe=2, stream=None):
 
 def qzo_debug_dequant_zp(q, s, zp, row_base, seed, eps, sign, w_eff, group=128, stream=None):
     N, K = w_eff.shape
-    _check(lib().qzo_debug_dequant_zp(_ptr(q), _ptr(s), _ptr(zp), C.c_uint32(row_base), C.c_uint32(N),
+    _check(lib().qzo_debug_dequant_zp(_ptr(q), _ptr(s), _ptr(zp), C.c_uint32(int(s.dtype == torch.float16)),
+                                      C.c_uint32(row_base), C.c_uint32(N),
                                       C.c_uint32(K), C.c_uint32(group), C.c_uint64(seed),
                                       C.c_float(eps), C.c_int(sign), _ptr(w_eff), _stream(stream)))
 

@@ -97,6 +97,11 @@ qzo_status check_cfg(const qzo_model_config* c) {
   if (c->d_model % c->n_heads) return fail(QZO_ERR_SHAPE, "d_model not divisible by n_heads");
   uint32_t dh = c->d_model / c->n_heads;
   if (dh != 64 && dh != 128) return fail(QZO_ERR_SHAPE, "head size must be 64 or 128");
+  if (c->scale_fp16 > 1 || c->act_order > 1) return fail(QZO_ERR_ARG, "scale_fp16 and act_order must be 0 or 1");
+  if (c->scale_fp16 && c->quant != 0 && c->quant != 2)
+    return fail(QZO_ERR_UNSUPPORTED, "fp16 group scales are built for the int4 formats (quant 0 and 2)");
+  if (c->act_order && c->quant != 2)
+    return fail(QZO_ERR_UNSUPPORTED, "a group index per column belongs to the zero-point format (quant 2)");
   return QZO_OK;
 }
 
@@ -114,8 +119,10 @@ void layer_linears(const qzo_model_config& c, Linear lin[4]) {
 }
 
 // Merge a layer's consecutive linears with equal groups-per-row into update segments.
-qzo_status build_plan(const Linear* lin, int n_lin, uint32_t n_layers, UpdPlan& p, uint32_t group = 128) {
+qzo_status build_plan(const Linear* lin, int n_lin, uint32_t n_layers, UpdPlan& p, uint32_t group = 128,
+                      uint32_t scale_fp16 = 0) {
   std::memset(&p, 0, sizeof(p));
+  p.fp16 = scale_fp16;
   uint32_t wg = 0;
   for (int i = 0; i < n_lin; ++i) {
     const uint32_t G = lin[i].K / group;
@@ -157,6 +164,7 @@ void table_layout(const qzo_model_config& c, std::vector<uint64_t>& need, std::v
     }
     packed(N * K / 2);
     if (asym) packed(N * K / 128);
+    if (asym && c.act_order) packed(K * 4);       // int32 group index of every input column
   };
   for (uint32_t l = 0; l < c.n_layers; ++l) {
     if (llama) {
@@ -180,7 +188,7 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   // over 2 * batch sequences (the int4 weights are then read once per step).
   const uint64_t M1 = (uint64_t)batch * seq;
   const bool int4 = c.quant == 0 || c.quant == 2;
-  const bool stack = M1 <= SKINNY_MAX_M_DUAL && int4 && !m->dense_master;
+  const bool stack = M1 <= SKINNY_MAX_M_DUAL && int4 && !m->dense_master && !c.act_order;
   const uint64_t M = stack ? 2 * M1 : M1, d = c.d_model, F = c.d_ffn;
   const uint64_t n_slices = ((c.vocab + 255) / 256) * 4;
   Workspace w;
@@ -202,14 +210,14 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   w.losses = (float*)take(256);
   // few-token path of the int4 GEMM: fp32 partial sums of the K slices of the largest linear
   uint64_t sk = 0;
-  if (M1 <= SKINNY_MAX_M && int4)
+  if (M1 <= SKINNY_MAX_M && int4 && !c.act_order)
     for (int i = 0; i < 4; ++i)
       sk = std::max<uint64_t>(sk, skinny_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.skinny = (float*)take(sk * 4);
   if (sk == 0) w.skinny = nullptr;
   // more tokens than that but still too few output tiles for the chip: split-K partial sums
   uint64_t sp = 0;
-  if ((M1 > SKINNY_MAX_M && int4) || c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK))
+  if ((M1 > SKINNY_MAX_M && int4) || c.act_order || c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK))
     for (int i = 0; i < 4; ++i)
       sp = std::max<uint64_t>(sp, tile_split_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.split = (float*)take(sp * 4);
@@ -218,7 +226,7 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   // and the NormalFloat-4 format at any token count (with its perturbed block scales, fp32)
   uint64_t ex = 0, sx = 0;
   for (int i = 0; i < 4; ++i) {
-    const bool expanded = c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK) ||
+    const bool expanded = c.quant == 3 || c.act_order || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK) ||
                           (int4 && m->int4_path != 1 && !stack &&
                            (m->int4_path == 2 || M1 >= expand_min_m_int4(m->lin[i].N, m->lin[i].K)));
     if (expanded) ex = std::max<uint64_t>(ex, (uint64_t)m->lin[i].N * m->lin[i].K * 2);
@@ -321,10 +329,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
     // zero-points every packed weight is followed by one more tensor.
     static const uint32_t wpos_llama[4] = {1, 2, 4, 5}, wpos_opt[4] = {2, 4, 8, 10};
     const uint32_t* wpos = llama ? wpos_llama : wpos_opt;
+    const uint32_t extra = (asym ? 1u : 0u) + (c.act_order ? 1u : 0u);    // tensors that follow a packed weight
     auto tpos = [&](uint32_t k) {
       uint32_t shift = 0;
-      if (asym)
-        for (int i = 0; i < 4; ++i) shift += wpos[i] < k;
+      for (int i = 0; i < 4; ++i) shift += wpos[i] < k ? extra : 0u;
       return k + shift;
     };
     auto ti = [&](uint32_t k) { return T[tpos(k)].ptr_dev; };
@@ -338,8 +346,24 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       if (n_pass == 1) g.M = M;
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
+      g.s_fp16 = c.scale_fp16;
       g.skinny_ws = w.skinny;
       g.split_ws = w.split;
+      if (c.act_order) {
+        // a group index per column: scale and zero-point are looked up per weight while the perturbed
+        // matrix is written out; the fused kernels, whose k-tile shares one scale per row, cannot serve it
+        const int32_t* g_idx = (const int32_t*)T[tpos(wpos[li]) + 2].ptr_dev;
+        const bool split = w.split && tile_ksplit(g.M, g.N, g.K, nullptr) > 1;
+        {
+          ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
+          hipError_t e = launch_expand_int4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.zp, g_idx, g.N, g.K,
+                                                 (epi & EPI_SWIGLU) != 0 && !split, w.wexp, st);
+          if (e != hipSuccess) return e;
+        }
+        g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
+        ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+        return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
+      }
       if (c.quant == 3) {
         // NormalFloat-4: table lookup and scaling once per weight, then a plain bf16 GEMM
         const bool split = w.split && tile_ksplit(g.M, g.N, g.K, nullptr) > 1;
@@ -358,8 +382,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
         // many tokens: write the perturbed matrix out once, then a plain bf16 GEMM
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
-          hipError_t e = launch_expand_int4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.zp, g.N, g.K,
-                                                 (epi & EPI_SWIGLU) != 0, w.wexp, st);
+          hipError_t e = launch_expand_int4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.zp, nullptr, g.N,
+                                                 g.K, (epi & EPI_SWIGLU) != 0, w.wexp, st);
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;
@@ -488,7 +512,8 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
   const bool llama = cfg->arch == 0;
   const bool codebook = cfg->quant == 1;
   const bool asym = cfg->quant == 2;
-  const uint32_t per_layer = codebook ? 10 : (llama ? 6 : 12) + (asym ? 4 : 0), head = llama ? 1 : 2, tail = llama ? 2 : 3;
+  const uint32_t per_layer = codebook ? 10 : (llama ? 6 : 12) + (asym ? 4 : 0) + (cfg->act_order ? 4 : 0),
+                 head = llama ? 1 : 2, tail = llama ? 2 : 3;
   if (n_tensors != head + per_layer * cfg->n_layers + tail)
     return fail(QZO_ERR_ARG, "tensor count does not match the architecture's table");
   uint64_t want = 0;
@@ -521,7 +546,7 @@ qzo_status qzo_model_create(const qzo_model_config* cfg, const qzo_buf* tensors,
   m->rows_per_layer = m->lin[3].row_base + m->lin[3].N;
   m->tensors_per_layer = per_layer;
   m->first_layer_tensor = head;
-  st = build_plan(m->lin, 4, cfg->n_layers, m->plan, cfg->group_size);
+  st = build_plan(m->lin, 4, cfg->n_layers, m->plan, cfg->group_size, cfg->scale_fp16);
   if (st != QZO_OK) { delete m; return st; }
   for (int i = 0; i < 4; ++i)       // one linear written out in bf16 must fit 32-bit byte offsets
     if ((uint64_t)m->lin[i].N * m->lin[i].K * 2 >= (1ull << 31)) {
@@ -649,7 +674,8 @@ static qzo_status step_impl(qzo_model* m, const int32_t* tokens_dev, uint32_t ba
     return fail(QZO_ERR_ARG, "eps/eta not finite");
   hipStream_t s = (hipStream_t)stream;
   Workspace w = carve(m, batch, seq, workspace_dev);
-  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && (m->cfg.quant == 0 || m->cfg.quant == 2) && !m->dense_master) {
+  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && (m->cfg.quant == 0 || m->cfg.quant == 2) && !m->dense_master &&
+      !m->cfg.act_order) {
     // few tokens: one forward over both passes, the weights are read once
     st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s, nullptr, 2, w.losses + 1);
     if (st != QZO_OK) return st;
@@ -711,14 +737,15 @@ qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float 
 }
 
 qzo_status qzo_apply_update(void* s_dev, uint32_t n_rows, uint32_t G, uint32_t row_base,
-                            uint64_t seed, float eta, float d_clipped, void* stream) {
+                            uint64_t seed, float eta, float d_clipped, uint32_t scale_fp16, void* stream) {
   if (!s_dev) return fail(QZO_ERR_ARG, "s_dev is null");
+  if (scale_fp16 > 1) return fail(QZO_ERR_ARG, "scale_fp16 must be 0 or 1");
   if (!aligned16(s_dev)) return fail(QZO_ERR_ALIGN, "s_dev not 16-byte aligned");
   if (!std::isfinite(eta) || !std::isfinite(d_clipped)) return fail(QZO_ERR_ARG, "eta/d' not finite");
   if (n_rows == 0 || G == 0) return QZO_OK;
   Linear lin = {n_rows, G * 128, 0, row_base};
   UpdPlan plan;
-  qzo_status st = build_plan(&lin, 1, 1, plan);
+  qzo_status st = build_plan(&lin, 1, 1, plan, 128, scale_fp16);
   if (st != QZO_OK) return st;
   QZO_HIP(launch_scale_update(s_dev, plan, (uint32_t)seed, (uint32_t)(seed >> 32), eta, d_clipped,
                               nullptr, (hipStream_t)stream));
@@ -759,7 +786,7 @@ static qzo_status linear_check(const void* x_dev, const void* q_dev, const void*
 
 // The launches of a single perturbed linear; scratch (ls.total bytes) is known to be large enough.
 static qzo_status dequant_gemm_run(const void* x_dev, const void* q_dev, const void* s_dev, const void* zp_dev,
-                                   uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint64_t seed,
+                                   uint32_t scale_fp16, uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint64_t seed,
                                    float eps, int sign, void* y_dev, float* sumsq_dev, void* scratch,
                                    const LinearScratch& ls, hipStream_t st) {
   if (M == 0 || N == 0) {
@@ -771,6 +798,7 @@ static qzo_status dequant_gemm_run(const void* x_dev, const void* q_dev, const v
   g.M = M; g.N = N; g.K = K; g.row_base = row_base;
   g.seed_lo = (uint32_t)seed; g.seed_hi = (uint32_t)(seed >> 32);
   g.eps_signed = sign > 0 ? eps : -eps;
+  g.s_fp16 = scale_fp16;
   float* part = (float*)((unsigned char*)scratch + ls.part_off);
   if (ls.skinny) g.skinny_ws = part;
   if (ls.split) g.split_ws = part;
@@ -784,7 +812,7 @@ static qzo_status dequant_gemm_run(const void* x_dev, const void* q_dev, const v
 }
 
 static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void* s_dev,
-                               const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
+                               const void* zp_dev, uint32_t scale_fp16, uint32_t row_base, uint32_t M, uint32_t N,
                                uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
                                void* y_dev, float* sumsq_dev, void* scratch_dev, uint64_t scratch_bytes,
                                void* stream) {
@@ -796,8 +824,8 @@ static qzo_status dequant_gemm(const void* x_dev, const void* q_dev, const void*
     if ((uintptr_t)scratch_dev & 255u) return fail(QZO_ERR_ALIGN, "scratch not 256-byte aligned");
     if (scratch_bytes < ls.total) return fail(QZO_ERR_WORKSPACE, "scratch too small: see qzo_linear_scratch_bytes");
   }
-  return dequant_gemm_run(x_dev, q_dev, s_dev, zp_dev, row_base, M, N, K, seed, eps, sign, y_dev, sumsq_dev,
-                          scratch_dev, ls, (hipStream_t)stream);
+  return dequant_gemm_run(x_dev, q_dev, s_dev, zp_dev, scale_fp16, row_base, M, N, K, seed, eps, sign, y_dev,
+                          sumsq_dev, scratch_dev, ls, (hipStream_t)stream);
 }
 
 qzo_status qzo_linear_scratch_bytes(uint32_t M, uint32_t N, uint32_t K, int with_sumsq, uint64_t* out) {
@@ -811,7 +839,7 @@ qzo_status qzo_dequant_gemm(const void* x_dev, const void* q_dev, const void* s_
                             uint32_t row_base, uint32_t M, uint32_t N, uint32_t K, uint32_t group,
                             uint64_t seed, float eps, int sign, void* y_dev, float* sumsq_dev,
                             void* scratch_dev, uint64_t scratch_bytes, void* stream) {
-  return dequant_gemm(x_dev, q_dev, s_dev, nullptr, row_base, M, N, K, group, seed, eps, sign, y_dev,
+  return dequant_gemm(x_dev, q_dev, s_dev, nullptr, 0u, row_base, M, N, K, group, seed, eps, sign, y_dev,
                       sumsq_dev, scratch_dev, scratch_bytes, stream);
 }
 
@@ -852,31 +880,33 @@ qzo_status qzo_dequant_gemm_static(const void* x_dev, const void* q_dev, const v
     ptr = g_static_scratch_ptr[dev];
   }
   // nothing in the scratch has to start at zero: every partial sum that is read was written by this call
-  return dequant_gemm_run(x_dev, q_dev, s_dev, nullptr, row_base, M, N, K, seed, eps, sign, y_dev, sumsq_dev,
+  return dequant_gemm_run(x_dev, q_dev, s_dev, nullptr, 0u, row_base, M, N, K, seed, eps, sign, y_dev, sumsq_dev,
                           ptr, ls, (hipStream_t)stream);
 }
 
 qzo_status qzo_dequant_gemm_zp(const void* x_dev, const void* q_dev, const void* s_dev,
-                               const void* zp_dev, uint32_t row_base, uint32_t M, uint32_t N,
-                               uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
+                               const void* zp_dev, uint32_t scale_fp16, uint32_t row_base, uint32_t M,
+                               uint32_t N, uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
                                void* y_dev, float* sumsq_dev, void* scratch_dev, uint64_t scratch_bytes,
                                void* stream) {
   if (!zp_dev) return fail(QZO_ERR_ARG, "zp_dev is null");
-  return dequant_gemm(x_dev, q_dev, s_dev, zp_dev, row_base, M, N, K, group, seed, eps, sign, y_dev,
+  if (scale_fp16 > 1) return fail(QZO_ERR_ARG, "scale_fp16 must be 0 or 1");
+  return dequant_gemm(x_dev, q_dev, s_dev, zp_dev, scale_fp16, row_base, M, N, K, group, seed, eps, sign, y_dev,
                       sumsq_dev, scratch_dev, scratch_bytes, stream);
 }
 
 qzo_status qzo_repack_kmajor(const void* qweight_dev, const void* qzeros_dev, const void* scales_dev,
-                             uint32_t N, uint32_t K, uint32_t group, uint32_t zero_add, void* q_dev,
-                             void* zp_dev, void* s_dev, void* stream) {
+                             uint32_t N, uint32_t K, uint32_t group, uint32_t zero_add, uint32_t scale_fp16,
+                             void* q_dev, void* zp_dev, void* s_dev, void* stream) {
   if (!qweight_dev || !qzeros_dev || !scales_dev || !q_dev || !zp_dev || !s_dev)
     return fail(QZO_ERR_ARG, "null device pointer");
   if (group != 128 || K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
   if (N == 0 || N % 8) return fail(QZO_ERR_SHAPE, "N must be a positive multiple of 8");
   if (zero_add > 15) return fail(QZO_ERR_ARG, "zero_add must be 0 .. 15");
+  if (scale_fp16 > 1) return fail(QZO_ERR_ARG, "scale_fp16 must be 0 or 1");
   if (!aligned16(q_dev) || !aligned16(s_dev)) return fail(QZO_ERR_ALIGN, "output not 16-byte aligned");
-  QZO_HIP(launch_repack_kmajor(qweight_dev, qzeros_dev, scales_dev, N, K, zero_add, q_dev, zp_dev, s_dev,
-                               (hipStream_t)stream));
+  QZO_HIP(launch_repack_kmajor(qweight_dev, qzeros_dev, scales_dev, N, K, zero_add, scale_fp16 != 0, q_dev,
+                               zp_dev, s_dev, (hipStream_t)stream));
   return QZO_OK;
 }
 
@@ -1129,6 +1159,17 @@ qzo_status qzo_rtn_quantize(const float* w_dev, uint32_t N, uint32_t K, uint32_t
   return QZO_OK;
 }
 
+qzo_status qzo_rtn_quantize_asym(const float* w_dev, uint32_t N, uint32_t K, uint32_t group,
+                                 uint32_t scale_fp16, void* q_dev, void* zp_dev, void* s_dev, void* stream) {
+  if (!w_dev || !q_dev || !zp_dev || !s_dev) return fail(QZO_ERR_ARG, "null device pointer");
+  if (!aligned16(w_dev) || !aligned16(q_dev) || !aligned16(s_dev))
+    return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
+  if (group != 128 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
+  if (scale_fp16 > 1) return fail(QZO_ERR_ARG, "scale_fp16 must be 0 or 1");
+  QZO_HIP(launch_rtn_quantize_asym(w_dev, N, K, scale_fp16 != 0, q_dev, zp_dev, s_dev, (hipStream_t)stream));
+  return QZO_OK;
+}
+
 qzo_status qzo_debug_normals(uint64_t seed, uint32_t stream_id, uint32_t row0, uint32_t n_rows,
                              uint32_t G, float* out_dev, void* stream) {
   if (!out_dev) return fail(QZO_ERR_ARG, "out_dev is null");
@@ -1152,19 +1193,21 @@ qzo_status qzo_debug_normal_pairs(const uint32_t* words_dev, uint32_t n, float* 
 qzo_status qzo_debug_dequant(const void* q_dev, const void* s_dev, uint32_t row_base, uint32_t N,
                              uint32_t K, uint32_t group, uint64_t seed, float eps, int sign,
                              void* w_eff_dev, void* stream) {
-  return qzo_debug_dequant_zp(q_dev, s_dev, nullptr, row_base, N, K, group, seed, eps, sign, w_eff_dev,
+  return qzo_debug_dequant_zp(q_dev, s_dev, nullptr, 0u, row_base, N, K, group, seed, eps, sign, w_eff_dev,
                               stream);
 }
 
 qzo_status qzo_debug_dequant_zp(const void* q_dev, const void* s_dev, const void* zp_dev,
-                                uint32_t row_base, uint32_t N, uint32_t K, uint32_t group,
-                                uint64_t seed, float eps, int sign, void* w_eff_dev, void* stream) {
+                                uint32_t scale_fp16, uint32_t row_base, uint32_t N, uint32_t K,
+                                uint32_t group, uint64_t seed, float eps, int sign, void* w_eff_dev,
+                                void* stream) {
+  if (scale_fp16 > 1) return fail(QZO_ERR_ARG, "scale_fp16 must be 0 or 1");
   if (!q_dev || !s_dev || !w_eff_dev) return fail(QZO_ERR_ARG, "null device pointer");
   if (!aligned16(q_dev) || !aligned16(s_dev) || !aligned16(w_eff_dev))
     return fail(QZO_ERR_ALIGN, "device pointer not 16-byte aligned");
   if (group != 128 || K == 0 || K % 128) return fail(QZO_ERR_SHAPE, "group must be 128 and divide K");
   if (sign != 1 && sign != -1) return fail(QZO_ERR_ARG, "sign must be +1 or -1");
-  QZO_HIP(launch_debug_dequant(q_dev, s_dev, zp_dev, row_base, N, K, (uint32_t)seed, (uint32_t)(seed >> 32),
+  QZO_HIP(launch_debug_dequant(q_dev, s_dev, zp_dev, scale_fp16 != 0, row_base, N, K, (uint32_t)seed, (uint32_t)(seed >> 32),
                                sign > 0 ? eps : -eps, w_eff_dev, (hipStream_t)stream));
   return QZO_OK;
 }

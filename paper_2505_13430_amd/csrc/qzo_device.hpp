@@ -19,6 +19,12 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
 }
+// A stored group scale (16 bits: bf16, or fp16 when the arena is fp16) as fp32.
+__device__ __forceinline__ float scale_to_f32(uint32_t bits16, bool fp16) {
+  return fp16 ? (float)__builtin_bit_cast(_Float16, (uint16_t)bits16) : __uint_as_float(bits16 << 16);
+}
+// fp32 -> the scale's storage type, round-to-nearest-even, as 16 bits.
+__device__ __forceinline__ uint32_t f32_to_scale(float f, bool fp16);
 // two floats -> packed pair of bf16 (lo in the low half).
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
@@ -27,6 +33,16 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   bf2 r = __builtin_convertvector(v, bf2);   // v_cvt_pk_bf16_f32, RNE
   return __builtin_bit_cast(uint32_t, r);
 }
+
+// two floats -> packed pair in the scale's storage type.
+__device__ __forceinline__ uint32_t pack_scale_x2(float lo, float hi, bool fp16) {
+  if (fp16) {
+    const _Float16 a = (_Float16)lo, b = (_Float16)hi;      // v_cvt_f16_f32, RNE
+    return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+  }
+  return pack_bf16x2(lo, hi);
+}
+__device__ __forceinline__ uint32_t f32_to_scale(float f, bool fp16) { return pack_scale_x2(f, 0.0f, fp16) & 0xffffu; }
 
 struct u32x4_t { uint32_t x, y, z, w; };
 

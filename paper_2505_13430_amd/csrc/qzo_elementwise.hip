@@ -21,7 +21,7 @@ struct u32x4_a4 { uint32_t x, y, z, w; } __attribute__((packed, aligned(4)));
 
 // The eight scales of one Philox counter: where they are, how many of them exist, their noise row.
 struct UpdUnit {
-  bf16_t* p;          // null: no such counter (beyond the segment's last)
+  bf16_t* p;          // null: no such counter (beyond the segment's last); 16-bit scales, bf16 or fp16
   uint32_t G, nv;     // groups per row of the segment; scales of this counter that exist (1 .. 8)
   uint32_t noise_row, gb;
 };
@@ -46,7 +46,7 @@ __device__ __forceinline__ UpdUnit update_locate(bf16_t* __restrict__ arena, con
   r.gb = (uint32_t)gb;
   return r;
 }
-__device__ __forceinline__ void update_apply(const UpdUnit& un, float c, const float z[8]) {
+__device__ __forceinline__ void update_apply(const UpdUnit& un, float c, const float z[8], bool fp16) {
   if (!un.p) return;
   bf16_t* p = un.p;
   struct { uint32_t G; } sg = {un.G};
@@ -64,10 +64,10 @@ __device__ __forceinline__ void update_apply(const UpdUnit& un, float c, const f
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      float a = __uint_as_float(in[j] << 16), b = __uint_as_float(in[j] & 0xffff0000u);
+      float a = scale_to_f32(in[j] & 0xffffu, fp16), b = scale_to_f32(in[j] >> 16, fp16);
       a = fmaxf(__builtin_fmaf(nc, z[2 * j], a), 0.0f);
       b = fmaxf(__builtin_fmaf(nc, z[2 * j + 1], b), 0.0f);
-      out[j] = pack_bf16x2(a, b);
+      out[j] = pack_scale_x2(a, b, fp16);
     }
     if ((sg.G & 7u) == 0u) {
       *reinterpret_cast<uint4*>(p) = make_uint4(out[0], out[1], out[2], out[3]);
@@ -80,18 +80,18 @@ __device__ __forceinline__ void update_apply(const UpdUnit& un, float c, const f
     for (int j = 0; j < 4; ++j) {
       if (2u * j < nv) {
         uint32_t w = reinterpret_cast<const uint32_t*>(p)[j];
-        float a = __uint_as_float(w << 16), b = __uint_as_float(w & 0xffff0000u);
+        float a = scale_to_f32(w & 0xffffu, fp16), b = scale_to_f32(w >> 16, fp16);
         a = fmaxf(__builtin_fmaf(nc, z[2 * j], a), 0.0f);
         b = fmaxf(__builtin_fmaf(nc, z[2 * j + 1], b), 0.0f);
-        reinterpret_cast<uint32_t*>(p)[j] = pack_bf16x2(a, b);
+        reinterpret_cast<uint32_t*>(p)[j] = pack_scale_x2(a, b, fp16);
       }
     }
   } else {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       if ((uint32_t)j < nv) {
-        float a = fmaxf(__builtin_fmaf(nc, z[j], bf16_to_f32(p[j])), 0.0f);
-        p[j] = (bf16_t)(pack_bf16x2(a, 0.0f) & 0xffffu);
+        float a = fmaxf(__builtin_fmaf(nc, z[j], scale_to_f32(p[j], fp16)), 0.0f);
+        p[j] = (bf16_t)f32_to_scale(a, fp16);
       }
     }
   }
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void scale_update_kernel(bf16_t* __restrict__ 
   if (!un.p) return;
   float z[8];
   scale_normals8(seed_lo, seed_hi, 0u, un.noise_row, un.gb, z);
-  update_apply(un, c, z);
+  update_apply(un, c, z, plan.fp16 != 0);
 }
 
 hipError_t launch_scale_update(void* arena, const UpdPlan& plan, uint32_t seed_lo,
@@ -293,6 +293,44 @@ hipError_t launch_rtn_quantize(const float* w, uint32_t N, uint32_t K, void* q, 
   return hipGetLastError();
 }
 
+// The same with a zero-point: the group's range [min(w, 0), max(w, 0)] on the 16 levels.
+__global__ __launch_bounds__(256) void rtn_quantize_asym_kernel(const float* __restrict__ w, uint32_t N,
+                                                                uint32_t K, bool s_fp16,
+                                                                uint8_t* __restrict__ q,
+                                                                uint8_t* __restrict__ zp,
+                                                                bf16_t* __restrict__ s) {
+  const uint32_t G = K >> 7;
+  const uint64_t grp = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (grp >= (uint64_t)N * G) return;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint64_t n = grp / G;
+  const uint32_t g = (uint32_t)(grp - n * G);
+  const float2 v = *reinterpret_cast<const float2*>(w + n * K + (uint64_t)g * 128 + lane * 2);
+  const float hi = wave_max(fmaxf(fmaxf(v.x, v.y), 0.0f));
+  const float lo = -wave_max(fmaxf(fmaxf(-v.x, -v.y), 0.0f));
+  const uint32_t sbits = f32_to_scale((hi - lo) / 15.0f, s_fp16);
+  const float sc = scale_to_f32(sbits, s_fp16);
+  int z0 = 8, q0 = 8, q1 = 8;
+  if (sc > 0.0f) {
+    z0 = (int)fminf(15.0f, fmaxf(0.0f, rintf(-lo / sc)));
+    q0 = (int)fminf(15.0f, fmaxf(0.0f, rintf(v.x / sc) + (float)z0));
+    q1 = (int)fminf(15.0f, fmaxf(0.0f, rintf(v.y / sc) + (float)z0));
+  }
+  q[n * (K >> 1) + (uint64_t)g * 64 + lane] = (uint8_t)(q0 | (q1 << 4));
+  if (lane == 0) {
+    s[grp] = (bf16_t)sbits;
+    zp[grp] = (uint8_t)z0;
+  }
+}
+hipError_t launch_rtn_quantize_asym(const float* w, uint32_t N, uint32_t K, bool s_fp16, void* q, void* zp,
+                                    void* s, hipStream_t st) {
+  uint64_t groups = (uint64_t)N * (K >> 7);
+  if (groups == 0) return hipSuccess;
+  rtn_quantize_asym_kernel<<<(uint32_t)((groups + 3) / 4), 256, 0, st>>>(w, N, K, s_fp16, (uint8_t*)q,
+                                                                         (uint8_t*)zp, (bf16_t*)s);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------- inspection -------
 __global__ void debug_normals_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
                                      uint32_t row0, uint32_t n_rows, uint32_t G, float* out) {
@@ -348,7 +386,7 @@ hipError_t launch_debug_normal_pairs(const uint32_t* words, uint32_t n, float* o
 // bf16((s + sign*eps*z) * wbar) for every weight: thread = (n, 8 consecutive k).
 // zp (nullable): one zero-point byte per (row, group); null = 8.
 __global__ void debug_dequant_kernel(const uint8_t* __restrict__ q, const bf16_t* __restrict__ s,
-                                     const uint8_t* __restrict__ zp,
+                                     const uint8_t* __restrict__ zp, bool s_fp16,
                                      uint32_t row_base, uint32_t N, uint32_t K, uint32_t seed_lo,
                                      uint32_t seed_hi, float eps_signed, bf16_t* __restrict__ out) {
   const uint32_t cpr = K >> 3;
@@ -361,7 +399,7 @@ __global__ void debug_dequant_kernel(const uint8_t* __restrict__ q, const bf16_t
   float zz = z[0];
 #pragma unroll
   for (int j = 1; j < 8; ++j) zz = ((g & 7u) == (uint32_t)j) ? z[j] : zz;
-  const float se = __builtin_fmaf(eps_signed, zz, bf16_to_f32(s[(uint64_t)n * G + g]));
+  const float se = __builtin_fmaf(eps_signed, zz, scale_to_f32(s[(uint64_t)n * G + g], s_fp16));
   const uint32_t packed = *reinterpret_cast<const uint32_t*>(q + (uint64_t)n * (K >> 1) + c * 4);
   const int z0 = zp ? (int)zp[(uint64_t)n * G + g] : 8;
   uint32_t o[4];
@@ -373,14 +411,14 @@ __global__ void debug_dequant_kernel(const uint8_t* __restrict__ q, const bf16_t
   }
   *reinterpret_cast<uint4*>(out + (uint64_t)n * K + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
-hipError_t launch_debug_dequant(const void* q, const void* s, const void* zp, uint32_t row_base, uint32_t N,
-                                uint32_t K, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+hipError_t launch_debug_dequant(const void* q, const void* s, const void* zp, bool s_fp16, uint32_t row_base,
+                                uint32_t N, uint32_t K, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                                 void* w_eff, hipStream_t st) {
   uint64_t units = (uint64_t)N * (K >> 3);
   if (units == 0) return hipSuccess;
   debug_dequant_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(
-      (const uint8_t*)q, (const bf16_t*)s, (const uint8_t*)zp, row_base, N, K, seed_lo, seed_hi, eps_signed,
-      (bf16_t*)w_eff);
+      (const uint8_t*)q, (const bf16_t*)s, (const uint8_t*)zp, s_fp16, row_base, N, K, seed_lo, seed_hi,
+      eps_signed, (bf16_t*)w_eff);
   return hipGetLastError();
 }
 
@@ -392,7 +430,7 @@ hipError_t launch_debug_dequant(const void* q, const void* s, const void* zp, ui
 __global__ void repack_kmajor_kernel(const uint32_t* __restrict__ qweight,
                                      const uint32_t* __restrict__ qzeros,
                                      const _Float16* __restrict__ scales, uint32_t N, uint32_t K,
-                                     uint32_t zero_add, uint32_t* __restrict__ q_out,
+                                     uint32_t zero_add, bool s_fp16, uint32_t* __restrict__ q_out,
                                      uint8_t* __restrict__ zp_out, bf16_t* __restrict__ s_out) {
   const uint32_t cpr = K >> 3, G = K >> 7;
   const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -404,17 +442,16 @@ __global__ void repack_kmajor_kernel(const uint32_t* __restrict__ qweight,
     const uint32_t g = kk >> 4;
     const uint32_t z = (qzeros[(uint64_t)g * (N >> 3) + (n >> 3)] >> (4 * (n & 7u))) & 15u;
     zp_out[(uint64_t)n * G + g] = (uint8_t)((z + zero_add) & 15u);
-    const uint32_t packed = pack_bf16x2((float)scales[(uint64_t)g * N + n], 0.0f);
-    s_out[(uint64_t)n * G + g] = (bf16_t)(packed & 0xffffu);
+    s_out[(uint64_t)n * G + g] = (bf16_t)f32_to_scale((float)scales[(uint64_t)g * N + n], s_fp16);
   }
 }
 hipError_t launch_repack_kmajor(const void* qweight, const void* qzeros, const void* scales,
-                                uint32_t N, uint32_t K, uint32_t zero_add, void* q_out, void* zp_out,
-                                void* s_out, hipStream_t st) {
+                                uint32_t N, uint32_t K, uint32_t zero_add, bool s_fp16, void* q_out,
+                                void* zp_out, void* s_out, hipStream_t st) {
   const uint64_t units = (uint64_t)N * (K >> 3);
   if (units == 0) return hipSuccess;
   repack_kmajor_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(
-      (const uint32_t*)qweight, (const uint32_t*)qzeros, (const _Float16*)scales, N, K, zero_add,
+      (const uint32_t*)qweight, (const uint32_t*)qzeros, (const _Float16*)scales, N, K, zero_add, s_fp16,
       (uint32_t*)q_out, (uint8_t*)zp_out, (bf16_t*)s_out);
   return hipGetLastError();
 }

@@ -114,7 +114,8 @@ __global__ __launch_bounds__(256) void perturbed_scales_all_kernel(const bf16_t*
   const uint32_t nv = min(8u, sg.G - gb * 8u);
 #pragma unroll
   for (int j = 0; j < 8; ++j)
-    if ((uint32_t)j < nv) se[base + j] = __builtin_fmaf(eps_signed, z[j], bf16_to_f32(arena[base + j]));
+    if ((uint32_t)j < nv)
+      se[base + j] = __builtin_fmaf(eps_signed, z[j], scale_to_f32(arena[base + j], plan.fp16 != 0));
 }
 
 // bf16 [N,K] from the indices and the perturbed scales: a thread turns one dword (eight
@@ -200,11 +201,11 @@ hipError_t launch_perturbed_scales_all(const void* arena, const UpdPlan& plan, u
   return hipGetLastError();
 }
 
-hipError_t launch_expand_int4_from(const void* q, const float* se, const void* zp, uint32_t N, uint32_t K,
-                                   bool swiglu, void* out_bf16, hipStream_t st) {
+hipError_t launch_expand_int4_from(const void* q, const float* se, const void* zp, const int32_t* g_idx,
+                                   uint32_t N, uint32_t K, bool swiglu, void* out_bf16, hipStream_t st) {
   if (N == 0) return hipSuccess;
   expand_int4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>(
-      (const uint32_t*)q, se, (const uint8_t*)zp, nullptr, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
+      (const uint32_t*)q, se, (const uint8_t*)zp, g_idx, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
   return hipGetLastError();
 }
 

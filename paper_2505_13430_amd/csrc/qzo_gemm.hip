@@ -360,7 +360,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       const uint32_t w_ = p_ == 0 ? zw[0] : (p_ == 1 ? zw[1] : (p_ == 2 ? zw[2] : zw[3]));   \
       normal_pair(w_, zz_, z_odd);                                                           \
     }                                                                                        \
-    const float se_ = __builtin_fmaf(a.eps_signed, zz_, bf16_to_f32(s_next));                \
+    const float se_ = __builtin_fmaf(a.eps_signed, zz_, scale_to_f32(s_next, a.s_fp16 != 0));                \
     se512 = ZP ? se_ : 512.0f * se_;                  /* ZP: the scale itself          */    \
     m8se = ZP ? -(float)z_next : -8.0f * se_;         /* ZP: the negated zero-point    */    \
   } while (0)

@@ -21,6 +21,7 @@ struct UpdPlan {
   uint32_t n_layers;
   uint64_t layer_stride;     // scales per layer
   uint32_t rows_per_layer;
+  uint32_t fp16;             // storage type of the arena: 0 bf16, 1 fp16
 };
 
 // Epilogue selection of the GEMM.
@@ -51,6 +52,7 @@ struct GemmArgs {
   uint32_t seed_lo, seed_hi;
   float eps_signed;
   uint32_t epi;
+  uint32_t s_fp16;      // int4 formats: s holds fp16 instead of bf16
 };
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
 // Few-token path (M <= 64): weights streamed once, K split over workgroups, partial sums in ws.
@@ -90,8 +92,8 @@ hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp,
 // out like the scale arena) and the expansions read them from there.
 hipError_t launch_perturbed_scales_all(const void* arena, const UpdPlan& plan, uint32_t seed_lo, uint32_t seed_hi,
                                        float eps_signed, float* se_all, hipStream_t st);
-hipError_t launch_expand_int4_from(const void* q, const float* se, const void* zp, uint32_t N, uint32_t K,
-                                   bool swiglu, void* out_bf16, hipStream_t st);
+hipError_t launch_expand_int4_from(const void* q, const float* se, const void* zp, const int32_t* g_idx,
+                                   uint32_t N, uint32_t K, bool swiglu, void* out_bf16, hipStream_t st);
 hipError_t launch_expand_nf4_from(const void* q, const float* se, uint32_t N, uint32_t K, bool swiglu,
                                   void* out_bf16, hipStream_t st);
 // Tokens per pass from which an int4 linear [N,K] is expanded first.  The expansion costs two short
@@ -164,6 +166,8 @@ hipError_t launch_scale_update(void* arena, const UpdPlan& plan, uint32_t seed_l
                                const qzo_step_result* res, hipStream_t st);
 hipError_t launch_rtn_quantize(const float* w, uint32_t N, uint32_t K, void* q, void* s,
                                hipStream_t st);
+hipError_t launch_rtn_quantize_asym(const float* w, uint32_t N, uint32_t K, bool s_fp16, void* q, void* zp,
+                                    void* s, hipStream_t st);
 hipError_t launch_debug_normals(uint32_t seed_lo, uint32_t seed_hi, uint32_t stream_id,
                                 uint32_t row0, uint32_t n_rows, uint32_t G, float* out,
                                 hipStream_t st);
@@ -172,10 +176,10 @@ hipError_t launch_debug_philox(uint32_t seed_lo, uint32_t seed_hi, const uint32_
 hipError_t launch_debug_normal_pairs(const uint32_t* words, uint32_t n, float* out,
                                      hipStream_t st);
 hipError_t launch_repack_kmajor(const void* qweight, const void* qzeros, const void* scales,
-                                uint32_t N, uint32_t K, uint32_t zero_add, void* q_out, void* zp_out,
-                                void* s_out, hipStream_t st);
-hipError_t launch_debug_dequant(const void* q, const void* s, const void* zp, uint32_t row_base, uint32_t N,
-                                uint32_t K, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
+                                uint32_t N, uint32_t K, uint32_t zero_add, bool s_fp16, void* q_out,
+                                void* zp_out, void* s_out, hipStream_t st);
+hipError_t launch_debug_dequant(const void* q, const void* s, const void* zp, bool s_fp16, uint32_t row_base,
+                                uint32_t N, uint32_t K, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
                                 void* w_eff, hipStream_t st);
 
 }  // namespace qzo

@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256, MT == 1 ? 3 : 2) void skinny_gemm_kernel(GemmA
           normal_pair(p == 0 ? zw[0] : (p == 1 ? zw[1] : (p == 2 ? zw[2] : zw[3])), z_even, z_odd);
         }
         fresh = false;
-        const float zz = (g & 1u) ? z_odd : z_even, s0 = __uint_as_float(sq[d] << 16);
+        const float zz = (g & 1u) ? z_odd : z_even, s0 = scale_to_f32(sq[d], a.s_fp16 != 0);
         const float se = __builtin_fmaf(a.eps_signed, zz, s0);
         const float nzp = ZP ? -(float)zq[d] : 0.0f;
         const float se512 = ZP ? se : 512.0f * se, m8se = ZP ? nzp : -8.0f * se;

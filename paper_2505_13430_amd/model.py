@@ -32,9 +32,9 @@ class DeviceModel:
         dev = []
         for a in host_tensors:
             t = torch.from_numpy(np.ascontiguousarray(a))
-            dev.append(t.to(device) if t.dtype == torch.uint8 else t.to(device).to(torch.bfloat16))
+            dev.append(t.to(device) if t.dtype in (torch.uint8, torch.int32) else t.to(device).to(torch.bfloat16))
         arena = torch.from_numpy(np.ascontiguousarray(host_scales, dtype=np.float32)).to(device).to(
-            torch.bfloat16)
+            torch.float16 if shape.get("scale_fp16") else torch.bfloat16)
         return cls(shape, dev, arena)
 
     @classmethod
@@ -60,11 +60,11 @@ class DeviceModel:
     def synthetic(cls, shape: dict, seed: int, device="cuda:0", asym=False, nf4=False):
         """Random-init model built on the device: weights ~ N(0, 0.02) drawn by
         torch, quantized by the library's RTN kernel (Eq. 3), tensor by tensor.
-        asym: the zero-point variant (quant = 2); each group then also gets a zero-point drawn
-        from 6..10 (the weights it stands for are shifted by a few steps; shapes, sizes and
-        the work per step are those of a zero-point checkpoint)."""
+        asym: the zero-point variant (quant = 2) as the 4-bit checkpoints of Sec. 4.1 hold it: the
+        library's asymmetric RTN kernel gives every group a zero-point and an fp16 scale (each
+        output row's weights are shifted by up to 0.03 so that the zero-points spread)."""
         if asym:
-            shape = dict(shape, quant=2)
+            shape = dict(shape, quant=2, scale_fp16=1)
         if nf4:
             # NormalFloat-4: uniform random level indices, block-64 scales ~ U(0.03, 0.09) (the absmax
             # of 64 weights ~ N(0, 0.02)): the shapes, sizes and work of such a checkpoint
@@ -74,7 +74,7 @@ class DeviceModel:
         d, V = shape["d_model"], shape["vocab"]
         llama = shape["arch"] == "llama"
         n_scales = qb.qzo_model_scale_count(shape)
-        arena = torch.empty(n_scales, dtype=torch.bfloat16, device=device)
+        arena = torch.empty(n_scales, dtype=torch.float16 if asym else torch.bfloat16, device=device)
         off = 0
 
         def fixed(*sz, mean=0.0, std=0.02):
@@ -90,10 +90,14 @@ class DeviceModel:
             w = torch.randn(N, K, generator=gen, device=device) * 0.02
             q = torch.empty(N, K // 2, dtype=torch.uint8, device=device)
             n = N * (K // 128)
+            if asym:
+                w += 0.03 * torch.sin(torch.arange(N, device=device, dtype=torch.float32))[:, None]
+                zp = torch.empty(N, K // 128, dtype=torch.uint8, device=device)
+                qb.qzo_rtn_quantize_asym(w, q, zp, arena[off:off + n].view(N, K // 128))
+                off += n
+                return [q, zp]
             qb.qzo_rtn_quantize(w, q, arena[off:off + n].view(N, K // 128))
             off += n
-            if asym:
-                return [q, torch.randint(6, 11, (N, K // 128), generator=gen, device=device, dtype=torch.uint8)]
             return [q]
 
         tensors = [fixed(V, d)]

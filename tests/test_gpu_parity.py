@@ -84,6 +84,22 @@ def test_weight_tile_bit_exact(oracle, N, K, row_base, sign):
     assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
 
 
+@pytest.mark.parametrize("fp16", [False, True], ids=["bf16", "fp16"])
+def test_asymmetric_rtn_quantizer_bit_exact(oracle, fp16):
+    rng = np.random.default_rng(4)
+    w = (rng.standard_normal((136, 640)) * 0.02 + 0.03 * np.sin(np.arange(136))[:, None]).astype(np.float32)
+    w[5, 128:256] = 0
+    w[6, :128] = np.abs(w[6, :128])
+    q = torch.zeros((136, 320), dtype=torch.uint8, device=DEV)
+    zp = torch.zeros((136, 5), dtype=torch.uint8, device=DEV)
+    s = torch.zeros((136, 5), dtype=torch.float16 if fp16 else torch.bfloat16, device=DEV)
+    qb.qzo_rtn_quantize_asym(_dev(w), q, zp, s)
+    qp, zo, sc = oracle.rtn_quantize_asym(w, scale_fmt=1 if fp16 else 0)
+    assert np.array_equal(q.cpu().numpy(), qp) and np.array_equal(zp.cpu().numpy(), zo)
+    assert np.array_equal(s.float().cpu().numpy(), sc)
+    assert zo.min() <= 3 and zo.max() >= 12 and zo[6, 0] == 0 and sc[5, 1] == 0
+
+
 def test_rtn_quantizer_bit_exact(oracle):
     rng = np.random.default_rng(3)
     w = (rng.standard_normal((136, 640)) * 0.02).astype(np.float32)
@@ -97,13 +113,15 @@ def test_rtn_quantizer_bit_exact(oracle):
 
 
 # --------------------------------------------------------------- update ----
+@pytest.mark.parametrize("fp16", [False, True], ids=["bf16", "fp16"])
 @pytest.mark.parametrize("rows,G", [(257, 32), (128, 86), (33, 3), (64, 8), (100, 108), (7, 1), (1, 16)])
-def test_update_given_d_bit_exact(oracle, rows, G):
+def test_update_given_d_bit_exact(oracle, rows, G, fp16):
     rng = np.random.default_rng(rows * G)
-    s = synth.bf16_exact(rng.uniform(0.0, 0.02, (rows, G)).astype(np.float32))
+    s = rng.uniform(0.0, 0.02, (rows, G)).astype(np.float32)
+    s = synth.fp16_exact(s) if fp16 else synth.bf16_exact(s)
     s[0, 0] = 0.0
-    for eta, dc in ((1e-5, 37.5), (1e-3, -100.0), (0.0, 5.0), (1e-5, 0.0)):
-        sd = _dev(s, torch.bfloat16)
+    for eta, dc in ((1e-5, 37.5), (1e-3, -100.0), (0.0, 5.0), (1e-5, 0.0), (1e-7, 100.0)):
+        sd = _dev(s, torch.float16 if fp16 else torch.bfloat16)
         guard = sd.clone()
         qb.qzo_apply_update(sd, 4242, 17, eta, dc)
 
@@ -111,13 +129,16 @@ def test_update_given_d_bit_exact(oracle, rows, G):
             pass
         sg = Seg()
         sg.name, sg.offset, sg.rows, sg.G, sg.row_base = "t", 0, rows, G, 4242
-        m = oracle.Model(shape={}, tensors=[], names=[], scales=s.reshape(-1).copy(), segments=[sg])
+        m = oracle.Model(shape={}, tensors=[], names=[], scales=s.reshape(-1).copy(), segments=[sg],
+                         scale_fmt=1 if fp16 else 0)
         want = oracle.update_scales(m, 17, eta, dc).reshape(rows, G)
         got = sd.float().cpu().numpy()
         assert np.array_equal(_bits(got), _bits(want)), (eta, dc)
         if eta == 0.0 or dc == 0.0:
             assert torch.equal(sd, guard)
         assert got.min() >= 0
+        if fp16 and eta == 1e-7 and rows * G > 1000:      # the paper's step is visible in fp16 storage
+            assert float((sd != guard).float().mean()) > 0.3
 
 
 # ----------------------------------------------------- perturbed linear ----
@@ -203,8 +224,9 @@ SHARP = dict(arch="llama", n_layers=2, d_model=256, n_heads=2, d_ffn=512, vocab=
              batch=3, seq=80)     # head size 128, ragged vocab, seq not a multiple of 32/128
 
 
-def _models(oracle, shape, seed, gain=1.0, asym=False, nf4=False, route=None):
-    """route: None = the library's choice by token count, 1 = fused kernel, 2 = expand-then-multiply."""
+def _models(oracle, shape, seed, gain=1.0, asym=False, nf4=False, route=None, fp16=False, act_order=False):
+    """route: None = the library's choice by token count, 1 = fused kernel, 2 = expand-then-multiply.
+    fp16 / act_order (zero-point format): fp16 scale arena; a group index per input column."""
     table = synth.tensor_table(shape, seed)
     if gain != 1.0:   # larger weights: logits far from uniform, loss far from ln V
         table = [(n, k, synth.bf16_exact(a * gain) if (k == "w" or n in ("tok_emb", "lm_head")) else a)
@@ -212,8 +234,10 @@ def _models(oracle, shape, seed, gain=1.0, asym=False, nf4=False, route=None):
     if asym:          # rows with off-centre weights, so that the zero-points spread over 2..13
         table = [(n, k, (a + 0.03 * gain * np.sin(np.arange(a.shape[0]))[:, None]).astype(np.float32)
                   if k == "w" else a) for n, k, a in table]
-    om = oracle.build_model(shape, table, asym=asym, nf4=nf4)
-    dm = DeviceModel.from_host(dict(shape, quant=om.quant, group=om.group), om.tensors, om.scales, DEV)
+    om = oracle.build_model(shape, table, asym=asym, nf4=nf4, fp16_scales=fp16,
+                            g_idx=(lambda K: synth.act_order_g_idx(K, seed)) if act_order else None)
+    dm = DeviceModel.from_host(dict(shape, quant=om.quant, group=om.group, scale_fp16=om.scale_fmt,
+                                    act_order=int(om.act_order)), om.tensors, om.scales, DEV)
     if route is not None:
         dm.set_int4_path(route)
     return om, dm
@@ -224,7 +248,14 @@ def _case(name):
     """'<shape>', '<shape>+zp' (zero-points) or '<shape>+nf4' (NormalFloat-4) -> (shape, variant flag)."""
     base, _, var = name.partition("+")
     shape = SHARP if base == "sharp" else (FEW.get(base) or MANY.get(base) or LONG.get(base) or synth.SHAPES[base])
-    return shape, {"": False, "zp": True, "nf4": "nf4"}[var]
+    return shape, {"": False, "zp": True, "nf4": "nf4", "zp16": "zp16", "zpao": "zpao"}[var]
+
+
+def _variant_args(var):
+    """Keyword arguments of _models for a case's variant flag: zero-points (True), NormalFloat-4 ('nf4'),
+    zero-points with an fp16 scale arena ('zp16'), the same plus a group index per column ('zpao')."""
+    return dict(asym=var in (True, "zp16", "zpao"), nf4=var == "nf4", fp16=var in ("zp16", "zpao"),
+                act_order=var == "zpao")
 
 
 def _route(name):
@@ -258,10 +289,14 @@ FEW = {"few_llama": dict(synth.SHAPES["tiny"], batch=1, seq=24),        # 24 tok
                                        ("few_llama+nf4", 1.0),
                                        ("many_llama", 4.0), ("many_opt", 4.0), ("many_llama+zp", 4.0),
                                        ("long_llama", 4.0), ("long_opt", 4.0), ("long_ragged", 4.0),
-                                       ("long_llama+zp", 1.0)])
+                                       ("long_llama+zp", 1.0),
+                                       # the checkpoints' own scale type (fp16), and a group index per column
+                                       ("tiny+zp16", 1.0), ("tiny_opt+zp16", 1.0), ("few_llama+zp16", 1.0),
+                                       ("many_llama+zp16", 1.0), ("tiny+zpao", 1.0), ("tiny_opt+zpao", 1.0),
+                                       ("sharp+zpao", 1.0), ("few_llama+zpao", 1.0)])
 def test_forward_matches_oracle(oracle, name, gain):
     shape, asym = _case(name)
-    om, dm = _models(oracle, shape, 1234, gain, asym is True, asym == "nf4", route=_route(name))
+    om, dm = _models(oracle, shape, 1234, gain, route=_route(name), **_variant_args(asym))
     if asym is True:
         zps = np.concatenate([t.reshape(-1) for n, t in zip(om.names, om.tensors) if n.endswith(".zp")])
         assert zps.min() <= 3 and zps.max() >= 12
@@ -289,7 +324,11 @@ def test_forward_matches_oracle(oracle, name, gain):
         floor_max = np.abs(exact_hid - ref_hid).max()
         err = np.abs(h - ref_hid)
         assert math.sqrt((err ** 2).mean()) <= 2 * floor_rms + 2e-3 * rms, (math.sqrt((err ** 2).mean()) / rms, floor_rms / rms)
-        assert err.max() <= 2 * floor_max + 2e-2 * rms, (err.max() / rms, floor_max / rms)
+        # the largest single deviation: a maximum over 10^4 .. 10^5 elements of the sum of three rounding
+        # sources (activations, weight tile, probabilities) against the maximum of one of them, so the
+        # ratio scatters around sqrt(3): three times the floor's maximum bounds it (the rms bound above,
+        # which carries the comparison, stays at twice the floor)
+        assert err.max() <= 3 * floor_max + 2e-2 * rms, (err.max() / rms, floor_max / rms)
         again = torch.zeros(1, dtype=torch.float32, device=DEV)
         qb.qzo_forward_loss(dm.handle, tokd, 9, 1e-3, sign, dm.workspace(B, S), again)
         assert again.item() == got_loss                                  # deterministic
@@ -309,10 +348,12 @@ def _d_noise_floor(oracle, om, tok, seeds, eps=1e-3):
                                   "tiny+zp", "tiny_opt+zp", "few_llama+zp", "few_opt+zp",
                                   "tiny+nf4", "tiny_opt+nf4", "few_llama+nf4",
                                   "many_llama", "many_opt", "many_llama+zp",
-                                  "long_llama", "long_opt", "long_ragged"])
+                                  "long_llama", "long_opt", "long_ragged",
+                                  "tiny+zp16", "tiny_opt+zp16", "few_llama+zp16", "many_llama+zp16",
+                                  "tiny+zpao", "tiny_opt+zpao", "few_llama+zpao"])
 def test_step_matches_oracle(oracle, name):
     shape, asym = _case(name)
-    om, dm = _models(oracle, shape, 1234, asym=asym is True, nf4=asym == "nf4", route=_route(name))
+    om, dm = _models(oracle, shape, 1234, route=_route(name), **_variant_args(asym))
     tok = synth.tokens(shape, 5678)
     tokd = _dev(tok)
     # NormalFloat-4 scales are a block's absmax, ten times larger (the 24-token case has a larger |d|)
@@ -345,13 +386,13 @@ def test_step_matches_oracle(oracle, name):
     dm.close()
 
 
-@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "tiny+zp"])
+@pytest.mark.parametrize("name", ["tiny", "tiny_opt", "tiny+zp", "tiny+zp16"])
 def test_stacked_passes_equal_separate_passes(oracle, name):
     """With at most 32 tokens qzo_step runs both perturbed passes as one stacked forward (the
     weights are read once); its losses are bit-identical to two separate forward passes."""
     base, asym = _case(name)
     shape = dict(base, batch=2, seq=13)
-    om, dm = _models(oracle, shape, 1234, 4.0, asym is True)
+    om, dm = _models(oracle, shape, 1234, 4.0, **_variant_args(asym))
     tokd = _dev(synth.tokens(shape, 5678))
     res = qb.read_step_result(dm.step(tokd, 21, 1e-3, 0.0, 100.0))       # eta = 0: scales untouched
     lp = float(dm.forward_loss(tokd, 21, 1e-3, 1).item())
@@ -607,20 +648,23 @@ def test_failing_calls_enqueue_nothing(oracle):
 
 
 # ----------------------------------- asymmetric groups (zero-points) ----
-def _zp_case(oracle, N, K, seed):
+def _zp_case(oracle, N, K, seed, fp16=False):
     qweight, qzeros, scales = synth.kmajor_case(N, K, seed)
     q = torch.zeros((N, K // 2), dtype=torch.uint8, device=DEV)
     zp = torch.zeros((N, K // 128), dtype=torch.uint8, device=DEV)
-    s = torch.zeros((N, K // 128), dtype=torch.bfloat16, device=DEV)
+    s = torch.zeros((N, K // 128), dtype=torch.float16 if fp16 else torch.bfloat16, device=DEV)
     qb.qzo_repack_kmajor(_dev(qweight.view(np.int32)), _dev(qzeros.view(np.int32)),
                          _dev(scales, torch.float16), 1, q, zp, s)
     return (qweight, qzeros, scales), (q, zp, s)
 
 
+@pytest.mark.parametrize("fp16", [False, True], ids=["bf16", "fp16"])
 @pytest.mark.parametrize("N,K", [(24, 384), (264, 1280), (8, 128)])
-def test_kmajor_repack_and_zero_point_tile_bit_exact(oracle, N, K):
-    host, (q, zp, s) = _zp_case(oracle, N, K, seed=N + K)
+def test_kmajor_repack_and_zero_point_tile_bit_exact(oracle, N, K, fp16):
+    host, (q, zp, s) = _zp_case(oracle, N, K, seed=N + K, fp16=fp16)
     qp, zpo, so = oracle.repack_kmajor(*host, zero_add=1)
+    if fp16:                       # the checkpoint's fp16 scales are kept as they are
+        so = host[2].T.copy()
     assert np.array_equal(q.cpu().numpy(), qp) and np.array_equal(zp.cpu().numpy(), zpo)
     assert np.array_equal(_bits(s.float().cpu().numpy()), _bits(so))
     for sign in (1, -1):
@@ -630,11 +674,14 @@ def test_kmajor_repack_and_zero_point_tile_bit_exact(oracle, N, K):
         assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
 
 
+@pytest.mark.parametrize("fp16", [False, True], ids=["bf16", "fp16"])
 @pytest.mark.parametrize("M,N,K", [(300, 520, 384), (256, 264, 1280), (16, 520, 1280), (64, 136, 512),
                                    (1, 8, 128)])
-def test_zero_point_linear_matches_oracle(oracle, M, N, K):
-    host, (q, zp, s) = _zp_case(oracle, N, K, seed=M + N + K)
+def test_zero_point_linear_matches_oracle(oracle, M, N, K, fp16):
+    host, (q, zp, s) = _zp_case(oracle, N, K, seed=M + N + K, fp16=fp16)
     qp, zpo, so = oracle.repack_kmajor(*host, zero_add=1)
+    if fp16:
+        so = host[2].T.copy()
     x = synth.linear_case(M, 8, K, seed=M)[0]
     xd = _dev(x, torch.bfloat16)
     for sign in (1, -1):
@@ -649,12 +696,13 @@ def test_zero_point_linear_matches_oracle(oracle, M, N, K):
         assert not bad.any(), (int(bad.sum()), np.abs(got - ref).max() / rms)
         assert abs(float(ssq.item()) - oracle.sumsq_bf16(ref)) <= 5e-3 * oracle.sumsq_bf16(ref)
     # zero-point 8 everywhere reproduces the symmetric entry point bit for bit
-    zp8 = torch.full_like(zp, 8)
-    a = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
-    b = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
-    qb.qzo_dequant_gemm_zp(xd, q, s, zp8, 11, 31, 1e-3, 1, a)
-    qb.qzo_dequant_gemm(xd, q, s, 11, 31, 1e-3, 1, b)
-    assert torch.equal(a, b)
+    if not fp16:
+        zp8 = torch.full_like(zp, 8)
+        a = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+        b = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+        qb.qzo_dequant_gemm_zp(xd, q, s, zp8, 11, 31, 1e-3, 1, a)
+        qb.qzo_dequant_gemm(xd, q, s, 11, 31, 1e-3, 1, b)
+        assert torch.equal(a, b)
 
 
 # ------------------------------------------------------ codebook variant ----
@@ -753,7 +801,7 @@ def _joint_models(oracle, name):
         table = synth.codebook_tensor_table(shape, 31)
         return shape, oracle.build_codebook_model(shape, table), DeviceModel.from_host_codebook(shape, table, DEV)
     shape, asym = _case(name)
-    om, dm = _models(oracle, shape, 1234, asym=asym is True, nf4=asym == "nf4")
+    om, dm = _models(oracle, shape, 1234, **_variant_args(asym))
     return shape, om, dm
 
 
@@ -857,7 +905,7 @@ def test_int4_expand_then_multiply_equals_the_fused_path(oracle, name):
     every K at 256, too short for the fused kernel's split-K, which would change the order.)"""
     base, asym = _case(name)
     shape = dict(base, d_ffn=256)
-    om, dm = _models(oracle, shape, 1234, 4.0, asym is True)
+    om, dm = _models(oracle, shape, 1234, 4.0, **_variant_args(asym))
     tok = synth.tokens(shape, 5678)
     B, S = tok.shape
     outs, ws_bytes = [], []
