@@ -188,7 +188,11 @@ def test_perturbed_linear_sign_and_eps_identities(oracle):
 
 def test_few_token_path_is_deterministic_and_close_to_the_tile_path(oracle):
     """The same rows computed as a 64-token call (few-token kernel) and inside a 200-token call
-    (tile kernel) agree to bf16 rounding of the outputs; repeated calls are bit-identical."""
+    (tile kernel) agree; repeated calls are bit-identical.  The tile kernel rounds every perturbed
+    weight to bf16 (relative error up to 2^-9, independent from weight to weight), the few-token
+    kernel multiplies the integer codes and scales the group sums in fp32: per output the two
+    differ by about 2^-9 / sqrt(3) = 1.1e-3 of the outputs' rms (a sum of K independent terms),
+    bounded here at six times that, plus one bf16 rounding of the output itself."""
     x, qp, s = synth.linear_case(200, 520, 1280, seed=9)
     xd, qd, sd = _dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16)
     big = torch.zeros((200, 520), dtype=torch.bfloat16, device=DEV)
@@ -200,7 +204,7 @@ def test_few_token_path_is_deterministic_and_close_to_the_tile_path(oracle):
         outs.append(y)
     assert torch.equal(outs[0], outs[1])
     a, b = outs[0].float(), big[:64].float()
-    assert ((a - b).abs() <= 2.0 ** -7 * b.abs() + 1e-3 * b.abs().max()).all()
+    assert ((a - b).abs() <= 2.0 ** -7 * b.abs() + 7e-3 * b.pow(2).mean().sqrt()).all()
 
 
 def test_boundary_rejects_bad_arguments():
