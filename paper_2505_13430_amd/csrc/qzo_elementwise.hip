@@ -498,7 +498,9 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-template <bool LAYERNORM>
+// CACHED: the row fits four 16-byte chunks per thread and is read from memory once; else every
+// pass over the row reads it again.
+template <bool LAYERNORM, bool CACHED>
 __global__ __launch_bounds__(256) void norm_kernel(const bf16_t* __restrict__ x,
                                                    const bf16_t* __restrict__ gain,
                                                    const bf16_t* __restrict__ bias, uint32_t d,
@@ -507,61 +509,91 @@ __global__ __launch_bounds__(256) void norm_kernel(const bf16_t* __restrict__ x,
   const bf16_t* xr = x + (uint64_t)blockIdx.x * d;
   bf16_t* yr = y + (uint64_t)blockIdx.x * d;
   const uint32_t cpr = d >> 3;
+  constexpr int NC = 4;
+  uint4 xv[NC];
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const uint32_t c = threadIdx.x + 256u * i;
+      xv[i] = c < cpr ? *reinterpret_cast<const uint4*>(xr + c * 8) : make_uint4(0, 0, 0, 0);
+    }
+  }
+  // chunk i of this thread (CACHED) or chunk c of the row
+  auto chunk = [&](int i, uint32_t c) { return CACHED ? xv[i] : *reinterpret_cast<const uint4*>(xr + c * 8); };
+  const uint32_t passes = CACHED ? NC : (cpr + 255) / 256;
   float mu = 0.0f;
   if (LAYERNORM) {
     float acc = 0.0f;
-    for (uint32_t c = threadIdx.x; c < cpr; c += 256) {
-      uint4 v = *reinterpret_cast<const uint4*>(xr + c * 8);
-      uint32_t a[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc += __uint_as_float(a[j] << 16) + __uint_as_float(a[j] & 0xffff0000u);
+    for (uint32_t i = 0; i < passes; ++i) {
+      const uint32_t c = threadIdx.x + 256u * i;
+      if (c < cpr) {
+        const uint4 v = chunk(i, c);
+        const uint32_t a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc += __uint_as_float(a[j] << 16) + __uint_as_float(a[j] & 0xffff0000u);
+      }
     }
     mu = block_sum(acc, red) / (float)d;
   }
   float ss = 0.0f;
-  for (uint32_t c = threadIdx.x; c < cpr; c += 256) {
-    uint4 v = *reinterpret_cast<const uint4*>(xr + c * 8);
-    uint32_t a[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float lo = __uint_as_float(a[j] << 16) - mu, hi = __uint_as_float(a[j] & 0xffff0000u) - mu;
-      ss = __builtin_fmaf(lo, lo, ss);
-      ss = __builtin_fmaf(hi, hi, ss);
+  for (uint32_t i = 0; i < passes; ++i) {
+    const uint32_t c = threadIdx.x + 256u * i;
+    if (c < cpr) {
+      const uint4 v = chunk(i, c);
+      const uint32_t a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float lo = __uint_as_float(a[j] << 16) - mu, hi = __uint_as_float(a[j] & 0xffff0000u) - mu;
+        ss = __builtin_fmaf(lo, lo, ss);
+        ss = __builtin_fmaf(hi, hi, ss);
+      }
     }
   }
   const float var = block_sum(ss, red) / (float)d;
   const float inv = 1.0f / sqrtf(var + eps);
-  for (uint32_t c = threadIdx.x; c < cpr; c += 256) {
-    uint4 v = *reinterpret_cast<const uint4*>(xr + c * 8);
-    uint4 gq = *reinterpret_cast<const uint4*>(gain + c * 8);
-    uint32_t a[4] = {v.x, v.y, v.z, v.w}, g[4] = {gq.x, gq.y, gq.z, gq.w}, b[4] = {0, 0, 0, 0}, o[4];
-    if (LAYERNORM) {
-      uint4 bq = *reinterpret_cast<const uint4*>(bias + c * 8);
-      b[0] = bq.x; b[1] = bq.y; b[2] = bq.z; b[3] = bq.w;
-    }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float lo = (__uint_as_float(a[j] << 16) - mu) * inv * __uint_as_float(g[j] << 16);
-      float hi = (__uint_as_float(a[j] & 0xffff0000u) - mu) * inv * __uint_as_float(g[j] & 0xffff0000u);
+  for (uint32_t i = 0; i < passes; ++i) {
+    const uint32_t c = threadIdx.x + 256u * i;
+    if (c < cpr) {
+      const uint4 v = chunk(i, c);
+      uint4 gq = *reinterpret_cast<const uint4*>(gain + c * 8);
+      uint32_t a[4] = {v.x, v.y, v.z, v.w}, g[4] = {gq.x, gq.y, gq.z, gq.w}, b[4] = {0, 0, 0, 0}, o[4];
       if (LAYERNORM) {
-        lo += __uint_as_float(b[j] << 16);
-        hi += __uint_as_float(b[j] & 0xffff0000u);
+        uint4 bq = *reinterpret_cast<const uint4*>(bias + c * 8);
+        b[0] = bq.x; b[1] = bq.y; b[2] = bq.z; b[3] = bq.w;
       }
-      o[j] = pack_bf16x2(lo, hi);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float lo = (__uint_as_float(a[j] << 16) - mu) * inv * __uint_as_float(g[j] << 16);
+        float hi = (__uint_as_float(a[j] & 0xffff0000u) - mu) * inv * __uint_as_float(g[j] & 0xffff0000u);
+        if (LAYERNORM) {
+          lo += __uint_as_float(b[j] << 16);
+          hi += __uint_as_float(b[j] & 0xffff0000u);
+        }
+        o[j] = pack_bf16x2(lo, hi);
+      }
+      *reinterpret_cast<uint4*>(yr + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
     }
-    *reinterpret_cast<uint4*>(yr + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
 hipError_t launch_rmsnorm(const void* x, const void* gain, uint32_t M, uint32_t d, float eps,
                           void* y, hipStream_t st) {
-  norm_kernel<false><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, nullptr, d, eps,
-                                        (bf16_t*)y);
+  if (d <= 8192)
+    norm_kernel<false, true><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, nullptr, d, eps, (bf16_t*)y);
+  else
+    norm_kernel<false, false><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, nullptr, d, eps, (bf16_t*)y);
   return hipGetLastError();
 }
 hipError_t launch_layernorm(const void* x, const void* gain, const void* bias, uint32_t M,
                             uint32_t d, float eps, void* y, hipStream_t st) {
-  norm_kernel<true><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, (const bf16_t*)bias,
-                                       d, eps, (bf16_t*)y);
+  if (d <= 8192)
+    norm_kernel<true, true><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, (const bf16_t*)bias, d, eps,
+                                               (bf16_t*)y);
+  else
+    norm_kernel<true, false><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, (const bf16_t*)bias, d, eps,
+                                                (bf16_t*)y);
   return hipGetLastError();
 }
 

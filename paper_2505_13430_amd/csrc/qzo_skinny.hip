@@ -101,13 +101,23 @@ __device__ __forceinline__ float reduce_item(const GemmArgs& a, const float* __r
   auto load4 = [&](uint32_t ks, uint32_t col) {
     return *reinterpret_cast<const float4*>(part + ((uint64_t)ks * a.M + m) * a.N + col);
   };
+  // four slices' loads in flight at a time (one at a time, the loop is a chain of memory
+  // latencies); the additions stay in slice order
   float v[4] = {0, 0, 0, 0}, u[4] = {0, 0, 0, 0};
-  for (uint32_t ks = 0; ks < ksplit; ++ks) {
-    const float4 p = load4(ks, f);
-    v[0] += p.x; v[1] += p.y; v[2] += p.z; v[3] += p.w;
-    if (swiglu) {
-      const float4 pu = load4(ks, NO + f);
-      u[0] += pu.x; u[1] += pu.y; u[2] += pu.z; u[3] += pu.w;
+  for (uint32_t k0 = 0; k0 < ksplit; k0 += 4) {
+    float4 p[4], pu[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t ks = min(k0 + i, ksplit - 1);
+      p[i] = load4(ks, f);
+      if (swiglu) pu[i] = load4(ks, NO + f);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (k0 + i < ksplit) {
+        v[0] += p[i].x; v[1] += p[i].y; v[2] += p[i].z; v[3] += p[i].w;
+        if (swiglu) { u[0] += pu[i].x; u[1] += pu[i].y; u[2] += pu[i].z; u[3] += pu[i].w; }
+      }
     }
   }
   if (swiglu) {
