@@ -302,6 +302,12 @@ def main():
     dm.step(tok, 10_000, eps, eta, clip)
     torch.cuda.synchronize()
     changed = float((dm.scales.view(torch.int16) != before.view(torch.int16)).float().mean().item())
+    # ... and one with a hundred times the learning rate, where the stored format decides: a step of
+    # eta*d'*z ~ 5e-6*z crosses half an fp16 ulp of a scale near 0.008 (3.8e-6) but not half a bf16 ulp (3e-5)
+    before.copy_(dm.scales)
+    dm.step(tok, 10_001, eps, 100.0 * eta, clip)
+    torch.cuda.synchronize()
+    changed_100 = float((dm.scales.view(torch.int16) != before.view(torch.int16)).float().mean().item())
     del before
 
     # whether the linears were written out as perturbed bf16 matrices first (most of them, when mixed)
@@ -335,6 +341,7 @@ def main():
         "forward_tokens_per_s": 2 * B * S * steps_per_s,
         "last_step": res,
         "scales_changed_frac": changed,
+        "scales_changed_frac_at_100x_eta": changed_100,
         "roofline": {"bound": "mfma",
                      "kernel": "gemm_kernel<1,false,4,3> (plain bf16 GEMM on the expanded perturbed weights)"
                      if expanded
