@@ -185,6 +185,23 @@ def probe(torch, qb):
                                "mfma rate 20000 iters x 16 MFMAs per wavefront (zero, then random operands)"}))
 
 
+def probe_few(torch, qb):
+    """Launches for rocprofv3 counter runs of the few-token kernel: the perturbed linear at the
+    Llama-2-7B qkv shape with 16 tokens (M 16, N 12288, K 4096), six times."""
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    M, N, K = 16, 12288, 4096
+    x = torch.randn(M, K, generator=g, device=dev).to(torch.bfloat16)
+    q = torch.randint(0, 256, (N, K // 2), generator=g, device=dev, dtype=torch.uint8)
+    s = (torch.rand(N, K // 128, generator=g, device=dev) * 0.015 + 0.005).to(torch.bfloat16)
+    y = torch.empty(M, N, dtype=torch.bfloat16, device=dev)
+    for _ in range(6):
+        qb.qzo_dequant_gemm(x, q, s, 0, 7, 1e-3, 1, y)
+        torch.cuda.synchronize()
+    print(json.dumps({"probe": "few-token perturbed linear 16x12288x4096, 6 launches"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -210,6 +227,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-other", action="store_true",
                     help="skip the untimed Llama-2-13B-shaped memory report (two variants, two steps each)")
+    ap.add_argument("--probe-few", action="store_true",
+                    help="counter probe: the few-token W4A16 kernel at 16 x 12288 x 4096, six launches")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe: a plain 256 MiB copy, the qkv-shaped W4A16 GEMM and the "
                          "7B-sized scale update, three launches each (for rocprofv3 --pmc)")
@@ -224,6 +243,9 @@ def main():
     from paper_2505_13430_amd import synth
     from paper_2505_13430_amd.model import DeviceModel
 
+    if args.probe_few:
+        probe_few(torch, qb)
+        return
     if args.probe:
         probe(torch, qb)
         return
