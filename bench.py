@@ -324,8 +324,8 @@ def main():
     dm.step(tok, 10_000, eps, eta, clip)
     torch.cuda.synchronize()
     changed = float((dm.scales.view(torch.int16) != before.view(torch.int16)).float().mean().item())
-    # ... and one with a hundred times the learning rate, where the stored format decides: a step of
-    # eta*d'*z ~ 5e-6*z crosses half an fp16 ulp of a scale near 0.008 (3.8e-6) but not half a bf16 ulp (3e-5)
+    # ... and one with a hundred times the learning rate, where steps of eta*d'*z ~ 1e-5*z reach half an ulp
+    # of a scale near 0.008 (3.8e-6 in fp16, 3e-5 in bf16), so that the update is seen to move the stored values
     before.copy_(dm.scales)
     dm.step(tok, 10_001, eps, 100.0 * eta, clip)
     torch.cuda.synchronize()
