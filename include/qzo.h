@@ -222,9 +222,12 @@ qzo_status qzo_model_apply_update(qzo_model* m, uint64_t seed, float eta, float 
  * afterwards; calls that share a scratch buffer must not overlap.  It holds the per-tile
  * partial sums of sum y^2 and the K-slice partial sums of the two paths below.
  * With M <= 64 the call takes the few-token path (the paper's batch-1 memory
- * profile and short-prompt batches, Sec. 4.3): the int4 weights are streamed once,
- * K is split over workgroups and the fp32 partial sums (at most 8 * M * N floats) are
- * added in slice order (deterministic).  Inside a model the same path uses the workspace.
+ * profile and short-prompt batches, Sec. 4.3): the int4 weights are streamed once and
+ * enter the matrix unit as integer codes, each 128-wide group's sum is scaled by the
+ * perturbed scale in fp32 (Eq. 4-5 without a bf16 rounding of the weights),
+ * K is split over workgroups (slices of 8 groups, 4 for small outputs) and the fp32
+ * partial sums (slices * M * N floats) are added in slice order (deterministic).
+ * Inside a model the same path uses the workspace.
  * With more tokens but fewer than half as many 256 x 256 output tiles as the chip has compute units,
  * the tile kernel also splits K (slices of a multiple of 256 input features, at most
  * compute units / tiles of them) and a second kernel adds the slices in slice order.
