@@ -153,7 +153,9 @@ __device__ __forceinline__ float reduce_item(const GemmArgs& a, const float* __r
 // fp32 with rows = M, or 2 M in dual mode.  In dual mode the tile rows are split between the
 // passes: rows [0, 16 MT) are tokens of the +eps pass, rows [16 MT, 32 MT) the same tokens of
 // the -eps pass (M <= 16 MT).
-template <int MT, bool DUAL, bool ZP>
+// XSUM_BY_MFMA (one token tile, at most 16 tokens per pass: the stacked and the separate passes of
+// a step then sum alike, bit for bit): the block sums come from the matrix unit, see below.
+template <int MT, bool DUAL, bool ZP, bool XSUM_BY_MFMA>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* part,
                                                              uint32_t groups_per_split) {
   constexpr uint32_t TPP = DUAL ? MT * 16 : MT * 32;      // tile rows per pass
@@ -202,6 +204,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
 
     // activation staging: a group's block is MT*32 rows x 16 chunks of 16 bytes; a thread moves MT*2 chunks.
     // Tile row -> row of x: clamped to the pass's last token.
+    static_assert(!XSUM_BY_MFMA || MT == 1, "no registers for it with two token tiles");
     constexpr int NX = MT * 2;
     uint32_t xoff[NX];
 #pragma unroll
@@ -222,6 +225,10 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
     _Pragma("unroll") for (int i = 0; i < NX; ++i)                                           \
       xr[SLOT][i] = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(xoff[i] + go_), 0, 0);   \
   } while (0)
+    // The block sums X[m,g] = sum_k x[m,k]: with few tokens the matrix unit computes them (a second
+    // MFMA per k-step on the same activation fragment, against a fragment of ones: its accumulator
+    // holds X of exactly the tile rows the lane rescales, and the matrix unit has the time); with two
+    // tiles there are no registers for that, and the staging threads add them up:
     // the 16 threads of a row are 16 consecutive lanes: their chunk sums meet in four exchange steps.
     // The K loop holds no divergent branch, so that its uniform branches stay plain scalar branches.
 #define QZO_SK_XSTORE(SLOT, BUF)                                                             \
@@ -229,10 +236,12 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
     _Pragma("unroll") for (int i = 0; i < NX; ++i) {                                         \
       const uint32_t c = t + 256u * i, row = c >> 4, ch = c & 15u;                           \
       *reinterpret_cast<u32x4*>(xs[BUF] + x_lds_off(row, ch)) = permute8(xr[SLOT][i]);       \
-      float sx_ = sum8_bf16(xr[SLOT][i]);                                                    \
-      sx_ += __shfl_xor(sx_, 1, 64); sx_ += __shfl_xor(sx_, 2, 64);                          \
-      sx_ += __shfl_xor(sx_, 4, 64); sx_ += __shfl_xor(sx_, 8, 64);                          \
-      xsum[BUF][row] = sx_;           /* all 16 lanes of the row hold the sum */             \
+      if (!XSUM_BY_MFMA) {                                                                   \
+        float sx_ = sum8_bf16(xr[SLOT][i]);                                                  \
+        sx_ += __shfl_xor(sx_, 1, 64); sx_ += __shfl_xor(sx_, 2, 64);                        \
+        sx_ += __shfl_xor(sx_, 4, 64); sx_ += __shfl_xor(sx_, 8, 64);                        \
+        xsum[BUF][row] = sx_;         /* all 16 lanes of the row hold the sum */             \
+      }                                                                                      \
     }                                                                                        \
   } while (0)
 
@@ -284,6 +293,8 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
     }                                                                                        \
   } while (0)
 
+    union { bf16x8 v; uint32_t u[4]; } ones;
+    ones.u[0] = ones.u[1] = ones.u[2] = ones.u[3] = 0x3f803f80u;
     // noise: one Philox counter per 8 groups, one Box-Muller pair per 2 groups
     uint32_t zw[4] = {0, 0, 0, 0};
     float z_even = 0.0f, z_odd = 0.0f;
@@ -344,7 +355,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
           const u32x4 w0 = *reinterpret_cast<const u32x4*>(wtw + lrow * 128 + ((c0 ^ (lrow & 7u)) << 4));
           const u32x4 w1 = *reinterpret_cast<const u32x4*>(wtw + lrow * 128 + (((c0 + 1) ^ (lrow & 7u)) << 4));
           const uint32_t wd[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-          floatx16 pg[MT];
+          floatx16 pg[MT], px;                    // px: X[m,g] of tile rows 8 b + 4 half + c in every lane
 #pragma unroll
           for (int j = 0; j < 8; ++j) {           // k-step j: inputs 64 half + 8 j .. + 7 of the group
             const bf16x8 wf = unpack8_biased(wd[j], nib_mask, nib_magic);
@@ -353,6 +364,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
               const bf16x8 xf = *reinterpret_cast<const bf16x8*>(xs[buf] + x_lds_off(m * 32 + lrow, half * 8 + j));
               const floatx16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
               pg[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, wf, j == 0 ? zero : pg[m], 0, 0, 0);
+              if (XSUM_BY_MFMA) px = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf, ones.v, j == 0 ? zero : px, 0, 0, 0);
             }
           }
           // y += s_eff * (P - (128 + zp) X)
@@ -360,7 +372,9 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
           for (int m = 0; m < MT; ++m)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-              const float4 xg = *reinterpret_cast<const float4*>(&xsum[buf][m * 32 + 8 * b + 4 * half]);
+              const float4 xg = XSUM_BY_MFMA
+                                    ? make_float4(px[4 * b], px[4 * b + 1], px[4 * b + 2], px[4 * b + 3])
+                                    : *reinterpret_cast<const float4*>(&xsum[buf][m * 32 + 8 * b + 4 * half]);
               const float se = !DUAL ? se_p : ((MT == 2 ? m == 1 : b >= 2) ? se_m : se_p);
               y[m][4 * b + 0] = __builtin_fmaf(se, __builtin_fmaf(cz, xg.x, pg[m][4 * b + 0]), y[m][4 * b + 0]);
               y[m][4 * b + 1] = __builtin_fmaf(se, __builtin_fmaf(cz, xg.y, pg[m][4 * b + 1]), y[m][4 * b + 1]);
@@ -436,12 +450,12 @@ uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi) {
 
 // a.M <= 64, a.N % 8 == 0 (N % 16 == 0 with SwiGLU), a.K % 128 == 0; ws holds skinny_ws_floats
 // floats; with EPI_SUMSQ a.partials holds skinny_reduce_blocks floats.
-template <int MT, bool DUAL>
+template <int MT, bool DUAL, bool XMF>
 static void skinny_launch(const GemmArgs& a, dim3 grid, float* ws, uint32_t per, hipStream_t st) {
   if (a.zp)
-    skinny_gemm_kernel<MT, DUAL, true><<<grid, 256, 0, st>>>(a, ws, per);
+    skinny_gemm_kernel<MT, DUAL, true, XMF><<<grid, 256, 0, st>>>(a, ws, per);
   else
-    skinny_gemm_kernel<MT, DUAL, false><<<grid, 256, 0, st>>>(a, ws, per);
+    skinny_gemm_kernel<MT, DUAL, false, XMF><<<grid, 256, 0, st>>>(a, ws, per);
 }
 hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
@@ -453,12 +467,14 @@ hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st) {
   const uint32_t ks = skinny_ksplit(a.N, a.K), ngrp = a.K >> 7, per = (ngrp + ks - 1) / ks;
   dim3 grid((a.N + SK_ROWS - 1) / SK_ROWS, ks);
   if (a.dual) {
-    if (a.M <= 16) skinny_launch<1, true>(a, grid, ws, per, st);
-    else skinny_launch<2, true>(a, grid, ws, per, st);
+    if (a.M <= 16) skinny_launch<1, true, true>(a, grid, ws, per, st);
+    else skinny_launch<2, true, false>(a, grid, ws, per, st);
+  } else if (a.M <= 16) {
+    skinny_launch<1, false, true>(a, grid, ws, per, st);
   } else if (a.M <= 32) {
-    skinny_launch<1, false>(a, grid, ws, per, st);
+    skinny_launch<1, false, false>(a, grid, ws, per, st);
   } else {
-    skinny_launch<2, false>(a, grid, ws, per, st);
+    skinny_launch<2, false, false>(a, grid, ws, per, st);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
