@@ -84,6 +84,33 @@ def test_weight_tile_bit_exact(oracle, N, K, row_base, sign):
     assert np.array_equal(_bits(out.float().cpu().numpy()), _bits(want))
 
 
+@pytest.mark.parametrize("M", [16, 32, 64, 256], ids=["few16", "few32", "few64", "tile"])
+@pytest.mark.parametrize("zp", [False, True], ids=["sym", "zp"])
+def test_gemm_kernels_reproduce_the_perturbed_weights_bit_for_bit(oracle, M, zp):
+    """The GEMM kernels' own unpacking and perturbation, read out through one-hot activations: row m
+    of X is the unit vector of column k_m, so y[m, n] is the perturbed weight (n, k_m) itself, one
+    fp32 product rounded to bf16 (Eq. 4-5).  256 tokens take the tile kernel (every column), fewer the
+    few-token kernel in each of its variants (64 columns spread over both groups and all nibble
+    positions): its integer-code products and fp32 group scaling round like the definition here."""
+    N, K = 72, 256
+    _, qp, s = synth.linear_case(1, N, K, seed=77)
+    cols = np.arange(K) if M == K else (np.arange(M) * (K // M) + np.arange(M) % (K // M))
+    x = np.zeros((M, K), dtype=np.float32)
+    x[np.arange(M), cols] = 1.0
+    y = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    eps = np.float32(1e-3)
+    if zp:
+        zo = np.random.default_rng(3).integers(0, 16, size=(N, K // 128), dtype=np.uint8)
+        qb.qzo_dequant_gemm_zp(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), _dev(zo), 11, 99, 1e-3, -1, y)
+        want = oracle.dequant_zp(qp, s, zo, 99, 11, -eps, to_bf16=True)
+    else:
+        qb.qzo_dequant_gemm(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), 11, 99, 1e-3, -1, y)
+        want = oracle.dequant(qp, s, 99, 11, -eps, to_bf16=True)
+    got = y.float().cpu().numpy()                      # [M, N] = W_eff[:, cols]^T
+    assert len(set(cols.tolist())) == M
+    assert np.array_equal(_bits(got), _bits(np.ascontiguousarray(want[:, cols].T)))
+
+
 @pytest.mark.parametrize("fp16", [False, True], ids=["bf16", "fp16"])
 def test_asymmetric_rtn_quantizer_bit_exact(oracle, fp16):
     rng = np.random.default_rng(4)
