@@ -169,6 +169,14 @@ qzo_status qzo_forward_loss(qzo_model* m, const int32_t* tokens_dev, uint32_t ba
  * regenerated from `seed`.  No host synchronisation inside; result_dev
  * receives the scalars.  clip must be >= 0.  A non-finite d leaves the scales
  * untouched and sets result.status = QZO_ERR_NONFINITE.
+ * With int4 weights (no joint mode, no group index per column) the two forwards run as one
+ * forward over 2*batch sequences when batch*seq <= 32 (the few-token kernel then reads the
+ * weights once for both passes; losses bit-identical to two qzo_forward_loss calls) or when
+ * batch*seq is a multiple of 256 up to 2048 and the model is not forced onto the
+ * expand-then-multiply route (a launch of the tile kernel then holds the token tiles of
+ * both passes, the second pass's with -eps; losses equal to two qzo_forward_loss calls
+ * within the 16-bit activations' noise, the K split of a linear being a function of the
+ * number of token tiles).  qzo_workspace_bytes accounts for it.
  */
 qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
                     uint64_t seed, float eps, float eta, float clip, void* workspace_dev,

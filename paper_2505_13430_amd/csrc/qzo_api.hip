@@ -182,13 +182,23 @@ void table_layout(const qzo_model_config& c, std::vector<uint64_t>& need, std::v
   b16(V * d);
 }
 
+// Whether qzo_step runs its two perturbed passes as one forward over 2 * batch sequences.  With at
+// most 32 tokens the few-token kernel reads the int4 weights once for both; with whole 256-token
+// tiles per pass (up to 2048 tokens, where the fused kernel serves) a launch of the tile kernel
+// holds both passes' tiles, the second pass's with -eps: twice the tiles per launch for a chip that
+// such token counts do not fill, half the launches.
+bool passes_stacked(const qzo_model* m, uint64_t M1) {
+  const qzo_model_config& c = m->cfg;
+  if (!(c.quant == 0 || c.quant == 2) || m->dense_master || c.act_order) return false;
+  if (M1 <= SKINNY_MAX_M_DUAL) return true;
+  return M1 % 256 == 0 && M1 <= STACK_TILE_MAX_M && m->int4_path != 2;
+}
+
 Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   const qzo_model_config& c = m->cfg;
-  // With very few tokens qzo_step stacks its two perturbed passes into one forward
-  // over 2 * batch sequences (the int4 weights are then read once per step).
   const uint64_t M1 = (uint64_t)batch * seq;
   const bool int4 = c.quant == 0 || c.quant == 2;
-  const bool stack = M1 <= SKINNY_MAX_M_DUAL && int4 && !m->dense_master && !c.act_order;
+  const bool stack = passes_stacked(m, M1);
   const uint64_t M = stack ? 2 * M1 : M1, d = c.d_model, F = c.d_ffn;
   const uint64_t n_slices = ((c.vocab + 255) / 256) * 4;
   Workspace w;
@@ -251,9 +261,9 @@ qzo_status check_batch(const qzo_model* m, const void* tok, uint32_t batch, uint
   if ((uint64_t)batch * seq > 0x7fffffffull) return fail(QZO_ERR_SHAPE, "batch*seq too large");
   {
     // the kernels address every operand with 32-bit byte offsets: tokens x widest tensor row, in
-    // bf16, must stay below 2^31 bytes (stacked passes have at most 64 tokens)
+    // bf16, must stay below 2^31 bytes (stacked passes count twice)
     const qzo_model_config& c = m->cfg;
-    const uint64_t M1 = (uint64_t)batch * seq;
+    const uint64_t M1 = (uint64_t)batch * seq * (passes_stacked(m, (uint64_t)batch * seq) ? 2 : 1);
     const uint64_t widest = std::max<uint64_t>({3ull * c.d_model, (c.arch == 0 ? 2ull : 1ull) * c.d_ffn});
     if (M1 * widest * 2 >= (1ull << 31))
       return fail(QZO_ERR_SHAPE, "batch*seq too large for this model: an activation tensor would exceed 2^31 bytes");
@@ -293,7 +303,7 @@ enum { PK_W4GEMM = 0, PK_LMHEAD = 1, PK_ATTN = 2, PK_UPDATE = 3, PK_OTHER = 4, P
 
 
 // The decoder forward with every quantized linear perturbed by sign*eps*z.
-// n_pass = 2 (few tokens, int4 only): both passes of a step stacked, rows [0,M1) perturbed by
+// n_pass = 2 (int4 only; see passes_stacked): both passes of a step stacked, rows [0,M1) perturbed by
 // +eps_signed and rows [M1, 2 M1) by -eps_signed; their losses go to loss_out and loss_out2.
 qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t seq, uint64_t seed,
                    float eps_signed, const Workspace& w, float* loss_out, hipStream_t st,
@@ -674,9 +684,8 @@ static qzo_status step_impl(qzo_model* m, const int32_t* tokens_dev, uint32_t ba
     return fail(QZO_ERR_ARG, "eps/eta not finite");
   hipStream_t s = (hipStream_t)stream;
   Workspace w = carve(m, batch, seq, workspace_dev);
-  if ((uint64_t)batch * seq <= SKINNY_MAX_M_DUAL && (m->cfg.quant == 0 || m->cfg.quant == 2) && !m->dense_master &&
-      !m->cfg.act_order) {
-    // few tokens: one forward over both passes, the weights are read once
+  if (passes_stacked(m, (uint64_t)batch * seq)) {
+    // one forward over both passes
     st = forward(m, tokens_dev, batch, seq, seed, eps, w, w.losses, s, nullptr, 2, w.losses + 1);
     if (st != QZO_OK) return st;
   } else {

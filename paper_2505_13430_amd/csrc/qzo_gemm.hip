@@ -224,6 +224,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   const uint32_t lds_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds +
                             __builtin_amdgcn_readfirstlane(wave) * 1024u;
   uint32_t xo[NA], wo[NA], so = 0, gn_w4 = 0;
+  float eps_tile = a.eps_signed;      // stacked passes: token tiles from row a.flip_row on take -eps
   const uint32_t brow = t / TPR, bpart = t % TPR;
   // LDS offsets: rows t/8 + RSTEP i share their swizzle, so chunk i is a_lds + i * RSTEP rows.
   const uint32_t a_lds = lds_off(t >> 3, t & 7u);
@@ -241,6 +242,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       xo[i] = (min((TM) * BM + row, a.M - 1) * K + c * 8) * 2;                               \
       if (!ROWMAP) wo[i] = (min((TN) * BN + row, a.N - 1) * K + c * 8) * 2;                  \
     }                                                                                        \
+    eps_tile = (a.flip_row && (TM) * BM >= a.flip_row) ? -a.eps_signed : a.eps_signed;       \
     if (ROWMAP) {                                                                            \
       /* fused SwiGLU: the tile's rows are 4 x (32 gate rows, 32 up rows of the same   */      \
       /* features), so a lane's two accumulators hold gate and up of one feature      */      \
@@ -360,7 +362,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       const uint32_t w_ = p_ == 0 ? zw[0] : (p_ == 1 ? zw[1] : (p_ == 2 ? zw[2] : zw[3]));   \
       normal_pair(w_, zz_, z_odd);                                                           \
     }                                                                                        \
-    const float se_ = __builtin_fmaf(a.eps_signed, zz_, scale_to_f32(s_next, a.s_fp16 != 0));                \
+    const float se_ = __builtin_fmaf(eps_tile, zz_, scale_to_f32(s_next, a.s_fp16 != 0));    \
     se512 = ZP ? se_ : 512.0f * se_;                  /* ZP: the scale itself          */    \
     m8se = ZP ? -(float)z_next : -8.0f * se_;         /* ZP: the negated zero-point    */    \
   } while (0)
@@ -941,7 +943,7 @@ static hipError_t set_lds_attr(const void* fn) {
 constexpr int W4_NWN = 4;
 constexpr int W4_PIPE = 2;
 
-hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
+hipError_t launch_w4a16_gemm(const GemmArgs& a0, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
     hipError_t e = set_lds_attr((const void*)gemm_kernel<0, false, W4_NWN, W4_PIPE>);
@@ -949,9 +951,14 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     ready = true;
   }
-  if (a.M == 0 || a.N == 0) return hipSuccess;
-  if (a.M <= SKINNY_MAX_M && a.skinny_ws) return launch_skinny_gemm(a, a.skinny_ws, st);
-  if (a.dual) return hipErrorInvalidValue;          // only the few-token path stacks the two passes
+  if (a0.M == 0 || a0.N == 0) return hipSuccess;
+  if (a0.M <= SKINNY_MAX_M && a0.skinny_ws) return launch_skinny_gemm(a0, a0.skinny_ws, st);
+  GemmArgs a = a0;
+  if (a0.dual) {
+    // both passes of a step stacked: 2 M rows, whole token tiles per pass, the second pass's tiles take -eps
+    if (a0.M % BM != 0) return hipErrorInvalidValue;
+    a.M = 2 * a0.M; a.flip_row = a0.M; a.dual = 0;
+  }
   // buffer loads address each operand with 32-bit byte offsets
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;

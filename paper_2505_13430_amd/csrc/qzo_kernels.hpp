@@ -46,7 +46,9 @@ struct GemmArgs {
   float* skinny_ws;     // fp32 scratch of skinny_ws_floats(rows, N, K) floats: enables the few-token path (M <= 64)
   float* split_ws;      // fp32 scratch of tile_split_ws_floats(M, N, K) floats: enables split-K of the int4 tile kernel
   uint32_t ksplit, kt_per;   // set by the launcher: K slices and k-tiles per slice
-  uint32_t dual;        // few-token path only: x, y, resid hold 2 M rows; rows [0,M) use +eps_signed, [M,2M) -eps_signed
+  uint32_t dual;        // both passes of a step stacked: x, y, resid hold 2 M rows; rows [0,M) use +eps_signed,
+                        // [M,2M) -eps_signed (few-token path: M <= 32; tile path: M a multiple of 256)
+  uint32_t flip_row;    // set by the launcher for the tile kernel: rows from here on take -eps_signed (0: none)
   uint32_t M, N, K;
   uint32_t row_base;
   uint32_t seed_lo, seed_hi;
@@ -57,6 +59,7 @@ struct GemmArgs {
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
 // Few-token path (M <= 64): weights streamed once, K split over workgroups, partial sums in ws.
 constexpr uint32_t SKINNY_MAX_M = 64;
+constexpr uint32_t STACK_TILE_MAX_M = 2048;  // tile kernel: the two passes share a launch up to this many tokens per pass
 constexpr uint32_t SKINNY_MAX_M_DUAL = 32;   // per sign, when both perturbed passes share one launch
 uint32_t skinny_ksplit(uint32_t N, uint32_t K);
 uint64_t skinny_ws_floats(uint32_t M, uint32_t N, uint32_t K);

@@ -432,6 +432,28 @@ def test_stacked_passes_equal_separate_passes(oracle, name):
     dm.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "long_opt+zp"])
+def test_stacked_tile_passes_match_separate_passes(oracle, name):
+    """With whole 256-token tiles per pass (256 .. 2048 tokens) qzo_step runs both perturbed passes
+    as one stacked forward through the tile kernel, the second pass's tiles with -eps.  The K split
+    of a linear depends on the number of token tiles, so the sums are ordered differently than in
+    two separate passes: equal to within the 16-bit activations' noise, not bit for bit."""
+    base, asym = _case(name)
+    om, dm = _models(oracle, base, 1234, 4.0, **_variant_args(asym))
+    assert (base["batch"] * base["seq"]) % 256 == 0
+    tokd = _dev(synth.tokens(base, 5678))
+    res = qb.read_step_result(dm.step(tokd, 21, 1e-3, 0.0, 100.0))       # eta = 0: scales untouched
+    lp = float(dm.forward_loss(tokd, 21, 1e-3, 1).item())
+    lm = float(dm.forward_loss(tokd, 21, 1e-3, -1).item())
+    assert abs(res["loss_plus"] - lp) <= 2e-3 * lp and abs(res["loss_minus"] - lm) <= 2e-3 * lm
+    assert res["loss_plus"] != res["loss_minus"]
+    # the sign of each pass is the right one: the stacked losses are closer to their own pass than to the other
+    if abs(lp - lm) > 8e-3 * lp:
+        assert abs(res["loss_plus"] - lp) < abs(res["loss_plus"] - lm)
+        assert abs(res["loss_minus"] - lm) < abs(res["loss_minus"] - lp)
+    dm.close()
+
+
 def test_step_special_cases(oracle):
     shape = synth.SHAPES["tiny"]
     om, dm = _models(oracle, shape, 1234)
