@@ -184,14 +184,21 @@ void table_layout(const qzo_model_config& c, std::vector<uint64_t>& need, std::v
 
 // Whether qzo_step runs its two perturbed passes as one forward over 2 * batch sequences.  With at
 // most 32 tokens the few-token kernel reads the int4 weights once for both; with whole 256-token
-// tiles per pass (up to 2048 tokens, where the fused kernel serves) a launch of the tile kernel
+// tiles per pass (where the fused kernel serves, at most 4096 tokens) a launch of the tile kernel
 // holds both passes' tiles, the second pass's with -eps: twice the tiles per launch for a chip that
 // such token counts do not fill, half the launches.
 bool passes_stacked(const qzo_model* m, uint64_t M1) {
   const qzo_model_config& c = m->cfg;
   if (!(c.quant == 0 || c.quant == 2) || m->dense_master || c.act_order) return false;
   if (M1 <= SKINNY_MAX_M_DUAL) return true;
-  return M1 % 256 == 0 && M1 <= STACK_TILE_MAX_M && m->int4_path != 2;
+  if (M1 % 256 != 0 || M1 > STACK_TILE_MAX_M || m->int4_path == 2) return false;
+  // Stacked, the fused kernel stays ahead of expand-then-multiply for a fifth more tokens than the
+  // break-even of separate passes (7B widths: 72.2 against 74.9 ms per step at 2560 tokens, 83.8
+  // against 85.0 at 3072, 103.5 against 100.1 at 4096).
+  if (m->int4_path == 0)
+    for (int i = 0; i < 4; ++i)
+      if (M1 * 5 >= (uint64_t)expand_min_m_int4(m->lin[i].N, m->lin[i].K) * 6) return false;
+  return true;
 }
 
 Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {

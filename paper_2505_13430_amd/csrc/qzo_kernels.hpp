@@ -59,7 +59,7 @@ struct GemmArgs {
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
 // Few-token path (M <= 64): weights streamed once, K split over workgroups, partial sums in ws.
 constexpr uint32_t SKINNY_MAX_M = 64;
-constexpr uint32_t STACK_TILE_MAX_M = 2048;  // tile kernel: the two passes share a launch up to this many tokens per pass
+constexpr uint32_t STACK_TILE_MAX_M = 4096;  // tile kernel: the two passes share a launch up to this many tokens per pass
 constexpr uint32_t SKINNY_MAX_M_DUAL = 32;   // per sign, when both perturbed passes share one launch
 uint32_t skinny_ksplit(uint32_t N, uint32_t K);
 uint64_t skinny_ws_floats(uint32_t M, uint32_t N, uint32_t K);
