@@ -172,12 +172,12 @@ qzo_status qzo_forward_loss(qzo_model* m, const int32_t* tokens_dev, uint32_t ba
  * With int4 weights (no joint mode, no group index per column) the two forwards run as one
  * forward over 2*batch sequences when batch*seq <= 32 (the few-token kernel then reads the
  * weights once for both passes; losses bit-identical to two qzo_forward_loss calls) or when
- * batch*seq is a multiple of 256 below the token count from which the model's linears take
- * the expand-then-multiply route (about 3200 at Llama-2-7B widths; at most 4096; never when that
- * route is forced) (a launch of the tile kernel then holds the token tiles of
- * both passes, the second pass's with -eps; losses equal to two qzo_forward_loss calls
- * within the 16-bit activations' noise, the K split of a linear being a function of the
- * number of token tiles).  qzo_workspace_bytes accounts for it.
+ * batch*seq is above 64 and below the token count from which the model's linears take the
+ * expand-then-multiply route (about 3200 at Llama-2-7B widths; at most 4096; never when that
+ * route is forced): a launch of the tile kernel then holds the token tiles of both passes, the
+ * second pass's with -eps and starting on a 256-row tile boundary (padding rows in between);
+ * losses equal to two qzo_forward_loss calls within the 16-bit activations' noise, the K split
+ * of a linear being a function of the number of token tiles.  qzo_workspace_bytes accounts for it.
  */
 qzo_status qzo_step(qzo_model* m, const int32_t* tokens_dev, uint32_t batch, uint32_t seq,
                     uint64_t seed, float eps, float eta, float clip, void* workspace_dev,

@@ -183,15 +183,17 @@ void table_layout(const qzo_model_config& c, std::vector<uint64_t>& need, std::v
 }
 
 // Whether qzo_step runs its two perturbed passes as one forward over 2 * batch sequences.  With at
-// most 32 tokens the few-token kernel reads the int4 weights once for both; with whole 256-token
-// tiles per pass (where the fused kernel serves, at most 4096 tokens) a launch of the tile kernel
-// holds both passes' tiles, the second pass's with -eps: twice the tiles per launch for a chip that
-// such token counts do not fill, half the launches.
+// most 32 tokens the few-token kernel reads the int4 weights once for both.  Beyond the few-token
+// kernel's range and as long as the fused kernel serves (at most 4096 tokens per pass), a launch of
+// the tile kernel holds both passes' token tiles, the second pass's with -eps: twice the tiles per
+// launch for a chip that such token counts do not fill, half the launches.  The second pass starts
+// on a tile boundary (stacked_pass_stride); the rows in between are padding (zeros at the embedding,
+// never read back).
 bool passes_stacked(const qzo_model* m, uint64_t M1) {
   const qzo_model_config& c = m->cfg;
   if (!(c.quant == 0 || c.quant == 2) || m->dense_master || c.act_order) return false;
   if (M1 <= SKINNY_MAX_M_DUAL) return true;
-  if (M1 % 256 != 0 || M1 > STACK_TILE_MAX_M || m->int4_path == 2) return false;
+  if (M1 <= SKINNY_MAX_M || M1 > STACK_TILE_MAX_M || m->int4_path == 2) return false;
   // Stacked, the fused kernel stays ahead of expand-then-multiply for a fifth more tokens than the
   // break-even of separate passes (7B widths: 72.2 against 74.9 ms per step at 2560 tokens, 83.8
   // against 85.0 at 3072, 103.5 against 100.1 at 4096).
@@ -200,13 +202,15 @@ bool passes_stacked(const qzo_model* m, uint64_t M1) {
       if (M1 * 5 >= (uint64_t)expand_min_m_int4(m->lin[i].N, m->lin[i].K) * 6) return false;
   return true;
 }
+// Row at which the second pass of a stacked forward starts.
+uint64_t stacked_pass_stride(uint64_t M1) { return M1 <= SKINNY_MAX_M_DUAL ? M1 : (M1 + 255) / 256 * 256; }
 
 Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   const qzo_model_config& c = m->cfg;
   const uint64_t M1 = (uint64_t)batch * seq;
   const bool int4 = c.quant == 0 || c.quant == 2;
   const bool stack = passes_stacked(m, M1);
-  const uint64_t M = stack ? 2 * M1 : M1, d = c.d_model, F = c.d_ffn;
+  const uint64_t M = stack ? stacked_pass_stride(M1) + M1 : M1, d = c.d_model, F = c.d_ffn;
   const uint64_t n_slices = ((c.vocab + 255) / 256) * 4;
   Workspace w;
   uint64_t off = 0;
@@ -270,7 +274,8 @@ qzo_status check_batch(const qzo_model* m, const void* tok, uint32_t batch, uint
     // the kernels address every operand with 32-bit byte offsets: tokens x widest tensor row, in
     // bf16, must stay below 2^31 bytes (stacked passes count twice)
     const qzo_model_config& c = m->cfg;
-    const uint64_t M1 = (uint64_t)batch * seq * (passes_stacked(m, (uint64_t)batch * seq) ? 2 : 1);
+    const uint64_t M1 = (uint64_t)batch * seq +
+                        (passes_stacked(m, (uint64_t)batch * seq) ? stacked_pass_stride((uint64_t)batch * seq) : 0);
     const uint64_t widest = std::max<uint64_t>({3ull * c.d_model, (c.arch == 0 ? 2ull : 1ull) * c.d_ffn});
     if (M1 * widest * 2 >= (1ull << 31))
       return fail(QZO_ERR_SHAPE, "batch*seq too large for this model: an activation tensor would exceed 2^31 bytes");
@@ -311,13 +316,17 @@ enum { PK_W4GEMM = 0, PK_LMHEAD = 1, PK_ATTN = 2, PK_UPDATE = 3, PK_OTHER = 4, P
 
 // The decoder forward with every quantized linear perturbed by sign*eps*z.
 // n_pass = 2 (int4 only; see passes_stacked): both passes of a step stacked, rows [0,M1) perturbed by
-// +eps_signed and rows [M1, 2 M1) by -eps_signed; their losses go to loss_out and loss_out2.
+// +eps_signed and rows [P, P + M1) by -eps_signed, P = stacked_pass_stride(M1); their losses go to
+// loss_out and loss_out2.
 qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t seq, uint64_t seed,
                    float eps_signed, const Workspace& w, float* loss_out, hipStream_t st,
                    void* hidden_out = nullptr, uint32_t n_pass = 1, float* loss_out2 = nullptr) {
   const qzo_model_config& c = m->cfg;
   const uint32_t batch = batch1 * n_pass, M1 = batch1 * seq;
-  const uint32_t M = batch * seq, d = c.d_model, F = c.d_ffn, H = c.n_heads, dh = d / H;
+  const uint32_t P = n_pass == 2 ? (uint32_t)stacked_pass_stride(M1) : M1;     // rows per pass
+  const bool padded = P != M1;                                                // rows [M1, P) are padding
+  const uint32_t M = n_pass == 2 ? P + M1 : M1;                               // rows of every activation
+  const uint32_t d = c.d_model, F = c.d_ffn, H = c.n_heads, dh = d / H;
   const bool llama = c.arch == 0, asym = c.quant == 2;
   const uint32_t seed_lo = (uint32_t)seed, seed_hi = (uint32_t)(seed >> 32);
   const unsigned char* arena = (const unsigned char*)m->arena;
@@ -334,9 +343,19 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   {
     ProfScope ps(PK_OTHER, 0, st);
     if (llama) QZO_HIP(launch_rope_table(w.rope, seq, dh, c.rope_theta, st));
-    QZO_HIP(launch_embed(tok, M1, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
+    QZO_HIP(launch_embed(tok, M1, P, m->T[0].ptr_dev, llama ? nullptr : m->T[1].ptr_dev, M, seq, d, w.h, st));
   }
   const double attn_flops = 2.0 * batch * H * (double)seq * seq * dh;   // causal: half of 4 B H S^2 dh
+  const double Mreal = (double)n_pass * M1;                             // rows that count as work
+  // attention over both passes: one launch when they are contiguous, one per pass otherwise
+  auto attention = [&]() {
+    ProfScope ps(PK_ATTN, attn_flops, st);
+    if (!padded) return launch_attention(w.qkv, batch, seq, H, dh, w.att, st);
+    hipError_t e = launch_attention(w.qkv, batch1, seq, H, dh, w.att, st);
+    if (e != hipSuccess) return e;
+    return launch_attention((const unsigned char*)w.qkv + (size_t)P * 3 * d * 2, batch1, seq, H, dh,
+                            (unsigned char*)w.att + (size_t)P * d * 2, st);
+  };
   auto other = [&](hipError_t e) { return e; };
   (void)other;
   for (uint32_t l = 0; l < c.n_layers; ++l) {
@@ -360,7 +379,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.bias = bias; g.resid = resid; g.y = y;
       g.M = M1; g.N = m->lin[li].N; g.K = m->lin[li].K;
       g.dual = n_pass == 2;
-      if (n_pass == 1) g.M = M;
+      g.pass_stride = n_pass == 2 ? P : 0;
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
       g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
       g.s_fp16 = c.scale_fp16;
@@ -378,7 +397,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
-        ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+        ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
       if (c.quant == 3) {
@@ -391,7 +410,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
-        ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+        ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
       if (w.wexp && m->int4_path != 1 && n_pass == 1 &&
@@ -404,10 +423,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;
-        ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+        ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
-      ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+      ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
       return launch_w4a16_gemm(g, st);
     };
     auto cgemm = [&](int li, const void* x, const void* codes, const void* cb, const void* resid,
@@ -430,21 +449,18 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.cb = nullptr; g.s = nullptr; g.split_ws = split ? w.split : nullptr;
-        ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+        ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
-      ProfScope ps(PK_W4GEMM, 2.0 * M * (double)g.N * g.K, st);
+      ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
       return launch_codebook_gemm(g, st);
     };
     if (llama && c.quant == 1) {
       // attn_norm, codes/cb qkv, codes/cb o, ffn_norm, codes/cb gate+up, codes/cb down
       QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(cgemm(0, w.a, T[1].ptr_dev, T[2].ptr_dev, nullptr, w.qkv, 0));
-      QZO_HIP(launch_rope(w.qkv, w.rope, batch, seq, d, H, st));
-      {
-        ProfScope ps(PK_ATTN, attn_flops, st);
-        QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
-      }
+      QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
+      QZO_HIP(attention());
       QZO_HIP(cgemm(1, w.att, T[3].ptr_dev, T[4].ptr_dev, w.h, w.h, EPI_RESIDUAL));
       QZO_HIP(launch_rmsnorm(w.h, T[5].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(cgemm(2, w.a, T[6].ptr_dev, T[7].ptr_dev, nullptr, w.act, EPI_SWIGLU));
@@ -453,11 +469,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       // attn_norm, wqkv, wo, ffn_norm, wgu, wdown (symmetric-table positions)
       QZO_HIP(launch_rmsnorm(w.h, ti(0), M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(0, w.a, nullptr, nullptr, w.qkv, 0));
-      QZO_HIP(launch_rope(w.qkv, w.rope, batch, seq, d, H, st));
-      {
-        ProfScope ps(PK_ATTN, attn_flops, st);
-        QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
-      }
+      QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
+      QZO_HIP(attention());
       QZO_HIP(gemm(1, w.att, nullptr, w.h, w.h, EPI_RESIDUAL));
       QZO_HIP(launch_rmsnorm(w.h, ti(3), M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(2, w.a, nullptr, nullptr, w.act, EPI_SWIGLU));
@@ -466,10 +479,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       // ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, wfc1, bfc1, wfc2, bfc2 (symmetric-table positions)
       QZO_HIP(launch_layernorm(w.h, ti(0), ti(1), M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(0, w.a, ti(3), nullptr, w.qkv, EPI_BIAS));
-      {
-        ProfScope ps(PK_ATTN, attn_flops, st);
-        QZO_HIP(launch_attention(w.qkv, batch, seq, H, dh, w.att, st));
-      }
+      QZO_HIP(attention());
       QZO_HIP(gemm(1, w.att, ti(5), w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
       QZO_HIP(launch_layernorm(w.h, ti(6), ti(7), M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(2, w.a, ti(9), nullptr, w.ff, EPI_BIAS | EPI_RELU));
@@ -488,16 +498,22 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   if (hidden_out)
     QZO_HIP(hipMemcpyAsync(hidden_out, w.a, (size_t)M * d * 2, hipMemcpyDeviceToDevice, st));
   CeArgs ce = {};
-  ce.x = w.a; ce.w = lm_head; ce.tok = tok; ce.tok_rows = M1; ce.part = w.ce_part; ce.tgt = w.tgt;
-  ce.M = M; ce.V = c.vocab; ce.K = d; ce.S = seq; ce.n_slices = ((c.vocab + 255) / 256) * 4;
-  {
-    ProfScope ps(PK_LMHEAD, 2.0 * M * (double)c.vocab * d, st);
+  ce.w = lm_head; ce.tok = tok; ce.tok_rows = M1;
+  ce.V = c.vocab; ce.K = d; ce.S = seq; ce.n_slices = ((c.vocab + 255) / 256) * 4;
+  // both passes in one launch when they are contiguous, one launch per pass otherwise
+  for (uint32_t r0 = 0; r0 < M; r0 += P) {
+    ce.x = (const unsigned char*)w.a + (size_t)r0 * d * 2;
+    ce.part = w.ce_part + (size_t)r0 * ce.n_slices * 2;
+    ce.tgt = w.tgt + r0;
+    ce.M = padded ? M1 : M;
+    ProfScope ps(PK_LMHEAD, 2.0 * ce.M * (double)c.vocab * d, st);
     QZO_HIP(launch_lmhead_ce(ce, st));
+    if (!padded) break;
   }
   QZO_HIP(launch_ce_reduce(w.ce_part, w.tgt, M1, seq, ce.n_slices, w.rowloss, loss_out, st));
   if (n_pass == 2)
-    QZO_HIP(launch_ce_reduce(w.ce_part + (size_t)M1 * ce.n_slices * 2, w.tgt + M1, M1, seq, ce.n_slices,
-                             w.rowloss + M1, loss_out2, st));
+    QZO_HIP(launch_ce_reduce(w.ce_part + (size_t)P * ce.n_slices * 2, w.tgt + P, M1, seq, ce.n_slices,
+                             w.rowloss + P, loss_out2, st));
   return QZO_OK;
 }
 

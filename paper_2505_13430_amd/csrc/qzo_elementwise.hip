@@ -457,31 +457,35 @@ hipError_t launch_repack_kmajor(const void* qweight, const void* qzeros, const v
 }
 
 // -------------------------------------------------------- embedding -------
-// row m embeds tok[m % tok_rows] (the same batch may be stacked twice)
-__global__ void embed_kernel(const int32_t* __restrict__ tok, uint32_t tok_rows,
+// Row m belongs to pass m / pass_stride and is row r = m % pass_stride of it: it embeds tok[r] at
+// position r % S, or zeros when r >= tok_rows (rows that pad a pass to a whole number of GEMM tiles).
+__global__ void embed_kernel(const int32_t* __restrict__ tok, uint32_t tok_rows, uint32_t pass_stride,
                              const bf16_t* __restrict__ te,
                              const bf16_t* __restrict__ pe, uint32_t M, uint32_t S, uint32_t d,
                              bf16_t* __restrict__ h) {
   const uint32_t cpr = d >> 3;
   const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (u >= (uint64_t)M * cpr) return;
-  const uint32_t m = (uint32_t)(u / cpr), c = (uint32_t)(u % cpr);
-  uint4 v = *reinterpret_cast<const uint4*>(te + (uint64_t)tok[m % tok_rows] * d + c * 8);
-  if (pe) {
-    uint4 p = *reinterpret_cast<const uint4*>(pe + (uint64_t)(m % S) * d + c * 8);
-    uint32_t a[4] = {v.x, v.y, v.z, v.w}, b[4] = {p.x, p.y, p.z, p.w}, o[4];
+  const uint32_t m = (uint32_t)(u / cpr), c = (uint32_t)(u % cpr), r = m % pass_stride;
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (r < tok_rows) {
+    v = *reinterpret_cast<const uint4*>(te + (uint64_t)tok[r] * d + c * 8);
+    if (pe) {
+      uint4 p = *reinterpret_cast<const uint4*>(pe + (uint64_t)(r % S) * d + c * 8);
+      uint32_t a[4] = {v.x, v.y, v.z, v.w}, b[4] = {p.x, p.y, p.z, p.w}, o[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      o[j] = pack_bf16x2(__uint_as_float(a[j] << 16) + __uint_as_float(b[j] << 16),
-                         __uint_as_float(a[j] & 0xffff0000u) + __uint_as_float(b[j] & 0xffff0000u));
-    v = make_uint4(o[0], o[1], o[2], o[3]);
+      for (int j = 0; j < 4; ++j)
+        o[j] = pack_bf16x2(__uint_as_float(a[j] << 16) + __uint_as_float(b[j] << 16),
+                           __uint_as_float(a[j] & 0xffff0000u) + __uint_as_float(b[j] & 0xffff0000u));
+      v = make_uint4(o[0], o[1], o[2], o[3]);
+    }
   }
   *reinterpret_cast<uint4*>(h + (uint64_t)m * d + c * 8) = v;
 }
-hipError_t launch_embed(const int32_t* tok, uint32_t tok_rows, const void* tok_emb, const void* pos_emb, uint32_t M,
-                        uint32_t S, uint32_t d, void* h, hipStream_t st) {
+hipError_t launch_embed(const int32_t* tok, uint32_t tok_rows, uint32_t pass_stride, const void* tok_emb,
+                        const void* pos_emb, uint32_t M, uint32_t S, uint32_t d, void* h, hipStream_t st) {
   uint64_t units = (uint64_t)M * (d >> 3);
-  embed_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(tok, tok_rows, (const bf16_t*)tok_emb,
+  embed_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>(tok, tok_rows, pass_stride, (const bf16_t*)tok_emb,
                                                                (const bf16_t*)pos_emb, M, S, d,
                                                                (bf16_t*)h);
   return hipGetLastError();
@@ -614,9 +618,10 @@ hipError_t launch_rope_table(float* table, uint32_t max_seq, uint32_t dh, float 
                                                      (double)theta, (double)dh);
   return hipGetLastError();
 }
-// rotate-half pairing (i, i+dh/2) on the q and k thirds of qkv [M, 3d], in place.
+// rotate-half pairing (i, i+dh/2) on the q and k thirds of qkv [M, 3d], in place; row m is at
+// position (m % pass_stride) % S.
 __global__ void rope_kernel(bf16_t* __restrict__ qkv, const float2* __restrict__ table, uint32_t M,
-                            uint32_t S, uint32_t d, uint32_t n_heads) {
+                            uint32_t S, uint32_t pass_stride, uint32_t d, uint32_t n_heads) {
   const uint32_t dh = d / n_heads, half = dh >> 1, cph = half >> 3;   // 8-wide chunks per half head
   const uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint64_t per_row = (uint64_t)2 * n_heads * cph;
@@ -626,7 +631,7 @@ __global__ void rope_kernel(bf16_t* __restrict__ qkv, const float2* __restrict__
   const uint32_t c = r % cph; r /= cph;
   const uint32_t h = r % n_heads, which = r / n_heads;
   bf16_t* p = qkv + (uint64_t)m * 3 * d + (uint64_t)which * d + h * dh + c * 8;
-  const float2* tb = table + (uint64_t)(m % S) * half + c * 8;
+  const float2* tb = table + (uint64_t)((m % pass_stride) % S) * half + c * 8;
   uint4 va = *reinterpret_cast<const uint4*>(p), vb = *reinterpret_cast<const uint4*>(p + half);
   uint32_t a[4] = {va.x, va.y, va.z, va.w}, b[4] = {vb.x, vb.y, vb.z, vb.w}, oa[4], ob[4];
 #pragma unroll
@@ -640,12 +645,12 @@ __global__ void rope_kernel(bf16_t* __restrict__ qkv, const float2* __restrict__
   *reinterpret_cast<uint4*>(p) = make_uint4(oa[0], oa[1], oa[2], oa[3]);
   *reinterpret_cast<uint4*>(p + half) = make_uint4(ob[0], ob[1], ob[2], ob[3]);
 }
-hipError_t launch_rope(void* qkv, const float* table, uint32_t B, uint32_t S, uint32_t d,
+hipError_t launch_rope(void* qkv, const float* table, uint32_t M, uint32_t S, uint32_t pass_stride, uint32_t d,
                        uint32_t n_heads, hipStream_t st) {
   const uint32_t dh = d / n_heads;
-  uint64_t units = (uint64_t)B * S * 2 * n_heads * (dh / 16);
+  uint64_t units = (uint64_t)M * 2 * n_heads * (dh / 16);
   rope_kernel<<<(uint32_t)((units + 255) / 256), 256, 0, st>>>((bf16_t*)qkv, (const float2*)table,
-                                                              B * S, S, d, n_heads);
+                                                              M, S, pass_stride, d, n_heads);
   return hipGetLastError();
 }
 

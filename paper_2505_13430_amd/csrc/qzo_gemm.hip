@@ -955,9 +955,10 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a0, hipStream_t st) {
   if (a0.M <= SKINNY_MAX_M && a0.skinny_ws) return launch_skinny_gemm(a0, a0.skinny_ws, st);
   GemmArgs a = a0;
   if (a0.dual) {
-    // both passes of a step stacked: 2 M rows, whole token tiles per pass, the second pass's tiles take -eps
-    if (a0.M % BM != 0) return hipErrorInvalidValue;
-    a.M = 2 * a0.M; a.flip_row = a0.M; a.dual = 0;
+    // both passes of a step stacked: the second pass starts on a tile boundary and its tiles take -eps
+    const uint32_t stride = a0.pass_stride ? a0.pass_stride : a0.M;
+    if (stride % BM != 0 || stride < a0.M) return hipErrorInvalidValue;
+    a.M = stride + a0.M; a.flip_row = stride; a.dual = 0;
   }
   // buffer loads address each operand with 32-bit byte offsets
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))

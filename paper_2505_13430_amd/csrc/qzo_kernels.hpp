@@ -47,7 +47,9 @@ struct GemmArgs {
   float* split_ws;      // fp32 scratch of tile_split_ws_floats(M, N, K) floats: enables split-K of the int4 tile kernel
   uint32_t ksplit, kt_per;   // set by the launcher: K slices and k-tiles per slice
   uint32_t dual;        // both passes of a step stacked: x, y, resid hold 2 M rows; rows [0,M) use +eps_signed,
-                        // [M,2M) -eps_signed (few-token path: M <= 32; tile path: M a multiple of 256)
+                        // [M,2M) -eps_signed (few-token path: M <= 32; tile path: see pass_stride)
+  uint32_t pass_stride; // dual, tile path: the second pass starts at this row (a multiple of 256 >= M; x, y, resid
+                        // hold pass_stride + M rows, the rows in between are padding); 0: at row M
   uint32_t flip_row;    // set by the launcher for the tile kernel: rows from here on take -eps_signed (0: none)
   uint32_t M, N, K;
   uint32_t row_base;
@@ -150,15 +152,16 @@ hipError_t launch_ce_reduce(const float* part, const float* tgt, uint32_t M, uin
 
 hipError_t launch_sum_partials(const float* partials, uint32_t n, float* out, hipStream_t st);
 
-hipError_t launch_embed(const int32_t* tok, uint32_t tok_rows, const void* tok_emb, const void* pos_emb, uint32_t M,
-                        uint32_t S, uint32_t d, void* h, hipStream_t st);
+// pass_stride: rows per pass of a stacked forward (M for a single pass); rows m % pass_stride >= tok_rows get zeros.
+hipError_t launch_embed(const int32_t* tok, uint32_t tok_rows, uint32_t pass_stride, const void* tok_emb,
+                        const void* pos_emb, uint32_t M, uint32_t S, uint32_t d, void* h, hipStream_t st);
 hipError_t launch_rmsnorm(const void* x, const void* gain, uint32_t M, uint32_t d, float eps,
                           void* y, hipStream_t st);
 hipError_t launch_layernorm(const void* x, const void* gain, const void* bias, uint32_t M,
                             uint32_t d, float eps, void* y, hipStream_t st);
 hipError_t launch_rope_table(float* table, uint32_t max_seq, uint32_t dh, float theta,
                              hipStream_t st);
-hipError_t launch_rope(void* qkv, const float* table, uint32_t B, uint32_t S, uint32_t d,
+hipError_t launch_rope(void* qkv, const float* table, uint32_t M, uint32_t S, uint32_t pass_stride, uint32_t d,
                        uint32_t n_heads, hipStream_t st);
 hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_heads,
                             uint32_t dh, void* out, hipStream_t st);
