@@ -358,6 +358,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   };
   auto other = [&](hipError_t e) { return e; };
   (void)other;
+  bool rope_fused = false;     // set by a qkv linear whose GEMM applied the rotary embedding itself
   for (uint32_t l = 0; l < c.n_layers; ++l) {
     const qzo_buf* T = &m->T[m->first_layer_tensor + (size_t)l * m->tensors_per_layer];
     const uint64_t layer_off = (uint64_t)l * m->scales_per_layer;
@@ -381,7 +382,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.dual = n_pass == 2;
       g.pass_stride = n_pass == 2 ? P : 0;
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
-      g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
+      g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed;
+      g.epi = epi & ~EPI_ROPE;                // a request: only the plain GEMM of the int4 expansion route serves it
       g.s_fp16 = c.scale_fp16;
       g.skinny_ws = w.skinny;
       g.split_ws = w.split;
@@ -415,11 +417,19 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       }
       if (w.wexp && m->int4_path != 1 && n_pass == 1 &&
           (m->int4_path == 2 || M >= expand_min_m_int4(g.N, g.K))) {
-        // many tokens: write the perturbed matrix out once, then a plain bf16 GEMM
+        // many tokens: write the perturbed matrix out once, then a plain bf16 GEMM.  The rotary embedding
+        // of a qkv linear rides on that GEMM's epilogue (heads of 64 or 128; with 128 the matrix is
+        // written in the row order that puts feature i and i + 64 of a head into one lane).
+        int order = (epi & EPI_SWIGLU) ? ROW_ORDER_SWIGLU : ROW_ORDER_NATURAL;
+        if (epi == EPI_ROPE && (dh == 64 || (dh == 128 && g.N % 256 == 0))) {
+          if (dh == 128) order = ROW_ORDER_ROPE128;
+          g.epi = EPI_ROPE; g.rope = w.rope; g.rope_S = seq; g.rope_dh = dh;
+          rope_fused = true;
+        }
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
           hipError_t e = launch_expand_int4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.zp, nullptr, g.N,
-                                                 g.K, (epi & EPI_SWIGLU) != 0, w.wexp, st);
+                                                 g.K, order, w.wexp, st);
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;
@@ -468,8 +478,9 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
     } else if (llama) {
       // attn_norm, wqkv, wo, ffn_norm, wgu, wdown (symmetric-table positions)
       QZO_HIP(launch_rmsnorm(w.h, ti(0), M, d, c.norm_eps, w.a, st));
-      QZO_HIP(gemm(0, w.a, nullptr, nullptr, w.qkv, 0));
-      QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
+      rope_fused = false;
+      QZO_HIP(gemm(0, w.a, nullptr, nullptr, w.qkv, EPI_ROPE));
+      if (!rope_fused) QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
       QZO_HIP(attention());
       QZO_HIP(gemm(1, w.att, nullptr, w.h, w.h, EPI_RESIDUAL));
       QZO_HIP(launch_rmsnorm(w.h, ti(3), M, d, c.norm_eps, w.a, st));

@@ -9,13 +9,17 @@
 
 namespace qzo {
 
-// Row p of the output holds source row gn(p): the identity, or for a fused-SwiGLU consumer
-// the tile order of the GEMM (each 256-row tile = 4 x (32 gate rows, 32 up rows of the same
-// features); N = 2F, F a multiple of 128).
-__device__ __forceinline__ uint32_t expand_source_row(uint32_t p, uint32_t N, bool swiglu) {
-  if (!swiglu) return p;
+// Row p of the output holds source row gn(p): the identity; for a fused-SwiGLU consumer the tile
+// order of the GEMM (each 256-row tile = 4 x (32 gate rows, 32 up rows of the same features); N = 2F,
+// F a multiple of 128); for a fused-RoPE consumer with heads of 128 features, within every 256 rows
+// (two heads; N a multiple of 256) wavefront wn's 64 columns = features 32 (wn % 2) .. + 31 of head
+// wn / 2 and the same features + 64.
+__device__ __forceinline__ uint32_t expand_source_row(uint32_t p, uint32_t N, int order) {
+  if (order == ROW_ORDER_NATURAL) return p;
   const uint32_t tn = p >> 8, r = p & 255u;
-  return ((r >> 5) & 1u) * (N >> 1) + tn * 128u + (r >> 6) * 32u + (r & 31u);
+  if (order == ROW_ORDER_SWIGLU) return ((r >> 5) & 1u) * (N >> 1) + tn * 128u + (r >> 6) * 32u + (r & 31u);
+  const uint32_t wn = r >> 6, j = (r >> 5) & 1u;
+  return tn * 256u + (wn >> 1) * 128u + j * 64u + (wn & 1u) * 32u + (r & 31u);
 }
 
 // Codebook variant: W[n, 8c .. 8c+7] = (c_n + sigma*eps*z_n) * codebook[code[n,c]][0..7],
@@ -30,7 +34,7 @@ __global__ __launch_bounds__(256) void expand_codebook_kernel(const uint16_t* __
                                                               uint4* __restrict__ out) {
   const uint32_t p = blockIdx.x * 4u + (threadIdx.x >> 6), lane = threadIdx.x & 63u;
   if (p >= N) return;
-  const uint32_t gn = expand_source_row(p, N, swiglu != 0);
+  const uint32_t gn = expand_source_row(p, N, swiglu);
   const float ce = __builtin_fmaf(eps_signed, flat_normal(seed_lo, seed_hi, 1u, row_base + gn), (float)c[gn]);
   const uint32_t nc = K >> 3;
   const uint16_t* crow = codes + (uint64_t)gn * nc;
@@ -59,11 +63,11 @@ __global__ __launch_bounds__(256) void expand_codebook_kernel(const uint16_t* __
 
 hipError_t launch_expand_codebook(const void* codes, const void* cb, const void* c_fp16, uint32_t N,
                                   uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi,
-                                  float eps_signed, bool swiglu, void* out_bf16, hipStream_t st) {
+                                  float eps_signed, int swiglu, void* out_bf16, hipStream_t st) {
   if (N == 0) return hipSuccess;
   expand_codebook_kernel<<<(N + 3) / 4, 256, 0, st>>>((const uint16_t*)codes, (const uint4*)cb,
                                                       (const _Float16*)c_fp16, N, K, row_base, seed_lo,
-                                                      seed_hi, eps_signed, swiglu ? 1 : 0, (uint4*)out_bf16);
+                                                      seed_hi, eps_signed, swiglu, (uint4*)out_bf16);
   return hipGetLastError();
 }
 
@@ -129,7 +133,7 @@ __global__ __launch_bounds__(256) void expand_nf4_kernel(const uint32_t* __restr
   __syncthreads();
   const uint32_t p = blockIdx.x, nc = K >> 3, kc = blockIdx.y * 256u + threadIdx.x;
   if (kc >= nc) return;
-  const uint32_t gn = expand_source_row(p, N, swiglu != 0);
+  const uint32_t gn = expand_source_row(p, N, swiglu);
   const uint32_t w = q[(uint64_t)gn * nc + kc];
   const float sc = se[(uint64_t)gn * (K >> 6) + (kc >> 3)];
   uint32_t o[4];
@@ -151,7 +155,7 @@ __global__ __launch_bounds__(256) void expand_int4_kernel(const uint32_t* __rest
                                                           uint32_t K, int swiglu, uint4* __restrict__ out) {
   const uint32_t p = blockIdx.x, nc = K >> 3, kc = blockIdx.y * 256u + threadIdx.x;
   if (kc >= nc) return;
-  const uint32_t gn = expand_source_row(p, N, swiglu != 0);
+  const uint32_t gn = expand_source_row(p, N, swiglu);
   const uint32_t w = q[(uint64_t)gn * nc + kc];
   const uint64_t g0 = (uint64_t)gn * (K >> 7);
   uint32_t o[4];
@@ -180,7 +184,7 @@ __global__ __launch_bounds__(256) void expand_int4_kernel(const uint32_t* __rest
 
 hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, const int32_t* g_idx,
                               uint32_t N, uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
-                              bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st) {
+                              int swiglu, float* se_scratch, void* out_bf16, hipStream_t st) {
   if (N == 0) return hipSuccess;
   const uint32_t G = K >> 7, Gb = (G + 7u) >> 3;
   const uint64_t units = (uint64_t)N * Gb;
@@ -189,7 +193,7 @@ hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   expand_int4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>(
-      (const uint32_t*)q, se_scratch, (const uint8_t*)zp, g_idx, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
+      (const uint32_t*)q, se_scratch, (const uint8_t*)zp, g_idx, N, K, swiglu, (uint4*)out_bf16);
   return hipGetLastError();
 }
 
@@ -202,23 +206,23 @@ hipError_t launch_perturbed_scales_all(const void* arena, const UpdPlan& plan, u
 }
 
 hipError_t launch_expand_int4_from(const void* q, const float* se, const void* zp, const int32_t* g_idx,
-                                   uint32_t N, uint32_t K, bool swiglu, void* out_bf16, hipStream_t st) {
+                                   uint32_t N, uint32_t K, int swiglu, void* out_bf16, hipStream_t st) {
   if (N == 0) return hipSuccess;
   expand_int4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>(
-      (const uint32_t*)q, se, (const uint8_t*)zp, g_idx, N, K, swiglu ? 1 : 0, (uint4*)out_bf16);
+      (const uint32_t*)q, se, (const uint8_t*)zp, g_idx, N, K, swiglu, (uint4*)out_bf16);
   return hipGetLastError();
 }
 
-hipError_t launch_expand_nf4_from(const void* q, const float* se, uint32_t N, uint32_t K, bool swiglu,
+hipError_t launch_expand_nf4_from(const void* q, const float* se, uint32_t N, uint32_t K, int swiglu,
                                   void* out_bf16, hipStream_t st) {
   if (N == 0) return hipSuccess;
-  expand_nf4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>((const uint32_t*)q, se, N, K, swiglu ? 1 : 0,
+  expand_nf4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>((const uint32_t*)q, se, N, K, swiglu,
                                                                    (uint4*)out_bf16);
   return hipGetLastError();
 }
 
 hipError_t launch_expand_nf4(const void* q, const void* s_bf16, uint32_t N, uint32_t K, uint32_t row_base,
-                             uint32_t seed_lo, uint32_t seed_hi, float eps_signed, bool swiglu,
+                             uint32_t seed_lo, uint32_t seed_hi, float eps_signed, int swiglu,
                              float* se_scratch, void* out_bf16, hipStream_t st) {
   if (N == 0) return hipSuccess;
   const uint32_t G = K >> 6, Gb = (G + 7u) >> 3;
@@ -228,7 +232,7 @@ hipError_t launch_expand_nf4(const void* q, const void* s_bf16, uint32_t N, uint
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   expand_nf4_kernel<<<dim3(N, ((K >> 3) + 255) / 256), 256, 0, st>>>((const uint32_t*)q, se_scratch, N, K,
-                                                                   swiglu ? 1 : 0, (uint4*)out_bf16);
+                                                                   swiglu, (uint4*)out_bf16);
   return hipGetLastError();
 }
 

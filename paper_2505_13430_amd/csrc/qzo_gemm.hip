@@ -790,6 +790,78 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
       }
     }
     trail_stores = TRAIL ? 8 : 0;
+  } else if (!CE && TJ == 2 && !W4 && !CB && (a.epi & EPI_ROPE)) {
+    // qkv [M, 3d] with the rotary embedding on its q and k thirds.  The wavefront's two 32-wide
+    // feature tiles hold feature i and feature i + dh/2 of a head for the same token (heads of 64:
+    // the natural order; heads of 128: the rows of W were written in ROW_ORDER_ROPE128), so a lane
+    // rotates its own pairs: each output is first rounded to bf16 (the value a separate RoPE pass
+    // would read), then (a cos - b sin, b cos + a sin) in fp32 at position m % rope_S, rounded again.
+    const uint32_t half = a.rope_dh >> 1, d2 = (a.N / 3u) * 2u;
+    const float2* table = reinterpret_cast<const float2*>(a.rope);
+    // step u = 2 i + bp handles token 32 i + frow and the lane's 8 features (2 bp + fhalf) * 8 .. + 7 of the
+    // first tile with their partners in the second; the (cos, sin) values of step u + 1 are requested
+    // before step u is worked on, so that one memory latency is exposed per output tile, not eight
+    const uint32_t na_base = half == 64u ? n0 + (wn >> 1) * 128u + (wn & 1u) * 32u : n0 + wn * 64u;
+    const uint32_t idx_base = half == 64u ? (wn & 1u) * 32u : 0u;
+    const bool rotate = na_base < d2;            // a wavefront's 64 columns lie within one third of qkv
+    auto tb_of = [&](int u) {
+      const uint32_t m = m0 + wm * 128 + (u >> 1) * 32 + frow;
+      const uint32_t pos = min(m, a.M - 1) % a.rope_S;
+      return reinterpret_cast<const float4*>(table + (uint64_t)pos * half + idx_base + (2u * (u & 1) + fhalf) * 8u);
+    };
+    float4 tn[4] = {};
+    if (rotate) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) tn[j] = tb_of(0)[j];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = u >> 1, bp = u & 1;
+      const uint32_t m = m0 + wm * 128 + i * 32 + frow;
+      float4 t[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) t[j] = tn[j];
+      if (rotate && u < 7) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tn[j] = tb_of(u + 1)[j];
+      }
+      float va[2][4], vb[2][4];
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          va[h][c] = acc[i][0][4 * (2 * bp + h) + c];
+          vb[h][c] = acc[i][1][4 * (2 * bp + h) + c];
+        }
+      QZO_SWAP8(va[0], va[1]);
+      QZO_SWAP8(vb[0], vb[1]);
+      const uint32_t na = na_base + (2u * bp + fhalf) * 8u;
+      uint32_t oa[4], ob[4];
+      oa[0] = pack_bf16x2(va[0][0], va[0][1]); oa[1] = pack_bf16x2(va[0][2], va[0][3]);
+      oa[2] = pack_bf16x2(va[1][0], va[1][1]); oa[3] = pack_bf16x2(va[1][2], va[1][3]);
+      ob[0] = pack_bf16x2(vb[0][0], vb[0][1]); ob[1] = pack_bf16x2(vb[0][2], vb[0][3]);
+      ob[2] = pack_bf16x2(vb[1][0], vb[1][1]); ob[3] = pack_bf16x2(vb[1][2], vb[1][3]);
+      if (rotate) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {                  // t[j]: (cos, sin) of pairs 2 j and 2 j + 1
+          const float a0 = __uint_as_float(oa[j] << 16), a1 = __uint_as_float(oa[j] & 0xffff0000u);
+          const float b0 = __uint_as_float(ob[j] << 16), b1 = __uint_as_float(ob[j] & 0xffff0000u);
+          oa[j] = pack_bf16x2(a0 * t[j].x - b0 * t[j].y, a1 * t[j].z - b1 * t[j].w);
+          ob[j] = pack_bf16x2(b0 * t[j].x + a0 * t[j].y, b1 * t[j].z + a1 * t[j].w);
+        }
+      }
+      const bool inside = m < a.M && na < a.N;
+      const uint32_t o = (m * a.N + na) * 2u;
+      const uint4 outa = {oa[0], oa[1], oa[2], oa[3]}, outb = {ob[0], ob[1], ob[2], ob[3]};
+      if (TRAIL) {
+        QZO_STORE_OUT_ALWAYS(inside ? o : 0x80000000u, outa);
+        QZO_STORE_OUT_ALWAYS(inside ? o + half * 2u : 0x80000000u, outb);
+      } else if (inside) {
+        QZO_STORE_OUT((bf16_t*)a.y + (uint64_t)m * a.N + na, outa);
+        QZO_STORE_OUT((bf16_t*)a.y + (uint64_t)m * a.N + na + half, outb);
+      }
+    }
+    trail_stores = TRAIL ? 16 : 0;
   } else if (!CE) {
     float ssq = 0.0f;
     const bf16_t* bias = (const bf16_t*)a.bias;

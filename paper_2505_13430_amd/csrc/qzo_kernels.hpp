@@ -31,6 +31,9 @@ enum : uint32_t {
   EPI_RELU = 4u,
   EPI_SUMSQ = 8u,      // per-workgroup sum of bf16(y)^2 into partials
   EPI_SWIGLU = 16u,    // W is [gate rows | up rows] (N = 2F): y[M,F] = silu(gate) * up
+  EPI_ROPE = 32u,      // plain bf16 GEMM only: y is qkv [M, 3d] of heads of 64 or 128 features; the rotary embedding
+                       // is applied to the q and k thirds on the way out (rope, rope_S); with heads of 128 the rows
+                       // of W must be in ROW_ORDER_ROPE128 order
 };
 
 struct GemmArgs {
@@ -46,6 +49,8 @@ struct GemmArgs {
   float* skinny_ws;     // fp32 scratch of skinny_ws_floats(rows, N, K) floats: enables the few-token path (M <= 64)
   float* split_ws;      // fp32 scratch of tile_split_ws_floats(M, N, K) floats: enables split-K of the int4 tile kernel
   uint32_t ksplit, kt_per;   // set by the launcher: K slices and k-tiles per slice
+  const float* rope;    // EPI_ROPE: (cos, sin) of [rope_S positions][dh/2 pairs]; row m sits at position m % rope_S
+  uint32_t rope_S, rope_dh;
   uint32_t dual;        // both passes of a step stacked: x, y, resid hold 2 M rows; rows [0,M) use +eps_signed,
                         // [M,2M) -eps_signed (few-token path: M <= 32; tile path: see pass_stride)
   uint32_t pass_stride; // dual, tile path: the second pass starts at this row (a multiple of 256 >= M; x, y, resid
@@ -59,6 +64,10 @@ struct GemmArgs {
   uint32_t s_fp16;      // int4 formats: s holds fp16 instead of bf16
 };
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
+// Order of the rows of an expanded (bf16) weight matrix: natural; the fused-SwiGLU consumer's tile order;
+// the fused-RoPE consumer's order for heads of 128 features (within every 256 rows, so that a lane of the
+// GEMM holds feature i and feature i + 64 of a head).
+enum : int { ROW_ORDER_NATURAL = 0, ROW_ORDER_SWIGLU = 1, ROW_ORDER_ROPE128 = 2 };
 // Few-token path (M <= 64): weights streamed once, K split over workgroups, partial sums in ws.
 constexpr uint32_t SKINNY_MAX_M = 64;
 constexpr uint32_t STACK_TILE_MAX_M = 4096;  // tile kernel: the two passes share a launch up to this many tokens per pass
@@ -83,23 +92,23 @@ constexpr int PLAIN_GEMM_PIPE = 2;     // the route the models take: 3 % faster 
 // when the consumer fuses SwiGLU), for launch_bf16_gemm.
 hipError_t launch_expand_codebook(const void* codes, const void* cb, const void* c_fp16, uint32_t N,
                                   uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi,
-                                  float eps_signed, bool swiglu, void* out_bf16, hipStream_t st);
+                                  float eps_signed, int swiglu, void* out_bf16, hipStream_t st);
 // NormalFloat-4 blocks of 64: se_scratch receives the perturbed scales, fp32 [N, K/64].
 hipError_t launch_expand_nf4(const void* q, const void* s_bf16, uint32_t N, uint32_t K, uint32_t row_base,
-                             uint32_t seed_lo, uint32_t seed_hi, float eps_signed, bool swiglu,
+                             uint32_t seed_lo, uint32_t seed_hi, float eps_signed, int swiglu,
                              float* se_scratch, void* out_bf16, hipStream_t st);
 // int4 groups of 128 (zp: uint8 [N, K/128] or null = 8; g_idx: int32 [K] group of each column, or
 // null = k / 128): se_scratch fp32 [N, K/128].
 hipError_t launch_expand_int4(const void* q, const void* s_bf16, const void* zp, const int32_t* g_idx,
                               uint32_t N, uint32_t K, uint32_t row_base, uint32_t seed_lo, uint32_t seed_hi, float eps_signed,
-                              bool swiglu, float* se_scratch, void* out_bf16, hipStream_t st);
+                              int swiglu, float* se_scratch, void* out_bf16, hipStream_t st);
 // Inside a model the perturbed scales of every linear are written by one launch per pass (fp32, laid
 // out like the scale arena) and the expansions read them from there.
 hipError_t launch_perturbed_scales_all(const void* arena, const UpdPlan& plan, uint32_t seed_lo, uint32_t seed_hi,
                                        float eps_signed, float* se_all, hipStream_t st);
 hipError_t launch_expand_int4_from(const void* q, const float* se, const void* zp, const int32_t* g_idx,
-                                   uint32_t N, uint32_t K, bool swiglu, void* out_bf16, hipStream_t st);
-hipError_t launch_expand_nf4_from(const void* q, const float* se, uint32_t N, uint32_t K, bool swiglu,
+                                   uint32_t N, uint32_t K, int swiglu, void* out_bf16, hipStream_t st);
+hipError_t launch_expand_nf4_from(const void* q, const float* se, uint32_t N, uint32_t K, int swiglu,
                                   void* out_bf16, hipStream_t st);
 // Tokens per pass from which an int4 linear [N,K] is expanded first.  The expansion costs two short
 // launches (about 8 us) plus 2.5 bytes per weight at about 4.5 TB/s; the fused kernel needs about 13.6 %

@@ -959,11 +959,14 @@ def test_nf4_linear_matches_oracle(oracle, M, N, K):
         qb.qzo_nf4_gemm(_dev(x, torch.bfloat16), _dev(qp), _dev(s, torch.bfloat16), 11, 31, 1e-3, 1, y, scratch[:256])
 
 
-@pytest.mark.parametrize("name", ["many_llama", "many_opt+zp"])
+@pytest.mark.parametrize("name", ["many_llama", "many_opt+zp", "long_llama", "long_llama+zp"])
 def test_int4_expand_then_multiply_equals_the_fused_path(oracle, name):
     """Both routes form the same bf16 weights (one rounding of scale x integer) and accumulate each
     output over k in the same order, so losses and hidden states agree bit for bit.  (d_ffn = 256 keeps
-    every K at 256, too short for the fused kernel's split-K, which would change the order.)"""
+    every K at 256, too short for the fused kernel's split-K, which would change the order.)
+    On the expanded route the rotary embedding is applied by the qkv GEMM's epilogue (heads of 64 in
+    many_llama, heads of 128 with the permuted weight rows in long_llama), on the fused route by its own
+    kernel: the same arithmetic on the same bf16 values, so this equality covers it too."""
     base, asym = _case(name)
     shape = dict(base, d_ffn=256)
     om, dm = _models(oracle, shape, 1234, 4.0, **_variant_args(asym))
