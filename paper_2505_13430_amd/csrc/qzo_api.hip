@@ -405,10 +405,15 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       if (c.quant == 3) {
         // NormalFloat-4: table lookup and scaling once per weight, then a plain bf16 GEMM
         const bool split = w.split && tile_ksplit(g.M, g.N, g.K, nullptr) > 1;
+        int order = ((epi & EPI_SWIGLU) && !split) ? ROW_ORDER_SWIGLU : ROW_ORDER_NATURAL;
+        if (epi == EPI_ROPE && !split && (dh == 64 || (dh == 128 && g.N % 256 == 0))) {   // as for int4 below
+          if (dh == 128) order = ROW_ORDER_ROPE128;
+          g.epi = EPI_ROPE; g.rope = w.rope; g.rope_S = seq; g.rope_dh = dh;
+          rope_fused = true;
+        }
         {
           ProfScope pe(PK_EXPAND, 2.5 * (double)g.N * g.K, st);
-          hipError_t e = launch_expand_nf4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.N, g.K,
-                                                (epi & EPI_SWIGLU) != 0 && !split, w.wexp, st);
+          hipError_t e = launch_expand_nf4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.N, g.K, order, w.wexp, st);
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
