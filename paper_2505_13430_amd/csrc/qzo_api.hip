@@ -348,13 +348,16 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   const double attn_flops = 2.0 * batch * H * (double)seq * seq * dh;   // causal: half of 4 B H S^2 dh
   const double Mreal = (double)n_pass * M1;                             // rows that count as work
   // attention over both passes: one launch when they are contiguous, one per pass otherwise
-  auto attention = [&]() {
+  // short sequences: no RoPE launch, the attention kernel rotates q and k itself
+  const bool rope_in_attention = llama && seq <= ATTENTION_ROPE_MAX_S;
+  auto attention = [&](bool rotated) {
     ProfScope ps(PK_ATTN, attn_flops, st);
-    if (!padded) return launch_attention(w.qkv, batch, seq, H, dh, w.att, st);
-    hipError_t e = launch_attention(w.qkv, batch1, seq, H, dh, w.att, st);
+    const float* tb = (llama && !rotated) ? w.rope : nullptr;
+    if (!padded) return launch_attention(w.qkv, batch, seq, H, dh, w.att, tb, st);
+    hipError_t e = launch_attention(w.qkv, batch1, seq, H, dh, w.att, tb, st);
     if (e != hipSuccess) return e;
     return launch_attention((const unsigned char*)w.qkv + (size_t)P * 3 * d * 2, batch1, seq, H, dh,
-                            (unsigned char*)w.att + (size_t)P * d * 2, st);
+                            (unsigned char*)w.att + (size_t)P * d * 2, tb, st);
   };
   auto other = [&](hipError_t e) { return e; };
   (void)other;
@@ -474,8 +477,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       // attn_norm, codes/cb qkv, codes/cb o, ffn_norm, codes/cb gate+up, codes/cb down
       QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(cgemm(0, w.a, T[1].ptr_dev, T[2].ptr_dev, nullptr, w.qkv, 0));
-      QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
-      QZO_HIP(attention());
+      if (!rope_in_attention) QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
+      QZO_HIP(attention(!rope_in_attention));
       QZO_HIP(cgemm(1, w.att, T[3].ptr_dev, T[4].ptr_dev, w.h, w.h, EPI_RESIDUAL));
       QZO_HIP(launch_rmsnorm(w.h, T[5].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(cgemm(2, w.a, T[6].ptr_dev, T[7].ptr_dev, nullptr, w.act, EPI_SWIGLU));
@@ -485,8 +488,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       QZO_HIP(launch_rmsnorm(w.h, ti(0), M, d, c.norm_eps, w.a, st));
       rope_fused = false;
       QZO_HIP(gemm(0, w.a, nullptr, nullptr, w.qkv, EPI_ROPE));
-      if (!rope_fused) QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
-      QZO_HIP(attention());
+      if (!rope_fused && !rope_in_attention) QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
+      QZO_HIP(attention(rope_fused || !rope_in_attention));
       QZO_HIP(gemm(1, w.att, nullptr, w.h, w.h, EPI_RESIDUAL));
       QZO_HIP(launch_rmsnorm(w.h, ti(3), M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(2, w.a, nullptr, nullptr, w.act, EPI_SWIGLU));
@@ -495,7 +498,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       // ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, wfc1, bfc1, wfc2, bfc2 (symmetric-table positions)
       QZO_HIP(launch_layernorm(w.h, ti(0), ti(1), M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(0, w.a, ti(3), nullptr, w.qkv, EPI_BIAS));
-      QZO_HIP(attention());
+      QZO_HIP(attention(true));
       QZO_HIP(gemm(1, w.att, ti(5), w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
       QZO_HIP(launch_layernorm(w.h, ti(6), ti(7), M, d, c.norm_eps, w.a, st));
       QZO_HIP(gemm(2, w.a, ti(9), nullptr, w.ff, EPI_BIAS | EPI_RELU));

@@ -25,9 +25,27 @@ namespace qzo {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-template <int DH>
+// ROPE: q and k arrive without the rotary embedding and get it here: the queries once in
+// registers, the keys of a tile on their way from registers to the LDS (the table of (cos, sin)
+// per position and pair is read when a tile is stored, not ahead: the variant is for short
+// sequences, where the separate RoPE launch costs more than these few exposed latencies).
+// A lane rounds nothing extra: the inputs are the bf16 values a separate pass would read, the
+// rotation is the same fp32 arithmetic, rounded once to bf16.
+__device__ __forceinline__ void rope_pair8(uint32_t (&a)[4], uint32_t (&b)[4], const float4* tb) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float4 t = tb[j];                          // (cos, sin) of pairs 2 j and 2 j + 1
+    const float a0 = __uint_as_float(a[j] << 16), a1 = __uint_as_float(a[j] & 0xffff0000u);
+    const float b0 = __uint_as_float(b[j] << 16), b1 = __uint_as_float(b[j] & 0xffff0000u);
+    a[j] = pack_bf16x2(a0 * t.x - b0 * t.y, a1 * t.z - b1 * t.w);
+    b[j] = pack_bf16x2(b0 * t.x + a0 * t.y, b1 * t.z + a1 * t.w);
+  }
+}
+
+template <int DH, bool ROPE>
 __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restrict__ qkv, uint32_t S,
-                                                           uint32_t n_heads, bf16_t* __restrict__ out) {
+                                                           uint32_t n_heads, bf16_t* __restrict__ out,
+                                                           const float2* __restrict__ rope) {
   constexpr int KB = 64;             // keys per tile
   constexpr int KT = DH / 16;        // k-steps of the score MFMA
   constexpr int DT = DH / 32;        // 32-wide slices of the head for the PV MFMA
@@ -52,6 +70,16 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
 #pragma unroll
   for (int ks = 0; ks < KT; ++ks)
     qf[ks] = *reinterpret_cast<const bf16x8*>(base + (uint64_t)qc * ld + ks * 16 + lhalf * 8);
+  if (ROPE) {
+    // k-step ks < KT/2 holds features ks*16 + 8 lhalf .. + 7 of the head, k-step ks + KT/2 the same + DH/2
+#pragma unroll
+    for (int ks = 0; ks < KT / 2; ++ks) {
+      union { bf16x8 v; uint32_t u[4]; } qa, qb;
+      qa.v = qf[ks]; qb.v = qf[ks + KT / 2];
+      rope_pair8(qa.u, qb.u, reinterpret_cast<const float4*>(rope + (uint64_t)qc * (DH / 2) + ks * 16 + lhalf * 8));
+      qf[ks] = qa.v; qf[ks + KT / 2] = qb.v;
+    }
+  }
 
   floatx16 o[DT];
 #pragma unroll
@@ -73,10 +101,14 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   const uint32_t v_ch = wave * 4 + (lane >> 4), v_kq = lane & 15u;
   const bool v_on = v_ch < (uint32_t)CH;
   // (macros, not lambdas: arrays captured by reference would be kept in scratch memory)
+  // K chunk i of this thread: (row, chunk) = (c / CH, c % CH) with c = t + 256 i; with ROPE a thread
+  // takes pairs of chunks (ch, ch + CH/2) of one row, which hold the two halves of 8 rotation pairs
+#define QZO_ATT_KROW(I) (ROPE ? (t + 256u * ((I) >> 1)) / (CH / 2) : (t + 256u * (I)) / CH)
+#define QZO_ATT_KCH(I) (ROPE ? (t + 256u * ((I) >> 1)) % (CH / 2) + ((I) & 1) * (CH / 2) : (t + 256u * (I)) % CH)
 #define QZO_ATT_GLOAD(KB_)                                                                   \
   do {                                                                                       \
     _Pragma("unroll") for (int i = 0; i < NK; ++i) {                                         \
-      const uint32_t c = t + 256u * i, row = c / CH, ch = c % CH;                            \
+      const uint32_t row = QZO_ATT_KROW(i), ch = QZO_ATT_KCH(i);                             \
       const uint32_t key = min((KB_) * KB + row, S - 1);                                     \
       kreg[i] = *reinterpret_cast<const u32x4*>(base + (uint64_t)key * ld + d + ch * 8);     \
     }                                                                                        \
@@ -96,10 +128,21 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     o_.y = __builtin_amdgcn_perm(vreg[3][(J) >> 1], vreg[2][(J) >> 1], SEL);                 \
     *reinterpret_cast<uint2*>(Vt2[BUF] + (v_ch * 8 + (J)) * VT_STRIDE + v_pos) = o_;         \
   } while (0)
-#define QZO_ATT_LSTORE(BUF)                                                                  \
+#define QZO_ATT_LSTORE(BUF, KB_)                                                             \
   do {                                                                                       \
+    if (ROPE) {                                                                              \
+      _Pragma("unroll") for (int p = 0; p < NK / 2; ++p) {                                   \
+        const uint32_t row = QZO_ATT_KROW(2 * p), ch = QZO_ATT_KCH(2 * p);                   \
+        const uint32_t key = min((KB_) * KB + row, S - 1);                                   \
+        uint32_t ka_[4] = {kreg[2 * p].x, kreg[2 * p].y, kreg[2 * p].z, kreg[2 * p].w};      \
+        uint32_t kb_[4] = {kreg[2 * p + 1].x, kreg[2 * p + 1].y, kreg[2 * p + 1].z, kreg[2 * p + 1].w}; \
+        rope_pair8(ka_, kb_, reinterpret_cast<const float4*>(rope + (uint64_t)key * (DH / 2) + ch * 8)); \
+        kreg[2 * p] = u32x4{ka_[0], ka_[1], ka_[2], ka_[3]};                                 \
+        kreg[2 * p + 1] = u32x4{kb_[0], kb_[1], kb_[2], kb_[3]};                             \
+      }                                                                                      \
+    }                                                                                        \
     _Pragma("unroll") for (int i = 0; i < NK; ++i) {                                         \
-      const uint32_t c = t + 256u * i, row = c / CH, ch = c % CH;                            \
+      const uint32_t row = QZO_ATT_KROW(i), ch = QZO_ATT_KCH(i);                             \
       *reinterpret_cast<u32x4*>(Ks2[BUF] + row * DH + ((ch ^ swz(row)) * 8)) = kreg[i];      \
     }                                                                                        \
     if (v_on) { /* features 2j take the low halves of dword j, 2j+1 the high halves */       \
@@ -112,14 +155,14 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   // Tile kb is computed from LDS buffer kb & 1 while tile kb+1 goes from registers to the
   // other buffer and tile kb+2 is requested from memory: one barrier per tile.
   QZO_ATT_GLOAD(0u);
-  QZO_ATT_LSTORE(0);
+  QZO_ATT_LSTORE(0, 0u);
   if (nkb > 1) QZO_ATT_GLOAD(1u);
   __syncthreads();
 
   for (uint32_t kb = 0; kb < nkb; ++kb) {
     if (kb > 0) __syncthreads();                // tile kb is complete, tile kb-1 has been read
     if (kb + 1 < nkb) {
-      if (kb & 1u) QZO_ATT_LSTORE(0); else QZO_ATT_LSTORE(1);
+      if (kb & 1u) QZO_ATT_LSTORE(0, kb + 1); else QZO_ATT_LSTORE(1, kb + 1);
       if (kb + 2 < nkb) QZO_ATT_GLOAD(kb + 2);
     }
     const bf16_t* Ks = Ks2[kb & 1u];
@@ -235,17 +278,25 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   }
 }
 
+#undef QZO_ATT_KROW
+#undef QZO_ATT_KCH
 #undef QZO_ATT_GLOAD
 #undef QZO_ATT_LSTORE
 #undef QZO_ATT_VROW
 
+// rope (nullable): (cos, sin) of [S positions][dh/2 pairs]; with it q and k are rotated on the fly.
 hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_heads,
-                            uint32_t dh, void* out, hipStream_t st) {
+                            uint32_t dh, void* out, const float* rope, hipStream_t st) {
   dim3 grid((S + 127) / 128, n_heads, B);
-  if (dh == 128)
-    attention_kernel<128><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out);
+  const float2* tb = (const float2*)rope;
+  if (dh == 128 && rope)
+    attention_kernel<128, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+  else if (dh == 128)
+    attention_kernel<128, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+  else if (dh == 64 && rope)
+    attention_kernel<64, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
   else if (dh == 64)
-    attention_kernel<64><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out);
+    attention_kernel<64, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -172,8 +172,10 @@ hipError_t launch_rope_table(float* table, uint32_t max_seq, uint32_t dh, float 
                              hipStream_t st);
 hipError_t launch_rope(void* qkv, const float* table, uint32_t M, uint32_t S, uint32_t pass_stride, uint32_t d,
                        uint32_t n_heads, hipStream_t st);
+// rope (nullable): the (cos, sin) table; with it the kernel rotates q and k itself (qkv holds them unrotated).
+constexpr uint32_t ATTENTION_ROPE_MAX_S = 256;   // up to this sequence length the models let it do so
 hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_heads,
-                            uint32_t dh, void* out, hipStream_t st);
+                            uint32_t dh, void* out, const float* rope, hipStream_t st);
 hipError_t launch_spsa_clip(const float* losses, float eps, float clip, qzo_step_result* res,
                             hipStream_t st);
 hipError_t launch_scale_update(void* arena, const UpdPlan& plan, uint32_t seed_lo,
