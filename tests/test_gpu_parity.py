@@ -433,7 +433,7 @@ def test_stacked_passes_equal_separate_passes(oracle, name):
 
 
 @pytest.mark.parametrize("name,batch,seq", [("tiny", 4, 64), ("long_opt+zp", 3, 256), ("long_ragged", 2, 300),
-                                            ("tiny_opt", 3, 40)])
+                                            ("tiny_opt", 3, 40), ("tiny+zp", 3, 40)])
 def test_stacked_tile_passes_match_separate_passes(oracle, name, batch, seq):
     """Beyond the few-token kernel's range qzo_step runs both perturbed passes as one stacked forward
     through the tile kernel, the second pass's token tiles with -eps; the second pass starts on a
