@@ -630,6 +630,31 @@ def test_real_width_one_layer_expanded_route(oracle, name, asym):
     dm.close()
 
 
+@pytest.mark.parametrize("name,asym", [("llama-2-7b", False), ("opt-1.3b", True)])
+def test_real_width_one_layer_stacked_tile_step(oracle, name, asym):
+    """The step of the paper's batch regime at real widths: 272 tokens per pass on the default route,
+    i.e. both passes in one forward through the fused tile kernel (the second pass from row 512 on, 240
+    padding rows), K split of the 4096- / 2048-wide projections, RoPE inside the attention kernel.
+    Losses, and the scales after the update, against the oracle."""
+    shape = dict(synth.SHAPES[name], n_layers=1, batch=2, seq=136, max_seq=136)
+    if shape["arch"] == "llama":
+        shape["vocab"] = 1000
+    om, dm = _models(oracle, shape, 77, asym=asym)
+    tok = synth.tokens(shape, 78)
+    eta = 1e-5 if name == "opt-1.3b" else 1e-7
+    ref = oracle.qzo_step(om, tok, seed=3, eps=1e-3, eta=eta, Cthr=100.0)
+    res = qb.read_step_result(dm.step(_dev(tok), 3, 1e-3, eta, 100.0))
+    assert res["status"] == 0
+    for k in ("loss_plus", "loss_minus"):
+        assert abs(res[k] - ref[k]) <= 2e-2 * abs(ref[k]), (k, res[k], ref[k])
+    assert res["loss_plus"] != res["loss_minus"]
+    got = dm.scales.float().cpu().numpy()
+    assert (np.abs(got - ref["scales"]) <= 2e-2 * np.abs(ref["scales"]) + 1e-7).all()
+    assert np.array_equal(_bits(got), _bits(oracle.update_scales(om, 3, eta, res["d_clipped"])))
+    print(name, "loss", res["loss_plus"], ref["loss_plus"], "d", res["d"], ref["d"])
+    dm.close()
+
+
 def test_failing_calls_enqueue_nothing(oracle):
     """Every error that the library finds itself (anything but a failing HIP call) is found before
     the first launch: outputs, workspace and scales are untouched afterwards."""
