@@ -455,15 +455,22 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.resid = resid; g.y = y;
       g.M = M; g.N = m->lin[li].N; g.K = m->lin[li].K;
       g.row_base = l * m->rows_per_layer + m->lin[li].row_base;
-      g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed; g.epi = epi;
+      g.seed_lo = seed_lo; g.seed_hi = seed_hi; g.eps_signed = eps_signed;
+      g.epi = epi & ~EPI_ROPE;                // a request, served by the plain GEMM below when it does not split K
       if (w.wexp) {
         // many tokens: reconstruct the perturbed matrix once, then a plain bf16 GEMM
         // (rows in natural order when the GEMM will split K: its reduction applies SwiGLU)
         const bool split = w.split && tile_ksplit(g.M, g.N, g.K, nullptr) > 1;
+        int order = ((epi & EPI_SWIGLU) && !split) ? ROW_ORDER_SWIGLU : ROW_ORDER_NATURAL;
+        if (epi == EPI_ROPE && !split && (dh == 64 || (dh == 128 && g.N % 256 == 0))) {   // as for int4
+          if (dh == 128) order = ROW_ORDER_ROPE128;
+          g.epi = EPI_ROPE; g.rope = w.rope; g.rope_S = seq; g.rope_dh = dh;
+          rope_fused = true;
+        }
         {
           ProfScope pe(PK_EXPAND, 2.25 * (double)g.N * g.K, st);
           hipError_t e = launch_expand_codebook(codes, cb, g.s, g.N, g.K, g.row_base, seed_lo, seed_hi,
-                                                eps_signed, (epi & EPI_SWIGLU) != 0 && !split, w.wexp, st);
+                                                eps_signed, order, w.wexp, st);
           if (e != hipSuccess) return e;
         }
         g.w = w.wexp; g.cb = nullptr; g.s = nullptr; g.split_ws = split ? w.split : nullptr;
@@ -476,9 +483,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
     if (llama && c.quant == 1) {
       // attn_norm, codes/cb qkv, codes/cb o, ffn_norm, codes/cb gate+up, codes/cb down
       QZO_HIP(launch_rmsnorm(w.h, T[0].ptr_dev, M, d, c.norm_eps, w.a, st));
-      QZO_HIP(cgemm(0, w.a, T[1].ptr_dev, T[2].ptr_dev, nullptr, w.qkv, 0));
-      if (!rope_in_attention) QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
-      QZO_HIP(attention(!rope_in_attention));
+      rope_fused = false;
+      QZO_HIP(cgemm(0, w.a, T[1].ptr_dev, T[2].ptr_dev, nullptr, w.qkv, EPI_ROPE));
+      if (!rope_fused && !rope_in_attention) QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
+      QZO_HIP(attention(rope_fused || !rope_in_attention));
       QZO_HIP(cgemm(1, w.att, T[3].ptr_dev, T[4].ptr_dev, w.h, w.h, EPI_RESIDUAL));
       QZO_HIP(launch_rmsnorm(w.h, T[5].ptr_dev, M, d, c.norm_eps, w.a, st));
       QZO_HIP(cgemm(2, w.a, T[6].ptr_dev, T[7].ptr_dev, nullptr, w.act, EPI_SWIGLU));
