@@ -116,10 +116,29 @@ __global__ __launch_bounds__(256) void perturbed_scales_all_kernel(const bf16_t*
   scale_normals8(seed_lo, seed_hi, 0u, layer * plan.rows_per_layer + sg.row_base + row, gb, z);
   const uint64_t base = (uint64_t)layer * plan.layer_stride + sg.off + (uint64_t)row * sg.G + gb * 8u;
   const uint32_t nv = min(8u, sg.G - gb * 8u);
+  const bool fp16 = plan.fp16 != 0;
+  if (nv == 8u && (sg.G & 1u) == 0u) {
+    // a whole counter of a row that starts on a dword: one 16-byte load, two 16-byte stores
+    // (4-byte aligned accesses: rows of 86 or 108 groups start on a dword only)
+    struct a4_u32x4 { uint32_t x, y, z, w; } __attribute__((packed, aligned(4)));
+    struct a4_f32x4 { float x, y, z, w; } __attribute__((packed, aligned(4)));
+    const a4_u32x4 v = *reinterpret_cast<const a4_u32x4*>(arena + base);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    float o[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      o[2 * j] = __builtin_fmaf(eps_signed, z[2 * j], scale_to_f32(w[j] & 0xffffu, fp16));
+      o[2 * j + 1] = __builtin_fmaf(eps_signed, z[2 * j + 1], scale_to_f32(w[j] >> 16, fp16));
+    }
+    a4_f32x4* dst = reinterpret_cast<a4_f32x4*>(se + base);
+    dst[0] = a4_f32x4{o[0], o[1], o[2], o[3]};
+    dst[1] = a4_f32x4{o[4], o[5], o[6], o[7]};
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < 8; ++j)
     if ((uint32_t)j < nv)
-      se[base + j] = __builtin_fmaf(eps_signed, z[j], scale_to_f32(arena[base + j], plan.fp16 != 0));
+      se[base + j] = __builtin_fmaf(eps_signed, z[j], scale_to_f32(arena[base + j], fp16));
 }
 
 // bf16 [N,K] from the indices and the perturbed scales: a thread turns one dword (eight
