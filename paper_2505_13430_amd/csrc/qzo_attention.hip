@@ -57,8 +57,17 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   __shared__ __attribute__((aligned(16))) bf16_t Vt2[2][DH * VT_STRIDE];
 
   const uint32_t d = n_heads * DH, ld = 3 * d;
-  // heavy query blocks (late positions, many keys) are dispatched first
-  const uint32_t b = blockIdx.z, h = blockIdx.y, q0 = (gridDim.x - 1 - blockIdx.x) * 128;
+  // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2: the
+  // query blocks of one (batch, head) are given to workgroups of one XCD, so that its K and V are
+  // fetched into one L2 only; within that, heavy query blocks (late positions, many keys) come first.
+  uint32_t bx = blockIdx.x, hb = blockIdx.y + gridDim.y * blockIdx.z;
+  const uint32_t nhb = gridDim.y * gridDim.z;
+  if ((nhb & 7u) == 0u) {
+    const uint32_t L = blockIdx.x + gridDim.x * hb, slot = L >> 3;
+    hb = (L & 7u) + 8u * (slot / gridDim.x);
+    bx = slot % gridDim.x;
+  }
+  const uint32_t b = hb / gridDim.y, h = hb % gridDim.y, q0 = (gridDim.x - 1 - bx) * 128;
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
   const bf16_t* base = qkv + (uint64_t)b * S * ld + h * DH;
