@@ -1015,6 +1015,58 @@ def test_int4_expand_then_multiply_equals_the_fused_path(oracle, name):
     dm.close()
 
 
+def test_full_size_token_count_sampled_sequence_matches_oracle(oracle):
+    """The benchmark's launch configuration (16 x 512 tokens, the default route: expansion, plain GEMM at
+    32 token tiles, RoPE in the qkv epilogue at positions up to 511, attention over 8 key tiles) through
+    one decoder layer at Llama-2-7B widths, checked on a sample the oracle can afford: a decoder treats
+    the sequences of a batch independently, so the oracle runs sequence 11 alone and its final hidden
+    states are compared with rows 11*512 .. 12*512-1 of the batch's."""
+    shape = dict(synth.SHAPES["llama-2-7b"], n_layers=1, vocab=1000)
+    om, dm = _models(oracle, shape, 77)
+    tok = synth.tokens(shape, 78)
+    B, S = tok.shape
+    assert (B, S) == (16, 512)
+    hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    qb.qzo_debug_forward(dm.handle, _dev(tok), 3, 1e-3, 1, dm.workspace(B, S), loss, hid)
+    b = 11
+    se = oracle.perturbed_scales(om, 3, np.float32(1e-3))
+    _, ref_hid = oracle.forward_loss(om, se, tok[b:b + 1], act_bf16=True, want_hidden=True)
+    _, exact_hid = oracle.forward_loss(om, se, tok[b:b + 1], act_bf16=False, want_hidden=True)
+    got = hid[b * S:(b + 1) * S].float().cpu().numpy().astype(np.float64)
+    rms = math.sqrt((ref_hid ** 2).mean())
+    err = np.abs(got - ref_hid)
+    floor_rms = math.sqrt(((exact_hid - ref_hid) ** 2).mean())
+    print("hidden rms err", math.sqrt((err ** 2).mean()) / rms, "floor", floor_rms / rms)
+    assert math.isfinite(loss.item())
+    assert math.sqrt((err ** 2).mean()) <= 2 * floor_rms + 2e-3 * rms
+    assert err.max() <= 2 * np.abs(exact_hid - ref_hid).max() + 2e-2 * rms
+    dm.close()
+
+
+def test_full_size_token_count_one_layer_routes_agree_bit_for_bit():
+    """The benchmark's token count (16 x 512) through one decoder layer at Llama-2-7B widths, once on the
+    route the benchmark times (perturbed scales of the arena, expanded bf16 weights, plain GEMM with the
+    rotary embedding in the qkv epilogue: 6 / 2 / 10.75 / 2 rounds of output tiles per CU) and once on
+    the fused dequantizing GEMM with the separate RoPE kernel: the same bf16 weights, the same order of
+    the sums, so loss and final hidden states agree bit for bit.  (The fused route is the one that the
+    smaller cases compare with the oracle element by element.)"""
+    shape = dict(synth.SHAPES["llama-2-7b"], n_layers=1, vocab=2000)
+    dm = DeviceModel.synthetic(shape, seed=5, device=DEV)
+    B, S = shape["batch"], shape["seq"]
+    tok = _dev(synth.tokens(shape, 6))
+    outs = []
+    for mode in (2, 1):
+        dm.set_int4_path(mode)
+        hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        qb.qzo_debug_forward(dm.handle, tok, 9, 1e-3, -1, dm.workspace(B, S), loss, hid)
+        outs.append((float(loss.item()), hid))
+    assert math.isfinite(outs[0][0]) and outs[0][0] == outs[1][0]
+    assert torch.equal(outs[0][1], outs[1][1])
+    dm.close()
+
+
 @pytest.mark.parametrize("N,K,row_base,with_zp", [(24, 384, 0, False), (40, 1024 + 128, 77, True), (8, 128, 5, False),
                                                   (16, 11008, 3, True)])
 def test_int4_expanded_matrix_bit_exact(oracle, N, K, row_base, with_zp):
