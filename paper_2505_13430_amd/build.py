@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqzo.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["qzo_elementwise.hip", "qzo_gemm.hip", "qzo_skinny.hip", "qzo_expand.hip", "qzo_attention.hip", "qzo_api.hip"]
+SOURCES = ["qzo_elementwise.hip", "qzo_gemm.hip", "qzo_gemm_wide.hip", "qzo_skinny.hip", "qzo_expand.hip", "qzo_attention.hip", "qzo_api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -ffp-contract=off: the noise recipe is defined operation by operation; fused
 # steps are written as explicit fma.  packed-fp32 code generation is disabled.

@@ -87,6 +87,9 @@ hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st);
 // pipe: 0 / 1 = operand tiles staged through registers (compiler's / explicit issue order),
 // 2 = loaded from memory straight into the LDS.
 hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st);
+// The plain bf16 GEMM with one wavefront per SIMD and deferred output stores (no split-K): what
+// launch_bf16_gemm(pipe = 2) runs when the output tiles fill the chip.
+hipError_t launch_bf16_gemm_wide(const GemmArgs& a, hipStream_t st);
 constexpr int PLAIN_GEMM_PIPE = 2;     // the route the models take: 3 % faster than 1 on a full step
 // One linear's perturbed weights written out as bf16 [N,K] (rows in the GEMM's tile order
 // when the consumer fuses SwiGLU), for launch_bf16_gemm.

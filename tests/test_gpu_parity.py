@@ -947,6 +947,29 @@ def test_plain_bf16_gemm_matches_oracle(oracle, M, N, K, pipe):
     assert err.max() <= 1e-2 * np.abs(ref).max()
 
 
+def test_plain_bf16_gemm_deferred_stores_ragged_edges(oracle):
+    """More output tiles than compute units and a k-loop of 16 k-tiles: the kernel of the expanded route keeps
+    the packed output of a workgroup's first tile in registers and stores it during its second tile's k-loop.
+    Ragged on both sides (rows past M fall outside the buffer, columns past N are masked per piece).  Checked
+    against the oracle, and bit for bit against the register-staged kernel, which sums in the same order."""
+    M, N, K = 4400, 3848, 1024
+    rng = np.random.default_rng(5)
+    x = synth.bf16_exact(rng.standard_normal((M, K), dtype=np.float32))
+    w = synth.bf16_exact(rng.standard_normal((N, K), dtype=np.float32) * np.float32(0.05))
+    xd, wd = _dev(x, torch.bfloat16), _dev(w, torch.bfloat16)
+    guard = 4096
+    buf = torch.full((M * N + guard,), 7.0, dtype=torch.bfloat16, device=DEV)
+    y = buf[:M * N].view(M, N)
+    qb.qzo_debug_bf16_gemm(xd, wd, y, 2)
+    y1 = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    qb.qzo_debug_bf16_gemm(xd, wd, y1, 1)
+    assert torch.equal(y, y1)
+    assert bool((buf[M * N:] == 7.0).all())                      # nothing written past the last row
+    ref = oracle.linear(x.astype(np.float64), w)
+    err = np.abs(y.float().cpu().numpy() - ref)
+    assert (err <= 2e-2 * np.abs(ref) + 2e-2 * math.sqrt(K) * 0.05).all()
+
+
 # ------------------------------------- NormalFloat-4 blocks (the quantizer of Sec. 4.3) ----
 @pytest.mark.parametrize("N,K,row_base", [(24, 384, 0), (264, 1280, 77), (8, 128, 5), (40, 11008, 3)])
 def test_nf4_perturbed_scales_and_matrix_bit_exact(oracle, N, K, row_base):
