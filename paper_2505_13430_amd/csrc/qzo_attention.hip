@@ -10,13 +10,11 @@
 // rescale.
 //
 // Keys are processed 64 at a time.  The K tile sits row-major in LDS (16-byte
-// chunks XOR-swizzled by row); the V tile is stored transposed (head dimension x
-// keys) with the keys of each group of 16 permuted so that the eight keys a lane
-// needs for one MFMA k-step are contiguous: one 16-byte read per operand.  A
-// thread transposes a 4-key x 8-feature block in registers (byte permutes) and
-// writes eight 8-byte rows.  Two LDS buffers: tile kb is computed from one while tile
-// kb+1 goes from registers to the other and tile kb+2 is requested from memory, so
-// there is one barrier per tile and the global loads have a whole tile to land.
+// chunks XOR-swizzled by row).  The V tile sits row-major as well (keys x head dimension, 32-byte segments
+// XOR-swizzled by row): the second MFMA needs, per lane, eight keys of one feature, and gets them from two
+// transposing LDS reads (ds_read_b64_tr_b16: within 16 lanes, lane j supplies four consecutive features of
+// key j/4, lane i receives feature i of keys 0..3), so V is loaded from memory in whole rows and lands in
+// the LDS as it is.  Two LDS buffers, one barrier per tile.
 #include "qzo_device.hpp"
 #include "qzo_kernels.hpp"
 
@@ -51,10 +49,14 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   constexpr int DT = DH / 32;        // 32-wide slices of the head for the PV MFMA
   constexpr int CH = DH / 8;         // 16-byte chunks per K row
   constexpr int NK = KB * CH / 256;  // K chunks per thread and tile (4 or 2)
-  constexpr int VT_STRIDE = KB + 8;  // padded keys per V^T row (bf16 units): 144 B rows
   constexpr uint32_t SWZ = CH - 1;   // chunk swizzle mask: DH 128 -> row & 15, DH 64 -> (row >> 1) & 7
-  __shared__ __attribute__((aligned(16))) bf16_t Ks2[2][KB * DH];
-  __shared__ __attribute__((aligned(16))) bf16_t Vt2[2][DH * VT_STRIDE];
+  // Without ROPE both tiles go from memory straight into the LDS (buffer loads with the lds modifier: a
+  // wavefront's load fills 1 KB in lane order, so both swizzles are applied on the memory side); with ROPE
+  // the keys pass through registers to be rotated and V takes the same way.
+  constexpr bool DTL = !ROPE;
+  constexpr int NI = KB * DH * 2 / 4096;   // direct loads per wavefront, tile and operand (4 or 2)
+  __shared__ __attribute__((aligned(1024))) bf16_t Ks2[2][KB * DH];
+  __shared__ __attribute__((aligned(1024))) bf16_t Vs2[2][KB * DH];
 
   const uint32_t d = n_heads * DH, ld = 3 * d;
   // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2: the
@@ -74,6 +76,9 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   const uint32_t qq = q0 + wave * 32 + lrow;            // this lane's query
   const uint32_t qc = min(qq, S - 1);
   auto swz = [](uint32_t row) { return DH == 128 ? (row & SWZ) : ((row >> 1) & SWZ); };
+  // V rows are unpadded; their 32-byte segments are XOR-swizzled so that the 4 rows x 2 segments that half a
+  // wavefront touches in one transposing read fall into 8 different 32-byte bank groups
+  auto vsw = [](uint32_t row) { return DH == 128 ? 2u * (row & 3u) : 2u * ((row >> 1) & 1u); };
 
   bf16x8 qf[KT];
 #pragma unroll
@@ -102,13 +107,9 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   const uint32_t nkb = q_hi / KB + 1;
   const uint32_t wave_q_hi = q0 + wave * 32 + 31;
 
-  // staging registers: K chunks (row kc / CH, chunk kc % CH) and one 4-key x 8-feature V block
+  // staging registers: K and V chunks (row c / CH, chunk c % CH of the tile, c = t + 256 i)
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  u32x4 kreg[NK], vreg[4];
-  // 16 consecutive lanes take the 16 key quads of one feature chunk: their 8-byte
-  // stores fill 128 contiguous bytes of one V^T row
-  const uint32_t v_ch = wave * 4 + (lane >> 4), v_kq = lane & 15u;
-  const bool v_on = v_ch < (uint32_t)CH;
+  u32x4 kreg[NK], vreg[NK];
   // (macros, not lambdas: arrays captured by reference would be kept in scratch memory)
   // K chunk i of this thread: (row, chunk) = (c / CH, c % CH) with c = t + 256 i; with ROPE a thread
   // takes pairs of chunks (ch, ch + CH/2) of one row, which hold the two halves of 8 rotation pairs
@@ -121,21 +122,11 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
       const uint32_t key = min((KB_) * KB + row, S - 1);                                     \
       kreg[i] = *reinterpret_cast<const u32x4*>(base + (uint64_t)key * ld + d + ch * 8);     \
     }                                                                                        \
-    if (v_on) {                                                                              \
-      _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                        \
-        const uint32_t key = min((KB_) * KB + v_kq * 4 + r, S - 1);                          \
-        vreg[r] = *reinterpret_cast<const u32x4*>(base + (uint64_t)key * ld + 2 * d + v_ch * 8); \
-      }                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < NK; ++i) {                                         \
+      const uint32_t c = t + 256u * i;                                                       \
+      const uint32_t key = min((KB_) * KB + c / CH, S - 1);                                  \
+      vreg[i] = *reinterpret_cast<const u32x4*>(base + (uint64_t)key * ld + 2 * d + (c % CH) * 8); \
     }                                                                                        \
-  } while (0)
-  // key 8a + 4h + c of a group of 16 goes to position 8h + 4a + c of the V^T row
-  const uint32_t v_pos = (v_kq >> 2) * 16 + (v_kq & 1u) * 8 + ((v_kq & 3u) >> 1) * 4;
-#define QZO_ATT_VROW(J, SEL, BUF)                                                            \
-  do {                                                                                       \
-    uint2 o_;                                                                                \
-    o_.x = __builtin_amdgcn_perm(vreg[1][(J) >> 1], vreg[0][(J) >> 1], SEL);                 \
-    o_.y = __builtin_amdgcn_perm(vreg[3][(J) >> 1], vreg[2][(J) >> 1], SEL);                 \
-    *reinterpret_cast<uint2*>(Vt2[BUF] + (v_ch * 8 + (J)) * VT_STRIDE + v_pos) = o_;         \
   } while (0)
 #define QZO_ATT_LSTORE(BUF, KB_)                                                             \
   do {                                                                                       \
@@ -154,28 +145,83 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
       const uint32_t row = QZO_ATT_KROW(i), ch = QZO_ATT_KCH(i);                             \
       *reinterpret_cast<u32x4*>(Ks2[BUF] + row * DH + ((ch ^ swz(row)) * 8)) = kreg[i];      \
     }                                                                                        \
-    if (v_on) { /* features 2j take the low halves of dword j, 2j+1 the high halves */       \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                        \
-        QZO_ATT_VROW(2 * j, 0x05040100u, BUF);                                               \
-        QZO_ATT_VROW(2 * j + 1, 0x07060302u, BUF);                                           \
-      }                                                                                      \
+    _Pragma("unroll") for (int i = 0; i < NK; ++i) {                                         \
+      const uint32_t c = t + 256u * i;                                                       \
+      const uint32_t row = c / CH, ch = c % CH;                                              \
+      *reinterpret_cast<u32x4*>(Vs2[BUF] + row * DH + (((ch >> 1) ^ vsw(row)) * 16 + (ch & 1u) * 8)) = vreg[i]; \
     }                                                                                        \
   } while (0)
-  // Tile kb is computed from LDS buffer kb & 1 while tile kb+1 goes from registers to the
-  // other buffer and tile kb+2 is requested from memory: one barrier per tile.
-  QZO_ATT_GLOAD(0u);
-  QZO_ATT_LSTORE(0, 0u);
-  if (nkb > 1) QZO_ATT_GLOAD(1u);
+  // Direct loads: load n of wavefront w fills bytes (4 n + w) 1024 .. + 1023 of a tile, lane l its 16 bytes at
+  // l 16: row and physical chunk follow, the logical chunk is the physical one un-swizzled.
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  const uint64_t base_addr = (uint64_t)(uintptr_t)base;
+  const uint64_t left = ((uint64_t)(gridDim.z - b) * S * ld - h * DH) * 2;      // bytes from base to the end of qkv
+  const i32x4 rqkv = {(int)(uint32_t)base_addr, (int)(uint32_t)(base_addr >> 32),
+                      (int)(uint32_t)(left < 0xffffffffull ? left : 0xffffffffull), 0x00020000};
+  uint32_t d_row[DTL ? NI : 1], d_koff[DTL ? NI : 1], d_voff[DTL ? NI : 1];
+  if (DTL) {
+#pragma unroll
+    for (int n = 0; n < NI; ++n) {
+      const uint32_t byte = (4u * n + wave) * 1024u + lane * 16u;
+      const uint32_t row = byte / (DH * 2), pc = (byte % (DH * 2)) / 16;
+      d_row[n] = row;
+      d_koff[n] = (d + (pc ^ swz(row)) * 8) * 2;
+      d_voff[n] = (2 * d + (((pc >> 1) ^ vsw(row)) * 2 + (pc & 1u)) * 8) * 2;
+    }
+  }
+  const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16_t*)&Ks2[0][0] +
+                         __builtin_amdgcn_readfirstlane(wave) * 1024u;
+  const uint32_t lds_v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16_t*)&Vs2[0][0] +
+                         __builtin_amdgcn_readfirstlane(wave) * 1024u;
+#define QZO_ATT_DTL16(LDSADDR, VOFF)                                                         \
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"                 \
+               : : "s"(LDSADDR), "v"(VOFF), "s"(rqkv) : "memory", "m0")
+// load J of a tile: J < NI the K loads, then the V loads; BUF, KB_ may be run-time values
+#define QZO_ATT_DTL_ONE(BUF, KB_, J)                                                         \
+  do {                                                                                       \
+    const int n_ = (J) < NI ? (J) : (J) - NI;                                                \
+    const uint32_t key = min((KB_) * KB + d_row[n_], S - 1);                                 \
+    if ((J) < NI) QZO_ATT_DTL16(lds_k + (uint32_t)((BUF) * (KB * DH * 2) + n_ * 4096), key * (ld * 2) + d_koff[n_]); \
+    else QZO_ATT_DTL16(lds_v + (uint32_t)((BUF) * (KB * DH * 2) + n_ * 4096), key * (ld * 2) + d_voff[n_]); \
+  } while (0)
+#define QZO_ATT_DTL(BUF, KB_)                                                                \
+  do {                                                                                       \
+    _Pragma("unroll") for (int j_ = 0; j_ < 2 * NI; ++j_) QZO_ATT_DTL_ONE(BUF, KB_, j_);     \
+  } while (0)
+  // Registers (ROPE): tile kb is computed from LDS buffer kb & 1 while tile kb+1 goes from registers to the
+  // other buffer and tile kb+2 is requested from memory.  Direct loads: tile kb+1 is requested into the
+  // other buffer at the start of tile kb (every wavefront is past the barrier, so tile kb-1 has been read)
+  // and has landed when each wavefront's own loads are back and the next barrier is passed.  One barrier
+  // per tile either way.
+  if (DTL) {
+    QZO_ATT_DTL(0, 0u);
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
+  } else {
+    QZO_ATT_GLOAD(0u);
+    QZO_ATT_LSTORE(0, 0u);
+    if (nkb > 1) QZO_ATT_GLOAD(1u);
+  }
   __syncthreads();
 
   for (uint32_t kb = 0; kb < nkb; ++kb) {
-    if (kb > 0) __syncthreads();                // tile kb is complete, tile kb-1 has been read
+    if (kb > 0) {                               // tile kb is complete, tile kb-1 has been read
+      if (DTL) __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+    }
+    // direct loads of tile kb+1: one per k-step of the score MFMAs below (a wavefront whose tile is wholly
+    // in its future issues them here)
+    const bool dtl_next = DTL && kb + 1 < nkb;
+    const uint32_t nbuf = (kb + 1) & 1u;
     if (kb + 1 < nkb) {
-      if (kb & 1u) QZO_ATT_LSTORE(0, kb + 1); else QZO_ATT_LSTORE(1, kb + 1);
-      if (kb + 2 < nkb) QZO_ATT_GLOAD(kb + 2);
+      if (DTL) {
+        if (kb * KB > wave_q_hi) QZO_ATT_DTL(nbuf, kb + 1);
+      } else {
+        if (kb & 1u) QZO_ATT_LSTORE(0, kb + 1); else QZO_ATT_LSTORE(1, kb + 1);
+        if (kb + 2 < nkb) QZO_ATT_GLOAD(kb + 2);
+      }
     }
     const bf16_t* Ks = Ks2[kb & 1u];
-    const bf16_t* Vt = Vt2[kb & 1u];
+    const bf16_t* Vs = Vs2[kb & 1u];
     if (kb * KB > wave_q_hi) continue;          // every key of the tile is in this wave's future
     const bool two = kb * KB + 32 <= wave_q_hi; // the tile's second half holds visible keys
 
@@ -194,6 +240,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
         const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(Ks + (32 + lrow) * DH + ((ch ^ swz(32 + lrow)) * 8));
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], s[0], 0, 0, 0);
         s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], s[1], 0, 0, 0);
+        if (DTL && ks < 2 * NI) { if (dtl_next) QZO_ATT_DTL_ONE(nbuf, kb + 1, ks); }
       }
       // issue order: six fragment reads ahead, then one pair of reads per pair of MFMAs
       __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
@@ -208,6 +255,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
         const uint32_t ch = ks * 2 + lhalf;
         const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(Ks + lrow * DH + ((ch ^ swz(lrow)) * 8));
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], s[0], 0, 0, 0);
+        if (DTL && ks < 2 * NI) { if (dtl_next) QZO_ATT_DTL_ONE(nbuf, kb + 1, ks); }
       }
       __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
@@ -254,8 +302,14 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
         for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
     }
     // P^T as the B operand: element e of k-step st (16 keys) is key 8 (e/4) + 4 half + e%4 of
-    // that group, i.e. score register 8 (st & 1) + e of sub-tile st / 2; the V^T tile holds the
-    // same eight keys contiguously at position 16 st + 8 half.
+    // that group, i.e. score register 8 (st & 1) + e of sub-tile st / 2.  The V operand of the same
+    // k-step: a lane's feature is 32 i + lane % 32, its keys come from two transposing reads (keys
+    // 16 st + 4 half + 0..3 and the same + 8), for which lane j of each 16 supplies features
+    // 4 (j % 4) .. + 3 of its 16-feature block at key + j / 4.
+    // (rows 16 st + 4 half + j / 4 (+ 8): the swizzle depends on j / 4 only; segment 2 i + (lane / 16) % 2)
+    const uint32_t v_r = (lane & 15u) >> 2;
+    const uint32_t v_src = (4 * lhalf + v_r) * DH + ((lane >> 4) & 1u) * 16 + (lane & 3u) * 4;
+    const uint32_t v_x = vsw(v_r);
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
       if (st < 2 || two) {
@@ -265,8 +319,13 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
           pf.u[e] = pack_bf16x2(s[st >> 1][8 * (st & 1) + 2 * e], s[st >> 1][8 * (st & 1) + 2 * e + 1]);
 #pragma unroll
         for (int i = 0; i < DT; ++i) {
-          const bf16x8 vf = *reinterpret_cast<const bf16x8*>(Vt + (i * 32 + lrow) * VT_STRIDE + 16 * st + 8 * lhalf);
-          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, o[i], 0, 0, 0);
+          typedef short short4v __attribute__((ext_vector_type(4)));
+          typedef __attribute__((address_space(3))) short4v* lds_s4;
+          union { bf16x8 v; short4v h[2]; } vf;
+          const bf16_t* src = Vs + v_src + (16 * st) * DH + ((2u * i) ^ v_x) * 16;
+          vf.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(src));
+          vf.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(src + 8 * DH));
+          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[i], 0, 0, 0);
         }
       }
     }
@@ -291,7 +350,9 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
 #undef QZO_ATT_KCH
 #undef QZO_ATT_GLOAD
 #undef QZO_ATT_LSTORE
-#undef QZO_ATT_VROW
+#undef QZO_ATT_DTL
+#undef QZO_ATT_DTL_ONE
+#undef QZO_ATT_DTL16
 
 // rope (nullable): (cos, sin) of [S positions][dh/2 pairs]; with it q and k are rotated on the fly.
 hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_heads,
