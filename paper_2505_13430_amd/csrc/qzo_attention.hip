@@ -176,17 +176,19 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
 #define QZO_ATT_DTL16(LDSADDR, VOFF)                                                         \
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"                 \
                : : "s"(LDSADDR), "v"(VOFF), "s"(rqkv) : "memory", "m0")
-// load J of a tile: J < NI the K loads, then the V loads; BUF, KB_ may be run-time values
-#define QZO_ATT_DTL_ONE(BUF, KB_, J)                                                         \
+// load J of a tile: J < NI the K loads, then the V loads; BUF, KB_ may be run-time values.  ON (uniform)
+// false: the offset is out of the buffer's range, the load fetches nothing and writes zeros to a buffer
+// that nobody reads (no branch around the load: the score loop stays one block for the scheduler)
+#define QZO_ATT_DTL_ONE(BUF, KB_, J, ON)                                                     \
   do {                                                                                       \
     const int n_ = (J) < NI ? (J) : (J) - NI;                                                \
     const uint32_t key = min((KB_) * KB + d_row[n_], S - 1);                                 \
-    if ((J) < NI) QZO_ATT_DTL16(lds_k + (uint32_t)((BUF) * (KB * DH * 2) + n_ * 4096), key * (ld * 2) + d_koff[n_]); \
-    else QZO_ATT_DTL16(lds_v + (uint32_t)((BUF) * (KB * DH * 2) + n_ * 4096), key * (ld * 2) + d_voff[n_]); \
+    const uint32_t off_ = key * (ld * 2) + ((J) < NI ? d_koff[n_] : d_voff[n_]);             \
+    QZO_ATT_DTL16(((J) < NI ? lds_k : lds_v) + (uint32_t)((BUF) * (KB * DH * 2) + n_ * 4096), (ON) ? off_ : 0xfffffff0u); \
   } while (0)
 #define QZO_ATT_DTL(BUF, KB_)                                                                \
   do {                                                                                       \
-    _Pragma("unroll") for (int j_ = 0; j_ < 2 * NI; ++j_) QZO_ATT_DTL_ONE(BUF, KB_, j_);     \
+    _Pragma("unroll") for (int j_ = 0; j_ < 2 * NI; ++j_) QZO_ATT_DTL_ONE(BUF, KB_, j_, true); \
   } while (0)
   // Registers (ROPE): tile kb is computed from LDS buffer kb & 1 while tile kb+1 goes from registers to the
   // other buffer and tile kb+2 is requested from memory.  Direct loads: tile kb+1 is requested into the
@@ -240,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
         const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(Ks + (32 + lrow) * DH + ((ch ^ swz(32 + lrow)) * 8));
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], s[0], 0, 0, 0);
         s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[ks], s[1], 0, 0, 0);
-        if (DTL && ks < 2 * NI) { if (dtl_next) QZO_ATT_DTL_ONE(nbuf, kb + 1, ks); }
+        if (DTL && ks < 2 * NI) QZO_ATT_DTL_ONE(nbuf, kb + 1, ks, dtl_next);
       }
       // issue order: six fragment reads ahead, then one pair of reads per pair of MFMAs
       __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
@@ -255,7 +257,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
         const uint32_t ch = ks * 2 + lhalf;
         const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(Ks + lrow * DH + ((ch ^ swz(lrow)) * 8));
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[ks], s[0], 0, 0, 0);
-        if (DTL && ks < 2 * NI) { if (dtl_next) QZO_ATT_DTL_ONE(nbuf, kb + 1, ks); }
+        if (DTL && ks < 2 * NI) QZO_ATT_DTL_ONE(nbuf, kb + 1, ks, dtl_next);
       }
       __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
@@ -280,7 +282,10 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[u][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    {   // both halves of the wavefront: lane l and lane l ^ 32 hold the two halves of a query's keys
+      const auto r_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(r_[0]), __uint_as_float(r_[1]));
+    }
     const float m_new = fmaxf(m_run, mx);
     const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
     const float nm = -m_new * sc;
@@ -292,7 +297,10 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
         s[u][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[u][r], sc, nm));
         psum += s[u][r];
       }
-    psum += __shfl_xor(psum, 32, 64);
+    {
+      const auto r_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(psum), __float_as_uint(psum), false, false);
+      psum = __uint_as_float(r_[0]) + __uint_as_float(r_[1]);
+    }
     l_run = l_run * alpha + psum;
     m_run = m_new;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // some lane's maximum moved
@@ -331,6 +339,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     }
   }
 
+  if (DTL) __builtin_amdgcn_s_waitcnt(0x0F70);   // the last tile's (empty) direct loads have written their zeros
   if (qq < S) {
     const float inv = 1.0f / l_run;
     bf16_t* dst = out + ((uint64_t)b * S + qq) * d + h * DH;
@@ -357,6 +366,8 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
 // rope (nullable): (cos, sin) of [S positions][dh/2 pairs]; with it q and k are rotated on the fly.
 hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_heads,
                             uint32_t dh, void* out, const float* rope, hipStream_t st) {
+  // the direct loads address qkv with 32-bit byte offsets and use an offset near 2^32 as "out of range"
+  if ((uint64_t)B * S * 3 * n_heads * dh * 2 >= (1ull << 31)) return hipErrorInvalidValue;
   dim3 grid((S + 127) / 128, n_heads, B);
   const float2* tb = (const float2*)rope;
   if (dh == 128 && rope)
