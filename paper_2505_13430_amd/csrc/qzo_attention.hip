@@ -55,8 +55,10 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   // the keys pass through registers to be rotated and V takes the same way.
   constexpr bool DTL = !ROPE;
   constexpr int NI = KB * DH * 2 / 4096;   // direct loads per wavefront, tile and operand (4 or 2)
-  __shared__ __attribute__((aligned(1024))) bf16_t Ks2[2][KB * DH];
-  __shared__ __attribute__((aligned(1024))) bf16_t Vs2[2][KB * DH];
+  // LDS: K tile, V tile of buffer 0, then of buffer 1 (buffer 1 first holds the workgroup's 128 queries, at the
+  // end the four wavefronts' output rows pass through buffer 0 and 1)
+  constexpr int TILE = KB * DH;            // elements of one K or V tile
+  __shared__ __attribute__((aligned(1024))) bf16_t smem[4 * TILE];
 
   const uint32_t d = n_heads * DH, ld = 3 * d;
   // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2: the
@@ -81,19 +83,6 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   auto vsw = [](uint32_t row) { return DH == 128 ? 2u * (row & 3u) : 2u * ((row >> 1) & 1u); };
 
   bf16x8 qf[KT];
-#pragma unroll
-  for (int ks = 0; ks < KT; ++ks)
-    qf[ks] = *reinterpret_cast<const bf16x8*>(base + (uint64_t)qc * ld + ks * 16 + lhalf * 8);
-  if (ROPE) {
-    // k-step ks < KT/2 holds features ks*16 + 8 lhalf .. + 7 of the head, k-step ks + KT/2 the same + DH/2
-#pragma unroll
-    for (int ks = 0; ks < KT / 2; ++ks) {
-      union { bf16x8 v; uint32_t u[4]; } qa, qb;
-      qa.v = qf[ks]; qb.v = qf[ks + KT / 2];
-      rope_pair8(qa.u, qb.u, reinterpret_cast<const float4*>(rope + (uint64_t)qc * (DH / 2) + ks * 16 + lhalf * 8));
-      qf[ks] = qa.v; qf[ks + KT / 2] = qb.v;
-    }
-  }
 
   floatx16 o[DT];
 #pragma unroll
@@ -143,12 +132,12 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     }                                                                                        \
     _Pragma("unroll") for (int i = 0; i < NK; ++i) {                                         \
       const uint32_t row = QZO_ATT_KROW(i), ch = QZO_ATT_KCH(i);                             \
-      *reinterpret_cast<u32x4*>(Ks2[BUF] + row * DH + ((ch ^ swz(row)) * 8)) = kreg[i];      \
+      *reinterpret_cast<u32x4*>((smem + (BUF) * 2 * TILE) + row * DH + ((ch ^ swz(row)) * 8)) = kreg[i];      \
     }                                                                                        \
     _Pragma("unroll") for (int i = 0; i < NK; ++i) {                                         \
       const uint32_t c = t + 256u * i;                                                       \
       const uint32_t row = c / CH, ch = c % CH;                                              \
-      *reinterpret_cast<u32x4*>(Vs2[BUF] + row * DH + (((ch >> 1) ^ vsw(row)) * 16 + (ch & 1u) * 8)) = vreg[i]; \
+      *reinterpret_cast<u32x4*>((smem + (BUF) * 2 * TILE + TILE) + row * DH + (((ch >> 1) ^ vsw(row)) * 16 + (ch & 1u) * 8)) = vreg[i]; \
     }                                                                                        \
   } while (0)
   // Direct loads: load n of wavefront w fills bytes (4 n + w) 1024 .. + 1023 of a tile, lane l its 16 bytes at
@@ -169,9 +158,9 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
       d_voff[n] = (2 * d + (((pc >> 1) ^ vsw(row)) * 2 + (pc & 1u)) * 8) * 2;
     }
   }
-  const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16_t*)&Ks2[0][0] +
+  const uint32_t lds_k = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16_t*)&smem[0] +
                          __builtin_amdgcn_readfirstlane(wave) * 1024u;
-  const uint32_t lds_v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16_t*)&Vs2[0][0] +
+  const uint32_t lds_v = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) bf16_t*)&smem[TILE] +
                          __builtin_amdgcn_readfirstlane(wave) * 1024u;
 #define QZO_ATT_DTL16(LDSADDR, VOFF)                                                         \
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"                 \
@@ -184,7 +173,7 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     const int n_ = (J) < NI ? (J) : (J) - NI;                                                \
     const uint32_t key = min((KB_) * KB + d_row[n_], S - 1);                                 \
     const uint32_t off_ = key * (ld * 2) + ((J) < NI ? d_koff[n_] : d_voff[n_]);             \
-    QZO_ATT_DTL16(((J) < NI ? lds_k : lds_v) + (uint32_t)((BUF) * (KB * DH * 2) + n_ * 4096), (ON) ? off_ : 0xfffffff0u); \
+    QZO_ATT_DTL16(((J) < NI ? lds_k : lds_v) + (uint32_t)((BUF) * (4 * TILE) + n_ * 4096), (ON) ? off_ : 0xfffffff0u); \
   } while (0)
 #define QZO_ATT_DTL(BUF, KB_)                                                                \
   do {                                                                                       \
@@ -195,15 +184,48 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   // other buffer at the start of tile kb (every wavefront is past the barrier, so tile kb-1 has been read)
   // and has landed when each wavefront's own loads are back and the next barrier is passed.  One barrier
   // per tile either way.
+  // The 128 queries come in whole rows as well: direct loads put them (K's layout and swizzle, 128 rows) where
+  // buffer 1 will be; every wavefront then reads its fragments (a lane: its query, k-step ks, half) from there.
+  {
+    constexpr int NQ = 128 * DH * 2 / 4096;      // loads per wavefront
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      const uint32_t byte = (4u * n + wave) * 1024u + lane * 16u;
+      const uint32_t row = byte / (DH * 2), pc = (byte % (DH * 2)) / 16;
+      const uint32_t q = min(q0 + row, S - 1);
+      QZO_ATT_DTL16(lds_k + (uint32_t)(4 * TILE + n * 4096), q * (ld * 2) + ((pc ^ swz(row)) * 8) * 2);
+    }
+  }
   if (DTL) {
     QZO_ATT_DTL(0, 0u);
-    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
   } else {
     QZO_ATT_GLOAD(0u);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this wavefront's part of the queries (and of tile 0)
+  __syncthreads();
+  {
+    const bf16_t* Qs = smem + 2 * TILE;
+    const uint32_t row = wave * 32 + lrow;
+#pragma unroll
+    for (int ks = 0; ks < KT; ++ks)
+      qf[ks] = *reinterpret_cast<const bf16x8*>(Qs + row * DH + (((uint32_t)(ks * 2) + lhalf) ^ swz(row)) * 8);
+  }
+  if (ROPE) {
+    // k-step ks < KT/2 holds features ks*16 + 8 lhalf .. + 7 of the head, k-step ks + KT/2 the same + DH/2
+#pragma unroll
+    for (int ks = 0; ks < KT / 2; ++ks) {
+      union { bf16x8 v; uint32_t u[4]; } qa, qb;
+      qa.v = qf[ks]; qb.v = qf[ks + KT / 2];
+      rope_pair8(qa.u, qb.u, reinterpret_cast<const float4*>(rope + (uint64_t)qc * (DH / 2) + ks * 16 + lhalf * 8));
+      qf[ks] = qa.v; qf[ks + KT / 2] = qb.v;
+    }
+  }
+
+  if (!DTL) {
     QZO_ATT_LSTORE(0, 0u);
     if (nkb > 1) QZO_ATT_GLOAD(1u);
   }
-  __syncthreads();
+  __syncthreads();                              // the queries have been read: buffer 1 is free (tile 0 is complete)
 
   for (uint32_t kb = 0; kb < nkb; ++kb) {
     if (kb > 0) {                               // tile kb is complete, tile kb-1 has been read
@@ -222,8 +244,8 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
         if (kb + 2 < nkb) QZO_ATT_GLOAD(kb + 2);
       }
     }
-    const bf16_t* Ks = Ks2[kb & 1u];
-    const bf16_t* Vs = Vs2[kb & 1u];
+    const bf16_t* Ks = smem + (kb & 1u) * 2 * TILE;
+    const bf16_t* Vs = Ks + TILE;
     if (kb * KB > wave_q_hi) continue;          // every key of the tile is in this wave's future
     const bool two = kb * KB + 32 <= wave_q_hi; // the tile's second half holds visible keys
 
@@ -339,10 +361,14 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     }
   }
 
+  // Output: a lane holds one query's features in 4-feature pieces; each wavefront passes its 32 rows through
+  // the LDS (rows padded by 16 bytes) so that they leave in whole rows, 16 bytes per lane.
   if (DTL) __builtin_amdgcn_s_waitcnt(0x0F70);   // the last tile's (empty) direct loads have written their zeros
-  if (qq < S) {
+  __syncthreads();                               // every wavefront is done with the tiles
+  {
+    constexpr int OS = DH + 8;                   // padded output row (elements)
+    bf16_t* Os = smem + wave * (32 * OS);
     const float inv = 1.0f / l_run;
-    bf16_t* dst = out + ((uint64_t)b * S + qq) * d + h * DH;
 #pragma unroll
     for (int i = 0; i < DT; ++i)
 #pragma unroll
@@ -350,8 +376,20 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
         uint2 v;
         v.x = pack_bf16x2(o[i][4 * g] * inv, o[i][4 * g + 1] * inv);
         v.y = pack_bf16x2(o[i][4 * g + 2] * inv, o[i][4 * g + 3] * inv);
-        *reinterpret_cast<uint2*>(dst + i * 32 + 8 * g + 4 * lhalf) = v;
+        *reinterpret_cast<uint2*>(Os + lrow * OS + i * 32 + 8 * g + 4 * lhalf) = v;
       }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int LPR = DH / 8;                  // lanes per row
+    constexpr int RPI = 64 / LPR;                // rows per store instruction
+#pragma unroll
+    for (int j = 0; j < 32 / RPI; ++j) {
+      const uint32_t row = j * RPI + lane / LPR, ch = lane % LPR;
+      const uint32_t q = q0 + wave * 32 + row;
+      const uint4 v = *reinterpret_cast<const uint4*>(Os + row * OS + ch * 8);
+      if (q < S) *reinterpret_cast<uint4*>(out + ((uint64_t)b * S + q) * d + h * DH + ch * 8) = v;
+    }
   }
 }
 
