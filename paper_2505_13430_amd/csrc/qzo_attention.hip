@@ -71,30 +71,16 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     hb = (L & 7u) + 8u * (slot / gridDim.x);
     bx = slot % gridDim.x;
   }
-  const uint32_t b = hb / gridDim.y, h = hb % gridDim.y, q0 = (gridDim.x - 1 - bx) * 128;
+  const uint32_t b = hb / gridDim.y, h = hb % gridDim.y;
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t lrow = lane & 31u, lhalf = lane >> 5;
   const bf16_t* base = qkv + (uint64_t)b * S * ld + h * DH;
-  const uint32_t qq = q0 + wave * 32 + lrow;            // this lane's query
-  const uint32_t qc = min(qq, S - 1);
   auto swz = [](uint32_t row) { return DH == 128 ? (row & SWZ) : ((row >> 1) & SWZ); };
   // V rows are unpadded; their 32-byte segments are XOR-swizzled so that the 4 rows x 2 segments that half a
   // wavefront touches in one transposing read fall into 8 different 32-byte bank groups
   auto vsw = [](uint32_t row) { return DH == 128 ? 2u * (row & 3u) : 2u * ((row >> 1) & 1u); };
 
-  bf16x8 qf[KT];
-
-  floatx16 o[DT];
-#pragma unroll
-  for (int i = 0; i < DT; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[i][r] = 0.0f;
-  float m_run = -INFINITY, l_run = 0.0f;
   const float sc = 1.44269504088896f / sqrtf((float)DH);   // log2(e)/sqrt(dh)
-
-  const uint32_t q_hi = min(q0 + 127u, S - 1);
-  const uint32_t nkb = q_hi / KB + 1;
-  const uint32_t wave_q_hi = q0 + wave * 32 + 31;
 
   // staging registers: K and V chunks (row c / CH, chunk c % CH of the tile, c = t + 256 i)
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -184,6 +170,26 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   // other buffer at the start of tile kb (every wavefront is past the barrier, so tile kb-1 has been read)
   // and has landed when each wavefront's own loads are back and the next barrier is passed.  One barrier
   // per tile either way.
+  // A grid of one workgroup per (batch, head) (gridDim.x == 1) walks the head's query blocks itself, late
+  // (heavy) blocks first: every workgroup then has the same work and the chip is filled once; otherwise a
+  // workgroup serves the one query block its launch index names.
+  const uint32_t nqb = (S + 127) / 128;
+  const uint32_t n_it = gridDim.x == 1 ? nqb : 1u;
+  for (uint32_t it = 0; it < n_it; ++it) {
+  const uint32_t q0 = (gridDim.x == 1 ? nqb - 1 - it : gridDim.x - 1 - bx) * 128;
+  const uint32_t qq = q0 + wave * 32 + lrow;            // this lane's query
+  const uint32_t qc = min(qq, S - 1);
+  bf16x8 qf[KT];
+  floatx16 o[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.0f;
+  float m_run = -INFINITY, l_run = 0.0f;
+  const uint32_t q_hi = min(q0 + 127u, S - 1);
+  const uint32_t nkb = q_hi / KB + 1;
+  const uint32_t wave_q_hi = q0 + wave * 32 + 31;
+
   // The 128 queries come in whole rows as well: direct loads put them (K's layout and swizzle, 128 rows) where
   // buffer 1 will be; every wavefront then reads its fragments (a lane: its query, k-step ks, half) from there.
   {
@@ -391,6 +397,8 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
       if (q < S) *reinterpret_cast<uint4*>(out + ((uint64_t)b * S + q) * d + h * DH + ch * 8) = v;
     }
   }
+  if (it + 1 < n_it) __syncthreads();            // the output rows have been read: the LDS is free for the next block
+  }   // query blocks
 }
 
 #undef QZO_ATT_KROW
@@ -406,7 +414,16 @@ hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_
                             uint32_t dh, void* out, const float* rope, hipStream_t st) {
   // the direct loads address qkv with 32-bit byte offsets and use an offset near 2^32 as "out of range"
   if ((uint64_t)B * S * 3 * n_heads * dh * 2 >= (1ull << 31)) return hipErrorInvalidValue;
-  dim3 grid((S + 127) / 128, n_heads, B);
+  // one workgroup per (batch, head) when those alone fill the chip twice over (two workgroups fit a CU)
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+      n_cu = 256;
+  }
+  const bool per_head = (uint64_t)n_heads * B >= 2ull * (uint64_t)n_cu && S > 128;
+  dim3 grid(per_head ? 1 : (S + 127) / 128, n_heads, B);
   const float2* tb = (const float2*)rope;
   if (dh == 128 && rope)
     attention_kernel<128, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
