@@ -40,7 +40,7 @@ __device__ __forceinline__ void rope_pair8(uint32_t (&a)[4], uint32_t (&b)[4], c
   }
 }
 
-template <int DH, bool ROPE>
+template <int DH, bool ROPE, bool LONG>
 __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restrict__ qkv, uint32_t S,
                                                            uint32_t n_heads, bf16_t* __restrict__ out,
                                                            const float2* __restrict__ rope) {
@@ -174,9 +174,10 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   // (heavy) blocks first: every workgroup then has the same work and the chip is filled once; otherwise a
   // workgroup serves the one query block its launch index names.
   const uint32_t nqb = (S + 127) / 128;
-  const uint32_t n_it = gridDim.x == 1 ? nqb : 1u;
+  constexpr bool via_lds = LONG;               // more than one query block per head
+  const uint32_t n_it = (LONG && gridDim.x == 1) ? nqb : 1u;
   for (uint32_t it = 0; it < n_it; ++it) {
-  const uint32_t q0 = (gridDim.x == 1 ? nqb - 1 - it : gridDim.x - 1 - bx) * 128;
+  const uint32_t q0 = ((LONG && gridDim.x == 1) ? nqb - 1 - it : gridDim.x - 1 - bx) * 128;
   const uint32_t qq = q0 + wave * 32 + lrow;            // this lane's query
   const uint32_t qc = min(qq, S - 1);
   bf16x8 qf[KT];
@@ -190,9 +191,11 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   const uint32_t nkb = q_hi / KB + 1;
   const uint32_t wave_q_hi = q0 + wave * 32 + 31;
 
-  // The 128 queries come in whole rows as well: direct loads put them (K's layout and swizzle, 128 rows) where
-  // buffer 1 will be; every wavefront then reads its fragments (a lane: its query, k-step ks, half) from there.
-  {
+  // Long sequences: the 128 queries come in whole rows as well: direct loads put them (K's layout and swizzle,
+  // 128 rows) where buffer 1 will be; every wavefront then reads its fragments (a lane: its query, k-step ks,
+  // half) from there.  Short sequences (one or a few tiles per workgroup) cannot afford the two barriers this
+  // takes: there a lane reads its query's fragments from memory.
+  if (via_lds) {
     constexpr int NQ = 128 * DH * 2 / 4096;      // loads per wavefront
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
@@ -201,15 +204,19 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
       const uint32_t q = min(q0 + row, S - 1);
       QZO_ATT_DTL16(lds_k + (uint32_t)(4 * TILE + n * 4096), q * (ld * 2) + ((pc ^ swz(row)) * 8) * 2);
     }
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < KT; ++ks)
+      qf[ks] = *reinterpret_cast<const bf16x8*>(base + (uint64_t)qc * ld + ks * 16 + lhalf * 8);
   }
   if (DTL) {
     QZO_ATT_DTL(0, 0u);
   } else {
     QZO_ATT_GLOAD(0u);
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this wavefront's part of the queries (and of tile 0)
-  __syncthreads();
-  {
+  if (via_lds) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): this wavefront's part of the queries (and of tile 0)
+    __syncthreads();
     const bf16_t* Qs = smem + 2 * TILE;
     const uint32_t row = wave * 32 + lrow;
 #pragma unroll
@@ -230,8 +237,10 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   if (!DTL) {
     QZO_ATT_LSTORE(0, 0u);
     if (nkb > 1) QZO_ATT_GLOAD(1u);
+  } else if (!via_lds) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0): this wavefront's part of tile 0
   }
-  __syncthreads();                              // the queries have been read: buffer 1 is free (tile 0 is complete)
+  __syncthreads();                              // tile 0 is complete (and the queries have been read: buffer 1 is free)
 
   for (uint32_t kb = 0; kb < nkb; ++kb) {
     if (kb > 0) {                               // tile kb is complete, tile kb-1 has been read
@@ -367,14 +376,15 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
     }
   }
 
-  // Output: a lane holds one query's features in 4-feature pieces; each wavefront passes its 32 rows through
-  // the LDS (rows padded by 16 bytes) so that they leave in whole rows, 16 bytes per lane.
+  // Output: a lane holds one query's features in 4-feature pieces.  Long sequences: each wavefront passes its
+  // 32 rows through the LDS (rows padded by 16 bytes) so that they leave in whole rows, 16 bytes per lane;
+  // short sequences store the pieces as they are.
   if (DTL) __builtin_amdgcn_s_waitcnt(0x0F70);   // the last tile's (empty) direct loads have written their zeros
-  __syncthreads();                               // every wavefront is done with the tiles
-  {
+  const float inv = 1.0f / l_run;
+  if (via_lds) {
+    __syncthreads();                             // every wavefront is done with the tiles
     constexpr int OS = DH + 8;                   // padded output row (elements)
     bf16_t* Os = smem + wave * (32 * OS);
-    const float inv = 1.0f / l_run;
 #pragma unroll
     for (int i = 0; i < DT; ++i)
 #pragma unroll
@@ -396,6 +406,17 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
       const uint4 v = *reinterpret_cast<const uint4*>(Os + row * OS + ch * 8);
       if (q < S) *reinterpret_cast<uint4*>(out + ((uint64_t)b * S + q) * d + h * DH + ch * 8) = v;
     }
+  } else if (qq < S) {
+    bf16_t* dst = out + ((uint64_t)b * S + qq) * d + h * DH;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 v;
+        v.x = pack_bf16x2(o[i][4 * g] * inv, o[i][4 * g + 1] * inv);
+        v.y = pack_bf16x2(o[i][4 * g + 2] * inv, o[i][4 * g + 3] * inv);
+        *reinterpret_cast<uint2*>(dst + i * 32 + 8 * g + 4 * lhalf) = v;
+      }
   }
   if (it + 1 < n_it) __syncthreads();            // the output rows have been read: the LDS is free for the next block
   }   // query blocks
@@ -422,17 +443,22 @@ hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_
         hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
       n_cu = 256;
   }
-  const bool per_head = (uint64_t)n_heads * B >= 2ull * (uint64_t)n_cu && S > 128;
+  const bool lng = S > 128 && !rope;           // more than one query block per head: the long-sequence paths
+  const bool per_head = (uint64_t)n_heads * B >= 2ull * (uint64_t)n_cu && lng;
   dim3 grid(per_head ? 1 : (S + 127) / 128, n_heads, B);
   const float2* tb = (const float2*)rope;
   if (dh == 128 && rope)
-    attention_kernel<128, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<128, true, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+  else if (dh == 128 && lng)
+    attention_kernel<128, false, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
   else if (dh == 128)
-    attention_kernel<128, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<128, false, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
   else if (dh == 64 && rope)
-    attention_kernel<64, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<64, true, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+  else if (dh == 64 && lng)
+    attention_kernel<64, false, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
   else if (dh == 64)
-    attention_kernel<64, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<64, false, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
