@@ -364,7 +364,7 @@ def main():
         "scales_changed_frac": changed,
         "scales_changed_frac_at_clip": changed_clip,
         "roofline": {"bound": "mfma",
-                     "kernel": "gemm_kernel<1,false,4,3> (plain bf16 GEMM on the expanded perturbed weights)"
+                     "kernel": "wide_gemm_kernel (qkv, o, down) and gemm_kernel<1,false,4,3> (gate/up with SwiGLU): plain bf16 GEMM on the expanded perturbed weights"
                      if expanded
                      else ("gemm_kernel<2,...> (codebook GEMM, perturbed channel scales)" if codebook
                            else "gemm_kernel<0,false,4,2> (fused perturbed W4A16 GEMM)"),
