@@ -1067,6 +1067,34 @@ def test_full_size_token_count_sampled_sequence_matches_oracle(oracle):
     dm.close()
 
 
+@pytest.mark.parametrize("S", [256, 300])
+def test_attention_per_head_walk_head_size_64_sampled_sequence_matches_oracle(oracle, S):
+    """16 sequences x 32 heads of 64 features fill the chip twice over, so one attention workgroup walks all
+    query blocks of its (batch, head): 2 blocks at 256 positions, 3 at 300 (the last one ragged, 44 rows).
+    One decoder layer at OPT-1.3B widths (LayerNorm, bias, ReLU, learned positions); the oracle runs one
+    sequence of the batch alone, whose final hidden states are compared with the batch's rows."""
+    shape = dict(synth.SHAPES["opt-1.3b"], n_layers=1, vocab=1000, max_seq=S, seq=S)
+    om, dm = _models(oracle, shape, 91)
+    tok = synth.tokens(shape, 92)
+    B = tok.shape[0]
+    assert tok.shape == (16, S)
+    hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    qb.qzo_debug_forward(dm.handle, _dev(tok), 5, 1e-3, -1, dm.workspace(B, S), loss, hid)
+    b = 6
+    se = oracle.perturbed_scales(om, 5, np.float32(-1e-3))
+    _, ref_hid = oracle.forward_loss(om, se, tok[b:b + 1], act_bf16=True, want_hidden=True)
+    _, exact_hid = oracle.forward_loss(om, se, tok[b:b + 1], act_bf16=False, want_hidden=True)
+    got = hid[b * S:(b + 1) * S].float().cpu().numpy().astype(np.float64)
+    rms = math.sqrt((ref_hid ** 2).mean())
+    err = np.abs(got - ref_hid)
+    floor_rms = math.sqrt(((exact_hid - ref_hid) ** 2).mean())
+    assert math.isfinite(loss.item())
+    assert math.sqrt((err ** 2).mean()) <= 2 * floor_rms + 2e-3 * rms
+    assert err.max() <= 2 * np.abs(exact_hid - ref_hid).max() + 2e-2 * rms
+    dm.close()
+
+
 def test_full_size_token_count_one_layer_routes_agree_bit_for_bit():
     """The benchmark's token count (16 x 512) through one decoder layer at Llama-2-7B widths, once on the
     route the benchmark times (perturbed scales of the arena, expanded bf16 weights, plain GEMM with the
