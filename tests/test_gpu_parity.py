@@ -1067,6 +1067,27 @@ def test_full_size_token_count_sampled_sequence_matches_oracle(oracle):
     dm.close()
 
 
+def test_opt_width_token_count_routes_agree_bit_for_bit():
+    """16 x 256 tokens through one decoder layer at OPT-1.3B widths: on the expanded route the qkv (bias) and
+    fc1 (bias + ReLU) GEMMs have more output tiles than compute units, so the one-wavefront-per-SIMD kernel
+    defers a tile's stores into the next tile's k-loop with those epilogues; the narrow o and fc2 projections
+    are cut along K.  Loss and hidden states must equal the fused route's bit for bit."""
+    shape = dict(synth.SHAPES["opt-1.3b"], n_layers=1, vocab=2000)
+    dm = DeviceModel.synthetic(shape, seed=8, device=DEV)
+    B, S = shape["batch"], shape["seq"]
+    tok = _dev(synth.tokens(shape, 9))
+    outs = []
+    for mode in (2, 1):
+        dm.set_int4_path(mode)
+        hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        qb.qzo_debug_forward(dm.handle, tok, 4, 1e-3, 1, dm.workspace(B, S), loss, hid)
+        outs.append((float(loss.item()), hid))
+    assert math.isfinite(outs[0][0]) and outs[0][0] == outs[1][0]
+    assert torch.equal(outs[0][1], outs[1][1])
+    dm.close()
+
+
 @pytest.mark.parametrize("S", [256, 300])
 def test_attention_per_head_walk_head_size_64_sampled_sequence_matches_oracle(oracle, S):
     """16 sequences x 32 heads of 64 features fill the chip twice over, so one attention workgroup walks all
