@@ -239,8 +239,11 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
   // more tokens than that but still too few output tiles for the chip: split-K partial sums
   uint64_t sp = 0;
   if ((M1 > SKINNY_MAX_M && int4) || c.act_order || c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK))
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
       sp = std::max<uint64_t>(sp, tile_split_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
+      // a single pass (qzo_forward_loss) of a batch whose step stacks its two passes
+      if (stack) sp = std::max<uint64_t>(sp, tile_split_ws_floats((uint32_t)M1, m->lin[i].N, m->lin[i].K));
+    }
   w.split = (float*)take(sp * 4);
   if (sp == 0) w.split = nullptr;
   // codebook variant with many tokens: the largest linear written out as bf16
@@ -401,7 +404,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
                                                  (epi & EPI_SWIGLU) != 0 && !split, w.wexp, st);
           if (e != hipSuccess) return e;
         }
-        g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
+        g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = (split || (w.split && tile_tail_cols(g.M, g.N, g.K, g.epi))) ? w.split : nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
@@ -419,7 +422,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
           hipError_t e = launch_expand_nf4_from(g.w, w.se + layer_off + m->lin[li].s_off, g.N, g.K, order, w.wexp, st);
           if (e != hipSuccess) return e;
         }
-        g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = split ? w.split : nullptr;
+        g.w = w.wexp; g.s = nullptr; g.skinny_ws = nullptr; g.split_ws = (split || (w.split && tile_tail_cols(g.M, g.N, g.K, g.epi))) ? w.split : nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
@@ -440,7 +443,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
                                                  g.K, order, w.wexp, st);
           if (e != hipSuccess) return e;
         }
-        g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr; g.split_ws = nullptr;
+        g.w = w.wexp; g.s = nullptr; g.zp = nullptr; g.skinny_ws = nullptr;
+        // (plain epilogues: the launcher cuts K where the output tiles do not fill the chip, or the last
+        // columns' K where they are a little more than whole rounds, exactly as it does for the fused kernel)
+        g.split_ws = (g.epi & (EPI_SWIGLU | EPI_ROPE)) ? nullptr : w.split;
         ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }
@@ -473,7 +479,7 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
                                                 eps_signed, order, w.wexp, st);
           if (e != hipSuccess) return e;
         }
-        g.w = w.wexp; g.cb = nullptr; g.s = nullptr; g.split_ws = split ? w.split : nullptr;
+        g.w = w.wexp; g.cb = nullptr; g.s = nullptr; g.split_ws = (split || (w.split && tile_tail_cols(g.M, g.N, g.K, g.epi))) ? w.split : nullptr;
         ProfScope ps(PK_W4GEMM, 2.0 * Mreal * (double)g.N * g.K, st);
         return launch_bf16_gemm(g, PLAIN_GEMM_PIPE, st);
       }

@@ -48,9 +48,25 @@ uint32_t tile_ksplit(uint32_t M, uint32_t N, uint32_t K, uint32_t* kt_per) {
   if (kt_per) *kt_per = per;
   return (nkt + per - 1) / per;
 }
+uint32_t tile_tail_cols(uint32_t M, uint32_t N, uint32_t K, uint32_t epi) {
+  if (epi & (EPI_SWIGLU | EPI_ROPE | EPI_SUMSQ)) return 0;
+  const uint32_t tm = (M + BM - 1) / BM, tn = (N + BN - 1) / BN, tiles = tm * tn;
+  const uint32_t cus = gemm_workgroups(1u << 20, 1u << 20);
+  if (tiles <= cus || tiles % cus == 0) return 0;
+  uint32_t n1 = tn - 1;                              // feature tiles of the whole rounds
+  while (n1 > 0 && (tm * n1) % cus != 0) --n1;
+  if (n1 == 0) return 0;
+  const uint32_t tail = tm * (tn - n1);
+  // worth it when the tail can be cut into at least two K slices of at least 8 k-tiles
+  if (tail * 2 > cus || tile_ksplit(M, N - n1 * BN, K, nullptr) < 2 || K / BK < 16) return 0;
+  return n1 * BN;
+}
 uint64_t tile_split_ws_floats(uint32_t M, uint32_t N, uint32_t K) {
   const uint32_t ks = tile_ksplit(M, N, K, nullptr);
-  return ks > 1 ? (uint64_t)ks * M * N : 0;
+  if (ks > 1) return (uint64_t)ks * M * N;
+  const uint32_t n1 = tile_tail_cols(M, N, K, 0);    // the epilogue is not known here: room for the plain case
+  if (n1) return (uint64_t)tile_ksplit(M, N - n1, K, nullptr) * M * (N - n1);
+  return 0;
 }
 
 // 8 nibbles of one dword -> 8 bf16 of (nibble-8)*se, in k order.  A byte holding
@@ -357,7 +373,9 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
   constexpr bool TRAIL = DTL && !CE && TJ == 2;
   uint32_t trail_stores = 0;                       // stores issued by the last epilogue: 0, 8 or 16
   const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
-      a.y, 0, (int)((uint64_t)a.M * ((a.epi & EPI_SWIGLU) ? (a.N >> 1) : a.N) * 2), 0x00020000);
+      a.y, 0, (int)(a.ldy ? ((uint64_t)(a.M - 1) * a.ldy + a.N) * 2
+                          : (uint64_t)a.M * ((a.epi & EPI_SWIGLU) ? (a.N >> 1) : a.N) * 2), 0x00020000);
+  const uint32_t ldy = a.ldy ? a.ldy : a.N;        // row stride of y and resid (plain epilogue)
   const uint32_t frow = lane & 31u, fhalf = lane >> 5;
   // fragment addresses: row base + swizzled chunk of k-step ks (chunk 2 ks + half);
   // row tiles i / j and the stage are immediate offsets.
@@ -835,7 +853,7 @@ __global__ __launch_bounds__(128 * NWN, 1) void gemm_kernel(GemmArgs a, CeEpilog
           const uint32_t n = n0 + wn * (32 * TJ) + j * 32 + (2u * bp + fhalf) * 8u;
           const bool inside = m < a.M && n < a.N;
           uint4 out = {0u, 0u, 0u, 0u};
-          const uint64_t o = (uint64_t)m * a.N + n;
+          const uint64_t o = (uint64_t)m * ldy + n;
           if (inside) {
             if (a.epi & EPI_BIAS) {
               const uint4 bb = *reinterpret_cast<const uint4*>(bias + n);
@@ -963,6 +981,25 @@ static hipError_t set_lds_attr(const void* fn) {
 constexpr int W4_NWN = 4;
 constexpr int W4_PIPE = 2;
 
+// Columns [n1, N) of a GEMM as a call of its own: weights, scales, zero-points, bias, output and residual
+// advanced, the noise rows offset; y and resid keep the full matrix's row stride.
+static GemmArgs column_block(const GemmArgs& a, uint32_t first, uint32_t count, int w_bits, bool codes_per_scale_group) {
+  (void)codes_per_scale_group;
+  GemmArgs s = a;
+  const uint32_t ld = a.ldy ? a.ldy : a.N;
+  s.N = count; s.ldy = ld;
+  s.w = (const char*)a.w + (uint64_t)first * a.K * w_bits / 8;
+  if (w_bits == 4) {
+    if (a.s) s.s = (const char*)a.s + (uint64_t)first * (a.K >> 7) * 2;
+    if (a.zp) s.zp = (const char*)a.zp + (uint64_t)first * (a.K >> 7);
+    s.row_base = a.row_base + first;
+  }
+  if (a.bias) s.bias = (const char*)a.bias + (uint64_t)first * 2;
+  s.y = (char*)a.y + (uint64_t)first * 2;
+  if (a.resid) s.resid = (const char*)a.resid + (uint64_t)first * 2;
+  return s;
+}
+
 hipError_t launch_w4a16_gemm(const GemmArgs& a0, hipStream_t st) {
   static bool ready = false;
   if (!ready) {
@@ -983,6 +1020,16 @@ hipError_t launch_w4a16_gemm(const GemmArgs& a0, hipStream_t st) {
   // buffer loads address each operand with 32-bit byte offsets
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K / 2 >= (1ull << 31))
     return hipErrorInvalidValue;
+  if (a.split_ws && !a.ldy) {
+    // a little more than whole rounds of tiles: the whole rounds as they are, the rest cut along K
+    const uint32_t n1 = tile_tail_cols(a.M, a.N, a.K, a.epi);
+    if (n1) {
+      GemmArgs h = column_block(a, 0, n1, 4, false), t = column_block(a, n1, a.N - n1, 4, false);
+      h.split_ws = nullptr;
+      hipError_t e = launch_w4a16_gemm(h, st);
+      return e != hipSuccess ? e : launch_w4a16_gemm(t, st);
+    }
+  }
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
   GemmArgs g = a;
   g.ksplit = 1;
@@ -1031,8 +1078,18 @@ hipError_t launch_bf16_gemm(const GemmArgs& a, int pipe, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
   // buffer loads and stores address the operands and the output with 32-bit byte offsets
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K * 2 >= (1ull << 31) ||
-      (uint64_t)a.M * a.N * 2 >= (1ull << 31))
+      (uint64_t)a.M * (a.ldy ? a.ldy : a.N) * 2 >= (1ull << 31))
     return hipErrorInvalidValue;
+  if (a.split_ws && !a.ldy && pipe == 2) {
+    // a little more than whole rounds of tiles: the whole rounds as they are, the rest cut along K
+    const uint32_t n1 = tile_tail_cols(a.M, a.N, a.K, a.epi);
+    if (n1) {
+      GemmArgs h = column_block(a, 0, n1, 16, false), t = column_block(a, n1, a.N - n1, 16, false);
+      h.split_ws = nullptr;
+      hipError_t e = launch_bf16_gemm(h, pipe, st);
+      return e != hipSuccess ? e : launch_bf16_gemm(t, pipe, st);
+    }
+  }
   CeEpilogue ce = {nullptr, nullptr, nullptr, 1, 1, 1};
   GemmArgs g = a;
   g.ksplit = 1;

@@ -47,7 +47,9 @@ __global__ __launch_bounds__(256, 1) void wide_gemm_kernel(GemmArgs a) {
                      (int)((uint64_t)a.M * K * 2), 0x00020000};
   const i32x4 rw4 = {(int)(uint32_t)(uintptr_t)a.w, (int)(uint32_t)((uintptr_t)a.w >> 32),
                      (int)((uint64_t)a.N * K * 2), 0x00020000};
-  const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(a.y, 0, (int)((uint64_t)a.M * a.N * 2), 0x00020000);
+  const uint32_t ldy = a.ldy ? a.ldy : a.N;        // row stride of y and resid (a column block of a wider matrix)
+  const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(
+      a.y, 0, (int)(((uint64_t)(a.M - 1) * ldy + a.N) * 2), 0x00020000);
   const uint32_t lds_wave = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds + wave * 1024u;
   unsigned char* const lds_a = lds;
   unsigned char* const lds_b = lds + 2 * TILE_BYTES;
@@ -267,10 +269,11 @@ __global__ __launch_bounds__(256, 1) void wide_gemm_kernel(GemmArgs a) {
       const bf16_t* bias = (const bf16_t*)a.bias;
       const bf16_t* resid = (const bf16_t*)a.resid;
       pend_col = n0 + wn * 128u + fhalf * 8u;
-      pend_base = (mrow * a.N + pend_col) * 2u;
-      pend_istride = 32u * a.N * 2u;
+      pend_base = (mrow * ldy + pend_col) * 2u;
+      pend_istride = 32u * ldy * 2u;
       const __amdgpu_buffer_rsrc_t rr_ = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<bf16_t*>((a.epi & EPI_RESIDUAL) ? resid : (const bf16_t*)a.y), 0, (int)((uint64_t)a.M * a.N * 2), 0x00020000);
+          const_cast<bf16_t*>((a.epi & EPI_RESIDUAL) ? resid : (const bf16_t*)a.y), 0,
+          (int)(((uint64_t)(a.M - 1) * ldy + a.N) * 2), 0x00020000);
       auto resid_of = [&](int u) {
         const int i = u >> 3, j = (u >> 1) & 3, bp = u & 1;
         const bool ok = pend_col + j * 32 + bp * 16 < a.N && (a.epi & EPI_RESIDUAL);
@@ -371,9 +374,10 @@ hipError_t launch_bf16_gemm_wide(const GemmArgs& a, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
   // buffer loads and stores address the operands and the output with 32-bit byte offsets; K in whole groups
   if ((uint64_t)a.M * a.K * 2 >= (1ull << 31) || (uint64_t)a.N * a.K * 2 >= (1ull << 31) ||
-      (uint64_t)a.M * a.N * 2 >= (1ull << 31) || a.K % 128 != 0 || a.K == 0)
+      (uint64_t)a.M * (a.ldy ? a.ldy : a.N) * 2 >= (1ull << 31) || a.K % 128 != 0 || a.K == 0)
     return hipErrorInvalidValue;
   if (a.epi & EPI_SWIGLU) return hipErrorInvalidValue;      // the 512-thread kernel's epilogue
+  if (a.ldy && (a.epi & EPI_ROPE)) return hipErrorInvalidValue;   // a column block has no thirds
   const uint64_t out_bytes = (uint64_t)a.M * a.N * 2;
   const uint32_t wgs = gemm_workgroups(a.M, a.N);
   if (out_bytes >= WIDE_NT_MIN_BYTES) wide_gemm_kernel<2><<<wgs, 256, LDS_BYTES + 1024, st>>>(a);

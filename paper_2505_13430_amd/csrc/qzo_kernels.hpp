@@ -57,6 +57,8 @@ struct GemmArgs {
                         // hold pass_stride + M rows, the rows in between are padding); 0: at row M
   uint32_t flip_row;    // set by the launcher for the tile kernel: rows from here on take -eps_signed (0: none)
   uint32_t M, N, K;
+  uint32_t ldy;         // row stride of y and resid in elements when the call covers a column block of a wider
+                        // matrix (0: N); plain epilogues only (bias, residual, ReLU)
   uint32_t row_base;
   uint32_t seed_lo, seed_hi;
   float eps_signed;
@@ -81,6 +83,10 @@ hipError_t launch_partial_reduce(const GemmArgs& a, const float* part, uint32_t 
 // Split-K of the int4 tile kernel when an M x N output has too few 256 x 256 tiles for the chip:
 // number of K slices (1: none) and k-tiles per slice.
 uint32_t tile_ksplit(uint32_t M, uint32_t N, uint32_t K, uint32_t* kt_per);
+// Column split of a launch whose output tiles are a little more than whole rounds of the chip: the first
+// tile_tail_cols(...) columns (whole rounds, ordinary launch) and the rest (at most half a round of tiles,
+// cut along K so that they fill the chip); 0: no split.  Plain epilogues only.
+uint32_t tile_tail_cols(uint32_t M, uint32_t N, uint32_t K, uint32_t epi);
 uint64_t tile_split_ws_floats(uint32_t M, uint32_t N, uint32_t K);
 // w = uint16 codes [N,K/8]; cb and s as above; N % 8 == 0, K % 128 == 0.
 hipError_t launch_codebook_gemm(const GemmArgs& a, hipStream_t st);

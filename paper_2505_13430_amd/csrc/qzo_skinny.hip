@@ -130,7 +130,7 @@ __device__ __forceinline__ float reduce_item(const GemmArgs& a, const float* __r
     v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xffff0000u);
     v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xffff0000u);
   }
-  const uint64_t o = (uint64_t)m * NO + f;
+  const uint64_t o = (uint64_t)m * (a.ldy ? a.ldy : NO) + f;
   if (a.epi & EPI_RESIDUAL) {
     const uint2 rr = *reinterpret_cast<const uint2*>((const bf16_t*)a.resid + o);
     v[0] += __uint_as_float(rr.x << 16); v[1] += __uint_as_float(rr.x & 0xffff0000u);

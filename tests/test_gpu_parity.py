@@ -1067,6 +1067,39 @@ def test_full_size_token_count_sampled_sequence_matches_oracle(oracle):
     dm.close()
 
 
+def test_llama_13b_width_column_tail_split(oracle):
+    """8 x 512 tokens through one decoder layer at Llama-2-13B widths: the o and down projections have
+    16 x 20 = 320 output tiles, a quarter more than one round of the chip, so their launch is cut in two: the
+    first 4096 columns as they are, the last 1024 along K in four slices whose partial sums a reduction adds
+    (bias-free, residual epilogue, K = 5120 and 13824).  Fused and expanded routes must agree bit for bit, and
+    one sequence of the batch must match the oracle run on that sequence alone."""
+    shape = dict(synth.SHAPES["llama-2-13b"], n_layers=1, vocab=1000)
+    om, dm = _models(oracle, shape, 55)
+    tok = synth.tokens(shape, 56)
+    B, S = tok.shape
+    assert (B, S) == (8, 512)
+    outs = []
+    for mode in (2, 1):
+        dm.set_int4_path(mode)
+        hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
+        loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+        qb.qzo_debug_forward(dm.handle, _dev(tok), 3, 1e-3, 1, dm.workspace(B, S), loss, hid)
+        outs.append((float(loss.item()), hid))
+    assert math.isfinite(outs[0][0]) and outs[0][0] == outs[1][0]
+    assert torch.equal(outs[0][1], outs[1][1])
+    b = 5
+    se = oracle.perturbed_scales(om, 3, np.float32(1e-3))
+    _, ref_hid = oracle.forward_loss(om, se, tok[b:b + 1], act_bf16=True, want_hidden=True)
+    _, exact_hid = oracle.forward_loss(om, se, tok[b:b + 1], act_bf16=False, want_hidden=True)
+    got = outs[0][1][b * S:(b + 1) * S].float().cpu().numpy().astype(np.float64)
+    rms = math.sqrt((ref_hid ** 2).mean())
+    err = np.abs(got - ref_hid)
+    floor_rms = math.sqrt(((exact_hid - ref_hid) ** 2).mean())
+    assert math.sqrt((err ** 2).mean()) <= 2 * floor_rms + 2e-3 * rms
+    assert err.max() <= 2 * np.abs(exact_hid - ref_hid).max() + 2e-2 * rms
+    dm.close()
+
+
 def test_opt_width_token_count_routes_agree_bit_for_bit():
     """16 x 256 tokens through one decoder layer at OPT-1.3B widths: on the expanded route the qkv (bias) and
     fc1 (bias + ReLU) GEMMs have more output tiles than compute units, so the one-wavefront-per-SIMD kernel
