@@ -43,7 +43,7 @@ __device__ __forceinline__ void rope_pair8(uint32_t (&a)[4], uint32_t (&b)[4], c
 template <int DH, bool ROPE, bool LONG>
 __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restrict__ qkv, uint32_t S,
                                                            uint32_t n_heads, bf16_t* __restrict__ out,
-                                                           const float2* __restrict__ rope) {
+                                                           const float2* __restrict__ rope, uint32_t walk) {
   constexpr int KB = 64;             // keys per tile
   constexpr int KT = DH / 16;        // k-steps of the score MFMA
   constexpr int DT = DH / 32;        // 32-wide slices of the head for the PV MFMA
@@ -170,14 +170,20 @@ __global__ __launch_bounds__(256, 2) void attention_kernel(const bf16_t* __restr
   // other buffer at the start of tile kb (every wavefront is past the barrier, so tile kb-1 has been read)
   // and has landed when each wavefront's own loads are back and the next barrier is passed.  One barrier
   // per tile either way.
-  // A grid of one workgroup per (batch, head) (gridDim.x == 1) walks the head's query blocks itself, late
-  // (heavy) blocks first: every workgroup then has the same work and the chip is filled once; otherwise a
-  // workgroup serves the one query block its launch index names.
+  // walk != 0: the workgroups of a (batch, head) walk its query blocks themselves, late (heavy) blocks
+  // first.  gridDim.x == 1: one workgroup takes them all.  gridDim.x == 2: two workgroups share them in
+  // snake order (blocks n-1 | n-2, n-3 | n-4, n-5 | ... from the heavy end: equal work for 4 blocks);
+  // the launch-index remap above puts the two on one XCD in neighbouring slots, they start together
+  // and ask for the same K and V tiles at about the same time, so the second one's loads hit the L2
+  // (the kernel is bound by what crosses from memory into the L2s, not by its arithmetic).
+  // walk == 0: a workgroup serves the one query block its launch index names.
   const uint32_t nqb = (S + 127) / 128;
   constexpr bool via_lds = LONG;               // more than one query block per head
-  const uint32_t n_it = (LONG && gridDim.x == 1) ? nqb : 1u;
+  const bool walk_ = LONG && walk != 0u;
+  const uint32_t n_it = walk_ ? nqb : 1u;
   for (uint32_t it = 0; it < n_it; ++it) {
-  const uint32_t q0 = ((LONG && gridDim.x == 1) ? nqb - 1 - it : gridDim.x - 1 - bx) * 128;
+  if (walk_ && gridDim.x == 2u && (((it + 1u) >> 1) & 1u) != bx) continue;
+  const uint32_t q0 = (walk_ ? nqb - 1 - it : gridDim.x - 1 - bx) * 128;
   const uint32_t qq = q0 + wave * 32 + lrow;            // this lane's query
   const uint32_t qc = min(qq, S - 1);
   bf16x8 qf[KT];
@@ -435,7 +441,8 @@ hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_
                             uint32_t dh, void* out, const float* rope, hipStream_t st) {
   // the direct loads address qkv with 32-bit byte offsets and use an offset near 2^32 as "out of range"
   if ((uint64_t)B * S * 3 * n_heads * dh * 2 >= (1ull << 31)) return hipErrorInvalidValue;
-  // one workgroup per (batch, head) when those alone fill the chip twice over (two workgroups fit a CU)
+  // The (batch, head) pairs alone fill the chip twice over (two workgroups fit a CU): their workgroups walk
+  // the query blocks, two workgroups per pair from three query blocks on, else one.
   static int n_cu = 0;
   if (n_cu == 0) {
     int dev = 0;
@@ -445,20 +452,22 @@ hipError_t launch_attention(const void* qkv, uint32_t B, uint32_t S, uint32_t n_
   }
   const bool lng = S > 128 && !rope;           // more than one query block per head: the long-sequence paths
   const bool per_head = (uint64_t)n_heads * B >= 2ull * (uint64_t)n_cu && lng;
-  dim3 grid(per_head ? 1 : (S + 127) / 128, n_heads, B);
+  const bool pair = per_head && S > 256;
+  const uint32_t walk = per_head ? 1u : 0u;
+  dim3 grid(pair ? 2 : (per_head ? 1 : (S + 127) / 128), n_heads, B);
   const float2* tb = (const float2*)rope;
   if (dh == 128 && rope)
-    attention_kernel<128, true, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<128, true, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb, walk);
   else if (dh == 128 && lng)
-    attention_kernel<128, false, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<128, false, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb, walk);
   else if (dh == 128)
-    attention_kernel<128, false, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<128, false, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb, walk);
   else if (dh == 64 && rope)
-    attention_kernel<64, true, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<64, true, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb, walk);
   else if (dh == 64 && lng)
-    attention_kernel<64, false, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<64, false, true><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb, walk);
   else if (dh == 64)
-    attention_kernel<64, false, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb);
+    attention_kernel<64, false, false><<<grid, 256, 0, st>>>((const bf16_t*)qkv, S, n_heads, (bf16_t*)out, tb, walk);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
