@@ -1123,19 +1123,33 @@ def test_opt_width_token_count_routes_agree_bit_for_bit():
 
 @pytest.mark.parametrize("S", [256, 300])
 def test_attention_per_head_walk_head_size_64_sampled_sequence_matches_oracle(oracle, S):
-    """16 sequences x 32 heads of 64 features fill the chip twice over, so one attention workgroup walks all
-    query blocks of its (batch, head): 2 blocks at 256 positions, 3 at 300 (the last one ragged, 44 rows).
+    """16 sequences x 32 heads of 64 features fill the chip twice over, so the attention workgroups walk the
+    query blocks of their (batch, head) themselves: one workgroup the 2 blocks at 256 positions, two
+    workgroups in snake order the 3 at 300 (the last one ragged, 44 rows).
     One decoder layer at OPT-1.3B widths (LayerNorm, bias, ReLU, learned positions); the oracle runs one
     sequence of the batch alone, whose final hidden states are compared with the batch's rows."""
     shape = dict(synth.SHAPES["opt-1.3b"], n_layers=1, vocab=1000, max_seq=S, seq=S)
+    _walk_case(oracle, shape, 16, S, 6)
+
+
+def test_attention_shared_walk_five_blocks_odd_pair_count_matches_oracle(oracle):
+    """86 sequences x 6 heads of 64 features: 516 (batch, head) pairs, not a multiple of the 8 XCDs (the launch
+    index is then not remapped), 640 positions = 5 query blocks, which two workgroups share as 4, 1, 0 | 3, 2.
+    One decoder layer (OPT kind, d_model 384); a late sequence of the batch against the oracle."""
+    S = 640
+    shape = dict(synth.SHAPES["tiny_opt"], n_layers=1, d_model=384, n_heads=6, d_ffn=1024, vocab=1000,
+                 max_seq=S, seq=S, batch=86)
+    _walk_case(oracle, shape, 86, S, 85)
+
+
+def _walk_case(oracle, shape, n_seq, S, b):
     om, dm = _models(oracle, shape, 91)
     tok = synth.tokens(shape, 92)
     B = tok.shape[0]
-    assert tok.shape == (16, S)
+    assert tok.shape == (n_seq, S)
     hid = torch.zeros((B * S, shape["d_model"]), dtype=torch.bfloat16, device=DEV)
     loss = torch.zeros(1, dtype=torch.float32, device=DEV)
     qb.qzo_debug_forward(dm.handle, _dev(tok), 5, 1e-3, -1, dm.workspace(B, S), loss, hid)
-    b = 6
     se = oracle.perturbed_scales(om, 5, np.float32(-1e-3))
     _, ref_hid = oracle.forward_loss(om, se, tok[b:b + 1], act_bf16=True, want_hidden=True)
     _, exact_hid = oracle.forward_loss(om, se, tok[b:b + 1], act_bf16=False, want_hidden=True)
