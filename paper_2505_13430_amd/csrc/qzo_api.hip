@@ -47,6 +47,7 @@ struct Linear {           // one quantized linear of a layer
 struct Workspace {
   unsigned char *h, *a, *qkv, *att, *ff, *act;
   float *ce_part, *tgt, *rowloss, *losses, *skinny;
+  float *xs_a, *xs_act;     // few-token path: block sums of the norm output and of the MLP's hidden activation
   float* split;             // K-slice partial sums of the int4 tile kernel (too few tiles for the chip)
   unsigned char* wexp;      // one linear's expanded bf16 weights (expand-then-multiply paths)
   float* se;                // expand-then-multiply of int4 / NormalFloat-4: every perturbed scale of the model, fp32
@@ -236,6 +237,8 @@ Workspace carve(const qzo_model* m, uint32_t batch, uint32_t seq, void* base) {
       sk = std::max<uint64_t>(sk, skinny_ws_floats((uint32_t)M, m->lin[i].N, m->lin[i].K));
   w.skinny = (float*)take(sk * 4);
   if (sk == 0) w.skinny = nullptr;
+  w.xs_a = sk ? (float*)take((d / 128) * M * 4) : nullptr;
+  w.xs_act = sk ? (float*)take((F / 128) * M * 4) : nullptr;
   // more tokens than that but still too few output tiles for the chip: split-K partial sums
   uint64_t sp = 0;
   if ((M1 > SKINNY_MAX_M && int4) || c.act_order || c.quant == 3 || (c.quant == 1 && M1 >= EXPAND_MIN_M_CODEBOOK))
@@ -365,6 +368,9 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   auto other = [&](hipError_t e) { return e; };
   (void)other;
   bool rope_fused = false;     // set by a qkv linear whose GEMM applied the rotary embedding itself
+  // few-token linears with more than 16 tokens per pass take the block sums of their input from its producer
+  const bool few = w.skinny && M1 > 16 && M1 <= SKINNY_MAX_M && (c.quant == 0 || c.quant == 2) && !c.act_order;
+  float* const xs_a = few ? w.xs_a : nullptr;
   for (uint32_t l = 0; l < c.n_layers; ++l) {
     const qzo_buf* T = &m->T[m->first_layer_tensor + (size_t)l * m->tensors_per_layer];
     const uint64_t layer_off = (uint64_t)l * m->scales_per_layer;
@@ -393,6 +399,10 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       g.s_fp16 = c.scale_fp16;
       g.skinny_ws = w.skinny;
       g.split_ws = w.split;
+      if (few) {     // the few-token kernel takes the block sums of its input from the kernel that wrote it
+        g.xsum = (li == 0 || li == 2) ? w.xs_a : (li == 3 ? w.xs_act : nullptr);
+        g.xsum_out = li == 2 ? w.xs_act : nullptr;
+      }
       if (c.act_order) {
         // a group index per column: scale and zero-point are looked up per weight while the perturbed
         // matrix is written out; the fused kernels, whose k-tile shares one scale per row, cannot serve it
@@ -499,22 +509,22 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
       QZO_HIP(cgemm(3, w.act, T[8].ptr_dev, T[9].ptr_dev, w.h, w.h, EPI_RESIDUAL));
     } else if (llama) {
       // attn_norm, wqkv, wo, ffn_norm, wgu, wdown (symmetric-table positions)
-      QZO_HIP(launch_rmsnorm(w.h, ti(0), M, d, c.norm_eps, w.a, st));
+      QZO_HIP(launch_rmsnorm(w.h, ti(0), M, d, c.norm_eps, w.a, st, xs_a));
       rope_fused = false;
       QZO_HIP(gemm(0, w.a, nullptr, nullptr, w.qkv, EPI_ROPE));
       if (!rope_fused && !rope_in_attention) QZO_HIP(launch_rope(w.qkv, w.rope, M, seq, P, d, H, st));
       QZO_HIP(attention(rope_fused || !rope_in_attention));
       QZO_HIP(gemm(1, w.att, nullptr, w.h, w.h, EPI_RESIDUAL));
-      QZO_HIP(launch_rmsnorm(w.h, ti(3), M, d, c.norm_eps, w.a, st));
+      QZO_HIP(launch_rmsnorm(w.h, ti(3), M, d, c.norm_eps, w.a, st, xs_a));
       QZO_HIP(gemm(2, w.a, nullptr, nullptr, w.act, EPI_SWIGLU));
       QZO_HIP(gemm(3, w.act, nullptr, w.h, w.h, EPI_RESIDUAL));
     } else {
       // ln1_g, ln1_b, wqkv, bqkv, wo, bo, ln2_g, ln2_b, wfc1, bfc1, wfc2, bfc2 (symmetric-table positions)
-      QZO_HIP(launch_layernorm(w.h, ti(0), ti(1), M, d, c.norm_eps, w.a, st));
+      QZO_HIP(launch_layernorm(w.h, ti(0), ti(1), M, d, c.norm_eps, w.a, st, xs_a));
       QZO_HIP(gemm(0, w.a, ti(3), nullptr, w.qkv, EPI_BIAS));
       QZO_HIP(attention(true));
       QZO_HIP(gemm(1, w.att, ti(5), w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
-      QZO_HIP(launch_layernorm(w.h, ti(6), ti(7), M, d, c.norm_eps, w.a, st));
+      QZO_HIP(launch_layernorm(w.h, ti(6), ti(7), M, d, c.norm_eps, w.a, st, xs_a));
       QZO_HIP(gemm(2, w.a, ti(9), nullptr, w.ff, EPI_BIAS | EPI_RELU));
       QZO_HIP(gemm(3, w.ff, ti(11), w.h, w.h, EPI_BIAS | EPI_RESIDUAL));
     }

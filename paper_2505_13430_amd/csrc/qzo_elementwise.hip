@@ -508,7 +508,8 @@ template <bool LAYERNORM, bool CACHED>
 __global__ __launch_bounds__(256) void norm_kernel(const bf16_t* __restrict__ x,
                                                    const bf16_t* __restrict__ gain,
                                                    const bf16_t* __restrict__ bias, uint32_t d,
-                                                   float eps, bf16_t* __restrict__ y) {
+                                                   float eps, bf16_t* __restrict__ y,
+                                                   float* __restrict__ xsum_t) {
   __shared__ float red[4];
   const bf16_t* xr = x + (uint64_t)blockIdx.x * d;
   bf16_t* yr = y + (uint64_t)blockIdx.x * d;
@@ -560,10 +561,11 @@ __global__ __launch_bounds__(256) void norm_kernel(const bf16_t* __restrict__ x,
 #pragma unroll
   for (uint32_t i = 0; i < passes; ++i) {
     const uint32_t c = threadIdx.x + 256u * i;
+    uint32_t o[4] = {0, 0, 0, 0};
     if (c < cpr) {
       const uint4 v = chunk(i, c);
       uint4 gq = *reinterpret_cast<const uint4*>(gain + c * 8);
-      uint32_t a[4] = {v.x, v.y, v.z, v.w}, g[4] = {gq.x, gq.y, gq.z, gq.w}, b[4] = {0, 0, 0, 0}, o[4];
+      uint32_t a[4] = {v.x, v.y, v.z, v.w}, g[4] = {gq.x, gq.y, gq.z, gq.w}, b[4] = {0, 0, 0, 0};
       if (LAYERNORM) {
         uint4 bq = *reinterpret_cast<const uint4*>(bias + c * 8);
         b[0] = bq.x; b[1] = bq.y; b[2] = bq.z; b[3] = bq.w;
@@ -580,24 +582,42 @@ __global__ __launch_bounds__(256) void norm_kernel(const bf16_t* __restrict__ x,
       }
       *reinterpret_cast<uint4*>(yr + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
     }
+    if (xsum_t) {
+      // block sums of the row's output for a few-token linear that reads it: the 16 chunks of 128 features
+      // sit in 16 consecutive lanes (every lane takes part: lanes beyond the row add zero)
+      float lo = 0.0f, hi = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        lo += __uint_as_float(o[j] << 16);
+        hi += __uint_as_float(o[j] & 0xffff0000u);
+      }
+      float sx = lo + hi;
+      sx += __shfl_xor(sx, 1, 64); sx += __shfl_xor(sx, 2, 64);
+      sx += __shfl_xor(sx, 4, 64); sx += __shfl_xor(sx, 8, 64);
+      if (c < cpr && (c & 15u) == 0u) xsum_t[(uint64_t)(c >> 4) * gridDim.x + blockIdx.x] = sx;
+    }
   }
 }
 hipError_t launch_rmsnorm(const void* x, const void* gain, uint32_t M, uint32_t d, float eps,
-                          void* y, hipStream_t st) {
+                          void* y, hipStream_t st, float* xsum_t) {
+  if (d % 128) xsum_t = nullptr;
   if (d <= 8192)
-    norm_kernel<false, true><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, nullptr, d, eps, (bf16_t*)y);
+    norm_kernel<false, true><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, nullptr, d, eps, (bf16_t*)y,
+                                                xsum_t);
   else
-    norm_kernel<false, false><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, nullptr, d, eps, (bf16_t*)y);
+    norm_kernel<false, false><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, nullptr, d, eps, (bf16_t*)y,
+                                                 xsum_t);
   return hipGetLastError();
 }
 hipError_t launch_layernorm(const void* x, const void* gain, const void* bias, uint32_t M,
-                            uint32_t d, float eps, void* y, hipStream_t st) {
+                            uint32_t d, float eps, void* y, hipStream_t st, float* xsum_t) {
+  if (d % 128) xsum_t = nullptr;
   if (d <= 8192)
     norm_kernel<true, true><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, (const bf16_t*)bias, d, eps,
-                                               (bf16_t*)y);
+                                               (bf16_t*)y, xsum_t);
   else
     norm_kernel<true, false><<<M, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)gain, (const bf16_t*)bias, d, eps,
-                                                (bf16_t*)y);
+                                                (bf16_t*)y, xsum_t);
   return hipGetLastError();
 }
 

@@ -64,6 +64,11 @@ struct GemmArgs {
   float eps_signed;
   uint32_t epi;
   uint32_t s_fp16;      // int4 formats: s holds fp16 instead of bf16
+  // Few-token path: block sums X[g][row] = sum of x[row, 128 g .. 128 g + 127] (fp32, [K/128][rows], rows = M or
+  // 2 M when dual), delivered by the kernel that wrote x (null: the kernel sums them itself), and the same for
+  // the output y of the K-slice reduction ([N_out/128][rows], N_out % 128 == 0; null: not wanted).
+  const float* xsum;
+  float* xsum_out;
 };
 hipError_t launch_w4a16_gemm(const GemmArgs& a, hipStream_t st);
 // Order of the rows of an expanded (bf16) weight matrix: natural; the fused-SwiGLU consumer's tile order;
@@ -173,10 +178,11 @@ hipError_t launch_sum_partials(const float* partials, uint32_t n, float* out, hi
 // pass_stride: rows per pass of a stacked forward (M for a single pass); rows m % pass_stride >= tok_rows get zeros.
 hipError_t launch_embed(const int32_t* tok, uint32_t tok_rows, uint32_t pass_stride, const void* tok_emb,
                         const void* pos_emb, uint32_t M, uint32_t S, uint32_t d, void* h, hipStream_t st);
+// xsum_t (nullable, d % 128 == 0): receives the block sums of the output, [d/128][M] fp32 (see GemmArgs::xsum)
 hipError_t launch_rmsnorm(const void* x, const void* gain, uint32_t M, uint32_t d, float eps,
-                          void* y, hipStream_t st);
+                          void* y, hipStream_t st, float* xsum_t = nullptr);
 hipError_t launch_layernorm(const void* x, const void* gain, const void* bias, uint32_t M,
-                            uint32_t d, float eps, void* y, hipStream_t st);
+                            uint32_t d, float eps, void* y, hipStream_t st, float* xsum_t = nullptr);
 hipError_t launch_rope_table(float* table, uint32_t max_seq, uint32_t dh, float theta,
                              hipStream_t st);
 hipError_t launch_rope(void* qkv, const float* table, uint32_t M, uint32_t S, uint32_t pass_stride, uint32_t d,

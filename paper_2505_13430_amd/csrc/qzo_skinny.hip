@@ -93,9 +93,9 @@ __device__ __forceinline__ uint32_t x_lds_off(uint32_t row, uint32_t chunk) {   
 
 // One output item of the slice reduction: 4 consecutive output features f .. f+3 of token m.
 // Adds the K-slice partials in slice order and applies the epilogue; returns the sum of the squares
-// of the stored bf16 values.
+// of the stored bf16 values (and their plain sum in `sum`).
 __device__ __forceinline__ float reduce_item(const GemmArgs& a, const float* __restrict__ part, uint32_t ksplit,
-                                             uint32_t m, uint32_t f) {
+                                             uint32_t m, uint32_t f, float& sum) {
   const bool swiglu = (a.epi & EPI_SWIGLU) != 0;
   const uint32_t NO = swiglu ? a.N >> 1 : a.N;
   auto load4 = [&](uint32_t ks, uint32_t col) {
@@ -146,6 +146,7 @@ __device__ __forceinline__ float reduce_item(const GemmArgs& a, const float* __r
   *reinterpret_cast<uint2*>((bf16_t*)a.y + o) = out;
   const float q0 = __uint_as_float(out.x << 16), q1 = __uint_as_float(out.x & 0xffff0000u);
   const float q2 = __uint_as_float(out.y << 16), q3 = __uint_as_float(out.y & 0xffff0000u);
+  sum = (q0 + q2) + (q1 + q3);
   return q0 * q0 + q1 * q1 + q2 * q2 + q3 * q3;
 }
 
@@ -155,13 +156,16 @@ __device__ __forceinline__ float reduce_item(const GemmArgs& a, const float* __r
 // the -eps pass (M <= 16 MT).
 // XSUM_BY_MFMA (one token tile, at most 16 tokens per pass: the stacked and the separate passes of
 // a step then sum alike, bit for bit): the block sums come from the matrix unit, see below.
-template <int MT, bool DUAL, bool ZP, bool XSUM_BY_MFMA>
+// XIN: the block sums come from memory (GemmArgs::xsum, written by the kernel that wrote x); a pass's 8 groups
+// x tile rows are fetched one pass ahead, one or two values per thread, and handed on through the LDS.
+template <int MT, bool DUAL, bool ZP, bool XSUM_BY_MFMA, bool XIN>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* part,
                                                              uint32_t groups_per_split) {
   constexpr uint32_t TPP = DUAL ? MT * 16 : MT * 32;      // tile rows per pass
   __shared__ __attribute__((aligned(16))) unsigned char xs[2][MT * 32 * 256];
   __shared__ __attribute__((aligned(16))) float xsum[2][MT * 32];          // X[m,g] of the block in the same buffer
   __shared__ __attribute__((aligned(16))) unsigned char wt[4][32 * 128];   // per wavefront: a round of its 32 rows
+  __shared__ __attribute__((aligned(16))) float xin[2][XIN ? SK_WD : 1][MT * 32];   // XIN: X[g][tile row] of two passes
   const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
   const uint32_t lrow = lane & 31u, half = lane >> 5;     // MFMA operand: row of the wavefront, half of the k-step
   const uint32_t lr = lane >> 3, lc = lane & 7u;          // loads: row within an instruction's 8 rows, 16-byte chunk
@@ -205,6 +209,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
     // activation staging: a group's block is MT*32 rows x 16 chunks of 16 bytes; a thread moves MT*2 chunks.
     // Tile row -> row of x: clamped to the pass's last token.
     static_assert(!XSUM_BY_MFMA || MT == 1, "no registers for it with two token tiles");
+    static_assert(!(XIN && XSUM_BY_MFMA), "one source of the block sums");
     constexpr int NX = MT * 2;
     uint32_t xoff[NX];
 #pragma unroll
@@ -236,7 +241,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
     _Pragma("unroll") for (int i = 0; i < NX; ++i) {                                         \
       const uint32_t c = t + 256u * i, row = c >> 4, ch = c & 15u;                           \
       *reinterpret_cast<u32x4*>(xs[BUF] + x_lds_off(row, ch)) = permute8(xr[SLOT][i]);       \
-      if (!XSUM_BY_MFMA) {                                                                   \
+      if (!XSUM_BY_MFMA && !XIN) {                                                           \
         float sx_ = sum8_bf16(xr[SLOT][i]);                                                  \
         sx_ += __shfl_xor(sx_, 1, 64); sx_ += __shfl_xor(sx_, 2, 64);                        \
         sx_ += __shfl_xor(sx_, 4, 64); sx_ += __shfl_xor(sx_, 8, 64);                        \
@@ -293,6 +298,29 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
     }                                                                                        \
   } while (0)
 
+    // XIN: element e = t + 256 i of a pass is (group e / (32 MT), tile row e % (32 MT)); X is [K/128][rows]
+    const uint32_t xrows = DUAL ? 2 * a.M : a.M;
+    const __amdgpu_buffer_rsrc_t rxs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(XIN ? a.xsum : (const float*)a.x), 0, (int)((uint64_t)xrows * ngrp * 4), 0x00020000);
+    uint32_t xin_off[MT];
+    float xin_next[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const uint32_t e = t + 256u * i, row = e % (MT * 32u);
+      const uint32_t xrow = DUAL ? (row / TPP) * a.M + min(row % TPP, a.M - 1) : min(row, a.M - 1);
+      xin_off[i] = ((e / (MT * 32u)) * xrows + xrow) * 4u;
+      xin_next[i] = 0.0f;
+    }
+#define QZO_SK_XINLOAD(G_)                                                                   \
+  do {                                                                                       \
+    if (XIN) {                                                                               \
+      _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                       \
+        const uint32_t gi_ = (G_) + (t + 256u * i) / (MT * 32u);                             \
+        xin_next[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(                  \
+            rxs, (int)(gi_ < g1 ? xin_off[i] + (G_) * xrows * 4u : OUT_OF_RANGE), 0, 0));    \
+      }                                                                                      \
+    }                                                                                        \
+  } while (0)
     union { bf16x8 v; uint32_t u[4]; } ones;
     ones.u[0] = ones.u[1] = ones.u[2] = ones.u[3] = 0x3f803f80u;
     // noise: one Philox counter per 8 groups, one Box-Muller pair per 2 groups
@@ -305,6 +333,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
     QZO_SK_XLOAD(0, g0);
     QZO_SK_WLOAD(0, g0);
     QZO_SK_SLOAD(g0);
+    QZO_SK_XINLOAD(g0);
     QZO_SK_XLOAD(1, g0 + 1);
     QZO_SK_WLOAD(1, g0 + 2);
 #pragma unroll
@@ -319,6 +348,12 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
       sv = sv_next;
       zv[0] = zv_next[0]; zv[1] = zv_next[1];
       QZO_SK_SLOAD(gb + SK_WD);
+      const uint32_t xpp = ((gb - g0) / SK_WD) & 1u;      // XIN: this pass's LDS buffer (visible after the barrier of d = 0)
+      if (XIN) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i) (&xin[xpp][0][0])[t + 256u * i] = xin_next[i];
+      }
+      QZO_SK_XINLOAD(gb + SK_WD);
 #pragma unroll
       for (int d = 0; d < SK_WD; ++d) {
         const uint32_t g = gb + d;
@@ -372,7 +407,8 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
           for (int m = 0; m < MT; ++m)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-              const float4 xg = XSUM_BY_MFMA
+              const float4 xg = XIN ? *reinterpret_cast<const float4*>(&xin[xpp][XIN ? d : 0][m * 32 + 8 * b + 4 * half])
+                                : XSUM_BY_MFMA
                                     ? make_float4(px[4 * b], px[4 * b + 1], px[4 * b + 2], px[4 * b + 3])
                                     : *reinterpret_cast<const float4*>(&xsum[buf][m * 32 + 8 * b + 4 * half]);
               const float se = !DUAL ? se_p : ((MT == 2 ? m == 1 : b >= 2) ? se_m : se_p);
@@ -389,6 +425,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
 #undef QZO_SK_WLOAD
 #undef QZO_SK_WSTORE
 #undef QZO_SK_SLOAD
+#undef QZO_SK_XINLOAD
 
     // partial sums of this slice
     const uint32_t rows = DUAL ? 2 * a.M : a.M;
@@ -415,8 +452,16 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(GemmArgs a, const fl
                                                             uint32_t ksplit) {
   const uint32_t NO = (a.epi & EPI_SWIGLU) ? a.N >> 1 : a.N;                  // output width
   const uint32_t q = blockIdx.x * 256 + threadIdx.x, per_row = NO >> 2;
-  float ssq = 0.0f;
-  if (q < a.M * per_row) ssq = reduce_item(a, part, ksplit, q / per_row, (q % per_row) * 4);
+  float ssq = 0.0f, sx = 0.0f;
+  const bool own = q < a.M * per_row;
+  if (own) ssq = reduce_item(a, part, ksplit, q / per_row, (q % per_row) * 4, sx);
+  if (a.xsum_out) {
+    // block sums of the output for a few-token linear that reads it: 128 features = 32 consecutive
+    // threads of one token (the output width is a multiple of 128)
+    sx += __shfl_xor(sx, 1, 64); sx += __shfl_xor(sx, 2, 64); sx += __shfl_xor(sx, 4, 64);
+    sx += __shfl_xor(sx, 8, 64); sx += __shfl_xor(sx, 16, 64);
+    if (own && (threadIdx.x & 31u) == 0u) a.xsum_out[(uint64_t)((q % per_row) >> 5) * a.M + q / per_row] = sx;
+  }
   if (a.epi & EPI_SUMSQ) {
     __shared__ float red[4];
     ssq = wave_sum(ssq);
@@ -452,10 +497,20 @@ uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi) {
 // floats; with EPI_SUMSQ a.partials holds skinny_reduce_blocks floats.
 template <int MT, bool DUAL, bool XMF>
 static void skinny_launch(const GemmArgs& a, dim3 grid, float* ws, uint32_t per, hipStream_t st) {
+  // (with at most 16 tokens per pass the matrix unit's block sums cost less than fetching them)
+  if constexpr (!XMF) {
+    if (a.xsum) {
+      if (a.zp)
+        skinny_gemm_kernel<MT, DUAL, true, false, true><<<grid, 256, 0, st>>>(a, ws, per);
+      else
+        skinny_gemm_kernel<MT, DUAL, false, false, true><<<grid, 256, 0, st>>>(a, ws, per);
+      return;
+    }
+  }
   if (a.zp)
-    skinny_gemm_kernel<MT, DUAL, true, XMF><<<grid, 256, 0, st>>>(a, ws, per);
+    skinny_gemm_kernel<MT, DUAL, true, XMF, false><<<grid, 256, 0, st>>>(a, ws, per);
   else
-    skinny_gemm_kernel<MT, DUAL, false, XMF><<<grid, 256, 0, st>>>(a, ws, per);
+    skinny_gemm_kernel<MT, DUAL, false, XMF, false><<<grid, 256, 0, st>>>(a, ws, per);
 }
 hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
@@ -480,13 +535,16 @@ hipError_t launch_skinny_gemm(const GemmArgs& a, float* ws, hipStream_t st) {
   if (e != hipSuccess) return e;
   GemmArgs r = a;                               // the reduction sees the stacked rows as one matrix
   if (a.dual) r.M = 2 * a.M;
+  if (r.ldy || ((r.epi & EPI_SWIGLU) ? r.N >> 1 : r.N) % 128) r.xsum_out = nullptr;
   skinny_reduce_kernel<<<skinny_reduce_blocks(r.M, r.N, r.epi), 256, 0, st>>>(r, ws, ks);
   return hipGetLastError();
 }
 
 hipError_t launch_partial_reduce(const GemmArgs& a, const float* part, uint32_t ksplit, hipStream_t st) {
   if (a.M == 0 || a.N == 0) return hipSuccess;
-  skinny_reduce_kernel<<<skinny_reduce_blocks(a.M, a.N, a.epi), 256, 0, st>>>(a, part, ksplit);
+  GemmArgs r = a;
+  r.xsum_out = nullptr;                         // block sums are a service of the few-token path only
+  skinny_reduce_kernel<<<skinny_reduce_blocks(a.M, a.N, a.epi), 256, 0, st>>>(r, part, ksplit);
   return hipGetLastError();
 }
 

@@ -565,6 +565,10 @@ def test_update_at_real_tensor_sizes_bit_exact(oracle, rows, G, row_base):
 
 @pytest.mark.parametrize("name,batch,seq,eta", [("opt-1.3b", 1, 24, 1e-5), ("llama-2-7b", 1, 16, 1e-7),
                                                 ("llama-2-13b", 1, 16, 1e-7),      # few-token path
+                                                # few-token path with the block sums of the activations delivered
+                                                # by the norm and by the SwiGLU reduction: 24 tokens (stacked
+                                                # passes), 48 tokens (two passes, two token tiles)
+                                                ("llama-2-7b", 1, 24, 1e-7), ("llama-2-7b", 2, 24, 1e-7),
                                                 ("opt-1.3b", 3, 24, 1e-5), ("llama-2-7b", 3, 24, 1e-7)])
 def test_real_width_one_layer_step(oracle, name, batch, seq, eta):
     # depth-reduced copy: real widths (incl. the ragged OPT vocabulary), one layer, short batch.
