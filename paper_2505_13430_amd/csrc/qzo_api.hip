@@ -368,8 +368,8 @@ qzo_status forward(qzo_model* m, const int32_t* tok, uint32_t batch1, uint32_t s
   auto other = [&](hipError_t e) { return e; };
   (void)other;
   bool rope_fused = false;     // set by a qkv linear whose GEMM applied the rotary embedding itself
-  // few-token linears with more than 16 tokens per pass take the block sums of their input from its producer
-  const bool few = w.skinny && M1 > 16 && M1 <= SKINNY_MAX_M && (c.quant == 0 || c.quant == 2) && !c.act_order;
+  // few-token linears take the block sums of their input from its producer
+  const bool few = w.skinny && M1 <= SKINNY_MAX_M && (c.quant == 0 || c.quant == 2) && !c.act_order;
   float* const xs_a = few ? w.xs_a : nullptr;
   for (uint32_t l = 0; l < c.n_layers; ++l) {
     const qzo_buf* T = &m->T[m->first_layer_tensor + (size_t)l * m->tensors_per_layer];

@@ -158,8 +158,10 @@ __device__ __forceinline__ float reduce_item(const GemmArgs& a, const float* __r
 // a step then sum alike, bit for bit): the block sums come from the matrix unit, see below.
 // XIN: the block sums come from memory (GemmArgs::xsum, written by the kernel that wrote x); a pass's 8 groups
 // x tile rows are fetched one pass ahead, one or two values per thread, and handed on through the LDS.
+// (One token tile with XIN fits 168 registers: three workgroups per CU, which holds the 688 workgroups of a
+// 22016-row gate/up linear in one round.)
 template <int MT, bool DUAL, bool ZP, bool XSUM_BY_MFMA, bool XIN>
-__global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* part,
+__global__ __launch_bounds__(256, (MT == 1 && XIN) ? 3 : 2) void skinny_gemm_kernel(GemmArgs a, float* part,
                                                              uint32_t groups_per_split) {
   constexpr uint32_t TPP = DUAL ? MT * 16 : MT * 32;      // tile rows per pass
   __shared__ __attribute__((aligned(16))) unsigned char xs[2][MT * 32 * 256];
@@ -221,8 +223,9 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(GemmArgs a, float* 
     // The counter of outstanding loads retires in issue order: waiting for a load waits for every
     // older one.  So the activation blocks are requested as far ahead as the weights (four groups);
     // a block requested just in time would cut the weights' lead down to its own.
-    // With two token tiles the registers do not allow it: two groups ahead there.
-    constexpr int XD = MT == 1 ? 4 : 2;
+    // With two token tiles the registers do not allow it: two groups ahead there, and also where one tile
+    // runs three workgroups per CU (XIN).
+    constexpr int XD = (MT == 1 && !XIN) ? 4 : 2;
     u32x4 xr[XD][NX];           // the next XD blocks on their way: block g0 + j in slot j % XD
 #define QZO_SK_XLOAD(SLOT, G_)                                                               \
   do {                                                                                       \
@@ -497,15 +500,12 @@ uint32_t skinny_reduce_blocks(uint32_t M, uint32_t N, uint32_t epi) {
 // floats; with EPI_SUMSQ a.partials holds skinny_reduce_blocks floats.
 template <int MT, bool DUAL, bool XMF>
 static void skinny_launch(const GemmArgs& a, dim3 grid, float* ws, uint32_t per, hipStream_t st) {
-  // (with at most 16 tokens per pass the matrix unit's block sums cost less than fetching them)
-  if constexpr (!XMF) {
-    if (a.xsum) {
-      if (a.zp)
-        skinny_gemm_kernel<MT, DUAL, true, false, true><<<grid, 256, 0, st>>>(a, ws, per);
-      else
-        skinny_gemm_kernel<MT, DUAL, false, false, true><<<grid, 256, 0, st>>>(a, ws, per);
-      return;
-    }
+  if (a.xsum) {       // block sums delivered by the kernel that wrote x
+    if (a.zp)
+      skinny_gemm_kernel<MT, DUAL, true, false, true><<<grid, 256, 0, st>>>(a, ws, per);
+    else
+      skinny_gemm_kernel<MT, DUAL, false, false, true><<<grid, 256, 0, st>>>(a, ws, per);
+    return;
   }
   if (a.zp)
     skinny_gemm_kernel<MT, DUAL, true, XMF, false><<<grid, 256, 0, st>>>(a, ws, per);
